@@ -1,0 +1,342 @@
+/*
+ * SKVQ CPU oracle: TEST INFRASTRUCTURE ONLY (see skvq_oracle.h).
+ *
+ * Build: gcc -O2 -std=c11 -fPIC -shared -fopenmp -ffp-contract=off
+ *        (no -ffast-math: the encoder's fp32 operations must each round once).
+ *
+ * Packed formats (the paper gives none; these are this build's):
+ *
+ *  K codes, one 32-byte row per (token, kv head): the 2-bit code of reordered
+ *  position p sits in byte p/4 at bits [2*(p%4), 2*(p%4)+2).
+ *
+ *  V codes, one block per 32 consecutive tokens of a kv head, stored so that
+ *  the codes of CONSECUTIVE TOKENS of one channel are neighbours (the value
+ *  product sums over tokens).  Token slot s = t % 32 splits as kb = s / 8,
+ *  i = s % 8; position p splits as n = p / 16, j = p % 16.  The block holds 64
+ *  units, unit u = 16*kb + j, each covering 8 tokens x 8 positions.
+ *    2-bit : unit = 16 bytes read as a 128-bit little-endian string; code
+ *            (n, i) sits at bit 32*(n/2) + 16*(i%2) + 8*(n%2) + 2*(i/2).
+ *    3-level: unit = 13 bytes read as a 104-bit little-endian string; field n
+ *            is bits [13n, 13n+13) and holds sum_i code(n, i) * 3^i  (< 6561).
+ *  A block is zero-filled when its first token arrives, so slots of tokens
+ *  that do not exist yet read as code 0.
+ *
+ *  Meta: (scale, zero) fp32 pairs, [token][group].
+ */
+#include "skvq_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define D SKVQ_REF_HEAD_DIM
+#define VBT SKVQ_REF_VBLOCK_TOKENS
+
+/* ---------------------------------------------------------------- fp16 --- */
+
+float skvq_ref_half_to_float(uint16_t h) {
+  int sign = (h >> 15) & 1, e = (h >> 10) & 31, m = h & 1023;
+  double v;
+  if (e == 0)
+    v = ldexp((double)m, -24);
+  else if (e == 31)
+    v = m ? NAN : INFINITY;
+  else
+    v = ldexp((double)(m + 1024), e - 25);
+  return (float)(sign ? -v : v); /* every fp16 value is exact in fp32 */
+}
+
+uint16_t skvq_ref_float_to_half(float f) {
+  if (isnan(f)) return 0x7e00;
+  uint16_t sign = signbit(f) ? 0x8000 : 0;
+  double a = fabs((double)f);
+  if (a >= 65520.0) return sign | 0x7c00; /* rounds to infinity */
+  if (a < ldexp(1.0, -14)) {              /* subnormal range: spacing 2^-24 */
+    double r = nearbyint(ldexp(a, 24));   /* ties to even */
+    return sign | (uint16_t)r;            /* r == 1024 lands on the first normal */
+  }
+  int e;
+  double fr = frexp(a, &e);                /* a = fr * 2^e, fr in [0.5, 1) */
+  double r = nearbyint(ldexp(fr, 11));     /* 11 significant bits, in [1024, 2048] */
+  if (r == 2048.0) {
+    r = 1024.0;
+    e += 1;
+  }
+  int be = e - 1 + 15;
+  return sign | (uint16_t)(be << 10) | (uint16_t)((int)r - 1024);
+}
+
+/* ------------------------------------------------------------- encoder --- */
+
+void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels,
+                           uint8_t *codes, float *scale, float *zero) {
+  float mn = xp[0], mx = xp[0];
+  for (int p = 1; p < n; ++p) {
+    if (xp[p] < mn) mn = xp[p];
+    if (xp[p] > mx) mx = xp[p];
+  }
+  if (mn == 0.0f) mn = 0.0f; /* -0 -> +0, so that the stored zero has one bit pattern */
+  if (mx == 0.0f) mx = 0.0f;
+  float top = (float)(levels - 1);
+  float lo = alpha * mn;
+  float hi = alpha * mx;
+  float h = (hi - lo) / top;
+  float inv = h > 0.0f ? 1.0f / h : 0.0f;
+  for (int p = 0; p < n; ++p) {
+    float t = (xp[p] - lo) * inv;
+    float r = nearbyintf(t);
+    if (r < 0.0f) r = 0.0f;
+    if (r > top) r = top;
+    codes[p] = (uint8_t)r;
+  }
+  *scale = h;
+  *zero = lo;
+}
+
+double skvq_ref_avg_bits(double code_bits, int meta_bits, int group_size) {
+  return code_bits + 2.0 * (double)meta_bits / (double)group_size;
+}
+
+/* -------------------------------------------------------------- format --- */
+
+static size_t v_block_bytes(int levels) { return levels == 3 ? 832 : 1024; }
+
+void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
+  size_t heads = (size_t)c->batch * c->n_kv_heads;
+  size_t tcap = (size_t)c->max_quant_tokens;
+  size_t ng = (size_t)(c->head_dim / c->group_size);
+  bytes[0] = heads * tcap * (D / 4);
+  bytes[1] = heads * ((tcap + VBT - 1) / VBT) * v_block_bytes(c->v_levels);
+  bytes[2] = heads * tcap * ng * 2 * sizeof(float);
+  bytes[3] = bytes[2];
+  bytes[4] = heads * (size_t)c->window * D * 2;
+  bytes[5] = bytes[4];
+}
+
+int skvq_ref_k_get(const uint8_t *row, int p) { return (row[p >> 2] >> (2 * (p & 3))) & 3; }
+
+void skvq_ref_k_put(uint8_t *row, int p, int code) {
+  int sh = 2 * (p & 3);
+  row[p >> 2] = (uint8_t)((row[p >> 2] & ~(3 << sh)) | (code << sh));
+}
+
+/* little-endian bit strings */
+static unsigned bits_get(const uint8_t *s, int bit, int width) {
+  unsigned v = 0;
+  for (int k = 0; k < width; ++k) v |= (unsigned)((s[(bit + k) >> 3] >> ((bit + k) & 7)) & 1) << k;
+  return v;
+}
+
+static void bits_put(uint8_t *s, int bit, int width, unsigned v) {
+  for (int k = 0; k < width; ++k) {
+    uint8_t m = (uint8_t)(1u << ((bit + k) & 7));
+    if ((v >> k) & 1)
+      s[(bit + k) >> 3] |= m;
+    else
+      s[(bit + k) >> 3] &= (uint8_t)~m;
+  }
+}
+
+static const unsigned POW3[8] = {1, 3, 9, 27, 81, 243, 729, 2187};
+
+int skvq_ref_v_get(const uint8_t *block, int levels, int s, int p) {
+  int kb = s / 8, i = s % 8, n = p / 16, j = p % 16;
+  int u = 16 * kb + j;
+  if (levels == 3) {
+    unsigned f = bits_get(block + 13 * u, 13 * n, 13);
+    return (int)((f / POW3[i]) % 3);
+  }
+  return (int)bits_get(block + 16 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2);
+}
+
+void skvq_ref_v_put(uint8_t *block, int levels, int s, int p, int code) {
+  int kb = s / 8, i = s % 8, n = p / 16, j = p % 16;
+  int u = 16 * kb + j;
+  if (levels == 3) {
+    unsigned f = bits_get(block + 13 * u, 13 * n, 13);
+    unsigned old = (f / POW3[i]) % 3;
+    f = f - old * POW3[i] + (unsigned)code * POW3[i];
+    bits_put(block + 13 * u, 13 * n, 13, f);
+  } else {
+    bits_put(block + 16 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2,
+             (unsigned)code);
+  }
+}
+
+/* --------------------------------------------------- quantize one token --- */
+
+/* x: fp16 bits [D] of one (token, kv head), original channel order.
+ * Gathers through perm (out[p] = in[perm[p]]), encodes each group, returns
+ * codes[D] in reordered order and meta[D/G][2]. */
+static void encode_token(const uint16_t *x, const int32_t *perm, const float *alpha, int G,
+                         int levels, uint8_t *codes, float *meta) {
+  float xp[D];
+  for (int p = 0; p < D; ++p) xp[p] = skvq_ref_half_to_float(x[perm[p]]);
+  for (int g = 0; g < D / G; ++g)
+    skvq_ref_encode_group(xp + g * G, G, alpha[g], levels, codes + g * G, &meta[2 * g],
+                          &meta[2 * g + 1]);
+}
+
+/* Quantize token (b, hk) and store it as packed row t. */
+static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *buf, int b, int hk,
+                            int64_t t, const uint16_t *kx, const uint16_t *vx) {
+  int G = c->group_size, ng = D / G;
+  size_t head = (size_t)b * c->n_kv_heads + hk;
+  size_t tcap = (size_t)c->max_quant_tokens;
+  uint8_t codes[D];
+  float meta[2 * D];
+
+  encode_token(kx, c->perm_k + hk * D, c->clip_k + hk * ng, G, c->k_levels, codes, meta);
+  uint8_t *krow = buf->k_codes + (head * tcap + (size_t)t) * (D / 4);
+  memset(krow, 0, D / 4);
+  for (int p = 0; p < D; ++p) skvq_ref_k_put(krow, p, codes[p]);
+  memcpy(buf->k_meta + (head * tcap + (size_t)t) * ng * 2, meta, sizeof(float) * 2 * ng);
+
+  encode_token(vx, c->perm_v + hk * D, c->clip_v + hk * ng, G, c->v_levels, codes, meta);
+  size_t nblk = (tcap + VBT - 1) / VBT, bb = v_block_bytes(c->v_levels);
+  uint8_t *blk = buf->v_codes + (head * nblk + (size_t)(t / VBT)) * bb;
+  if (t % VBT == 0) memset(blk, 0, bb);
+  for (int p = 0; p < D; ++p) skvq_ref_v_put(blk, c->v_levels, (int)(t % VBT), p, codes[p]);
+  memcpy(buf->v_meta + (head * tcap + (size_t)t) * ng * 2, meta, sizeof(float) * 2 * ng);
+}
+
+static int check_config(const skvq_ref_config *c) {
+  if (c->head_dim != D || c->group_size <= 0 || D % c->group_size) return -1;
+  if (c->k_levels != 4 || (c->v_levels != 4 && c->v_levels != 3)) return -2;
+  if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1)
+    return -1;
+  return 0;
+}
+
+int skvq_ref_prefill_quantize(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                              const uint16_t *k, const uint16_t *v, int64_t T,
+                              int64_t *n_tokens) {
+  int rc = check_config(c);
+  if (rc) return rc;
+  if (T < 0) return -1;
+  int64_t W = c->window, nq = T > W ? T - W : 0;
+  if (nq > c->max_quant_tokens) return -3;
+  int heads = c->batch * c->n_kv_heads;
+#pragma omp parallel for schedule(static)
+  for (int bh = 0; bh < heads; ++bh) {
+    int b = bh / c->n_kv_heads, hk = bh % c->n_kv_heads;
+    const uint16_t *kh = k + (size_t)bh * (size_t)T * D;
+    const uint16_t *vh = v + (size_t)bh * (size_t)T * D;
+    for (int64_t t = 0; t < nq; ++t) store_quantized(c, buf, b, hk, t, kh + t * D, vh + t * D);
+    for (int64_t a = nq; a < T; ++a) {
+      size_t slot = (size_t)bh * (size_t)W + (size_t)(a % W);
+      memcpy(buf->k_win + slot * D, kh + a * D, D * 2);
+      memcpy(buf->v_win + slot * D, vh + a * D, D * 2);
+    }
+  }
+  *n_tokens = T;
+  return 0;
+}
+
+int skvq_ref_quantize_append(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                             const uint16_t *k_new, const uint16_t *v_new, int64_t *n_tokens) {
+  int rc = check_config(c);
+  if (rc) return rc;
+  int64_t T = *n_tokens, W = c->window;
+  if (T >= W && T - W >= c->max_quant_tokens) return -3;
+  for (int b = 0; b < c->batch; ++b)
+    for (int hk = 0; hk < c->n_kv_heads; ++hk) {
+      size_t bh = (size_t)b * c->n_kv_heads + hk;
+      size_t slot = bh * (size_t)W + (size_t)(T % W);
+      if (T >= W) /* the slot holds token T-W, which now leaves the window */
+        store_quantized(c, buf, b, hk, T - W, buf->k_win + slot * D, buf->v_win + slot * D);
+      memcpy(buf->k_win + slot * D, k_new + bh * D, D * 2);
+      memcpy(buf->v_win + slot * D, v_new + bh * D, D * 2);
+    }
+  *n_tokens = T + 1;
+  return 0;
+}
+
+/* ---------------------------------------------------- decode attention --- */
+
+int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                              int64_t T, const uint16_t *q, float *out_f32, uint16_t *out_f16) {
+  int rc = check_config(c);
+  if (rc) return rc;
+  if (T <= 0) return -4;
+  int64_t W = c->window, nq = T > W ? T - W : 0;
+  int G = c->group_size, ng = D / G, rep = c->n_q_heads / c->n_kv_heads;
+  size_t tcap = (size_t)c->max_quant_tokens, nblk = (tcap + VBT - 1) / VBT;
+  size_t bb = v_block_bytes(c->v_levels);
+  int nqh = c->batch * c->n_q_heads;
+  int fail = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int bq = 0; bq < nqh; ++bq) {
+    int b = bq / c->n_q_heads, hq = bq % c->n_q_heads, hk = hq / rep;
+    size_t head = (size_t)b * c->n_kv_heads + hk;
+    const int32_t *pk = c->perm_k + hk * D, *pv = c->perm_v + hk * D;
+    double qf[D], acc[D];
+    for (int ch = 0; ch < D; ++ch) qf[ch] = skvq_ref_half_to_float(q[(size_t)bq * D + ch]);
+    double *s = (double *)malloc(sizeof(double) * (size_t)T);
+    if (!s) {
+      fail = 1;
+      continue;
+    }
+    /* scores of packed rows: reordered query . dequantized reordered key */
+    for (int64_t t = 0; t < nq; ++t) {
+      const uint8_t *row = buf->k_codes + (head * tcap + (size_t)t) * (D / 4);
+      const float *meta = buf->k_meta + (head * tcap + (size_t)t) * ng * 2;
+      double dot = 0.0;
+      for (int p = 0; p < D; ++p) {
+        double kd = (double)skvq_ref_k_get(row, p) * (double)meta[2 * (p / G)] +
+                    (double)meta[2 * (p / G) + 1];
+        dot += qf[pk[p]] * kd;
+      }
+      s[t] = (double)c->sm_scale * dot;
+    }
+    /* scores of ring tokens, original channel order */
+    for (int64_t a = nq; a < T; ++a) {
+      const uint16_t *kw = buf->k_win + (head * (size_t)W + (size_t)(a % W)) * D;
+      double dot = 0.0;
+      for (int ch = 0; ch < D; ++ch) dot += qf[ch] * (double)skvq_ref_half_to_float(kw[ch]);
+      s[a] = (double)c->sm_scale * dot;
+    }
+    double m = s[0];
+    for (int64_t t = 1; t < T; ++t)
+      if (s[t] > m) m = s[t];
+    double denom = 0.0;
+    for (int ch = 0; ch < D; ++ch) acc[ch] = 0.0;
+    for (int64_t t = 0; t < nq; ++t) {
+      double w = exp(s[t] - m);
+      denom += w;
+      const uint8_t *blk = buf->v_codes + (head * nblk + (size_t)(t / VBT)) * bb;
+      const float *meta = buf->v_meta + (head * tcap + (size_t)t) * ng * 2;
+      for (int p = 0; p < D; ++p) {
+        double vd = (double)skvq_ref_v_get(blk, c->v_levels, (int)(t % VBT), p) *
+                        (double)meta[2 * (p / G)] +
+                    (double)meta[2 * (p / G) + 1];
+        acc[pv[p]] += w * vd;
+      }
+    }
+    for (int64_t a = nq; a < T; ++a) {
+      double w = exp(s[a] - m);
+      denom += w;
+      const uint16_t *vw = buf->v_win + (head * (size_t)W + (size_t)(a % W)) * D;
+      for (int ch = 0; ch < D; ++ch) acc[ch] += w * (double)skvq_ref_half_to_float(vw[ch]);
+    }
+    for (int ch = 0; ch < D; ++ch) {
+      float o = (float)(acc[ch] / denom);
+      out_f32[(size_t)bq * D + ch] = o;
+      if (out_f16) out_f16[(size_t)bq * D + ch] = skvq_ref_float_to_half(o);
+    }
+    free(s);
+  }
+  return fail ? -5 : 0;
+}
+
+int skvq_ref_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

@@ -1,0 +1,116 @@
+/*
+ * SKVQ CPU oracle: TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, single-purpose reference of the SKVQ hot path (arXiv
+ * 2405.06219): clipped dynamic group quantization with channel reorder
+ * (Section 3.1, Eq. 2; Algorithm 1 clipping_quant), the sliding fp16 window
+ * (Section 3.2), and one decode-step attention over the mixed-precision
+ * cache (Eq. 1; Algorithm 1 body with l = 1).
+ *
+ * Nothing in the product (the HIP library and its Python binding) may
+ * include, link or call this; only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg do.  It shares no code with the HIP path.
+ *
+ * All pointers are HOST pointers.  fp16 values travel as raw uint16_t bits.
+ *
+ * Pins (tests marked "not gpu"): every function below is pinned to something
+ * outside this file -- hand-derived values of Eq. 2, the scale/2 error bound,
+ * lossless round trips, exact textbook attention (a library routine) on the
+ * window-only and lossless cases, permutation invariance of Eq. 1, the
+ * paper's printed average-bit figures.  The one thing with no external pin is
+ * the meaning of "1.5-bit": the paper never defines it; three-level codes are
+ * this build's reading ("parity with the authors' 1.5-bit numbers: unpinned").
+ */
+#ifndef SKVQ_ORACLE_H
+#define SKVQ_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SKVQ_REF_HEAD_DIM 128
+#define SKVQ_REF_VBLOCK_TOKENS 32
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128      */
+  int32_t group_size;                             /* G, divides head_dim       */
+  int32_t k_levels, v_levels;                     /* 4 = 2-bit, 3 = "1.5-bit"  */
+  int32_t window;                                 /* W >= 1                    */
+  int64_t max_quant_tokens;                       /* rows in the packed region */
+  const int32_t *perm_k, *perm_v;                 /* [Hk][D] gather index      */
+  const float *clip_k, *clip_v;                   /* [Hk][D/G] alpha           */
+  float sm_scale;                                 /* softmax scale             */
+} skvq_ref_config;
+
+typedef struct {
+  uint8_t *k_codes;  /* [B][Hk][Tcap][32]                                      */
+  uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][1024 or 832]                    */
+  float *k_meta;     /* [B][Hk][Tcap][D/G][2] = (scale, zero)                  */
+  float *v_meta;     /* same                                                   */
+  uint16_t *k_win;   /* fp16 bits [B][Hk][W][D], token a lives in slot a % W   */
+  uint16_t *v_win;
+} skvq_ref_buffers;
+
+/* fp16 <-> fp32 helpers (exact widening; round-to-nearest-even narrowing). */
+float skvq_ref_half_to_float(uint16_t h);
+uint16_t skvq_ref_float_to_half(float f);
+
+/* Eq. 2 for one group of n already-reordered values: codes[n], scale, zero.
+ * levels = 2^N (or 3).  Every fp32 operation is a separately rounded IEEE
+ * operation, in this order:
+ *   mn, mx = min, max (a zero of either sign becomes +0)
+ *   lo = alpha*mn ; hi = alpha*mx ; scale = (hi-lo)/(levels-1)
+ *   inv = scale > 0 ? 1/scale : 0
+ *   code = clamp(rint((x-lo)*inv), 0, levels-1)   (ties to even)
+ *   zero = lo                                                                */
+void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels,
+                           uint8_t *codes, float *scale, float *zero);
+
+/* Storage accounting in the paper's style: average bits per cached element
+ * = code bits + 2 * meta_bits / group_size (Section 4.3, breakdown paragraph). */
+double skvq_ref_avg_bits(double code_bits, int meta_bits, int group_size);
+
+/* Byte sizes of the six cache buffers for this build's formats. */
+void skvq_ref_sizes(const skvq_ref_config *cfg, size_t bytes[6]);
+
+/* Packed-format accessors (the format is stated in the .c file). */
+int skvq_ref_k_get(const uint8_t *k_row, int p);
+void skvq_ref_k_put(uint8_t *k_row, int p, int code);
+int skvq_ref_v_get(const uint8_t *v_block, int levels, int t_in_block, int p);
+void skvq_ref_v_put(uint8_t *v_block, int levels, int t_in_block, int p, int code);
+
+/* Prefill (Section 3.2, phase 1): tokens [0, T-W) are reordered, quantized
+ * and packed into rows [0, T-W); the last min(T, W) tokens are copied bit for
+ * bit into the fp16 ring.  k, v: fp16 bits [B][Hk][T][D], original channel
+ * order.  Returns 0, or -3 if T-W exceeds max_quant_tokens.  *n_tokens = T. */
+int skvq_ref_prefill_quantize(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                              const uint16_t *k, const uint16_t *v, int64_t T,
+                              int64_t *n_tokens);
+
+/* Decode (Section 3.2, phase 2): the token that slides out of the window is
+ * quantized into row n_tokens-W, then the new token takes its ring slot.
+ * k_new, v_new: fp16 bits [B][Hk][D].  *n_tokens is advanced by one.        */
+int skvq_ref_quantize_append(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                             const uint16_t *k_new, const uint16_t *v_new,
+                             int64_t *n_tokens);
+
+/* One decode-step attention (Eq. 1 with the standard 1/sqrt(d)-style scale):
+ * dequantize every packed row in fp64, score against the reordered query,
+ * score the ring tokens in original order, one softmax over all of them,
+ * weighted sum of dequantized values scattered back to original channel
+ * order.  q: fp16 bits [B][Hq][D]; out_f32: [B][Hq][D]; out_f16 may be NULL.
+ * Returns 0, or -4 if the cache is empty.                                    */
+int skvq_ref_decode_attention(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                              int64_t n_tokens, const uint16_t *q, float *out_f32,
+                              uint16_t *out_f16);
+
+/* Number of OpenMP threads the decode/prefill loops will use. */
+int skvq_ref_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

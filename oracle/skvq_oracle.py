@@ -1,0 +1,197 @@
+"""ctypes front end of the SKVQ CPU oracle: TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this.  It marshals numpy arrays into oracle/skvq_oracle.c and does no
+arithmetic of its own.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libskvq_oracle.so")
+_SRC = os.path.join(_HERE, "skvq_oracle.c")
+
+HEAD_DIM = 128
+VBLOCK = 32
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C11, one rounding per fp32 operation)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < max(
+            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "skvq_oracle.h"))):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+class _Config(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("group_size", C.c_int32), ("k_levels", C.c_int32),
+                ("v_levels", C.c_int32), ("window", C.c_int32), ("max_quant_tokens", C.c_int64),
+                ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
+                ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
+
+
+class _Buffers(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.skvq_ref_half_to_float.restype = C.c_float
+        _lib.skvq_ref_half_to_float.argtypes = [C.c_uint16]
+        _lib.skvq_ref_float_to_half.restype = C.c_uint16
+        _lib.skvq_ref_float_to_half.argtypes = [C.c_float]
+        _lib.skvq_ref_avg_bits.restype = C.c_double
+        _lib.skvq_ref_avg_bits.argtypes = [C.c_double, C.c_int, C.c_int]
+        _lib.skvq_ref_encode_group.restype = None
+        _lib.skvq_ref_encode_group.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int,
+                                               C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_k_get.argtypes = [C.c_void_p, C.c_int]
+        _lib.skvq_ref_k_put.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        _lib.skvq_ref_k_put.restype = None
+        _lib.skvq_ref_v_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
+        _lib.skvq_ref_v_put.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
+        _lib.skvq_ref_v_put.restype = None
+        _lib.skvq_ref_sizes.restype = None
+        _lib.skvq_ref_sizes.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_prefill_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_int64, C.c_void_p]
+        _lib.skvq_ref_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                  C.c_void_p]
+        _lib.skvq_ref_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p]
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def half_to_float(bits: int) -> float:
+    return float(lib().skvq_ref_half_to_float(int(bits)))
+
+
+def float_to_half(x: float) -> int:
+    return int(lib().skvq_ref_float_to_half(float(x)))
+
+
+def avg_bits(code_bits: float, meta_bits: int, group_size: int) -> float:
+    return float(lib().skvq_ref_avg_bits(code_bits, meta_bits, group_size))
+
+
+def encode_group(xp: np.ndarray, alpha: float, levels: int):
+    """Eq. 2 on one group of already reordered float32 values."""
+    xp = np.ascontiguousarray(xp, dtype=np.float32)
+    codes = np.zeros(xp.size, np.uint8)
+    scale = np.zeros(1, np.float32)
+    zero = np.zeros(1, np.float32)
+    lib().skvq_ref_encode_group(_ptr(xp), xp.size, float(alpha), int(levels), _ptr(codes),
+                                _ptr(scale), _ptr(zero))
+    return codes, scale[0], zero[0]
+
+
+def levels_of(bits: float) -> int:
+    return {2.0: 4, 1.5: 3}[float(bits)]
+
+
+class OracleCache:
+    """Host-side mixed-precision cache of one attention layer, driven by the oracle."""
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens,
+                 perm_k, perm_v, clip_k, clip_v, sm_scale=None, k_bits=2.0, fill=0):
+        self.perm_k = np.ascontiguousarray(perm_k, np.int32)
+        self.perm_v = np.ascontiguousarray(perm_v, np.int32)
+        self.clip_k = np.ascontiguousarray(clip_k, np.float32)
+        self.clip_v = np.ascontiguousarray(clip_v, np.float32)
+        if sm_scale is None:
+            sm_scale = 1.0 / np.sqrt(HEAD_DIM)
+        self.cfg = _Config(batch, n_q_heads, n_kv_heads, HEAD_DIM, group_size, levels_of(k_bits),
+                           levels_of(v_bits), window, max_quant_tokens, _ptr(self.perm_k),
+                           _ptr(self.perm_v), _ptr(self.clip_k), _ptr(self.clip_v), sm_scale)
+        sizes = (C.c_size_t * 6)()
+        lib().skvq_ref_sizes(C.byref(self.cfg), sizes)
+        self.sizes = [int(s) for s in sizes]
+        ng = HEAD_DIM // group_size
+        heads = batch * n_kv_heads
+        nblk = (max_quant_tokens + VBLOCK - 1) // VBLOCK
+        vb = 832 if levels_of(v_bits) == 3 else 1024
+        self.k_codes = np.full((batch, n_kv_heads, max_quant_tokens, 32), fill, np.uint8)
+        self.v_codes = np.full((batch, n_kv_heads, nblk, vb), fill, np.uint8)
+        self.k_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
+        self.v_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
+        self.k_win = np.zeros((batch, n_kv_heads, window, HEAD_DIM), np.uint16)
+        self.v_win = np.zeros((batch, n_kv_heads, window, HEAD_DIM), np.uint16)
+        assert [a.nbytes for a in self.arrays()] == self.sizes, (self.sizes, heads)
+        self.buf = _Buffers(*[_ptr(a) for a in self.arrays()])
+        self.n_tokens = 0
+        self.window = window
+        self.shape = (batch, n_q_heads, n_kv_heads)
+
+    def arrays(self):
+        return [self.k_codes, self.v_codes, self.k_meta, self.v_meta, self.k_win, self.v_win]
+
+    @property
+    def n_quant(self) -> int:
+        return max(self.n_tokens - self.window, 0)
+
+    def prefill(self, k: np.ndarray, v: np.ndarray) -> int:
+        b, _, hk = self.shape
+        assert k.dtype == np.float16 and v.dtype == np.float16
+        assert k.shape == v.shape and k.shape[:2] == (b, hk) and k.shape[3] == HEAD_DIM
+        k = np.ascontiguousarray(k)
+        v = np.ascontiguousarray(v)
+        n = C.c_int64(0)
+        rc = lib().skvq_ref_prefill_quantize(C.byref(self.cfg), C.byref(self.buf), _ptr(k), _ptr(v),
+                                             k.shape[2], C.byref(n))
+        if rc == 0:
+            self.n_tokens = n.value
+        return rc
+
+    def append(self, k_new: np.ndarray, v_new: np.ndarray) -> int:
+        b, _, hk = self.shape
+        assert k_new.dtype == np.float16 and k_new.shape == (b, hk, HEAD_DIM) == v_new.shape
+        k_new = np.ascontiguousarray(k_new)
+        v_new = np.ascontiguousarray(v_new)
+        n = C.c_int64(self.n_tokens)
+        rc = lib().skvq_ref_quantize_append(C.byref(self.cfg), C.byref(self.buf), _ptr(k_new),
+                                            _ptr(v_new), C.byref(n))
+        if rc == 0:
+            self.n_tokens = n.value
+        return rc
+
+    def decode(self, q: np.ndarray, want_f16: bool = False):
+        b, hq, _ = self.shape
+        assert q.dtype == np.float16 and q.shape == (b, hq, HEAD_DIM)
+        q = np.ascontiguousarray(q)
+        out = np.zeros((b, hq, HEAD_DIM), np.float32)
+        out16 = np.zeros((b, hq, HEAD_DIM), np.float16) if want_f16 else None
+        rc = lib().skvq_ref_decode_attention(C.byref(self.cfg), C.byref(self.buf), self.n_tokens,
+                                             _ptr(q), _ptr(out), _ptr(out16) if want_f16 else None)
+        if rc != 0:
+            raise RuntimeError(f"oracle decode failed: {rc}")
+        return (out, out16) if want_f16 else out
+
+    # format accessors, for tests that look inside the packed buffers
+    def k_code(self, b, h, t, p) -> int:
+        row = self.k_codes[b, h, t]
+        return int(lib().skvq_ref_k_get(_ptr(row), p))
+
+    def v_code(self, b, h, t, p) -> int:
+        blk = self.v_codes[b, h, t // VBLOCK]
+        return int(lib().skvq_ref_v_get(_ptr(blk), self.cfg.v_levels, t % VBLOCK, p))
+
+
+def num_threads() -> int:
+    return int(lib().skvq_ref_num_threads())

@@ -1,0 +1,403 @@
+"""Pins of the CPU oracle to things outside it (no GPU needed).
+
+Each test fixes the oracle to a value or property that the paper or plain
+mathematics dictates: hand-derived values of Eq. 2, the scale/2 error bound,
+lossless grids, textbook softmax attention from a library routine (window-only
+and lossless caches), permutation invariance of Eq. 1, closed forms, and the
+average-bit figures the paper prints.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+D = 128
+
+
+# ----------------------------------------------------------------- fp16 ----
+
+def test_half_to_float_all_bit_patterns(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float32)
+    got = np.array([oracle.half_to_float(int(b)) for b in bits], np.float32)
+    fin = np.isfinite(want)
+    assert np.array_equal(got[fin].view(np.uint32), want[fin].view(np.uint32))
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(np.isinf(got), np.isinf(want))
+
+
+def test_float_to_half_rounds_to_nearest_even(oracle):
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32) * 10.0 ** rng.uniform(-9, 5, 20000).astype(np.float32),
+        # exact ties between neighbouring fp16 values, normal and subnormal
+        np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2.0 ** -25, 3 * 2.0 ** -25, 65519.9, 65520.0,
+                  2.0 ** -14 - 2.0 ** -25, 0.0, -0.0, 1e-9], np.float32)])
+    with np.errstate(over="ignore"):
+        want = xs.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.float_to_half(float(x)) for x in xs], np.uint16)
+    assert np.array_equal(got, want)
+
+
+# -------------------------------------------------------- Eq. 2 encoder ----
+
+def test_encoder_hand_derived_values(oracle):
+    # Eq. 2 by hand, N = 2: x = [-1, 0, 1, 2], alpha = 1 -> h = 3/3 = 1, alpha*min = -1.
+    c, h, z = oracle.encode_group(np.array([-1, 0, 1, 2], np.float32), 1.0, 4)
+    assert list(c) == [0, 1, 2, 3] and h == 1.0 and z == -1.0
+    # alpha = 0.5 -> range [-0.5, 1], h = 0.5, (x + 0.5)/0.5 = [-1, 1, 3, 5] -> clamp to [0, 1, 3, 3].
+    c, h, z = oracle.encode_group(np.array([-1, 0, 1, 2], np.float32), 0.5, 4)
+    assert list(c) == [0, 1, 3, 3] and h == 0.5 and z == -0.5
+    # ties: h = 1, zero = 0, (x - z)/h = x ; 0.5 -> 0, 1.5 -> 2, 2.5 -> 2 (ties to even)
+    c, h, z = oracle.encode_group(np.array([0, 0.5, 1.5, 2.5, 3], np.float32), 1.0, 4)
+    assert list(c) == [0, 0, 2, 2, 3] and h == 1.0 and z == 0.0
+    # three levels ("1.5-bit" reading): top code 2, h = (2 - 0)/2 = 1
+    c, h, z = oracle.encode_group(np.array([0, 0.5, 1, 1.5, 2], np.float32), 1.0, 3)
+    assert list(c) == [0, 0, 1, 2, 2] and h == 1.0 and z == 0.0
+    # both ends are scaled by alpha (Eq. 2 and Algorithm 1 agree): all-positive group
+    c, h, z = oracle.encode_group(np.array([4, 8, 16], np.float32), 0.5, 4)
+    assert z == 2.0 and h == (8.0 - 2.0) / 3 and list(c) == [1, 3, 3]
+
+
+@pytest.mark.parametrize("levels", [4, 3])
+def test_encoder_error_bound_and_clipping(oracle, levels):
+    rng = np.random.default_rng(11 + levels)
+    top = levels - 1
+    for trial in range(200):
+        n = int(rng.choice([4, 32, 64, 128]))
+        x = (rng.standard_normal(n) * 10.0 ** rng.uniform(-2, 1.5)).astype(np.float16).astype(np.float32)
+        alpha = float(np.float32(rng.choice([1.0, 0.95, 0.8, 0.5])))
+        c, h, z = oracle.encode_group(x, alpha, levels)
+        lo, hi = np.float64(z), np.float64(z) + top * np.float64(h)
+        deq = c.astype(np.float64) * np.float64(h) + np.float64(z)
+        assert c.min() >= 0 and c.max() <= top
+        inside = (x >= lo) & (x <= hi)
+        assert np.all(np.abs(x[inside] - deq[inside]) <= 0.5 * h * (1 + 1e-5) + 1e-30)
+        assert np.all(c[x < lo] == 0) and np.all(c[x > hi + 1e-6 * abs(hi)] == top)
+        # zero and scale are exactly what Eq. 2 prescribes, evaluated in fp32
+        a32 = np.float32(alpha)
+        assert z == a32 * x.min()
+        assert h == np.float32(np.float32(a32 * x.max()) - np.float32(a32 * x.min())) / np.float32(top)
+
+
+@pytest.mark.parametrize("levels", [4, 3])
+def test_encoder_picks_the_nearest_level(oracle, levels):
+    """Brute force: among all codes the chosen one is nearest to x (exact arithmetic)."""
+    rng = np.random.default_rng(23 + levels)
+    for trial in range(100):
+        x = rng.standard_normal(16).astype(np.float16).astype(np.float32)
+        c, h, z = oracle.encode_group(x, 0.9, levels)
+        grid = np.float64(z) + np.arange(levels)[None, :] * np.float64(h)
+        dist = np.abs(x.astype(np.float64)[:, None] - grid)
+        best = dist.min(axis=1)
+        chosen = dist[np.arange(16), c]
+        assert np.all(chosen <= best + 1e-6 * h)
+
+
+@pytest.mark.parametrize("levels", [4, 3])
+def test_encoder_lossless_on_a_grid_and_power_of_two_scaling(oracle, levels):
+    rng = np.random.default_rng(31 + levels)
+    top = levels - 1
+    for trial in range(50):
+        step = 2.0 ** int(rng.integers(-6, 4))
+        base = step * int(rng.integers(-40, 40))
+        k = rng.integers(0, levels, 32)
+        k[0], k[1] = 0, top
+        x = (base + step * k).astype(np.float32)
+        c, h, z = oracle.encode_group(x, 1.0, levels)
+        assert h == step and z == base and np.array_equal(c, k)
+        c2, h2, z2 = oracle.encode_group(x * 8.0, 1.0, levels)
+        assert np.array_equal(c2, c) and h2 == 8 * h and z2 == 8 * z
+    # lossy data too: multiplying by a power of two scales scale and zero exactly, codes unchanged
+    x = rng.standard_normal(128).astype(np.float16).astype(np.float32)
+    c, h, z = oracle.encode_group(x, 0.95, levels)
+    c2, h2, z2 = oracle.encode_group(x * 0.25, 0.95, levels)
+    assert np.array_equal(c, c2) and h2 == np.float32(0.25) * h and z2 == np.float32(0.25) * z
+
+
+def test_encoder_degenerate_groups(oracle):
+    c, h, z = oracle.encode_group(np.full(8, 3.0, np.float32), 0.5, 4)
+    assert h == 0.0 and z == 1.5 and not c.any()          # decodes to alpha*min, the formula's own value
+    c, h, z = oracle.encode_group(np.array([-0.0, 0.0, -0.0], np.float32), 1.0, 4)
+    assert h == 0.0 and np.float32(z).view(np.uint32) == 0  # one bit pattern for a zero minimum
+    c, h, z = oracle.encode_group(np.array([-0.0, 1.0], np.float32), 1.0, 3)
+    assert np.float32(z).view(np.uint32) == 0 and h == 0.5 and list(c) == [0, 2]
+
+
+# ----------------------------------------------------- paper's avg bits ----
+
+def test_average_bits_match_the_paper(oracle):
+    rows = 0
+    for line in open(os.path.join(HERE, "golden", "avg_bits.txt")):
+        line = line.split("#")[0].split()
+        if not line:
+            continue
+        cb, mb, g, want = float(line[0]), int(line[1]), int(line[2]), float(line[3])
+        assert oracle.avg_bits(cb, mb, g) == pytest.approx(want, abs=1e-12)
+        rows += 1
+    assert rows == 8
+
+
+# -------------------------------------------------------------- formats ----
+
+def test_k_row_layout_is_position_p_at_bit_2p(oracle):
+    for p in range(D):
+        row = np.zeros(32, np.uint8)
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, p, 3)
+        assert int.from_bytes(row.tobytes(), "little") == 3 << (2 * p)
+        assert oracle.lib().skvq_ref_k_get(row.ctypes.data, p) == 3
+    rng = np.random.default_rng(3)
+    row = rng.integers(0, 256, 32, dtype=np.uint8)
+    big = int.from_bytes(row.tobytes(), "little")
+    assert [oracle.lib().skvq_ref_k_get(row.ctypes.data, p) for p in range(D)] == \
+           [(big >> (2 * p)) & 3 for p in range(D)]
+
+
+def test_v_block_2bit_layout_is_a_bijection_with_token_neighbours(oracle):
+    seen = 0
+    for s in range(32):
+        for p in range(D):
+            blk = np.zeros(1024, np.uint8)
+            oracle.lib().skvq_ref_v_put(blk.ctypes.data, 4, s, p, 3)
+            big = int.from_bytes(blk.tobytes(), "little")
+            assert bin(big).count("1") == 2 and not (big & seen)
+            seen |= big
+            # unit u = 16*(s/8) + p%16 of 16 bytes; tokens 2m and 2m+1 sit 16 bits apart in one dword
+            u, n, i = 16 * (s // 8) + p % 16, p // 16, s % 8
+            assert big == 3 << (128 * u + 32 * (n // 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i // 2))
+    assert seen == (1 << 8192) - 1
+
+
+def test_v_block_ternary_fields_are_base3_numbers(oracle):
+    rng = np.random.default_rng(4)
+    codes = rng.integers(0, 3, (32, D))
+    blk = np.full(832, 0, np.uint8)
+    for s in range(32):
+        for p in range(D):
+            oracle.lib().skvq_ref_v_put(blk.ctypes.data, 3, s, p, int(codes[s, p]))
+    for u in range(64):
+        unit = int.from_bytes(blk[13 * u:13 * u + 13].tobytes(), "little")
+        kb, j = u // 16, u % 16
+        for n in range(8):
+            f = (unit >> (13 * n)) & 0x1FFF
+            assert f < 3 ** 8
+            assert f == sum(int(codes[8 * kb + i, 16 * n + j]) * 3 ** i for i in range(8))
+    got = [[oracle.lib().skvq_ref_v_get(blk.ctypes.data, 3, s, p) for p in range(D)] for s in range(32)]
+    assert np.array_equal(np.array(got), codes)
+    # overwriting one code leaves every other code alone
+    oracle.lib().skvq_ref_v_put(blk.ctypes.data, 3, 5, 77, (int(codes[5, 77]) + 1) % 3)
+    got2 = np.array([[oracle.lib().skvq_ref_v_get(blk.ctypes.data, 3, s, p) for p in range(D)] for s in range(32)])
+    assert (got2 != codes).sum() == 1
+
+
+def test_bytes_per_token_match_the_byte_model(oracle):
+    perm = np.tile(np.arange(D, dtype=np.int32), (8, 1))
+    clip = np.ones((8, 1), np.float32)
+    c = oracle.OracleCache(1, 32, 8, 128, 1.5, 128, 4096, perm, perm, clip, clip)
+    per_token = sum(c.sizes[:4]) / (8 * 4096)
+    assert per_token == 32 + 26 + 8 + 8       # 2-bit K row, 13 bits per 8 values for V, fp32 scale+zero each
+    assert c.sizes[4] == 8 * 128 * 128 * 2
+    c2 = oracle.OracleCache(1, 32, 8, 32, 2.0, 128, 4096, perm, perm, np.ones((8, 4), np.float32),
+                            np.ones((8, 4), np.float32))
+    assert sum(c2.sizes[:4]) / (8 * 4096) == 32 + 32 + 32 + 32
+
+
+# ------------------------------------------------------------ attention ----
+
+def sdpa64(q, k, v, sm_scale):
+    """Textbook softmax attention from the library, fp64, GQA by repeating kv heads.
+    q [B][Hq][D], k/v [B][Hk][T][D] -> [B][Hq][D]."""
+    qt = torch.from_numpy(q.astype(np.float64))[:, :, None, :]
+    rep = q.shape[1] // k.shape[1]
+    kt = torch.from_numpy(k.astype(np.float64)).repeat_interleave(rep, dim=1)
+    vt = torch.from_numpy(v.astype(np.float64)).repeat_interleave(rep, dim=1)
+    o = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, scale=float(sm_scale))
+    return o[:, :, 0, :].numpy()
+
+
+def random_perms(rng, hk):
+    return np.stack([rng.permutation(D) for _ in range(hk)]).astype(np.int32)
+
+
+def grid_data(rng, shape_bht, G, levels, perm):
+    """fp16 tensor [B][Hk][T][D] whose every (token, head, group of the REORDERED axis)
+    lies on its own `levels`-point grid with a power-of-two step, both end points present."""
+    B, Hk, T = shape_bht
+    x = np.zeros((B, Hk, T, D), np.float32)
+    for b in range(B):
+        for h in range(Hk):
+            for t in range(T):
+                for g in range(D // G):
+                    step = 2.0 ** int(rng.integers(-5, 2))
+                    base = step * int(rng.integers(-20, 20))
+                    k = rng.integers(0, levels, G)
+                    k[rng.integers(0, G // 2)] = 0
+                    k[G // 2 + rng.integers(0, G // 2)] = levels - 1
+                    x[b, h, t, perm[h, g * G:(g + 1) * G]] = base + step * k
+    return x.astype(np.float16)
+
+
+def test_window_only_cache_is_textbook_attention(oracle):
+    rng = np.random.default_rng(100)
+    B, Hq, Hk, W = 2, 8, 2, 16
+    for T in (1, 7, 16):
+        k = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+        v = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+        q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+        c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, W, 64, random_perms(rng, Hk), random_perms(rng, Hk),
+                               np.full((Hk, 1), 0.9, np.float32), np.full((Hk, 1), 0.9, np.float32))
+        assert c.prefill(k, v) == 0 and c.n_quant == 0
+        out, out16 = c.decode(q, want_f16=True)
+        ref = sdpa64(q, k, v, 1 / np.sqrt(D))
+        assert np.abs(out - ref).max() < 2e-6
+        assert np.array_equal(out16, out.astype(np.float16))
+        # the ring holds the tokens bit for bit, token a in slot a % W
+        for a in range(T):
+            assert np.array_equal(c.k_win[:, :, a % W].view(np.float16), k[:, :, a])
+            assert np.array_equal(c.v_win[:, :, a % W].view(np.float16), v[:, :, a])
+
+
+@pytest.mark.parametrize("v_bits,G", [(2.0, 128), (1.5, 128), (1.5, 32), (2.0, 64)])
+def test_lossless_cache_equals_textbook_attention(oracle, v_bits, G):
+    """Data that Eq. 2 represents exactly (alpha = 1) makes the quantized path exact, so the whole
+    chain reorder -> encode -> pack -> unpack -> dequantize -> Eq. 1 must reproduce the library's
+    attention on the ORIGINAL tensors, for any permutation (Eq. 1's invariance)."""
+    rng = np.random.default_rng(200 + G)
+    B, Hq, Hk, W, T = 1, 4, 2, 8, 77
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    k = grid_data(rng, (B, Hk, T), G, 4, pk)
+    v = grid_data(rng, (B, Hk, T), G, oracle.levels_of(v_bits), pv)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    ones = np.ones((Hk, D // G), np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 96, pk, pv, ones, ones, sm_scale=0.05)
+    assert c.prefill(k, v) == 0 and c.n_quant == T - W
+    out = c.decode(q)
+    ref = sdpa64(q, k, v, 0.05)
+    assert np.abs(out - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+
+
+def test_permutation_invariance_when_group_is_the_whole_head(oracle):
+    """With G = D a permutation only moves codes around (same min/max, same codes), so by
+    Eq. 1 the attention output cannot depend on P_k or P_v, lossy data included."""
+    rng = np.random.default_rng(300)
+    B, Hq, Hk, W, T = 1, 4, 2, 8, 60
+    k = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    clip = np.full((Hk, 1), 0.95, np.float32)
+    outs = []
+    for trial in range(3):
+        c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, W, 64, random_perms(rng, Hk), random_perms(rng, Hk),
+                               clip, clip)
+        c.prefill(k, v)
+        outs.append(c.decode(q))
+    assert np.abs(outs[0] - outs[1]).max() < 1e-6 and np.abs(outs[0] - outs[2]).max() < 1e-6
+
+
+def numpy_dequantize(c, T):
+    """Independent unpack + dequantize of an OracleCache's packed rows, straight from the
+    format statement, vectorised; returns K', V' float64 [B][Hk][nq][D] in ORIGINAL channel order."""
+    B, Hk = c.k_codes.shape[:2]
+    nq = max(T - c.window, 0)
+    G = c.cfg.group_size
+    kq = np.zeros((B, Hk, nq, D))
+    vq = np.zeros((B, Hk, nq, D))
+    p = np.arange(D)
+    kc = (c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3
+    ks = c.k_meta[:, :, :nq, p // G, 0].astype(np.float64)
+    kz = c.k_meta[:, :, :nq, p // G, 1].astype(np.float64)
+    kd = kc * ks + kz
+    vs = c.v_meta[:, :, :nq, p // G, 0].astype(np.float64)
+    vz = c.v_meta[:, :, :nq, p // G, 1].astype(np.float64)
+    vc = np.zeros((B, Hk, nq, D), np.int64)
+    for b in range(B):
+        for h in range(Hk):
+            for t in range(nq):
+                blk = c.v_codes[b, h, t // 32]
+                s = t % 32
+                for pp in range(D):
+                    u, n, i = 16 * (s // 8) + pp % 16, pp // 16, s % 8
+                    if c.cfg.v_levels == 3:
+                        unit = int.from_bytes(blk[13 * u:13 * u + 13].tobytes(), "little")
+                        vc[b, h, t, pp] = ((unit >> (13 * n)) & 0x1FFF) // 3 ** i % 3
+                    else:
+                        unit = int.from_bytes(blk[16 * u:16 * u + 16].tobytes(), "little")
+                        vc[b, h, t, pp] = (unit >> (32 * (n // 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i // 2))) & 3
+    vd = vc * vs + vz
+    for h in range(Hk):
+        kq[:, h][..., c.perm_k[h]] = kd[:, h]      # position p holds channel perm[p]
+        vq[:, h][..., c.perm_v[h]] = vd[:, h]
+    return kq, vq
+
+
+@pytest.mark.parametrize("v_bits,G", [(1.5, 128), (2.0, 32), (1.5, 64)])
+def test_lossy_cache_equals_dequantize_then_textbook_attention(oracle, v_bits, G):
+    rng = np.random.default_rng(400 + G)
+    B, Hq, Hk, W, T = 2, 4, 2, 8, 45
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    ck = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    cv = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv)
+    c.prefill(k, v)
+    out = c.decode(q)
+    kq, vq = numpy_dequantize(c, T)
+    kfull = np.concatenate([kq, k[:, :, T - W:].astype(np.float64)], axis=2)
+    vfull = np.concatenate([vq, v[:, :, T - W:].astype(np.float64)], axis=2)
+    ref = sdpa64(q, kfull, vfull, 1 / np.sqrt(D))
+    assert np.abs(out - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    # the decoded keys really are within scale/2 (or clipped) of the originals
+    err = np.abs(kq - k[:, :, :T - W].astype(np.float64))
+    assert err.max() < np.abs(k.astype(np.float64)).max()
+    # uniform weights (softmax scale 0): output is the plain mean of the decoded values
+    c0 = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, sm_scale=0.0)
+    c0.prefill(k, v)
+    out0 = c0.decode(q)
+    mean = vfull.mean(axis=2).repeat(Hq // Hk, axis=1)
+    assert np.abs(out0 - mean).max() < 1e-5 * max(1.0, np.abs(mean).max())
+    # convex combination: every output channel lies between min and max of the decoded values
+    lo = vfull.min(axis=2).repeat(Hq // Hk, axis=1)
+    hi = vfull.max(axis=2).repeat(Hq // Hk, axis=1)
+    assert np.all(out >= lo - 1e-4) and np.all(out <= hi + 1e-4)
+
+
+def test_prefill_then_appends_equals_one_longer_prefill(oracle):
+    rng = np.random.default_rng(500)
+    B, Hq, Hk, W, T0, n = 2, 4, 2, 8, 37, 44
+    k = rng.standard_normal((B, Hk, T0 + n, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hk, T0 + n, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, 2), 0.95, np.float32)
+    for v_bits in (1.5, 2.0):
+        a = oracle.OracleCache(B, Hq, Hk, 64, v_bits, W, 96, pk, pv, clip, clip, fill=0xAB)
+        b = oracle.OracleCache(B, Hq, Hk, 64, v_bits, W, 96, pk, pv, clip, clip, fill=0xAB)
+        assert a.prefill(k[:, :, :T0], v[:, :, :T0]) == 0
+        for s in range(n):
+            assert a.append(k[:, :, T0 + s], v[:, :, T0 + s]) == 0
+        assert b.prefill(k, v) == 0
+        assert a.n_tokens == b.n_tokens == T0 + n
+        for x, y in zip(a.arrays(), b.arrays()):
+            assert np.array_equal(x, y)
+    # appends from an empty cache too (the window fills first, nothing is quantized until it is full)
+    e = oracle.OracleCache(B, Hq, Hk, 64, 1.5, W, 96, pk, pv, clip, clip, fill=0xAB)
+    for s in range(W):
+        e.append(k[:, :, s], v[:, :, s])
+    assert e.n_quant == 0 and np.all(e.k_codes == 0xAB)
+    e.append(k[:, :, W], v[:, :, W])
+    assert e.n_quant == 1
+
+
+def test_capacity_and_empty_cache_errors(oracle):
+    perm = np.tile(np.arange(D, dtype=np.int32), (1, 1))
+    clip = np.ones((1, 1), np.float32)
+    c = oracle.OracleCache(1, 1, 1, 128, 2.0, 4, 2, perm, perm, clip, clip)
+    x = np.zeros((1, 1, 7, D), np.float16)
+    assert c.prefill(x, x) == -3                      # 7 - 4 = 3 rows > capacity 2
+    assert c.prefill(x[:, :, :6], x[:, :, :6]) == 0
+    assert c.append(x[:, :, 0], x[:, :, 0]) == -3
+    with pytest.raises(RuntimeError):
+        oracle.OracleCache(1, 1, 1, 128, 2.0, 4, 2, perm, perm, clip, clip).decode(np.zeros((1, 1, D), np.float16))
