@@ -1,0 +1,156 @@
+/*
+ * skvq.h -- C ABI of the MI355X (gfx950) SKVQ hot path.
+ *
+ * SKVQ (arXiv 2405.06219) keeps the last W tokens of a KV cache in fp16 and
+ * stores every older token as low-bit codes: channels are reordered by an
+ * offline permutation, then each group of G reordered channels of a token is
+ * quantized with clipped dynamic asymmetric quantization (Section 3.1, Eq. 2;
+ * Section 3.2; Algorithm 1).  This library is that cache's data path for one
+ * attention layer on one GPU:
+ *
+ *   skvq_prefill_quantize   bulk-quantize a prompt, keep its last W tokens fp16
+ *   skvq_quantize_append    one decode step: the token leaving the window is
+ *                           quantized, the new token enters the window
+ *   skvq_decode_attention   one query token attends over packed + fp16 tokens
+ *
+ * Conventions
+ *  - C99, plain pointers and sizes.  Pointers marked HOST are read during the
+ *    call only.  Pointers marked DEVICE are HIP device memory that the caller
+ *    owns (allocates, keeps alive until the stream has drained, frees).
+ *  - Work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
+ *    default stream) and the call returns without synchronising.  The token
+ *    counters live on the host and advance when a call is enqueued.
+ *  - Every function returns a skvq_status (0 = ok, negative = error).  On
+ *    error nothing is enqueued and no state changes.
+ *  - Calls on one skvq_cache must not overlap (one stream, or ordered streams).
+ *  - Inputs must be finite fp16; the result for inf/nan input is unspecified.
+ *
+ * Numerics contract: codes and (scale, zero) are a pure function of the
+ * inputs -- each fp32 operation of Eq. 2 is a single IEEE round-to-nearest
+ * operation in a fixed order (listed at skvq_prefill_quantize).  Attention
+ * outputs are computed with fp32 accumulation.
+ */
+#ifndef SKVQ_H
+#define SKVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct skvq_cache skvq_cache; /* opaque host object */
+
+typedef enum {
+  SKVQ_OK = 0,
+  SKVQ_ERR_INVALID_ARG = -1, /* NULL pointer, bad shape, non-permutation, alpha outside (0,1] */
+  SKVQ_ERR_UNSUPPORTED = -2, /* a bit-width / head_dim / group size this build has no kernel for */
+  SKVQ_ERR_CAPACITY = -3,    /* the packed region (max_quant_tokens) would overflow */
+  SKVQ_ERR_STATE = -4,       /* e.g. attention over an empty cache */
+  SKVQ_ERR_HIP = -5          /* a HIP runtime call failed; see skvq_last_error */
+} skvq_status;
+
+/* Code widths, named by twice the nominal bits (Abstract: 2-bit keys, 1.5-bit values). */
+typedef enum {
+  SKVQ_BITS_2 = 4,  /* four levels, codes 0..3 */
+  SKVQ_BITS_1P5 = 3 /* three levels, codes 0..2 (this build's reading of "1.5-bit") */
+} skvq_bits;
+
+/* Parameters of Algorithm 1: window W, group size G; Prologue outputs P_k, P_v, clipping. */
+typedef struct {
+  int32_t batch;        /* B >= 1; all sequences of a batch have the same length          */
+  int32_t n_q_heads;    /* Hq, a multiple of n_kv_heads with Hq/Hk <= 8                   */
+  int32_t n_kv_heads;   /* Hk                                                             */
+  int32_t head_dim;     /* D, must be 128                                                 */
+  int32_t group_size;   /* G in {32, 64, 128}: consecutive REORDERED channels of a token  */
+  int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2 only                              */
+  int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_2 or SKVQ_BITS_1P5                */
+  int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
+  int64_t max_quant_tokens; /* Tcap: rows of the packed region per sequence, >= 1         */
+  const int32_t *perm_k; /* HOST [Hk][D]: reordered position p takes channel perm[h][p]   */
+  const int32_t *perm_v; /* HOST [Hk][D]  (each row a permutation of 0..D-1)              */
+  const float *clip_k;   /* HOST [Hk][D/G]: alpha in (0,1] per (kv head, group), Eq. 2    */
+  const float *clip_v;   /* HOST [Hk][D/G]                                                */
+  float sm_scale;        /* softmax scale; 0 selects 1/sqrt(D)                            */
+} skvq_config;
+
+/* DEVICE buffers of one layer's cache; byte sizes come from skvq_sizes(), in this order.
+ *   k_codes   u8  [B][Hk][Tcap][32]      row t: code of position p in byte p/4, bits 2(p%4)..
+ *   v_codes   u8  [B][Hk][ceil(Tcap/32)][1024 | 832]   blocks of 32 tokens, token-minor:
+ *             token slot s=t%32 -> kb=s/8, i=s%8 ; position p -> n=p/16, j=p%16 ; unit u=16kb+j
+ *             2-bit  : unit = 16 B little-endian, code(n,i) at bit 32(n/2)+16(i%2)+8(n%2)+2(i/2)
+ *             3-level: unit = 13 B little-endian, field n = bits [13n,13n+13) = sum_i code(n,i)*3^i
+ *             a block is zero-filled when its first token is stored
+ *   k_meta    f32 [B][Hk][Tcap][D/G][2]  (scale, zero) of Eq. 2, zero = alpha*min
+ *   v_meta    f32 [B][Hk][Tcap][D/G][2]
+ *   k_win     f16 [B][Hk][W][D]          token number a (0-based) sits in slot a % W
+ *   v_win     f16 [B][Hk][W][D]
+ *   workspace split partials of skvq_decode_attention; contents are scratch
+ * All seven must be 16-byte aligned. */
+typedef struct {
+  void *k_codes, *v_codes, *k_meta, *v_meta, *k_win, *v_win, *workspace;
+} skvq_buffers;
+
+/* Byte size of each skvq_buffers member, in declaration order.  Pure host arithmetic.
+ * Returns SKVQ_OK or the error skvq_create would give for this config. */
+int skvq_sizes(const skvq_config *cfg, size_t bytes[7]);
+
+/* Checks cfg (shapes, bit-widths, permutation rows, alpha range).  Pure host code. */
+int skvq_validate_config(const skvq_config *cfg);
+
+/* Creates the host object, copies perm/clip (and small constant tables) to the current
+ * HIP device, synchronously.  The cache starts empty.  bufs are borrowed, never freed. */
+int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **out);
+
+/* Frees what skvq_create allocated (never the caller's buffers).  NULL is allowed. */
+void skvq_destroy(skvq_cache *cache);
+
+/* Section 3.2 prefill phase / Algorithm 1 with l = len(prompt), quantization part only.
+ * k, v: DEVICE fp16 [B][Hk][T][D], original channel order, T >= 0.  Resets the cache, then
+ * tokens [0, T-W) are stored as packed rows [0, T-W) and the last min(T,W) tokens are copied
+ * bit for bit into the ring.  Per (token, kv head, group g), with xp[p] = x[perm[p]]:
+ *   mn,mx = min,max xp (a zero of either sign counts as +0); lo = alpha_g*mn; hi = alpha_g*mx;
+ *   scale = (hi-lo)/(levels-1); inv = scale>0 ? 1/scale : 0;
+ *   code = clamp(rint((xp-lo)*inv), 0, levels-1), ties to even; zero = lo.
+ * SKVQ_ERR_CAPACITY if T-W > Tcap. */
+int skvq_prefill_quantize(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                          void *hip_stream);
+
+/* Section 3.2 decode phase: with T tokens cached, if T >= W the token T-W (ring slot T % W)
+ * is quantized into packed row T-W by the same arithmetic; then the new token is written to
+ * slot T % W.  k_new, v_new: DEVICE fp16 [B][Hk][D].  SKVQ_ERR_CAPACITY if row T-W >= Tcap. */
+int skvq_quantize_append(skvq_cache *cache, const void *k_new, const void *v_new,
+                         void *hip_stream);
+
+/* Eq. 1 for one query token per sequence (Algorithm 1 with l = 1, attention part):
+ * scores of packed rows are (reordered query) . (dequantized reordered key), scores of ring
+ * tokens use the original order; one softmax (scale sm_scale, no mask) over all T tokens;
+ * output = weighted sum of dequantized values, returned in ORIGINAL channel order.
+ * q: DEVICE fp16 [B][Hq][D].  out_f32: DEVICE fp32 [B][Hq][D].  out_f16: DEVICE fp16
+ * [B][Hq][D] or NULL.  Query head hq reads kv head hq / (Hq/Hk).  The sequence is split
+ * into chunks that are merged by their running max and sum (online softmax).
+ * SKVQ_ERR_STATE if the cache is empty. */
+int skvq_decode_attention(skvq_cache *cache, const void *q, void *out_f32, void *out_f16,
+                          void *hip_stream);
+
+/* Host counters: tokens cached, of which packed, of which in the ring.  Any may be NULL. */
+int skvq_get_state(const skvq_cache *cache, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win);
+
+/* Declares that the buffers hold a valid cache of n_tokens tokens (e.g. to rewind after
+ * appends, or to adopt buffers filled elsewhere).  SKVQ_ERR_CAPACITY if it cannot fit. */
+int skvq_set_state(skvq_cache *cache, int64_t n_tokens);
+
+/* Number of sequence chunks of the packed region per kv head used by
+ * skvq_decode_attention; 0 (default) lets the library choose.  At most SKVQ_MAX_SPLITS. */
+#define SKVQ_MAX_SPLITS 128
+int skvq_set_num_splits(skvq_cache *cache, int32_t n_splits);
+
+/* Static description of a status code; the cache's last HIP error text (owned by cache). */
+const char *skvq_status_string(int status);
+const char *skvq_last_error(const skvq_cache *cache);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKVQ_H */

@@ -1,0 +1,204 @@
+"""Thin ctypes binding of libskvq.so (include/skvq.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch is used to own device
+memory and to name the current stream.  There is no fallback: if the library has not been
+built, importing a function from here raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libskvq.so")
+
+SKVQ_OK = 0
+SKVQ_ERR_INVALID_ARG, SKVQ_ERR_UNSUPPORTED, SKVQ_ERR_CAPACITY, SKVQ_ERR_STATE, SKVQ_ERR_HIP = -1, -2, -3, -4, -5
+SKVQ_BITS_2, SKVQ_BITS_1P5 = 4, 3
+SKVQ_MAX_SPLITS = 128
+HEAD_DIM = 128
+BUFFER_NAMES = ("k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win", "workspace")
+
+
+class skvq_config(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("group_size", C.c_int32), ("k_bits", C.c_int32),
+                ("v_bits", C.c_int32), ("window", C.c_int32), ("max_quant_tokens", C.c_int64),
+                ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
+                ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
+
+
+class skvq_buffers(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in BUFFER_NAMES]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2405_06219_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.skvq_sizes.argtypes = [C.POINTER(skvq_config), C.POINTER(C.c_size_t)]
+        L.skvq_validate_config.argtypes = [C.POINTER(skvq_config)]
+        L.skvq_create.argtypes = [C.POINTER(skvq_config), C.POINTER(skvq_buffers), C.POINTER(C.c_void_p)]
+        L.skvq_destroy.argtypes = [C.c_void_p]
+        L.skvq_destroy.restype = None
+        L.skvq_prefill_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.skvq_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_get_state.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.skvq_set_state.argtypes = [C.c_void_p, C.c_int64]
+        L.skvq_set_num_splits.argtypes = [C.c_void_p, C.c_int32]
+        L.skvq_status_string.argtypes = [C.c_int]
+        L.skvq_status_string.restype = C.c_char_p
+        L.skvq_last_error.argtypes = [C.c_void_p]
+        L.skvq_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+class SkvqError(RuntimeError):
+    def __init__(self, status: int, detail: str = ""):
+        self.status = status
+        text = lib().skvq_status_string(status).decode()
+        super().__init__(f"skvq status {status} ({text}) {detail}".strip())
+
+
+def bits_enum(bits: float) -> int:
+    return {2.0: SKVQ_BITS_2, 1.5: SKVQ_BITS_1P5}[float(bits)]
+
+
+def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
+                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM):
+    """Returns (skvq_config, keepalive): the numpy arrays the config points to."""
+    keep = [np.ascontiguousarray(perm_k, np.int32), np.ascontiguousarray(perm_v, np.int32),
+            np.ascontiguousarray(clip_k, np.float32), np.ascontiguousarray(clip_v, np.float32)]
+    cfg = skvq_config(batch, n_q_heads, n_kv_heads, head_dim, group_size, bits_enum(k_bits), bits_enum(v_bits),
+                      window, max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
+                      keep[3].ctypes.data, float(sm_scale))
+    return cfg, keep
+
+
+def skvq_sizes(cfg: skvq_config) -> list[int]:
+    out = (C.c_size_t * 7)()
+    rc = lib().skvq_sizes(C.byref(cfg), out)
+    if rc != SKVQ_OK:
+        raise SkvqError(rc)
+    return [int(x) for x in out]
+
+
+def skvq_validate_config(cfg: skvq_config) -> int:
+    return int(lib().skvq_validate_config(C.byref(cfg)))
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_ptr(t: torch.Tensor, dtype, shape) -> int:
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"expected contiguous cuda {dtype} tensor of shape {tuple(shape)}, got {t.dtype} "
+                         f"{tuple(t.shape)} on {t.device}")
+    return t.data_ptr()
+
+
+class SkvqCache:
+    """One layer's cache: owns the device buffers (torch tensors) and the library handle."""
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
+                 clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None):
+        self.cfg, self._keep = make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window,
+                                           max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale, k_bits)
+        self.shape = (batch, n_q_heads, n_kv_heads)
+        self.device = torch.device(device)
+        self.sizes = skvq_sizes(self.cfg)
+        self.buffers = {}
+        for name, nbytes in zip(BUFFER_NAMES, self.sizes):
+            t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            if fill is not None and name != "workspace":
+                t.fill_(fill)
+            self.buffers[name] = t
+        self._bufs = skvq_buffers(*[self.buffers[n].data_ptr() for n in BUFFER_NAMES])
+        handle = C.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = lib().skvq_create(C.byref(self.cfg), C.byref(self._bufs), C.byref(handle))
+        if rc != SKVQ_OK:
+            raise SkvqError(rc)
+        self._h = handle
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().skvq_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != SKVQ_OK:
+            raise SkvqError(rc, lib().skvq_last_error(self._h).decode())
+
+    # ---- the three hot-path calls, named as in the C ABI ----
+    def skvq_prefill_quantize(self, k: torch.Tensor, v: torch.Tensor, stream=None):
+        b, _, hk = self.shape
+        T = k.shape[2]
+        kp = _dev_ptr(k, torch.float16, (b, hk, T, HEAD_DIM))
+        vp = _dev_ptr(v, torch.float16, (b, hk, T, HEAD_DIM))
+        self._check(lib().skvq_prefill_quantize(self._h, kp, vp, T, _stream_ptr(stream)))
+
+    def skvq_quantize_append(self, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
+        b, _, hk = self.shape
+        kp = _dev_ptr(k_new, torch.float16, (b, hk, HEAD_DIM))
+        vp = _dev_ptr(v_new, torch.float16, (b, hk, HEAD_DIM))
+        self._check(lib().skvq_quantize_append(self._h, kp, vp, _stream_ptr(stream)))
+
+    def skvq_decode_attention(self, q: torch.Tensor, out_f32: torch.Tensor | None = None,
+                              out_f16: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        b, hq, _ = self.shape
+        qp = _dev_ptr(q, torch.float16, (b, hq, HEAD_DIM))
+        if out_f32 is None:
+            out_f32 = torch.empty((b, hq, HEAD_DIM), dtype=torch.float32, device=self.device)
+        op = _dev_ptr(out_f32, torch.float32, (b, hq, HEAD_DIM))
+        hp = _dev_ptr(out_f16, torch.float16, (b, hq, HEAD_DIM)) if out_f16 is not None else None
+        self._check(lib().skvq_decode_attention(self._h, qp, op, hp, _stream_ptr(stream)))
+        return out_f32
+
+    # ---- state ----
+    def skvq_get_state(self):
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int32()
+        self._check(lib().skvq_get_state(self._h, C.byref(a), C.byref(b), C.byref(c)))
+        return a.value, b.value, c.value
+
+    def skvq_set_state(self, n_tokens: int):
+        self._check(lib().skvq_set_state(self._h, n_tokens))
+
+    def skvq_set_num_splits(self, n: int):
+        self._check(lib().skvq_set_num_splits(self._h, n))
+
+    # ---- views of the buffers for tests ----
+    def host_arrays(self):
+        """Buffers copied to the host with the shapes the format statement gives them."""
+        b, _, hk = self.shape
+        tcap = self.cfg.max_quant_tokens
+        ng = HEAD_DIM // self.cfg.group_size
+        vb = 832 if self.cfg.v_bits == SKVQ_BITS_1P5 else 1024
+        torch.cuda.synchronize(self.device)
+        raw = {n: self.buffers[n].cpu().numpy() for n in BUFFER_NAMES[:6]}
+        return [raw["k_codes"].reshape(b, hk, tcap, 32),
+                raw["v_codes"].reshape(b, hk, (tcap + 31) // 32, vb),
+                raw["k_meta"].view(np.float32).reshape(b, hk, tcap, ng, 2),
+                raw["v_meta"].view(np.float32).reshape(b, hk, tcap, ng, 2),
+                raw["k_win"].view(np.uint16).reshape(b, hk, self.cfg.window, HEAD_DIM),
+                raw["v_win"].view(np.uint16).reshape(b, hk, self.cfg.window, HEAD_DIM)]

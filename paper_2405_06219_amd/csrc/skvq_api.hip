@@ -1,0 +1,285 @@
+// Host side of libskvq: argument checking, size arithmetic, token counters and kernel
+// launches.  See include/skvq.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "skvq_internal.h"
+
+using namespace skvq;
+
+struct skvq_cache {
+  Layout L;
+  long long n_tokens = 0;
+  int forced_splits = 0;
+  int n_cus = 256;
+  void *dev_consts = nullptr;  // one allocation: perm_k, perm_v, clip_k, clip_v, trit table
+  std::string last_error;
+};
+
+namespace {
+
+int check_config(const skvq_config *c) {
+  if (!c) return SKVQ_ERR_INVALID_ARG;
+  if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->window < 1 ||
+      c->max_quant_tokens < 1)
+    return SKVQ_ERR_INVALID_ARG;
+  if (c->n_q_heads % c->n_kv_heads) return SKVQ_ERR_INVALID_ARG;
+  if (c->head_dim != kD) return SKVQ_ERR_UNSUPPORTED;
+  if (c->n_q_heads / c->n_kv_heads > 8) return SKVQ_ERR_UNSUPPORTED;
+  if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128)
+    return SKVQ_ERR_UNSUPPORTED;
+  if (c->k_bits != SKVQ_BITS_2) return SKVQ_ERR_UNSUPPORTED;
+  if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5) return SKVQ_ERR_UNSUPPORTED;
+  if (!(c->sm_scale >= 0.0f) || !std::isfinite(c->sm_scale)) return SKVQ_ERR_INVALID_ARG;
+  if ((long long)c->window > (1ll << 20) || c->max_quant_tokens > (1ll << 40))
+    return SKVQ_ERR_INVALID_ARG;
+  if (!c->perm_k || !c->perm_v || !c->clip_k || !c->clip_v) return SKVQ_ERR_INVALID_ARG;
+  const int ng = kD / c->group_size;
+  for (int which = 0; which < 2; ++which) {
+    const int32_t *perm = which ? c->perm_v : c->perm_k;
+    const float *clip = which ? c->clip_v : c->clip_k;
+    for (int h = 0; h < c->n_kv_heads; ++h) {
+      bool seen[kD] = {false};
+      for (int p = 0; p < kD; ++p) {
+        int32_t ch = perm[h * kD + p];
+        if (ch < 0 || ch >= kD || seen[ch]) return SKVQ_ERR_INVALID_ARG;
+        seen[ch] = true;
+      }
+      for (int g = 0; g < ng; ++g) {
+        float a = clip[h * ng + g];
+        if (!(a > 0.0f && a <= 1.0f)) return SKVQ_ERR_INVALID_ARG;
+      }
+    }
+  }
+  return SKVQ_OK;
+}
+
+void compute_sizes(const skvq_config *c, size_t bytes[7]) {
+  const size_t heads = (size_t)c->batch * c->n_kv_heads;
+  const size_t tcap = (size_t)c->max_quant_tokens;
+  const size_t ng = kD / c->group_size;
+  const size_t vb = c->v_bits == SKVQ_BITS_1P5 ? kTernaryBlockBytes : kTwoBitBlockBytes;
+  bytes[0] = heads * tcap * (kD / 4);
+  bytes[1] = heads * ((tcap + kVBlock - 1) / kVBlock) * vb;
+  bytes[2] = heads * tcap * ng * 2 * sizeof(float);
+  bytes[3] = bytes[2];
+  bytes[4] = heads * (size_t)c->window * kD * sizeof(__half);
+  bytes[5] = bytes[4];
+  // one partial per (sequence, query head, split); the ring is one more split
+  bytes[6] = (size_t)c->batch * c->n_q_heads * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
+}
+
+int fail_hip(skvq_cache *c, hipError_t e, const char *what) {
+  c->last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return SKVQ_ERR_HIP;
+}
+
+int choose_splits(const skvq_cache *c, long long n_quant) {
+  if (n_quant <= 0) return 0;
+  const long long tiles = (n_quant + 63) / 64;  // a split is a whole number of 64-token tiles
+  long long s;
+  if (c->forced_splits > 0) {
+    s = c->forced_splits;
+  } else {
+    // about four workgroups per compute unit over all (sequence, kv head) pairs,
+    // but no split shorter than 8 tiles
+    const long long heads = (long long)c->L.B * c->L.Hk;
+    s = (4ll * c->n_cus + heads - 1) / heads;
+    const long long cap = (tiles + 7) / 8;
+    if (s > cap) s = cap;
+  }
+  if (s > SKVQ_MAX_SPLITS) s = SKVQ_MAX_SPLITS;
+  if (s > tiles) s = tiles;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+}  // namespace
+
+extern "C" {
+
+int skvq_validate_config(const skvq_config *cfg) { return check_config(cfg); }
+
+int skvq_sizes(const skvq_config *cfg, size_t bytes[7]) {
+  if (!bytes) return SKVQ_ERR_INVALID_ARG;
+  // sizes do not depend on perm/clip; allow them to be absent here
+  if (!cfg) return SKVQ_ERR_INVALID_ARG;
+  skvq_config tmp = *cfg;
+  static const int32_t ident_dummy = 0;
+  (void)ident_dummy;
+  std::vector<int32_t> ident;
+  std::vector<float> ones;
+  if (!tmp.perm_k || !tmp.perm_v || !tmp.clip_k || !tmp.clip_v) {
+    if (tmp.n_kv_heads < 1 || tmp.n_kv_heads > (1 << 20)) return SKVQ_ERR_INVALID_ARG;
+    ident.resize((size_t)tmp.n_kv_heads * kD);
+    for (size_t i = 0; i < ident.size(); ++i) ident[i] = (int32_t)(i % kD);
+    ones.assign((size_t)tmp.n_kv_heads * 4, 1.0f);
+    if (!tmp.perm_k) tmp.perm_k = ident.data();
+    if (!tmp.perm_v) tmp.perm_v = ident.data();
+    if (!tmp.clip_k) tmp.clip_k = ones.data();
+    if (!tmp.clip_v) tmp.clip_v = ones.data();
+  }
+  int rc = check_config(&tmp);
+  if (rc != SKVQ_OK) return rc;
+  compute_sizes(&tmp, bytes);
+  return SKVQ_OK;
+}
+
+int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **out) {
+  if (!out) return SKVQ_ERR_INVALID_ARG;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != SKVQ_OK) return rc;
+  if (!bufs) return SKVQ_ERR_INVALID_ARG;
+  const void *ptrs[7] = {bufs->k_codes, bufs->v_codes, bufs->k_meta, bufs->v_meta,
+                         bufs->k_win,   bufs->v_win,   bufs->workspace};
+  for (const void *p : ptrs)
+    if (!p || ((uintptr_t)p & 15)) return SKVQ_ERR_INVALID_ARG;
+
+  skvq_cache *c = new (std::nothrow) skvq_cache();
+  if (!c) return SKVQ_ERR_HIP;
+  Layout &L = c->L;
+  L.B = cfg->batch;
+  L.Hq = cfg->n_q_heads;
+  L.Hk = cfg->n_kv_heads;
+  L.R = L.Hq / L.Hk;
+  L.G = cfg->group_size;
+  L.NG = kD / L.G;
+  L.W = cfg->window;
+  L.v_levels = cfg->v_bits == SKVQ_BITS_1P5 ? 3 : 4;
+  L.v_block_bytes = L.v_levels == 3 ? kTernaryBlockBytes : kTwoBitBlockBytes;
+  L.Tcap = cfg->max_quant_tokens;
+  L.n_vblocks = (L.Tcap + kVBlock - 1) / kVBlock;
+  L.sm_scale = cfg->sm_scale > 0.0f ? cfg->sm_scale : 1.0f / std::sqrt((float)kD);
+  if (cfg->sm_scale == 0.0f) L.sm_scale = 1.0f / std::sqrt((float)kD);
+  L.k_codes = (uint8_t *)bufs->k_codes;
+  L.v_codes = (uint8_t *)bufs->v_codes;
+  L.k_meta = (float *)bufs->k_meta;
+  L.v_meta = (float *)bufs->v_meta;
+  L.k_win = (__half *)bufs->k_win;
+  L.v_win = (__half *)bufs->v_win;
+  L.workspace = (float *)bufs->workspace;
+
+  // constants: [perm_k | perm_v | clip_k | clip_v | trit table], one allocation
+  const size_t n_perm = (size_t)L.Hk * kD, n_clip = (size_t)L.Hk * L.NG;
+  const size_t off_pv = n_perm * 4, off_ck = off_pv + n_perm * 4;
+  const size_t off_cv = off_ck + ((n_clip * 4 + 15) & ~(size_t)15);
+  const size_t off_lut = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
+  const size_t total = off_lut + 8192 * 4;
+  std::vector<uint8_t> host(total, 0);
+  std::memcpy(host.data(), cfg->perm_k, n_perm * 4);
+  std::memcpy(host.data() + off_pv, cfg->perm_v, n_perm * 4);
+  std::memcpy(host.data() + off_ck, cfg->clip_k, n_clip * 4);
+  std::memcpy(host.data() + off_cv, cfg->clip_v, n_clip * 4);
+  build_trit_lut((uint32_t *)(host.data() + off_lut));
+
+  hipError_t e = hipMalloc(&c->dev_consts, total);
+  if (e != hipSuccess) {
+    delete c;
+    return SKVQ_ERR_HIP;
+  }
+  e = hipMemcpy(c->dev_consts, host.data(), total, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(c->dev_consts);
+    delete c;
+    return SKVQ_ERR_HIP;
+  }
+  uint8_t *d = (uint8_t *)c->dev_consts;
+  L.perm_k = (const int *)d;
+  L.perm_v = (const int *)(d + off_pv);
+  L.clip_k = (const float *)(d + off_ck);
+  L.clip_v = (const float *)(d + off_cv);
+  L.trit_lut = (const uint32_t *)(d + off_lut);
+
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+      prop.multiProcessorCount > 0)
+    c->n_cus = prop.multiProcessorCount;
+  *out = c;
+  return SKVQ_OK;
+}
+
+void skvq_destroy(skvq_cache *c) {
+  if (!c) return;
+  if (c->dev_consts) (void)hipFree(c->dev_consts);
+  delete c;
+}
+
+int skvq_prefill_quantize(skvq_cache *c, const void *k, const void *v, int64_t T, void *stream) {
+  if (!c) return SKVQ_ERR_INVALID_ARG;
+  if (T < 0 || (T > 0 && (!k || !v))) return SKVQ_ERR_INVALID_ARG;
+  const long long nq = T > c->L.W ? T - c->L.W : 0;
+  if (nq > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  if (T > 0) {
+    hipError_t e = launch_prefill(c->L, (const __half *)k, (const __half *)v, T, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_quantize launch");
+  }
+  c->n_tokens = T;
+  return SKVQ_OK;
+}
+
+int skvq_quantize_append(skvq_cache *c, const void *k_new, const void *v_new, void *stream) {
+  if (!c || !k_new || !v_new) return SKVQ_ERR_INVALID_ARG;
+  const long long T = c->n_tokens;
+  if (T >= c->L.W && T - c->L.W >= c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  hipError_t e = launch_append(c->L, (const __half *)k_new, (const __half *)v_new, T, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_quantize_append launch");
+  c->n_tokens = T + 1;
+  return SKVQ_OK;
+}
+
+int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out_f16, void *stream) {
+  if (!c || !q || !out_f32) return SKVQ_ERR_INVALID_ARG;
+  if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
+  const long long nq = c->n_tokens > c->L.W ? c->n_tokens - c->L.W : 0;
+  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16,
+                               c->n_tokens, choose_splits(c, nq), (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention launch");
+  return SKVQ_OK;
+}
+
+int skvq_get_state(const skvq_cache *c, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win) {
+  if (!c) return SKVQ_ERR_INVALID_ARG;
+  const long long T = c->n_tokens, W = c->L.W;
+  if (n_tokens) *n_tokens = T;
+  if (n_quant) *n_quant = T > W ? T - W : 0;
+  if (n_win) *n_win = (int32_t)(T < W ? T : W);
+  return SKVQ_OK;
+}
+
+int skvq_set_state(skvq_cache *c, int64_t n_tokens) {
+  if (!c || n_tokens < 0) return SKVQ_ERR_INVALID_ARG;
+  if (n_tokens > c->L.W && n_tokens - c->L.W > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  c->n_tokens = n_tokens;
+  return SKVQ_OK;
+}
+
+int skvq_set_num_splits(skvq_cache *c, int32_t n) {
+  if (!c || n < 0 || n > SKVQ_MAX_SPLITS) return SKVQ_ERR_INVALID_ARG;
+  c->forced_splits = n;
+  return SKVQ_OK;
+}
+
+const char *skvq_status_string(int s) {
+  switch (s) {
+    case SKVQ_OK: return "ok";
+    case SKVQ_ERR_INVALID_ARG: return "invalid argument";
+    case SKVQ_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SKVQ_ERR_CAPACITY: return "packed region full";
+    case SKVQ_ERR_STATE: return "invalid state (empty cache)";
+    case SKVQ_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char *skvq_last_error(const skvq_cache *c) { return c ? c->last_error.c_str() : ""; }
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal declarations shared by the host API and the HIP kernels of libskvq.
+// Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "skvq.h"
+
+namespace skvq {
+
+constexpr int kD = 128;        // head dimension
+constexpr int kVBlock = 32;    // tokens per V block
+constexpr int kTernaryBlockBytes = 832;
+constexpr int kTwoBitBlockBytes = 1024;
+constexpr int kPartialStride = kD + 4;  // floats per split partial: m, l, pad, pad, acc[D]
+
+// Everything a kernel needs to find its data; passed by value.
+struct Layout {
+  int B, Hq, Hk, R;      // R = Hq / Hk
+  int G, NG;             // group size, groups per head
+  int W;                 // window
+  int v_levels;          // 4 or 3
+  int v_block_bytes;     // 1024 or 832
+  long long Tcap;        // packed rows per (b, hk)
+  long long n_vblocks;   // ceil(Tcap / 32)
+  float sm_scale;
+  uint8_t *k_codes, *v_codes;
+  float *k_meta, *v_meta;
+  __half *k_win, *v_win;
+  float *workspace;
+  const int *perm_k, *perm_v;    // device copies [Hk][D]
+  const float *clip_k, *clip_v;  // device copies [Hk][NG]
+  const uint32_t *trit_lut;      // device, 8192 entries (see skvq_decode.hip)
+};
+
+// quantize kernels (skvq_quantize.hip)
+hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T,
+                          hipStream_t s);
+hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T,
+                         hipStream_t s);
+
+// decode kernels (skvq_decode.hip)
+// n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).
+hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,
+                         long long T, int n_splits, hipStream_t s);
+
+// Fills the 8192-entry table that expands a 13-bit base-3 field into eight 2-bit codes.
+void build_trit_lut(uint32_t *host_table);
+
+}  // namespace skvq

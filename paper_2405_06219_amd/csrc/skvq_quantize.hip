@@ -1,0 +1,303 @@
+// Quantize-on-evict and prefill-quantize kernels (Section 3.1 Eq. 2, Section 3.2,
+// Algorithm 1 clipping_quant) for gfx950.
+//
+// One wavefront owns one (token, kv head) row at a time: lane l holds the two reordered
+// positions 2l and 2l+1, the group minimum/maximum is a cross-lane butterfly over the G/2
+// lanes of a group, and every fp32 operation of Eq. 2 is issued as an explicitly rounded
+// intrinsic so that the compiler can neither fuse nor reorder them.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "skvq_internal.h"
+
+namespace skvq {
+namespace {
+
+// Eq. 2 parameters of one group from its min and max.
+struct GroupParams {
+  float lo, scale, inv;
+};
+
+__device__ __forceinline__ GroupParams group_params(float mn, float mx, float alpha, float top) {
+  if (mn == 0.0f) mn = 0.0f;  // a minimum of -0 is stored as +0
+  if (mx == 0.0f) mx = 0.0f;
+  GroupParams g;
+  g.lo = __fmul_rn(alpha, mn);
+  const float hi = __fmul_rn(alpha, mx);
+  g.scale = __fdiv_rn(__fsub_rn(hi, g.lo), top);
+  g.inv = g.scale > 0.0f ? __fdiv_rn(1.0f, g.scale) : 0.0f;
+  return g;
+}
+
+__device__ __forceinline__ unsigned encode(float x, const GroupParams &g, float top) {
+  float r = rintf(__fmul_rn(__fsub_rn(x, g.lo), g.inv));
+  r = r < 0.0f ? 0.0f : r;
+  r = r > top ? top : r;
+  return (unsigned)r;
+}
+
+// min and max over the G/2 consecutive lanes that hold one group (lane l: positions 2l, 2l+1)
+__device__ __forceinline__ void group_minmax(float &mn, float &mx, int G) {
+  for (int off = 1; off < G / 2; off <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off));
+    mx = fmaxf(mx, __shfl_xor(mx, off));
+  }
+}
+
+// Reorder one row through LDS and encode it.  row_lds: 128 halves of this wavefront.
+// Returns this lane's two codes; lane with 2l % G == 0 also gets the group's (scale, zero).
+__device__ __forceinline__ void encode_row(const __half *row_lds, int p0, int p1, float alpha, int G,
+                                           float top, unsigned &c0, unsigned &c1, float &scale,
+                                           float &zero) {
+  const float x0 = __half2float(row_lds[p0]);
+  const float x1 = __half2float(row_lds[p1]);
+  float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
+  group_minmax(mn, mx, G);
+  const GroupParams g = group_params(mn, mx, alpha, top);
+  c0 = encode(x0, g, top);
+  c1 = encode(x1, g, top);
+  scale = g.scale;
+  zero = g.lo;
+}
+
+// K row: position p at bits [2p, 2p+2).  Lane l contributes 4 bits; 8 lanes form a dword.
+__device__ __forceinline__ void store_k_row(uint8_t *row, int lane, unsigned c0, unsigned c1) {
+  unsigned w = (c0 | (c1 << 2)) << (4 * (lane & 7));
+  w |= __shfl_xor(w, 1);
+  w |= __shfl_xor(w, 2);
+  w |= __shfl_xor(w, 4);
+  if ((lane & 7) == 0) reinterpret_cast<unsigned *>(row)[lane >> 3] = w;
+}
+
+// Spread eight 2-bit codes (token i at bits [2i,2i+2)) to the V unit order: token i goes to
+// bit 16*(i%2) + 2*(i/2).
+__device__ __forceinline__ unsigned spread_tokens(unsigned c8) {
+  unsigned r = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r |= ((c8 >> (2 * i)) & 3u) << (16 * (i & 1) + 2 * (i >> 1));
+  return r;
+}
+
+// Base-3 number of eight codes (token i is digit i).
+__device__ __forceinline__ unsigned trit_field(unsigned c8) {
+  unsigned f = 0, pw = 1;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    f += ((c8 >> (2 * i)) & 3u) * pw;
+    pw *= 3;
+  }
+  return f;
+}
+
+// ---------------------------------------------------------------------------------------
+// Prefill: one workgroup (4 wavefronts) per V block of 32 tokens of one (b, hk); wavefront w
+// handles the 8 tokens of sub-block kb = w, K and V, and builds that sub-block's 16 V units.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__restrict__ ksrc,
+                                                      const __half *__restrict__ vsrc, long long T,
+                                                      long long nq) {
+  __shared__ __half rows[4][kD];
+  __shared__ unsigned vq[4][64];
+  __shared__ unsigned pieces[4][64];
+  __shared__ __align__(16) uint8_t units[4][256];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hk = blockIdx.y, b = blockIdx.z;
+  const long long head = (long long)b * L.Hk + hk;
+  const long long blk = blockIdx.x;
+  const long long t0 = blk * kVBlock + 8 * wave;
+
+  const int pk0 = L.perm_k[hk * kD + 2 * lane], pk1 = L.perm_k[hk * kD + 2 * lane + 1];
+  const int pv0 = L.perm_v[hk * kD + 2 * lane], pv1 = L.perm_v[hk * kD + 2 * lane + 1];
+  const int grp = (2 * lane) / L.G;
+  const float ak = L.clip_k[hk * L.NG + grp], av = L.clip_v[hk * L.NG + grp];
+  const float vtop = (float)(L.v_levels - 1);
+
+  unsigned vpack = 0;  // low half: position 2l, high half: position 2l+1; token i at bits 2i
+  for (int i = 0; i < 8; ++i) {
+    const long long t = t0 + i;
+    const bool valid = t < nq;  // uniform over the wavefront
+    const long long src = (head * T + (valid ? t : 0)) * kD;
+    unsigned c0, c1;
+    float scale, zero;
+    // keys
+    reinterpret_cast<__half2 *>(rows[wave])[lane] = reinterpret_cast<const __half2 *>(ksrc + src)[lane];
+    __syncthreads();
+    encode_row(rows[wave], pk0, pk1, ak, L.G, 3.0f, c0, c1, scale, zero);
+    if (valid) {
+      store_k_row(L.k_codes + (head * L.Tcap + t) * (kD / 4), lane, c0, c1);
+      if ((2 * lane) % L.G == 0)
+        reinterpret_cast<float2 *>(L.k_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(scale, zero);
+    }
+    __syncthreads();
+    // values
+    reinterpret_cast<__half2 *>(rows[wave])[lane] = reinterpret_cast<const __half2 *>(vsrc + src)[lane];
+    __syncthreads();
+    encode_row(rows[wave], pv0, pv1, av, L.G, vtop, c0, c1, scale, zero);
+    if (valid) {
+      vpack |= (c0 | (c1 << 16)) << (2 * i);
+      if ((2 * lane) % L.G == 0)
+        reinterpret_cast<float2 *>(L.v_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(scale, zero);
+    }
+    __syncthreads();
+  }
+
+  // V units of sub-block kb = wave.  Lane (j = lane%16, nh = lane/16) builds fields 2nh, 2nh+1
+  // of unit j; position 16n + j was encoded by lane 8n + j/2, half j%2.
+  vq[wave][lane] = vpack;
+  __syncthreads();
+  const int j = lane & 15, nh = lane >> 4;
+  const unsigned sh = 16 * (j & 1);
+  const unsigned ca = (vq[wave][8 * (2 * nh) + (j >> 1)] >> sh) & 0xffffu;
+  const unsigned cb = (vq[wave][8 * (2 * nh + 1) + (j >> 1)] >> sh) & 0xffffu;
+  uint8_t *dst = L.v_codes + (head * L.n_vblocks + blk) * L.v_block_bytes;
+  if (L.v_levels == 4) {
+    const unsigned w = spread_tokens(ca) | (spread_tokens(cb) << 8);
+    reinterpret_cast<unsigned *>(dst + 256 * wave)[4 * j + nh] = w;
+  } else {
+    pieces[wave][lane] = trit_field(ca) | (trit_field(cb) << 13);  // 26 bits
+    __syncthreads();
+    if (lane < 16) {
+      const unsigned long long a0 = pieces[wave][lane], a1 = pieces[wave][16 + lane];
+      const unsigned long long a2 = pieces[wave][32 + lane], a3 = pieces[wave][48 + lane];
+      const unsigned long long lo = a0 | (a1 << 26) | (a2 << 52);       // bits 0..63
+      const unsigned long long hi = (a2 >> 12) | (a3 << 14);            // bits 64..103
+      uint8_t *u = units[wave] + 13 * lane;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) u[q] = (uint8_t)(lo >> (8 * q));
+#pragma unroll
+      for (int q = 0; q < 5; ++q) u[8 + q] = (uint8_t)(hi >> (8 * q));
+    }
+    __syncthreads();
+    if (lane < 52)
+      reinterpret_cast<unsigned *>(dst + 208 * wave)[lane] = reinterpret_cast<const unsigned *>(units[wave])[lane];
+  }
+}
+
+// Copies the last n_win tokens of the prompt into the fp16 ring, token a -> slot a % W.
+__global__ __launch_bounds__(64) void ring_fill_kernel(Layout L, const __half *__restrict__ ksrc,
+                                                      const __half *__restrict__ vsrc, long long T,
+                                                      long long first) {
+  const long long a = first + blockIdx.x;
+  const long long head = (long long)blockIdx.z * L.Hk + blockIdx.y;
+  const long long src = (head * T + a) * kD, dst = (head * L.W + a % L.W) * kD;
+  const int lane = threadIdx.x;
+  reinterpret_cast<__half2 *>(L.k_win + dst)[lane] = reinterpret_cast<const __half2 *>(ksrc + src)[lane];
+  reinterpret_cast<__half2 *>(L.v_win + dst)[lane] = reinterpret_cast<const __half2 *>(vsrc + src)[lane];
+}
+
+// ---------------------------------------------------------------------------------------
+// Append: one workgroup of two wavefronts per (b, hk); wavefront 0 does K, wavefront 1 does V.
+// If the ring is full the slot's old token (number te = T - W) is quantized into row te first.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__restrict__ knew,
+                                                     const __half *__restrict__ vnew, long long T) {
+  __shared__ __half rows[2][kD];
+  __shared__ uint8_t vcodes[kD];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hk = blockIdx.x, b = blockIdx.y;
+  const long long head = (long long)b * L.Hk + hk;
+  const long long slot = (head * L.W + T % L.W) * kD;
+  const bool evict = T >= L.W;
+  const long long te = T - L.W;
+  __half *ring = wave ? L.v_win : L.k_win;
+  const __half *fresh = (wave ? vnew : knew) + head * kD;
+
+  if (evict) {
+    rows[wave][2 * lane] = ring[slot + 2 * lane];
+    rows[wave][2 * lane + 1] = ring[slot + 2 * lane + 1];
+  }
+  __syncthreads();
+  // the old token is now in LDS; the new one may take its slot
+  reinterpret_cast<__half2 *>(ring + slot)[lane] = reinterpret_cast<const __half2 *>(fresh)[lane];
+  if (!evict) return;
+
+  const int *perm = (wave ? L.perm_v : L.perm_k) + hk * kD;
+  const int grp = (2 * lane) / L.G;
+  const float alpha = (wave ? L.clip_v : L.clip_k)[hk * L.NG + grp];
+  const float top = wave ? (float)(L.v_levels - 1) : 3.0f;
+  unsigned c0, c1;
+  float scale, zero;
+  encode_row(rows[wave], perm[2 * lane], perm[2 * lane + 1], alpha, L.G, top, c0, c1, scale, zero);
+  float *meta = wave ? L.v_meta : L.k_meta;
+  if ((2 * lane) % L.G == 0)
+    reinterpret_cast<float2 *>(meta)[(head * L.Tcap + te) * L.NG + grp] = make_float2(scale, zero);
+
+  if (wave == 0) {
+    store_k_row(L.k_codes + (head * L.Tcap + te) * (kD / 4), lane, c0, c1);
+  } else {
+    vcodes[2 * lane] = (uint8_t)c0;
+    vcodes[2 * lane + 1] = (uint8_t)c1;
+  }
+  __syncthreads();
+  if (wave == 0) return;
+
+  const int s = (int)(te % kVBlock), kb = s >> 3, i = s & 7;
+  uint8_t *blk = L.v_codes + (head * L.n_vblocks + te / kVBlock) * L.v_block_bytes;
+  if (s == 0) {
+    // First token of a block: the block starts as zeros.  The 16 units of sub-block 0 are
+    // written whole below (i == 0), so only the other three sub-blocks are cleared here.
+    const int first = L.v_block_bytes / 16;  // dwords of one sub-block
+    for (int w = first + lane; w < L.v_block_bytes / 4; w += 64) reinterpret_cast<unsigned *>(blk)[w] = 0u;
+  }
+  if (L.v_levels == 4) {
+    // lane (j, nh): dword nh of unit j holds fields 2nh and 2nh+1
+    const int j = lane & 15, nh = lane >> 4;
+    const unsigned bit = 16 * (i & 1) + 2 * (i >> 1);
+    const unsigned add = ((unsigned)vcodes[16 * (2 * nh) + j] << bit) | ((unsigned)vcodes[16 * (2 * nh + 1) + j] << (bit + 8));
+    unsigned *w = reinterpret_cast<unsigned *>(blk + 16 * (16 * kb + j)) + nh;
+    *w = (i == 0 ? 0u : *w) | add;
+  } else if (lane < 16) {
+    const int j = lane;
+    uint8_t *u = blk + 13 * (16 * kb + j);
+    unsigned long long lo = 0, hi = 0;
+    if (i != 0) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) lo |= (unsigned long long)u[q] << (8 * q);
+#pragma unroll
+      for (int q = 0; q < 5; ++q) hi |= (unsigned long long)u[8 + q] << (8 * q);
+    }
+    unsigned pw = 1;
+    for (int q = 0; q < i; ++q) pw *= 3;
+    unsigned long long f[8];
+    f[0] = lo & 0x1fff; f[1] = (lo >> 13) & 0x1fff; f[2] = (lo >> 26) & 0x1fff; f[3] = (lo >> 39) & 0x1fff;
+    f[4] = ((lo >> 52) | (hi << 12)) & 0x1fff; f[5] = (hi >> 1) & 0x1fff; f[6] = (hi >> 14) & 0x1fff;
+    f[7] = (hi >> 27) & 0x1fff;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) f[n] += (unsigned long long)vcodes[16 * n + j] * pw;
+    lo = f[0] | (f[1] << 13) | (f[2] << 26) | (f[3] << 39) | (f[4] << 52);
+    hi = (f[4] >> 12) | (f[5] << 1) | (f[6] << 14) | (f[7] << 27);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) u[q] = (uint8_t)(lo >> (8 * q));
+#pragma unroll
+    for (int q = 0; q < 5; ++q) u[8 + q] = (uint8_t)(hi >> (8 * q));
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T, hipStream_t s) {
+  const long long nq = T > L.W ? T - L.W : 0;
+  if (nq > 0) {
+    const long long nblk = (nq + kVBlock - 1) / kVBlock;
+    if (nblk > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)nblk, L.Hk, L.B), dim3(256), 0, s, L, k, v, T, nq);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const long long nw = T - nq;
+  if (nw > 0) {
+    hipLaunchKernelGGL(ring_fill_kernel, dim3((unsigned)nw, L.Hk, L.B), dim3(64), 0, s, L, k, v, T, nq);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T, hipStream_t s) {
+  if (L.B > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(append_kernel, dim3(L.Hk, L.B), dim3(128), 0, s, L, k_new, v_new, T);
+  return hipGetLastError();
+}
+
+}  // namespace skvq

@@ -1,0 +1,104 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/skvq.h declares,
+and its pure-host entry points (sizes, validation) agree with the oracle and reject bad input."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+D = 128
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2405_06219_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2405_06219_amd import build
+        build.build()
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "skvq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(skvq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_entry_point(B):
+    names = declared_functions()
+    assert {"skvq_prefill_quantize", "skvq_quantize_append", "skvq_decode_attention", "skvq_create",
+            "skvq_destroy", "skvq_sizes"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_missing_library_fails_loudly(B, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libskvq.so")
+    with pytest.raises(RuntimeError):
+        B.lib()
+
+
+def cfg_for(B, **kw):
+    hk = kw.get("n_kv_heads", 8)
+    g = kw.get("group_size", 128)
+    perm = kw.pop("perm", np.tile(np.arange(D, dtype=np.int32), (hk, 1)))
+    clip = kw.pop("clip", np.ones((hk, D // g), np.float32))
+    args = dict(batch=1, n_q_heads=32, n_kv_heads=hk, group_size=g, v_bits=1.5, window=128,
+                max_quant_tokens=4096, perm_k=perm, perm_v=perm, clip_k=clip, clip_v=clip)
+    args.update(kw)
+    return B.make_config(**args)
+
+
+def test_sizes_agree_with_the_oracle(B, oracle):
+    for hk, hq, g, vb, tcap, w, b in [(8, 32, 128, 1.5, 4096, 128, 1), (4, 4, 32, 2.0, 1000, 16, 3),
+                                      (2, 16, 64, 1.5, 33, 7, 2)]:
+        cfg, keep = cfg_for(B, batch=b, n_q_heads=hq, n_kv_heads=hk, group_size=g, v_bits=vb, window=w,
+                            max_quant_tokens=tcap)
+        sizes = B.skvq_sizes(cfg)
+        perm = np.tile(np.arange(D, dtype=np.int32), (hk, 1))
+        clip = np.ones((hk, D // g), np.float32)
+        oc = oracle.OracleCache(b, hq, hk, g, vb, w, tcap, perm, perm, clip, clip)
+        assert sizes[:6] == oc.sizes
+        assert sizes[6] == b * hq * (B.SKVQ_MAX_SPLITS + 1) * (D + 4) * 4
+
+
+def test_validation_rejects_bad_configs(B):
+    ok, keep = cfg_for(B)
+    assert B.skvq_validate_config(ok) == B.SKVQ_OK
+    bad_perm = np.tile(np.arange(D, dtype=np.int32), (8, 1))
+    bad_perm[3, 5] = 6                                   # channel 6 twice, 5 missing
+    cases = [
+        (dict(perm=bad_perm), B.SKVQ_ERR_INVALID_ARG),
+        (dict(clip=np.full((8, 1), 1.5, np.float32)), B.SKVQ_ERR_INVALID_ARG),
+        (dict(clip=np.full((8, 1), 0.0, np.float32)), B.SKVQ_ERR_INVALID_ARG),
+        (dict(clip=np.full((8, 1), np.nan, np.float32)), B.SKVQ_ERR_INVALID_ARG),
+        (dict(n_q_heads=30), B.SKVQ_ERR_INVALID_ARG),
+        (dict(window=0), B.SKVQ_ERR_INVALID_ARG),
+        (dict(max_quant_tokens=0), B.SKVQ_ERR_INVALID_ARG),
+        (dict(batch=0), B.SKVQ_ERR_INVALID_ARG),
+        (dict(head_dim=64), B.SKVQ_ERR_UNSUPPORTED),
+        (dict(group_size=16, clip=np.ones((8, 8), np.float32)), B.SKVQ_ERR_UNSUPPORTED),
+        (dict(k_bits=1.5), B.SKVQ_ERR_UNSUPPORTED),
+        (dict(n_q_heads=128), B.SKVQ_ERR_UNSUPPORTED),     # 16 query heads per kv head
+    ]
+    for kw, want in cases:
+        cfg, keep = cfg_for(B, **kw)
+        assert B.skvq_validate_config(cfg) == want, kw
+        with pytest.raises(B.SkvqError):
+            B.skvq_sizes(cfg)
+    assert B.lib().skvq_validate_config(None) == B.SKVQ_ERR_INVALID_ARG
+    # create refuses a bad config and null / misaligned buffers before touching the device
+    cfg, keep = cfg_for(B, window=0)
+    h = C.c_void_p()
+    bufs = B.skvq_buffers(*([16] * 7))
+    assert B.lib().skvq_create(C.byref(cfg), C.byref(bufs), C.byref(h)) == B.SKVQ_ERR_INVALID_ARG
+    assert B.lib().skvq_create(C.byref(ok), None, C.byref(h)) == B.SKVQ_ERR_INVALID_ARG
+    bufs = B.skvq_buffers(*([16] * 6 + [8]))
+    assert B.lib().skvq_create(C.byref(ok), C.byref(bufs), C.byref(h)) == B.SKVQ_ERR_INVALID_ARG
+    assert not h.value
+    assert B.lib().skvq_status_string(B.SKVQ_ERR_CAPACITY) == b"packed region full"
+    B.lib().skvq_destroy(None)

@@ -1,0 +1,168 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs, through the
+C ABI.  Codes, (scale, zero) and ring contents must match bit for bit; attention outputs
+within 2e-3 max-abs (fp32 outputs)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2405_06219_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import parity_util
+    return parity_util
+
+
+def small(name, **kw):
+    base = dict(name=name, batch=1, n_q_heads=4, n_kv_heads=4, context=700, v_bits=1.5, group_size=128,
+                window=128, seed=77)
+    base.update(kw)
+    return synth.Workload(**base)
+
+
+QUANT_CASES = [
+    small("mha_t15_g128"),
+    small("mha_v2_g128", v_bits=2.0, channel_profile="outlier4", perm_stat="absmax"),
+    small("gqa_t15_g64", n_q_heads=8, n_kv_heads=2, group_size=64, batch=2, context=391),
+    small("gqa_v2_g32", n_q_heads=8, n_kv_heads=2, group_size=32, v_bits=2.0, context=333, window=16),
+    small("short_window_only", context=100),
+    small("one_quantized_token", context=129),
+    small("w1", window=1, context=70),
+]
+
+
+@pytest.mark.parametrize("w", QUANT_CASES, ids=lambda w: w.name)
+def test_prefill_codes_and_meta_bit_exact(P, w):
+    print("case", w, flush=True)
+    pair, k, v, q = P.make_pair(w, extra_tokens=40)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
+
+
+@pytest.mark.parametrize("w", [QUANT_CASES[0], QUANT_CASES[2], QUANT_CASES[3], small("from_empty", context=0, window=8)],
+                         ids=lambda w: w.name)
+def test_append_evicts_bit_exact_and_equals_longer_prefill(P, w):
+    print("case", w, flush=True)
+    n = 75
+    pair, k, v, q = P.make_pair(w, extra_tokens=n)
+    if w.context:
+        pair.prefill(k, v)
+    for s in range(n):
+        kn, vn = synth.make_new_token(w, s)
+        pair.append(kn, vn)
+        if s in (0, 1, 7, 8, 31, 32, 33, n - 1):
+            pair.assert_buffers_equal()
+
+
+def test_encoder_special_values_bit_exact(P):
+    """Constant groups, signed zeros, tiny and large magnitudes, exact ties."""
+    w = small("special", n_q_heads=2, n_kv_heads=2, context=8 + 64, window=8, group_size=32, v_bits=1.5)
+    rng = np.random.default_rng(9)
+    T = w.context
+    k = rng.standard_normal((1, 2, T, D)).astype(np.float16)
+    v = rng.standard_normal((1, 2, T, D)).astype(np.float16)
+    k[0, 0, 0] = 3.0                       # constant -> scale 0
+    v[0, 0, 0] = -2.5
+    k[0, 0, 1, ::2], k[0, 0, 1, 1::2] = -0.0, 0.0
+    v[0, 0, 1] = -0.0
+    k[0, 0, 2] = (rng.integers(0, 4, D) * 0.5).astype(np.float16)      # exact grid and ties
+    v[0, 0, 2] = (rng.integers(0, 5, D) * 0.25).astype(np.float16)
+    k[0, 1, 3] = (rng.standard_normal(D) * 6e-6).astype(np.float16)    # fp16 subnormals
+    v[0, 1, 3] = (rng.standard_normal(D) * 2e4).astype(np.float16)     # near the top of fp16
+    k[0, 1, 4, :64] = 0.0
+    v[0, 1, 5] = np.float16(65504.0) * np.sign(rng.standard_normal(D)).astype(np.float16)
+    pk = np.stack([rng.permutation(D) for _ in range(2)]).astype(np.int32)
+    pv = np.stack([rng.permutation(D) for _ in range(2)]).astype(np.int32)
+    ck = rng.uniform(0.5, 1.0, (2, 4)).astype(np.float32)
+    cv = rng.uniform(0.5, 1.0, (2, 4)).astype(np.float32)
+    pair = P.Pair(w, 96, pk, pv, ck, cv)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
+
+
+DECODE_CASES = [
+    small("mha_t15", context=1500),
+    small("mha_v2_outlier", v_bits=2.0, channel_profile="outlier4", perm_stat="absmax", context=2048),
+    small("gqa4_t15", n_q_heads=16, n_kv_heads=4, context=1333, batch=2),
+    small("gqa4_v2", n_q_heads=8, n_kv_heads=2, context=999, v_bits=2.0),
+    small("gqa2_g64", n_q_heads=4, n_kv_heads=2, group_size=64, context=611),
+    small("gqa8_g32_v2", n_q_heads=8, n_kv_heads=1, group_size=32, v_bits=2.0, context=450, window=16),
+    small("mha_g32_t15", group_size=32, context=300),
+    small("window_only", context=77),
+    small("exactly_window", context=128),
+    small("one_packed_row", context=129),
+    small("single_token", context=1),
+]
+
+
+@pytest.mark.parametrize("w", DECODE_CASES, ids=lambda w: w.name)
+def test_decode_attention_matches_oracle(P, w):
+    print("case", w, flush=True)
+    pair, k, v, q = P.make_pair(w)
+    pair.prefill(k, v)
+    (out, out16), (ref, ref16) = pair.decode_both(q, want_f16=True)
+    err = np.abs(out - ref).max()
+    print("max abs err", err, "ref max", np.abs(ref).max(), flush=True)
+    assert err <= P.TOL
+    assert np.abs(out16.astype(np.float32) - out).max() <= 2.0 ** -11 * np.abs(out).max() + 1e-7
+
+
+def test_decode_is_independent_of_the_split_count(P):
+    w = small("splits", n_q_heads=8, n_kv_heads=2, context=128 + 64 * 37 + 5)
+    pair, k, v, q = P.make_pair(w)
+    pair.prefill(k, v)
+    ref = pair.ref.decode(q)
+    qd = torch.from_numpy(q).cuda()
+    outs = []
+    for s in (1, 2, 3, 7, 37, 38, 128):
+        pair.gpu.skvq_set_num_splits(s)
+        o = pair.gpu.skvq_decode_attention(qd).cpu().numpy()
+        assert np.abs(o - ref).max() <= P.TOL, s
+        outs.append(o)
+    assert max(np.abs(o - outs[0]).max() for o in outs) <= 1e-4
+
+
+def test_decode_after_appends_and_peaked_softmax(P):
+    """Appends move tokens from the ring into the packed region; a large softmax scale makes
+    one token dominate (the worst case for rounding of the weights)."""
+    w = small("peaked", n_q_heads=8, n_kv_heads=2, context=900)
+    pair, k, v, q = P.make_pair(w, extra_tokens=50, sm_scale=0.6)
+    pair.prefill(k, v)
+    for s in range(50):
+        pair.append(*synth.make_new_token(w, s))
+    pair.assert_buffers_equal()
+    out, ref = pair.decode_both(q)
+    assert np.abs(out - ref).max() <= P.TOL
+
+
+def test_runtime_errors(P):
+    w = small("errors", context=300)
+    pair, k, v, q = P.make_pair(w, extra_tokens=2)
+    B = P.B
+    qd = torch.from_numpy(q).cuda()
+    with pytest.raises(B.SkvqError) as e:
+        pair.gpu.skvq_decode_attention(qd)           # empty cache
+    assert e.value.status == B.SKVQ_ERR_STATE
+    kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    big_k = torch.zeros((1, 4, 300 + 10, D), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.SkvqError) as e:
+        pair.gpu.skvq_prefill_quantize(big_k, big_k)  # 310 - 128 rows > capacity 174
+    assert e.value.status == B.SKVQ_ERR_CAPACITY
+    pair.gpu.skvq_prefill_quantize(kd, vd)
+    x = torch.zeros((1, 4, D), dtype=torch.float16, device="cuda")
+    pair.gpu.skvq_quantize_append(x, x)
+    pair.gpu.skvq_quantize_append(x, x)
+    with pytest.raises(B.SkvqError) as e:
+        pair.gpu.skvq_quantize_append(x, x)
+    assert e.value.status == B.SKVQ_ERR_CAPACITY
+    assert pair.gpu.skvq_get_state() == (302, 174, 128)
+    torch.cuda.synchronize()
