@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the SKVQ hot path on one MI355X.
+
+A step is one generated token of a 7B-shaped model: for each of `--layers` attention layers
+(each with its own cache, so that no layer's data is still in the 256 MB Infinity Cache when
+its turn comes again) the token leaving the fp16 window is quantized
+(skvq_quantize_append) and the new query attends over the whole cache
+(skvq_decode_attention).  Inputs are seeded synthetic tensors already resident in HBM.
+
+Prints ONE JSON line.  `value` is microseconds per token (all layers); `roofline` prices the
+decode kernel's algorithmic bytes against the 8 TB/s HBM peak; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+D = 128
+
+
+def algorithmic_bytes_decode(w, n_tokens: int) -> int:
+    """Bytes one decode call must move: packed rows (K 32 B + V 26|32 B + two fp32
+    (scale, zero) pairs per group each), the fp16 ring, the query and the fp32 output."""
+    nq = max(n_tokens - w.window, 0)
+    nwin = min(n_tokens, w.window)
+    ng = D // w.group_size
+    vrow = 26 if w.v_bits == 1.5 else 32
+    per_row = 32 + 8 * ng + vrow + 8 * ng
+    return (w.batch * w.n_kv_heads * (nq * per_row + nwin * 2 * D * 2)
+            + w.batch * w.n_q_heads * D * (2 + 4))
+
+
+def build_layers(w, n_layers: int, headroom: int, device):
+    """Per layer: a cache prefilled with w.context seeded synthetic tokens."""
+    import torch
+    from paper_2405_06219_amd import binding as B
+    from paper_2405_06219_amd import synth
+
+    sk, sv = synth.channel_scales(w)
+    sk_d = torch.from_numpy(sk).to(device)[None, :, None, :]
+    sv_d = torch.from_numpy(sv).to(device)[None, :, None, :]
+    ck, cv = synth.make_clip(w)
+    gen = torch.Generator(device=device)
+    caches = []
+    shape = (w.batch, w.n_kv_heads, w.context, D)
+    for layer in range(n_layers):
+        gen.manual_seed(w.seed * 1000 + layer)
+        k = (torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * sk_d).to(torch.float16)
+        v = (torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * sv_d).to(torch.float16)
+        # reorder index: channels sorted by their range over the sequence (offline calibration stand-in)
+        rk = (k.amax(dim=(0, 2)) - k.amin(dim=(0, 2))).float().cpu().numpy()
+        rv = (v.amax(dim=(0, 2)) - v.amin(dim=(0, 2))).float().cpu().numpy()
+        pk = np.argsort(rk, axis=-1, kind="stable").astype(np.int32)
+        pv = np.argsort(rv, axis=-1, kind="stable").astype(np.int32)
+        c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
+                        w.context - w.window + headroom, pk, pv, ck, cv, device=device)
+        c.skvq_prefill_quantize(k, v)
+        torch.cuda.synchronize()
+        del k, v
+        caches.append(c)
+    return caches, (sk_d, sv_d)
+
+
+def cpu_baseline(w, seconds_budget: float = 25.0):
+    """Times the CPU oracle (as it stands) on one layer of the same workload: its own prefill
+    from host inputs (untimed), then one append + one decode (timed)."""
+    from oracle import skvq_oracle as O
+    from paper_2405_06219_amd import synth
+
+    # bound the sample: shrink the context until the oracle's decode fits the budget
+    ctx = w.context
+    per_token_ns = 1100.0 * w.n_q_heads * w.batch / max(O.num_threads(), 1)
+    while ctx > 4096 and ctx * per_token_ns * 1e-9 > seconds_budget / 3:
+        ctx //= 2
+    ws = w.scaled(ctx)
+    k, v = synth.make_kv(ws)
+    pk, pv = synth.make_permutations(ws, k[:, :, :4096], v[:, :, :4096])
+    ck, cv = synth.make_clip(ws)
+    oc = O.OracleCache(ws.batch, ws.n_q_heads, ws.n_kv_heads, ws.group_size, ws.v_bits, ws.window,
+                       ctx - ws.window + 4, pk, pv, ck, cv)
+    assert oc.prefill(k, v) == 0
+    q = synth.make_query(ws)
+    kn, vn = synth.make_new_token(ws, 0)
+    t0 = time.perf_counter()
+    assert oc.append(kn, vn) == 0
+    t1 = time.perf_counter()
+    oc.decode(q)
+    t2 = time.perf_counter()
+    per_layer_us = (t2 - t0) * 1e6 * (w.context / ctx)
+    return {"per_layer_us": per_layer_us, "append_us": (t1 - t0) * 1e6, "decode_us": (t2 - t1) * 1e6,
+            "context_timed": ctx, "threads": O.num_threads()}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--workload", default="c3_mistral7b_128k")
+    ap.add_argument("--context", type=int, default=0, help="override the workload's context (tests)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2405_06219_amd import binding as B
+    from paper_2405_06219_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    B.lib()  # fail loudly if the HIP library is missing
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+    w = synth.WORKLOADS[args.workload]
+    if args.context:
+        w = w.scaled(args.context)
+    n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers
+    headroom = n_warm + 2 * n_steps + 9
+
+    caches, (sk_d, sv_d) = build_layers(w, n_layers, headroom, device)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed)
+    total = n_warm + 2 * n_steps + 1
+    # per (step, layer) inputs, resident before the timed region
+    q_all = torch.randn((total, n_layers, w.batch, w.n_q_heads, D), generator=gen, device=device).to(torch.float16)
+    kn_all = (torch.randn((total, n_layers, w.batch, w.n_kv_heads, D), generator=gen, device=device)
+              * sk_d[:, :, 0]).to(torch.float16)
+    vn_all = (torch.randn((total, n_layers, w.batch, w.n_kv_heads, D), generator=gen, device=device)
+              * sv_d[:, :, 0]).to(torch.float16)
+    out = torch.empty((n_layers, w.batch, w.n_q_heads, D), dtype=torch.float32, device=device)
+
+    def step(i, events=None):
+        for layer, c in enumerate(caches):
+            c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            c.skvq_decode_attention(q_all[i, layer], out_f32=out[layer])
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+
+    i = 0
+    for _ in range(n_warm):
+        step(i)
+        i += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_steps):
+        step(i)
+        i += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / n_steps
+    n_tokens_mid = w.context + n_warm + n_steps // 2
+
+    # roofline pass: the same calls again, with an event pair around each decode call
+    events = []
+    for _ in range(n_steps):
+        step(i, events)
+        i += 1
+    torch.cuda.synchronize()
+    dec_us = np.array([a.elapsed_time(b) * 1e3 for a, b in events])
+    dec_avg_us = float(dec_us.mean())
+    n_tokens_roof = w.context + n_warm + n_steps + n_steps // 2
+    alg_bytes = algorithmic_bytes_decode(w, n_tokens_roof)
+    achieved = alg_bytes / (dec_avg_us * 1e-6) / 1e9
+
+    # append alone (launch-latency bound, reported for completeness)
+    torch.cuda.synchronize()
+    ta = time.perf_counter()
+    for layer, c in enumerate(caches):
+        c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
+    torch.cuda.synchronize()
+    append_us = (time.perf_counter() - ta) * 1e6 / n_layers
+
+    result = {
+        "metric": "decode-attention us/token at 128k ctx" if w.context == 131072 else f"decode-attention us/token at {w.context} ctx",
+        "value": ms_per_step * 1e3,
+        "unit": "us/token",
+        "n_gpus": 1,
+        "steps": n_steps,
+        "warmup": n_warm,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "layers": n_layers, "batch": w.batch, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": D, "context": w.context, "k_bits": 2,
+                   "v_bits": w.v_bits, "group_size": w.group_size, "window": w.window,
+                   "step": "per layer: skvq_quantize_append + skvq_decode_attention"},
+        "us_per_layer": ms_per_step * 1e3 / n_layers,
+        "decode_call_us": dec_avg_us,
+        "decode_call_us_min": float(dec_us.min()),
+        "append_call_us": append_us,
+        "effective_hbm_gbps": achieved,
+        "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "skvq_decode_attention", "bytes_per_launch": alg_bytes,
+                     "avg_launch_us": dec_avg_us},
+    }
+    if not args.no_cpu_baseline:
+        cb = cpu_baseline(w)
+        result["cpu_baseline"] = {
+            "value": cb["per_layer_us"] * n_layers, "unit": "us/token", "cores": cb["threads"], "kind": "oracle",
+            "sample": (f"1 of {n_layers} layers (append + decode) at context {cb['context_timed']}"
+                       f", scaled to {w.context} tokens and x{n_layers} layers"),
+            "decode_us_timed": cb["decode_us"], "append_us_timed": cb["append_us"]}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

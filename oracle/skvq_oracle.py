@@ -133,6 +133,8 @@ class OracleCache:
         self.v_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
         self.k_win = np.zeros((batch, n_kv_heads, window, HEAD_DIM), np.uint16)
         self.v_win = np.zeros((batch, n_kv_heads, window, HEAD_DIM), np.uint16)
+        for a in (self.k_meta, self.v_meta, self.k_win, self.v_win):
+            a.view(np.uint8)[...] = fill     # untouched bytes keep the caller's initial pattern
         assert [a.nbytes for a in self.arrays()] == self.sizes, (self.sizes, heads)
         self.buf = _Buffers(*[_ptr(a) for a in self.arrays()])
         self.n_tokens = 0
