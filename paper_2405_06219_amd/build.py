@@ -19,6 +19,7 @@ SOURCES = {
     "skvq_api.hip": [],
     "skvq_quantize.hip": ["-ffp-contract=off"],
     "skvq_decode.hip": [],
+    "skvq_decode_mfma.hip": ["-Rpass-analysis=kernel-resource-usage"] if os.environ.get("SKVQ_RESOURCE_USAGE") else [],
 }
 
 

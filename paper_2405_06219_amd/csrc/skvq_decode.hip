@@ -14,13 +14,17 @@
 
 namespace skvq {
 
+// Entry f (a base-3 number of eight digits, digit i = code of token i) -> the eight codes laid
+// out for the matrix-core kernel: token 2m in the low half and 2m+1 in the high half of the
+// word, at bit 4, 6, 8 for m = 0, 1, 2 and at bit 0 for m = 3.
 void build_trit_lut(uint32_t *t) {
+  static const int pos[4] = {4, 6, 8, 0};
   for (unsigned f = 0; f < 8192; ++f) {
     uint32_t e = 0;
     if (f < 6561) {
       unsigned r = f;
       for (int i = 0; i < 8; ++i) {
-        e |= (r % 3) << (16 * (i & 1) + 2 * (i >> 1));
+        e |= (r % 3) << (16 * (i & 1) + pos[i >> 1]);
         r /= 3;
       }
     }
@@ -65,7 +69,7 @@ __device__ __forceinline__ unsigned v_code(const uint8_t *blk, int levels, int s
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __half *__restrict__ q,
                                                              long long T, long long nq, int n_splits,
-                                                             long long tiles_per_split) {
+                                                             long long tiles_per_split, int sp_base) {
   __shared__ float qs[kMaxR][kD];     // query in the order the chunk's keys use, times sm_scale*log2(e)
   __shared__ float qsum[kMaxR][4];    // its per-group sums
   __shared__ float pr[kMaxR][256];    // softmax numerators of the current tile
@@ -73,7 +77,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
   __shared__ float accs[kMaxR][kD];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int sp = blockIdx.x + sp_base, hk = blockIdx.y, b = blockIdx.z;
   const bool ring = sp == n_splits;
   const long long head = (long long)b * L.Hk + hk;
   const int R = L.R, G = L.G, NG = L.NG;
@@ -239,9 +243,18 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
   if (nq == 0) n_splits = 0;
   const long long tiles = (nq + 63) / 64;
   const long long tps = n_splits ? (tiles + n_splits - 1) / n_splits : 0;
-  hipLaunchKernelGGL(decode_generic_kernel, dim3(n_splits + 1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq,
-                     n_splits, tps);
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  if (n_splits > 0 && decode_mfma_supported(L)) {
+    e = launch_decode_mfma(L, q, nq, n_splits, tps, s);
+    if (e != hipSuccess) return e;
+    // the fp16 ring is the chunk after the last packed one
+    hipLaunchKernelGGL(decode_generic_kernel, dim3(1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq, n_splits, tps,
+                       n_splits);
+  } else {
+    hipLaunchKernelGGL(decode_generic_kernel, dim3(n_splits + 1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq,
+                       n_splits, tps, 0);
+  }
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(L.Hq, L.B), dim3(128), 0, s, L, out_f32, out_f16, n_splits, 1);
   return hipGetLastError();

@@ -45,6 +45,12 @@ hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_n
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,
                          long long T, int n_splits, hipStream_t s);
 
+// Matrix-core chunk kernel for the packed region (skvq_decode_mfma.hip): group size 128,
+// 1, 2 or 4 query heads per kv head.  Writes partials 0..n_splits-1.
+bool decode_mfma_supported(const Layout &L);
+hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long nq, int n_splits,
+                              long long tiles_per_split, hipStream_t s);
+
 // Fills the 8192-entry table that expands a 13-bit base-3 field into eight 2-bit codes.
 void build_trit_lut(uint32_t *host_table);
 

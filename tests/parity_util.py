@@ -1,6 +1,8 @@
 """Builds the same cache twice -- CPU oracle and HIP library -- from one set of seeded inputs."""
 from __future__ import annotations
 
+import os
+
 import numpy as np
 import torch
 
@@ -9,6 +11,15 @@ from paper_2405_06219_amd import binding as B
 from paper_2405_06219_amd import synth
 
 TOL = 2e-3  # max-abs bound on attention outputs (fp32), the build's stated floating-point bar
+
+
+def log(msg: str):
+    """Progress line on stdout and, when the folder exists, in gpurun_out/parity.log."""
+    print(msg, flush=True)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "parity.log"), "a") as f:
+            f.write(msg + "\n")
 
 
 class Pair:
