@@ -88,11 +88,11 @@ int choose_splits(const skvq_cache *c, long long n_quant) {
   if (c->forced_splits > 0) {
     s = c->forced_splits;
   } else {
-    // about four workgroups per compute unit over all (sequence, kv head) pairs,
-    // but no split shorter than 8 tiles
+    // three resident workgroups per compute unit over all (sequence, kv head) pairs, the fp16
+    // ring being one workgroup per pair; but no packed chunk shorter than 4 tiles
     const long long heads = (long long)c->L.B * c->L.Hk;
-    s = (4ll * c->n_cus + heads - 1) / heads;
-    const long long cap = (tiles + 7) / 8;
+    s = (3ll * c->n_cus) / heads - 1;
+    const long long cap = (tiles + 3) / 4;
     if (s > cap) s = cap;
   }
   if (s > SKVQ_MAX_SPLITS) s = SKVQ_MAX_SPLITS;

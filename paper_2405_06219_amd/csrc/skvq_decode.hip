@@ -207,30 +207,58 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
 }
 
 // Combines the chunk partials of one (sequence, query head): out = sum_i acc_i 2^(m_i - m*) /
-// sum_i l_i 2^(m_i - m*).  Partials hold base-2 exponents.  grid (Hq, B), 128 threads.
-__global__ __launch_bounds__(128) void merge_kernel(Layout L, float *__restrict__ out_f32,
-                                                    __half *__restrict__ out_f16, int n_parts_first,
-                                                    int has_ring) {
-  const int hq = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
+// sum_i l_i 2^(m_i - m*).  Partials hold base-2 exponents.  grid (Hq, B), 1024 threads:
+// wavefront 0 turns the (m_i, l_i) into weights, then thread (channel, slice) adds every
+// eighth partial so that all loads of a thread are in flight together.
+__global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict__ out_f32,
+                                                     __half *__restrict__ out_f16, int n_all) {
+  __shared__ float wts[SKVQ_MAX_SPLITS + 1];
+  __shared__ float den_s;
+  __shared__ float red[8][kD];
+  const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const float *base = L.workspace + ((long long)b * L.Hq + hq) * (SKVQ_MAX_SPLITS + 1) * kPartialStride;
-  float mstar = -INFINITY;
-  for (int i = 0; i < n_parts_first; ++i) mstar = fmaxf(mstar, base[i * kPartialStride]);
-  if (has_ring) mstar = fmaxf(mstar, base[n_parts_first * kPartialStride]);
-  float num = 0.f, den = 0.f;
-  const int n_all = n_parts_first + (has_ring ? 1 : 0);
-  for (int i = 0; i < n_all; ++i) {
-    const float *part = base + i * kPartialStride;
-    const float li = part[1];
-    if (li > 0.f) {
-      const float w = exp2f(part[0] - mstar);
-      den += w * li;
-      num += w * part[4 + ch];
+  if (tid < 64) {
+    float mi[3], li[3], mstar = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const int i = tid + 64 * k;
+      mi[k] = -INFINITY, li[k] = 0.f;
+      if (i < n_all) {
+        const float2 ml = *reinterpret_cast<const float2 *>(base + (long long)i * kPartialStride);
+        mi[k] = ml.x, li[k] = ml.y;
+      }
+      if (li[k] > 0.f) mstar = fmaxf(mstar, mi[k]);
     }
+    mstar = wave_max(mstar);
+    float den = 0.f;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const int i = tid + 64 * k;
+      const float w = li[k] > 0.f ? exp2f(mi[k] - mstar) : 0.f;
+      if (i < n_all) wts[i] = w;
+      den += w * li[k];
+    }
+    den = wave_sum(den);
+    if (tid == 0) den_s = den;
   }
-  const float o = num / den;
-  const long long idx = ((long long)b * L.Hq + hq) * kD + ch;
-  out_f32[idx] = o;
-  if (out_f16) out_f16[idx] = __float2half_rn(o);
+  __syncthreads();
+  const int ch = tid & 127, sl = tid >> 7;
+  float num = 0.f;
+  for (int i = sl; i < n_all; i += 8) {
+    const float w = wts[i];
+    if (w > 0.f) num = fmaf(w, base[(long long)i * kPartialStride + 4 + ch], num);
+  }
+  red[sl][ch] = num;
+  __syncthreads();
+  if (tid < kD) {
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) tot += red[k][tid];
+    const float o = tot / den_s;
+    const long long idx = ((long long)b * L.Hq + hq) * kD + tid;
+    out_f32[idx] = o;
+    if (out_f16) out_f16[idx] = __float2half_rn(o);
+  }
 }
 
 }  // namespace
@@ -245,18 +273,15 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
   const long long tps = n_splits ? (tiles + n_splits - 1) / n_splits : 0;
   hipError_t e;
   if (n_splits > 0 && decode_mfma_supported(L)) {
-    e = launch_decode_mfma(L, q, nq, n_splits, tps, s);
+    e = launch_decode_mfma(L, q, T, nq, n_splits, tps, s);
     if (e != hipSuccess) return e;
-    // the fp16 ring is the chunk after the last packed one
-    hipLaunchKernelGGL(decode_generic_kernel, dim3(1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq, n_splits, tps,
-                       n_splits);
   } else {
     hipLaunchKernelGGL(decode_generic_kernel, dim3(n_splits + 1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq,
                        n_splits, tps, 0);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(L.Hq, L.B), dim3(128), 0, s, L, out_f32, out_f16, n_splits, 1);
+  hipLaunchKernelGGL(merge_kernel, dim3(L.Hq, L.B), dim3(1024), 0, s, L, out_f32, out_f16, n_splits + 1);
   return hipGetLastError();
 }
 

@@ -46,9 +46,10 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
                          long long T, int n_splits, hipStream_t s);
 
 // Matrix-core chunk kernel for the packed region (skvq_decode_mfma.hip): group size 128,
-// 1, 2 or 4 query heads per kv head.  Writes partials 0..n_splits-1.
+// 1, 2 or 4 query heads per kv head.  Writes partials 0..n_splits-1 and the ring's partial
+// (index n_splits).
 bool decode_mfma_supported(const Layout &L);
-hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long nq, int n_splits,
+hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
                               long long tiles_per_split, hipStream_t s);
 
 // Fills the 8192-entry table that expands a 13-bit base-3 field into eight 2-bit codes.
