@@ -86,7 +86,8 @@ typedef struct {
  *   v_meta    f32 [B][Hk][Tcap][D/G][2]
  *   k_win     f16 [B][Hk][W][D]          token number a (0-based) sits in slot a % W
  *   v_win     f16 [B][Hk][W][D]
- *   workspace split partials of skvq_decode_attention; contents are scratch
+ *   workspace split partials and workgroup counters of skvq_decode_attention; skvq_create
+ *             clears the counters, the library keeps them zero between calls; do not write it
  * All seven must be 16-byte aligned. */
 typedef struct {
   void *k_codes, *v_codes, *k_meta, *v_meta, *k_win, *v_win, *workspace;

@@ -73,7 +73,8 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
   bytes[4] = heads * (size_t)c->window * kD * sizeof(__half);
   bytes[5] = bytes[4];
   // one partial per (sequence, query head, split); the ring is one more split
-  bytes[6] = (size_t)c->batch * c->n_q_heads * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
+  // ... followed by one 4-byte workgroup counter per (sequence, kv head)
+  bytes[6] = counters_offset(c->batch, c->n_q_heads) + ((heads * sizeof(unsigned) + 15) & ~(size_t)15);
 }
 
 int fail_hip(skvq_cache *c, hipError_t e, const char *what) {
@@ -88,11 +89,11 @@ int choose_splits(const skvq_cache *c, long long n_quant) {
   if (c->forced_splits > 0) {
     s = c->forced_splits;
   } else {
-    // three resident workgroups per compute unit over all (sequence, kv head) pairs, the fp16
-    // ring being one workgroup per pair; but no packed chunk shorter than 4 tiles
+    // one workgroup per compute unit over all (sequence, kv head) pairs, but every wavefront of
+    // a workgroup should have at least two tiles
     const long long heads = (long long)c->L.B * c->L.Hk;
-    s = (3ll * c->n_cus) / heads - 1;
-    const long long cap = (tiles + 3) / 4;
+    s = c->n_cus / heads;
+    const long long cap = tiles / (2 * kMfmaWavesPerGroup);
     if (s > cap) s = cap;
   }
   if (s > SKVQ_MAX_SPLITS) s = SKVQ_MAX_SPLITS;
@@ -112,8 +113,6 @@ int skvq_sizes(const skvq_config *cfg, size_t bytes[7]) {
   // sizes do not depend on perm/clip; allow them to be absent here
   if (!cfg) return SKVQ_ERR_INVALID_ARG;
   skvq_config tmp = *cfg;
-  static const int32_t ident_dummy = 0;
-  (void)ident_dummy;
   std::vector<int32_t> ident;
   std::vector<float> ones;
   if (!tmp.perm_k || !tmp.perm_v || !tmp.clip_k || !tmp.clip_v) {
@@ -166,6 +165,7 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.k_win = (__half *)bufs->k_win;
   L.v_win = (__half *)bufs->v_win;
   L.workspace = (float *)bufs->workspace;
+  L.counters = (unsigned *)((uint8_t *)bufs->workspace + counters_offset(L.B, L.Hq));
 
   // constants: [perm_k | perm_v | clip_k | clip_v | trit table], one allocation
   const size_t n_perm = (size_t)L.Hk * kD, n_clip = (size_t)L.Hk * L.NG;
@@ -186,6 +186,13 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
     return SKVQ_ERR_HIP;
   }
   e = hipMemcpy(c->dev_consts, host.data(), total, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(c->dev_consts);
+    delete c;
+    return SKVQ_ERR_HIP;
+  }
+  e = hipMemset(L.counters, 0, (size_t)L.B * L.Hk * sizeof(unsigned));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     (void)hipFree(c->dev_consts);
     delete c;

@@ -272,16 +272,20 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
   const long long tiles = (nq + 63) / 64;
   const long long tps = n_splits ? (tiles + n_splits - 1) / n_splits : 0;
   hipError_t e;
-  if (n_splits > 0 && decode_mfma_supported(L)) {
-    e = launch_decode_mfma(L, q, T, nq, n_splits, tps, s);
+  int n_parts;
+  if (decode_mfma_supported(L)) {
+    if (n_splits < 1) n_splits = 1;
+    e = launch_decode_mfma(L, q, T, nq, n_splits, s);
     if (e != hipSuccess) return e;
+    n_parts = n_splits;  // the ring is folded into the chunks' partials
   } else {
     hipLaunchKernelGGL(decode_generic_kernel, dim3(n_splits + 1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq,
                        n_splits, tps, 0);
+    n_parts = n_splits + 1;
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(L.Hq, L.B), dim3(1024), 0, s, L, out_f32, out_f16, n_splits + 1);
+  hipLaunchKernelGGL(merge_kernel, dim3(L.Hq, L.B), dim3(1024), 0, s, L, out_f32, out_f16, n_parts);
   return hipGetLastError();
 }
 

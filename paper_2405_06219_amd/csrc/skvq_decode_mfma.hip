@@ -1,7 +1,10 @@
-// Matrix-core chunk kernel of skvq_decode_attention for gfx950 (group size 128, up to four
-// query heads per kv head).
+// Matrix-core kernel of skvq_decode_attention for gfx950 (group size 128, up to four query
+// heads per kv head): packed chunks and the fp16 ring in one launch, one partial per chunk.
+// (Merging the partials inside this launch was tried and dropped: the device-scope fences it
+// needs write back and invalidate a whole L2 each, 25 us over 256 workgroups.)
 //
-// Per wavefront, per tile of 64 packed tokens:
+// One workgroup of 12 wavefronts per chunk (one per compute unit when the cache is long
+// enough).  Per wavefront, per tile of 64 packed tokens:
 //   QK   S^T[head][token] by 32 v_mfma_f32_4x4x4_16b_f16 (16 independent 4x4 blocks, lane =
 //        token): the B operand is the lane's own 32-byte key row, its 2-bit codes turned into
 //        fp16 SUBNORMALS by one AND each (a code c sitting at mantissa bit s is the fp16 value
@@ -29,10 +32,10 @@
 
 namespace skvq {
 #ifdef SKVQ_TIMING
-__device__ unsigned long long skvq_timing[8 * 4096];
+__device__ unsigned long long skvq_timing[16 * 4096];
 #define SKVQ_STAMP(slot)                                                                    \
   if (threadIdx.x == 0)                                                                     \
-  skvq_timing[8 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + (slot)] = \
+  skvq_timing[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + (slot)] = \
       __builtin_amdgcn_s_memrealtime()
 #else
 #define SKVQ_STAMP(slot)
@@ -99,18 +102,29 @@ __device__ __forceinline__ half8_t unpack_v_field(unsigned f) {
   return __builtin_bit_cast(half8_t, uint4_t{a & kM4, a & kM6, a & kM8, b & kM8});
 }
 
+constexpr int kNW = 12;             // wavefronts per workgroup (3 per SIMD)
+constexpr int kThreads = 64 * kNW;
+constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
+constexpr int kRingSlice = 4;       // ring tokens per slice
+
+constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumulator columns over the banks
+
 template <int R, bool TERNARY>
 struct Smem {
   union {
-    unsigned lut[TERNARY ? 8192 : 1];  // main loop: 13-bit field -> eight codes
-    float stage[4][2 * R][kD];         // epilogue: O^T per wave and column
+    unsigned lut[TERNARY ? 8192 : 1];      // main loop: 13-bit field -> eight codes (6561 used)
+    float stage[kNW][2 * R][kCombStride];  // epilogue: O^T per wave and column, reordered positions
   };
   float qraw[4][kD];                   // the query heads as loaded (rows >= R are zero)
   _Float16 qa[32][4][4];               // A operands of the score product: [step][head][k slot]
   float qsum[4];                       // sm_scale*log2(e) * sum of the query, per head
   float qinit[4];                      // -1.5 * sum of the query, in the score product's units (2^-16)
-  _Float16 pbuf[4][2][2 * R][32];      // per wave: [block][column][token slot]
-  float wm[4][R], wl[4][R], wz[4][R];
+  _Float16 pbuf[kNW][2][2 * R][32];    // per wave: [block][column][token slot]
+  // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
+  // tiles (w*) and for the ring slices (r*) of the wave; then each wave's factor 2^(m_w - m*)
+  float wm[kNW][R], wl[kNW][R], wz[kNW][R], rm[kNW][R], rl[kNW][R];
+  float ew[kNW][R], er[kNW][R], mstar[R], den[R], zsum[R];
+  float ring_o[kNW][R][kD];            // per wave: its ring slices' outputs, original channel order
 };
 
 // One 4-channel step of the score product.  The A operand of step ST lives in lanes
@@ -133,148 +147,6 @@ __device__ __forceinline__ float4_t qk_dword(unsigned w, half4_t a_lo, half4_t a
   return d;
 }
 
-// ---------------------------------------------------------------------------------------
-// The fp16 ring (last W tokens, original channel order) as one more chunk, in tiles of 64
-// tokens staged through LDS: plain vector arithmetic.  Scores: four threads per token, 32
-// channels each.  Value sum: thread = (channel pair, quarter of the tile).  The next tile's
-// rows are already in flight while a tile is computed.
-// ---------------------------------------------------------------------------------------
-constexpr int kRingTile = 64;
-constexpr int kRingKStride = kD + 8;  // halves; the padding spreads the rows over the LDS banks
-
-template <int R>
-struct RingSmem {
-  __half kt[kRingTile][kRingKStride];
-  __half vt[kRingTile][kD];
-  float qf[R][kD];          // query * sm_scale * log2(e)
-  float sc[R][kRingTile];   // scores, then softmax numerators, of the current tile
-  float m[R], l[R], scale[R];
-  float accs[4][R][kD];
-};
-
-template <int R>
-__device__ void ring_chunk(const Layout &L, RingSmem<R> &rs, const __half *__restrict__ q, long long T,
-                           long long nq, int part_index) {
-  // This workgroup is short and latency-bound; let its waves win the issue arbitration against
-  // the packed chunks they share the compute unit with, so that it is never the last to end.
-  __builtin_amdgcn_s_setprio(3);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int hk = blockIdx.y, b = blockIdx.z;
-  const long long head = (long long)b * L.Hk + hk;
-  const float c = L.sm_scale * kLog2e;
-  const int n_win = (int)(T - nq), W = L.W;
-  const uint4_t *kwin = reinterpret_cast<const uint4_t *>(L.k_win + head * W * kD);
-  const uint4_t *vwin = reinterpret_cast<const uint4_t *>(L.v_win + head * W * kD);
-  const int tk = tid >> 2, qt = tid & 3;   // scores: token of the tile, quarter of its channels
-  const int cp = tid & 63, tq = tid >> 6;  // values: channel pair, quarter of the tile
-  const int slot0 = (int)(nq % W);         // ring slot of the first ring token
-
-  // staging: thread copies 16-byte piece (tid%16) of rows tid/16 + 16*i, i = 0..3, of K and of V
-  const int crow = tid >> 4, cpiece = tid & 15;
-  uint4_t kst[4], vst[4];
-  auto load_stage = [&](int tile0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int t = tile0 + crow + 16 * i;
-      if (t >= n_win) t = n_win - 1;  // rows past the end repeat the last one; they get weight 0
-      int slot = slot0 + t;
-      slot -= (slot / W) * W;
-      kst[i] = kwin[(size_t)slot * 16 + cpiece];
-      vst[i] = vwin[(size_t)slot * 16 + cpiece];
-    }
-  };
-  load_stage(0);
-  for (int x = tid; x < R * kD; x += 256)
-    rs.qf[x >> 7][x & 127] = c * __half2float(q[((long long)b * L.Hq + hk * R + (x >> 7)) * kD + (x & 127)]);
-  if (tid < R) rs.m[tid] = -INFINITY, rs.l[tid] = 0.f;
-
-  float acc[R][2];
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r][0] = acc[r][1] = 0.f;
-
-  for (int tile0 = 0; tile0 < n_win; tile0 += kRingTile) {
-    const int n_in = n_win - tile0 < kRingTile ? n_win - tile0 : kRingTile;
-    __syncthreads();  // the previous tile's kt/vt/sc are no longer read
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<uint4_t *>(&rs.kt[crow + 16 * i][8 * cpiece]) = kst[i];
-      *reinterpret_cast<uint4_t *>(&rs.vt[crow + 16 * i][8 * cpiece]) = vst[i];
-    }
-    if (tile0 + kRingTile < n_win) load_stage(tile0 + kRingTile);
-    __syncthreads();
-
-    // ---- scores: 32 channels per thread ----
-    float s[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) s[r] = 0.f;
-#pragma unroll 1
-    for (int i = 0; i < 4; ++i) {
-      const half8_t x = *reinterpret_cast<const half8_t *>(&rs.kt[tk][32 * qt + 8 * i]);
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float4_t qa = *reinterpret_cast<const float4_t *>(&rs.qf[r][32 * qt + 8 * i]);
-        const float4_t qb = *reinterpret_cast<const float4_t *>(&rs.qf[r][32 * qt + 8 * i + 4]);
-        s[r] = fmaf(qa[0], (float)x[0], s[r]);
-        s[r] = fmaf(qa[1], (float)x[1], s[r]);
-        s[r] = fmaf(qa[2], (float)x[2], s[r]);
-        s[r] = fmaf(qa[3], (float)x[3], s[r]);
-        s[r] = fmaf(qb[0], (float)x[4], s[r]);
-        s[r] = fmaf(qb[1], (float)x[5], s[r]);
-        s[r] = fmaf(qb[2], (float)x[6], s[r]);
-        s[r] = fmaf(qb[3], (float)x[7], s[r]);
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      s[r] += __shfl_xor(s[r], 1);
-      s[r] += __shfl_xor(s[r], 2);
-      if (qt == 0) rs.sc[r][tk] = tk < n_in ? s[r] : -INFINITY;
-    }
-    __syncthreads();
-    for (int r = wave; r < R; r += 4) {  // one wavefront per head: tile max, numerators, sum
-      const float v0 = rs.sc[r][lane];
-      const float tm = wave_max(v0);
-      const float mold = rs.m[r], mnew = fmaxf(mold, tm);
-      const float p0 = exp2f(v0 - mnew);  // -inf gives 0
-      rs.sc[r][lane] = p0;
-      const float sum = wave_sum(p0);
-      if (lane == 0) {
-        const float sc_old = exp2f(mold - mnew);  // 0 on the first tile
-        rs.m[r] = mnew;
-        rs.scale[r] = sc_old;
-        rs.l[r] = rs.l[r] * sc_old + sum;
-      }
-    }
-    __syncthreads();
-    // ---- values: 16 tokens per thread ----
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r][0] *= rs.scale[r], acc[r][1] *= rs.scale[r];
-#pragma unroll 4
-    for (int k = 0; k < 16; ++k) {
-      const __half2 v2 = *reinterpret_cast<const __half2 *>(&rs.vt[16 * tq + k][2 * cp]);
-      const float vx = __low2float(v2), vy = __high2float(v2);
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float p = rs.sc[r][16 * tq + k];  // 0 for tokens past the end
-        acc[r][0] = fmaf(p, vx, acc[r][0]);
-        acc[r][1] = fmaf(p, vy, acc[r][1]);
-      }
-    }
-  }
-#pragma unroll
-  for (int r = 0; r < R; ++r) rs.accs[tq][r][2 * cp] = acc[r][0], rs.accs[tq][r][2 * cp + 1] = acc[r][1];
-  __syncthreads();
-  for (int x = tid; x < R * kD; x += 256) {
-    const int r = x >> 7, ch = x & 127;
-    float *part = L.workspace + (((long long)b * L.Hq + hk * R + r) * (SKVQ_MAX_SPLITS + 1) + part_index) * kPartialStride;
-    part[4 + ch] = rs.accs[0][r][ch] + rs.accs[1][r][ch] + rs.accs[2][r][ch] + rs.accs[3][r][ch];
-    if (ch == 0) {
-      part[0] = rs.m[r];
-      part[1] = rs.l[r];
-    }
-  }
-}
-
 // What one wavefront loads for one tile of 64 tokens.
 struct TileData {
   uint4_t k0, k1;       // lane = token: its 32-byte key row
@@ -282,33 +154,28 @@ struct TileData {
   Unit16 v0, v1;        // lane = unit of V block 2*tile and 2*tile+1
 };
 
+// What one wavefront loads for one slice of 4 fp16 ring tokens.
+struct RingData {
+  uint4_t k;      // lane (token = l/16, piece = l%16): 8 channels of the token's key row
+  unsigned v[4];  // lane = channel pair: the 4 tokens' values of channels 2l, 2l+1
+};
+
 template <int R, bool TERNARY>
-__global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
-                                                             long long T, long long nq, int n_splits,
-                                                             int tiles_per_split) {
-  // grid (n_splits + 1, Hk, B): x = 0 is the fp16 ring (partial index n_splits), x = 1 + sp
-  // is packed chunk sp.  The ring goes first so that it runs beside the packed chunks.
-  __shared__ union SharedUnion {
-    Smem<R, TERNARY> sm;
-    RingSmem<R> rs;
-    __device__ SharedUnion() {}
-  } shared;
+__global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
+                                                                  long long T, long long nq, int n_splits) {
+  // grid (n_splits, Hk, B).  Workgroup sp owns an even share of the packed 64-token tiles of
+  // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
+  // j = sp (mod n_splits), dealt the same way.
+  __shared__ Smem<R, TERNARY> sm;
   SKVQ_STAMP(0);
-  if (blockIdx.x == 0) {
-    ring_chunk<R>(L, shared.rs, q, T, nq, n_splits);
-    SKVQ_STAMP(3);
-    return;
-  }
-  Smem<R, TERNARY> &sm = shared.sm;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sp = blockIdx.x - 1, hk = blockIdx.y, b = blockIdx.z;
+  const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;
 
   // ---- this chunk, this wave's tiles ----
   const int n_tiles = (int)((nq + 63) >> 6);
-  (void)tiles_per_split;  // the packed tiles are dealt out evenly: chunk sizes differ by at most one
   const int tile_begin = (int)(((long long)sp * n_tiles) / n_splits);
   const int tile_end = (int)(((long long)(sp + 1) * n_tiles) / n_splits);
 
@@ -316,13 +183,13 @@ __global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __h
   const float2 *km = reinterpret_cast<const float2 *>(L.k_meta) + head * L.Tcap;
   const float2 *vm = reinterpret_cast<const float2 *>(L.v_meta) + head * L.Tcap;
   const uint8_t *vc = L.v_codes + head * L.n_vblocks * L.v_block_bytes;
-  const int last_blk = (int)((nq - 1) >> 5);
+  const int last_token = (int)(nq - 1);  // -1 when nothing is packed (then there are no tiles)
+  const int last_blk = last_token >> 5;
   const int vbb = TERNARY ? kTernaryBlockBytes : kTwoBitBlockBytes;
   const unsigned unit_off = TERNARY ? ((13 * lane) & ~3) : 16 * lane;
   const int unit_sh = TERNARY ? ((13 * lane) & 3) : 0;
   // token slot i = lane%8 sits in register m = i/2 at bit {4,6,8,8}[m]: undo 2^(bit-4)
   const float kslot_scale = ((lane >> 1) & 3) == 0 ? 1.f : ((lane >> 1) & 3) == 1 ? 0.25f : 0.0625f;
-  const int last_token = (int)(nq - 1);
 
   auto load_tile = [&](int tile) {
     TileData d;
@@ -341,38 +208,77 @@ __global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __h
     return d;
   };
 
-  // ---- prologue: one memory round trip (first tile, table, query, permutation), then LDS ----
+  // ---- the fp16 ring: slices of 16 tokens, slice j belongs to workgroup j % n_splits, wave
+  //      (j / n_splits) % kRingWaves ----
+  const int n_win = (int)(T - nq), W = L.W;
+  const int n_slices = (n_win + kRingSlice - 1) / kRingSlice;
+  const int ring_stride = n_splits * kRingWaves;
+  const int ring_first = sp + n_splits * wave;  // meaningful for wave < kRingWaves
+  const bool ring_owner = wave < kRingWaves && ring_first < n_slices;
+  const int slot0 = (int)(nq % W);
+  const __half *kwin = L.k_win + head * W * kD;
+  const __half *vwin = L.v_win + head * W * kD;
+  auto ring_slot = [&](int t) {  // ring slot of ring token t (clamped to the last one)
+    if (t >= n_win) t = n_win - 1;
+    int s = slot0 + t;
+    return s >= W ? s - W : s;
+  };
+  auto load_ring = [&](int slice) {
+    RingData d;
+    d.k = reinterpret_cast<const uint4_t *>(kwin + (size_t)ring_slot(slice * kRingSlice + (lane >> 4)) * kD)[lane & 15];
+#pragma unroll
+    for (int k = 0; k < kRingSlice; ++k)
+      d.v[k] = reinterpret_cast<const unsigned *>(vwin + (size_t)ring_slot(slice * kRingSlice + k) * kD)[lane];
+    return d;
+  };
+
+  // ---- prologue: one memory round trip.  The small loads (query, permutations, table) are
+  //      issued BEFORE the tile loads: loads return in order, so the staging below only has to
+  //      wait for them and not for the two tiles of packed data behind them. ----
+  __half2 q2 = __floats2half2_rn(0.f, 0.f);
+  if (tid < 64 * R) q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * R + (tid >> 6)) * kD)[lane];
+  const int pk = L.perm_k[hk * kD + (tid & 127)];
+  const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
+  uint4_t lut_piece[3];
+  if (TERNARY) {
+    const uint4_t *src = reinterpret_cast<const uint4_t *>(L.trit_lut);
+#pragma unroll
+    for (int x = 0; x < 3; ++x)  // 6561 entries = 1641 16-byte pieces; fields of valid data stay below
+      if (tid + kThreads * x < 1641) lut_piece[x] = src[tid + kThreads * x];
+  }
+  asm volatile("" ::: "memory");
   int tile = tile_begin + wave;
   TileData cur, nxt;
   if (tile < tile_end) cur = load_tile(tile);
   nxt = cur;
-  if (tile + 4 < tile_end) nxt = load_tile(tile + 4);
+  if (tile + kNW < tile_end) nxt = load_tile(tile + kNW);
+  RingData ring;
+  if (ring_owner) ring = load_ring(ring_first);
   {
-    const int r = tid >> 6;  // 64 threads load one query head as half2
-    __half2 q2 = __floats2half2_rn(0.f, 0.f);
-    if (r < R) q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * R + r) * kD)[lane];
-    const int pk = L.perm_k[hk * kD + (tid & 127)];
+    if (tid < 256) {
+      sm.qraw[tid >> 6][2 * lane] = __low2float(q2);
+      sm.qraw[tid >> 6][2 * lane + 1] = __high2float(q2);
+    }
     if (TERNARY) {
-      const uint4_t *src = reinterpret_cast<const uint4_t *>(L.trit_lut);
       uint4_t *dst = reinterpret_cast<uint4_t *>(sm.lut);
 #pragma unroll
-      for (int x = 0; x < 7; ++x)  // 6561 entries = 1641 16-byte pieces; fields of valid data stay below
-        if (tid + 256 * x < 1641) dst[tid + 256 * x] = src[tid + 256 * x];
+      for (int x = 0; x < 3; ++x)
+        if (tid + kThreads * x < 1641) dst[tid + kThreads * x] = lut_piece[x];
     }
-    sm.qraw[r][2 * lane] = __low2float(q2);
-    sm.qraw[r][2 * lane + 1] = __high2float(q2);
     __syncthreads();
+    if (tid < 256) {
 #pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {  // thread (p = tid%128, heads tid/128 and tid/128 + 2)
-      const int row = (tid >> 7) + 2 * rr, p = tid & 127;
-      int step, kslot, shift;
-      k_slot_of(p, step, kslot, shift);
-      sm.qa[step][row][kslot] = (_Float16)ldexpf(sm.qraw[row][pk], 8 - shift);  // exact: a power of two
-    }
-    const float v = wave_sum(sm.qraw[wave][lane] + sm.qraw[wave][lane + 64]);  // wave r sums head r
-    if (lane == 0) {
-      sm.qsum[wave] = c * v;
-      sm.qinit[wave] = -1.5f * v * (1.0f / 65536.0f);
+      for (int rr = 0; rr < 2; ++rr) {  // thread (p = tid%128, heads tid/128 and tid/128 + 2)
+        const int row = (tid >> 7) + 2 * rr, p = tid & 127;
+        int step, kslot, shift;
+        k_slot_of(p, step, kslot, shift);
+        sm.qa[step][row][kslot] = (_Float16)ldexpf(sm.qraw[row][pk], 8 - shift);  // exact: a power of two
+      }
+      const float v = wave_sum(sm.qraw[wave][lane] + sm.qraw[wave][lane + 64]);  // wave r sums head r
+      if (lane == 0) {
+        sm.qsum[wave] = c * v;
+        sm.qinit[wave] = -1.5f * v * (1.0f / 65536.0f);
+      }
     }
     __syncthreads();
   }
@@ -386,6 +292,67 @@ __global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __h
   // codes, which keeps both halves of  scale*sum q(c-1.5) + (zero+1.5 scale)*sum q  small.
   const float4_t dinit = {sm.qinit[0], sm.qinit[1], sm.qinit[2], sm.qinit[3]};
 
+  // ---- ring slices of this wave (plain vector arithmetic, wave-local) ----
+  if (ring_owner) {
+    float rm[R], rl[R], ro[R][2];  // reference, sum of weights, outputs
+#pragma unroll
+    for (int r = 0; r < R; ++r) rm[r] = -INFINITY, rl[r] = 0.f, ro[r][0] = ro[r][1] = 0.f;
+    for (int slice = ring_first; slice < n_slices; slice += ring_stride) {
+      RingData ring_next = ring;
+      if (slice + ring_stride < n_slices) ring_next = load_ring(slice + ring_stride);
+      const int tk = lane >> 4, pc = lane & 15;  // token of the slice, 8-channel piece of its row
+      const bool valid = slice * kRingSlice + tk < n_win;
+      const half8_t x = __builtin_bit_cast(half8_t, ring.k);
+      float p[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float4_t qa = *reinterpret_cast<const float4_t *>(&sm.qraw[r][8 * pc]);
+        const float4_t qb = *reinterpret_cast<const float4_t *>(&sm.qraw[r][8 * pc + 4]);
+        float s = qa[0] * (float)x[0];
+        s = fmaf(qa[1], (float)x[1], s);
+        s = fmaf(qa[2], (float)x[2], s);
+        s = fmaf(qa[3], (float)x[3], s);
+        s = fmaf(qb[0], (float)x[4], s);
+        s = fmaf(qb[1], (float)x[5], s);
+        s = fmaf(qb[2], (float)x[6], s);
+        s = fmaf(qb[3], (float)x[7], s);
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        s += __shfl_xor(s, 4);
+        s += __shfl_xor(s, 8);  // all sixteen lanes of a token now hold its score
+        s = valid ? c * s : -INFINITY;
+        const float mnew = fmaxf(rm[r], fmaxf(fmaxf(s, __shfl_xor(s, 16)), fmaxf(__shfl_xor(s, 32), __shfl_xor(s, 48))));
+        const float f = exp2f(rm[r] - mnew);  // 0 for the first slice
+        p[r] = exp2f(s - mnew);               // 0 for tokens past the end
+        rl[r] = rl[r] * f + (p[r] + __shfl_xor(p[r], 16)) + (__shfl_xor(p[r], 32) + __shfl_xor(p[r], 48));
+        ro[r][0] *= f;
+        ro[r][1] *= f;
+        rm[r] = mnew;
+      }
+#pragma unroll
+      for (int k = 0; k < kRingSlice; ++k) {
+        const __half2 v2 = __builtin_bit_cast(__half2, ring.v[k]);
+        const float vx = __low2float(v2), vy = __high2float(v2);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const float pk = __shfl(p[r], 16 * k);
+          ro[r][0] = fmaf(pk, vx, ro[r][0]);
+          ro[r][1] = fmaf(pk, vy, ro[r][1]);
+        }
+      }
+      ring = ring_next;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      sm.ring_o[wave][r][2 * lane] = ro[r][0];
+      sm.ring_o[wave][r][2 * lane + 1] = ro[r][1];
+      if (lane == 0) sm.rm[wave][r] = rm[r], sm.rl[wave][r] = rl[r];
+    }
+  } else if (lane < R) {
+    sm.rm[wave][lane] = -INFINITY;
+    sm.rl[wave][lane] = 0.f;
+  }
+
   float mref[R], lsum[R], zacc[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) mref[r] = 0.f, lsum[r] = 0.f, zacc[r] = 0.f;
@@ -396,9 +363,9 @@ __global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __h
   bool first = true;
 
   SKVQ_STAMP(1);
-  for (; tile < tile_end; tile += 4) {
+  for (; tile < tile_end; tile += kNW) {
     TileData nxt2 = nxt;
-    if (tile + 8 < tile_end) nxt2 = load_tile(tile + 8);  // two tiles are in flight while this one is computed
+    if (tile + 2 * kNW < tile_end) nxt2 = load_tile(tile + 2 * kNW);  // two tiles in flight while this one is computed
     const bool valid = tile * 64 + lane <= last_token;
 
     // ---- scores: 32 products of 4 channels each ----
@@ -521,9 +488,19 @@ __global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __h
   }
 
   SKVQ_STAMP(2);
-  // ---- epilogue: fold columns, lanes and the four waves; write this chunk's partial ----
-  __syncthreads();  // `stage` shares its memory with the table that slower waves may still read
-  {
+  // ---- epilogue: fold lanes, columns, waves and ring slices; write this chunk's partial ----
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const float ls = wave_sum(lsum[r]), zs = wave_sum(zacc[r]);
+    if (lane == 0) {
+      sm.wm[wave][r] = first ? -INFINITY : mref[r];
+      sm.wl[wave][r] = ls;
+      sm.wz[wave][r] = zs;
+    }
+  }
+  __syncthreads();  // also: no wave reads the table any more, `stage` may overwrite it
+  SKVQ_STAMP(8);
+  if (!first) {
     const int col = lane & 15, kb = lane >> 4;
     const float unscale = 1048576.0f / beta;  // codes carried 2^(4-24)
     if (col < 2 * R) {
@@ -532,34 +509,41 @@ __global__ __launch_bounds__(256, 3) void decode_mfma_kernel(Layout L, const __h
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) sm.stage[wave][col][16 * n + 4 * kb + rr] = acc[n][rr] * unscale;
     }
+  }
+  if (tid < 16 * R) {
+    // thread (head r, wave w): the chunk's reference m* = max over waves, the wave's factors
+    // 2^(m_w - m*), and the sums that need no channel; reductions over the 16 lanes of a head
+    const int r = tid >> 4, w = tid & 15;
+    const bool in = w < kNW;
+    const float wl = in ? sm.wl[w][r] : 0.f, rl = in ? sm.rl[w][r] : 0.f;
+    const float wm = wl > 0.f ? sm.wm[w][r] : -INFINITY, rm = rl > 0.f ? sm.rm[w][r] : -INFINITY;
+    float m = fmaxf(wm, rm);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const float ls = wave_sum(lsum[r]), zs = wave_sum(zacc[r]);
-      if (lane == 0) {
-        sm.wm[wave][r] = first ? -INFINITY : mref[r];
-        sm.wl[wave][r] = ls;
-        sm.wz[wave][r] = zs;
-      }
-    }
+    for (int off = 1; off < 16; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
+    const float e = wl > 0.f ? exp2f(wm - m) : 0.f, g = rl > 0.f ? exp2f(rm - m) : 0.f;
+    float den = e * wl + g * rl, zsum = in ? e * sm.wz[w][r] : 0.f;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) den += __shfl_xor(den, off), zsum += __shfl_xor(zsum, off);
+    if (in) sm.ew[w][r] = e, sm.er[w][r] = g;
+    if (w == 0) sm.mstar[r] = m, sm.den[r] = den, sm.zsum[r] = zsum;
   }
   __syncthreads();
-  for (int x = tid; x < R * kD; x += 256) {
-    const int r = x >> 7, p = x & 127;
-    const float mstar = fmaxf(fmaxf(sm.wm[0][r], sm.wm[1][r]), fmaxf(sm.wm[2][r], sm.wm[3][r]));
-    float num = 0.f, den = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      if (sm.wl[w][r] > 0.f) {
-        const float e = exp2f(sm.wm[w][r] - mstar);
-        den += e * sm.wl[w][r];
-        num += e * (sm.stage[w][r][p] + sm.stage[w][R + r][p] + sm.wz[w][r]);
-      }
+  SKVQ_STAMP(9);
+  if (tid < R * kD) {
+    const int r = tid >> 7, p = tid & 127;
+    const int ch = pv_ch;
+    float num = sm.zsum[r];
+#pragma unroll 4
+    for (int w = 0; w < kNW; ++w) {
+      const float e = sm.ew[w][r], g = sm.er[w][r];
+      if (e > 0.f) num = fmaf(e, sm.stage[w][r][p] + sm.stage[w][R + r][p], num);
+      if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
     float *part = L.workspace + (((long long)b * L.Hq + hk * R + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
-    part[4 + L.perm_v[hk * kD + p]] = num;
+    part[4 + ch] = num;
     if (p == 0) {
-      part[0] = mstar;
-      part[1] = den;
+      part[0] = sm.mstar[r];
+      part[1] = sm.den[r];
     }
   }
   SKVQ_STAMP(3);
@@ -576,13 +560,13 @@ extern "C" int skvq_debug_read_timing(unsigned long long *host, int n) {
 bool decode_mfma_supported(const Layout &L) { return L.G == kD && (L.R == 1 || L.R == 2 || L.R == 4); }
 
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
-                              long long tiles_per_split, hipStream_t s) {
-  if (nq <= 0 || nq > 0x7fffffffll * 32 || tiles_per_split > 0x7fffffff || T - nq > 0x7fffffff)
+                              hipStream_t s) {
+  if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
+      n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
-  const dim3 grid(n_splits + 1, L.Hk, L.B), block(256);
-  const int tps = (int)tiles_per_split;
+  const dim3 grid(n_splits, L.Hk, L.B), block(kThreads);
 #define SKVQ_LAUNCH(RR, TT) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT>), grid, block, 0, s, L, q, T, nq, n_splits, tps)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT>), grid, block, 0, s, L, q, T, nq, n_splits)
   const bool ter = L.v_levels == 3;
   switch (L.R) {
     case 1: if (ter) SKVQ_LAUNCH(1, true); else SKVQ_LAUNCH(1, false); break;

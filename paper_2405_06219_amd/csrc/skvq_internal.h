@@ -14,6 +14,10 @@ constexpr int kVBlock = 32;    // tokens per V block
 constexpr int kTernaryBlockBytes = 832;
 constexpr int kTwoBitBlockBytes = 1024;
 constexpr int kPartialStride = kD + 4;  // floats per split partial: m, l, pad, pad, acc[D]
+// byte offset of the per-(b, hk) workgroup counters inside the workspace
+inline size_t counters_offset(int B, int Hq) {
+  return (size_t)B * Hq * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
+}
 
 // Everything a kernel needs to find its data; passed by value.
 struct Layout {
@@ -29,6 +33,7 @@ struct Layout {
   float *k_meta, *v_meta;
   __half *k_win, *v_win;
   float *workspace;
+  unsigned *counters;            // in the workspace, after the partials: one per (b, hk), zero between calls
   const int *perm_k, *perm_v;    // device copies [Hk][D]
   const float *clip_k, *clip_v;  // device copies [Hk][NG]
   const uint32_t *trit_lut;      // device, 8192 entries (see skvq_decode.hip)
@@ -46,11 +51,12 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
                          long long T, int n_splits, hipStream_t s);
 
 // Matrix-core chunk kernel for the packed region (skvq_decode_mfma.hip): group size 128,
-// 1, 2 or 4 query heads per kv head.  Writes partials 0..n_splits-1 and the ring's partial
-// (index n_splits).
+// 1, 2 or 4 query heads per kv head.  Packed chunks and the fp16 ring; writes partials
+// 0..n_splits-1 (n_splits >= 1 even when nothing is packed yet).
 bool decode_mfma_supported(const Layout &L);
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
-                              long long tiles_per_split, hipStream_t s);
+                              hipStream_t s);
+constexpr int kMfmaWavesPerGroup = 12;  // wavefronts per workgroup of the matrix-core kernel
 
 // Fills the 8192-entry table that expands a 13-bit base-3 field into eight 2-bit codes.
 void build_trit_lut(uint32_t *host_table);
