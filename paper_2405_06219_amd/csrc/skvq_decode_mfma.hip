@@ -102,7 +102,7 @@ __device__ __forceinline__ half8_t unpack_v_field(unsigned f) {
   return __builtin_bit_cast(half8_t, uint4_t{a & kM4, a & kM6, a & kM8, b & kM8});
 }
 
-constexpr int kNW = 12;             // wavefronts per workgroup (3 per SIMD)
+constexpr int kNW = 8;              // wavefronts per workgroup (2 per SIMD: 256 registers each)
 constexpr int kThreads = 64 * kNW;
 constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
 constexpr int kRingSlice = 4;       // ring tokens per slice
@@ -161,7 +161,7 @@ struct RingData {
 };
 
 template <int R, bool TERNARY>
-__global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
+__global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_splits) {
   // grid (n_splits, Hk, B).  Workgroup sp owns an even share of the packed 64-token tiles of
   // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
@@ -191,18 +191,25 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
   // token slot i = lane%8 sits in register m = i/2 at bit {4,6,8,8}[m]: undo 2^(bit-4)
   const float kslot_scale = ((lane >> 1) & 3) == 0 ? 1.f : ((lane >> 1) & 3) == 1 ? 0.25f : 0.0625f;
 
+  // Loads are issued unconditionally (a tile index past the end is redirected to the last
+  // tile, whose lines are in cache by then, and the data is ignored): the compiler can then
+  // count the loads in flight and wait for exactly the ones a tile needs.
+  const int safe_last_tile = n_tiles > 0 ? n_tiles - 1 : 0;
+  const int safe_last_token = last_token > 0 ? last_token : 0;
+  const int safe_last_blk = last_blk > 0 ? last_blk : 0;
   auto load_tile = [&](int tile) {
     TileData d;
+    if (tile > safe_last_tile) tile = safe_last_tile;
+    if (tile < 0) tile = 0;
     int t = tile * 64 + lane;
-    if (t > last_token) t = last_token;  // only in the last tile; such lanes are masked below
-    const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)tile * 2048) + 2 * lane;
-    if (tile * 64 + 63 > last_token) krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * 32);
+    if (t > safe_last_token) t = safe_last_token;  // only in the last tile; such lanes are masked below
+    const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * 32);
     d.k0 = krow[0];
     d.k1 = krow[1];
     d.kmeta = km[t];
     d.vmeta = vm[t];
-    const int blk0 = 2 * tile;
-    const int blk1 = blk0 + 1 > last_blk ? last_blk : blk0 + 1;
+    const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
+    const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
     d.v0 = *reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off);
     d.v1 = *reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off);
     return d;
@@ -239,21 +246,21 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
   if (tid < 64 * R) q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * R + (tid >> 6)) * kD)[lane];
   const int pk = L.perm_k[hk * kD + (tid & 127)];
   const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
-  uint4_t lut_piece[3];
+  uint4_t lut_piece[4];
   if (TERNARY) {
     const uint4_t *src = reinterpret_cast<const uint4_t *>(L.trit_lut);
 #pragma unroll
-    for (int x = 0; x < 3; ++x)  // 6561 entries = 1641 16-byte pieces; fields of valid data stay below
+    for (int x = 0; x < 4; ++x)  // 6561 entries = 1641 16-byte pieces; fields of valid data stay below
       if (tid + kThreads * x < 1641) lut_piece[x] = src[tid + kThreads * x];
   }
   asm volatile("" ::: "memory");
-  int tile = tile_begin + wave;
-  TileData cur, nxt;
-  if (tile < tile_end) cur = load_tile(tile);
-  nxt = cur;
-  if (tile + kNW < tile_end) nxt = load_tile(tile + kNW);
-  RingData ring;
-  if (ring_owner) ring = load_ring(ring_first);
+  // three tile buffers used in turn (no register copies): while one tile is computed the
+  // next two are in flight
+  int tile_a = tile_begin + wave, tile_b = tile_a + kNW, tile_c = tile_b + kNW;
+  TileData buf_a, buf_b, buf_c;
+  buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
+  buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
+  RingData ring = load_ring(ring_first < n_slices ? ring_first : n_slices - 1);
   {
     if (tid < 256) {
       sm.qraw[tid >> 6][2 * lane] = __low2float(q2);
@@ -262,10 +269,11 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
     if (TERNARY) {
       uint4_t *dst = reinterpret_cast<uint4_t *>(sm.lut);
 #pragma unroll
-      for (int x = 0; x < 3; ++x)
+      for (int x = 0; x < 4; ++x)
         if (tid + kThreads * x < 1641) dst[tid + kThreads * x] = lut_piece[x];
     }
     __syncthreads();
+    SKVQ_STAMP(10);
     if (tid < 256) {
 #pragma unroll
       for (int rr = 0; rr < 2; ++rr) {  // thread (p = tid%128, heads tid/128 and tid/128 + 2)
@@ -281,6 +289,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
       }
     }
     __syncthreads();
+    SKVQ_STAMP(11);
   }
   // lane l supplies row l%4 (= head) of step l/4 (first register pair) and 16 + l/4 (second)
   const half4_t qop_lo = *reinterpret_cast<const half4_t *>(sm.qa[lane >> 2][lane & 3]);
@@ -298,8 +307,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
 #pragma unroll
     for (int r = 0; r < R; ++r) rm[r] = -INFINITY, rl[r] = 0.f, ro[r][0] = ro[r][1] = 0.f;
     for (int slice = ring_first; slice < n_slices; slice += ring_stride) {
-      RingData ring_next = ring;
-      if (slice + ring_stride < n_slices) ring_next = load_ring(slice + ring_stride);
+      const RingData ring_next = load_ring(slice + ring_stride < n_slices ? slice + ring_stride : slice);
       const int tk = lane >> 4, pc = lane & 15;  // token of the slice, 8-channel piece of its row
       const bool valid = slice * kRingSlice + tk < n_win;
       const half8_t x = __builtin_bit_cast(half8_t, ring.k);
@@ -363,9 +371,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
   bool first = true;
 
   SKVQ_STAMP(1);
-  for (; tile < tile_end; tile += kNW) {
-    TileData nxt2 = nxt;
-    if (tile + 2 * kNW < tile_end) nxt2 = load_tile(tile + 2 * kNW);  // two tiles in flight while this one is computed
+  auto compute_tile = [&](const TileData &cur, const int tile) {
     const bool valid = tile * 64 + lane <= last_token;
 
     // ---- scores: 32 products of 4 channels each ----
@@ -483,8 +489,22 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_kernel(Layout L, cons
       }
     }
     __builtin_amdgcn_wave_barrier();
-    cur = nxt;
-    nxt = nxt2;
+  };
+  while (tile_a < tile_end) {
+    buf_c = load_tile(tile_c < tile_end ? tile_c : tile_end - 1);
+    compute_tile(buf_a, tile_a);
+#ifdef SKVQ_TIMING
+    if (tile_a == tile_begin + wave) { SKVQ_STAMP(12); }
+#endif
+    if (tile_b >= tile_end) break;
+    tile_a += 3 * kNW;
+    buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
+    compute_tile(buf_b, tile_b);
+    if (tile_c >= tile_end) break;
+    tile_b += 3 * kNW;
+    buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
+    compute_tile(buf_c, tile_c);
+    tile_c += 3 * kNW;
   }
 
   SKVQ_STAMP(2);

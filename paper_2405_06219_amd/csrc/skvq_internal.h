@@ -56,7 +56,7 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
 bool decode_mfma_supported(const Layout &L);
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
                               hipStream_t s);
-constexpr int kMfmaWavesPerGroup = 12;  // wavefronts per workgroup of the matrix-core kernel
+constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel
 
 // Fills the 8192-entry table that expands a 13-bit base-3 field into eight 2-bit codes.
 void build_trit_lut(uint32_t *host_table);
