@@ -168,3 +168,23 @@ def test_runtime_errors(P):
     assert e.value.status == B.SKVQ_ERR_CAPACITY
     assert pair.gpu.skvq_get_state() == (302, 174, 128)
     torch.cuda.synchronize()
+
+
+def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
+    """Mistral-7B-shaped layer at 131072 tokens (the benchmark's workload, library-chosen split
+    count): every packed byte, every (scale, zero) and the ring bit-exact against the oracle's
+    own prefill of the same seeded inputs, after appends too; attention outputs within 2e-3."""
+    w = synth.WORKLOADS["c3_mistral7b_128k"]
+    P.log(f"full size: generating {w.name}")
+    pair, k, v, q = P.make_pair(w, extra_tokens=4)
+    P.log("full size: prefill (oracle + gpu)")
+    pair.prefill(k, v)
+    del k, v
+    for s in range(3):
+        pair.append(*synth.make_new_token(w, s))
+    pair.assert_buffers_equal()
+    P.log("full size: decode (oracle + gpu)")
+    out, ref = pair.decode_both(q)
+    err = np.abs(out - ref).max()
+    P.log(f"full size c3: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
+    assert err <= P.TOL
