@@ -208,8 +208,8 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
 
 // Combines the chunk partials of one (sequence, query head): out = sum_i acc_i 2^(m_i - m*) /
 // sum_i l_i 2^(m_i - m*).  Partials hold base-2 exponents.  grid (Hq, B), 1024 threads:
-// wavefront 0 turns the (m_i, l_i) into weights, then thread (channel, slice) adds every
-// eighth partial so that all loads of a thread are in flight together.
+// wavefront 0 turns the (m_i, l_i) into weights, thread (channel, slice) adds every eighth
+// partial.
 __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict__ out_f32,
                                                      __half *__restrict__ out_f16, int n_all) {
   __shared__ float wts[SKVQ_MAX_SPLITS + 1];
@@ -217,6 +217,14 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
   __shared__ float red[8][kD];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const float *base = L.workspace + ((long long)b * L.Hq + hq) * (SKVQ_MAX_SPLITS + 1) * kPartialStride;
+  const int ch = tid & 127, sl = tid >> 7;
+  // the first 32 partials' values are requested before their weights are known: one round trip
+  float pre[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = sl + 8 * k;
+    pre[k] = i < n_all ? base[(long long)i * kPartialStride + 4 + ch] : 0.f;
+  }
   if (tid < 64) {
     float mi[3], li[3], mstar = -INFINITY;
 #pragma unroll
@@ -242,9 +250,13 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
     if (tid == 0) den_s = den;
   }
   __syncthreads();
-  const int ch = tid & 127, sl = tid >> 7;
   float num = 0.f;
-  for (int i = sl; i < n_all; i += 8) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = sl + 8 * k;
+    if (i < n_all && wts[i] > 0.f) num = fmaf(wts[i], pre[k], num);
+  }
+  for (int i = sl + 32; i < n_all; i += 8) {
     const float w = wts[i];
     if (w > 0.f) num = fmaf(w, base[(long long)i * kPartialStride + 4 + ch], num);
   }

@@ -465,17 +465,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         const unsigned u1 = __builtin_amdgcn_alignbyte(raw.z, raw.y, unit_sh);
         const unsigned u2 = __builtin_amdgcn_alignbyte(raw.w, raw.z, unit_sh);
         const unsigned u3 = raw.w >> (8 * unit_sh);
+        // byte offsets into the table (field * 4), two operations per field
         unsigned f[8], fld[8];
-        f[0] = u0 & 0x1fffu;
-        f[1] = (u0 >> 13) & 0x1fffu;
-        f[2] = __builtin_amdgcn_alignbit(u1, u0, 26) & 0x1fffu;
-        f[3] = (u1 >> 7) & 0x1fffu;
-        f[4] = __builtin_amdgcn_alignbit(u2, u1, 20) & 0x1fffu;
-        f[5] = (u2 >> 1) & 0x1fffu;
-        f[6] = (u2 >> 14) & 0x1fffu;
-        f[7] = __builtin_amdgcn_alignbit(u3, u2, 27) & 0x1fffu;
+        f[0] = (u0 << 2) & 0x7ffcu;
+        f[1] = (u0 >> 11) & 0x7ffcu;
+        f[2] = __builtin_amdgcn_alignbit(u1, u0, 24) & 0x7ffcu;
+        f[3] = (u1 >> 5) & 0x7ffcu;
+        f[4] = __builtin_amdgcn_alignbit(u2, u1, 18) & 0x7ffcu;
+        f[5] = (u2 << 1) & 0x7ffcu;
+        f[6] = (u2 >> 12) & 0x7ffcu;
+        f[7] = __builtin_amdgcn_alignbit(u3, u2, 25) & 0x7ffcu;
 #pragma unroll
-        for (int n = 0; n < 8; ++n) fld[n] = sm.lut[f[n]];
+        for (int n = 0; n < 8; ++n)
+          fld[n] = *reinterpret_cast<const unsigned *>(reinterpret_cast<const char *>(sm.lut) + f[n]);
 #pragma unroll
         for (int n = 0; n < 8; ++n)
           acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_entry(fld[n]), pop, acc[n], 0, 0, 0);
