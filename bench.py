@@ -26,6 +26,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 D = 128
+# HBM bytes per skvq_decode_attention call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (chunk kernel + merge kernel, counters scaled by a plain copy of known size); see
+# profiles/decode_c3_mistral7b_128k_pmc.txt.  Only workloads that were measured have an entry.
+MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 78228 * 1024}
 
 
 def algorithmic_bytes_decode(w, n_tokens: int) -> int:
@@ -212,7 +216,8 @@ def main() -> int:
         "effective_hbm_gbps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w.context == synth.WORKLOADS[w.name].context else None,
                      "kernel": "skvq_decode_attention", "bytes_per_launch": alg_bytes,
                      "avg_launch_us": dec_avg_us},
     }
