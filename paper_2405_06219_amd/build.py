@@ -19,8 +19,11 @@ SOURCES = {
     "skvq_api.hip": [],
     "skvq_quantize.hip": ["-ffp-contract=off"],
     "skvq_decode.hip": [],
-    "skvq_decode_mfma.hip": ["-Rpass-analysis=kernel-resource-usage"] if os.environ.get("SKVQ_RESOURCE_USAGE") else [],
+    "skvq_decode_mfma.hip": [],
 }
+# SKVQ_RESOURCE_USAGE=1 prints each kernel's registers, scratch and LDS
+if os.environ.get("SKVQ_RESOURCE_USAGE"):
+    COMMON.append("-Rpass-analysis=kernel-resource-usage")
 
 
 def build(verbose: bool = False) -> str:

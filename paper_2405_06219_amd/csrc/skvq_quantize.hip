@@ -1,10 +1,11 @@
 // Quantize-on-evict and prefill-quantize kernels (Section 3.1 Eq. 2, Section 3.2,
 // Algorithm 1 clipping_quant) for gfx950.
 //
-// One wavefront owns one (token, kv head) row at a time: lane l holds the two reordered
-// positions 2l and 2l+1, the group minimum/maximum is a cross-lane butterfly over the G/2
-// lanes of a group, and every fp32 operation of Eq. 2 is issued as an explicitly rounded
-// intrinsic so that the compiler can neither fuse nor reorder them.
+// Append: one wavefront owns one (token, kv head) row; lane l holds the two reordered
+// positions 2l and 2l+1 and the group minimum/maximum is a cross-lane butterfly over the G/2
+// lanes of a group.  Prefill: one wavefront owns eight rows; a lane holds sixteen consecutive
+// reordered positions of one of them.  Every fp32 operation of Eq. 2 is issued as an explicitly
+// rounded intrinsic so that the compiler can neither fuse nor reorder them.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -92,14 +93,58 @@ __device__ __forceinline__ unsigned trit_field(unsigned c8) {
 // ---------------------------------------------------------------------------------------
 // Prefill: one workgroup (4 wavefronts) per V block of 32 tokens of one (b, hk); wavefront w
 // handles the 8 tokens of sub-block kb = w, K and V, and builds that sub-block's 16 V units.
+//
+// The 8 fp16 rows of a wavefront (2 KB, contiguous in the source) arrive with two 16-byte loads
+// per lane and are parked in LDS.  Lane (i = lane / 8, n = lane % 8) then owns the 16 reordered
+// positions 16n .. 16n+15 of token i: it gathers them through the permutation, reduces
+// min/max with the other lanes of its group, and encodes them (Eq. 2).  Its sixteen key codes
+// are dword n of the token's packed row, so a wavefront stores 256 contiguous bytes.  Its
+// sixteen value codes are exactly the codes (n, i) of units j = 0..15, which a second set of
+// lanes (j = lane % 16, two fields each) collects from LDS to build the units.
 // ---------------------------------------------------------------------------------------
+constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte alignment and
+                                 // puts the same channel of the 8 rows in 8 different banks
+
+// Gathers positions 16n..16n+15 of one parked row, finds the group's Eq. 2 parameters and
+// returns this lane's 16 codes packed two bits each (position 16n + e at bits [2e, 2e+2)).
+__device__ __forceinline__ unsigned encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
+                                             float top, GroupParams &gp) {
+  const int ch[16] = {pm[0].x, pm[0].y, pm[0].z, pm[0].w, pm[1].x, pm[1].y, pm[1].z, pm[1].w,
+                      pm[2].x, pm[2].y, pm[2].z, pm[2].w, pm[3].x, pm[3].y, pm[3].z, pm[3].w};
+  float x[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) x[e] = __half2float(row[ch[e]]);
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int e = 1; e < 16; ++e) {
+    mn = fminf(mn, x[e]);
+    mx = fmaxf(mx, x[e]);
+  }
+  for (int off = 1; off < G / 16; off <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off));
+    mx = fmaxf(mx, __shfl_xor(mx, off));
+  }
+  gp = group_params(mn, mx, alpha, top);
+  // code = rint(clamp(y, 0, top)): clamping first gives the same integer because the bounds are
+  // integers; adding 1.5 * 2^23 rounds to the nearest integer, ties to even, and leaves the code
+  // in the two low bits of the sum, which alignbit shifts into the row word from the top.
+  unsigned w = 0;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const float y = __fmul_rn(__fsub_rn(x[e], gp.lo), gp.inv);
+    const float r = __fadd_rn(__builtin_amdgcn_fmed3f(y, 0.0f, top), 12582912.0f);
+    w = __builtin_amdgcn_alignbit(__float_as_uint(r), w, 2);
+  }
+  return w;
+}
+
 __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
                                                       long long nq) {
-  __shared__ __half rows[4][kD];
-  __shared__ unsigned vq[4][64];
+  __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
+  __shared__ unsigned vq[4][8][8];                            // [wave][token i][n]: 16 codes, j-minor
   __shared__ unsigned pieces[4][64];
-  __shared__ __align__(16) uint8_t units[4][256];
+  __shared__ __align__(16) uint8_t units[4][208];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int hk = blockIdx.y, b = blockIdx.z;
@@ -107,55 +152,75 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   const long long blk = blockIdx.x;
   const long long t0 = blk * kVBlock + 8 * wave;
 
-  const int pk0 = L.perm_k[hk * kD + 2 * lane], pk1 = L.perm_k[hk * kD + 2 * lane + 1];
-  const int pv0 = L.perm_v[hk * kD + 2 * lane], pv1 = L.perm_v[hk * kD + 2 * lane + 1];
-  const int grp = (2 * lane) / L.G;
-  const float ak = L.clip_k[hk * L.NG + grp], av = L.clip_v[hk * L.NG + grp];
-  const float vtop = (float)(L.v_levels - 1);
-
-  unsigned vpack = 0;  // low half: position 2l, high half: position 2l+1; token i at bits 2i
-  for (int i = 0; i < 8; ++i) {
-    const long long t = t0 + i;
-    const bool valid = t < nq;  // uniform over the wavefront
-    const long long src = (head * T + (valid ? t : 0)) * kD;
-    unsigned c0, c1;
-    float scale, zero;
-    // keys
-    reinterpret_cast<__half2 *>(rows[wave])[lane] = reinterpret_cast<const __half2 *>(ksrc + src)[lane];
-    __syncthreads();
-    encode_row(rows[wave], pk0, pk1, ak, L.G, 3.0f, c0, c1, scale, zero);
-    if (valid) {
-      store_k_row(L.k_codes + (head * L.Tcap + t) * (kD / 4), lane, c0, c1);
-      if ((2 * lane) % L.G == 0)
-        reinterpret_cast<float2 *>(L.k_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(scale, zero);
-    }
-    __syncthreads();
-    // values
-    reinterpret_cast<__half2 *>(rows[wave])[lane] = reinterpret_cast<const __half2 *>(vsrc + src)[lane];
-    __syncthreads();
-    encode_row(rows[wave], pv0, pv1, av, L.G, vtop, c0, c1, scale, zero);
-    if (valid) {
-      vpack |= (c0 | (c1 << 16)) << (2 * i);
-      if ((2 * lane) % L.G == 0)
-        reinterpret_cast<float2 *>(L.v_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(scale, zero);
-    }
-    __syncthreads();
+  // Source rows; rows past the end of the prompt are replaced by its last row and never stored.
+  {
+    const int lr = lane >> 4, lp = lane & 15;
+    long long ta = t0 + lr, tb = t0 + 4 + lr;
+    ta = ta < T ? ta : T - 1;
+    tb = tb < T ? tb : T - 1;
+    const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + head * T * kD);
+    const uint4 *vs = reinterpret_cast<const uint4 *>(vsrc + head * T * kD);
+    const uint4 ka = ks[ta * 16 + lp], kb = ks[tb * 16 + lp];
+    const uint4 va = vs[ta * 16 + lp], vb = vs[tb * 16 + lp];
+    *reinterpret_cast<uint4 *>(&rows[wave][0][lr][8 * lp]) = ka;
+    *reinterpret_cast<uint4 *>(&rows[wave][0][4 + lr][8 * lp]) = kb;
+    *reinterpret_cast<uint4 *>(&rows[wave][1][lr][8 * lp]) = va;
+    *reinterpret_cast<uint4 *>(&rows[wave][1][4 + lr][8 * lp]) = vb;
   }
-
-  // V units of sub-block kb = wave.  Lane (j = lane%16, nh = lane/16) builds fields 2nh, 2nh+1
-  // of unit j; position 16n + j was encoded by lane 8n + j/2, half j%2.
-  vq[wave][lane] = vpack;
+  const int i = lane >> 3, n = lane & 7;
+  const int grp = (16 * n) / L.G;
+  const bool writes_meta = (16 * n) % L.G == 0;
+  const float ak = L.clip_k[hk * L.NG + grp], av = L.clip_v[hk * L.NG + grp];
+  int4 pk[4], pv[4];
+  {
+    const int4 *ppk = reinterpret_cast<const int4 *>(L.perm_k + hk * kD + 16 * n);
+    const int4 *ppv = reinterpret_cast<const int4 *>(L.perm_v + hk * kD + 16 * n);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      pk[q] = ppk[q];
+      pv[q] = ppv[q];
+    }
+  }
+  const long long t = t0 + i;
+  const bool valid = t < nq;
+  const float vtop = (float)(L.v_levels - 1);
   __syncthreads();
+
+  GroupParams gk, gv;
+  const unsigned kw = encode16(rows[wave][0][i], pk, ak, L.G, 3.0f, gk);
+  const unsigned vw = encode16(rows[wave][1][i], pv, av, L.G, vtop, gv);
+  if (valid) {
+    reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw;
+    if (writes_meta) {
+      reinterpret_cast<float2 *>(L.k_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(gk.scale, gk.lo);
+      reinterpret_cast<float2 *>(L.v_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(gv.scale, gv.lo);
+    }
+  }
+  vq[wave][i][n] = valid ? vw : 0u;  // rows past the packed region leave zeros in the block
+  __syncthreads();
+
+  // V units of sub-block kb = wave.  Lane (j = lane % 16, nh = lane / 16) builds fields 2nh and
+  // 2nh+1 of unit j from the codes of its eight tokens.
   const int j = lane & 15, nh = lane >> 4;
-  const unsigned sh = 16 * (j & 1);
-  const unsigned ca = (vq[wave][8 * (2 * nh) + (j >> 1)] >> sh) & 0xffffu;
-  const unsigned cb = (vq[wave][8 * (2 * nh + 1) + (j >> 1)] >> sh) & 0xffffu;
   uint8_t *dst = L.v_codes + (head * L.n_vblocks + blk) * L.v_block_bytes;
   if (L.v_levels == 4) {
-    const unsigned w = spread_tokens(ca) | (spread_tokens(cb) << 8);
+    unsigned w = 0;
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      const unsigned ca = (vq[wave][ii][2 * nh] >> (2 * j)) & 3u;
+      const unsigned cb = (vq[wave][ii][2 * nh + 1] >> (2 * j)) & 3u;
+      w |= (ca << (16 * (ii & 1) + 2 * (ii >> 1))) | (cb << (8 + 16 * (ii & 1) + 2 * (ii >> 1)));
+    }
     reinterpret_cast<unsigned *>(dst + 256 * wave)[4 * j + nh] = w;
   } else {
-    pieces[wave][lane] = trit_field(ca) | (trit_field(cb) << 13);  // 26 bits
+    unsigned fa = 0, fb = 0, pw = 1;
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      fa += ((vq[wave][ii][2 * nh] >> (2 * j)) & 3u) * pw;
+      fb += ((vq[wave][ii][2 * nh + 1] >> (2 * j)) & 3u) * pw;
+      pw *= 3;
+    }
+    pieces[wave][lane] = fa | (fb << 13);  // 26 bits
     __syncthreads();
     if (lane < 16) {
       const unsigned long long a0 = pieces[wave][lane], a1 = pieces[wave][16 + lane];
