@@ -86,8 +86,9 @@ typedef struct {
  *   v_meta    f32 [B][Hk][Tcap][D/G][2]
  *   k_win     f16 [B][Hk][W][D]          token number a (0-based) sits in slot a % W
  *   v_win     f16 [B][Hk][W][D]
- *   workspace split partials and workgroup counters of skvq_decode_attention; skvq_create
- *             clears the counters, the library keeps them zero between calls; do not write it
+ *   workspace f32 [B][Hq][SKVQ_MAX_SPLITS+1][132]  split partials of skvq_decode_attention
+ *             (running max, sum of weights, two pads, 128 weighted value sums); scratch: any
+ *             content is fine before a call and nothing in it survives one
  * All seven must be 16-byte aligned. */
 typedef struct {
   void *k_codes, *v_codes, *k_meta, *v_meta, *k_win, *v_win, *workspace;

@@ -124,7 +124,7 @@ class SkvqCache:
         self.buffers = {}
         for name, nbytes in zip(BUFFER_NAMES, self.sizes):
             t = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-            if fill is not None and name != "workspace":
+            if fill is not None:
                 t.fill_(fill)
             self.buffers[name] = t
         self._bufs = skvq_buffers(*[self.buffers[n].data_ptr() for n in BUFFER_NAMES])

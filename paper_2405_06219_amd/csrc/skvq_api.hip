@@ -19,7 +19,7 @@ struct skvq_cache {
   long long n_tokens = 0;
   int forced_splits = 0;
   int n_cus = 256;
-  void *dev_consts = nullptr;  // one allocation: perm_k, perm_v, clip_k, clip_v, trit table
+  void *dev_consts = nullptr;  // one allocation: perm_k, perm_v, clip_k, clip_v
   std::string last_error;
 };
 
@@ -73,8 +73,7 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
   bytes[4] = heads * (size_t)c->window * kD * sizeof(__half);
   bytes[5] = bytes[4];
   // one partial per (sequence, query head, split); the ring is one more split
-  // ... followed by one 4-byte workgroup counter per (sequence, kv head)
-  bytes[6] = counters_offset(c->batch, c->n_q_heads) + ((heads * sizeof(unsigned) + 15) & ~(size_t)15);
+  bytes[6] = (size_t)c->batch * c->n_q_heads * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
 }
 
 int fail_hip(skvq_cache *c, hipError_t e, const char *what) {
@@ -165,20 +164,17 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.k_win = (__half *)bufs->k_win;
   L.v_win = (__half *)bufs->v_win;
   L.workspace = (float *)bufs->workspace;
-  L.counters = (unsigned *)((uint8_t *)bufs->workspace + counters_offset(L.B, L.Hq));
 
-  // constants: [perm_k | perm_v | clip_k | clip_v | trit table], one allocation
+  // constants: [perm_k | perm_v | clip_k | clip_v], one allocation
   const size_t n_perm = (size_t)L.Hk * kD, n_clip = (size_t)L.Hk * L.NG;
   const size_t off_pv = n_perm * 4, off_ck = off_pv + n_perm * 4;
   const size_t off_cv = off_ck + ((n_clip * 4 + 15) & ~(size_t)15);
-  const size_t off_lut = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
-  const size_t total = off_lut + 8192 * 4;
+  const size_t total = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
   std::vector<uint8_t> host(total, 0);
   std::memcpy(host.data(), cfg->perm_k, n_perm * 4);
   std::memcpy(host.data() + off_pv, cfg->perm_v, n_perm * 4);
   std::memcpy(host.data() + off_ck, cfg->clip_k, n_clip * 4);
   std::memcpy(host.data() + off_cv, cfg->clip_v, n_clip * 4);
-  build_trit_lut((uint32_t *)(host.data() + off_lut));
 
   hipError_t e = hipMalloc(&c->dev_consts, total);
   if (e != hipSuccess) {
@@ -191,19 +187,11 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
     delete c;
     return SKVQ_ERR_HIP;
   }
-  e = hipMemset(L.counters, 0, (size_t)L.B * L.Hk * sizeof(unsigned));
-  if (e == hipSuccess) e = hipDeviceSynchronize();
-  if (e != hipSuccess) {
-    (void)hipFree(c->dev_consts);
-    delete c;
-    return SKVQ_ERR_HIP;
-  }
   uint8_t *d = (uint8_t *)c->dev_consts;
   L.perm_k = (const int *)d;
   L.perm_v = (const int *)(d + off_pv);
   L.clip_k = (const float *)(d + off_ck);
   L.clip_v = (const float *)(d + off_cv);
-  L.trit_lut = (const uint32_t *)(d + off_lut);
 
   int dev = 0;
   hipDeviceProp_t prop;

@@ -14,24 +14,6 @@
 
 namespace skvq {
 
-// Entry f (a base-3 number of eight digits, digit i = code of token i) -> the eight codes laid
-// out for the matrix-core kernel: token 2m in the low half and 2m+1 in the high half of the
-// word, at bit 4, 6, 8 for m = 0, 1, 2 and at bit 0 for m = 3.
-void build_trit_lut(uint32_t *t) {
-  static const int pos[4] = {4, 6, 8, 0};
-  for (unsigned f = 0; f < 8192; ++f) {
-    uint32_t e = 0;
-    if (f < 6561) {
-      unsigned r = f;
-      for (int i = 0; i < 8; ++i) {
-        e |= (r % 3) << (16 * (i & 1) + pos[i >> 1]);
-        r /= 3;
-      }
-    }
-    t[f] = e;
-  }
-}
-
 namespace {
 
 constexpr int kMaxR = 8;

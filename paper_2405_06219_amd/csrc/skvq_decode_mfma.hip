@@ -3,8 +3,8 @@
 // (Merging the partials inside this launch was tried and dropped: the device-scope fences it
 // needs write back and invalidate a whole L2 each, 25 us over 256 workgroups.)
 //
-// One workgroup of 12 wavefronts per chunk (one per compute unit when the cache is long
-// enough).  Per wavefront, per tile of 64 packed tokens:
+// One workgroup of 8 wavefronts per chunk (one per compute unit when the cache is long
+// enough; 256 registers per wavefront).  Per wavefront, per tile of 64 packed tokens:
 //   QK   S^T[head][token] by 32 v_mfma_f32_4x4x4_16b_f16 (16 independent 4x4 blocks, lane =
 //        token): the B operand is the lane's own 32-byte key row, its 2-bit codes turned into
 //        fp16 SUBNORMALS by one AND each (a code c sitting at mantissa bit s is the fp16 value
@@ -14,8 +14,8 @@
 //   softmax  lazily re-referenced online softmax in the exp2 domain: the running reference m
 //        only moves when a score exceeds it by more than 2^6 (wave-uniform branch).
 //   PV   O^T[channel][head] by 16 v_mfma_f32_16x16x32_f16: the A operand is the V block unit
-//        that the lane loaded (8 tokens x 8 channels, token-minor; 3-level units go through a
-//        13-bit -> 8-code table in LDS), the B operand holds p*scale split into a high and a
+//        that the lane loaded (8 tokens x 8 channels, token-minor; a 3-level field is the index
+//        of a 16-byte table entry in LDS that IS the operand), the B operand holds p*scale split into a high and a
 //        low fp16 part (two columns per head) so that the weights keep ~22 bits.
 // The zero-points never enter the matrix products: sum_p q_p (s c_p + z) = s sum q c + z sum q
 // and sum_t w_t (s_t c + z_t) = sum (w_t s_t) c + sum w_t z_t.
@@ -37,8 +37,14 @@ __device__ unsigned long long skvq_timing[16 * 4096];
   if (threadIdx.x == 0)                                                                     \
   skvq_timing[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + (slot)] = \
       __builtin_amdgcn_s_memrealtime()
+__device__ unsigned long long skvq_timing_w[16 * 4096];
+#define SKVQ_WSTAMP(slot)                                                                   \
+  if ((threadIdx.x & 63) == 0)                                                              \
+  skvq_timing_w[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + 2 * (threadIdx.x >> 6) + (slot)] = \
+      __builtin_amdgcn_s_memrealtime()
 #else
 #define SKVQ_STAMP(slot)
+#define SKVQ_WSTAMP(slot)
 #endif
 namespace {
 
@@ -67,6 +73,29 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Cross-lane moves inside a row of 16 lanes (data-parallel primitives: no LDS round trip).
+// A source lane outside the row reads as 0.
+template <int CTRL>
+__device__ __forceinline__ float row_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+constexpr int kQuadSwap1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141;  // lane i reads lane 7 - i of its half row
+constexpr int kRowMirror = 0x140;      // lane i reads lane 15 - i of its row
+constexpr int kRowShl = 0x100;         // + n: lane i reads lane i + n of its row
+// Sum over the wavefront, returned in every lane (as a wave-uniform value).
+__device__ __forceinline__ float wave_sum_fast(float v) {
+  v += row_move<kQuadSwap1>(v);
+  v += row_move<kQuadSwap2>(v);
+  v += row_move<kRowHalfMirror>(v);
+  v += row_move<kRowMirror>(v);  // every lane: the sum of its row
+  return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0)) +
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16))) +
+         (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32)) +
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48)));
+}
+
 __device__ __forceinline__ half4_t h4(unsigned a, unsigned b) { return __builtin_bit_cast(half4_t, uint2_t{a, b}); }
 
 // Key dword (16 codes, position e at bit 2e) -> four B operands of the 4x4x4 product.
@@ -91,11 +120,8 @@ __device__ __forceinline__ void k_slot_of(int p, int &step, int &kslot, int &shi
 }
 
 // Eight tokens of one channel -> A operand of the 16x16x32 product: register m holds tokens
-// 2m (low half) and 2m+1 (high half) at mantissa bit {4, 6, 8, 8}[m].
-// From a table entry (pairs 0,1,2 at bits 4,6,8; pair 3 at bit 0):
-__device__ __forceinline__ half8_t unpack_v_entry(unsigned e) {
-  return __builtin_bit_cast(half8_t, uint4_t{e & kM4, e & kM6, e & kM8, (e << 8) & kM8});
-}
+// 2m (low half) and 2m+1 (high half); 2-bit units: at mantissa bit {4, 6, 8, 8}[m] (masked out
+// of the unit's field), 3-level units: all at bit 8 (read from the table).
 // From a 2-bit unit field (pair m at bit 2m of each half; `f` has the field in bits 0..7):
 __device__ __forceinline__ half8_t unpack_v_field(unsigned f) {
   const unsigned a = f << 4, b = f << 2;
@@ -111,10 +137,11 @@ constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumul
 
 template <int R, bool TERNARY>
 struct Smem {
-  union {
-    unsigned lut[TERNARY ? 8192 : 1];      // main loop: 13-bit field -> eight codes (6561 used)
-    float stage[kNW][2 * R][kCombStride];  // epilogue: O^T per wave and column, reordered positions
-  };
+  // 13-bit field -> the A operand of its eight tokens (104976 bytes, built by the workgroup
+  // from the two 81-entry tables: four base-3 digits -> the operand halves of tokens 0..3 / 4..7)
+  uint4_t lut[TERNARY ? 6561 : 1];
+  uint2_t lut4[TERNARY ? 2 : 1][81];
+  float stage[kNW][R][kCombStride];  // epilogue: O^T per wave and head, reordered positions
   float qraw[4][kD];                   // the query heads as loaded (rows >= R are zero)
   _Float16 qa[32][4][4];               // A operands of the score product: [step][head][k slot]
   float qsum[4];                       // sm_scale*log2(e) * sum of the query, per head
@@ -188,8 +215,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int vbb = TERNARY ? kTernaryBlockBytes : kTwoBitBlockBytes;
   const unsigned unit_off = TERNARY ? ((13 * lane) & ~3) : 16 * lane;
   const int unit_sh = TERNARY ? ((13 * lane) & 3) : 0;
-  // token slot i = lane%8 sits in register m = i/2 at bit {4,6,8,8}[m]: undo 2^(bit-4)
-  const float kslot_scale = ((lane >> 1) & 3) == 0 ? 1.f : ((lane >> 1) & 3) == 1 ? 0.25f : 0.0625f;
+  // 2-bit units: token slot i = lane%8 sits in register m = i/2 at bit {4,6,8,8}[m]: undo
+  // 2^(bit-4).  3-level units: every slot at bit 8.
+  const float kslot_scale =
+      TERNARY ? 1.f : ((lane >> 1) & 3) == 0 ? 1.f : ((lane >> 1) & 3) == 1 ? 0.25f : 0.0625f;
 
   // Loads are issued unconditionally (a tile index past the end is redirected to the last
   // tile, whose lines are in cache by then, and the data is ignored): the compiler can then
@@ -242,17 +271,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // ---- prologue: one memory round trip.  The small loads (query, permutations, table) are
   //      issued BEFORE the tile loads: loads return in order, so the staging below only has to
   //      wait for them and not for the two tiles of packed data behind them. ----
+  SKVQ_STAMP(4);
   __half2 q2 = __floats2half2_rn(0.f, 0.f);
   if (tid < 64 * R) q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * R + (tid >> 6)) * kD)[lane];
   const int pk = L.perm_k[hk * kD + (tid & 127)];
   const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
-  uint4_t lut_piece[4];
-  if (TERNARY) {
-    const uint4_t *src = reinterpret_cast<const uint4_t *>(L.trit_lut);
-#pragma unroll
-    for (int x = 0; x < 4; ++x)  // 6561 entries = 1641 16-byte pieces; fields of valid data stay below
-      if (tid + kThreads * x < 1641) lut_piece[x] = src[tid + kThreads * x];
-  }
+  RingData ring = load_ring(ring_first < n_slices ? ring_first : n_slices - 1);
   asm volatile("" ::: "memory");
   // three tile buffers used in turn (no register copies): while one tile is computed the
   // next two are in flight
@@ -260,18 +284,29 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   TileData buf_a, buf_b, buf_c;
   buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
   buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
-  RingData ring = load_ring(ring_first < n_slices ? ring_first : n_slices - 1);
+  if (TERNARY) {
+    // While the loads are in flight the workgroup builds the table: entry f (a base-3 number of
+    // eight digits, digit i = code of token i) is the operand itself, register m = codes of
+    // tokens 2m (low half) and 2m+1 (high half) as fp16 subnormals c * 2^(8-24).
+    if (tid < 162) {
+      const int half = tid >= 81, x = half ? tid - 81 : tid;
+      const unsigned d0 = x % 3, d1 = (x / 3) % 3, d2 = (x / 9) % 3, d3 = x / 27;
+      sm.lut4[half][x] = uint2_t{(d0 << 8) | (d1 << 24), (d2 << 8) | (d3 << 24)};
+    }
+    __syncthreads();
+    for (int e = tid; e < 6561; e += kThreads) {
+      const unsigned hi = e / 81u, lo = e - 81u * hi;
+      const uint2_t a = sm.lut4[0][lo], b2 = sm.lut4[1][hi];
+      sm.lut[e] = uint4_t{a.x, a.y, b2.x, b2.y};
+    }
+  }
   {
     if (tid < 256) {
       sm.qraw[tid >> 6][2 * lane] = __low2float(q2);
       sm.qraw[tid >> 6][2 * lane + 1] = __high2float(q2);
     }
-    if (TERNARY) {
-      uint4_t *dst = reinterpret_cast<uint4_t *>(sm.lut);
-#pragma unroll
-      for (int x = 0; x < 4; ++x)
-        if (tid + kThreads * x < 1641) dst[tid + kThreads * x] = lut_piece[x];
-    }
+    SKVQ_STAMP(5);
+    SKVQ_STAMP(6);
     __syncthreads();
     SKVQ_STAMP(10);
     if (tid < 256) {
@@ -360,6 +395,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     sm.rm[wave][lane] = -INFINITY;
     sm.rl[wave][lane] = 0.f;
   }
+  // Every ring load has to have landed before the tile loop, also the ones whose data nobody
+  // reads (a wave without ring slices, the look-ahead of the last slice): a load still pending
+  // at the loop's entry would make every wait inside the loop a wait for all loads.
+  asm volatile("" ::"v"(ring.k.x), "v"(ring.k.y), "v"(ring.k.z), "v"(ring.k.w), "v"(ring.v[0]), "v"(ring.v[1]),
+               "v"(ring.v[2]), "v"(ring.v[3]));
 
   float mref[R], lsum[R], zacc[R];
 #pragma unroll
@@ -371,6 +411,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   bool first = true;
 
   SKVQ_STAMP(1);
+  SKVQ_WSTAMP(0);
   auto compute_tile = [&](const TileData &cur, const int tile) {
     const bool valid = tile * 64 + lane <= last_token;
 
@@ -465,22 +506,23 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         const unsigned u1 = __builtin_amdgcn_alignbyte(raw.z, raw.y, unit_sh);
         const unsigned u2 = __builtin_amdgcn_alignbyte(raw.w, raw.z, unit_sh);
         const unsigned u3 = raw.w >> (8 * unit_sh);
-        // byte offsets into the table (field * 4), two operations per field
-        unsigned f[8], fld[8];
-        f[0] = (u0 << 2) & 0x7ffcu;
-        f[1] = (u0 >> 11) & 0x7ffcu;
-        f[2] = __builtin_amdgcn_alignbit(u1, u0, 24) & 0x7ffcu;
-        f[3] = (u1 >> 5) & 0x7ffcu;
-        f[4] = __builtin_amdgcn_alignbit(u2, u1, 18) & 0x7ffcu;
-        f[5] = (u2 << 1) & 0x7ffcu;
-        f[6] = (u2 >> 12) & 0x7ffcu;
-        f[7] = __builtin_amdgcn_alignbit(u3, u2, 25) & 0x7ffcu;
+        // byte offsets into the table (field * 16), two operations per field
+        unsigned f[8];
+        f[0] = (u0 << 4) & 0x1fff0u;
+        f[1] = (u0 >> 9) & 0x1fff0u;
+        f[2] = __builtin_amdgcn_alignbit(u1, u0, 22) & 0x1fff0u;
+        f[3] = (u1 >> 3) & 0x1fff0u;
+        f[4] = __builtin_amdgcn_alignbit(u2, u1, 16) & 0x1fff0u;
+        f[5] = (u2 << 3) & 0x1fff0u;
+        f[6] = (u2 >> 10) & 0x1fff0u;
+        f[7] = __builtin_amdgcn_alignbit(u3, u2, 23) & 0x1fff0u;
+        uint4_t aop[8];
 #pragma unroll
         for (int n = 0; n < 8; ++n)
-          fld[n] = *reinterpret_cast<const unsigned *>(reinterpret_cast<const char *>(sm.lut) + f[n]);
+          aop[n] = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(sm.lut) + f[n]);
 #pragma unroll
         for (int n = 0; n < 8; ++n)
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_entry(fld[n]), pop, acc[n], 0, 0, 0);
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop, acc[n], 0, 0, 0);
       } else {
         const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -492,46 +534,58 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     }
     __builtin_amdgcn_wave_barrier();
   };
-  while (tile_a < tile_end) {
-    buf_c = load_tile(tile_c < tile_end ? tile_c : tile_end - 1);
+  // Whole triples first.  The loop has no early exit: the wait counters the compiler places
+  // are exact only if every path into the loop's top has the same loads in flight, in the
+  // same order (buffer a's, then buffer b's).
+  while (tile_c < tile_end) {
+    buf_c = load_tile(tile_c);
     compute_tile(buf_a, tile_a);
 #ifdef SKVQ_TIMING
     if (tile_a == tile_begin + wave) { SKVQ_STAMP(12); }
 #endif
-    if (tile_b >= tile_end) break;
     tile_a += 3 * kNW;
     buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
     compute_tile(buf_b, tile_b);
-    if (tile_c >= tile_end) break;
     tile_b += 3 * kNW;
     buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
     compute_tile(buf_c, tile_c);
     tile_c += 3 * kNW;
   }
+  // At most two tiles are left, already loaded into a and b.
+#pragma unroll 1
+  for (int k = 0; k < 2 && tile_a < tile_end; ++k) {
+    compute_tile(buf_a, tile_a);
+    buf_a = buf_b;
+    tile_a = tile_b;
+    tile_b = tile_end;
+  }
 
   SKVQ_STAMP(2);
+  SKVQ_WSTAMP(1);
   // ---- epilogue: fold lanes, columns, waves and ring slices; write this chunk's partial ----
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const float ls = wave_sum(lsum[r]), zs = wave_sum(zacc[r]);
+    const float ls = wave_sum_fast(lsum[r]), zs = wave_sum_fast(zacc[r]);
     if (lane == 0) {
       sm.wm[wave][r] = first ? -INFINITY : mref[r];
       sm.wl[wave][r] = ls;
       sm.wz[wave][r] = zs;
     }
   }
-  __syncthreads();  // also: no wave reads the table any more, `stage` may overwrite it
-  SKVQ_STAMP(8);
   if (!first) {
     const int col = lane & 15, kb = lane >> 4;
-    const float unscale = 1048576.0f / beta;  // codes carried 2^(4-24)
-    if (col < 2 * R) {
+    // codes carried 2^(4-24) (2-bit units) or 2^(8-24) (3-level units)
+    const float unscale = (TERNARY ? 65536.0f : 1048576.0f) / beta;
 #pragma unroll
-      for (int n = 0; n < 8; ++n)
+    for (int n = 0; n < 8; ++n)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) sm.stage[wave][col][16 * n + 4 * kb + rr] = acc[n][rr] * unscale;
-    }
+      for (int rr = 0; rr < 4; ++rr) {
+        const float lo_part = row_move<kRowShl + R>(acc[n][rr]);  // column R + r: the low halves' sum
+        if (col < R) sm.stage[wave][col][16 * n + 4 * kb + rr] = (acc[n][rr] + lo_part) * unscale;
+      }
   }
+  __syncthreads();
+  SKVQ_STAMP(8);
   if (tid < 16 * R) {
     // thread (head r, wave w): the chunk's reference m* = max over waves, the wave's factors
     // 2^(m_w - m*), and the sums that need no channel; reductions over the 16 lanes of a head
@@ -558,7 +612,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #pragma unroll 4
     for (int w = 0; w < kNW; ++w) {
       const float e = sm.ew[w][r], g = sm.er[w][r];
-      if (e > 0.f) num = fmaf(e, sm.stage[w][r][p] + sm.stage[w][R + r][p], num);
+      if (e > 0.f) num = fmaf(e, sm.stage[w][r][p], num);
       if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
     float *part = L.workspace + (((long long)b * L.Hq + hk * R + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
@@ -576,6 +630,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #ifdef SKVQ_TIMING
 extern "C" int skvq_debug_read_timing(unsigned long long *host, int n) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(skvq_timing), sizeof(unsigned long long) * n);
+}
+extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(skvq_timing_w), sizeof(unsigned long long) * n);
 }
 #endif
 

@@ -14,10 +14,6 @@ constexpr int kVBlock = 32;    // tokens per V block
 constexpr int kTernaryBlockBytes = 832;
 constexpr int kTwoBitBlockBytes = 1024;
 constexpr int kPartialStride = kD + 4;  // floats per split partial: m, l, pad, pad, acc[D]
-// byte offset of the per-(b, hk) workgroup counters inside the workspace
-inline size_t counters_offset(int B, int Hq) {
-  return (size_t)B * Hq * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
-}
 
 // Everything a kernel needs to find its data; passed by value.
 struct Layout {
@@ -33,10 +29,8 @@ struct Layout {
   float *k_meta, *v_meta;
   __half *k_win, *v_win;
   float *workspace;
-  unsigned *counters;            // in the workspace, after the partials: one per (b, hk), zero between calls
   const int *perm_k, *perm_v;    // device copies [Hk][D]
   const float *clip_k, *clip_v;  // device copies [Hk][NG]
-  const uint32_t *trit_lut;      // device, 8192 entries (see skvq_decode.hip)
 };
 
 // quantize kernels (skvq_quantize.hip)
@@ -57,8 +51,5 @@ bool decode_mfma_supported(const Layout &L);
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
                               hipStream_t s);
 constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel
-
-// Fills the 8192-entry table that expands a 13-bit base-3 field into eight 2-bit codes.
-void build_trit_lut(uint32_t *host_table);
 
 }  // namespace skvq

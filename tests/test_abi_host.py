@@ -63,7 +63,7 @@ def test_sizes_agree_with_the_oracle(B, oracle):
         clip = np.ones((hk, D // g), np.float32)
         oc = oracle.OracleCache(b, hq, hk, g, vb, w, tcap, perm, perm, clip, clip)
         assert sizes[:6] == oc.sizes
-        assert sizes[6] == b * hq * (B.SKVQ_MAX_SPLITS + 1) * (D + 4) * 4 + (b * hk * 4 + 15) // 16 * 16
+        assert sizes[6] == b * hq * (B.SKVQ_MAX_SPLITS + 1) * (D + 4) * 4
 
 
 def test_validation_rejects_bad_configs(B):
