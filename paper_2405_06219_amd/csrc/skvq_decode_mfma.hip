@@ -37,10 +37,10 @@ __device__ unsigned long long skvq_timing[16 * 4096];
   if (threadIdx.x == 0)                                                                     \
   skvq_timing[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + (slot)] = \
       __builtin_amdgcn_s_memrealtime()
-__device__ unsigned long long skvq_timing_w[16 * 4096];
+__device__ unsigned long long skvq_timing_w[32 * 4096];
 #define SKVQ_WSTAMP(slot)                                                                   \
   if ((threadIdx.x & 63) == 0)                                                              \
-  skvq_timing_w[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + 2 * (threadIdx.x >> 6) + (slot)] = \
+  skvq_timing_w[32 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + 2 * (threadIdx.x >> 6) + (slot)] = \
       __builtin_amdgcn_s_memrealtime()
 #else
 #define SKVQ_STAMP(slot)
