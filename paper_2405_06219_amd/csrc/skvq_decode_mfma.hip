@@ -276,14 +276,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   if (tid < 64 * R) q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * R + (tid >> 6)) * kD)[lane];
   const int pk = L.perm_k[hk * kD + (tid & 127)];
   const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
-  RingData ring = load_ring(ring_first < n_slices ? ring_first : n_slices - 1);
+  RingData ring = {};
+  if (ring_owner) ring = load_ring(ring_first);  // landed before the tile loop either way (see below)
   asm volatile("" ::: "memory");
   // three tile buffers used in turn (no register copies): while one tile is computed the
   // next two are in flight
   int tile_a = tile_begin + wave, tile_b = tile_a + kNW, tile_c = tile_b + kNW;
   TileData buf_a, buf_b, buf_c;
   buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
-  buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
   if (TERNARY) {
     // While the loads are in flight the workgroup builds the table: entry f (a base-3 number of
     // eight digits, digit i = code of token i) is the operand itself, register m = codes of
@@ -308,6 +308,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     SKVQ_STAMP(5);
     SKVQ_STAMP(6);
     __syncthreads();
+    asm volatile("" ::: "memory");
+    buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
     SKVQ_STAMP(10);
     if (tid < 256) {
 #pragma unroll
