@@ -45,7 +45,8 @@ def algorithmic_bytes_decode(w, n_tokens: int) -> int:
 
 
 def build_layers(w, n_layers: int, headroom: int, device):
-    """Per layer: a cache prefilled with w.context seeded synthetic tokens."""
+    """Per layer: a cache prefilled with w.context seeded synthetic tokens.  Returns the caches,
+    the K/V channel scales on the device, and each prefill call's duration (HIP events, us)."""
     import torch
     from paper_2405_06219_amd import binding as B
     from paper_2405_06219_amd import synth
@@ -54,25 +55,22 @@ def build_layers(w, n_layers: int, headroom: int, device):
     sk_d = torch.from_numpy(sk).to(device)[None, :, None, :]
     sv_d = torch.from_numpy(sv).to(device)[None, :, None, :]
     ck, cv = synth.make_clip(w)
-    gen = torch.Generator(device=device)
     caches = []
-    shape = (w.batch, w.n_kv_heads, w.context, D)
+    prefill_us = []
     for layer in range(n_layers):
-        gen.manual_seed(w.seed * 1000 + layer)
-        k = (torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * sk_d).to(torch.float16)
-        v = (torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * sv_d).to(torch.float16)
-        # reorder index: channels sorted by their range over the sequence (offline calibration stand-in)
-        rk = (k.amax(dim=(0, 2)) - k.amin(dim=(0, 2))).float().cpu().numpy()
-        rv = (v.amax(dim=(0, 2)) - v.amin(dim=(0, 2))).float().cpu().numpy()
-        pk = np.argsort(rk, axis=-1, kind="stable").astype(np.int32)
-        pv = np.argsort(rv, axis=-1, kind="stable").astype(np.int32)
+        # seeded synthetic K/V and the reorder index from their channel ranges (offline calibration stand-in)
+        k, v, pk, pv = synth.make_kv_device(w, device, stream=layer)
         c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                         w.context - w.window + headroom, pk, pv, ck, cv, device=device)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         c.skvq_prefill_quantize(k, v)
+        e1.record()
         torch.cuda.synchronize()
+        prefill_us.append(e0.elapsed_time(e1) * 1e3)
         del k, v
         caches.append(c)
-    return caches, (sk_d, sv_d)
+    return caches, (sk_d, sv_d), prefill_us
 
 
 def cpu_baseline(w, seconds_budget: float = 25.0):
@@ -135,7 +133,8 @@ def main() -> int:
     n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers
     headroom = n_warm + 2 * n_steps + 9
 
-    caches, (sk_d, sv_d) = build_layers(w, n_layers, headroom, device)
+    caches, (sk_d, sv_d), prefill_us = build_layers(w, n_layers, headroom, device)
+    prefill_med_us = float(np.median(prefill_us))
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
     total = n_warm + 2 * n_steps + 1
@@ -213,6 +212,11 @@ def main() -> int:
         "decode_call_us": dec_avg_us,
         "decode_call_us_min": float(dec_us.min()),
         "append_call_us": append_us,
+        "prefill_call_us": prefill_med_us,
+        "prefill_tokens_per_s": w.batch * w.context / (prefill_med_us * 1e-6),
+        "prefill_hbm_gbps": (w.batch * w.n_kv_heads * (w.context * 2 * D * 2 + max(w.context - w.window, 0)
+                                                     * (74 if w.v_bits == 1.5 else 80))
+                             / (prefill_med_us * 1e-6) / 1e9),
         "effective_hbm_gbps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -23,7 +23,7 @@ def main() -> int:
     n_layers = int(sys.argv[2]) if len(sys.argv) > 2 else 4
     dev = torch.device("cuda:0")
     w = synth.WORKLOADS[name]
-    caches, _ = bench.build_layers(w, n_layers, 8, dev)
+    caches = bench.build_layers(w, n_layers, 8, dev)[0]
     q = torch.randn((n_layers, w.batch, w.n_q_heads, 128), device=dev).to(torch.float16)
     out = torch.empty((n_layers, w.batch, w.n_q_heads, 128), dtype=torch.float32, device=dev)
     for _ in range(3):

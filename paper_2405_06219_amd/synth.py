@@ -91,6 +91,37 @@ def make_kv(w: Workload, n_tokens: int | None = None, stream: int = 0) -> tuple[
     return res[0], res[1]
 
 
+def make_kv_device(w: Workload, device, stream: int = 0):
+    """The same distributions as make_kv, drawn on the GPU with a seeded torch.Generator (the
+    host generator is too slow for the 1M-token and batch-16 workloads and for 32 layers).
+    Returns K, V as torch float16 [B][Hk][T][D] on `device`, and the two reorder indices
+    (int32 [Hk][D], channels sorted by their range over batch and sequence, ties by channel
+    index) computed from them."""
+    import torch
+
+    sk, sv = channel_scales(w)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed * 1000 + stream)
+    shape = (w.batch, w.n_kv_heads, w.context, w.head_dim)
+    out, perms = [], []
+    for s in (sk, sv):
+        s_d = torch.from_numpy(s).to(device)[None, :, None, :]
+        x = torch.empty(shape, dtype=torch.float16, device=device)
+        for b in range(w.batch):  # one sequence at a time bounds the fp32 temporaries
+            z = torch.randn(shape[1:], generator=gen, device=device, dtype=torch.float32)
+            x[b] = (z * s_d[0]).to(torch.float16)
+            del z
+        if w.perm_stat == "range":
+            stat = x.amax(dim=(0, 2)).float() - x.amin(dim=(0, 2)).float()
+        elif w.perm_stat == "absmax":
+            stat = x.abs().amax(dim=(0, 2)).float()
+        else:
+            raise ValueError(w.perm_stat)
+        perms.append(np.argsort(stat.cpu().numpy(), axis=-1, kind="stable").astype(np.int32))
+        out.append(x)
+    return out[0], out[1], perms[0], perms[1]
+
+
 def make_query(w: Workload, stream: int = 0) -> np.ndarray:
     """One decode-step query, float16 [B][Hq][D]."""
     r = _rng(w.seed, 500 + stream)

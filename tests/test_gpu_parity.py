@@ -188,3 +188,69 @@ def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
     err = np.abs(out - ref).max()
     P.log(f"full size c3: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
     assert err <= P.TOL
+
+
+@pytest.mark.parametrize("name,n_heads", [("c5_batch16_32k", 4), ("c4_llama7b_1m", 2)])
+def test_full_size_sampled_heads(P, name, n_heads):
+    """The batch-16 and the 1M-token workloads at full size, library-chosen split count: the
+    whole layer is prefilled, appended to and attended on the GPU; for seeded sampled
+    (sequence, kv head) pairs the oracle builds that head's cache from the same inputs and
+    must agree bit for bit on every packed byte, (scale, zero) and ring entry of the head and
+    within 2e-3 on the outputs of its query heads."""
+    from oracle import skvq_oracle as O
+    from paper_2405_06219_amd import binding as B
+
+    w = synth.WORKLOADS[name]
+    dev = torch.device("cuda:0")
+    P.log(f"{name}: generating on the device")
+    k, v, pk, pv = synth.make_kv_device(w, dev)
+    ck, cv = synth.make_clip(w)
+    n_app = 3
+    tcap = w.context - w.window + n_app + 1
+    gpu = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window, tcap, pk, pv, ck, cv,
+                      fill=0xAB, device=dev)
+    gpu.skvq_prefill_quantize(k, v)
+    news = [synth.make_new_token(w, s) for s in range(n_app)]
+    for kn, vn in news:
+        gpu.skvq_quantize_append(torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
+    q = synth.make_query(w)
+    out = gpu.skvq_decode_attention(torch.from_numpy(q).to(dev))
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    P.log(f"{name}: gpu done ({gpu.skvq_get_state()})")
+
+    R = w.n_q_heads // w.n_kv_heads
+    ng = D // w.group_size
+    vb = 832 if w.v_bits == 1.5 else 1024
+    views = {"k_codes": gpu.buffers["k_codes"].view(w.batch, w.n_kv_heads, tcap, 32),
+             "v_codes": gpu.buffers["v_codes"].view(w.batch, w.n_kv_heads, (tcap + 31) // 32, vb),
+             "k_meta": gpu.buffers["k_meta"].view(torch.float32).view(w.batch, w.n_kv_heads, tcap, ng, 2),
+             "v_meta": gpu.buffers["v_meta"].view(torch.float32).view(w.batch, w.n_kv_heads, tcap, ng, 2),
+             "k_win": gpu.buffers["k_win"].view(torch.int16).view(w.batch, w.n_kv_heads, w.window, D),
+             "v_win": gpu.buffers["v_win"].view(torch.int16).view(w.batch, w.n_kv_heads, w.window, D)}
+    rng = np.random.default_rng(w.seed)
+    picks = {(int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads))) for _ in range(n_heads)}
+    picks.add((w.batch - 1, w.n_kv_heads - 1))
+    worst = 0.0
+    for b, hk in sorted(picks):
+        ref = O.OracleCache(1, R, 1, w.group_size, w.v_bits, w.window, tcap, pk[hk:hk + 1], pv[hk:hk + 1],
+                            ck[hk:hk + 1], cv[hk:hk + 1], fill=0xAB)
+        assert ref.prefill(k[b:b + 1, hk:hk + 1].cpu().numpy(), v[b:b + 1, hk:hk + 1].cpu().numpy()) == 0
+        for kn, vn in news:
+            assert ref.append(np.ascontiguousarray(kn[b:b + 1, hk:hk + 1]), np.ascontiguousarray(vn[b:b + 1, hk:hk + 1])) == 0
+        for nm, r in zip(["k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win"], ref.arrays()):
+            g = views[nm][b, hk].cpu().numpy()
+            r = r[0, 0]
+            if nm.endswith("meta"):
+                g, r = g.view(np.uint32), r.view(np.uint32)
+            elif nm.endswith("win"):
+                g = g.view(np.uint16)
+            if not np.array_equal(g, r):
+                bad = np.argwhere(g != r)
+                raise AssertionError(f"{name} head ({b},{hk}) {nm}: {len(bad)} mismatches, first at {bad[0].tolist()}")
+        o_ref = ref.decode(np.ascontiguousarray(q[b:b + 1, hk * R:(hk + 1) * R]))
+        err = np.abs(out[b, hk * R:(hk + 1) * R] - o_ref[0]).max()
+        worst = max(worst, float(err))
+        P.log(f"{name} head ({b},{hk}): buffers bit-exact, max abs err {err:.3e} (ref max {np.abs(o_ref).max():.3f})")
+    del k, v
+    assert worst <= P.TOL
