@@ -130,8 +130,10 @@ __device__ __forceinline__ half8_t unpack_v_field(unsigned f) {
 
 constexpr int kNW = 8;              // wavefronts per workgroup (2 per SIMD: 256 registers each)
 constexpr int kThreads = 64 * kNW;
+constexpr int kOldShare = 3, kYoungShare = 2;                        // tiles per deal: waves 0..3 / 4..7
+constexpr int kDealPeriod = (kNW / 2) * (kOldShare + kYoungShare);  // tiles per deal
 constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
-constexpr int kRingSlice = 4;       // ring tokens per slice
+constexpr int kRingSlice = 4;       // ring tokens per slice (the slice code reads four rows of 16 lanes)
 
 constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumulator columns over the banks
 
@@ -281,7 +283,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   asm volatile("" ::: "memory");
   // three tile buffers used in turn (no register copies): while one tile is computed the
   // next two are in flight
-  int tile_a = tile_begin + wave, tile_b = tile_a + kNW, tile_c = tile_b + kNW;
+  // The two wavefronts of a SIMD do not share it evenly: the older one (waves 0..3) is served
+  // first and gets through about three tiles while the younger one gets through two.  The
+  // tiles are dealt in that ratio (per 20 tiles: three to each older, two to each younger
+  // wave) so that both finish together.
+  const int share = wave < kNW / 2 ? kOldShare : kYoungShare;
+  const int deal_base = wave < kNW / 2 ? wave : kOldShare * (kNW / 2) + (wave - kNW / 2);
+  auto tile_of = [&](int n) {  // n-th tile of this wave
+    const int r = n / share;
+    return tile_begin + kDealPeriod * r + deal_base + (kNW / 2) * (n - share * r);
+  };
+  int n_a = 0, n_b = 1, n_c = 2;
+  int tile_a = tile_of(n_a), tile_b = tile_of(n_b), tile_c = tile_of(n_c);
   TileData buf_a, buf_b, buf_c;
   buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
   if (TERNARY) {
@@ -343,12 +356,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     float rm[R], rl[R], ro[R][2];  // reference, sum of weights, outputs
 #pragma unroll
     for (int r = 0; r < R; ++r) rm[r] = -INFINITY, rl[r] = 0.f, ro[r][0] = ro[r][1] = 0.f;
-    for (int slice = ring_first; slice < n_slices; slice += ring_stride) {
-      const RingData ring_next = load_ring(slice + ring_stride < n_slices ? slice + ring_stride : slice);
+    auto ring_slice = [&](const RingData &rd, const int slice) {
       const int tk = lane >> 4, pc = lane & 15;  // token of the slice, 8-channel piece of its row
       const bool valid = slice * kRingSlice + tk < n_win;
-      const half8_t x = __builtin_bit_cast(half8_t, ring.k);
-      float p[R];
+      const half8_t x = __builtin_bit_cast(half8_t, rd.k);
+      float p[R][kRingSlice];  // the four tokens' weights, wave-uniform
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         const float4_t qa = *reinterpret_cast<const float4_t *>(&sm.qraw[r][8 * pc]);
@@ -361,31 +373,49 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         s = fmaf(qb[1], (float)x[5], s);
         s = fmaf(qb[2], (float)x[6], s);
         s = fmaf(qb[3], (float)x[7], s);
-        s += __shfl_xor(s, 1);
-        s += __shfl_xor(s, 2);
-        s += __shfl_xor(s, 4);
-        s += __shfl_xor(s, 8);  // all sixteen lanes of a token now hold its score
+        s += row_move<kQuadSwap1>(s);
+        s += row_move<kQuadSwap2>(s);
+        s += row_move<kRowHalfMirror>(s);
+        s += row_move<kRowMirror>(s);  // all sixteen lanes of a token now hold its score
         s = valid ? c * s : -INFINITY;
-        const float mnew = fmaxf(rm[r], fmaxf(fmaxf(s, __shfl_xor(s, 16)), fmaxf(__shfl_xor(s, 32), __shfl_xor(s, 48))));
-        const float f = exp2f(rm[r] - mnew);  // 0 for the first slice
-        p[r] = exp2f(s - mnew);               // 0 for tokens past the end
-        rl[r] = rl[r] * f + (p[r] + __shfl_xor(p[r], 16)) + (__shfl_xor(p[r], 32) + __shfl_xor(p[r], 48));
+        float sk[kRingSlice];  // the four tokens' scores, read from one lane of each row
+#pragma unroll
+        for (int k = 0; k < kRingSlice; ++k)
+          sk[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 16 * k));
+        const float mnew = fmaxf(rm[r], fmaxf(fmaxf(sk[0], sk[1]), fmaxf(sk[2], sk[3])));
+        const float f = fast_exp2(rm[r] - mnew);  // 0 for the first slice
+#pragma unroll
+        for (int k = 0; k < kRingSlice; ++k) p[r][k] = fast_exp2(sk[k] - mnew);  // 0 for tokens past the end
+        rl[r] = rl[r] * f + (p[r][0] + p[r][1]) + (p[r][2] + p[r][3]);
         ro[r][0] *= f;
         ro[r][1] *= f;
         rm[r] = mnew;
       }
 #pragma unroll
       for (int k = 0; k < kRingSlice; ++k) {
-        const __half2 v2 = __builtin_bit_cast(__half2, ring.v[k]);
+        const __half2 v2 = __builtin_bit_cast(__half2, rd.v[k]);
         const float vx = __low2float(v2), vy = __high2float(v2);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          const float pk = __shfl(p[r], 16 * k);
-          ro[r][0] = fmaf(pk, vx, ro[r][0]);
-          ro[r][1] = fmaf(pk, vy, ro[r][1]);
+          ro[r][0] = fmaf(p[r][k], vx, ro[r][0]);
+          ro[r][1] = fmaf(p[r][k], vy, ro[r][1]);
         }
       }
-      ring = ring_next;
+    };
+    if (ring_first + ring_stride >= n_slices) {
+      // one slice (the usual case): its data was requested before the tile loads
+      ring_slice(ring, ring_first);
+    } else {
+      // several slices: each next one is requested while the current one is computed; those
+      // requests queue behind the tile loads, and all of them have landed when this ends
+      for (int slice = ring_first; slice < n_slices; slice += ring_stride) {
+        RingData ring_next = ring;
+        if (slice + ring_stride < n_slices) ring_next = load_ring(slice + ring_stride);
+        ring_slice(ring, slice);
+        ring = ring_next;
+      }
+      asm volatile("" ::"v"(ring.k.x), "v"(ring.k.y), "v"(ring.k.z), "v"(ring.k.w), "v"(ring.v[0]),
+                   "v"(ring.v[1]), "v"(ring.v[2]), "v"(ring.v[3]));
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -397,11 +427,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     sm.rm[wave][lane] = -INFINITY;
     sm.rl[wave][lane] = 0.f;
   }
-  // Every ring load has to have landed before the tile loop, also the ones whose data nobody
-  // reads (a wave without ring slices, the look-ahead of the last slice): a load still pending
-  // at the loop's entry would make every wait inside the loop a wait for all loads.
-  asm volatile("" ::"v"(ring.k.x), "v"(ring.k.y), "v"(ring.k.z), "v"(ring.k.w), "v"(ring.v[0]), "v"(ring.v[1]),
-               "v"(ring.v[2]), "v"(ring.v[3]));
+  // (No ring load younger than the tile loads may be pending here: it would turn every wait
+  // inside the tile loop into a wait for all loads.)
 
   float mref[R], lsum[R], zacc[R];
 #pragma unroll
@@ -543,15 +570,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     buf_c = load_tile(tile_c);
     compute_tile(buf_a, tile_a);
 #ifdef SKVQ_TIMING
-    if (tile_a == tile_begin + wave) { SKVQ_STAMP(12); }
+    if (n_a == 0) { SKVQ_STAMP(12); }
 #endif
-    tile_a += 3 * kNW;
+    tile_a = tile_of(n_a += 3);
     buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
     compute_tile(buf_b, tile_b);
-    tile_b += 3 * kNW;
+    tile_b = tile_of(n_b += 3);
     buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
     compute_tile(buf_c, tile_c);
-    tile_c += 3 * kNW;
+    tile_c = tile_of(n_c += 3);
   }
   // At most two tiles are left, already loaded into a and b.
 #pragma unroll 1
