@@ -246,13 +246,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     return d;
   };
 
-  // ---- the fp16 ring: slices of 16 tokens, slice j belongs to workgroup j % n_splits, wave
-  //      (j / n_splits) % kRingWaves ----
+  // ---- the fp16 ring: slices of 4 tokens, slice j belongs to workgroup j % n_splits and to
+  //      the wave whose rank is (j / n_splits) % kRingWaves ----
   const int n_win = (int)(T - nq), W = L.W;
   const int n_slices = (n_win + kRingSlice - 1) / kRingSlice;
   const int ring_stride = n_splits * kRingWaves;
-  const int ring_first = sp + n_splits * wave;  // meaningful for wave < kRingWaves
-  const bool ring_owner = wave < kRingWaves && ring_first < n_slices;
+  // the younger waves (which get fewer tiles) are first in line for ring slices
+  const int ring_rank = (wave + kNW / 2) % kNW;
+  const int ring_first = sp + n_splits * ring_rank;
+  const bool ring_owner = ring_first < n_slices;
   const int slot0 = (int)(nq % W);
   const __half *kwin = L.k_win + head * W * kD;
   const __half *vwin = L.v_win + head * W * kD;
