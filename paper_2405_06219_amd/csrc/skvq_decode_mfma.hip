@@ -150,9 +150,8 @@ struct Smem {
   float qinit[4];                      // -1.5 * sum of the query, in the score product's units (2^-16)
   _Float16 pbuf[kNW][2][2 * R][32];    // per wave: [block][column][token slot]
   // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
-  // tiles (w*) and for the ring slices (r*) of the wave; then each wave's factor 2^(m_w - m*)
+  // tiles (w*) and for the ring slices (r*) of the wave
   float wm[kNW][R], wl[kNW][R], wz[kNW][R], rm[kNW][R], rl[kNW][R];
-  float ew[kNW][R], er[kNW][R], mstar[R], den[R], zsum[R];
   float ring_o[kNW][R][kD];            // per wave: its ring slices' outputs, original channel order
 };
 
@@ -617,40 +616,35 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   }
   __syncthreads();
   SKVQ_STAMP(8);
-  if (tid < 16 * R) {
-    // thread (head r, wave w): the chunk's reference m* = max over waves, the wave's factors
-    // 2^(m_w - m*), and the sums that need no channel; reductions over the 16 lanes of a head
-    const int r = tid >> 4, w = tid & 15;
-    const bool in = w < kNW;
-    const float wl = in ? sm.wl[w][r] : 0.f, rl = in ? sm.rl[w][r] : 0.f;
-    const float wm = wl > 0.f ? sm.wm[w][r] : -INFINITY, rm = rl > 0.f ? sm.rm[w][r] : -INFINITY;
-    float m = fmaxf(wm, rm);
-#pragma unroll
-    for (int off = 1; off < 16; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
-    const float e = wl > 0.f ? exp2f(wm - m) : 0.f, g = rl > 0.f ? exp2f(rm - m) : 0.f;
-    float den = e * wl + g * rl, zsum = in ? e * sm.wz[w][r] : 0.f;
-#pragma unroll
-    for (int off = 1; off < 16; off <<= 1) den += __shfl_xor(den, off), zsum += __shfl_xor(zsum, off);
-    if (in) sm.ew[w][r] = e, sm.er[w][r] = g;
-    if (w == 0) sm.mstar[r] = m, sm.den[r] = den, sm.zsum[r] = zsum;
-  }
-  __syncthreads();
   SKVQ_STAMP(9);
   if (tid < R * kD) {
+    // thread (head r, position p): the chunk's reference m* = max over waves and ring slices,
+    // each one's factor 2^(m - m*), the sums that need no channel (every thread of a head
+    // computes the same ones: cheaper than another exchange through LDS), its channel's sum
     const int r = tid >> 7, p = tid & 127;
     const int ch = pv_ch;
-    float num = sm.zsum[r];
-#pragma unroll 4
+    float wm[kNW], wl[kNW], rm[kNW], rl[kNW];
+    float m = -INFINITY;
+#pragma unroll
     for (int w = 0; w < kNW; ++w) {
-      const float e = sm.ew[w][r], g = sm.er[w][r];
-      if (e > 0.f) num = fmaf(e, sm.stage[w][r][p], num);
+      wl[w] = sm.wl[w][r], rl[w] = sm.rl[w][r];
+      wm[w] = wl[w] > 0.f ? sm.wm[w][r] : -INFINITY;
+      rm[w] = rl[w] > 0.f ? sm.rm[w][r] : -INFINITY;
+      m = fmaxf(m, fmaxf(wm[w], rm[w]));
+    }
+    float den = 0.f, num = 0.f;
+#pragma unroll
+    for (int w = 0; w < kNW; ++w) {
+      const float e = wl[w] > 0.f ? fast_exp2(wm[w] - m) : 0.f, g = rl[w] > 0.f ? fast_exp2(rm[w] - m) : 0.f;
+      den = fmaf(e, wl[w], fmaf(g, rl[w], den));
+      if (e > 0.f) num = fmaf(e, sm.stage[w][r][p] + sm.wz[w][r], num);
       if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
     float *part = L.workspace + (((long long)b * L.Hq + hk * R + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
     part[4 + ch] = num;
     if (p == 0) {
-      part[0] = sm.mstar[r];
-      part[1] = sm.den[r];
+      part[0] = m;
+      part[1] = den;
     }
   }
   SKVQ_STAMP(3);
