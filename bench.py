@@ -29,7 +29,7 @@ D = 128
 # HBM bytes per skvq_decode_attention call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (chunk kernel + merge kernel, counters scaled by a plain copy of known size); see
 # profiles/decode_c3_mistral7b_128k_pmc.txt.  Only workloads that were measured have an entry.
-MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 78139 * 1024}
+MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 77983 * 1024}
 
 
 def algorithmic_bytes_decode(w, n_tokens: int) -> int:
