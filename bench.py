@@ -8,8 +8,9 @@ its turn comes again) the token leaving the fp16 window is quantized
 (skvq_decode_attention).  Inputs are seeded synthetic tensors already resident in HBM.
 
 Prints ONE JSON line.  `value` is microseconds per token (all layers); `roofline` prices the
-decode kernel's algorithmic bytes against the 8 TB/s HBM peak; `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same workload.
+algorithmic bytes of one skvq_decode_attention call against the 8 TB/s HBM peak, its duration
+measured with HIP events around the layers' calls issued back to back; `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -146,16 +147,10 @@ def main() -> int:
               * sv_d[:, :, 0]).to(torch.float16)
     out = torch.empty((n_layers, w.batch, w.n_q_heads, D), dtype=torch.float32, device=device)
 
-    def step(i, events=None):
+    def step(i):
         for layer, c in enumerate(caches):
             c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
             c.skvq_decode_attention(q_all[i, layer], out_f32=out[layer])
-            if events is not None:
-                e1.record()
-                events.append((e0, e1))
 
     i = 0
     for _ in range(n_warm):
@@ -171,13 +166,22 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / n_steps
     n_tokens_mid = w.context + n_warm + n_steps // 2
 
-    # roofline pass: the same calls again, with an event pair around each decode call
-    events = []
+    # roofline pass: per step, the appends of all layers first, then the decode calls of all
+    # layers back to back between one pair of HIP events (an event pair around every single
+    # call adds about 2 us to each); average launch duration = elapsed / layers
+    dec_us = []
     for _ in range(n_steps):
-        step(i, events)
+        for layer, c in enumerate(caches):
+            c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for layer, c in enumerate(caches):
+            c.skvq_decode_attention(q_all[i, layer], out_f32=out[layer])
+        e1.record()
+        torch.cuda.synchronize()
+        dec_us.append(e0.elapsed_time(e1) * 1e3 / n_layers)
         i += 1
-    torch.cuda.synchronize()
-    dec_us = np.array([a.elapsed_time(b) * 1e3 for a, b in events])
+    dec_us = np.array(dec_us)
     dec_avg_us = float(dec_us.mean())
     n_tokens_roof = w.context + n_warm + n_steps + n_steps // 2
     alg_bytes = algorithmic_bytes_decode(w, n_tokens_roof)

@@ -269,22 +269,45 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   __half *ring = wave ? L.v_win : L.k_win;
   const __half *fresh = (wave ? vnew : knew) + head * kD;
 
-  if (evict) {
-    rows[wave][2 * lane] = ring[slot + 2 * lane];
-    rows[wave][2 * lane + 1] = ring[slot + 2 * lane + 1];
-  }
-  __syncthreads();
-  // the old token is now in LDS; the new one may take its slot
-  reinterpret_cast<__half2 *>(ring + slot)[lane] = reinterpret_cast<const __half2 *>(fresh)[lane];
-  if (!evict) return;
-
-  const int *perm = (wave ? L.perm_v : L.perm_k) + hk * kD;
+  // Everything the kernel reads is requested up front (one memory round trip): the new token,
+  // the slot's old token, the permutation, the clip factor, and what is already stored of the
+  // V units the old token will be merged into.
+  const __half2 fresh2 = reinterpret_cast<const __half2 *>(fresh)[lane];
+  const int s = evict ? (int)(te % kVBlock) : 0, kb = s >> 3, i = s & 7;
+  uint8_t *blk = L.v_codes + (head * L.n_vblocks + (evict ? te / kVBlock : 0)) * L.v_block_bytes;
   const int grp = (2 * lane) / L.G;
-  const float alpha = (wave ? L.clip_v : L.clip_k)[hk * L.NG + grp];
+  __half2 old2 = fresh2;
+  int p0 = 0, p1 = 0;
+  float alpha = 1.f;
+  unsigned old_word = 0;   // 2-bit V: dword nh of unit j (lane = (j, nh))
+  uint8_t old_unit[13];    // 3-level V: unit j (lane = j < 16)
+#pragma unroll
+  for (int q = 0; q < 13; ++q) old_unit[q] = 0;
+  if (evict) {
+    old2 = reinterpret_cast<const __half2 *>(ring + slot)[lane];
+    const int2 pp = reinterpret_cast<const int2 *>((wave ? L.perm_v : L.perm_k) + hk * kD)[lane];
+    p0 = pp.x, p1 = pp.y;
+    alpha = (wave ? L.clip_v : L.clip_k)[hk * L.NG + grp];
+    if (wave == 1 && i != 0) {
+      if (L.v_levels == 4) {
+        old_word = reinterpret_cast<const unsigned *>(blk + 16 * (16 * kb + (lane & 15)))[lane >> 4];
+      } else if (lane < 16) {
+        const uint8_t *u = blk + 13 * (16 * kb + lane);
+#pragma unroll
+        for (int q = 0; q < 13; ++q) old_unit[q] = u[q];
+      }
+    }
+  }
+  // the old token is in registers; the new one may take its slot
+  reinterpret_cast<__half2 *>(ring + slot)[lane] = fresh2;
+  if (!evict) return;
+  reinterpret_cast<__half2 *>(rows[wave])[lane] = old2;
+  __syncthreads();
+
   const float top = wave ? (float)(L.v_levels - 1) : 3.0f;
   unsigned c0, c1;
   float scale, zero;
-  encode_row(rows[wave], perm[2 * lane], perm[2 * lane + 1], alpha, L.G, top, c0, c1, scale, zero);
+  encode_row(rows[wave], p0, p1, alpha, L.G, top, c0, c1, scale, zero);
   float *meta = wave ? L.v_meta : L.k_meta;
   if ((2 * lane) % L.G == 0)
     reinterpret_cast<float2 *>(meta)[(head * L.Tcap + te) * L.NG + grp] = make_float2(scale, zero);
@@ -298,8 +321,6 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   __syncthreads();
   if (wave == 0) return;
 
-  const int s = (int)(te % kVBlock), kb = s >> 3, i = s & 7;
-  uint8_t *blk = L.v_codes + (head * L.n_vblocks + te / kVBlock) * L.v_block_bytes;
   if (s == 0) {
     // First token of a block: the block starts as zeros.  The 16 units of sub-block 0 are
     // written whole below (i == 0), so only the other three sub-blocks are cleared here.
@@ -311,18 +332,15 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
     const int j = lane & 15, nh = lane >> 4;
     const unsigned bit = 16 * (i & 1) + 2 * (i >> 1);
     const unsigned add = ((unsigned)vcodes[16 * (2 * nh) + j] << bit) | ((unsigned)vcodes[16 * (2 * nh + 1) + j] << (bit + 8));
-    unsigned *w = reinterpret_cast<unsigned *>(blk + 16 * (16 * kb + j)) + nh;
-    *w = (i == 0 ? 0u : *w) | add;
+    reinterpret_cast<unsigned *>(blk + 16 * (16 * kb + j))[nh] = old_word | add;  // old_word is 0 when i == 0
   } else if (lane < 16) {
     const int j = lane;
     uint8_t *u = blk + 13 * (16 * kb + j);
-    unsigned long long lo = 0, hi = 0;
-    if (i != 0) {
+    unsigned long long lo = 0, hi = 0;  // all zero when i == 0
 #pragma unroll
-      for (int q = 0; q < 8; ++q) lo |= (unsigned long long)u[q] << (8 * q);
+    for (int q = 0; q < 8; ++q) lo |= (unsigned long long)old_unit[q] << (8 * q);
 #pragma unroll
-      for (int q = 0; q < 5; ++q) hi |= (unsigned long long)u[8 + q] << (8 * q);
-    }
+    for (int q = 0; q < 5; ++q) hi |= (unsigned long long)old_unit[8 + q] << (8 * q);
     unsigned pw = 1;
     for (int q = 0; q < i; ++q) pw *= 3;
     unsigned long long f[8];
