@@ -94,6 +94,9 @@ DECODE_CASES = [
     small("mha_v2_outlier", v_bits=2.0, channel_profile="outlier4", perm_stat="absmax", context=2048),
     small("gqa4_t15", n_q_heads=16, n_kv_heads=4, context=1333, batch=2),
     small("gqa4_v2", n_q_heads=8, n_kv_heads=2, context=999, v_bits=2.0),
+    small("gqa2_t15", n_q_heads=8, n_kv_heads=4, context=2100),
+    small("gqa2_v2_w512", n_q_heads=4, n_kv_heads=2, v_bits=2.0, window=512, context=3000),
+    small("mha_t15_w33", window=33, context=5000, batch=3),
     small("gqa2_g64", n_q_heads=4, n_kv_heads=2, group_size=64, context=611),
     small("gqa8_g32_v2", n_q_heads=8, n_kv_heads=1, group_size=32, v_bits=2.0, context=450, window=16),
     small("mha_g32_t15", group_size=32, context=300),
