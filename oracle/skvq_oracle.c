@@ -112,7 +112,7 @@ void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
   bytes[1] = heads * ((tcap + VBT - 1) / VBT) * v_block_bytes(c->v_levels);
   bytes[2] = heads * tcap * ng * 2 * sizeof(float);
   bytes[3] = bytes[2];
-  bytes[4] = heads * (size_t)c->window * D * 2;
+  bytes[4] = heads * (size_t)(c->window + c->n_sink) * D * 2;
   bytes[5] = bytes[4];
 }
 
@@ -206,7 +206,8 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
 static int check_config(const skvq_ref_config *c) {
   if (c->head_dim != D || c->group_size <= 0 || D % c->group_size) return -1;
   if (c->k_levels != 4 || (c->v_levels != 4 && c->v_levels != 3)) return -2;
-  if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1)
+  if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1 ||
+      c->n_sink < 0)
     return -1;
   return 0;
 }
@@ -217,19 +218,27 @@ int skvq_ref_prefill_quantize(const skvq_ref_config *c, const skvq_ref_buffers *
   int rc = check_config(c);
   if (rc) return rc;
   if (T < 0) return -1;
-  int64_t W = c->window, nq = T > W ? T - W : 0;
-  if (nq > c->max_quant_tokens) return -3;
+  int64_t W = c->window, S = c->n_sink, first_win = T > W ? T - W : 0;
+  if (first_win - S > c->max_quant_tokens) return -3;
   int heads = c->batch * c->n_kv_heads;
 #pragma omp parallel for schedule(static)
   for (int bh = 0; bh < heads; ++bh) {
     int b = bh / c->n_kv_heads, hk = bh % c->n_kv_heads;
     const uint16_t *kh = k + (size_t)bh * (size_t)T * D;
     const uint16_t *vh = v + (size_t)bh * (size_t)T * D;
-    for (int64_t t = 0; t < nq; ++t) store_quantized(c, buf, b, hk, t, kh + t * D, vh + t * D);
-    for (int64_t a = nq; a < T; ++a) {
-      size_t slot = (size_t)bh * (size_t)W + (size_t)(a % W);
-      memcpy(buf->k_win + slot * D, kh + a * D, D * 2);
-      memcpy(buf->v_win + slot * D, vh + a * D, D * 2);
+    uint16_t *kw = buf->k_win + (size_t)bh * (size_t)(W + S) * D;
+    uint16_t *vw = buf->v_win + (size_t)bh * (size_t)(W + S) * D;
+    for (int64_t a = 0; a < first_win; ++a) {
+      if (a < S) { /* the filter rule keeps a sink token in full precision */
+        memcpy(kw + (size_t)(W + a) * D, kh + a * D, D * 2);
+        memcpy(vw + (size_t)(W + a) * D, vh + a * D, D * 2);
+      } else {
+        store_quantized(c, buf, b, hk, a - S, kh + a * D, vh + a * D);
+      }
+    }
+    for (int64_t a = first_win; a < T; ++a) {
+      memcpy(kw + (size_t)(a % W) * D, kh + a * D, D * 2);
+      memcpy(vw + (size_t)(a % W) * D, vh + a * D, D * 2);
     }
   }
   *n_tokens = T;
@@ -240,16 +249,25 @@ int skvq_ref_quantize_append(const skvq_ref_config *c, const skvq_ref_buffers *b
                              const uint16_t *k_new, const uint16_t *v_new, int64_t *n_tokens) {
   int rc = check_config(c);
   if (rc) return rc;
-  int64_t T = *n_tokens, W = c->window;
-  if (T >= W && T - W >= c->max_quant_tokens) return -3;
+  int64_t T = *n_tokens, W = c->window, S = c->n_sink;
+  if (T >= W && T - W >= S && T - W - S >= c->max_quant_tokens) return -3;
   for (int b = 0; b < c->batch; ++b)
     for (int hk = 0; hk < c->n_kv_heads; ++hk) {
       size_t bh = (size_t)b * c->n_kv_heads + hk;
-      size_t slot = bh * (size_t)W + (size_t)(T % W);
-      if (T >= W) /* the slot holds token T-W, which now leaves the window */
-        store_quantized(c, buf, b, hk, T - W, buf->k_win + slot * D, buf->v_win + slot * D);
-      memcpy(buf->k_win + slot * D, k_new + bh * D, D * 2);
-      memcpy(buf->v_win + slot * D, v_new + bh * D, D * 2);
+      uint16_t *kw = buf->k_win + bh * (size_t)(W + S) * D;
+      uint16_t *vw = buf->v_win + bh * (size_t)(W + S) * D;
+      size_t slot = (size_t)(T % W);
+      if (T >= W) { /* the slot holds token T-W, which now leaves the window */
+        int64_t a = T - W;
+        if (a < S) {
+          memcpy(kw + (size_t)(W + a) * D, kw + slot * D, D * 2);
+          memcpy(vw + (size_t)(W + a) * D, vw + slot * D, D * 2);
+        } else {
+          store_quantized(c, buf, b, hk, a - S, kw + slot * D, vw + slot * D);
+        }
+      }
+      memcpy(kw + slot * D, k_new + bh * D, D * 2);
+      memcpy(vw + slot * D, v_new + bh * D, D * 2);
     }
   *n_tokens = T + 1;
   return 0;
@@ -262,7 +280,8 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
   int rc = check_config(c);
   if (rc) return rc;
   if (T <= 0) return -4;
-  int64_t W = c->window, nq = T > W ? T - W : 0;
+  int64_t W = c->window, S = c->n_sink, first_win = T > W ? T - W : 0;
+  int64_t n_sink = first_win < S ? first_win : S; /* sink tokens present */
   int G = c->group_size, ng = D / G, rep = c->n_q_heads / c->n_kv_heads;
   size_t tcap = (size_t)c->max_quant_tokens, nblk = (tcap + VBT - 1) / VBT;
   size_t bb = v_block_bytes(c->v_levels);
@@ -281,21 +300,25 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       fail = 1;
       continue;
     }
+    const uint16_t *kwin = buf->k_win + head * (size_t)(W + S) * D;
+    const uint16_t *vwin = buf->v_win + head * (size_t)(W + S) * D;
     /* scores of packed rows: reordered query . dequantized reordered key */
-    for (int64_t t = 0; t < nq; ++t) {
-      const uint8_t *row = buf->k_codes + (head * tcap + (size_t)t) * (D / 4);
-      const float *meta = buf->k_meta + (head * tcap + (size_t)t) * ng * 2;
+    for (int64_t a = n_sink; a < first_win; ++a) {
+      size_t t = (size_t)(a - S);
+      const uint8_t *row = buf->k_codes + (head * tcap + t) * (D / 4);
+      const float *meta = buf->k_meta + (head * tcap + t) * ng * 2;
       double dot = 0.0;
       for (int p = 0; p < D; ++p) {
         double kd = (double)skvq_ref_k_get(row, p) * (double)meta[2 * (p / G)] +
                     (double)meta[2 * (p / G) + 1];
         dot += qf[pk[p]] * kd;
       }
-      s[t] = (double)c->sm_scale * dot;
+      s[a] = (double)c->sm_scale * dot;
     }
-    /* scores of ring tokens, original channel order */
-    for (int64_t a = nq; a < T; ++a) {
-      const uint16_t *kw = buf->k_win + (head * (size_t)W + (size_t)(a % W)) * D;
+    /* scores of sink and ring tokens, original channel order */
+    for (int64_t a = 0; a < T; ++a) {
+      if (a >= n_sink && a < first_win) continue;
+      const uint16_t *kw = kwin + (size_t)(a < n_sink ? W + a : a % W) * D;
       double dot = 0.0;
       for (int ch = 0; ch < D; ++ch) dot += qf[ch] * (double)skvq_ref_half_to_float(kw[ch]);
       s[a] = (double)c->sm_scale * dot;
@@ -305,11 +328,12 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       if (s[t] > m) m = s[t];
     double denom = 0.0;
     for (int ch = 0; ch < D; ++ch) acc[ch] = 0.0;
-    for (int64_t t = 0; t < nq; ++t) {
-      double w = exp(s[t] - m);
+    for (int64_t a = n_sink; a < first_win; ++a) {
+      double w = exp(s[a] - m);
       denom += w;
-      const uint8_t *blk = buf->v_codes + (head * nblk + (size_t)(t / VBT)) * bb;
-      const float *meta = buf->v_meta + (head * tcap + (size_t)t) * ng * 2;
+      size_t t = (size_t)(a - S);
+      const uint8_t *blk = buf->v_codes + (head * nblk + t / VBT) * bb;
+      const float *meta = buf->v_meta + (head * tcap + t) * ng * 2;
       for (int p = 0; p < D; ++p) {
         double vd = (double)skvq_ref_v_get(blk, c->v_levels, (int)(t % VBT), p) *
                         (double)meta[2 * (p / G)] +
@@ -317,10 +341,11 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
         acc[pv[p]] += w * vd;
       }
     }
-    for (int64_t a = nq; a < T; ++a) {
+    for (int64_t a = 0; a < T; ++a) {
+      if (a >= n_sink && a < first_win) continue;
       double w = exp(s[a] - m);
       denom += w;
-      const uint16_t *vw = buf->v_win + (head * (size_t)W + (size_t)(a % W)) * D;
+      const uint16_t *vw = vwin + (size_t)(a < n_sink ? W + a : a % W) * D;
       for (int ch = 0; ch < D; ++ch) acc[ch] += w * (double)skvq_ref_half_to_float(vw[ch]);
     }
     for (int ch = 0; ch < D; ++ch) {

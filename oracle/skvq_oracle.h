@@ -4,8 +4,9 @@
  * A plain, slow, single-purpose reference of the SKVQ hot path (arXiv
  * 2405.06219): clipped dynamic group quantization with channel reorder
  * (Section 3.1, Eq. 2; Algorithm 1 clipping_quant), the sliding fp16 window
- * (Section 3.2), and one decode-step attention over the mixed-precision
- * cache (Eq. 1; Algorithm 1 body with l = 1).
+ * (Section 3.2) with the attention-sink filter rule (Section 3.2, "filter
+ * rules"; Algorithm 1 body), and one decode-step attention over the
+ * mixed-precision cache (Eq. 1; Algorithm 1 body with l = 1).
  *
  * Nothing in the product (the HIP library and its Python binding) may
  * include, link or call this; only the tests, the smoke check and the
@@ -39,6 +40,8 @@ typedef struct {
   int32_t group_size;                             /* G, divides head_dim       */
   int32_t k_levels, v_levels;                     /* 4 = 2-bit, 3 = "1.5-bit"  */
   int32_t window;                                 /* W >= 1                    */
+  int32_t n_sink;                                 /* S >= 0: tokens 0..S-1 are
+                                                     never quantized           */
   int64_t max_quant_tokens;                       /* rows in the packed region */
   const int32_t *perm_k, *perm_v;                 /* [Hk][D] gather index      */
   const float *clip_k, *clip_v;                   /* [Hk][D/G] alpha           */
@@ -50,8 +53,8 @@ typedef struct {
   uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][1024 or 832]                    */
   float *k_meta;     /* [B][Hk][Tcap][D/G][2] = (scale, zero)                  */
   float *v_meta;     /* same                                                   */
-  uint16_t *k_win;   /* fp16 bits [B][Hk][W][D], token a lives in slot a % W   */
-  uint16_t *v_win;
+  uint16_t *k_win;   /* fp16 bits [B][Hk][W+S][D]: rows 0..W-1 are the ring    */
+  uint16_t *v_win;   /* (token a in slot a % W), row W+a keeps sink token a    */
 } skvq_ref_buffers;
 
 /* fp16 <-> fp32 helpers (exact widening; round-to-nearest-even narrowing). */
@@ -82,16 +85,23 @@ void skvq_ref_k_put(uint8_t *k_row, int p, int code);
 int skvq_ref_v_get(const uint8_t *v_block, int levels, int t_in_block, int p);
 void skvq_ref_v_put(uint8_t *v_block, int levels, int t_in_block, int p, int code);
 
-/* Prefill (Section 3.2, phase 1): tokens [0, T-W) are reordered, quantized
- * and packed into rows [0, T-W); the last min(T, W) tokens are copied bit for
- * bit into the fp16 ring.  k, v: fp16 bits [B][Hk][T][D], original channel
- * order.  Returns 0, or -3 if T-W exceeds max_quant_tokens.  *n_tokens = T. */
+/* Where token a of T cached tokens lives (Section 3.2): the last min(T, W)
+ * tokens are in the fp16 ring; of the older ones, tokens a < S (the attention
+ * sinks that the filter rule keeps in full precision) sit in sink row a and
+ * token a >= S is packed row a - S.
+ *
+ * Prefill (Section 3.2, phase 1): every token older than the window goes to
+ * its place as above (reordered, quantized and packed, or copied bit for bit
+ * if it is a sink); the last min(T, W) tokens are copied bit for bit into the
+ * ring.  k, v: fp16 bits [B][Hk][T][D], original channel order.  Returns 0,
+ * or -3 if T-W-S exceeds max_quant_tokens.  *n_tokens = T.                  */
 int skvq_ref_prefill_quantize(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
                               const uint16_t *k, const uint16_t *v, int64_t T,
                               int64_t *n_tokens);
 
-/* Decode (Section 3.2, phase 2): the token that slides out of the window is
- * quantized into row n_tokens-W, then the new token takes its ring slot.
+/* Decode (Section 3.2, phase 2): the token that slides out of the window
+ * (number n_tokens-W) goes to its place as above, then the new token takes
+ * its ring slot.
  * k_new, v_new: fp16 bits [B][Hk][D].  *n_tokens is advanced by one.        */
 int skvq_ref_quantize_append(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
                              const uint16_t *k_new, const uint16_t *v_new,
@@ -99,7 +109,7 @@ int skvq_ref_quantize_append(const skvq_ref_config *cfg, const skvq_ref_buffers 
 
 /* One decode-step attention (Eq. 1 with the standard 1/sqrt(d)-style scale):
  * dequantize every packed row in fp64, score against the reordered query,
- * score the ring tokens in original order, one softmax over all of them,
+ * score the sink and ring tokens in original order, one softmax over all,
  * weighted sum of dequantized values scattered back to original channel
  * order.  q: fp16 bits [B][Hq][D]; out_f32: [B][Hq][D]; out_f16 may be NULL.
  * Returns 0, or -4 if the cache is empty.                                    */

@@ -33,7 +33,8 @@ def build(force: bool = False) -> str:
 class _Config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("group_size", C.c_int32), ("k_levels", C.c_int32),
-                ("v_levels", C.c_int32), ("window", C.c_int32), ("max_quant_tokens", C.c_int64),
+                ("v_levels", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
+                ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
                 ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
 
@@ -110,7 +111,7 @@ class OracleCache:
     """Host-side mixed-precision cache of one attention layer, driven by the oracle."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens,
-                 perm_k, perm_v, clip_k, clip_v, sm_scale=None, k_bits=2.0, fill=0):
+                 perm_k, perm_v, clip_k, clip_v, sm_scale=None, k_bits=2.0, fill=0, n_sink=0):
         self.perm_k = np.ascontiguousarray(perm_k, np.int32)
         self.perm_v = np.ascontiguousarray(perm_v, np.int32)
         self.clip_k = np.ascontiguousarray(clip_k, np.float32)
@@ -118,7 +119,7 @@ class OracleCache:
         if sm_scale is None:
             sm_scale = 1.0 / np.sqrt(HEAD_DIM)
         self.cfg = _Config(batch, n_q_heads, n_kv_heads, HEAD_DIM, group_size, levels_of(k_bits),
-                           levels_of(v_bits), window, max_quant_tokens, _ptr(self.perm_k),
+                           levels_of(v_bits), window, n_sink, max_quant_tokens, _ptr(self.perm_k),
                            _ptr(self.perm_v), _ptr(self.clip_k), _ptr(self.clip_v), sm_scale)
         sizes = (C.c_size_t * 6)()
         lib().skvq_ref_sizes(C.byref(self.cfg), sizes)
@@ -131,14 +132,15 @@ class OracleCache:
         self.v_codes = np.full((batch, n_kv_heads, nblk, vb), fill, np.uint8)
         self.k_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
         self.v_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
-        self.k_win = np.zeros((batch, n_kv_heads, window, HEAD_DIM), np.uint16)
-        self.v_win = np.zeros((batch, n_kv_heads, window, HEAD_DIM), np.uint16)
+        self.k_win = np.zeros((batch, n_kv_heads, window + n_sink, HEAD_DIM), np.uint16)
+        self.v_win = np.zeros((batch, n_kv_heads, window + n_sink, HEAD_DIM), np.uint16)
         for a in (self.k_meta, self.v_meta, self.k_win, self.v_win):
             a.view(np.uint8)[...] = fill     # untouched bytes keep the caller's initial pattern
         assert [a.nbytes for a in self.arrays()] == self.sizes, (self.sizes, heads)
         self.buf = _Buffers(*[_ptr(a) for a in self.arrays()])
         self.n_tokens = 0
         self.window = window
+        self.n_sink = n_sink
         self.shape = (batch, n_q_heads, n_kv_heads)
 
     def arrays(self):
@@ -146,7 +148,7 @@ class OracleCache:
 
     @property
     def n_quant(self) -> int:
-        return max(self.n_tokens - self.window, 0)
+        return max(self.n_tokens - self.window - self.n_sink, 0)
 
     def prefill(self, k: np.ndarray, v: np.ndarray) -> int:
         b, _, hk = self.shape

@@ -401,3 +401,102 @@ def test_capacity_and_empty_cache_errors(oracle):
     assert c.append(x[:, :, 0], x[:, :, 0]) == -3
     with pytest.raises(RuntimeError):
         oracle.OracleCache(1, 1, 1, 128, 2.0, 4, 2, perm, perm, clip, clip).decode(np.zeros((1, 1, D), np.float16))
+
+
+# ------------------------------------------------ attention sinks (filter rule) ----
+# Section 3.2 ("filter rules") and the Algorithm 1 body: tokens a filter selects stay in full
+# precision when they slide out of the window; the rule used in the paper's experiments keeps the
+# first few tokens (the attention sinks).
+
+def test_sink_tokens_are_kept_bit_for_bit_and_only_shift_the_packed_rows(oracle):
+    """With S sinks the packed rows are exactly what a cache without sinks stores for the
+    sequence with its first S tokens removed, and sink row a is token a bit for bit."""
+    rng = np.random.default_rng(600)
+    B, Hq, Hk, W, T, S = 2, 4, 2, 8, 61, 5
+    k = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, 2), 0.9, np.float32)
+    for v_bits in (1.5, 2.0):
+        a = oracle.OracleCache(B, Hq, Hk, 64, v_bits, W, 64, pk, pv, clip, clip, n_sink=S)
+        b = oracle.OracleCache(B, Hq, Hk, 64, v_bits, W, 64, pk, pv, clip, clip)
+        assert a.prefill(k, v) == 0 and b.prefill(k[:, :, S:], v[:, :, S:]) == 0
+        assert a.n_quant == b.n_quant == T - W - S
+        for x, y in zip(a.arrays()[:4], b.arrays()[:4]):
+            assert np.array_equal(x, y)
+        for t in range(S):
+            assert np.array_equal(a.k_win[:, :, W + t].view(np.float16), k[:, :, t])
+            assert np.array_equal(a.v_win[:, :, W + t].view(np.float16), v[:, :, t])
+        for t in range(T - W, T):
+            assert np.array_equal(a.k_win[:, :, t % W].view(np.float16), k[:, :, t])
+
+
+def test_sinks_that_cover_everything_old_give_textbook_attention(oracle):
+    """If every token older than the window is a sink nothing is quantized: exact attention."""
+    rng = np.random.default_rng(601)
+    B, Hq, Hk, W = 1, 4, 2, 8
+    for T, S in ((20, 12), (20, 40), (9, 1), (5, 3)):
+        k = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+        v = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+        q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+        c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, W, 4, random_perms(rng, Hk), random_perms(rng, Hk),
+                               np.full((Hk, 1), 0.9, np.float32), np.full((Hk, 1), 0.9, np.float32), n_sink=S)
+        assert c.prefill(k, v) == 0 and c.n_quant == 0
+        assert np.abs(c.decode(q) - sdpa64(q, k, v, 1 / np.sqrt(D))).max() < 2e-6
+
+
+@pytest.mark.parametrize("v_bits,G,S", [(1.5, 128, 5), (2.0, 32, 3), (1.5, 64, 1)])
+def test_lossy_cache_with_sinks_equals_dequantize_then_textbook_attention(oracle, v_bits, G, S):
+    """Token order of the mixed cache: sinks (exact), packed rows (decoded independently from the
+    format statement), window (exact)."""
+    rng = np.random.default_rng(610 + G)
+    B, Hq, Hk, W, T = 2, 4, 2, 8, 45
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    ck = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    cv = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S)
+    c.prefill(k, v)
+    kq, vq = numpy_dequantize(c, T - S)     # T - S - W packed rows
+    f64 = np.float64
+    kfull = np.concatenate([k[:, :, :S].astype(f64), kq, k[:, :, T - W:].astype(f64)], axis=2)
+    vfull = np.concatenate([v[:, :, :S].astype(f64), vq, v[:, :, T - W:].astype(f64)], axis=2)
+    assert kfull.shape[2] == T
+    ref = sdpa64(q, kfull, vfull, 1 / np.sqrt(D))
+    assert np.abs(c.decode(q) - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    # keeping the sinks exact can only bring the cache closer to the fp16 one on those tokens:
+    # a query that attends (almost) only to token 0 gets (almost) exactly v[0] back
+    c2 = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S, sm_scale=40.0)
+    c2.prefill(k, v)
+    q0 = np.repeat(k[:, :, 0], Hq // Hk, axis=1)
+    out = c2.decode(q0)
+    want = np.repeat(v[:, :, 0].astype(f64), Hq // Hk, axis=1)
+    assert np.abs(out - want).max() < 1e-3 * np.abs(want).max()
+
+
+def test_prefill_then_appends_equals_one_longer_prefill_with_sinks(oracle):
+    """Appends walk tokens through all three places: ring -> sink rows (the first S) -> packed."""
+    rng = np.random.default_rng(620)
+    B, Hq, Hk, W, S = 2, 4, 2, 8, 5
+    k = rng.standard_normal((B, Hk, 60, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hk, 60, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, 2), 0.95, np.float32)
+    for T0 in (0, 3, 8, 11, 13, 30):
+        a = oracle.OracleCache(B, Hq, Hk, 64, 1.5, W, 64, pk, pv, clip, clip, fill=0xAB, n_sink=S)
+        b = oracle.OracleCache(B, Hq, Hk, 64, 1.5, W, 64, pk, pv, clip, clip, fill=0xAB, n_sink=S)
+        if T0:
+            assert a.prefill(k[:, :, :T0], v[:, :, :T0]) == 0
+        for s in range(T0, 60):
+            assert a.append(k[:, :, s], v[:, :, s]) == 0
+        assert b.prefill(k, v) == 0
+        assert a.n_tokens == b.n_tokens == 60 and a.n_quant == 60 - W - S
+        for x, y in zip(a.arrays(), b.arrays()):
+            assert np.array_equal(x, y)
+    # capacity counts packed rows only
+    c = oracle.OracleCache(B, Hq, Hk, 64, 1.5, W, 2, pk, pv, clip, clip, n_sink=S)
+    assert c.prefill(k[:, :, :W + S + 3], v[:, :, :W + S + 3]) == -3
+    assert c.prefill(k[:, :, :W + S + 2], v[:, :, :W + S + 2]) == 0
+    assert c.append(k[:, :, 0], v[:, :, 0]) == -3
