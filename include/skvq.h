@@ -67,6 +67,8 @@ typedef struct {
   int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2 only                              */
   int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_2 or SKVQ_BITS_1P5                */
   int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
+  int32_t n_sink;       /* S >= 0: the filter rule of Section 3.2 / Algorithm 1 that keeps
+                           the first S tokens (attention sinks) fp16 for ever; 0 = off    */
   int64_t max_quant_tokens; /* Tcap: rows of the packed region per sequence, >= 1         */
   const int32_t *perm_k; /* HOST [Hk][D]: reordered position p takes channel perm[h][p]   */
   const int32_t *perm_v; /* HOST [Hk][D]  (each row a permutation of 0..D-1)              */
@@ -84,8 +86,9 @@ typedef struct {
  *             a block is zero-filled when its first token is stored
  *   k_meta    f32 [B][Hk][Tcap][D/G][2]  (scale, zero) of Eq. 2, zero = alpha*min
  *   v_meta    f32 [B][Hk][Tcap][D/G][2]
- *   k_win     f16 [B][Hk][W][D]          token number a (0-based) sits in slot a % W
- *   v_win     f16 [B][Hk][W][D]
+ *   k_win     f16 [B][Hk][W+S][D]        rows 0..W-1: the ring, token number a (0-based) sits
+ *   v_win     f16 [B][Hk][W+S][D]        in slot a % W; row W+a: sink token a, once it has
+ *                                        left the window
  *   workspace f32 [B][Hq][SKVQ_MAX_SPLITS+1][132]  split partials of skvq_decode_attention
  *             (running max, sum of weights, two pads, 128 weighted value sums); scratch: any
  *             content is fine before a call and nothing in it survives one
@@ -108,26 +111,31 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
 /* Frees what skvq_create allocated (never the caller's buffers).  NULL is allowed. */
 void skvq_destroy(skvq_cache *cache);
 
-/* Section 3.2 prefill phase / Algorithm 1 with l = len(prompt), quantization part only.
+/* Where token a of T cached tokens lives: the last min(T,W) tokens are in the ring; of the
+ * older ones, token a < S is sink row a (fp16, bit for bit) and token a >= S is packed row
+ * a - S.
+ *
+ * Section 3.2 prefill phase / Algorithm 1 with l = len(prompt), quantization part only.
  * k, v: DEVICE fp16 [B][Hk][T][D], original channel order, T >= 0.  Resets the cache, then
- * tokens [0, T-W) are stored as packed rows [0, T-W) and the last min(T,W) tokens are copied
- * bit for bit into the ring.  Per (token, kv head, group g), with xp[p] = x[perm[p]]:
+ * every token goes to its place as above.  Per (token, kv head, group g) of a packed row,
+ * with xp[p] = x[perm[p]]:
  *   mn,mx = min,max xp (a zero of either sign counts as +0); lo = alpha_g*mn; hi = alpha_g*mx;
  *   scale = (hi-lo)/(levels-1); inv = scale>0 ? 1/scale : 0;
  *   code = clamp(rint((xp-lo)*inv), 0, levels-1), ties to even; zero = lo.
- * SKVQ_ERR_CAPACITY if T-W > Tcap. */
+ * SKVQ_ERR_CAPACITY if T-W-S > Tcap. */
 int skvq_prefill_quantize(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
                           void *hip_stream);
 
 /* Section 3.2 decode phase: with T tokens cached, if T >= W the token T-W (ring slot T % W)
- * is quantized into packed row T-W by the same arithmetic; then the new token is written to
- * slot T % W.  k_new, v_new: DEVICE fp16 [B][Hk][D].  SKVQ_ERR_CAPACITY if row T-W >= Tcap. */
+ * leaves the window: it is copied to sink row T-W if T-W < S, else quantized into packed row
+ * T-W-S by the same arithmetic; then the new token is written to slot T % W.
+ * k_new, v_new: DEVICE fp16 [B][Hk][D].  SKVQ_ERR_CAPACITY if row T-W-S >= Tcap. */
 int skvq_quantize_append(skvq_cache *cache, const void *k_new, const void *v_new,
                          void *hip_stream);
 
 /* Eq. 1 for one query token per sequence (Algorithm 1 with l = 1, attention part):
- * scores of packed rows are (reordered query) . (dequantized reordered key), scores of ring
- * tokens use the original order; one softmax (scale sm_scale, no mask) over all T tokens;
+ * scores of packed rows are (reordered query) . (dequantized reordered key), scores of sink
+ * and ring tokens use the original order; one softmax (scale sm_scale, no mask) over all T tokens;
  * output = weighted sum of dequantized values, returned in ORIGINAL channel order.
  * q: DEVICE fp16 [B][Hq][D].  out_f32: DEVICE fp32 [B][Hq][D].  out_f16: DEVICE fp16
  * [B][Hq][D] or NULL.  Query head hq reads kv head hq / (Hq/Hk).  The sequence is split
@@ -136,7 +144,8 @@ int skvq_quantize_append(skvq_cache *cache, const void *k_new, const void *v_new
 int skvq_decode_attention(skvq_cache *cache, const void *q, void *out_f32, void *out_f16,
                           void *hip_stream);
 
-/* Host counters: tokens cached, of which packed, of which in the ring.  Any may be NULL. */
+/* Host counters: tokens cached, of which packed, of which in the ring (the rest, at most S,
+ * are sink rows).  Any may be NULL. */
 int skvq_get_state(const skvq_cache *cache, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win);
 
 /* Declares that the buffers hold a valid cache of n_tokens tokens (e.g. to rewind after

@@ -26,7 +26,8 @@ BUFFER_NAMES = ("k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win", "wor
 class skvq_config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("group_size", C.c_int32), ("k_bits", C.c_int32),
-                ("v_bits", C.c_int32), ("window", C.c_int32), ("max_quant_tokens", C.c_int64),
+                ("v_bits", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
+                ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
                 ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
 
@@ -76,12 +77,12 @@ def bits_enum(bits: float) -> int:
 
 
 def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
-                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM):
+                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM, n_sink=0):
     """Returns (skvq_config, keepalive): the numpy arrays the config points to."""
     keep = [np.ascontiguousarray(perm_k, np.int32), np.ascontiguousarray(perm_v, np.int32),
             np.ascontiguousarray(clip_k, np.float32), np.ascontiguousarray(clip_v, np.float32)]
     cfg = skvq_config(batch, n_q_heads, n_kv_heads, head_dim, group_size, bits_enum(k_bits), bits_enum(v_bits),
-                      window, max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
+                      window, n_sink, max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
                       keep[3].ctypes.data, float(sm_scale))
     return cfg, keep
 
@@ -115,9 +116,10 @@ class SkvqCache:
     """One layer's cache: owns the device buffers (torch tensors) and the library handle."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
-                 clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None):
+                 clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None, n_sink=0):
         self.cfg, self._keep = make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window,
-                                           max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale, k_bits)
+                                           max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale, k_bits,
+                                           n_sink=n_sink)
         self.shape = (batch, n_q_heads, n_kv_heads)
         self.device = torch.device(device)
         self.sizes = skvq_sizes(self.cfg)
@@ -200,5 +202,5 @@ class SkvqCache:
                 raw["v_codes"].reshape(b, hk, (tcap + 31) // 32, vb),
                 raw["k_meta"].view(np.float32).reshape(b, hk, tcap, ng, 2),
                 raw["v_meta"].view(np.float32).reshape(b, hk, tcap, ng, 2),
-                raw["k_win"].view(np.uint16).reshape(b, hk, self.cfg.window, HEAD_DIM),
-                raw["v_win"].view(np.uint16).reshape(b, hk, self.cfg.window, HEAD_DIM)]
+                raw["k_win"].view(np.uint16).reshape(b, hk, self.cfg.window + self.cfg.n_sink, HEAD_DIM),
+                raw["v_win"].view(np.uint16).reshape(b, hk, self.cfg.window + self.cfg.n_sink, HEAD_DIM)]

@@ -27,7 +27,7 @@ namespace {
 
 int check_config(const skvq_config *c) {
   if (!c) return SKVQ_ERR_INVALID_ARG;
-  if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->window < 1 ||
+  if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->window < 1 || c->n_sink < 0 ||
       c->max_quant_tokens < 1)
     return SKVQ_ERR_INVALID_ARG;
   if (c->n_q_heads % c->n_kv_heads) return SKVQ_ERR_INVALID_ARG;
@@ -38,7 +38,7 @@ int check_config(const skvq_config *c) {
   if (c->k_bits != SKVQ_BITS_2) return SKVQ_ERR_UNSUPPORTED;
   if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5) return SKVQ_ERR_UNSUPPORTED;
   if (!(c->sm_scale >= 0.0f) || !std::isfinite(c->sm_scale)) return SKVQ_ERR_INVALID_ARG;
-  if ((long long)c->window > (1ll << 20) || c->max_quant_tokens > (1ll << 40))
+  if ((long long)c->window > (1ll << 20) || c->n_sink > (1 << 20) || c->max_quant_tokens > (1ll << 40))
     return SKVQ_ERR_INVALID_ARG;
   if (!c->perm_k || !c->perm_v || !c->clip_k || !c->clip_v) return SKVQ_ERR_INVALID_ARG;
   const int ng = kD / c->group_size;
@@ -70,7 +70,7 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
   bytes[1] = heads * ((tcap + kVBlock - 1) / kVBlock) * vb;
   bytes[2] = heads * tcap * ng * 2 * sizeof(float);
   bytes[3] = bytes[2];
-  bytes[4] = heads * (size_t)c->window * kD * sizeof(__half);
+  bytes[4] = heads * ((size_t)c->window + (size_t)c->n_sink) * kD * sizeof(__half);
   bytes[5] = bytes[4];
   // one partial per (sequence, query head, split); the ring is one more split
   bytes[6] = (size_t)c->batch * c->n_q_heads * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
@@ -151,6 +151,7 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.G = cfg->group_size;
   L.NG = kD / L.G;
   L.W = cfg->window;
+  L.S = cfg->n_sink;
   L.v_levels = cfg->v_bits == SKVQ_BITS_1P5 ? 3 : 4;
   L.v_block_bytes = L.v_levels == 3 ? kTernaryBlockBytes : kTwoBitBlockBytes;
   L.Tcap = cfg->max_quant_tokens;
@@ -211,8 +212,7 @@ void skvq_destroy(skvq_cache *c) {
 int skvq_prefill_quantize(skvq_cache *c, const void *k, const void *v, int64_t T, void *stream) {
   if (!c) return SKVQ_ERR_INVALID_ARG;
   if (T < 0 || (T > 0 && (!k || !v))) return SKVQ_ERR_INVALID_ARG;
-  const long long nq = T > c->L.W ? T - c->L.W : 0;
-  if (nq > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  if (counts_of(T, c->L.W, c->L.S).n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   if (T > 0) {
     hipError_t e = launch_prefill(c->L, (const __half *)k, (const __half *)v, T, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_quantize launch");
@@ -224,7 +224,7 @@ int skvq_prefill_quantize(skvq_cache *c, const void *k, const void *v, int64_t T
 int skvq_quantize_append(skvq_cache *c, const void *k_new, const void *v_new, void *stream) {
   if (!c || !k_new || !v_new) return SKVQ_ERR_INVALID_ARG;
   const long long T = c->n_tokens;
-  if (T >= c->L.W && T - c->L.W >= c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  if (counts_of(T + 1, c->L.W, c->L.S).n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   hipError_t e = launch_append(c->L, (const __half *)k_new, (const __half *)v_new, T, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_quantize_append launch");
   c->n_tokens = T + 1;
@@ -234,7 +234,7 @@ int skvq_quantize_append(skvq_cache *c, const void *k_new, const void *v_new, vo
 int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out_f16, void *stream) {
   if (!c || !q || !out_f32) return SKVQ_ERR_INVALID_ARG;
   if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
-  const long long nq = c->n_tokens > c->L.W ? c->n_tokens - c->L.W : 0;
+  const long long nq = counts_of(c->n_tokens, c->L.W, c->L.S).n_quant;
   hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16,
                                c->n_tokens, choose_splits(c, nq), (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention launch");
@@ -243,16 +243,16 @@ int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out
 
 int skvq_get_state(const skvq_cache *c, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win) {
   if (!c) return SKVQ_ERR_INVALID_ARG;
-  const long long T = c->n_tokens, W = c->L.W;
-  if (n_tokens) *n_tokens = T;
-  if (n_quant) *n_quant = T > W ? T - W : 0;
-  if (n_win) *n_win = (int32_t)(T < W ? T : W);
+  const Counts n = counts_of(c->n_tokens, c->L.W, c->L.S);
+  if (n_tokens) *n_tokens = c->n_tokens;
+  if (n_quant) *n_quant = n.n_quant;
+  if (n_win) *n_win = (int32_t)n.n_win;
   return SKVQ_OK;
 }
 
 int skvq_set_state(skvq_cache *c, int64_t n_tokens) {
   if (!c || n_tokens < 0) return SKVQ_ERR_INVALID_ARG;
-  if (n_tokens > c->L.W && n_tokens - c->L.W > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  if (counts_of(n_tokens, c->L.W, c->L.S).n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   c->n_tokens = n_tokens;
   return SKVQ_OK;
 }

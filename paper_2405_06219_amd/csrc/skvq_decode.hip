@@ -50,8 +50,9 @@ __device__ __forceinline__ unsigned v_code(const uint8_t *blk, int levels, int s
 // grid (n_splits + 1, Hk, B); the last x index is the fp16 ring.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __half *__restrict__ q,
-                                                             long long T, long long nq, int n_splits,
-                                                             long long tiles_per_split, int sp_base) {
+                                                             long long T, long long nq, int n_sink,
+                                                             int n_splits, long long tiles_per_split,
+                                                             int sp_base) {
   __shared__ float qs[kMaxR][kD];     // query in the order the chunk's keys use, times sm_scale*log2(e)
   __shared__ float qsum[kMaxR][4];    // its per-group sums
   __shared__ float pr[kMaxR][256];    // softmax numerators of the current tile
@@ -63,6 +64,10 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
   const bool ring = sp == n_splits;
   const long long head = (long long)b * L.Hk + hk;
   const int R = L.R, G = L.G, NG = L.NG;
+  // fp16 tokens in token order: n_sink sink rows (rows W.. of the ring buffers), then the window
+  const long long n_fp = T - nq, first_win = nq + n_sink;
+  const long long win_rows = (long long)L.W + L.S;
+  auto fp_row = [&](long long u) { return u < n_sink ? L.W + u : (first_win + (u - n_sink)) % L.W; };
   const float c = L.sm_scale * kLog2e;
 
   for (int x = tid; x < R * kD; x += 256) {
@@ -81,8 +86,8 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
 
   long long t_begin, t_end;
   if (ring) {
-    t_begin = nq;
-    t_end = T;
+    t_begin = 0;
+    t_end = n_fp;
   } else {
     t_begin = (long long)sp * tiles_per_split * 64;
     t_end = t_begin + tiles_per_split * 64;
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
     for (int r = 0; r < kMaxR; ++r) s[r] = -INFINITY;
     if (valid) {
       if (ring) {
-        const __half *row = L.k_win + (head * L.W + t % L.W) * kD;
+        const __half *row = L.k_win + (head * win_rows + fp_row(t)) * kD;
         for (int r = 0; r < R; ++r) s[r] = 0.f;
         for (int ch = 0; ch < kD; ++ch) {
           const float kv = __half2float(row[ch]);
@@ -160,7 +165,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
       const long long tt = tile + k;
       float val;
       if (ring) {
-        val = __half2float(L.v_win[(head * L.W + tt % L.W) * kD + p_own]);
+        val = __half2float(L.v_win[(head * win_rows + fp_row(tt)) * kD + p_own]);
       } else {
         const uint8_t *blk = L.v_codes + (head * L.n_vblocks + tt / kVBlock) * L.v_block_bytes;
         const float2 mz = reinterpret_cast<const float2 *>(L.v_meta)[(head * L.Tcap + tt) * NG + g_own];
@@ -259,7 +264,8 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
 
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16, long long T,
                          int n_splits, hipStream_t s) {
-  const long long nq = T > L.W ? T - L.W : 0;
+  const Counts n = counts_of(T, L.W, L.S);
+  const long long nq = n.n_quant;
   if (L.Hk > 65535 || L.B > 65535 || L.Hq > 65535) return hipErrorInvalidValue;
   if (n_splits > SKVQ_MAX_SPLITS || (nq > 0 && n_splits < 1)) return hipErrorInvalidValue;
   if (nq == 0) n_splits = 0;
@@ -269,12 +275,12 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
   int n_parts;
   if (decode_mfma_supported(L)) {
     if (n_splits < 1) n_splits = 1;
-    e = launch_decode_mfma(L, q, T, nq, n_splits, s);
+    e = launch_decode_mfma(L, q, T, nq, (int)n.n_sink, n_splits, s);
     if (e != hipSuccess) return e;
     n_parts = n_splits;  // the ring is folded into the chunks' partials
   } else {
     hipLaunchKernelGGL(decode_generic_kernel, dim3(n_splits + 1, L.Hk, L.B), dim3(256), 0, s, L, q, T, nq,
-                       n_splits, tps, 0);
+                       (int)n.n_sink, n_splits, tps, 0);
     n_parts = n_splits + 1;
   }
   e = hipGetLastError();

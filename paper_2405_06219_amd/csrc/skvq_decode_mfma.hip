@@ -190,7 +190,8 @@ struct RingData {
 
 template <int R, bool TERNARY>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
-                                                                  long long T, long long nq, int n_splits) {
+                                                                  long long T, long long nq, int n_sink,
+                                                                  int n_splits) {
   // grid (n_splits, Hk, B).  Workgroup sp owns an even share of the packed 64-token tiles of
   // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
   // j = sp (mod n_splits), dealt the same way.
@@ -247,19 +248,23 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 
   // ---- the fp16 ring: slices of 4 tokens, slice j belongs to workgroup j % n_splits and to
   //      the wave whose rank is (j / n_splits) % kRingWaves ----
-  const int n_win = (int)(T - nq), W = L.W;
-  const int n_slices = (n_win + kRingSlice - 1) / kRingSlice;
+  // The fp16 tokens in token order: the n_sink sink rows (rows W.. of the ring buffers), then
+  // the window's tokens.
+  const int n_win = (int)(T - nq) - n_sink, W = L.W;
+  const int n_fp = n_sink + n_win;
+  const int n_slices = (n_fp + kRingSlice - 1) / kRingSlice;
   const int ring_stride = n_splits * kRingWaves;
   // the younger waves (which get fewer tiles) are first in line for ring slices
   const int ring_rank = (wave + kNW / 2) % kNW;
   const int ring_first = sp + n_splits * ring_rank;
   const bool ring_owner = ring_first < n_slices;
-  const int slot0 = (int)(nq % W);
-  const __half *kwin = L.k_win + head * W * kD;
-  const __half *vwin = L.v_win + head * W * kD;
+  const int slot0 = (int)((T - n_win) % W);  // ring row of the window's oldest token
+  const __half *kwin = L.k_win + head * (W + L.S) * kD;
+  const __half *vwin = L.v_win + head * (W + L.S) * kD;
   auto ring_slot = [&](int t) {  // ring slot of ring token t (clamped to the last one)
-    if (t >= n_win) t = n_win - 1;
-    int s = slot0 + t;
+    if (t >= n_fp) t = n_fp - 1;
+    if (t < n_sink) return W + t;
+    int s = slot0 + t - n_sink;
     return s >= W ? s - W : s;
   };
   auto load_ring = [&](int slice) {
@@ -359,7 +364,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     for (int r = 0; r < R; ++r) rm[r] = -INFINITY, rl[r] = 0.f, ro[r][0] = ro[r][1] = 0.f;
     auto ring_slice = [&](const RingData &rd, const int slice) {
       const int tk = lane >> 4, pc = lane & 15;  // token of the slice, 8-channel piece of its row
-      const bool valid = slice * kRingSlice + tk < n_win;
+      const bool valid = slice * kRingSlice + tk < n_fp;
       const half8_t x = __builtin_bit_cast(half8_t, rd.k);
       float p[R][kRingSlice];  // the four tokens' weights, wave-uniform
 #pragma unroll
@@ -663,14 +668,14 @@ extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
 
 bool decode_mfma_supported(const Layout &L) { return L.G == kD && (L.R == 1 || L.R == 2 || L.R == 4); }
 
-hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
-                              hipStream_t s) {
+hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
+                              int n_splits, hipStream_t s) {
   if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk, L.B), block(kThreads);
 #define SKVQ_LAUNCH(RR, TT) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT>), grid, block, 0, s, L, q, T, nq, n_splits)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits)
   const bool ter = L.v_levels == 3;
   switch (L.R) {
     case 1: if (ter) SKVQ_LAUNCH(1, true); else SKVQ_LAUNCH(1, false); break;

@@ -20,6 +20,7 @@ struct Layout {
   int B, Hq, Hk, R;      // R = Hq / Hk
   int G, NG;             // group size, groups per head
   int W;                 // window
+  int S;                 // attention sinks: tokens 0..S-1 are never quantized
   int v_levels;          // 4 or 3
   int v_block_bytes;     // 1024 or 832
   long long Tcap;        // packed rows per (b, hk)
@@ -27,11 +28,26 @@ struct Layout {
   float sm_scale;
   uint8_t *k_codes, *v_codes;
   float *k_meta, *v_meta;
-  __half *k_win, *v_win;
+  __half *k_win, *v_win;         // [B][Hk][W + S][D]: ring rows, then sink rows
   float *workspace;
   const int *perm_k, *perm_v;    // device copies [Hk][D]
   const float *clip_k, *clip_v;  // device copies [Hk][NG]
 };
+
+// Where the T cached tokens of a sequence live (Section 3.2 with the attention-sink rule): the
+// last n_win in the ring, of the older ones the first n_sink in sink rows, the other n_quant
+// packed (token a is packed row a - S).
+struct Counts {
+  long long n_win, n_sink, n_quant;
+};
+inline Counts counts_of(long long T, int W, int S) {
+  Counts c;
+  c.n_win = T < W ? T : W;
+  const long long old = T - c.n_win;
+  c.n_sink = old < S ? old : S;
+  c.n_quant = old - c.n_sink;
+  return c;
+}
 
 // quantize kernels (skvq_quantize.hip)
 hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T,
@@ -45,11 +61,12 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
                          long long T, int n_splits, hipStream_t s);
 
 // Matrix-core chunk kernel for the packed region (skvq_decode_mfma.hip): group size 128,
-// 1, 2 or 4 query heads per kv head.  Packed chunks and the fp16 ring; writes partials
+// 1, 2 or 4 query heads per kv head.  Packed chunks and the fp16 tokens (n_sink sink rows, then
+// the window's T - nq - n_sink ring tokens); writes partials
 // 0..n_splits-1 (n_splits >= 1 even when nothing is packed yet).
 bool decode_mfma_supported(const Layout &L);
-hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_splits,
-                              hipStream_t s);
+hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
+                              int n_splits, hipStream_t s);
 constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel
 
 }  // namespace skvq

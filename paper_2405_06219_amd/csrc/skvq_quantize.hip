@@ -152,10 +152,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   const long long blk = blockIdx.x;
   const long long t0 = blk * kVBlock + 8 * wave;
 
-  // Source rows; rows past the end of the prompt are replaced by its last row and never stored.
+  // Source rows (packed row r is token r + S); rows past the end of the prompt are replaced by
+  // its last row and never stored.
   {
     const int lr = lane >> 4, lp = lane & 15;
-    long long ta = t0 + lr, tb = t0 + 4 + lr;
+    long long ta = t0 + L.S + lr, tb = t0 + L.S + 4 + lr;
     ta = ta < T ? ta : T - 1;
     tb = tb < T ? tb : T - 1;
     const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + head * T * kD);
@@ -239,13 +240,16 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   }
 }
 
-// Copies the last n_win tokens of the prompt into the fp16 ring, token a -> slot a % W.
+// Copies the tokens of the prompt that stay fp16: the last n_win into the ring (token a -> row
+// a % W) and the first n_sink into the sink rows (token a -> row W + a).
 __global__ __launch_bounds__(64) void ring_fill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
-                                                      long long first) {
-  const long long a = first + blockIdx.x;
+                                                      long long first_win, int n_win) {
+  const bool sink = (int)blockIdx.x >= n_win;
+  const long long a = sink ? (long long)blockIdx.x - n_win : first_win + blockIdx.x;
+  const long long row = sink ? L.W + a : a % L.W;
   const long long head = (long long)blockIdx.z * L.Hk + blockIdx.y;
-  const long long src = (head * T + a) * kD, dst = (head * L.W + a % L.W) * kD;
+  const long long src = (head * T + a) * kD, dst = (head * (L.W + L.S) + row) * kD;
   const int lane = threadIdx.x;
   reinterpret_cast<__half2 *>(L.k_win + dst)[lane] = reinterpret_cast<const __half2 *>(ksrc + src)[lane];
   reinterpret_cast<__half2 *>(L.v_win + dst)[lane] = reinterpret_cast<const __half2 *>(vsrc + src)[lane];
@@ -253,7 +257,8 @@ __global__ __launch_bounds__(64) void ring_fill_kernel(Layout L, const __half *_
 
 // ---------------------------------------------------------------------------------------
 // Append: one workgroup of two wavefronts per (b, hk); wavefront 0 does K, wavefront 1 does V.
-// If the ring is full the slot's old token (number te = T - W) is quantized into row te first.
+// If the ring is full the slot's old token (number T - W) leaves the window first: a sink token
+// is copied to its sink row, any other is quantized into packed row te = T - W - S.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__restrict__ knew,
                                                      const __half *__restrict__ vnew, long long T) {
@@ -263,9 +268,9 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int hk = blockIdx.x, b = blockIdx.y;
   const long long head = (long long)b * L.Hk + hk;
-  const long long slot = (head * L.W + T % L.W) * kD;
-  const bool evict = T >= L.W;
-  const long long te = T - L.W;
+  const long long slot = (head * (L.W + L.S) + T % L.W) * kD;
+  const bool leaves = T >= L.W, evict = T - L.W >= L.S;  // a token leaves the window; it is packed
+  const long long te = T - L.W - L.S;
   __half *ring = wave ? L.v_win : L.k_win;
   const __half *fresh = (wave ? vnew : knew) + head * kD;
 
@@ -283,8 +288,8 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   uint8_t old_unit[13];    // 3-level V: unit j (lane = j < 16)
 #pragma unroll
   for (int q = 0; q < 13; ++q) old_unit[q] = 0;
+  if (leaves) old2 = reinterpret_cast<const __half2 *>(ring + slot)[lane];
   if (evict) {
-    old2 = reinterpret_cast<const __half2 *>(ring + slot)[lane];
     const int2 pp = reinterpret_cast<const int2 *>((wave ? L.perm_v : L.perm_k) + hk * kD)[lane];
     p0 = pp.x, p1 = pp.y;
     alpha = (wave ? L.clip_v : L.clip_k)[hk * L.NG + grp];
@@ -300,6 +305,8 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   }
   // the old token is in registers; the new one may take its slot
   reinterpret_cast<__half2 *>(ring + slot)[lane] = fresh2;
+  if (leaves && !evict)  // an attention sink: kept as it is
+    reinterpret_cast<__half2 *>(ring + (head * (L.W + L.S) + L.W + (T - L.W)) * kD)[lane] = old2;
   if (!evict) return;
   reinterpret_cast<__half2 *>(rows[wave])[lane] = old2;
   __syncthreads();
@@ -361,17 +368,19 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
 }  // namespace
 
 hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T, hipStream_t s) {
-  const long long nq = T > L.W ? T - L.W : 0;
-  if (nq > 0) {
-    const long long nblk = (nq + kVBlock - 1) / kVBlock;
+  const Counts n = counts_of(T, L.W, L.S);
+  if (n.n_quant > 0) {
+    const long long nblk = (n.n_quant + kVBlock - 1) / kVBlock;
     if (nblk > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)nblk, L.Hk, L.B), dim3(256), 0, s, L, k, v, T, nq);
+    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)nblk, L.Hk, L.B), dim3(256), 0, s, L, k, v, T, n.n_quant);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const long long nw = T - nq;
-  if (nw > 0) {
-    hipLaunchKernelGGL(ring_fill_kernel, dim3((unsigned)nw, L.Hk, L.B), dim3(64), 0, s, L, k, v, T, nq);
+  const long long n_fp = n.n_win + n.n_sink;
+  if (n_fp > 0) {
+    if (L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(ring_fill_kernel, dim3((unsigned)n_fp, L.Hk, L.B), dim3(64), 0, s, L, k, v, T, T - n.n_win,
+                       (int)n.n_win);
     return hipGetLastError();
   }
   return hipSuccess;

@@ -54,14 +54,14 @@ def cfg_for(B, **kw):
 
 
 def test_sizes_agree_with_the_oracle(B, oracle):
-    for hk, hq, g, vb, tcap, w, b in [(8, 32, 128, 1.5, 4096, 128, 1), (4, 4, 32, 2.0, 1000, 16, 3),
-                                      (2, 16, 64, 1.5, 33, 7, 2)]:
+    for hk, hq, g, vb, tcap, w, b, sink in [(8, 32, 128, 1.5, 4096, 128, 1, 0), (4, 4, 32, 2.0, 1000, 16, 3, 5),
+                                            (2, 16, 64, 1.5, 33, 7, 2, 1)]:
         cfg, keep = cfg_for(B, batch=b, n_q_heads=hq, n_kv_heads=hk, group_size=g, v_bits=vb, window=w,
-                            max_quant_tokens=tcap)
+                            max_quant_tokens=tcap, n_sink=sink)
         sizes = B.skvq_sizes(cfg)
         perm = np.tile(np.arange(D, dtype=np.int32), (hk, 1))
         clip = np.ones((hk, D // g), np.float32)
-        oc = oracle.OracleCache(b, hq, hk, g, vb, w, tcap, perm, perm, clip, clip)
+        oc = oracle.OracleCache(b, hq, hk, g, vb, w, tcap, perm, perm, clip, clip, n_sink=sink)
         assert sizes[:6] == oc.sizes
         assert sizes[6] == b * hq * (B.SKVQ_MAX_SPLITS + 1) * (D + 4) * 4
 
@@ -78,6 +78,7 @@ def test_validation_rejects_bad_configs(B):
         (dict(clip=np.full((8, 1), np.nan, np.float32)), B.SKVQ_ERR_INVALID_ARG),
         (dict(n_q_heads=30), B.SKVQ_ERR_INVALID_ARG),
         (dict(window=0), B.SKVQ_ERR_INVALID_ARG),
+        (dict(n_sink=-1), B.SKVQ_ERR_INVALID_ARG),
         (dict(max_quant_tokens=0), B.SKVQ_ERR_INVALID_ARG),
         (dict(batch=0), B.SKVQ_ERR_INVALID_ARG),
         (dict(head_dim=64), B.SKVQ_ERR_UNSUPPORTED),

@@ -257,3 +257,55 @@ def test_full_size_sampled_heads(P, name, n_heads):
         P.log(f"{name} head ({b},{hk}): buffers bit-exact, max abs err {err:.3e} (ref max {np.abs(o_ref).max():.3f})")
     del k, v
     assert worst <= P.TOL
+
+
+# ---- attention sinks (the filter rule of Section 3.2 / Algorithm 1): the first S tokens stay fp16 ----
+
+SINK_CASES = [
+    (small("sink5_gqa4_t15", n_q_heads=16, n_kv_heads=4, context=1333, batch=2), 5),
+    (small("sink5_mha_v2", v_bits=2.0, context=900), 5),
+    (small("sink3_gqa2_g64", n_q_heads=4, n_kv_heads=2, group_size=64, context=611), 3),
+    (small("sink1_w16_g32", n_q_heads=8, n_kv_heads=1, group_size=32, v_bits=2.0, context=450, window=16), 1),
+    (small("sink_larger_than_old_part", context=140), 40),
+    (small("sink_window_only", context=77), 5),
+    (small("sink130_gqa4", n_q_heads=8, n_kv_heads=2, context=700), 130),
+]
+
+
+@pytest.mark.parametrize("w,S", SINK_CASES, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_sinks_prefill_bit_exact_and_decode_matches_oracle(P, w, S):
+    print("case", w, S, flush=True)
+    pair, k, v, q = P.make_pair(w, extra_tokens=8, n_sink=S)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
+    assert pair.gpu.skvq_get_state()[1] == max(w.context - w.window - S, 0)
+    out, ref = pair.decode_both(q)
+    err = np.abs(out - ref).max()
+    P.log(f"decode {w.name} S={S}: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
+    assert err <= P.TOL
+
+
+@pytest.mark.parametrize("T0", [0, 5, 130, 133, 200])
+def test_sinks_appends_walk_ring_then_sink_rows_then_packed_rows(P, T0):
+    """Appends from T0 tokens on: tokens leave the window into the sink rows (the first five) and
+    into packed rows (the others); buffers stay bit-exact and attention matches at every stage."""
+    S, n = 5, 150
+    w = small("sink_append", n_q_heads=8, n_kv_heads=2, context=T0)
+    pair, k, v, q = P.make_pair(w, extra_tokens=n + 128, n_sink=S)
+    if T0:
+        pair.prefill(k, v)
+    for s in range(n):
+        pair.append(*synth.make_new_token(w, s))
+        if s in (0, 1, 2, 3, 4, 5, 6, 127, 128, 129, 132, 133, 134, n - 1):
+            pair.assert_buffers_equal()
+            out, ref = pair.decode_both(q)
+            assert np.abs(out - ref).max() <= P.TOL, s
+    # capacity counts packed rows only
+    tight = P.Pair(w, 3, *synth.make_permutations(w, *synth.make_kv(w, n_tokens=64)), *synth.make_clip(w), n_sink=S)
+    x = torch.zeros((1, 2, D), dtype=torch.float16, device="cuda")
+    for _ in range(128 + S + 3):
+        tight.gpu.skvq_quantize_append(x, x)
+    with pytest.raises(P.B.SkvqError) as e:
+        tight.gpu.skvq_quantize_append(x, x)
+    assert e.value.status == P.B.SKVQ_ERR_CAPACITY
+    torch.cuda.synchronize()
