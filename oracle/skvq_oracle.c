@@ -21,7 +21,7 @@
  *  A block is zero-filled when its first token arrives, so slots of tokens
  *  that do not exist yet read as code 0.
  *
- *  Meta: (scale, zero) fp32 pairs, [token][group].
+ *  Meta: (scale, zero) pairs, [token][group], as fp32, fp16 or FP8 E4M3.
  */
 #include "skvq_oracle.h"
 
@@ -69,9 +69,67 @@ uint16_t skvq_ref_float_to_half(float f) {
   return sign | (uint16_t)(be << 10) | (uint16_t)((int)r - 1024);
 }
 
+/* ----------------------------------------------------------- FP8 E4M3 --- */
+
+float skvq_ref_e4m3_to_float(uint8_t b) {
+  int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0)
+    v = ldexp((double)m, -9); /* subnormal: m/8 * 2^-6 */
+  else
+    v = ldexp((double)(8 + m), e - 10); /* (1 + m/8) * 2^(e-7) */
+  return (float)(sign ? -v : v);
+}
+
+uint8_t skvq_ref_float_to_e4m3(float f) {
+  if (isnan(f)) return 0x7f;
+  uint8_t sign = signbit(f) ? 0x80 : 0;
+  double a = fabs((double)f);
+  if (a >= 448.0) return sign | 0x7e; /* saturate at the largest finite value */
+  if (a < ldexp(1.0, -6)) {           /* subnormal range: spacing 2^-9 */
+    double r = nearbyint(ldexp(a, 9)); /* ties to even; r == 8 lands on the first normal */
+    return sign | (uint8_t)r;
+  }
+  int e;
+  double fr = frexp(a, &e);            /* a = fr * 2^e, fr in [0.5, 1) */
+  double r = nearbyint(ldexp(fr, 4));  /* 4 significant bits, in [8, 16] */
+  if (r == 16.0) {
+    r = 8.0;
+    e += 1;
+  }
+  int be = e - 1 + 7;
+  uint8_t out = (uint8_t)((be << 3) | ((int)r - 8));
+  if (out > 0x7e) out = 0x7e; /* rounding up from just below 448 stays at 448 */
+  return sign | out;
+}
+
+float skvq_ref_round_meta(float x, int fmt) {
+  if (fmt == 1) return skvq_ref_half_to_float(skvq_ref_float_to_half(x));
+  if (fmt == 2) return skvq_ref_e4m3_to_float(skvq_ref_float_to_e4m3(x));
+  return x;
+}
+
+static size_t meta_bytes(int fmt) { return fmt == 2 ? 1 : fmt == 1 ? 2 : 4; }
+
+static void meta_store(void *base, size_t idx, float x, int fmt) {
+  if (fmt == 2)
+    ((uint8_t *)base)[idx] = skvq_ref_float_to_e4m3(x);
+  else if (fmt == 1)
+    ((uint16_t *)base)[idx] = skvq_ref_float_to_half(x);
+  else
+    ((float *)base)[idx] = x;
+}
+
+static float meta_load(const void *base, size_t idx, int fmt) {
+  if (fmt == 2) return skvq_ref_e4m3_to_float(((const uint8_t *)base)[idx]);
+  if (fmt == 1) return skvq_ref_half_to_float(((const uint16_t *)base)[idx]);
+  return ((const float *)base)[idx];
+}
+
 /* ------------------------------------------------------------- encoder --- */
 
-void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels,
+void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels, int meta_format,
                            uint8_t *codes, float *scale, float *zero) {
   float mn = xp[0], mx = xp[0];
   for (int p = 1; p < n; ++p) {
@@ -84,6 +142,9 @@ void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels,
   float lo = alpha * mn;
   float hi = alpha * mx;
   float h = (hi - lo) / top;
+  /* the values decoding will read back: the codes are computed with these */
+  h = skvq_ref_round_meta(h, meta_format);
+  lo = skvq_ref_round_meta(lo, meta_format);
   float inv = h > 0.0f ? 1.0f / h : 0.0f;
   for (int p = 0; p < n; ++p) {
     float t = (xp[p] - lo) * inv;
@@ -110,7 +171,7 @@ void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
   size_t ng = (size_t)(c->head_dim / c->group_size);
   bytes[0] = heads * tcap * (D / 4);
   bytes[1] = heads * ((tcap + VBT - 1) / VBT) * v_block_bytes(c->v_levels);
-  bytes[2] = heads * tcap * ng * 2 * sizeof(float);
+  bytes[2] = heads * tcap * ng * 2 * meta_bytes(c->meta_format);
   bytes[3] = bytes[2];
   bytes[4] = heads * (size_t)(c->window + c->n_sink) * D * 2;
   bytes[5] = bytes[4];
@@ -172,12 +233,12 @@ void skvq_ref_v_put(uint8_t *block, int levels, int s, int p, int code) {
  * Gathers through perm (out[p] = in[perm[p]]), encodes each group, returns
  * codes[D] in reordered order and meta[D/G][2]. */
 static void encode_token(const uint16_t *x, const int32_t *perm, const float *alpha, int G,
-                         int levels, uint8_t *codes, float *meta) {
+                         int levels, int meta_format, uint8_t *codes, float *meta) {
   float xp[D];
   for (int p = 0; p < D; ++p) xp[p] = skvq_ref_half_to_float(x[perm[p]]);
   for (int g = 0; g < D / G; ++g)
-    skvq_ref_encode_group(xp + g * G, G, alpha[g], levels, codes + g * G, &meta[2 * g],
-                          &meta[2 * g + 1]);
+    skvq_ref_encode_group(xp + g * G, G, alpha[g], levels, meta_format, codes + g * G,
+                          &meta[2 * g], &meta[2 * g + 1]);
 }
 
 /* Quantize token (b, hk) and store it as packed row t. */
@@ -189,25 +250,28 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
   uint8_t codes[D];
   float meta[2 * D];
 
-  encode_token(kx, c->perm_k + hk * D, c->clip_k + hk * ng, G, c->k_levels, codes, meta);
+  int fmt = c->meta_format;
+  encode_token(kx, c->perm_k + hk * D, c->clip_k + hk * ng, G, c->k_levels, fmt, codes, meta);
   uint8_t *krow = buf->k_codes + (head * tcap + (size_t)t) * (D / 4);
   memset(krow, 0, D / 4);
   for (int p = 0; p < D; ++p) skvq_ref_k_put(krow, p, codes[p]);
-  memcpy(buf->k_meta + (head * tcap + (size_t)t) * ng * 2, meta, sizeof(float) * 2 * ng);
+  for (int x = 0; x < 2 * ng; ++x)
+    meta_store(buf->k_meta, (head * tcap + (size_t)t) * ng * 2 + x, meta[x], fmt);
 
-  encode_token(vx, c->perm_v + hk * D, c->clip_v + hk * ng, G, c->v_levels, codes, meta);
+  encode_token(vx, c->perm_v + hk * D, c->clip_v + hk * ng, G, c->v_levels, fmt, codes, meta);
   size_t nblk = (tcap + VBT - 1) / VBT, bb = v_block_bytes(c->v_levels);
   uint8_t *blk = buf->v_codes + (head * nblk + (size_t)(t / VBT)) * bb;
   if (t % VBT == 0) memset(blk, 0, bb);
   for (int p = 0; p < D; ++p) skvq_ref_v_put(blk, c->v_levels, (int)(t % VBT), p, codes[p]);
-  memcpy(buf->v_meta + (head * tcap + (size_t)t) * ng * 2, meta, sizeof(float) * 2 * ng);
+  for (int x = 0; x < 2 * ng; ++x)
+    meta_store(buf->v_meta, (head * tcap + (size_t)t) * ng * 2 + x, meta[x], fmt);
 }
 
 static int check_config(const skvq_ref_config *c) {
   if (c->head_dim != D || c->group_size <= 0 || D % c->group_size) return -1;
   if (c->k_levels != 4 || (c->v_levels != 4 && c->v_levels != 3)) return -2;
   if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1 ||
-      c->n_sink < 0)
+      c->n_sink < 0 || c->meta_format < 0 || c->meta_format > 2)
     return -1;
   return 0;
 }
@@ -306,11 +370,12 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
     for (int64_t a = n_sink; a < first_win; ++a) {
       size_t t = (size_t)(a - S);
       const uint8_t *row = buf->k_codes + (head * tcap + t) * (D / 4);
-      const float *meta = buf->k_meta + (head * tcap + t) * ng * 2;
+      size_t mi = (head * tcap + t) * ng * 2;
       double dot = 0.0;
       for (int p = 0; p < D; ++p) {
-        double kd = (double)skvq_ref_k_get(row, p) * (double)meta[2 * (p / G)] +
-                    (double)meta[2 * (p / G) + 1];
+        double kd = (double)skvq_ref_k_get(row, p) *
+                        (double)meta_load(buf->k_meta, mi + 2 * (p / G), c->meta_format) +
+                    (double)meta_load(buf->k_meta, mi + 2 * (p / G) + 1, c->meta_format);
         dot += qf[pk[p]] * kd;
       }
       s[a] = (double)c->sm_scale * dot;
@@ -333,11 +398,11 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       denom += w;
       size_t t = (size_t)(a - S);
       const uint8_t *blk = buf->v_codes + (head * nblk + t / VBT) * bb;
-      const float *meta = buf->v_meta + (head * tcap + t) * ng * 2;
+      size_t mi = (head * tcap + t) * ng * 2;
       for (int p = 0; p < D; ++p) {
         double vd = (double)skvq_ref_v_get(blk, c->v_levels, (int)(t % VBT), p) *
-                        (double)meta[2 * (p / G)] +
-                    (double)meta[2 * (p / G) + 1];
+                        (double)meta_load(buf->v_meta, mi + 2 * (p / G), c->meta_format) +
+                    (double)meta_load(buf->v_meta, mi + 2 * (p / G) + 1, c->meta_format);
         acc[pv[p]] += w * vd;
       }
     }

@@ -42,6 +42,8 @@ typedef struct {
   int32_t window;                                 /* W >= 1                    */
   int32_t n_sink;                                 /* S >= 0: tokens 0..S-1 are
                                                      never quantized           */
+  int32_t meta_format;                            /* storage of (scale, zero):
+                                                     0 fp32, 1 fp16, 2 FP8 E4M3 */
   int64_t max_quant_tokens;                       /* rows in the packed region */
   const int32_t *perm_k, *perm_v;                 /* [Hk][D] gather index      */
   const float *clip_k, *clip_v;                   /* [Hk][D/G] alpha           */
@@ -51,8 +53,8 @@ typedef struct {
 typedef struct {
   uint8_t *k_codes;  /* [B][Hk][Tcap][32]                                      */
   uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][1024 or 832]                    */
-  float *k_meta;     /* [B][Hk][Tcap][D/G][2] = (scale, zero)                  */
-  float *v_meta;     /* same                                                   */
+  void *k_meta;      /* [B][Hk][Tcap][D/G][2] = (scale, zero), 4, 2 or 1 byte  */
+  void *v_meta;      /* each (meta_format)                                     */
   uint16_t *k_win;   /* fp16 bits [B][Hk][W+S][D]: rows 0..W-1 are the ring    */
   uint16_t *v_win;   /* (token a in slot a % W), row W+a keeps sink token a    */
 } skvq_ref_buffers;
@@ -61,15 +63,26 @@ typedef struct {
 float skvq_ref_half_to_float(uint16_t h);
 uint16_t skvq_ref_float_to_half(float f);
 
+/* FP8 E4M3 (the 8-bit format Section 4.1 stores scale and zero in: 1 sign, 4
+ * exponent bits with bias 7, 3 mantissa bits, no infinities, largest finite
+ * value 448, 0x7f/0xff = NaN).  Narrowing rounds to nearest, ties to even, and
+ * saturates at +-448. */
+uint8_t skvq_ref_float_to_e4m3(float f);
+float skvq_ref_e4m3_to_float(uint8_t b);
+
+/* A (scale, zero) value as it reads back from storage in the given format. */
+float skvq_ref_round_meta(float x, int meta_format);
+
 /* Eq. 2 for one group of n already-reordered values: codes[n], scale, zero.
  * levels = 2^N (or 3).  Every fp32 operation is a separately rounded IEEE
  * operation, in this order:
  *   mn, mx = min, max (a zero of either sign becomes +0)
- *   lo = alpha*mn ; hi = alpha*mx ; scale = (hi-lo)/(levels-1)
+ *   lo = alpha*mn ; hi = alpha*mx ; h = (hi-lo)/(levels-1)
+ *   scale = stored(h) ; zero = stored(lo)      (identity for fp32 storage:
+ *           the codes are computed with the values that decoding will read)
  *   inv = scale > 0 ? 1/scale : 0
- *   code = clamp(rint((x-lo)*inv), 0, levels-1)   (ties to even)
- *   zero = lo                                                                */
-void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels,
+ *   code = clamp(rint((x-zero)*inv), 0, levels-1)   (ties to even)           */
+void skvq_ref_encode_group(const float *xp, int n, float alpha, int levels, int meta_format,
                            uint8_t *codes, float *scale, float *zero);
 
 /* Storage accounting in the paper's style: average bits per cached element

@@ -34,7 +34,7 @@ class _Config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("group_size", C.c_int32), ("k_levels", C.c_int32),
                 ("v_levels", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
-                ("max_quant_tokens", C.c_int64),
+                ("meta_format", C.c_int32), ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
                 ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
 
@@ -57,8 +57,14 @@ def lib():
         _lib.skvq_ref_avg_bits.restype = C.c_double
         _lib.skvq_ref_avg_bits.argtypes = [C.c_double, C.c_int, C.c_int]
         _lib.skvq_ref_encode_group.restype = None
-        _lib.skvq_ref_encode_group.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int,
+        _lib.skvq_ref_encode_group.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_int,
                                                C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_float_to_e4m3.restype = C.c_uint8
+        _lib.skvq_ref_float_to_e4m3.argtypes = [C.c_float]
+        _lib.skvq_ref_e4m3_to_float.restype = C.c_float
+        _lib.skvq_ref_e4m3_to_float.argtypes = [C.c_uint8]
+        _lib.skvq_ref_round_meta.restype = C.c_float
+        _lib.skvq_ref_round_meta.argtypes = [C.c_float, C.c_int]
         _lib.skvq_ref_k_get.argtypes = [C.c_void_p, C.c_int]
         _lib.skvq_ref_k_put.argtypes = [C.c_void_p, C.c_int, C.c_int]
         _lib.skvq_ref_k_put.restype = None
@@ -92,14 +98,30 @@ def avg_bits(code_bits: float, meta_bits: int, group_size: int) -> float:
     return float(lib().skvq_ref_avg_bits(code_bits, meta_bits, group_size))
 
 
-def encode_group(xp: np.ndarray, alpha: float, levels: int):
+META_FORMATS = {"f32": 0, "f16": 1, "e4m3": 2}
+META_DTYPES = {0: np.float32, 1: np.float16, 2: np.uint8}
+
+
+def float_to_e4m3(x: float) -> int:
+    return int(lib().skvq_ref_float_to_e4m3(float(x)))
+
+
+def e4m3_to_float(b: int) -> float:
+    return float(lib().skvq_ref_e4m3_to_float(int(b)))
+
+
+def round_meta(x: float, meta: str) -> float:
+    return float(lib().skvq_ref_round_meta(float(x), META_FORMATS[meta]))
+
+
+def encode_group(xp: np.ndarray, alpha: float, levels: int, meta: str = "f32"):
     """Eq. 2 on one group of already reordered float32 values."""
     xp = np.ascontiguousarray(xp, dtype=np.float32)
     codes = np.zeros(xp.size, np.uint8)
     scale = np.zeros(1, np.float32)
     zero = np.zeros(1, np.float32)
-    lib().skvq_ref_encode_group(_ptr(xp), xp.size, float(alpha), int(levels), _ptr(codes),
-                                _ptr(scale), _ptr(zero))
+    lib().skvq_ref_encode_group(_ptr(xp), xp.size, float(alpha), int(levels), META_FORMATS[meta],
+                                _ptr(codes), _ptr(scale), _ptr(zero))
     return codes, scale[0], zero[0]
 
 
@@ -111,7 +133,8 @@ class OracleCache:
     """Host-side mixed-precision cache of one attention layer, driven by the oracle."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens,
-                 perm_k, perm_v, clip_k, clip_v, sm_scale=None, k_bits=2.0, fill=0, n_sink=0):
+                 perm_k, perm_v, clip_k, clip_v, sm_scale=None, k_bits=2.0, fill=0, n_sink=0,
+                 meta="f32"):
         self.perm_k = np.ascontiguousarray(perm_k, np.int32)
         self.perm_v = np.ascontiguousarray(perm_v, np.int32)
         self.clip_k = np.ascontiguousarray(clip_k, np.float32)
@@ -119,7 +142,8 @@ class OracleCache:
         if sm_scale is None:
             sm_scale = 1.0 / np.sqrt(HEAD_DIM)
         self.cfg = _Config(batch, n_q_heads, n_kv_heads, HEAD_DIM, group_size, levels_of(k_bits),
-                           levels_of(v_bits), window, n_sink, max_quant_tokens, _ptr(self.perm_k),
+                           levels_of(v_bits), window, n_sink, META_FORMATS[meta], max_quant_tokens,
+                           _ptr(self.perm_k),
                            _ptr(self.perm_v), _ptr(self.clip_k), _ptr(self.clip_v), sm_scale)
         sizes = (C.c_size_t * 6)()
         lib().skvq_ref_sizes(C.byref(self.cfg), sizes)
@@ -130,8 +154,10 @@ class OracleCache:
         vb = 832 if levels_of(v_bits) == 3 else 1024
         self.k_codes = np.full((batch, n_kv_heads, max_quant_tokens, 32), fill, np.uint8)
         self.v_codes = np.full((batch, n_kv_heads, nblk, vb), fill, np.uint8)
-        self.k_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
-        self.v_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), np.float32)
+        mdt = META_DTYPES[META_FORMATS[meta]]   # fp8 values are kept as their bytes
+        self.meta = meta
+        self.k_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), mdt)
+        self.v_meta = np.zeros((batch, n_kv_heads, max_quant_tokens, ng, 2), mdt)
         self.k_win = np.zeros((batch, n_kv_heads, window + n_sink, HEAD_DIM), np.uint16)
         self.v_win = np.zeros((batch, n_kv_heads, window + n_sink, HEAD_DIM), np.uint16)
         for a in (self.k_meta, self.v_meta, self.k_win, self.v_win):

@@ -500,3 +500,137 @@ def test_prefill_then_appends_equals_one_longer_prefill_with_sinks(oracle):
     assert c.prefill(k[:, :, :W + S + 3], v[:, :, :W + S + 3]) == -3
     assert c.prefill(k[:, :, :W + S + 2], v[:, :, :W + S + 2]) == 0
     assert c.append(k[:, :, 0], v[:, :, 0]) == -3
+
+
+# --------------------------------------- compact (scale, zero): fp16 and FP8 E4M3 ----
+# Section 4.1 stores scale and zero in FP8 (E4M3); Table 2 / the breakdown paragraph of Section
+# 4.3 count 2 + 16*2/32 bits with fp16 metadata and 2 + 8*2/32 with FP8.
+
+def e4m3_value(b: int) -> float:
+    """The format's definition, written out independently of the oracle."""
+    s, e, m = b >> 7, (b >> 3) & 15, b & 7
+    if e == 15 and m == 7:
+        return float("nan")
+    v = m / 8 * 2.0 ** -6 if e == 0 else (1 + m / 8) * 2.0 ** (e - 7)
+    return -v if s else v
+
+
+def test_e4m3_decoding_all_bit_patterns(oracle):
+    want = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()  # library
+    for b in range(256):
+        got = oracle.e4m3_to_float(b)
+        if b & 0x7f == 0x7f:
+            assert np.isnan(got) and np.isnan(want[b])
+        else:
+            assert got == e4m3_value(b) == want[b], b
+    assert oracle.e4m3_to_float(0x7e) == 448.0 and oracle.e4m3_to_float(0x01) == 2.0 ** -9
+
+
+def test_e4m3_narrowing_is_nearest_even_and_saturates(oracle):
+    rng = np.random.default_rng(700)
+    finite = [(e4m3_value(b), b) for b in range(256) if b & 0x7f != 0x7f]
+    xs = np.concatenate([rng.standard_normal(3000) * 10 ** rng.uniform(-4, 2.6, 3000),
+                         [0.0, -0.0, 2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -9, 432.0, 447.9, 448.0, 0.0029296875],
+                         [(finite[i][0] + finite[i + 1][0]) / 2 for i in range(0, 120, 7)]]).astype(np.float32)
+    xs = xs[np.abs(xs) <= 448]
+    lib = torch.from_numpy(xs).to(torch.float8_e4m3fn).view(torch.uint8).numpy()       # library routine
+    for x, lb in zip(xs, lib):
+        got = oracle.float_to_e4m3(float(x))
+        # brute force: nearest finite value, ties to the even mantissa
+        best = min(finite, key=lambda vb: (abs(vb[0] - float(x)), vb[1] & 1))
+        assert oracle.e4m3_to_float(got) == best[0], (x, got, best)
+        assert got & 0x7f == lb & 0x7f, (x, got, lb)          # (the sign of a rounded-to-zero value aside)
+    for x, want in ((449.0, 0x7e), (1e9, 0x7e), (-500.0, 0xfe), (464.0, 0x7e)):
+        assert oracle.float_to_e4m3(x) == want
+    # reading back what was stored changes nothing
+    for meta in ("f16", "e4m3"):
+        for x in xs[:200]:
+            r = oracle.round_meta(float(x), meta)
+            assert oracle.round_meta(r, meta) == r
+    assert oracle.round_meta(0.1, "f32") == float(np.float32(0.1))
+    assert oracle.round_meta(0.1, "f16") == float(np.float16(0.1))
+
+
+@pytest.mark.parametrize("meta", ["f16", "e4m3"])
+@pytest.mark.parametrize("levels", [4, 3])
+def test_encoder_with_compact_meta_uses_the_stored_values(oracle, meta, levels):
+    """scale and zero come back exactly representable in the storage format, and every code is
+    the nearest level of the grid THOSE values span (so decoding, which only sees them, is
+    as close as it can be)."""
+    rng = np.random.default_rng(710 + levels)
+    top = levels - 1
+    for trial in range(200):
+        n = int(rng.choice([4, 32, 128]))
+        x = (rng.standard_normal(n) * 10 ** rng.uniform(-2, 1.5)).astype(np.float16).astype(np.float32)
+        alpha = float(rng.uniform(0.7, 1.0))
+        c, h, z = oracle.encode_group(x, alpha, levels, meta)
+        assert oracle.round_meta(h, meta) == h and oracle.round_meta(z, meta) == z
+        # they are the rounded values of the fp32 formula's
+        c32, h32, z32 = oracle.encode_group(x, alpha, levels, "f32")
+        assert h == oracle.round_meta(h32, meta) and z == oracle.round_meta(z32, meta)
+        if h == 0:
+            assert not c.any()
+            continue
+        t = (x.astype(np.float64) - float(z)) / float(h)
+        grid = np.arange(levels)
+        for ti, ci in zip(t, c):
+            d = np.abs(grid - ti)
+            assert d[ci] <= d.min() + 1e-5 * max(1.0, abs(ti)), (ti, ci)
+        inside = (t >= 0) & (t <= top)
+        deq = c * np.float64(h) + np.float64(z)
+        assert np.all(np.abs(deq - x)[inside] <= float(h) / 2 * (1 + 1e-5))
+
+
+def test_fp32_meta_is_unchanged_by_the_format_argument(oracle):
+    rng = np.random.default_rng(720)
+    for _ in range(50):
+        x = (rng.standard_normal(64) * 3).astype(np.float16).astype(np.float32)
+        a = oracle.encode_group(x, 0.9, 4)
+        b = oracle.encode_group(x, 0.9, 4, "f32")
+        assert np.array_equal(a[0], b[0]) and a[1] == b[1] and a[2] == b[2]
+
+
+def meta_as_float64(arr, meta):
+    if meta == "e4m3":
+        table = np.array([e4m3_value(b) for b in range(256)])
+        return table[arr]
+    return arr.astype(np.float64)
+
+
+@pytest.mark.parametrize("meta,v_bits,G", [("f16", 1.5, 128), ("e4m3", 1.5, 128), ("e4m3", 2.0, 32), ("f16", 2.0, 64)])
+def test_lossy_cache_with_compact_meta_equals_dequantize_then_textbook_attention(oracle, meta, v_bits, G):
+    rng = np.random.default_rng(730 + G)
+    B, Hq, Hk, W, T, S = 2, 4, 2, 8, 45, 2
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    ck = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    cv = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S, meta=meta)
+    assert c.prefill(k, v) == 0
+    # independent dequantization: the stored meta decoded from the format statement
+    class View:
+        pass
+    vw = View()
+    vw.k_codes, vw.v_codes, vw.window, vw.cfg, vw.perm_k, vw.perm_v = c.k_codes, c.v_codes, c.window, c.cfg, c.perm_k, c.perm_v
+    vw.k_meta, vw.v_meta = meta_as_float64(c.k_meta, meta), meta_as_float64(c.v_meta, meta)
+    kq, vq = numpy_dequantize(vw, T - S)
+    f64 = np.float64
+    kfull = np.concatenate([k[:, :, :S].astype(f64), kq, k[:, :, T - W:].astype(f64)], axis=2)
+    vfull = np.concatenate([v[:, :, :S].astype(f64), vq, v[:, :, T - W:].astype(f64)], axis=2)
+    ref = sdpa64(q, kfull, vfull, 1 / np.sqrt(D))
+    assert np.abs(c.decode(q) - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    # the stored bytes per packed token-head: Section 4.3's accounting with 16- / 8-bit metadata
+    es = {"f16": 2, "e4m3": 1}[meta]
+    assert c.k_meta.nbytes == B * Hk * 64 * (D // G) * 2 * es
+    assert (32 * 8 + (D // G) * 2 * es * 8) / D == oracle.avg_bits(2, 8 * es, G)
+    # appends agree with the longer prefill in these formats too
+    a = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S, meta=meta, fill=0xAB)
+    b = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S, meta=meta, fill=0xAB)
+    a.prefill(k[:, :, :20], v[:, :, :20])
+    for s in range(20, T):
+        a.append(k[:, :, s], v[:, :, s])
+    b.prefill(k, v)
+    for x, y in zip(a.arrays(), b.arrays()):
+        assert np.array_equal(x, y)
