@@ -33,20 +33,23 @@ D = 128
 MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 77983 * 1024}
 
 
-def algorithmic_bytes_decode(w, n_tokens: int, n_sink: int = 0) -> int:
+META_BYTES = {"f32": 4, "f16": 2, "e4m3": 1}
+
+
+def algorithmic_bytes_decode(w, n_tokens: int, n_sink: int = 0, meta: str = "f32") -> int:
     """Bytes one decode call must move: packed rows (K 32 B + V 26|32 B + two fp32
-    (scale, zero) pairs per group each), the fp16 ring and sink rows, the query and the fp32
-    output."""
+    (or fp16 / FP8) (scale, zero) pairs per group each), the fp16 ring and sink rows, the query
+    and the fp32 output."""
     nq = max(n_tokens - w.window - n_sink, 0)
     nwin = n_tokens - nq
     ng = D // w.group_size
     vrow = 26 if w.v_bits == 1.5 else 32
-    per_row = 32 + 8 * ng + vrow + 8 * ng
+    per_row = 32 + vrow + 2 * (2 * META_BYTES[meta] * ng)
     return (w.batch * w.n_kv_heads * (nq * per_row + nwin * 2 * D * 2)
             + w.batch * w.n_q_heads * D * (2 + 4))
 
 
-def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0):
+def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta: str = "f32"):
     """Per layer: a cache prefilled with w.context seeded synthetic tokens.  Returns the caches,
     the K/V channel scales on the device, and each prefill call's duration (HIP events, us)."""
     import torch
@@ -63,7 +66,8 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0):
         # seeded synthetic K/V and the reorder index from their channel ranges (offline calibration stand-in)
         k, v, pk, pv = synth.make_kv_device(w, device, stream=layer)
         c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
-                        w.context - w.window + headroom, pk, pv, ck, cv, device=device, n_sink=n_sink)
+                        w.context - w.window + headroom, pk, pv, ck, cv, device=device, n_sink=n_sink,
+                        meta=meta)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         c.skvq_prefill_quantize(k, v)
@@ -75,7 +79,7 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0):
     return caches, (sk_d, sv_d), prefill_us
 
 
-def cpu_baseline(w, n_sink: int = 0, seconds_budget: float = 25.0):
+def cpu_baseline(w, n_sink: int = 0, meta: str = "f32", seconds_budget: float = 25.0):
     """Times the CPU oracle (as it stands) on one layer of the same workload: its own prefill
     from host inputs (untimed), then one append + one decode (timed)."""
     from oracle import skvq_oracle as O
@@ -91,7 +95,7 @@ def cpu_baseline(w, n_sink: int = 0, seconds_budget: float = 25.0):
     pk, pv = synth.make_permutations(ws, k[:, :, :4096], v[:, :, :4096])
     ck, cv = synth.make_clip(ws)
     oc = O.OracleCache(ws.batch, ws.n_q_heads, ws.n_kv_heads, ws.group_size, ws.v_bits, ws.window,
-                       ctx - ws.window + 4, pk, pv, ck, cv, n_sink=n_sink)
+                       ctx - ws.window + 4, pk, pv, ck, cv, n_sink=n_sink, meta=meta)
     assert oc.prefill(k, v) == 0
     q = synth.make_query(ws)
     kn, vn = synth.make_new_token(ws, 0)
@@ -115,6 +119,8 @@ def main() -> int:
     ap.add_argument("--context", type=int, default=0, help="override the workload's context (tests)")
     ap.add_argument("--sink", type=int, default=0,
                     help="attention sinks: the first N tokens stay fp16 (the headline workload has none)")
+    ap.add_argument("--meta", choices=sorted(META_BYTES), default="f32",
+                    help="storage of (scale, zero); the headline workload keeps them in fp32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -137,7 +143,7 @@ def main() -> int:
     n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers
     headroom = n_warm + 2 * n_steps + 9
 
-    caches, (sk_d, sv_d), prefill_us = build_layers(w, n_layers, headroom, device, args.sink)
+    caches, (sk_d, sv_d), prefill_us = build_layers(w, n_layers, headroom, device, args.sink, args.meta)
     prefill_med_us = float(np.median(prefill_us))
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
@@ -187,7 +193,7 @@ def main() -> int:
     dec_us = np.array(dec_us)
     dec_avg_us = float(dec_us.mean())
     n_tokens_roof = w.context + n_warm + n_steps + n_steps // 2
-    alg_bytes = algorithmic_bytes_decode(w, n_tokens_roof, args.sink)
+    alg_bytes = algorithmic_bytes_decode(w, n_tokens_roof, args.sink, args.meta)
     achieved = alg_bytes / (dec_avg_us * 1e-6) / 1e9
 
     # append alone (launch-latency bound, reported for completeness)
@@ -213,7 +219,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "layers": n_layers, "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": D, "context": w.context, "k_bits": 2,
-                   "v_bits": w.v_bits, "group_size": w.group_size, "window": w.window, "n_sink": args.sink,
+                   "v_bits": w.v_bits, "group_size": w.group_size, "window": w.window, "n_sink": args.sink, "meta": args.meta,
                    "step": "per layer: skvq_quantize_append + skvq_decode_attention"},
         "us_per_layer": ms_per_step * 1e3 / n_layers,
         "decode_call_us": dec_avg_us,
@@ -222,19 +228,21 @@ def main() -> int:
         "prefill_call_us": prefill_med_us,
         "prefill_tokens_per_s": w.batch * w.context / (prefill_med_us * 1e-6),
         "prefill_hbm_gbps": (w.batch * w.n_kv_heads * (w.context * 2 * D * 2 + max(w.context - w.window, 0)
-                                                     * (74 if w.v_bits == 1.5 else 80))
+                                                     * ((58 if w.v_bits == 1.5 else 64)
+                                                        + 4 * META_BYTES[args.meta] * (D // w.group_size)))
                              / (prefill_med_us * 1e-6) / 1e9),
         "effective_hbm_gbps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES.get(w.name)
-                                 if w.context == synth.WORKLOADS[w.name].context and not args.sink else None),
+                                 if w.context == synth.WORKLOADS[w.name].context and not args.sink
+                                 and args.meta == "f32" else None),
                      "kernel": "skvq_decode_attention", "bytes_per_launch": alg_bytes,
                      "avg_launch_us": dec_avg_us},
     }
     if not args.no_cpu_baseline:
-        cb = cpu_baseline(w, args.sink)
+        cb = cpu_baseline(w, args.sink, args.meta)
         result["cpu_baseline"] = {
             "value": cb["per_layer_us"] * n_layers, "unit": "us/token", "cores": cb["threads"], "kind": "oracle",
             "sample": (f"1 of {n_layers} layers (append + decode) at context {cb['context_timed']}"

@@ -57,6 +57,14 @@ typedef enum {
   SKVQ_BITS_1P5 = 3 /* three levels, codes 0..2 (this build's reading of "1.5-bit") */
 } skvq_bits;
 
+/* Storage of (scale, zero): Section 4.1 keeps them in FP8 (E4M3); Section 4.3 also counts
+ * fp16.  The rounded values are the ones the codes are computed with. */
+typedef enum {
+  SKVQ_META_F32 = 0,
+  SKVQ_META_F16 = 1,
+  SKVQ_META_FP8_E4M3 = 2 /* bias 7, largest finite value 448, saturating */
+} skvq_meta_format;
+
 /* Parameters of Algorithm 1: window W, group size G; Prologue outputs P_k, P_v, clipping. */
 typedef struct {
   int32_t batch;        /* B >= 1; all sequences of a batch have the same length          */
@@ -69,6 +77,7 @@ typedef struct {
   int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
   int32_t n_sink;       /* S >= 0: the filter rule of Section 3.2 / Algorithm 1 that keeps
                            the first S tokens (attention sinks) fp16 for ever; 0 = off    */
+  int32_t meta_format;  /* skvq_meta_format                                              */
   int64_t max_quant_tokens; /* Tcap: rows of the packed region per sequence, >= 1         */
   const int32_t *perm_k; /* HOST [Hk][D]: reordered position p takes channel perm[h][p]   */
   const int32_t *perm_v; /* HOST [Hk][D]  (each row a permutation of 0..D-1)              */
@@ -84,8 +93,8 @@ typedef struct {
  *             2-bit  : unit = 16 B little-endian, code(n,i) at bit 32(n/2)+16(i%2)+8(n%2)+2(i/2)
  *             3-level: unit = 13 B little-endian, field n = bits [13n,13n+13) = sum_i code(n,i)*3^i
  *             a block is zero-filled when its first token is stored
- *   k_meta    f32 [B][Hk][Tcap][D/G][2]  (scale, zero) of Eq. 2, zero = alpha*min
- *   v_meta    f32 [B][Hk][Tcap][D/G][2]
+ *   k_meta    [B][Hk][Tcap][D/G][2]      (scale, zero) of Eq. 2, zero = alpha*min, each an
+ *   v_meta    [B][Hk][Tcap][D/G][2]      fp32, fp16 or FP8 E4M3 value (meta_format)
  *   k_win     f16 [B][Hk][W+S][D]        rows 0..W-1: the ring, token number a (0-based) sits
  *   v_win     f16 [B][Hk][W+S][D]        in slot a % W; row W+a: sink token a, once it has
  *                                        left the window
@@ -120,8 +129,9 @@ void skvq_destroy(skvq_cache *cache);
  * every token goes to its place as above.  Per (token, kv head, group g) of a packed row,
  * with xp[p] = x[perm[p]]:
  *   mn,mx = min,max xp (a zero of either sign counts as +0); lo = alpha_g*mn; hi = alpha_g*mx;
- *   scale = (hi-lo)/(levels-1); inv = scale>0 ? 1/scale : 0;
- *   code = clamp(rint((xp-lo)*inv), 0, levels-1), ties to even; zero = lo.
+ *   scale = stored((hi-lo)/(levels-1)); zero = stored(lo)   (round to nearest even into
+ *   meta_format, FP8 saturating at +-448; the identity for fp32); inv = scale>0 ? 1/scale : 0;
+ *   code = clamp(rint((xp-zero)*inv), 0, levels-1), ties to even.
  * SKVQ_ERR_CAPACITY if T-W-S > Tcap. */
 int skvq_prefill_quantize(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
                           void *hip_stream);

@@ -27,7 +27,7 @@ class skvq_config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("group_size", C.c_int32), ("k_bits", C.c_int32),
                 ("v_bits", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
-                ("max_quant_tokens", C.c_int64),
+                ("meta_format", C.c_int32), ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
                 ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
 
@@ -72,17 +72,21 @@ class SkvqError(RuntimeError):
         super().__init__(f"skvq status {status} ({text}) {detail}".strip())
 
 
+META_FORMATS = {"f32": 0, "f16": 1, "e4m3": 2}   # skvq_meta_format
+META_DTYPES = {0: np.float32, 1: np.float16, 2: np.uint8}
+
+
 def bits_enum(bits: float) -> int:
     return {2.0: SKVQ_BITS_2, 1.5: SKVQ_BITS_1P5}[float(bits)]
 
 
 def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
-                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM, n_sink=0):
+                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM, n_sink=0, meta="f32"):
     """Returns (skvq_config, keepalive): the numpy arrays the config points to."""
     keep = [np.ascontiguousarray(perm_k, np.int32), np.ascontiguousarray(perm_v, np.int32),
             np.ascontiguousarray(clip_k, np.float32), np.ascontiguousarray(clip_v, np.float32)]
     cfg = skvq_config(batch, n_q_heads, n_kv_heads, head_dim, group_size, bits_enum(k_bits), bits_enum(v_bits),
-                      window, n_sink, max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
+                      window, n_sink, META_FORMATS[meta], max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
                       keep[3].ctypes.data, float(sm_scale))
     return cfg, keep
 
@@ -116,10 +120,11 @@ class SkvqCache:
     """One layer's cache: owns the device buffers (torch tensors) and the library handle."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
-                 clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None, n_sink=0):
+                 clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None, n_sink=0,
+                 meta="f32"):
         self.cfg, self._keep = make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window,
                                            max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale, k_bits,
-                                           n_sink=n_sink)
+                                           n_sink=n_sink, meta=meta)
         self.shape = (batch, n_q_heads, n_kv_heads)
         self.device = torch.device(device)
         self.sizes = skvq_sizes(self.cfg)
@@ -200,7 +205,7 @@ class SkvqCache:
         raw = {n: self.buffers[n].cpu().numpy() for n in BUFFER_NAMES[:6]}
         return [raw["k_codes"].reshape(b, hk, tcap, 32),
                 raw["v_codes"].reshape(b, hk, (tcap + 31) // 32, vb),
-                raw["k_meta"].view(np.float32).reshape(b, hk, tcap, ng, 2),
-                raw["v_meta"].view(np.float32).reshape(b, hk, tcap, ng, 2),
+                raw["k_meta"].view(META_DTYPES[self.cfg.meta_format]).reshape(b, hk, tcap, ng, 2),
+                raw["v_meta"].view(META_DTYPES[self.cfg.meta_format]).reshape(b, hk, tcap, ng, 2),
                 raw["k_win"].view(np.uint16).reshape(b, hk, self.cfg.window + self.cfg.n_sink, HEAD_DIM),
                 raw["v_win"].view(np.uint16).reshape(b, hk, self.cfg.window + self.cfg.n_sink, HEAD_DIM)]

@@ -37,6 +37,9 @@ int check_config(const skvq_config *c) {
     return SKVQ_ERR_UNSUPPORTED;
   if (c->k_bits != SKVQ_BITS_2) return SKVQ_ERR_UNSUPPORTED;
   if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5) return SKVQ_ERR_UNSUPPORTED;
+  if (c->meta_format != SKVQ_META_F32 && c->meta_format != SKVQ_META_F16 &&
+      c->meta_format != SKVQ_META_FP8_E4M3)
+    return SKVQ_ERR_UNSUPPORTED;
   if (!(c->sm_scale >= 0.0f) || !std::isfinite(c->sm_scale)) return SKVQ_ERR_INVALID_ARG;
   if ((long long)c->window > (1ll << 20) || c->n_sink > (1 << 20) || c->max_quant_tokens > (1ll << 40))
     return SKVQ_ERR_INVALID_ARG;
@@ -68,7 +71,8 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
   const size_t vb = c->v_bits == SKVQ_BITS_1P5 ? kTernaryBlockBytes : kTwoBitBlockBytes;
   bytes[0] = heads * tcap * (kD / 4);
   bytes[1] = heads * ((tcap + kVBlock - 1) / kVBlock) * vb;
-  bytes[2] = heads * tcap * ng * 2 * sizeof(float);
+  const size_t es = c->meta_format == SKVQ_META_FP8_E4M3 ? 1 : c->meta_format == SKVQ_META_F16 ? 2 : 4;
+  bytes[2] = heads * tcap * ng * 2 * es;
   bytes[3] = bytes[2];
   bytes[4] = heads * ((size_t)c->window + (size_t)c->n_sink) * kD * sizeof(__half);
   bytes[5] = bytes[4];
@@ -152,6 +156,7 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.NG = kD / L.G;
   L.W = cfg->window;
   L.S = cfg->n_sink;
+  L.meta_fmt = cfg->meta_format;
   L.v_levels = cfg->v_bits == SKVQ_BITS_1P5 ? 3 : 4;
   L.v_block_bytes = L.v_levels == 3 ? kTernaryBlockBytes : kTwoBitBlockBytes;
   L.Tcap = cfg->max_quant_tokens;
@@ -160,8 +165,8 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   if (cfg->sm_scale == 0.0f) L.sm_scale = 1.0f / std::sqrt((float)kD);
   L.k_codes = (uint8_t *)bufs->k_codes;
   L.v_codes = (uint8_t *)bufs->v_codes;
-  L.k_meta = (float *)bufs->k_meta;
-  L.v_meta = (float *)bufs->v_meta;
+  L.k_meta = bufs->k_meta;
+  L.v_meta = bufs->v_meta;
   L.k_win = (__half *)bufs->k_win;
   L.v_win = (__half *)bufs->v_win;
   L.workspace = (float *)bufs->workspace;

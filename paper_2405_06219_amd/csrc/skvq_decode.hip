@@ -11,6 +11,7 @@
 #include <math.h>
 
 #include "skvq_internal.h"
+#include "skvq_meta.h"
 
 namespace skvq {
 
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
         }
       } else {
         const unsigned *row = reinterpret_cast<const unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4));
-        const float2 *meta = reinterpret_cast<const float2 *>(L.k_meta) + (head * L.Tcap + t) * NG;
+        const long long meta0 = (head * L.Tcap + t) * NG;
         for (int r = 0; r < R; ++r) s[r] = 0.f;
         for (int g = 0; g < NG; ++g) {
           float dot[kMaxR];
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
             const float code = (float)((row[p >> 4] >> (2 * (p & 15))) & 3u);
             for (int r = 0; r < R; ++r) dot[r] += qs[r][p] * code;
           }
-          const float2 mz = meta[g];
+          const float2 mz = meta_load_pair(L.k_meta, meta0 + g, L.meta_fmt);
           for (int r = 0; r < R; ++r) s[r] += mz.x * dot[r] + mz.y * qsum[r][g];
         }
       }
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(Layout L, const __h
         val = __half2float(L.v_win[(head * win_rows + fp_row(tt)) * kD + p_own]);
       } else {
         const uint8_t *blk = L.v_codes + (head * L.n_vblocks + tt / kVBlock) * L.v_block_bytes;
-        const float2 mz = reinterpret_cast<const float2 *>(L.v_meta)[(head * L.Tcap + tt) * NG + g_own];
+        const float2 mz = meta_load_pair(L.v_meta, (head * L.Tcap + tt) * NG + g_own, L.meta_fmt);
         val = (float)v_code(blk, L.v_levels, (int)(tt % kVBlock), p_own) * mz.x + mz.y;
       }
       for (int r = 0; r < R; ++r) acc[r] += pr[r][k] * val;

@@ -175,10 +175,33 @@ __device__ __forceinline__ float4_t qk_dword(unsigned w, half4_t a_lo, half4_t a
   return d;
 }
 
+// A stored (scale, zero) pair as one lane loads it, and its value.
+template <int META>
+struct MetaWord {
+  typedef float2 type;
+};
+template <>
+struct MetaWord<SKVQ_META_F16> {
+  typedef unsigned type;
+};
+template <>
+struct MetaWord<SKVQ_META_FP8_E4M3> {
+  typedef unsigned short type;
+};
+__device__ __forceinline__ float2 meta_value(float2 w) { return w; }
+__device__ __forceinline__ float2 meta_value(unsigned w) {
+  const __half2 h = __builtin_bit_cast(__half2, w);
+  return make_float2(__low2float(h), __high2float(h));
+}
+__device__ __forceinline__ float2 meta_value(unsigned short w) {  // FP8 E4M3: conversion is exact
+  return make_float2(__builtin_amdgcn_cvt_f32_fp8((int)w, 0), __builtin_amdgcn_cvt_f32_fp8((int)w, 1));
+}
+
 // What one wavefront loads for one tile of 64 tokens.
+template <int META>
 struct TileData {
-  uint4_t k0, k1;       // lane = token: its 32-byte key row
-  float2 kmeta, vmeta;  // lane = token: (scale, zero)
+  uint4_t k0, k1;                              // lane = token: its 32-byte key row
+  typename MetaWord<META>::type kmeta, vmeta;  // lane = token: (scale, zero)
   Unit16 v0, v1;        // lane = unit of V block 2*tile and 2*tile+1
 };
 
@@ -188,7 +211,7 @@ struct RingData {
   unsigned v[4];  // lane = channel pair: the 4 tokens' values of channels 2l, 2l+1
 };
 
-template <int R, bool TERNARY>
+template <int R, bool TERNARY, int META>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
                                                                   int n_splits) {
@@ -209,8 +232,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int tile_end = (int)(((long long)(sp + 1) * n_tiles) / n_splits);
 
   const uint8_t *kc = L.k_codes + head * L.Tcap * (kD / 4);
-  const float2 *km = reinterpret_cast<const float2 *>(L.k_meta) + head * L.Tcap;
-  const float2 *vm = reinterpret_cast<const float2 *>(L.v_meta) + head * L.Tcap;
+  typedef typename MetaWord<META>::type meta_word;
+  typedef TileData<META> Tile;
+  const meta_word *km = reinterpret_cast<const meta_word *>(L.k_meta) + head * L.Tcap;
+  const meta_word *vm = reinterpret_cast<const meta_word *>(L.v_meta) + head * L.Tcap;
   const uint8_t *vc = L.v_codes + head * L.n_vblocks * L.v_block_bytes;
   const int last_token = (int)(nq - 1);  // -1 when nothing is packed (then there are no tiles)
   const int last_blk = last_token >> 5;
@@ -229,7 +254,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int safe_last_token = last_token > 0 ? last_token : 0;
   const int safe_last_blk = last_blk > 0 ? last_blk : 0;
   auto load_tile = [&](int tile) {
-    TileData d;
+    Tile d;
     if (tile > safe_last_tile) tile = safe_last_tile;
     if (tile < 0) tile = 0;
     int t = tile * 64 + lane;
@@ -301,7 +326,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   };
   int n_a = 0, n_b = 1, n_c = 2;
   int tile_a = tile_of(n_a), tile_b = tile_of(n_b), tile_c = tile_of(n_c);
-  TileData buf_a, buf_b, buf_c;
+  Tile buf_a, buf_b, buf_c;
   buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
   if (TERNARY) {
     // While the loads are in flight the workgroup builds the table: entry f (a base-3 number of
@@ -447,8 +472,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 
   SKVQ_STAMP(1);
   SKVQ_WSTAMP(0);
-  auto compute_tile = [&](const TileData &cur, const int tile) {
+  auto compute_tile = [&](const Tile &cur, const int tile) {
     const bool valid = tile * 64 + lane <= last_token;
+    const float2 kmeta = meta_value(cur.kmeta), vmeta = meta_value(cur.vmeta);
 
     // ---- scores: 32 products of 4 channels each ----
     float4_t d0 = dinit;
@@ -461,16 +487,16 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     d0 = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, d0);
     d0 = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, d0);
     // u = log2-domain score minus the running reference
-    const float a_t = cur.kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
-    const float zc = fmaf(1.5f, cur.kmeta.x, cur.kmeta.y);  // dequantized value of the centre code 1.5
+    const float a_t = kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
+    const float zc = fmaf(1.5f, kmeta.x, kmeta.y);  // dequantized value of the centre code 1.5
     float u[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       u[r] = fmaf(d0[r], a_t, fmaf(zc, qsc[r], -mref[r]));
       if (!valid) u[r] = -INFINITY;
     }
-    const float vs = valid ? cur.vmeta.x : 0.f;
-    const float vz = valid ? cur.vmeta.y : 0.f;
+    const float vs = valid ? vmeta.x : 0.f;
+    const float vz = valid ? vmeta.y : 0.f;
     bool trig = vs * beta > kVsLimit;
 #pragma unroll
     for (int r = 0; r < R; ++r) trig |= u[r] > kRefSlack;
@@ -674,15 +700,23 @@ hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, lon
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk, L.B), block(kThreads);
-#define SKVQ_LAUNCH(RR, TT) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits)
+#define SKVQ_LAUNCH(RR, TT, MM) \
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT, MM>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits)
+#define SKVQ_LAUNCH_META(RR, TT)                                              \
+  switch (L.meta_fmt) {                                                       \
+    case SKVQ_META_F32: SKVQ_LAUNCH(RR, TT, SKVQ_META_F32); break;            \
+    case SKVQ_META_F16: SKVQ_LAUNCH(RR, TT, SKVQ_META_F16); break;            \
+    case SKVQ_META_FP8_E4M3: SKVQ_LAUNCH(RR, TT, SKVQ_META_FP8_E4M3); break;  \
+    default: return hipErrorInvalidValue;                                     \
+  }
   const bool ter = L.v_levels == 3;
   switch (L.R) {
-    case 1: if (ter) SKVQ_LAUNCH(1, true); else SKVQ_LAUNCH(1, false); break;
-    case 2: if (ter) SKVQ_LAUNCH(2, true); else SKVQ_LAUNCH(2, false); break;
-    case 4: if (ter) SKVQ_LAUNCH(4, true); else SKVQ_LAUNCH(4, false); break;
+    case 1: if (ter) { SKVQ_LAUNCH_META(1, true) } else { SKVQ_LAUNCH_META(1, false) } break;
+    case 2: if (ter) { SKVQ_LAUNCH_META(2, true) } else { SKVQ_LAUNCH_META(2, false) } break;
+    case 4: if (ter) { SKVQ_LAUNCH_META(4, true) } else { SKVQ_LAUNCH_META(4, false) } break;
     default: return hipErrorInvalidValue;
   }
+#undef SKVQ_LAUNCH_META
 #undef SKVQ_LAUNCH
   return hipGetLastError();
 }

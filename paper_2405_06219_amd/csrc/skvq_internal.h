@@ -21,13 +21,14 @@ struct Layout {
   int G, NG;             // group size, groups per head
   int W;                 // window
   int S;                 // attention sinks: tokens 0..S-1 are never quantized
+  int meta_fmt;          // skvq_meta_format of (scale, zero)
   int v_levels;          // 4 or 3
   int v_block_bytes;     // 1024 or 832
   long long Tcap;        // packed rows per (b, hk)
   long long n_vblocks;   // ceil(Tcap / 32)
   float sm_scale;
   uint8_t *k_codes, *v_codes;
-  float *k_meta, *v_meta;
+  void *k_meta, *v_meta;         // (scale, zero) pairs, 8, 4 or 2 bytes each
   __half *k_win, *v_win;         // [B][Hk][W + S][D]: ring rows, then sink rows
   float *workspace;
   const int *perm_k, *perm_v;    // device copies [Hk][D]

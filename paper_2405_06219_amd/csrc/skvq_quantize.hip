@@ -10,6 +10,7 @@
 #include <hip/hip_fp16.h>
 
 #include "skvq_internal.h"
+#include "skvq_meta.h"
 
 namespace skvq {
 namespace {
@@ -17,15 +18,20 @@ namespace {
 // Eq. 2 parameters of one group from its min and max.
 struct GroupParams {
   float lo, scale, inv;
+  unsigned stored;  // storage word of (scale, lo) in the compact formats
 };
 
-__device__ __forceinline__ GroupParams group_params(float mn, float mx, float alpha, float top) {
+__device__ __forceinline__ GroupParams group_params(float mn, float mx, float alpha, float top, int fmt) {
   if (mn == 0.0f) mn = 0.0f;  // a minimum of -0 is stored as +0
   if (mx == 0.0f) mx = 0.0f;
   GroupParams g;
-  g.lo = __fmul_rn(alpha, mn);
+  const float lo = __fmul_rn(alpha, mn);
   const float hi = __fmul_rn(alpha, mx);
-  g.scale = __fdiv_rn(__fsub_rn(hi, g.lo), top);
+  // the codes are computed with the values that decoding will read back from storage
+  const MetaPair m = meta_make(__fdiv_rn(__fsub_rn(hi, lo), top), lo, fmt);
+  g.lo = m.zero;
+  g.scale = m.scale;
+  g.stored = m.stored;
   g.inv = g.scale > 0.0f ? __fdiv_rn(1.0f, g.scale) : 0.0f;
   return g;
 }
@@ -46,19 +52,17 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int G) {
 }
 
 // Reorder one row through LDS and encode it.  row_lds: 128 halves of this wavefront.
-// Returns this lane's two codes; lane with 2l % G == 0 also gets the group's (scale, zero).
+// Returns this lane's two codes and the group's (scale, zero).
 __device__ __forceinline__ void encode_row(const __half *row_lds, int p0, int p1, float alpha, int G,
-                                           float top, unsigned &c0, unsigned &c1, float &scale,
-                                           float &zero) {
+                                           float top, int fmt, unsigned &c0, unsigned &c1, MetaPair &meta) {
   const float x0 = __half2float(row_lds[p0]);
   const float x1 = __half2float(row_lds[p1]);
   float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
   group_minmax(mn, mx, G);
-  const GroupParams g = group_params(mn, mx, alpha, top);
+  const GroupParams g = group_params(mn, mx, alpha, top, fmt);
   c0 = encode(x0, g, top);
   c1 = encode(x1, g, top);
-  scale = g.scale;
-  zero = g.lo;
+  meta = MetaPair{g.scale, g.lo, g.stored};
 }
 
 // K row: position p at bits [2p, 2p+2).  Lane l contributes 4 bits; 8 lanes form a dword.
@@ -108,7 +112,7 @@ constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte a
 // Gathers positions 16n..16n+15 of one parked row, finds the group's Eq. 2 parameters and
 // returns this lane's 16 codes packed two bits each (position 16n + e at bits [2e, 2e+2)).
 __device__ __forceinline__ unsigned encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
-                                             float top, GroupParams &gp) {
+                                             float top, int fmt, GroupParams &gp) {
   const int ch[16] = {pm[0].x, pm[0].y, pm[0].z, pm[0].w, pm[1].x, pm[1].y, pm[1].z, pm[1].w,
                       pm[2].x, pm[2].y, pm[2].z, pm[2].w, pm[3].x, pm[3].y, pm[3].z, pm[3].w};
   float x[16];
@@ -124,7 +128,7 @@ __device__ __forceinline__ unsigned encode16(const __half *row, const int4 (&pm)
     mn = fminf(mn, __shfl_xor(mn, off));
     mx = fmaxf(mx, __shfl_xor(mx, off));
   }
-  gp = group_params(mn, mx, alpha, top);
+  gp = group_params(mn, mx, alpha, top, fmt);
   // code = rint(clamp(y, 0, top)): clamping first gives the same integer because the bounds are
   // integers; adding 1.5 * 2^23 rounds to the nearest integer, ties to even, and leaves the code
   // in the two low bits of the sum, which alignbit shifts into the row word from the top.
@@ -188,13 +192,13 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   __syncthreads();
 
   GroupParams gk, gv;
-  const unsigned kw = encode16(rows[wave][0][i], pk, ak, L.G, 3.0f, gk);
-  const unsigned vw = encode16(rows[wave][1][i], pv, av, L.G, vtop, gv);
+  const unsigned kw = encode16(rows[wave][0][i], pk, ak, L.G, 3.0f, L.meta_fmt, gk);
+  const unsigned vw = encode16(rows[wave][1][i], pv, av, L.G, vtop, L.meta_fmt, gv);
   if (valid) {
     reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw;
     if (writes_meta) {
-      reinterpret_cast<float2 *>(L.k_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(gk.scale, gk.lo);
-      reinterpret_cast<float2 *>(L.v_meta)[(head * L.Tcap + t) * L.NG + grp] = make_float2(gv.scale, gv.lo);
+      meta_store_pair(L.k_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, L.meta_fmt);
+      meta_store_pair(L.v_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, L.meta_fmt);
     }
   }
   vq[wave][i][n] = valid ? vw : 0u;  // rows past the packed region leave zeros in the block
@@ -313,11 +317,11 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
 
   const float top = wave ? (float)(L.v_levels - 1) : 3.0f;
   unsigned c0, c1;
-  float scale, zero;
-  encode_row(rows[wave], p0, p1, alpha, L.G, top, c0, c1, scale, zero);
-  float *meta = wave ? L.v_meta : L.k_meta;
+  MetaPair mp;
+  encode_row(rows[wave], p0, p1, alpha, L.G, top, L.meta_fmt, c0, c1, mp);
+  void *meta = wave ? L.v_meta : L.k_meta;
   if ((2 * lane) % L.G == 0)
-    reinterpret_cast<float2 *>(meta)[(head * L.Tcap + te) * L.NG + grp] = make_float2(scale, zero);
+    meta_store_pair(meta, (head * L.Tcap + te) * L.NG + grp, mp, L.meta_fmt);
 
   if (wave == 0) {
     store_k_row(L.k_codes + (head * L.Tcap + te) * (kD / 4), lane, c0, c1);

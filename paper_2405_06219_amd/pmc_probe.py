@@ -2,7 +2,7 @@
 plain device-to-device copy of known size (the yardstick that FETCH_SIZE / WRITE_SIZE are
 scaled by).  Run under `rocprofv3 --pmc FETCH_SIZE` (and again with WRITE_SIZE):
 
-    python3 paper_2405_06219_amd/pmc_probe.py [workload] [layers]
+    python3 paper_2405_06219_amd/pmc_probe.py [workload] [layers] [meta format] [sinks]
 """
 from __future__ import annotations
 
@@ -23,7 +23,9 @@ def main() -> int:
     n_layers = int(sys.argv[2]) if len(sys.argv) > 2 else 4
     dev = torch.device("cuda:0")
     w = synth.WORKLOADS[name]
-    caches = bench.build_layers(w, n_layers, 8, dev)[0]
+    meta = sys.argv[3] if len(sys.argv) > 3 else "f32"
+    n_sink = int(sys.argv[4]) if len(sys.argv) > 4 else 0
+    caches = bench.build_layers(w, n_layers, 8, dev, n_sink, meta)[0]
     q = torch.randn((n_layers, w.batch, w.n_q_heads, 128), device=dev).to(torch.float16)
     out = torch.empty((n_layers, w.batch, w.n_q_heads, 128), dtype=torch.float32, device=dev)
     for _ in range(3):
@@ -36,7 +38,7 @@ def main() -> int:
     for _ in range(3):
         dst.copy_(src)
     torch.cuda.synchronize()
-    print("decode algorithmic bytes per call:", bench.algorithmic_bytes_decode(w, w.context))
+    print("decode algorithmic bytes per call:", bench.algorithmic_bytes_decode(w, w.context, n_sink, meta))
     return 0
 
 

@@ -24,15 +24,15 @@ def log(msg: str):
 
 class Pair:
     def __init__(self, w: synth.Workload, max_quant_tokens: int, perm_k, perm_v, clip_k, clip_v, sm_scale=0.0,
-                 fill=0xAB, device="cuda:0", n_sink=0):
+                 fill=0xAB, device="cuda:0", n_sink=0, meta="f32"):
         self.w = w
         osm = sm_scale if sm_scale else None
         self.ref = O.OracleCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                  max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=osm, fill=fill,
-                                 n_sink=n_sink)
+                                 n_sink=n_sink, meta=meta)
         self.gpu = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=sm_scale, fill=fill,
-                               device=device, n_sink=n_sink)
+                               device=device, n_sink=n_sink, meta=meta)
         self.device = device
 
     def prefill(self, k: np.ndarray, v: np.ndarray):
@@ -51,6 +51,8 @@ class Pair:
         for name, g, r in zip(names, got, self.ref.arrays()):
             if g.dtype == np.float32:       # compare bit patterns (distinguishes -0 from +0)
                 g, r = g.view(np.uint32), r.view(np.uint32)
+            elif g.dtype == np.float16:
+                g, r = g.view(np.uint16), r.view(np.uint16)
             if not np.array_equal(g, r):
                 bad = np.argwhere(g != r)
                 raise AssertionError(f"{name}: {len(bad)} mismatches, first at {bad[0].tolist()}: "

@@ -309,3 +309,62 @@ def test_sinks_appends_walk_ring_then_sink_rows_then_packed_rows(P, T0):
         tight.gpu.skvq_quantize_append(x, x)
     assert e.value.status == P.B.SKVQ_ERR_CAPACITY
     torch.cuda.synchronize()
+
+
+# ---- compact (scale, zero): fp16 and FP8 E4M3 storage (Section 4.1; Section 4.3's bit accounting) ----
+
+META_CASES = [
+    (small("e4m3_gqa4_t15", n_q_heads=16, n_kv_heads=4, context=1333, batch=2), "e4m3", 5),
+    (small("f16_gqa4_t15", n_q_heads=16, n_kv_heads=4, context=1333, batch=2), "f16", 0),
+    (small("e4m3_mha_v2_outlier", v_bits=2.0, channel_profile="outlier4", perm_stat="absmax", context=2048), "e4m3", 0),
+    (small("f16_gqa2_v2", n_q_heads=4, n_kv_heads=2, v_bits=2.0, context=999), "f16", 3),
+    (small("e4m3_gqa2_g64", n_q_heads=4, n_kv_heads=2, group_size=64, context=611), "e4m3", 0),
+    (small("f16_gqa8_g32_v2", n_q_heads=8, n_kv_heads=1, group_size=32, v_bits=2.0, context=450, window=16), "f16", 1),
+    (small("e4m3_mha_g32_t15", group_size=32, context=300), "e4m3", 0),
+]
+
+
+@pytest.mark.parametrize("w,meta,S", META_CASES, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_compact_meta_prefill_appends_bit_exact_and_decode_matches_oracle(P, w, meta, S):
+    print("case", w, meta, S, flush=True)
+    n = 40
+    pair, k, v, q = P.make_pair(w, extra_tokens=n, n_sink=S, meta=meta)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
+    out, ref = pair.decode_both(q)
+    err = np.abs(out - ref).max()
+    P.log(f"decode {w.name} meta={meta}: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
+    assert err <= P.TOL
+    for s in range(n):
+        pair.append(*synth.make_new_token(w, s))
+    pair.assert_buffers_equal()
+    out, ref = pair.decode_both(q)
+    assert np.abs(out - ref).max() <= P.TOL
+
+
+@pytest.mark.parametrize("meta", ["f16", "e4m3"])
+def test_compact_meta_special_values_bit_exact(P, meta):
+    """Ranges that saturate FP8 (scale or zero beyond 448), that underflow it (scale below
+    2^-10 -> 0, codes all 0), ties of the meta rounding, constant and zero groups."""
+    rng = np.random.default_rng(5)
+    w = small("meta_special", n_q_heads=2, n_kv_heads=2, group_size=32, context=128 + 96)
+    T = w.context
+    k = (rng.standard_normal((1, 2, T, D)) * 3).astype(np.float16)
+    v = (rng.standard_normal((1, 2, T, D)) * 3).astype(np.float16)
+    k[0, 0, 0, :] = 0.0
+    k[0, 0, 1, :] = 1000.0                      # constant, zero point beyond 448
+    k[0, 0, 2, :] = np.linspace(-3000, 3000, D)  # scale beyond 448
+    k[0, 0, 3, :] = np.linspace(0, 2e-4, D)      # scale below the smallest FP8 value
+    k[0, 0, 4, :] = np.linspace(-6e-5, 6e-5, D)  # fp16 subnormal inputs
+    k[0, 1, 5, :32] = np.array([0, 27] * 16)     # scale 27/3 = 9 -> FP8 tie between 9 and 10? (9 is exact)
+    k[0, 1, 6, :32] = np.array([0, 25.5] * 16)   # scale 8.5: FP8 tie (8 and 9): to even
+    k[0, 1, 7, :] = 65504.0
+    k[0, 1, 8, :] = np.where(np.arange(D) % 2, 65504.0, -65504.0)
+    v[0, :, :16] = k[0, :, :16]
+    pk = np.stack([rng.permutation(D) for _ in range(2)]).astype(np.int32)
+    pv = np.stack([rng.permutation(D) for _ in range(2)]).astype(np.int32)
+    ck = rng.uniform(0.5, 1.0, (2, 4)).astype(np.float32)
+    cv = np.ones((2, 4), np.float32)
+    pair = P.Pair(w, 96, pk, pv, ck, cv, meta=meta)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
