@@ -137,21 +137,24 @@ constexpr int kRingSlice = 4;       // ring tokens per slice (the slice code rea
 
 constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumulator columns over the banks
 
-template <int R, bool TERNARY>
+template <int R, bool TERNARY, int NG>
 struct Smem {
   // 13-bit field -> the A operand of its eight tokens (104976 bytes, built by the workgroup
   // from the two 81-entry tables: four base-3 digits -> the operand halves of tokens 0..3 / 4..7)
   uint4_t lut[TERNARY ? 6561 : 1];
   uint2_t lut4[TERNARY ? 2 : 1][81];
-  float stage[kNW][R][kCombStride];  // epilogue: O^T per wave and head, reordered positions
+  // per wave: the weights of the current tile, [block][group][column][token slot]; after the
+  // wave's last tile the same bytes stage its O^T, [head][reordered position]
+  union WaveBuf {
+    _Float16 pbuf[2][NG][2 * R][32];
+    float stage[R][kCombStride];
+  } wb[kNW];
   float qraw[4][kD];                   // the query heads as loaded (rows >= R are zero)
   _Float16 qa[32][4][4];               // A operands of the score product: [step][head][k slot]
-  float qsum[4];                       // sm_scale*log2(e) * sum of the query, per head
-  float qinit[4];                      // -1.5 * sum of the query, in the score product's units (2^-16)
-  _Float16 pbuf[kNW][2][2 * R][32];    // per wave: [block][column][token slot]
+  float qpart[4][8];                   // per head: sums of the reordered query over 16 positions each
   // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
   // tiles (w*) and for the ring slices (r*) of the wave
-  float wm[kNW][R], wl[kNW][R], wz[kNW][R], rm[kNW][R], rl[kNW][R];
+  float wm[kNW][R], wl[kNW][R], wz[kNW][R][NG], rm[kNW][R], rl[kNW][R];
   float ring_o[kNW][R][kD];            // per wave: its ring slices' outputs, original channel order
 };
 
@@ -198,10 +201,15 @@ __device__ __forceinline__ float2 meta_value(unsigned short w) {  // FP8 E4M3: c
 }
 
 // What one wavefront loads for one tile of 64 tokens.
-template <int META>
+template <int META, int NG>
+struct alignas(sizeof(typename MetaWord<META>::type) * NG > 16 ? 16 : sizeof(typename MetaWord<META>::type) * NG)
+    MetaBlock {  // the NG pairs of one token
+  typename MetaWord<META>::type m[NG];
+};
+template <int META, int NG>
 struct TileData {
-  uint4_t k0, k1;                              // lane = token: its 32-byte key row
-  typename MetaWord<META>::type kmeta, vmeta;  // lane = token: (scale, zero)
+  uint4_t k0, k1;                  // lane = token: its 32-byte key row
+  MetaBlock<META, NG> kmeta, vmeta;  // lane = token: (scale, zero) per group
   Unit16 v0, v1;        // lane = unit of V block 2*tile and 2*tile+1
 };
 
@@ -211,14 +219,14 @@ struct RingData {
   unsigned v[4];  // lane = channel pair: the 4 tokens' values of channels 2l, 2l+1
 };
 
-template <int R, bool TERNARY, int META>
+template <int R, bool TERNARY, int META, int NG>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
                                                                   int n_splits) {
   // grid (n_splits, Hk, B).  Workgroup sp owns an even share of the packed 64-token tiles of
   // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
   // j = sp (mod n_splits), dealt the same way.
-  __shared__ Smem<R, TERNARY> sm;
+  __shared__ Smem<R, TERNARY, NG> sm;
   SKVQ_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -232,10 +240,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int tile_end = (int)(((long long)(sp + 1) * n_tiles) / n_splits);
 
   const uint8_t *kc = L.k_codes + head * L.Tcap * (kD / 4);
-  typedef typename MetaWord<META>::type meta_word;
-  typedef TileData<META> Tile;
-  const meta_word *km = reinterpret_cast<const meta_word *>(L.k_meta) + head * L.Tcap;
-  const meta_word *vm = reinterpret_cast<const meta_word *>(L.v_meta) + head * L.Tcap;
+  typedef TileData<META, NG> Tile;
+  typedef MetaBlock<META, NG> meta_block;
+  const meta_block *km = reinterpret_cast<const meta_block *>(L.k_meta) + head * L.Tcap;
+  const meta_block *vm = reinterpret_cast<const meta_block *>(L.v_meta) + head * L.Tcap;
   const uint8_t *vc = L.v_codes + head * L.n_vblocks * L.v_block_bytes;
   const int last_token = (int)(nq - 1);  // -1 when nothing is packed (then there are no tiles)
   const int last_blk = last_token >> 5;
@@ -361,12 +369,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         const int row = (tid >> 7) + 2 * rr, p = tid & 127;
         int step, kslot, shift;
         k_slot_of(p, step, kslot, shift);
-        sm.qa[step][row][kslot] = (_Float16)ldexpf(sm.qraw[row][pk], 8 - shift);  // exact: a power of two
-      }
-      const float v = wave_sum(sm.qraw[wave][lane] + sm.qraw[wave][lane + 64]);  // wave r sums head r
-      if (lane == 0) {
-        sm.qsum[wave] = c * v;
-        sm.qinit[wave] = -1.5f * v * (1.0f / 65536.0f);
+        const float x = sm.qraw[row][pk];
+        sm.qa[step][row][kslot] = (_Float16)ldexpf(x, 8 - shift);  // exact: a power of two
+        // sum of the reordered query over the 16 positions of this row of lanes
+        float s16 = x;
+        s16 += row_move<kQuadSwap1>(s16);
+        s16 += row_move<kQuadSwap2>(s16);
+        s16 += row_move<kRowHalfMirror>(s16);
+        s16 += row_move<kRowMirror>(s16);
+        if ((lane & 15) == 0) sm.qpart[row][p >> 4] = s16;
       }
     }
     __syncthreads();
@@ -375,12 +386,22 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // lane l supplies row l%4 (= head) of step l/4 (first register pair) and 16 + l/4 (second)
   const half4_t qop_lo = *reinterpret_cast<const half4_t *>(sm.qa[lane >> 2][lane & 3]);
   const half4_t qop_hi = *reinterpret_cast<const half4_t *>(sm.qa[16 + (lane >> 2)][lane & 3]);
-  float qsc[R];
+  // Per group: sm_scale*log2(e) * sum of the reordered query (qsc), and the start value of the
+  // score accumulators, -1.5*sum(q) in the product's units (2^-16): the products then sum
+  // q*(c - 1.5), centred codes, which keeps both halves of
+  // scale*sum q(c-1.5) + (zero+1.5 scale)*sum q  small.
+  float qsc[R][NG];
+  float4_t dinit[NG];
 #pragma unroll
-  for (int r = 0; r < R; ++r) qsc[r] = sm.qsum[r];
-  // The score accumulators start at -1.5*sum(q): the products then sum q*(c - 1.5), centred
-  // codes, which keeps both halves of  scale*sum q(c-1.5) + (zero+1.5 scale)*sum q  small.
-  const float4_t dinit = {sm.qinit[0], sm.qinit[1], sm.qinit[2], sm.qinit[3]};
+  for (int g = 0; g < NG; ++g)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float sum = 0.f;
+#pragma unroll
+      for (int x = 0; x < 8 / NG; ++x) sum += sm.qpart[r][g * (8 / NG) + x];
+      if (r < R) qsc[r][g] = c * sum;
+      dinit[g][r] = -1.5f * sum * (1.0f / 65536.0f);
+    }
 
   // ---- ring slices of this wave (plain vector arithmetic, wave-local) ----
   if (ring_owner) {
@@ -461,9 +482,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // (No ring load younger than the tile loads may be pending here: it would turn every wait
   // inside the tile loop into a wait for all loads.)
 
-  float mref[R], lsum[R], zacc[R];
+  float mref[R], lsum[R], zacc[R][NG];
 #pragma unroll
-  for (int r = 0; r < R; ++r) mref[r] = 0.f, lsum[r] = 0.f, zacc[r] = 0.f;
+  for (int r = 0; r < R; ++r) {
+    mref[r] = 0.f, lsum[r] = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) zacc[r][g] = 0.f;
+  }
   float beta = 1.f;
   float4_t acc[8];
 #pragma unroll
@@ -474,30 +499,43 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   SKVQ_WSTAMP(0);
   auto compute_tile = [&](const Tile &cur, const int tile) {
     const bool valid = tile * 64 + lane <= last_token;
-    const float2 kmeta = meta_value(cur.kmeta), vmeta = meta_value(cur.vmeta);
 
-    // ---- scores: 32 products of 4 channels each ----
-    float4_t d0 = dinit;
-    d0 = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, d0);
-    d0 = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, d0);
-    d0 = qk_dword<2>(cur.k0.z, qop_lo, qop_hi, d0);
-    d0 = qk_dword<3>(cur.k0.w, qop_lo, qop_hi, d0);
-    d0 = qk_dword<4>(cur.k1.x, qop_lo, qop_hi, d0);
-    d0 = qk_dword<5>(cur.k1.y, qop_lo, qop_hi, d0);
-    d0 = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, d0);
-    d0 = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, d0);
+    // ---- scores: 32 products of 4 channels each, one accumulator per group ----
+    float4_t dg[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) dg[g] = dinit[g];
+    dg[0 * NG / 8] = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, dg[0 * NG / 8]);
+    dg[1 * NG / 8] = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, dg[1 * NG / 8]);
+    dg[2 * NG / 8] = qk_dword<2>(cur.k0.z, qop_lo, qop_hi, dg[2 * NG / 8]);
+    dg[3 * NG / 8] = qk_dword<3>(cur.k0.w, qop_lo, qop_hi, dg[3 * NG / 8]);
+    dg[4 * NG / 8] = qk_dword<4>(cur.k1.x, qop_lo, qop_hi, dg[4 * NG / 8]);
+    dg[5 * NG / 8] = qk_dword<5>(cur.k1.y, qop_lo, qop_hi, dg[5 * NG / 8]);
+    dg[6 * NG / 8] = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, dg[6 * NG / 8]);
+    dg[7 * NG / 8] = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, dg[7 * NG / 8]);
     // u = log2-domain score minus the running reference
-    const float a_t = kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
-    const float zc = fmaf(1.5f, kmeta.x, kmeta.y);  // dequantized value of the centre code 1.5
     float u[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      u[r] = fmaf(d0[r], a_t, fmaf(zc, qsc[r], -mref[r]));
-      if (!valid) u[r] = -INFINITY;
+    for (int r = 0; r < R; ++r) u[r] = -mref[r];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float2 kmeta = meta_value(cur.kmeta.m[g]);
+      const float a_t = kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
+      const float zc = fmaf(1.5f, kmeta.x, kmeta.y);  // dequantized value of the centre code 1.5
+#pragma unroll
+      for (int r = 0; r < R; ++r) u[r] = fmaf(dg[g][r], a_t, fmaf(zc, qsc[r][g], u[r]));
     }
-    const float vs = valid ? vmeta.x : 0.f;
-    const float vz = valid ? vmeta.y : 0.f;
-    bool trig = vs * beta > kVsLimit;
+    float vs[NG], vz[NG], vs_top = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float2 vmeta = meta_value(cur.vmeta.m[g]);
+      vs[g] = valid ? vmeta.x : 0.f;
+      vz[g] = valid ? vmeta.y : 0.f;
+      vs_top = fmaxf(vs_top, vs[g]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (!valid) u[r] = -INFINITY;
+    bool trig = vs_top * beta > kVsLimit;
 #pragma unroll
     for (int r = 0; r < R; ++r) trig |= u[r] > kRefSlack;
     if (first || __any(trig)) {
@@ -511,9 +549,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         mref[r] += delta;
         u[r] -= delta;
         lsum[r] *= f[r];
-        zacc[r] *= f[r];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) zacc[r][g] *= f[r];
       }
-      const float vsmax = wave_max(vs);
+      const float vsmax = wave_max(vs_top);
       float g = 1.f;
       if (vsmax * beta > kVsTarget || first) {
         float nb = beta;
@@ -538,18 +577,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     }
 
     // ---- weights: p = 2^u, P' = p * vscale * beta * 2^-(bit-4), split into high and low fp16 ----
-    const float vsb = vs * beta * kslot_scale;
-    _Float16 *pw = &sm.pbuf[wave][lane >> 5][0][lane & 31];
+    const float bk = beta * kslot_scale;
+    _Float16 *pw = &sm.wb[wave].pbuf[lane >> 5][0][0][lane & 31];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const float p = fast_exp2(u[r]);
       lsum[r] += p;
-      zacc[r] = fmaf(p, vz, zacc[r]);
-      const float pp = p * vsb;
-      const float hi = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, pp) & 0xffffe000u);
-      const float lo = pp - hi;
-      pw[r * 32] = (_Float16)hi;
-      pw[(R + r) * 32] = (_Float16)lo;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        zacc[r][g] = fmaf(p, vz[g], zacc[r][g]);
+        const float pp = p * (vs[g] * bk);
+        const float hi = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, pp) & 0xffffe000u);
+        const float lo = pp - hi;
+        pw[(g * 2 * R + r) * 32] = (_Float16)hi;
+        pw[(g * 2 * R + R + r) * 32] = (_Float16)lo;
+      }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -559,8 +601,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     const int col = lane & 15, kb = lane >> 4;
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
-      half8_t pop = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (col < 2 * R) pop = *reinterpret_cast<const half8_t *>(&sm.pbuf[wave][blk][col][8 * kb]);
+      half8_t pop[NG];  // the weights (B operand) of each group of channel tiles
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        pop[g] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (col < 2 * R) pop[g] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col][8 * kb]);
+      }
       const Unit16 raw = blk ? cur.v1 : cur.v0;
       if (TERNARY) {
         const unsigned u0 = __builtin_amdgcn_alignbyte(raw.y, raw.x, unit_sh);
@@ -583,13 +629,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
           aop[n] = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(sm.lut) + f[n]);
 #pragma unroll
         for (int n = 0; n < 8; ++n)
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop, acc[n], 0, 0, 0);
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop[n * NG / 8],
+                                                          acc[n], 0, 0, 0);
       } else {
         const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
           const unsigned f = (n & 1) ? (w[n >> 1] >> 8) : w[n >> 1];
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_field(f), pop, acc[n], 0, 0, 0);
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_field(f), pop[n * NG / 8], acc[n], 0, 0, 0);
         }
       }
     }
@@ -626,11 +673,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // ---- epilogue: fold lanes, columns, waves and ring slices; write this chunk's partial ----
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const float ls = wave_sum_fast(lsum[r]), zs = wave_sum_fast(zacc[r]);
+    const float ls = wave_sum_fast(lsum[r]);
     if (lane == 0) {
       sm.wm[wave][r] = first ? -INFINITY : mref[r];
       sm.wl[wave][r] = ls;
-      sm.wz[wave][r] = zs;
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float zs = wave_sum_fast(zacc[r][g]);
+      if (lane == 0) sm.wz[wave][r][g] = zs;
     }
   }
   if (!first) {
@@ -642,7 +693,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         const float lo_part = row_move<kRowShl + R>(acc[n][rr]);  // column R + r: the low halves' sum
-        if (col < R) sm.stage[wave][col][16 * n + 4 * kb + rr] = (acc[n][rr] + lo_part) * unscale;
+        if (col < R) sm.wb[wave].stage[col][16 * n + 4 * kb + rr] = (acc[n][rr] + lo_part) * unscale;
       }
   }
   __syncthreads();
@@ -668,7 +719,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     for (int w = 0; w < kNW; ++w) {
       const float e = wl[w] > 0.f ? fast_exp2(wm[w] - m) : 0.f, g = rl[w] > 0.f ? fast_exp2(rm[w] - m) : 0.f;
       den = fmaf(e, wl[w], fmaf(g, rl[w], den));
-      if (e > 0.f) num = fmaf(e, sm.stage[w][r][p] + sm.wz[w][r], num);
+      if (e > 0.f) num = fmaf(e, sm.wb[w].stage[r][p] + sm.wz[w][r][p * NG / kD], num);
       if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
     float *part = L.workspace + (((long long)b * L.Hq + hk * R + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
@@ -692,7 +743,9 @@ extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
 }
 #endif
 
-bool decode_mfma_supported(const Layout &L) { return L.G == kD && (L.R == 1 || L.R == 2 || L.R == 4); }
+bool decode_mfma_supported(const Layout &L) {
+  return (L.G == 128 || L.G == 64 || L.G == 32) && (L.R == 1 || L.R == 2 || L.R == 4);
+}
 
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                               int n_splits, hipStream_t s) {
@@ -700,14 +753,21 @@ hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, lon
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk, L.B), block(kThreads);
-#define SKVQ_LAUNCH(RR, TT, MM) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT, MM>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits)
-#define SKVQ_LAUNCH_META(RR, TT)                                              \
-  switch (L.meta_fmt) {                                                       \
-    case SKVQ_META_F32: SKVQ_LAUNCH(RR, TT, SKVQ_META_F32); break;            \
-    case SKVQ_META_F16: SKVQ_LAUNCH(RR, TT, SKVQ_META_F16); break;            \
-    case SKVQ_META_FP8_E4M3: SKVQ_LAUNCH(RR, TT, SKVQ_META_FP8_E4M3); break;  \
-    default: return hipErrorInvalidValue;                                     \
+#define SKVQ_LAUNCH(RR, TT, MM, GG) \
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT, MM, GG>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits)
+#define SKVQ_LAUNCH_NG(RR, TT, MM)                 \
+  switch (L.NG) {                                  \
+    case 1: SKVQ_LAUNCH(RR, TT, MM, 1); break;     \
+    case 2: SKVQ_LAUNCH(RR, TT, MM, 2); break;     \
+    case 4: SKVQ_LAUNCH(RR, TT, MM, 4); break;     \
+    default: return hipErrorInvalidValue;          \
+  }
+#define SKVQ_LAUNCH_META(RR, TT)                                                \
+  switch (L.meta_fmt) {                                                         \
+    case SKVQ_META_F32: SKVQ_LAUNCH_NG(RR, TT, SKVQ_META_F32) break;            \
+    case SKVQ_META_F16: SKVQ_LAUNCH_NG(RR, TT, SKVQ_META_F16) break;            \
+    case SKVQ_META_FP8_E4M3: SKVQ_LAUNCH_NG(RR, TT, SKVQ_META_FP8_E4M3) break;  \
+    default: return hipErrorInvalidValue;                                       \
   }
   const bool ter = L.v_levels == 3;
   switch (L.R) {
@@ -717,6 +777,7 @@ hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, lon
     default: return hipErrorInvalidValue;
   }
 #undef SKVQ_LAUNCH_META
+#undef SKVQ_LAUNCH_NG
 #undef SKVQ_LAUNCH
   return hipGetLastError();
 }

@@ -98,6 +98,10 @@ DECODE_CASES = [
     small("gqa2_v2_w512", n_q_heads=4, n_kv_heads=2, v_bits=2.0, window=512, context=3000),
     small("mha_t15_w33", window=33, context=5000, batch=3),
     small("gqa2_g64", n_q_heads=4, n_kv_heads=2, group_size=64, context=611),
+    small("gqa4_g32_t15", n_q_heads=8, n_kv_heads=2, group_size=32, context=5000),
+    small("gqa4_g64_v2", n_q_heads=16, n_kv_heads=4, group_size=64, v_bits=2.0, context=3000),
+    small("mha_g64_t15_b2", group_size=64, context=9000, batch=2),
+    small("gqa2_g32_v2", n_q_heads=4, n_kv_heads=2, group_size=32, v_bits=2.0, context=2500, window=40),
     small("gqa8_g32_v2", n_q_heads=8, n_kv_heads=1, group_size=32, v_bits=2.0, context=450, window=16),
     small("mha_g32_t15", group_size=32, context=300),
     small("window_only", context=77),
@@ -133,6 +137,20 @@ def test_decode_is_independent_of_the_split_count(P):
         assert np.abs(o - ref).max() <= P.TOL, s
         outs.append(o)
     assert max(np.abs(o - outs[0]).max() for o in outs) <= 5e-4
+
+
+@pytest.mark.parametrize("G,meta", [(32, "f32"), (64, "e4m3")])
+def test_decode_with_small_groups_is_independent_of_the_split_count(P, G, meta):
+    w = small("splits_g", n_q_heads=8, n_kv_heads=2, group_size=G, context=128 + 64 * 41 + 17)
+    pair, k, v, q = P.make_pair(w, meta=meta, n_sink=2)
+    pair.prefill(k, v)
+    ref = pair.ref.decode(q)
+    qd = torch.from_numpy(q).cuda()
+    for s in (1, 2, 5, 41, 128):
+        pair.gpu.skvq_set_num_splits(s)
+        o = pair.gpu.skvq_decode_attention(qd).cpu().numpy()
+        P.log(f"G {G} splits {s}: max abs err {np.abs(o - ref).max():.3e}")
+        assert np.abs(o - ref).max() <= P.TOL, s
 
 
 def test_decode_after_appends_and_peaked_softmax(P):
