@@ -30,7 +30,7 @@ D = 128
 # HBM bytes per skvq_decode_attention call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (chunk kernel + merge kernel, counters scaled by a plain copy of known size); see
 # profiles/decode_c3_mistral7b_128k_pmc.txt.  Only workloads that were measured have an entry.
-MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 77983 * 1024}
+MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 77977 * 1024}
 
 
 META_BYTES = {"f32": 4, "f16": 2, "e4m3": 1}
