@@ -94,7 +94,7 @@ int choose_splits(const skvq_cache *c, long long n_quant) {
   } else {
     // one workgroup per compute unit over all (sequence, kv head) pairs, but every wavefront of
     // a workgroup should have at least two tiles
-    const long long heads = (long long)c->L.B * c->L.Hk;
+    const long long heads = (long long)c->L.B * c->L.Hk * decode_passes(c->L.R);
     s = c->n_cus / heads;
     const long long cap = tiles / (2 * kMfmaWavesPerGroup);
     if (s > cap) s = cap;

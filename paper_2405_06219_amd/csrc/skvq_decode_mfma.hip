@@ -222,15 +222,20 @@ struct RingData {
 template <int R, bool TERNARY, int META, int NG>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
-                                                                  int n_splits) {
-  // grid (n_splits, Hk, B).  Workgroup sp owns an even share of the packed 64-token tiles of
+                                                                  int n_splits, int passes) {
+  // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
+  // head with more than four (or with three) query heads is served by `passes` workgroups per
+  // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
+  // heads are computed with a zero query and not stored).
+  //   Workgroup sp owns an even share of the packed 64-token tiles of
   // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
   // j = sp (mod n_splits), dealt the same way.
   __shared__ Smem<R, TERNARY, NG> sm;
   SKVQ_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int sp = blockIdx.x, hk = blockIdx.y / passes, b = blockIdx.z;
+  const int head0 = (blockIdx.y % passes) * R;  // first of this workgroup's query heads, within the kv head's
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;
 
@@ -314,7 +319,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   //      wait for them and not for the two tiles of packed data behind them. ----
   SKVQ_STAMP(4);
   __half2 q2 = __floats2half2_rn(0.f, 0.f);
-  if (tid < 64 * R) q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * R + (tid >> 6)) * kD)[lane];
+  if (tid < 64 * R && head0 + (tid >> 6) < L.R)
+    q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * L.R + head0 + (tid >> 6)) * kD)[lane];
   const int pk = L.perm_k[hk * kD + (tid & 127)];
   const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
   RingData ring = {};
@@ -699,7 +705,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   __syncthreads();
   SKVQ_STAMP(8);
   SKVQ_STAMP(9);
-  if (tid < R * kD) {
+  if (tid < R * kD && head0 + (tid >> 7) < L.R) {
     // thread (head r, position p): the chunk's reference m* = max over waves and ring slices,
     // each one's factor 2^(m - m*), the sums that need no channel (every thread of a head
     // computes the same ones: cheaper than another exchange through LDS), its channel's sum
@@ -722,7 +728,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       if (e > 0.f) num = fmaf(e, sm.wb[w].stage[r][p] + sm.wz[w][r][p * NG / kD], num);
       if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
-    float *part = L.workspace + (((long long)b * L.Hq + hk * R + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
+    float *part =
+        L.workspace + (((long long)b * L.Hq + hk * L.R + head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
     part[4 + ch] = num;
     if (p == 0) {
       part[0] = m;
@@ -743,18 +750,17 @@ extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
 }
 #endif
 
-bool decode_mfma_supported(const Layout &L) {
-  return (L.G == 128 || L.G == 64 || L.G == 32) && (L.R == 1 || L.R == 2 || L.R == 4);
-}
 
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                               int n_splits, hipStream_t s) {
   if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
-  const dim3 grid(n_splits, L.Hk, L.B), block(kThreads);
+  const int passes = decode_passes(L.R), rk = L.R == 1 ? 1 : L.R == 2 ? 2 : 4;
+  if ((long long)L.Hk * passes > 65535 || L.R > 8) return hipErrorInvalidValue;
+  const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
 #define SKVQ_LAUNCH(RR, TT, MM, GG) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT, MM, GG>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT, MM, GG>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes)
 #define SKVQ_LAUNCH_NG(RR, TT, MM)                 \
   switch (L.NG) {                                  \
     case 1: SKVQ_LAUNCH(RR, TT, MM, 1); break;     \
@@ -770,7 +776,7 @@ hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, lon
     default: return hipErrorInvalidValue;                                       \
   }
   const bool ter = L.v_levels == 3;
-  switch (L.R) {
+  switch (rk) {
     case 1: if (ter) { SKVQ_LAUNCH_META(1, true) } else { SKVQ_LAUNCH_META(1, false) } break;
     case 2: if (ter) { SKVQ_LAUNCH_META(2, true) } else { SKVQ_LAUNCH_META(2, false) } break;
     case 4: if (ter) { SKVQ_LAUNCH_META(4, true) } else { SKVQ_LAUNCH_META(4, false) } break;

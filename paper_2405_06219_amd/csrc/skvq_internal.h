@@ -61,11 +61,11 @@ hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_n
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,
                          long long T, int n_splits, hipStream_t s);
 
-// Matrix-core chunk kernel for the packed region (skvq_decode_mfma.hip): group size 128,
-// 1, 2 or 4 query heads per kv head.  Packed chunks and the fp16 tokens (n_sink sink rows, then
-// the window's T - nq - n_sink ring tokens); writes partials
-// 0..n_splits-1 (n_splits >= 1 even when nothing is packed yet).
-bool decode_mfma_supported(const Layout &L);
+// Matrix-core chunk kernel (skvq_decode_mfma.hip): packed chunks and the fp16 tokens (n_sink sink
+// rows, then the window's T - nq - n_sink ring tokens); writes partials 0..n_splits-1 (n_splits
+// >= 1 even when nothing is packed yet).  A workgroup serves 1, 2 or 4 query heads of a kv head;
+// kv heads with 5..8 query heads are read by two workgroups per chunk.
+inline int decode_passes(int R) { return R > 4 ? 2 : 1; }
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                               int n_splits, hipStream_t s);
 constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel

@@ -103,6 +103,11 @@ DECODE_CASES = [
     small("mha_g64_t15_b2", group_size=64, context=9000, batch=2),
     small("gqa2_g32_v2", n_q_heads=4, n_kv_heads=2, group_size=32, v_bits=2.0, context=2500, window=40),
     small("gqa8_g32_v2", n_q_heads=8, n_kv_heads=1, group_size=32, v_bits=2.0, context=450, window=16),
+    small("gqa8_t15", n_q_heads=16, n_kv_heads=2, context=2300, batch=2),
+    small("gqa3_t15", n_q_heads=6, n_kv_heads=2, context=1900),
+    small("gqa5_v2_g64", n_q_heads=5, n_kv_heads=1, group_size=64, v_bits=2.0, context=1500),
+    small("gqa6_t15", n_q_heads=12, n_kv_heads=2, context=1000),
+    small("gqa7_t15_g32", n_q_heads=7, n_kv_heads=1, group_size=32, context=800),
     small("mha_g32_t15", group_size=32, context=300),
     small("window_only", context=77),
     small("exactly_window", context=128),
