@@ -1,24 +1,27 @@
-// Matrix-core kernel of skvq_decode_attention for gfx950 (group size 128, up to four query
-// heads per kv head): packed chunks and the fp16 ring in one launch, one partial per chunk.
+// Matrix-core kernel of skvq_decode_attention for gfx950: packed chunks and the fp16 tokens
+// (attention sinks, window) in one launch, one partial per chunk.  Templated on the query
+// heads a workgroup serves (1, 2, 4), the V format, the (scale, zero) format and the groups
+// per head (1, 2, 4).
 // (Merging the partials inside this launch was tried and dropped: the device-scope fences it
 // needs write back and invalidate a whole L2 each, 25 us over 256 workgroups.)
 //
 // One workgroup of 8 wavefronts per chunk (one per compute unit when the cache is long
-// enough; 256 registers per wavefront).  Per wavefront, per tile of 64 packed tokens:
+// enough).  Per wavefront, per tile of 64 packed tokens:
 //   QK   S^T[head][token] by 32 v_mfma_f32_4x4x4_16b_f16 (16 independent 4x4 blocks, lane =
 //        token): the B operand is the lane's own 32-byte key row, its 2-bit codes turned into
 //        fp16 SUBNORMALS by one AND each (a code c sitting at mantissa bit s is the fp16 value
 //        c*2^(s-24)); the A operand is the reordered query, pre-multiplied by the matching
-//        power of two, held in registers.  Afterwards lane l holds the scores of token l for
-//        the (up to) four heads.
+//        power of two, held in registers.  One accumulator per group; afterwards lane l holds
+//        the scores of token l for the (up to) four heads.
 //   softmax  lazily re-referenced online softmax in the exp2 domain: the running reference m
 //        only moves when a score exceeds it by more than 2^6 (wave-uniform branch).
 //   PV   O^T[channel][head] by 16 v_mfma_f32_16x16x32_f16: the A operand is the V block unit
 //        that the lane loaded (8 tokens x 8 channels, token-minor; a 3-level field is the index
-//        of a 16-byte table entry in LDS that IS the operand), the B operand holds p*scale split into a high and a
-//        low fp16 part (two columns per head) so that the weights keep ~22 bits.
+//        of a 16-byte table entry in LDS that IS the operand), the B operand holds p*scale
+//        (one per group) split into a high and a low fp16 part (two columns per head) so that
+//        the weights keep ~22 bits.
 // The zero-points never enter the matrix products: sum_p q_p (s c_p + z) = s sum q c + z sum q
-// and sum_t w_t (s_t c + z_t) = sum (w_t s_t) c + sum w_t z_t.
+// and sum_t w_t (s_t c + z_t) = sum (w_t s_t) c + sum w_t z_t, per group.
 //
 // The matrix core accumulates products of subnormal inputs as if their mantissa were full, so
 // a code at mantissa bit s costs about (10 - s) bits of the accumulator's precision; every
