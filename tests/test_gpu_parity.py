@@ -391,3 +391,35 @@ def test_compact_meta_special_values_bit_exact(P, meta):
     pair = P.Pair(w, 96, pk, pv, ck, cv, meta=meta)
     pair.prefill(k, v)
     pair.assert_buffers_equal()
+
+
+def test_random_configurations(P):
+    """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
+    heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
+    appended tokens and a forced split count.  Buffers bit-exact, outputs within 2e-3."""
+    rng = np.random.default_rng(20240506)
+    for case in range(28):
+        hk = int(rng.integers(1, 4))
+        r = int(rng.integers(1, 9))
+        w = small(f"rand{case}", batch=int(rng.integers(1, 4)), n_kv_heads=hk, n_q_heads=hk * r,
+                  group_size=int(rng.choice([32, 64, 128])), v_bits=float(rng.choice([1.5, 2.0])),
+                  window=int(rng.choice([1, 3, 16, 33, 128, 200])), context=int(rng.integers(0, 2600)),
+                  seed=500 + case)
+        S = int(rng.choice([0, 0, 1, 5, 9]))
+        meta = str(rng.choice(["f32", "f16", "e4m3"]))
+        n_app = int(rng.integers(0, 40))
+        splits = int(rng.choice([0, 0, 1, 2, 3, 9, 40, 128]))
+        P.log(f"random case {case}: {w} S={S} meta={meta} appends={n_app} splits={splits}")
+        pair, k, v, q = P.make_pair(w, extra_tokens=n_app + 1, n_sink=S, meta=meta)
+        if w.context:
+            pair.prefill(k, v)
+        for s in range(n_app):
+            pair.append(*synth.make_new_token(w, s))
+        pair.assert_buffers_equal()
+        if pair.ref.n_tokens == 0:
+            continue
+        pair.gpu.skvq_set_num_splits(splits)
+        out, ref = pair.decode_both(q)
+        err = np.abs(out - ref).max()
+        P.log(f"random case {case}: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
+        assert err <= P.TOL, case
