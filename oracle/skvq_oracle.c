@@ -6,8 +6,9 @@
  *
  * Packed formats (the paper gives none; these are this build's):
  *
- *  K codes, one 32-byte row per (token, kv head): the 2-bit code of reordered
- *  position p sits in byte p/4 at bits [2*(p%4), 2*(p%4)+2).
+ *  K codes, one row per (token, kv head).  2-bit: 32 bytes, the code of
+ *  reordered position p sits in byte p/4 at bits [2*(p%4), 2*(p%4)+2).
+ *  4-bit: 64 bytes, position p in byte p/2 at bits [4*(p%2), 4*(p%2)+4).
  *
  *  V codes, one block per 32 consecutive tokens of a kv head, stored so that
  *  the codes of CONSECUTIVE TOKENS of one channel are neighbours (the value
@@ -18,6 +19,8 @@
  *            (n, i) sits at bit 32*(n/2) + 16*(i%2) + 8*(n%2) + 2*(i/2).
  *    3-level: unit = 13 bytes read as a 104-bit little-endian string; field n
  *            is bits [13n, 13n+13) and holds sum_i code(n, i) * 3^i  (< 6561).
+ *    4-bit : unit = 32 bytes read as a 256-bit little-endian string; code
+ *            (n, i) sits at bit 32*n + 16*(i%2) + 4*(i/2).
  *  A block is zero-filled when its first token arrives, so slots of tokens
  *  that do not exist yet read as code 0.
  *
@@ -163,13 +166,14 @@ double skvq_ref_avg_bits(double code_bits, int meta_bits, int group_size) {
 
 /* -------------------------------------------------------------- format --- */
 
-static size_t v_block_bytes(int levels) { return levels == 3 ? 832 : 1024; }
+static size_t v_block_bytes(int levels) { return levels == 3 ? 832 : levels == 16 ? 2048 : 1024; }
+static size_t k_row_bytes(int levels) { return levels == 16 ? D / 2 : D / 4; }
 
 void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
   size_t heads = (size_t)c->batch * c->n_kv_heads;
   size_t tcap = (size_t)c->max_quant_tokens;
   size_t ng = (size_t)(c->head_dim / c->group_size);
-  bytes[0] = heads * tcap * (D / 4);
+  bytes[0] = heads * tcap * k_row_bytes(c->k_levels);
   bytes[1] = heads * ((tcap + VBT - 1) / VBT) * v_block_bytes(c->v_levels);
   bytes[2] = heads * tcap * ng * 2 * meta_bytes(c->meta_format);
   bytes[3] = bytes[2];
@@ -177,9 +181,17 @@ void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
   bytes[5] = bytes[4];
 }
 
-int skvq_ref_k_get(const uint8_t *row, int p) { return (row[p >> 2] >> (2 * (p & 3))) & 3; }
+int skvq_ref_k_get(const uint8_t *row, int levels, int p) {
+  if (levels == 16) return (row[p >> 1] >> (4 * (p & 1))) & 15;
+  return (row[p >> 2] >> (2 * (p & 3))) & 3;
+}
 
-void skvq_ref_k_put(uint8_t *row, int p, int code) {
+void skvq_ref_k_put(uint8_t *row, int levels, int p, int code) {
+  if (levels == 16) {
+    int sh = 4 * (p & 1);
+    row[p >> 1] = (uint8_t)((row[p >> 1] & ~(15 << sh)) | (code << sh));
+    return;
+  }
   int sh = 2 * (p & 3);
   row[p >> 2] = (uint8_t)((row[p >> 2] & ~(3 << sh)) | (code << sh));
 }
@@ -210,6 +222,7 @@ int skvq_ref_v_get(const uint8_t *block, int levels, int s, int p) {
     unsigned f = bits_get(block + 13 * u, 13 * n, 13);
     return (int)((f / POW3[i]) % 3);
   }
+  if (levels == 16) return (int)bits_get(block + 32 * u, 32 * n + 16 * (i % 2) + 4 * (i / 2), 4);
   return (int)bits_get(block + 16 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2);
 }
 
@@ -221,6 +234,8 @@ void skvq_ref_v_put(uint8_t *block, int levels, int s, int p, int code) {
     unsigned old = (f / POW3[i]) % 3;
     f = f - old * POW3[i] + (unsigned)code * POW3[i];
     bits_put(block + 13 * u, 13 * n, 13, f);
+  } else if (levels == 16) {
+    bits_put(block + 32 * u, 32 * n + 16 * (i % 2) + 4 * (i / 2), 4, (unsigned)code);
   } else {
     bits_put(block + 16 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2,
              (unsigned)code);
@@ -252,9 +267,9 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
 
   int fmt = c->meta_format;
   encode_token(kx, c->perm_k + hk * D, c->clip_k + hk * ng, G, c->k_levels, fmt, codes, meta);
-  uint8_t *krow = buf->k_codes + (head * tcap + (size_t)t) * (D / 4);
-  memset(krow, 0, D / 4);
-  for (int p = 0; p < D; ++p) skvq_ref_k_put(krow, p, codes[p]);
+  uint8_t *krow = buf->k_codes + (head * tcap + (size_t)t) * k_row_bytes(c->k_levels);
+  memset(krow, 0, k_row_bytes(c->k_levels));
+  for (int p = 0; p < D; ++p) skvq_ref_k_put(krow, c->k_levels, p, codes[p]);
   for (int x = 0; x < 2 * ng; ++x)
     meta_store(buf->k_meta, (head * tcap + (size_t)t) * ng * 2 + x, meta[x], fmt);
 
@@ -269,7 +284,9 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
 
 static int check_config(const skvq_ref_config *c) {
   if (c->head_dim != D || c->group_size <= 0 || D % c->group_size) return -1;
-  if (c->k_levels != 4 || (c->v_levels != 4 && c->v_levels != 3)) return -2;
+  if ((c->k_levels != 4 && c->k_levels != 16) ||
+      (c->v_levels != 4 && c->v_levels != 3 && c->v_levels != 16))
+    return -2;
   if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1 ||
       c->n_sink < 0 || c->meta_format < 0 || c->meta_format > 2)
     return -1;
@@ -369,11 +386,11 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
     /* scores of packed rows: reordered query . dequantized reordered key */
     for (int64_t a = n_sink; a < first_win; ++a) {
       size_t t = (size_t)(a - S);
-      const uint8_t *row = buf->k_codes + (head * tcap + t) * (D / 4);
+      const uint8_t *row = buf->k_codes + (head * tcap + t) * k_row_bytes(c->k_levels);
       size_t mi = (head * tcap + t) * ng * 2;
       double dot = 0.0;
       for (int p = 0; p < D; ++p) {
-        double kd = (double)skvq_ref_k_get(row, p) *
+        double kd = (double)skvq_ref_k_get(row, c->k_levels, p) *
                         (double)meta_load(buf->k_meta, mi + 2 * (p / G), c->meta_format) +
                     (double)meta_load(buf->k_meta, mi + 2 * (p / G) + 1, c->meta_format);
         dot += qf[pk[p]] * kd;

@@ -38,7 +38,7 @@ extern "C" {
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128      */
   int32_t group_size;                             /* G, divides head_dim       */
-  int32_t k_levels, v_levels;                     /* 4 = 2-bit, 3 = "1.5-bit"  */
+  int32_t k_levels, v_levels;                     /* 16 = 4-bit, 4 = 2-bit, 3 = "1.5-bit" (keys: 16 or 4) */
   int32_t window;                                 /* W >= 1                    */
   int32_t n_sink;                                 /* S >= 0: tokens 0..S-1 are
                                                      never quantized           */
@@ -51,8 +51,8 @@ typedef struct {
 } skvq_ref_config;
 
 typedef struct {
-  uint8_t *k_codes;  /* [B][Hk][Tcap][32]                                      */
-  uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][1024 or 832]                    */
+  uint8_t *k_codes;  /* [B][Hk][Tcap][32 (2-bit) or 64 (4-bit)]                */
+  uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][832, 1024 or 2048]              */
   void *k_meta;      /* [B][Hk][Tcap][D/G][2] = (scale, zero), 4, 2 or 1 byte  */
   void *v_meta;      /* each (meta_format)                                     */
   uint16_t *k_win;   /* fp16 bits [B][Hk][W+S][D]: rows 0..W-1 are the ring    */
@@ -93,8 +93,8 @@ double skvq_ref_avg_bits(double code_bits, int meta_bits, int group_size);
 void skvq_ref_sizes(const skvq_ref_config *cfg, size_t bytes[6]);
 
 /* Packed-format accessors (the format is stated in the .c file). */
-int skvq_ref_k_get(const uint8_t *k_row, int p);
-void skvq_ref_k_put(uint8_t *k_row, int p, int code);
+int skvq_ref_k_get(const uint8_t *k_row, int levels, int p);
+void skvq_ref_k_put(uint8_t *k_row, int levels, int p, int code);
 int skvq_ref_v_get(const uint8_t *v_block, int levels, int t_in_block, int p);
 void skvq_ref_v_put(uint8_t *v_block, int levels, int t_in_block, int p, int code);
 

@@ -65,8 +65,8 @@ def lib():
         _lib.skvq_ref_e4m3_to_float.argtypes = [C.c_uint8]
         _lib.skvq_ref_round_meta.restype = C.c_float
         _lib.skvq_ref_round_meta.argtypes = [C.c_float, C.c_int]
-        _lib.skvq_ref_k_get.argtypes = [C.c_void_p, C.c_int]
-        _lib.skvq_ref_k_put.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        _lib.skvq_ref_k_get.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        _lib.skvq_ref_k_put.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
         _lib.skvq_ref_k_put.restype = None
         _lib.skvq_ref_v_get.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
         _lib.skvq_ref_v_put.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
@@ -126,7 +126,7 @@ def encode_group(xp: np.ndarray, alpha: float, levels: int, meta: str = "f32"):
 
 
 def levels_of(bits: float) -> int:
-    return {2.0: 4, 1.5: 3}[float(bits)]
+    return {4.0: 16, 2.0: 4, 1.5: 3}[float(bits)]
 
 
 class OracleCache:
@@ -151,8 +151,9 @@ class OracleCache:
         ng = HEAD_DIM // group_size
         heads = batch * n_kv_heads
         nblk = (max_quant_tokens + VBLOCK - 1) // VBLOCK
-        vb = 832 if levels_of(v_bits) == 3 else 1024
-        self.k_codes = np.full((batch, n_kv_heads, max_quant_tokens, 32), fill, np.uint8)
+        vb = {3: 832, 4: 1024, 16: 2048}[levels_of(v_bits)]
+        kb = {4: 32, 16: 64}[levels_of(k_bits)]
+        self.k_codes = np.full((batch, n_kv_heads, max_quant_tokens, kb), fill, np.uint8)
         self.v_codes = np.full((batch, n_kv_heads, nblk, vb), fill, np.uint8)
         mdt = META_DTYPES[META_FORMATS[meta]]   # fp8 values are kept as their bytes
         self.meta = meta
@@ -216,7 +217,7 @@ class OracleCache:
     # format accessors, for tests that look inside the packed buffers
     def k_code(self, b, h, t, p) -> int:
         row = self.k_codes[b, h, t]
-        return int(lib().skvq_ref_k_get(_ptr(row), p))
+        return int(lib().skvq_ref_k_get(_ptr(row), self.cfg.k_levels, p))
 
     def v_code(self, b, h, t, p) -> int:
         blk = self.v_codes[b, h, t // VBLOCK]

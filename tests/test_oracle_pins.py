@@ -56,12 +56,17 @@ def test_encoder_hand_derived_values(oracle):
     # three levels ("1.5-bit" reading): top code 2, h = (2 - 0)/2 = 1
     c, h, z = oracle.encode_group(np.array([0, 0.5, 1, 1.5, 2], np.float32), 1.0, 3)
     assert list(c) == [0, 0, 1, 2, 2] and h == 1.0 and z == 0.0
+    # N = 4: sixteen levels, h = (15 - 0)/15 = 1; 7.5 and 8.5 both tie to 8; alpha = 0.5 clamps the top half
+    c, h, z = oracle.encode_group(np.array([0, 7.5, 8.5, 11, 15], np.float32), 1.0, 16)
+    assert list(c) == [0, 8, 8, 11, 15] and h == 1.0 and z == 0.0
+    c, h, z = oracle.encode_group(np.array([0, 1.25, 6, 15, 30], np.float32), 0.5, 16)
+    assert h == 1.0 and z == 0.0 and list(c) == [0, 1, 6, 15, 15]
     # both ends are scaled by alpha (Eq. 2 and Algorithm 1 agree): all-positive group
     c, h, z = oracle.encode_group(np.array([4, 8, 16], np.float32), 0.5, 4)
     assert z == 2.0 and h == (8.0 - 2.0) / 3 and list(c) == [1, 3, 3]
 
 
-@pytest.mark.parametrize("levels", [4, 3])
+@pytest.mark.parametrize("levels", [4, 3, 16])
 def test_encoder_error_bound_and_clipping(oracle, levels):
     rng = np.random.default_rng(11 + levels)
     top = levels - 1
@@ -82,7 +87,7 @@ def test_encoder_error_bound_and_clipping(oracle, levels):
         assert h == np.float32(np.float32(a32 * x.max()) - np.float32(a32 * x.min())) / np.float32(top)
 
 
-@pytest.mark.parametrize("levels", [4, 3])
+@pytest.mark.parametrize("levels", [4, 3, 16])
 def test_encoder_picks_the_nearest_level(oracle, levels):
     """Brute force: among all codes the chosen one is nearest to x (exact arithmetic)."""
     rng = np.random.default_rng(23 + levels)
@@ -96,7 +101,7 @@ def test_encoder_picks_the_nearest_level(oracle, levels):
         assert np.all(chosen <= best + 1e-6 * h)
 
 
-@pytest.mark.parametrize("levels", [4, 3])
+@pytest.mark.parametrize("levels", [4, 3, 16])
 def test_encoder_lossless_on_a_grid_and_power_of_two_scaling(oracle, levels):
     rng = np.random.default_rng(31 + levels)
     top = levels - 1
@@ -145,14 +150,54 @@ def test_average_bits_match_the_paper(oracle):
 def test_k_row_layout_is_position_p_at_bit_2p(oracle):
     for p in range(D):
         row = np.zeros(32, np.uint8)
-        oracle.lib().skvq_ref_k_put(row.ctypes.data, p, 3)
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, 4, p, 3)
         assert int.from_bytes(row.tobytes(), "little") == 3 << (2 * p)
-        assert oracle.lib().skvq_ref_k_get(row.ctypes.data, p) == 3
+        assert oracle.lib().skvq_ref_k_get(row.ctypes.data, 4, p) == 3
     rng = np.random.default_rng(3)
     row = rng.integers(0, 256, 32, dtype=np.uint8)
     big = int.from_bytes(row.tobytes(), "little")
-    assert [oracle.lib().skvq_ref_k_get(row.ctypes.data, p) for p in range(D)] == \
+    assert [oracle.lib().skvq_ref_k_get(row.ctypes.data, 4, p) for p in range(D)] == \
            [(big >> (2 * p)) & 3 for p in range(D)]
+
+
+def test_k_row_4bit_layout_is_position_p_at_bit_4p(oracle):
+    for p in range(D):
+        row = np.zeros(64, np.uint8)
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, 16, p, 15)
+        assert int.from_bytes(row.tobytes(), "little") == 15 << (4 * p)
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, 16, p, 9)      # overwrite, not OR
+        assert int.from_bytes(row.tobytes(), "little") == 9 << (4 * p)
+        assert oracle.lib().skvq_ref_k_get(row.ctypes.data, 16, p) == 9
+    rng = np.random.default_rng(5)
+    row = rng.integers(0, 256, 64, dtype=np.uint8)
+    big = int.from_bytes(row.tobytes(), "little")
+    assert [oracle.lib().skvq_ref_k_get(row.ctypes.data, 16, p) for p in range(D)] == \
+           [(big >> (4 * p)) & 15 for p in range(D)]
+
+
+def test_v_block_4bit_layout_is_a_bijection_with_token_neighbours(oracle):
+    seen = 0
+    for s in range(32):
+        for p in range(D):
+            blk = np.zeros(2048, np.uint8)
+            oracle.lib().skvq_ref_v_put(blk.ctypes.data, 16, s, p, 15)
+            big = int.from_bytes(blk.tobytes(), "little")
+            assert bin(big).count("1") == 4 and not (big & seen)
+            seen |= big
+            # unit u = 16*(s/8) + p%16 of 32 bytes, one dword per n = p/16; tokens 2m and 2m+1
+            # sit 16 bits apart in it
+            u, n, i = 16 * (s // 8) + p % 16, p // 16, s % 8
+            assert big == 15 << (256 * u + 32 * n + 16 * (i % 2) + 4 * (i // 2))
+            assert oracle.lib().skvq_ref_v_get(blk.ctypes.data, 16, s, p) == 15
+    assert seen == (1 << 16384) - 1
+    rng = np.random.default_rng(6)
+    codes = rng.integers(0, 16, (32, D))
+    blk = np.zeros(2048, np.uint8)
+    for s in range(32):
+        for p in range(D):
+            oracle.lib().skvq_ref_v_put(blk.ctypes.data, 16, s, p, int(codes[s, p]))
+    got = [[oracle.lib().skvq_ref_v_get(blk.ctypes.data, 16, s, p) for p in range(D)] for s in range(32)]
+    assert np.array_equal(np.array(got), codes)
 
 
 def test_v_block_2bit_layout_is_a_bijection_with_token_neighbours(oracle):
@@ -202,6 +247,11 @@ def test_bytes_per_token_match_the_byte_model(oracle):
     c2 = oracle.OracleCache(1, 32, 8, 32, 2.0, 128, 4096, perm, perm, np.ones((8, 4), np.float32),
                             np.ones((8, 4), np.float32))
     assert sum(c2.sizes[:4]) / (8 * 4096) == 32 + 32 + 32 + 32
+    # 4-bit keys and values, group 64, FP8 (scale, zero): Table 1's 4.25 average bits
+    two = np.ones((8, 2), np.float32)
+    c3 = oracle.OracleCache(1, 32, 8, 64, 4.0, 128, 4096, perm, perm, two, two, k_bits=4.0, meta="e4m3")
+    assert sum(c3.sizes[:4]) / (8 * 4096) == 64 + 64 + 4 + 4
+    assert sum(c3.sizes[:4]) * 8 / (8 * 4096 * 2 * D) == 4.25
 
 
 # ------------------------------------------------------------ attention ----
@@ -259,19 +309,20 @@ def test_window_only_cache_is_textbook_attention(oracle):
             assert np.array_equal(c.v_win[:, :, a % W].view(np.float16), v[:, :, a])
 
 
-@pytest.mark.parametrize("v_bits,G", [(2.0, 128), (1.5, 128), (1.5, 32), (2.0, 64)])
-def test_lossless_cache_equals_textbook_attention(oracle, v_bits, G):
+@pytest.mark.parametrize("k_bits,v_bits,G", [(2.0, 2.0, 128), (2.0, 1.5, 128), (2.0, 1.5, 32), (2.0, 2.0, 64),
+                                             (4.0, 4.0, 128), (4.0, 4.0, 32), (4.0, 2.0, 64), (2.0, 4.0, 128)])
+def test_lossless_cache_equals_textbook_attention(oracle, k_bits, v_bits, G):
     """Data that Eq. 2 represents exactly (alpha = 1) makes the quantized path exact, so the whole
     chain reorder -> encode -> pack -> unpack -> dequantize -> Eq. 1 must reproduce the library's
     attention on the ORIGINAL tensors, for any permutation (Eq. 1's invariance)."""
     rng = np.random.default_rng(200 + G)
     B, Hq, Hk, W, T = 1, 4, 2, 8, 77
     pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
-    k = grid_data(rng, (B, Hk, T), G, 4, pk)
+    k = grid_data(rng, (B, Hk, T), G, oracle.levels_of(k_bits), pk)
     v = grid_data(rng, (B, Hk, T), G, oracle.levels_of(v_bits), pv)
     q = rng.standard_normal((B, Hq, D)).astype(np.float16)
     ones = np.ones((Hk, D // G), np.float32)
-    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 96, pk, pv, ones, ones, sm_scale=0.05)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 96, pk, pv, ones, ones, sm_scale=0.05, k_bits=k_bits)
     assert c.prefill(k, v) == 0 and c.n_quant == T - W
     out = c.decode(q)
     ref = sdpa64(q, k, v, 0.05)
@@ -305,7 +356,10 @@ def numpy_dequantize(c, T):
     kq = np.zeros((B, Hk, nq, D))
     vq = np.zeros((B, Hk, nq, D))
     p = np.arange(D)
-    kc = (c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3
+    if c.cfg.k_levels == 16:
+        kc = (c.k_codes[:, :, :nq, p // 2] >> (4 * (p % 2))) & 15
+    else:
+        kc = (c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3
     ks = c.k_meta[:, :, :nq, p // G, 0].astype(np.float64)
     kz = c.k_meta[:, :, :nq, p // G, 1].astype(np.float64)
     kd = kc * ks + kz
@@ -322,6 +376,9 @@ def numpy_dequantize(c, T):
                     if c.cfg.v_levels == 3:
                         unit = int.from_bytes(blk[13 * u:13 * u + 13].tobytes(), "little")
                         vc[b, h, t, pp] = ((unit >> (13 * n)) & 0x1FFF) // 3 ** i % 3
+                    elif c.cfg.v_levels == 16:
+                        word = int.from_bytes(blk[32 * u + 4 * n:32 * u + 4 * n + 4].tobytes(), "little")
+                        vc[b, h, t, pp] = (word >> (16 * (i % 2) + 4 * (i // 2))) & 15
                     else:
                         unit = int.from_bytes(blk[16 * u:16 * u + 16].tobytes(), "little")
                         vc[b, h, t, pp] = (unit >> (32 * (n // 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i // 2))) & 3
@@ -332,8 +389,9 @@ def numpy_dequantize(c, T):
     return kq, vq
 
 
-@pytest.mark.parametrize("v_bits,G", [(1.5, 128), (2.0, 32), (1.5, 64)])
-def test_lossy_cache_equals_dequantize_then_textbook_attention(oracle, v_bits, G):
+@pytest.mark.parametrize("k_bits,v_bits,G", [(2.0, 1.5, 128), (2.0, 2.0, 32), (2.0, 1.5, 64), (4.0, 4.0, 128),
+                                             (4.0, 4.0, 32), (4.0, 2.0, 64)])
+def test_lossy_cache_equals_dequantize_then_textbook_attention(oracle, k_bits, v_bits, G):
     rng = np.random.default_rng(400 + G)
     B, Hq, Hk, W, T = 2, 4, 2, 8, 45
     k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
@@ -342,7 +400,7 @@ def test_lossy_cache_equals_dequantize_then_textbook_attention(oracle, v_bits, G
     pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
     ck = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
     cv = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
-    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, k_bits=k_bits)
     c.prefill(k, v)
     out = c.decode(q)
     kq, vq = numpy_dequantize(c, T)
@@ -354,7 +412,7 @@ def test_lossy_cache_equals_dequantize_then_textbook_attention(oracle, v_bits, G
     err = np.abs(kq - k[:, :, :T - W].astype(np.float64))
     assert err.max() < np.abs(k.astype(np.float64)).max()
     # uniform weights (softmax scale 0): output is the plain mean of the decoded values
-    c0 = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, sm_scale=0.0)
+    c0 = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, sm_scale=0.0, k_bits=k_bits)
     c0.prefill(k, v)
     out0 = c0.decode(q)
     mean = vfull.mean(axis=2).repeat(Hq // Hk, axis=1)
@@ -552,7 +610,7 @@ def test_e4m3_narrowing_is_nearest_even_and_saturates(oracle):
 
 
 @pytest.mark.parametrize("meta", ["f16", "e4m3"])
-@pytest.mark.parametrize("levels", [4, 3])
+@pytest.mark.parametrize("levels", [4, 3, 16])
 def test_encoder_with_compact_meta_uses_the_stored_values(oracle, meta, levels):
     """scale and zero come back exactly representable in the storage format, and every code is
     the nearest level of the grid THOSE values span (so decoding, which only sees them, is
