@@ -51,10 +51,12 @@ typedef enum {
   SKVQ_ERR_HIP = -5          /* a HIP runtime call failed; see skvq_last_error */
 } skvq_status;
 
-/* Code widths, named by twice the nominal bits (Abstract: 2-bit keys, 1.5-bit values). */
+/* Code widths; the value is the number of levels (Abstract: 2-bit keys, 1.5-bit values;
+ * Table 1 also runs 4-bit keys and values). */
 typedef enum {
-  SKVQ_BITS_2 = 4,  /* four levels, codes 0..3 */
-  SKVQ_BITS_1P5 = 3 /* three levels, codes 0..2 (this build's reading of "1.5-bit") */
+  SKVQ_BITS_4 = 16,  /* sixteen levels, codes 0..15 */
+  SKVQ_BITS_2 = 4,   /* four levels, codes 0..3 */
+  SKVQ_BITS_1P5 = 3  /* three levels, codes 0..2 (this build's reading of "1.5-bit") */
 } skvq_bits;
 
 /* Storage of (scale, zero): Section 4.1 keeps them in FP8 (E4M3); Section 4.3 also counts
@@ -72,8 +74,8 @@ typedef struct {
   int32_t n_kv_heads;   /* Hk                                                             */
   int32_t head_dim;     /* D, must be 128                                                 */
   int32_t group_size;   /* G in {32, 64, 128}: consecutive REORDERED channels of a token  */
-  int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2 only                              */
-  int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_2 or SKVQ_BITS_1P5                */
+  int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2 or SKVQ_BITS_4                    */
+  int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_1P5, SKVQ_BITS_2 or SKVQ_BITS_4   */
   int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
   int32_t n_sink;       /* S >= 0: the filter rule of Section 3.2 / Algorithm 1 that keeps
                            the first S tokens (attention sinks) fp16 for ever; 0 = off    */
@@ -87,11 +89,13 @@ typedef struct {
 } skvq_config;
 
 /* DEVICE buffers of one layer's cache; byte sizes come from skvq_sizes(), in this order.
- *   k_codes   u8  [B][Hk][Tcap][32]      row t: code of position p in byte p/4, bits 2(p%4)..
- *   v_codes   u8  [B][Hk][ceil(Tcap/32)][1024 | 832]   blocks of 32 tokens, token-minor:
+ *   k_codes   u8  [B][Hk][Tcap][32 | 64]  row t, 2-bit: code of position p in byte p/4, bits
+ *             2(p%4).. ; 4-bit: in byte p/2, bits 4(p%2)..
+ *   v_codes   u8  [B][Hk][ceil(Tcap/32)][832 | 1024 | 2048]   blocks of 32 tokens, token-minor:
  *             token slot s=t%32 -> kb=s/8, i=s%8 ; position p -> n=p/16, j=p%16 ; unit u=16kb+j
  *             2-bit  : unit = 16 B little-endian, code(n,i) at bit 32(n/2)+16(i%2)+8(n%2)+2(i/2)
  *             3-level: unit = 13 B little-endian, field n = bits [13n,13n+13) = sum_i code(n,i)*3^i
+ *             4-bit  : unit = 32 B little-endian, code(n,i) at bit 32n+16(i%2)+4(i/2)
  *             a block is zero-filled when its first token is stored
  *   k_meta    [B][Hk][Tcap][D/G][2]      (scale, zero) of Eq. 2, zero = alpha*min, each an
  *   v_meta    [B][Hk][Tcap][D/G][2]      fp32, fp16 or FP8 E4M3 value (meta_format)

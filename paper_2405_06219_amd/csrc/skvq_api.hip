@@ -35,8 +35,9 @@ int check_config(const skvq_config *c) {
   if (c->n_q_heads / c->n_kv_heads > 8) return SKVQ_ERR_UNSUPPORTED;
   if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128)
     return SKVQ_ERR_UNSUPPORTED;
-  if (c->k_bits != SKVQ_BITS_2) return SKVQ_ERR_UNSUPPORTED;
-  if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5) return SKVQ_ERR_UNSUPPORTED;
+  if (c->k_bits != SKVQ_BITS_2 && c->k_bits != SKVQ_BITS_4) return SKVQ_ERR_UNSUPPORTED;
+  if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5 && c->v_bits != SKVQ_BITS_4)
+    return SKVQ_ERR_UNSUPPORTED;
   if (c->meta_format != SKVQ_META_F32 && c->meta_format != SKVQ_META_F16 &&
       c->meta_format != SKVQ_META_FP8_E4M3)
     return SKVQ_ERR_UNSUPPORTED;
@@ -68,8 +69,8 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
   const size_t heads = (size_t)c->batch * c->n_kv_heads;
   const size_t tcap = (size_t)c->max_quant_tokens;
   const size_t ng = kD / c->group_size;
-  const size_t vb = c->v_bits == SKVQ_BITS_1P5 ? kTernaryBlockBytes : kTwoBitBlockBytes;
-  bytes[0] = heads * tcap * (kD / 4);
+  const size_t vb = v_block_bytes_of(c->v_bits);  // skvq_bits values are level counts
+  bytes[0] = heads * tcap * k_row_bytes_of(c->k_bits);
   bytes[1] = heads * ((tcap + kVBlock - 1) / kVBlock) * vb;
   const size_t es = c->meta_format == SKVQ_META_FP8_E4M3 ? 1 : c->meta_format == SKVQ_META_F16 ? 2 : 4;
   bytes[2] = heads * tcap * ng * 2 * es;
@@ -157,8 +158,10 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.W = cfg->window;
   L.S = cfg->n_sink;
   L.meta_fmt = cfg->meta_format;
-  L.v_levels = cfg->v_bits == SKVQ_BITS_1P5 ? 3 : 4;
-  L.v_block_bytes = L.v_levels == 3 ? kTernaryBlockBytes : kTwoBitBlockBytes;
+  L.k_levels = cfg->k_bits;
+  L.k_row_bytes = k_row_bytes_of(L.k_levels);
+  L.v_levels = cfg->v_bits;
+  L.v_block_bytes = v_block_bytes_of(L.v_levels);
   L.Tcap = cfg->max_quant_tokens;
   L.n_vblocks = (L.Tcap + kVBlock - 1) / kVBlock;
   L.sm_scale = cfg->sm_scale > 0.0f ? cfg->sm_scale : 1.0f / std::sqrt((float)kD);

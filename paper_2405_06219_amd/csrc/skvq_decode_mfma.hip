@@ -1,794 +1,33 @@
-// Matrix-core kernel of skvq_decode_attention for gfx950: packed chunks and the fp16 tokens
-// (attention sinks, window) in one launch, one partial per chunk.  Templated on the query
-// heads a workgroup serves (1, 2, 4), the V format, the (scale, zero) format and the groups
-// per head (1, 2, 4).
-// (Merging the partials inside this launch was tried and dropped: the device-scope fences it
-// needs write back and invalidate a whole L2 each, 25 us over 256 workgroups.)
-//
-// One workgroup of 8 wavefronts per chunk (one per compute unit when the cache is long
-// enough).  Per wavefront, per tile of 64 packed tokens:
-//   QK   S^T[head][token] by 32 v_mfma_f32_4x4x4_16b_f16 (16 independent 4x4 blocks, lane =
-//        token): the B operand is the lane's own 32-byte key row, its 2-bit codes turned into
-//        fp16 SUBNORMALS by one AND each (a code c sitting at mantissa bit s is the fp16 value
-//        c*2^(s-24)); the A operand is the reordered query, pre-multiplied by the matching
-//        power of two, held in registers.  One accumulator per group; afterwards lane l holds
-//        the scores of token l for the (up to) four heads.
-//   softmax  lazily re-referenced online softmax in the exp2 domain: the running reference m
-//        only moves when a score exceeds it by more than 2^6 (wave-uniform branch).
-//   PV   O^T[channel][head] by 16 v_mfma_f32_16x16x32_f16: the A operand is the V block unit
-//        that the lane loaded (8 tokens x 8 channels, token-minor; a 3-level field is the index
-//        of a 16-byte table entry in LDS that IS the operand), the B operand holds p*scale
-//        (one per group) split into a high and a low fp16 part (two columns per head) so that
-//        the weights keep ~22 bits.
-// The zero-points never enter the matrix products: sum_p q_p (s c_p + z) = s sum q c + z sum q
-// and sum_t w_t (s_t c + z_t) = sum (w_t s_t) c + sum w_t z_t, per group.
-//
-// The matrix core accumulates products of subnormal inputs as if their mantissa were full, so
-// a code at mantissa bit s costs about (10 - s) bits of the accumulator's precision; every
-// code is therefore moved to bit 4, 6 or 8 before it is masked out.
+// Dispatcher of the matrix-core decode kernels over the (K format, V format) pairs; each pair's
+// kernels are compiled in a translation unit of their own (skvq_decode_mfma_inst.hip).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
-
-#include <math.h>
 
 #include "skvq_internal.h"
 
 namespace skvq {
-#ifdef SKVQ_TIMING
-__device__ unsigned long long skvq_timing[16 * 4096];
-#define SKVQ_STAMP(slot)                                                                    \
-  if (threadIdx.x == 0)                                                                     \
-  skvq_timing[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + (slot)] = \
-      __builtin_amdgcn_s_memrealtime()
-__device__ unsigned long long skvq_timing_w[32 * 4096];
-#define SKVQ_WSTAMP(slot)                                                                   \
-  if ((threadIdx.x & 63) == 0)                                                              \
-  skvq_timing_w[32 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + 2 * (threadIdx.x >> 6) + (slot)] = \
-      __builtin_amdgcn_s_memrealtime()
-#else
-#define SKVQ_STAMP(slot)
-#define SKVQ_WSTAMP(slot)
-#endif
-namespace {
 
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
-typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
-typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
-struct __attribute__((aligned(4))) Unit16 {  // a 16-byte load that is only 4-byte aligned
-  unsigned x, y, z, w;
-};
-
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kRefSlack = 6.0f;    // scores may exceed the running reference by 2^6
-constexpr float kVsTarget = 256.0f;  // max(v scale)*beta is brought below this ...
-constexpr float kVsLimit = 512.0f;   // ... and re-normalised when a token exceeds this
-constexpr unsigned kM4 = 0x00300030u, kM6 = 0x00c000c0u, kM8 = 0x03000300u;
-
-__device__ __forceinline__ float wave_max(float v) {
-  for (int off = 32; off; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-  for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Cross-lane moves inside a row of 16 lanes (data-parallel primitives: no LDS round trip).
-// A source lane outside the row reads as 0.
-template <int CTRL>
-__device__ __forceinline__ float row_move(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
-}
-constexpr int kQuadSwap1 = 0xB1;       // quad_perm [1,0,3,2]
-constexpr int kQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]
-constexpr int kRowHalfMirror = 0x141;  // lane i reads lane 7 - i of its half row
-constexpr int kRowMirror = 0x140;      // lane i reads lane 15 - i of its row
-constexpr int kRowShl = 0x100;         // + n: lane i reads lane i + n of its row
-// Sum over the wavefront, returned in every lane (as a wave-uniform value).
-__device__ __forceinline__ float wave_sum_fast(float v) {
-  v += row_move<kQuadSwap1>(v);
-  v += row_move<kQuadSwap2>(v);
-  v += row_move<kRowHalfMirror>(v);
-  v += row_move<kRowMirror>(v);  // every lane: the sum of its row
-  return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0)) +
-          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16))) +
-         (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32)) +
-          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48)));
-}
-
-__device__ __forceinline__ half4_t h4(unsigned a, unsigned b) { return __builtin_bit_cast(half4_t, uint2_t{a, b}); }
-
-// Key dword (16 codes, position e at bit 2e) -> four B operands of the 4x4x4 product.
-// Operand x holds positions e = {2x, 2x+8, 2x+1, 2x+9}, at mantissa bits
-// {4,4,6,6}, {4,4,6,6}, {8,8,4,4}, {6,6,8,8} for x = 0..3.
-__device__ __forceinline__ void unpack_k(unsigned w, half4_t b[4]) {
-  const unsigned wl = w << 4, wr = w >> 6;
-  b[0] = h4(wl & kM4, wl & kM6);
-  b[1] = h4(w & kM4, w & kM6);
-  b[2] = h4(w & kM8, wr & kM4);
-  b[3] = h4(wr & kM6, wr & kM8);
-}
-
-// For reordered position p: which of the 32 products, which k slot of it, and the mantissa
-// bit the key code sits at there.
-__device__ __forceinline__ void k_slot_of(int p, int &step, int &kslot, int &shift) {
-  const int d = p >> 4, e = p & 15, lo = e & 7, hi = e >> 3;  // e = lo + 8*hi
-  step = 4 * d + (lo >> 1);
-  kslot = 2 * (lo & 1) + hi;
-  const int tab = 0x86486464;  // bit position of code lo (and lo+8), one nibble each
-  shift = (tab >> (4 * lo)) & 15;
-}
-
-// Eight tokens of one channel -> A operand of the 16x16x32 product: register m holds tokens
-// 2m (low half) and 2m+1 (high half); 2-bit units: at mantissa bit {4, 6, 8, 8}[m] (masked out
-// of the unit's field), 3-level units: all at bit 8 (read from the table).
-// From a 2-bit unit field (pair m at bit 2m of each half; `f` has the field in bits 0..7):
-__device__ __forceinline__ half8_t unpack_v_field(unsigned f) {
-  const unsigned a = f << 4, b = f << 2;
-  return __builtin_bit_cast(half8_t, uint4_t{a & kM4, a & kM6, a & kM8, b & kM8});
-}
-
-constexpr int kNW = 8;              // wavefronts per workgroup (2 per SIMD: 256 registers each)
-constexpr int kThreads = 64 * kNW;
-constexpr int kOldShare = 3, kYoungShare = 2;                        // tiles per deal: waves 0..3 / 4..7
-constexpr int kDealPeriod = (kNW / 2) * (kOldShare + kYoungShare);  // tiles per deal
-constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
-constexpr int kRingSlice = 4;       // ring tokens per slice (the slice code reads four rows of 16 lanes)
-
-constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumulator columns over the banks
-
-template <int R, bool TERNARY, int NG>
-struct Smem {
-  // 13-bit field -> the A operand of its eight tokens (104976 bytes, built by the workgroup
-  // from the two 81-entry tables: four base-3 digits -> the operand halves of tokens 0..3 / 4..7)
-  uint4_t lut[TERNARY ? 6561 : 1];
-  uint2_t lut4[TERNARY ? 2 : 1][81];
-  // per wave: the weights of the current tile, [block][group][column][token slot]; after the
-  // wave's last tile the same bytes stage its O^T, [head][reordered position]
-  union WaveBuf {
-    _Float16 pbuf[2][NG][2 * R][32];
-    float stage[R][kCombStride];
-  } wb[kNW];
-  float qraw[4][kD];                   // the query heads as loaded (rows >= R are zero)
-  _Float16 qa[32][4][4];               // A operands of the score product: [step][head][k slot]
-  float qpart[4][8];                   // per head: sums of the reordered query over 16 positions each
-  // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
-  // tiles (w*) and for the ring slices (r*) of the wave
-  float wm[kNW][R], wl[kNW][R], wz[kNW][R][NG], rm[kNW][R], rl[kNW][R];
-  float ring_o[kNW][R][kD];            // per wave: its ring slices' outputs, original channel order
-};
-
-// One 4-channel step of the score product.  The A operand of step ST lives in lanes
-// 4*(ST%16) .. 4*(ST%16)+3 of register pair ST/16 and is broadcast to all 16 blocks.
-template <int ST>
-__device__ __forceinline__ float4_t qk_step(half4_t a_lo, half4_t a_hi, half4_t b, float4_t d) {
-  if constexpr (ST < 16)
-    return __builtin_amdgcn_mfma_f32_4x4x4f16(a_lo, b, d, 4, ST, 0);
-  else
-    return __builtin_amdgcn_mfma_f32_4x4x4f16(a_hi, b, d, 4, ST - 16, 0);
-}
-template <int D>
-__device__ __forceinline__ float4_t qk_dword(unsigned w, half4_t a_lo, half4_t a_hi, float4_t d) {
-  half4_t bop[4];
-  unpack_k(w, bop);
-  d = qk_step<4 * D + 0>(a_lo, a_hi, bop[0], d);
-  d = qk_step<4 * D + 1>(a_lo, a_hi, bop[1], d);
-  d = qk_step<4 * D + 2>(a_lo, a_hi, bop[2], d);
-  d = qk_step<4 * D + 3>(a_lo, a_hi, bop[3], d);
-  return d;
-}
-
-// A stored (scale, zero) pair as one lane loads it, and its value.
-template <int META>
-struct MetaWord {
-  typedef float2 type;
-};
-template <>
-struct MetaWord<SKVQ_META_F16> {
-  typedef unsigned type;
-};
-template <>
-struct MetaWord<SKVQ_META_FP8_E4M3> {
-  typedef unsigned short type;
-};
-__device__ __forceinline__ float2 meta_value(float2 w) { return w; }
-__device__ __forceinline__ float2 meta_value(unsigned w) {
-  const __half2 h = __builtin_bit_cast(__half2, w);
-  return make_float2(__low2float(h), __high2float(h));
-}
-__device__ __forceinline__ float2 meta_value(unsigned short w) {  // FP8 E4M3: conversion is exact
-  return make_float2(__builtin_amdgcn_cvt_f32_fp8((int)w, 0), __builtin_amdgcn_cvt_f32_fp8((int)w, 1));
-}
-
-// What one wavefront loads for one tile of 64 tokens.
-template <int META, int NG>
-struct alignas(sizeof(typename MetaWord<META>::type) * NG > 16 ? 16 : sizeof(typename MetaWord<META>::type) * NG)
-    MetaBlock {  // the NG pairs of one token
-  typename MetaWord<META>::type m[NG];
-};
-template <int META, int NG>
-struct TileData {
-  uint4_t k0, k1;                  // lane = token: its 32-byte key row
-  MetaBlock<META, NG> kmeta, vmeta;  // lane = token: (scale, zero) per group
-  Unit16 v0, v1;        // lane = unit of V block 2*tile and 2*tile+1
-};
-
-// What one wavefront loads for one slice of 4 fp16 ring tokens.
-struct RingData {
-  uint4_t k;      // lane (token = l/16, piece = l%16): 8 channels of the token's key row
-  unsigned v[4];  // lane = channel pair: the 4 tokens' values of channels 2l, 2l+1
-};
-
-template <int R, bool TERNARY, int META, int NG>
-__global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
-                                                                  long long T, long long nq, int n_sink,
-                                                                  int n_splits, int passes) {
-  // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
-  // head with more than four (or with three) query heads is served by `passes` workgroups per
-  // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
-  // heads are computed with a zero query and not stored).
-  //   Workgroup sp owns an even share of the packed 64-token tiles of
-  // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
-  // j = sp (mod n_splits), dealt the same way.
-  __shared__ Smem<R, TERNARY, NG> sm;
-  SKVQ_STAMP(0);
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sp = blockIdx.x, hk = blockIdx.y / passes, b = blockIdx.z;
-  const int head0 = (blockIdx.y % passes) * R;  // first of this workgroup's query heads, within the kv head's
-  const long long head = (long long)b * L.Hk + hk;
-  const float c = L.sm_scale * kLog2e;
-
-  // ---- this chunk, this wave's tiles ----
-  const int n_tiles = (int)((nq + 63) >> 6);
-  const int tile_begin = (int)(((long long)sp * n_tiles) / n_splits);
-  const int tile_end = (int)(((long long)(sp + 1) * n_tiles) / n_splits);
-
-  const uint8_t *kc = L.k_codes + head * L.Tcap * (kD / 4);
-  typedef TileData<META, NG> Tile;
-  typedef MetaBlock<META, NG> meta_block;
-  const meta_block *km = reinterpret_cast<const meta_block *>(L.k_meta) + head * L.Tcap;
-  const meta_block *vm = reinterpret_cast<const meta_block *>(L.v_meta) + head * L.Tcap;
-  const uint8_t *vc = L.v_codes + head * L.n_vblocks * L.v_block_bytes;
-  const int last_token = (int)(nq - 1);  // -1 when nothing is packed (then there are no tiles)
-  const int last_blk = last_token >> 5;
-  const int vbb = TERNARY ? kTernaryBlockBytes : kTwoBitBlockBytes;
-  const unsigned unit_off = TERNARY ? ((13 * lane) & ~3) : 16 * lane;
-  const int unit_sh = TERNARY ? ((13 * lane) & 3) : 0;
-  // 2-bit units: token slot i = lane%8 sits in register m = i/2 at bit {4,6,8,8}[m]: undo
-  // 2^(bit-4).  3-level units: every slot at bit 8.
-  const float kslot_scale =
-      TERNARY ? 1.f : ((lane >> 1) & 3) == 0 ? 1.f : ((lane >> 1) & 3) == 1 ? 0.25f : 0.0625f;
-
-  // Loads are issued unconditionally (a tile index past the end is redirected to the last
-  // tile, whose lines are in cache by then, and the data is ignored): the compiler can then
-  // count the loads in flight and wait for exactly the ones a tile needs.
-  const int safe_last_tile = n_tiles > 0 ? n_tiles - 1 : 0;
-  const int safe_last_token = last_token > 0 ? last_token : 0;
-  const int safe_last_blk = last_blk > 0 ? last_blk : 0;
-  auto load_tile = [&](int tile) {
-    Tile d;
-    if (tile > safe_last_tile) tile = safe_last_tile;
-    if (tile < 0) tile = 0;
-    int t = tile * 64 + lane;
-    if (t > safe_last_token) t = safe_last_token;  // only in the last tile; such lanes are masked below
-    const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * 32);
-    d.k0 = krow[0];
-    d.k1 = krow[1];
-    d.kmeta = km[t];
-    d.vmeta = vm[t];
-    const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
-    const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
-    d.v0 = *reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off);
-    d.v1 = *reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off);
-    return d;
-  };
-
-  // ---- the fp16 ring: slices of 4 tokens, slice j belongs to workgroup j % n_splits and to
-  //      the wave whose rank is (j / n_splits) % kRingWaves ----
-  // The fp16 tokens in token order: the n_sink sink rows (rows W.. of the ring buffers), then
-  // the window's tokens.
-  const int n_win = (int)(T - nq) - n_sink, W = L.W;
-  const int n_fp = n_sink + n_win;
-  const int n_slices = (n_fp + kRingSlice - 1) / kRingSlice;
-  const int ring_stride = n_splits * kRingWaves;
-  // the younger waves (which get fewer tiles) are first in line for ring slices
-  const int ring_rank = (wave + kNW / 2) % kNW;
-  const int ring_first = sp + n_splits * ring_rank;
-  const bool ring_owner = ring_first < n_slices;
-  const int slot0 = (int)((T - n_win) % W);  // ring row of the window's oldest token
-  const __half *kwin = L.k_win + head * (W + L.S) * kD;
-  const __half *vwin = L.v_win + head * (W + L.S) * kD;
-  auto ring_slot = [&](int t) {  // ring slot of ring token t (clamped to the last one)
-    if (t >= n_fp) t = n_fp - 1;
-    if (t < n_sink) return W + t;
-    int s = slot0 + t - n_sink;
-    return s >= W ? s - W : s;
-  };
-  auto load_ring = [&](int slice) {
-    RingData d;
-    d.k = reinterpret_cast<const uint4_t *>(kwin + (size_t)ring_slot(slice * kRingSlice + (lane >> 4)) * kD)[lane & 15];
-#pragma unroll
-    for (int k = 0; k < kRingSlice; ++k)
-      d.v[k] = reinterpret_cast<const unsigned *>(vwin + (size_t)ring_slot(slice * kRingSlice + k) * kD)[lane];
-    return d;
-  };
-
-  // ---- prologue: one memory round trip.  The small loads (query, permutations, table) are
-  //      issued BEFORE the tile loads: loads return in order, so the staging below only has to
-  //      wait for them and not for the two tiles of packed data behind them. ----
-  SKVQ_STAMP(4);
-  __half2 q2 = __floats2half2_rn(0.f, 0.f);
-  if (tid < 64 * R && head0 + (tid >> 6) < L.R)
-    q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * L.R + head0 + (tid >> 6)) * kD)[lane];
-  const int pk = L.perm_k[hk * kD + (tid & 127)];
-  const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
-  RingData ring = {};
-  if (ring_owner) ring = load_ring(ring_first);  // landed before the tile loop either way (see below)
-  asm volatile("" ::: "memory");
-  // three tile buffers used in turn (no register copies): while one tile is computed the
-  // next two are in flight
-  // The two wavefronts of a SIMD do not share it evenly: the older one (waves 0..3) is served
-  // first and gets through about three tiles while the younger one gets through two.  The
-  // tiles are dealt in that ratio (per 20 tiles: three to each older, two to each younger
-  // wave) so that both finish together.
-  const int share = wave < kNW / 2 ? kOldShare : kYoungShare;
-  const int deal_base = wave < kNW / 2 ? wave : kOldShare * (kNW / 2) + (wave - kNW / 2);
-  auto tile_of = [&](int n) {  // n-th tile of this wave
-    const int r = n / share;
-    return tile_begin + kDealPeriod * r + deal_base + (kNW / 2) * (n - share * r);
-  };
-  int n_a = 0, n_b = 1, n_c = 2;
-  int tile_a = tile_of(n_a), tile_b = tile_of(n_b), tile_c = tile_of(n_c);
-  Tile buf_a, buf_b, buf_c;
-  buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
-  if (TERNARY) {
-    // While the loads are in flight the workgroup builds the table: entry f (a base-3 number of
-    // eight digits, digit i = code of token i) is the operand itself, register m = codes of
-    // tokens 2m (low half) and 2m+1 (high half) as fp16 subnormals c * 2^(8-24).
-    if (tid < 162) {
-      const int half = tid >= 81, x = half ? tid - 81 : tid;
-      const unsigned d0 = x % 3, d1 = (x / 3) % 3, d2 = (x / 9) % 3, d3 = x / 27;
-      sm.lut4[half][x] = uint2_t{(d0 << 8) | (d1 << 24), (d2 << 8) | (d3 << 24)};
-    }
-    __syncthreads();
-    for (int e = tid; e < 6561; e += kThreads) {
-      const unsigned hi = e / 81u, lo = e - 81u * hi;
-      const uint2_t a = sm.lut4[0][lo], b2 = sm.lut4[1][hi];
-      sm.lut[e] = uint4_t{a.x, a.y, b2.x, b2.y};
-    }
-  }
-  {
-    if (tid < 256) {
-      sm.qraw[tid >> 6][2 * lane] = __low2float(q2);
-      sm.qraw[tid >> 6][2 * lane + 1] = __high2float(q2);
-    }
-    SKVQ_STAMP(5);
-    SKVQ_STAMP(6);
-    __syncthreads();
-    asm volatile("" ::: "memory");
-    buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
-    SKVQ_STAMP(10);
-    if (tid < 256) {
-#pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {  // thread (p = tid%128, heads tid/128 and tid/128 + 2)
-        const int row = (tid >> 7) + 2 * rr, p = tid & 127;
-        int step, kslot, shift;
-        k_slot_of(p, step, kslot, shift);
-        const float x = sm.qraw[row][pk];
-        sm.qa[step][row][kslot] = (_Float16)ldexpf(x, 8 - shift);  // exact: a power of two
-        // sum of the reordered query over the 16 positions of this row of lanes
-        float s16 = x;
-        s16 += row_move<kQuadSwap1>(s16);
-        s16 += row_move<kQuadSwap2>(s16);
-        s16 += row_move<kRowHalfMirror>(s16);
-        s16 += row_move<kRowMirror>(s16);
-        if ((lane & 15) == 0) sm.qpart[row][p >> 4] = s16;
-      }
-    }
-    __syncthreads();
-    SKVQ_STAMP(11);
-  }
-  // lane l supplies row l%4 (= head) of step l/4 (first register pair) and 16 + l/4 (second)
-  const half4_t qop_lo = *reinterpret_cast<const half4_t *>(sm.qa[lane >> 2][lane & 3]);
-  const half4_t qop_hi = *reinterpret_cast<const half4_t *>(sm.qa[16 + (lane >> 2)][lane & 3]);
-  // Per group: sm_scale*log2(e) * sum of the reordered query (qsc), and the start value of the
-  // score accumulators, -1.5*sum(q) in the product's units (2^-16): the products then sum
-  // q*(c - 1.5), centred codes, which keeps both halves of
-  // scale*sum q(c-1.5) + (zero+1.5 scale)*sum q  small.
-  float qsc[R][NG];
-  float4_t dinit[NG];
-#pragma unroll
-  for (int g = 0; g < NG; ++g)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float sum = 0.f;
-#pragma unroll
-      for (int x = 0; x < 8 / NG; ++x) sum += sm.qpart[r][g * (8 / NG) + x];
-      if (r < R) qsc[r][g] = c * sum;
-      dinit[g][r] = -1.5f * sum * (1.0f / 65536.0f);
-    }
-
-  // ---- ring slices of this wave (plain vector arithmetic, wave-local) ----
-  if (ring_owner) {
-    float rm[R], rl[R], ro[R][2];  // reference, sum of weights, outputs
-#pragma unroll
-    for (int r = 0; r < R; ++r) rm[r] = -INFINITY, rl[r] = 0.f, ro[r][0] = ro[r][1] = 0.f;
-    auto ring_slice = [&](const RingData &rd, const int slice) {
-      const int tk = lane >> 4, pc = lane & 15;  // token of the slice, 8-channel piece of its row
-      const bool valid = slice * kRingSlice + tk < n_fp;
-      const half8_t x = __builtin_bit_cast(half8_t, rd.k);
-      float p[R][kRingSlice];  // the four tokens' weights, wave-uniform
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float4_t qa = *reinterpret_cast<const float4_t *>(&sm.qraw[r][8 * pc]);
-        const float4_t qb = *reinterpret_cast<const float4_t *>(&sm.qraw[r][8 * pc + 4]);
-        float s = qa[0] * (float)x[0];
-        s = fmaf(qa[1], (float)x[1], s);
-        s = fmaf(qa[2], (float)x[2], s);
-        s = fmaf(qa[3], (float)x[3], s);
-        s = fmaf(qb[0], (float)x[4], s);
-        s = fmaf(qb[1], (float)x[5], s);
-        s = fmaf(qb[2], (float)x[6], s);
-        s = fmaf(qb[3], (float)x[7], s);
-        s += row_move<kQuadSwap1>(s);
-        s += row_move<kQuadSwap2>(s);
-        s += row_move<kRowHalfMirror>(s);
-        s += row_move<kRowMirror>(s);  // all sixteen lanes of a token now hold its score
-        s = valid ? c * s : -INFINITY;
-        float sk[kRingSlice];  // the four tokens' scores, read from one lane of each row
-#pragma unroll
-        for (int k = 0; k < kRingSlice; ++k)
-          sk[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 16 * k));
-        const float mnew = fmaxf(rm[r], fmaxf(fmaxf(sk[0], sk[1]), fmaxf(sk[2], sk[3])));
-        const float f = fast_exp2(rm[r] - mnew);  // 0 for the first slice
-#pragma unroll
-        for (int k = 0; k < kRingSlice; ++k) p[r][k] = fast_exp2(sk[k] - mnew);  // 0 for tokens past the end
-        rl[r] = rl[r] * f + (p[r][0] + p[r][1]) + (p[r][2] + p[r][3]);
-        ro[r][0] *= f;
-        ro[r][1] *= f;
-        rm[r] = mnew;
-      }
-#pragma unroll
-      for (int k = 0; k < kRingSlice; ++k) {
-        const __half2 v2 = __builtin_bit_cast(__half2, rd.v[k]);
-        const float vx = __low2float(v2), vy = __high2float(v2);
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-          ro[r][0] = fmaf(p[r][k], vx, ro[r][0]);
-          ro[r][1] = fmaf(p[r][k], vy, ro[r][1]);
-        }
-      }
-    };
-    if (ring_first + ring_stride >= n_slices) {
-      // one slice (the usual case): its data was requested before the tile loads
-      ring_slice(ring, ring_first);
-    } else {
-      // several slices: each next one is requested while the current one is computed; those
-      // requests queue behind the tile loads, and all of them have landed when this ends
-      for (int slice = ring_first; slice < n_slices; slice += ring_stride) {
-        RingData ring_next = ring;
-        if (slice + ring_stride < n_slices) ring_next = load_ring(slice + ring_stride);
-        ring_slice(ring, slice);
-        ring = ring_next;
-      }
-      asm volatile("" ::"v"(ring.k.x), "v"(ring.k.y), "v"(ring.k.z), "v"(ring.k.w), "v"(ring.v[0]),
-                   "v"(ring.v[1]), "v"(ring.v[2]), "v"(ring.v[3]));
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      sm.ring_o[wave][r][2 * lane] = ro[r][0];
-      sm.ring_o[wave][r][2 * lane + 1] = ro[r][1];
-      if (lane == 0) sm.rm[wave][r] = rm[r], sm.rl[wave][r] = rl[r];
-    }
-  } else if (lane < R) {
-    sm.rm[wave][lane] = -INFINITY;
-    sm.rl[wave][lane] = 0.f;
-  }
-  // (No ring load younger than the tile loads may be pending here: it would turn every wait
-  // inside the tile loop into a wait for all loads.)
-
-  float mref[R], lsum[R], zacc[R][NG];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    mref[r] = 0.f, lsum[r] = 0.f;
-#pragma unroll
-    for (int g = 0; g < NG; ++g) zacc[r][g] = 0.f;
-  }
-  float beta = 1.f;
-  float4_t acc[8];
-#pragma unroll
-  for (int n = 0; n < 8; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
-  bool first = true;
-
-  SKVQ_STAMP(1);
-  SKVQ_WSTAMP(0);
-  auto compute_tile = [&](const Tile &cur, const int tile) {
-    const bool valid = tile * 64 + lane <= last_token;
-
-    // ---- scores: 32 products of 4 channels each, one accumulator per group ----
-    float4_t dg[NG];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) dg[g] = dinit[g];
-    dg[0 * NG / 8] = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, dg[0 * NG / 8]);
-    dg[1 * NG / 8] = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, dg[1 * NG / 8]);
-    dg[2 * NG / 8] = qk_dword<2>(cur.k0.z, qop_lo, qop_hi, dg[2 * NG / 8]);
-    dg[3 * NG / 8] = qk_dword<3>(cur.k0.w, qop_lo, qop_hi, dg[3 * NG / 8]);
-    dg[4 * NG / 8] = qk_dword<4>(cur.k1.x, qop_lo, qop_hi, dg[4 * NG / 8]);
-    dg[5 * NG / 8] = qk_dword<5>(cur.k1.y, qop_lo, qop_hi, dg[5 * NG / 8]);
-    dg[6 * NG / 8] = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, dg[6 * NG / 8]);
-    dg[7 * NG / 8] = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, dg[7 * NG / 8]);
-    // u = log2-domain score minus the running reference
-    float u[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) u[r] = -mref[r];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float2 kmeta = meta_value(cur.kmeta.m[g]);
-      const float a_t = kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
-      const float zc = fmaf(1.5f, kmeta.x, kmeta.y);  // dequantized value of the centre code 1.5
-#pragma unroll
-      for (int r = 0; r < R; ++r) u[r] = fmaf(dg[g][r], a_t, fmaf(zc, qsc[r][g], u[r]));
-    }
-    float vs[NG], vz[NG], vs_top = 0.f;
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float2 vmeta = meta_value(cur.vmeta.m[g]);
-      vs[g] = valid ? vmeta.x : 0.f;
-      vz[g] = valid ? vmeta.y : 0.f;
-      vs_top = fmaxf(vs_top, vs[g]);
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-      if (!valid) u[r] = -INFINITY;
-    bool trig = vs_top * beta > kVsLimit;
-#pragma unroll
-    for (int r = 0; r < R; ++r) trig |= u[r] > kRefSlack;
-    if (first || __any(trig)) {
-      // move the reference (and the value-scale normalisation) and rescale what is accumulated
-      float f[R];
-#pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float umax = wave_max(u[r]);
-        const float delta = first ? umax : fmaxf(umax, 0.f);
-        f[r] = first ? 0.f : exp2f(-delta);
-        mref[r] += delta;
-        u[r] -= delta;
-        lsum[r] *= f[r];
-#pragma unroll
-        for (int g = 0; g < NG; ++g) zacc[r][g] *= f[r];
-      }
-      const float vsmax = wave_max(vs_top);
-      float g = 1.f;
-      if (vsmax * beta > kVsTarget || first) {
-        float nb = beta;
-        if (vsmax > 0.f) {
-          int e;
-          (void)frexpf(vsmax, &e);  // vsmax = fr * 2^e, fr in [0.5, 1)
-          nb = ldexpf(1.f, 8 - e);  // vsmax * nb in [128, 256)
-        }
-        g = nb / beta;
-        beta = nb;
-      }
-      if (!first) {
-        const int col = lane & 15;
-        float fc = 0.f;
-#pragma unroll
-        for (int r = 0; r < R; ++r) fc = (col % R == r) ? f[r] : fc;
-        fc *= g;
-#pragma unroll
-        for (int n = 0; n < 8; ++n) acc[n] *= fc;
-      }
-      first = false;
-    }
-
-    // ---- weights: p = 2^u, P' = p * vscale * beta * 2^-(bit-4), split into high and low fp16 ----
-    const float bk = beta * kslot_scale;
-    _Float16 *pw = &sm.wb[wave].pbuf[lane >> 5][0][0][lane & 31];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const float p = fast_exp2(u[r]);
-      lsum[r] += p;
-#pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        zacc[r][g] = fmaf(p, vz[g], zacc[r][g]);
-        const float pp = p * (vs[g] * bk);
-        const float hi = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, pp) & 0xffffe000u);
-        const float lo = pp - hi;
-        pw[(g * 2 * R + r) * 32] = (_Float16)hi;
-        pw[(g * 2 * R + R + r) * 32] = (_Float16)lo;
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // ---- values: two blocks of 32 tokens, 8 channel tiles each ----
-    const int col = lane & 15, kb = lane >> 4;
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      half8_t pop[NG];  // the weights (B operand) of each group of channel tiles
-#pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        pop[g] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        if (col < 2 * R) pop[g] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col][8 * kb]);
-      }
-      const Unit16 raw = blk ? cur.v1 : cur.v0;
-      if (TERNARY) {
-        const unsigned u0 = __builtin_amdgcn_alignbyte(raw.y, raw.x, unit_sh);
-        const unsigned u1 = __builtin_amdgcn_alignbyte(raw.z, raw.y, unit_sh);
-        const unsigned u2 = __builtin_amdgcn_alignbyte(raw.w, raw.z, unit_sh);
-        const unsigned u3 = raw.w >> (8 * unit_sh);
-        // byte offsets into the table (field * 16), two operations per field
-        unsigned f[8];
-        f[0] = (u0 << 4) & 0x1fff0u;
-        f[1] = (u0 >> 9) & 0x1fff0u;
-        f[2] = __builtin_amdgcn_alignbit(u1, u0, 22) & 0x1fff0u;
-        f[3] = (u1 >> 3) & 0x1fff0u;
-        f[4] = __builtin_amdgcn_alignbit(u2, u1, 16) & 0x1fff0u;
-        f[5] = (u2 << 3) & 0x1fff0u;
-        f[6] = (u2 >> 10) & 0x1fff0u;
-        f[7] = __builtin_amdgcn_alignbit(u3, u2, 23) & 0x1fff0u;
-        uint4_t aop[8];
-#pragma unroll
-        for (int n = 0; n < 8; ++n)
-          aop[n] = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(sm.lut) + f[n]);
-#pragma unroll
-        for (int n = 0; n < 8; ++n)
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop[n * NG / 8],
-                                                          acc[n], 0, 0, 0);
-      } else {
-        const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int n = 0; n < 8; ++n) {
-          const unsigned f = (n & 1) ? (w[n >> 1] >> 8) : w[n >> 1];
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_field(f), pop[n * NG / 8], acc[n], 0, 0, 0);
-        }
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-  };
-  // Whole triples first.  The loop has no early exit: the wait counters the compiler places
-  // are exact only if every path into the loop's top has the same loads in flight, in the
-  // same order (buffer a's, then buffer b's).
-  while (tile_c < tile_end) {
-    buf_c = load_tile(tile_c);
-    compute_tile(buf_a, tile_a);
-#ifdef SKVQ_TIMING
-    if (n_a == 0) { SKVQ_STAMP(12); }
-#endif
-    tile_a = tile_of(n_a += 3);
-    buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
-    compute_tile(buf_b, tile_b);
-    tile_b = tile_of(n_b += 3);
-    buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
-    compute_tile(buf_c, tile_c);
-    tile_c = tile_of(n_c += 3);
-  }
-  // At most two tiles are left, already loaded into a and b.
-#pragma unroll 1
-  for (int k = 0; k < 2 && tile_a < tile_end; ++k) {
-    compute_tile(buf_a, tile_a);
-    buf_a = buf_b;
-    tile_a = tile_b;
-    tile_b = tile_end;
-  }
-
-  SKVQ_STAMP(2);
-  SKVQ_WSTAMP(1);
-  // ---- epilogue: fold lanes, columns, waves and ring slices; write this chunk's partial ----
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const float ls = wave_sum_fast(lsum[r]);
-    if (lane == 0) {
-      sm.wm[wave][r] = first ? -INFINITY : mref[r];
-      sm.wl[wave][r] = ls;
-    }
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float zs = wave_sum_fast(zacc[r][g]);
-      if (lane == 0) sm.wz[wave][r][g] = zs;
-    }
-  }
-  if (!first) {
-    const int col = lane & 15, kb = lane >> 4;
-    // codes carried 2^(4-24) (2-bit units) or 2^(8-24) (3-level units)
-    const float unscale = (TERNARY ? 65536.0f : 1048576.0f) / beta;
-#pragma unroll
-    for (int n = 0; n < 8; ++n)
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        const float lo_part = row_move<kRowShl + R>(acc[n][rr]);  // column R + r: the low halves' sum
-        if (col < R) sm.wb[wave].stage[col][16 * n + 4 * kb + rr] = (acc[n][rr] + lo_part) * unscale;
-      }
-  }
-  __syncthreads();
-  SKVQ_STAMP(8);
-  SKVQ_STAMP(9);
-  if (tid < R * kD && head0 + (tid >> 7) < L.R) {
-    // thread (head r, position p): the chunk's reference m* = max over waves and ring slices,
-    // each one's factor 2^(m - m*), the sums that need no channel (every thread of a head
-    // computes the same ones: cheaper than another exchange through LDS), its channel's sum
-    const int r = tid >> 7, p = tid & 127;
-    const int ch = pv_ch;
-    float wm[kNW], wl[kNW], rm[kNW], rl[kNW];
-    float m = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kNW; ++w) {
-      wl[w] = sm.wl[w][r], rl[w] = sm.rl[w][r];
-      wm[w] = wl[w] > 0.f ? sm.wm[w][r] : -INFINITY;
-      rm[w] = rl[w] > 0.f ? sm.rm[w][r] : -INFINITY;
-      m = fmaxf(m, fmaxf(wm[w], rm[w]));
-    }
-    float den = 0.f, num = 0.f;
-#pragma unroll
-    for (int w = 0; w < kNW; ++w) {
-      const float e = wl[w] > 0.f ? fast_exp2(wm[w] - m) : 0.f, g = rl[w] > 0.f ? fast_exp2(rm[w] - m) : 0.f;
-      den = fmaf(e, wl[w], fmaf(g, rl[w], den));
-      if (e > 0.f) num = fmaf(e, sm.wb[w].stage[r][p] + sm.wz[w][r][p * NG / kD], num);
-      if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
-    }
-    float *part =
-        L.workspace + (((long long)b * L.Hq + hk * L.R + head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
-    part[4 + ch] = num;
-    if (p == 0) {
-      part[0] = m;
-      part[1] = den;
-    }
-  }
-  SKVQ_STAMP(3);
-}
-
-}  // namespace
-
-#ifdef SKVQ_TIMING
-extern "C" int skvq_debug_read_timing(unsigned long long *host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(skvq_timing), sizeof(unsigned long long) * n);
-}
-extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(skvq_timing_w), sizeof(unsigned long long) * n);
-}
-#endif
-
+template <int KL, int VL>
+hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
+                                  int n_splits, hipStream_t s);
+#define SKVQ_FMT(KL, VL)                                                                              \
+  extern template hipError_t launch_decode_mfma_fmt<KL, VL>(const Layout &, const __half *, long long, \
+                                                            long long, int, int, hipStream_t);
+SKVQ_FMT(4, 3) SKVQ_FMT(4, 4) SKVQ_FMT(4, 16) SKVQ_FMT(16, 3) SKVQ_FMT(16, 4) SKVQ_FMT(16, 16)
+#undef SKVQ_FMT
 
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                               int n_splits, hipStream_t s) {
-  if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
-      n_splits > SKVQ_MAX_SPLITS)
-    return hipErrorInvalidValue;
-  const int passes = decode_passes(L.R), rk = L.R == 1 ? 1 : L.R == 2 ? 2 : 4;
-  if ((long long)L.Hk * passes > 65535 || L.R > 8) return hipErrorInvalidValue;
-  const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
-#define SKVQ_LAUNCH(RR, TT, MM, GG) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, TT, MM, GG>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes)
-#define SKVQ_LAUNCH_NG(RR, TT, MM)                 \
-  switch (L.NG) {                                  \
-    case 1: SKVQ_LAUNCH(RR, TT, MM, 1); break;     \
-    case 2: SKVQ_LAUNCH(RR, TT, MM, 2); break;     \
-    case 4: SKVQ_LAUNCH(RR, TT, MM, 4); break;     \
-    default: return hipErrorInvalidValue;          \
-  }
-#define SKVQ_LAUNCH_META(RR, TT)                                                \
-  switch (L.meta_fmt) {                                                         \
-    case SKVQ_META_F32: SKVQ_LAUNCH_NG(RR, TT, SKVQ_META_F32) break;            \
-    case SKVQ_META_F16: SKVQ_LAUNCH_NG(RR, TT, SKVQ_META_F16) break;            \
-    case SKVQ_META_FP8_E4M3: SKVQ_LAUNCH_NG(RR, TT, SKVQ_META_FP8_E4M3) break;  \
-    default: return hipErrorInvalidValue;                                       \
-  }
-  const bool ter = L.v_levels == 3;
-  switch (rk) {
-    case 1: if (ter) { SKVQ_LAUNCH_META(1, true) } else { SKVQ_LAUNCH_META(1, false) } break;
-    case 2: if (ter) { SKVQ_LAUNCH_META(2, true) } else { SKVQ_LAUNCH_META(2, false) } break;
-    case 4: if (ter) { SKVQ_LAUNCH_META(4, true) } else { SKVQ_LAUNCH_META(4, false) } break;
+  const int fmt = L.k_levels * 100 + L.v_levels;
+  switch (fmt) {
+    case 403: return launch_decode_mfma_fmt<4, 3>(L, q, T, nq, n_sink, n_splits, s);
+    case 404: return launch_decode_mfma_fmt<4, 4>(L, q, T, nq, n_sink, n_splits, s);
+    case 416: return launch_decode_mfma_fmt<4, 16>(L, q, T, nq, n_sink, n_splits, s);
+    case 1603: return launch_decode_mfma_fmt<16, 3>(L, q, T, nq, n_sink, n_splits, s);
+    case 1604: return launch_decode_mfma_fmt<16, 4>(L, q, T, nq, n_sink, n_splits, s);
+    case 1616: return launch_decode_mfma_fmt<16, 16>(L, q, T, nq, n_sink, n_splits, s);
     default: return hipErrorInvalidValue;
   }
-#undef SKVQ_LAUNCH_META
-#undef SKVQ_LAUNCH_NG
-#undef SKVQ_LAUNCH
-  return hipGetLastError();
 }
 
 }  // namespace skvq

@@ -74,6 +74,14 @@ __device__ __forceinline__ void store_k_row(uint8_t *row, int lane, unsigned c0,
   if ((lane & 7) == 0) reinterpret_cast<unsigned *>(row)[lane >> 3] = w;
 }
 
+// 4-bit K row: position p at bits [4p, 4p+4).  Lane l contributes one byte; 4 lanes form a dword.
+__device__ __forceinline__ void store_k_row4(uint8_t *row, int lane, unsigned c0, unsigned c1) {
+  unsigned w = (c0 | (c1 << 4)) << (8 * (lane & 3));
+  w |= __shfl_xor(w, 1);
+  w |= __shfl_xor(w, 2);
+  if ((lane & 3) == 0) reinterpret_cast<unsigned *>(row)[lane >> 2] = w;
+}
+
 // Spread eight 2-bit codes (token i at bits [2i,2i+2)) to the V unit order: token i goes to
 // bit 16*(i%2) + 2*(i/2).
 __device__ __forceinline__ unsigned spread_tokens(unsigned c8) {
@@ -110,9 +118,11 @@ constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte a
                                  // puts the same channel of the 8 rows in 8 different banks
 
 // Gathers positions 16n..16n+15 of one parked row, finds the group's Eq. 2 parameters and
-// returns this lane's 16 codes packed two bits each (position 16n + e at bits [2e, 2e+2)).
-__device__ __forceinline__ unsigned encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
-                                             float top, int fmt, GroupParams &gp) {
+// returns this lane's 16 codes: two bits each in .x (position 16n + e at bits [2e, 2e+2)), or,
+// WIDE, four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).
+template <bool WIDE>
+__device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
+                                          float top, int fmt, GroupParams &gp) {
   const int ch[16] = {pm[0].x, pm[0].y, pm[0].z, pm[0].w, pm[1].x, pm[1].y, pm[1].z, pm[1].w,
                       pm[2].x, pm[2].y, pm[2].z, pm[2].w, pm[3].x, pm[3].y, pm[3].z, pm[3].w};
   float x[16];
@@ -131,22 +141,29 @@ __device__ __forceinline__ unsigned encode16(const __half *row, const int4 (&pm)
   gp = group_params(mn, mx, alpha, top, fmt);
   // code = rint(clamp(y, 0, top)): clamping first gives the same integer because the bounds are
   // integers; adding 1.5 * 2^23 rounds to the nearest integer, ties to even, and leaves the code
-  // in the two low bits of the sum, which alignbit shifts into the row word from the top.
-  unsigned w = 0;
+  // in the low bits of the sum, which alignbit shifts into the row word from the top.
+  unsigned w0 = 0, w1 = 0;
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     const float y = __fmul_rn(__fsub_rn(x[e], gp.lo), gp.inv);
     const float r = __fadd_rn(__builtin_amdgcn_fmed3f(y, 0.0f, top), 12582912.0f);
-    w = __builtin_amdgcn_alignbit(__float_as_uint(r), w, 2);
+    if (!WIDE)
+      w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 2);
+    else if (e < 8)
+      w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 4);
+    else
+      w1 = __builtin_amdgcn_alignbit(__float_as_uint(r), w1, 4);
   }
-  return w;
+  return make_uint2(w0, w1);
 }
 
+template <int KL, int VL>  // levels of the key and value codes
 __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
                                                       long long nq) {
   __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
-  __shared__ unsigned vq[4][8][8];                            // [wave][token i][n]: 16 codes, j-minor
+  __shared__ unsigned vq[VL == 16 ? 1 : 4][8][8];             // [wave][token i][n]: 16 codes, j-minor
+  __shared__ uint2 vq4[VL == 16 ? 4 : 1][8][8 + 1];           // the same for 4-bit codes
   __shared__ unsigned pieces[4][64];
   __shared__ __align__(16) uint8_t units[4][208];
 
@@ -188,27 +205,45 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   }
   const long long t = t0 + i;
   const bool valid = t < nq;
-  const float vtop = (float)(L.v_levels - 1);
   __syncthreads();
 
   GroupParams gk, gv;
-  const unsigned kw = encode16(rows[wave][0][i], pk, ak, L.G, 3.0f, L.meta_fmt, gk);
-  const unsigned vw = encode16(rows[wave][1][i], pv, av, L.G, vtop, L.meta_fmt, gv);
+  const uint2 kw = encode16<KL == 16>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, gk);
+  const uint2 vw = encode16<VL == 16>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, gv);
   if (valid) {
-    reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw;
+    if (KL == 16)
+      reinterpret_cast<uint2 *>(L.k_codes + (head * L.Tcap + t) * (kD / 2))[n] = kw;
+    else
+      reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw.x;
     if (writes_meta) {
       meta_store_pair(L.k_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, L.meta_fmt);
       meta_store_pair(L.v_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, L.meta_fmt);
     }
   }
-  vq[wave][i][n] = valid ? vw : 0u;  // rows past the packed region leave zeros in the block
+  // rows past the packed region leave zeros in the block
+  if (VL == 16)
+    vq4[wave][i][n] = valid ? vw : make_uint2(0u, 0u);
+  else
+    vq[wave][i][n] = valid ? vw.x : 0u;
   __syncthreads();
 
   // V units of sub-block kb = wave.  Lane (j = lane % 16, nh = lane / 16) builds fields 2nh and
   // 2nh+1 of unit j from the codes of its eight tokens.
   const int j = lane & 15, nh = lane >> 4;
-  uint8_t *dst = L.v_codes + (head * L.n_vblocks + blk) * L.v_block_bytes;
-  if (L.v_levels == 4) {
+  uint8_t *dst = L.v_codes + (head * L.n_vblocks + blk) * v_block_bytes_of(VL);
+  if (VL == 16) {
+    // fields 2nh and 2nh+1 are dwords 2nh and 2nh+1 of the 32-byte unit
+    unsigned wa = 0, wb = 0;
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      const uint2 qa = vq4[wave][ii][2 * nh], qb = vq4[wave][ii][2 * nh + 1];
+      const unsigned ca = ((j < 8 ? qa.x : qa.y) >> (4 * (j & 7))) & 15u;
+      const unsigned cb = ((j < 8 ? qb.x : qb.y) >> (4 * (j & 7))) & 15u;
+      wa |= ca << (16 * (ii & 1) + 4 * (ii >> 1));
+      wb |= cb << (16 * (ii & 1) + 4 * (ii >> 1));
+    }
+    reinterpret_cast<uint2 *>(dst + 512 * wave + 32 * j)[nh] = make_uint2(wa, wb);
+  } else if (VL == 4) {
     unsigned w = 0;
 #pragma unroll
     for (int ii = 0; ii < 8; ++ii) {
@@ -289,6 +324,7 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   int p0 = 0, p1 = 0;
   float alpha = 1.f;
   unsigned old_word = 0;   // 2-bit V: dword nh of unit j (lane = (j, nh))
+  uint2 old_pair = make_uint2(0u, 0u);  // 4-bit V: dwords 2nh, 2nh+1 of unit j
   uint8_t old_unit[13];    // 3-level V: unit j (lane = j < 16)
 #pragma unroll
   for (int q = 0; q < 13; ++q) old_unit[q] = 0;
@@ -298,7 +334,9 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
     p0 = pp.x, p1 = pp.y;
     alpha = (wave ? L.clip_v : L.clip_k)[hk * L.NG + grp];
     if (wave == 1 && i != 0) {
-      if (L.v_levels == 4) {
+      if (L.v_levels == 16) {
+        old_pair = reinterpret_cast<const uint2 *>(blk + 32 * (16 * kb + (lane & 15)))[lane >> 4];
+      } else if (L.v_levels == 4) {
         old_word = reinterpret_cast<const unsigned *>(blk + 16 * (16 * kb + (lane & 15)))[lane >> 4];
       } else if (lane < 16) {
         const uint8_t *u = blk + 13 * (16 * kb + lane);
@@ -315,7 +353,7 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   reinterpret_cast<__half2 *>(rows[wave])[lane] = old2;
   __syncthreads();
 
-  const float top = wave ? (float)(L.v_levels - 1) : 3.0f;
+  const float top = (float)((wave ? L.v_levels : L.k_levels) - 1);
   unsigned c0, c1;
   MetaPair mp;
   encode_row(rows[wave], p0, p1, alpha, L.G, top, L.meta_fmt, c0, c1, mp);
@@ -324,7 +362,11 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
     meta_store_pair(meta, (head * L.Tcap + te) * L.NG + grp, mp, L.meta_fmt);
 
   if (wave == 0) {
-    store_k_row(L.k_codes + (head * L.Tcap + te) * (kD / 4), lane, c0, c1);
+    uint8_t *krow = L.k_codes + (head * L.Tcap + te) * L.k_row_bytes;
+    if (L.k_levels == 16)
+      store_k_row4(krow, lane, c0, c1);
+    else
+      store_k_row(krow, lane, c0, c1);
   } else {
     vcodes[2 * lane] = (uint8_t)c0;
     vcodes[2 * lane + 1] = (uint8_t)c1;
@@ -338,7 +380,14 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
     const int first = L.v_block_bytes / 16;  // dwords of one sub-block
     for (int w = first + lane; w < L.v_block_bytes / 4; w += 64) reinterpret_cast<unsigned *>(blk)[w] = 0u;
   }
-  if (L.v_levels == 4) {
+  if (L.v_levels == 16) {
+    // lane (j, nh): dwords 2nh and 2nh+1 of unit j are fields 2nh and 2nh+1
+    const int j = lane & 15, nh = lane >> 4;
+    const unsigned bit = 16 * (i & 1) + 4 * (i >> 1);
+    old_pair.x |= (unsigned)vcodes[16 * (2 * nh) + j] << bit;  // old_pair is 0 when i == 0
+    old_pair.y |= (unsigned)vcodes[16 * (2 * nh + 1) + j] << bit;
+    reinterpret_cast<uint2 *>(blk + 32 * (16 * kb + j))[nh] = old_pair;
+  } else if (L.v_levels == 4) {
     // lane (j, nh): dword nh of unit j holds fields 2nh and 2nh+1
     const int j = lane & 15, nh = lane >> 4;
     const unsigned bit = 16 * (i & 1) + 2 * (i >> 1);
@@ -376,7 +425,18 @@ hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, lon
   if (n.n_quant > 0) {
     const long long nblk = (n.n_quant + kVBlock - 1) / kVBlock;
     if (nblk > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)nblk, L.Hk, L.B), dim3(256), 0, s, L, k, v, T, n.n_quant);
+    const dim3 grid((unsigned)nblk, L.Hk, L.B), block(256);
+#define SKVQ_PREFILL(KL, VL) hipLaunchKernelGGL((prefill_kernel<KL, VL>), grid, block, 0, s, L, k, v, T, n.n_quant)
+    if (L.k_levels == 16) {
+      if (L.v_levels == 16) SKVQ_PREFILL(16, 16);
+      else if (L.v_levels == 4) SKVQ_PREFILL(16, 4);
+      else SKVQ_PREFILL(16, 3);
+    } else {
+      if (L.v_levels == 16) SKVQ_PREFILL(4, 16);
+      else if (L.v_levels == 4) SKVQ_PREFILL(4, 4);
+      else SKVQ_PREFILL(4, 3);
+    }
+#undef SKVQ_PREFILL
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

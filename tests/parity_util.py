@@ -29,10 +29,10 @@ class Pair:
         osm = sm_scale if sm_scale else None
         self.ref = O.OracleCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                  max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=osm, fill=fill,
-                                 n_sink=n_sink, meta=meta)
+                                 n_sink=n_sink, meta=meta, k_bits=w.k_bits)
         self.gpu = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=sm_scale, fill=fill,
-                               device=device, n_sink=n_sink, meta=meta)
+                               device=device, n_sink=n_sink, meta=meta, k_bits=w.k_bits)
         self.device = device
 
     def prefill(self, k: np.ndarray, v: np.ndarray):

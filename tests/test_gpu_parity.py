@@ -37,6 +37,13 @@ QUANT_CASES = [
     small("short_window_only", context=100),
     small("one_quantized_token", context=129),
     small("w1", window=1, context=70),
+    # 4-bit codes (Table 1's 4-bit setting), alone and mixed with the narrower formats
+    small("k4v4_g128", k_bits=4.0, v_bits=4.0),
+    small("k4v4_gqa_g64", k_bits=4.0, v_bits=4.0, n_q_heads=8, n_kv_heads=2, group_size=64, batch=2, context=391),
+    small("k4v4_g32_w16", k_bits=4.0, v_bits=4.0, n_q_heads=8, n_kv_heads=2, group_size=32, context=333, window=16),
+    small("k4v2_outlier", k_bits=4.0, v_bits=2.0, channel_profile="outlier4", perm_stat="absmax"),
+    small("k4_t15_g64", k_bits=4.0, v_bits=1.5, group_size=64, context=300),
+    small("k2v4_g32", k_bits=2.0, v_bits=4.0, group_size=32, context=450),
 ]
 
 
@@ -48,7 +55,9 @@ def test_prefill_codes_and_meta_bit_exact(P, w):
     pair.assert_buffers_equal()
 
 
-@pytest.mark.parametrize("w", [QUANT_CASES[0], QUANT_CASES[2], QUANT_CASES[3], small("from_empty", context=0, window=8)],
+@pytest.mark.parametrize("w", [QUANT_CASES[0], QUANT_CASES[2], QUANT_CASES[3], small("from_empty", context=0, window=8),
+                               QUANT_CASES[8], QUANT_CASES[9], QUANT_CASES[10], QUANT_CASES[12],
+                               small("k4v4_from_empty", k_bits=4.0, v_bits=4.0, context=0, window=8)],
                          ids=lambda w: w.name)
 def test_append_evicts_bit_exact_and_equals_longer_prefill(P, w):
     print("case", w, flush=True)
@@ -109,6 +118,17 @@ DECODE_CASES = [
     small("gqa6_t15", n_q_heads=12, n_kv_heads=2, context=1000),
     small("gqa7_t15_g32", n_q_heads=7, n_kv_heads=1, group_size=32, context=800),
     small("mha_g32_t15", group_size=32, context=300),
+    # 4-bit codes
+    small("k4v4_mha", k_bits=4.0, v_bits=4.0, context=1500),
+    small("k4v4_gqa4_b2", k_bits=4.0, v_bits=4.0, n_q_heads=16, n_kv_heads=4, context=1333, batch=2),
+    small("k4v4_gqa2_g64", k_bits=4.0, v_bits=4.0, n_q_heads=8, n_kv_heads=4, group_size=64, context=2100),
+    small("k4v4_gqa8_g32", k_bits=4.0, v_bits=4.0, n_q_heads=8, n_kv_heads=1, group_size=32, context=3000, window=16),
+    small("k4v4_gqa5_outlier", k_bits=4.0, v_bits=4.0, n_q_heads=5, n_kv_heads=1, context=5000,
+          channel_profile="outlier4", perm_stat="absmax"),
+    small("k4v2_gqa4", k_bits=4.0, v_bits=2.0, n_q_heads=8, n_kv_heads=2, context=999),
+    small("k4_t15_g32", k_bits=4.0, v_bits=1.5, n_q_heads=4, n_kv_heads=2, group_size=32, context=2500, window=40),
+    small("k2v4_g64_b3", k_bits=2.0, v_bits=4.0, group_size=64, context=5000, window=33, batch=3),
+    small("k4v4_one_packed_row", k_bits=4.0, v_bits=4.0, context=129),
     small("window_only", context=77),
     small("exactly_window", context=128),
     small("one_packed_row", context=129),
@@ -398,11 +418,12 @@ def test_random_configurations(P):
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
     appended tokens and a forced split count.  Buffers bit-exact, outputs within 2e-3."""
     rng = np.random.default_rng(20240506)
-    for case in range(28):
+    for case in range(48):
         hk = int(rng.integers(1, 4))
         r = int(rng.integers(1, 9))
         w = small(f"rand{case}", batch=int(rng.integers(1, 4)), n_kv_heads=hk, n_q_heads=hk * r,
-                  group_size=int(rng.choice([32, 64, 128])), v_bits=float(rng.choice([1.5, 2.0])),
+                  group_size=int(rng.choice([32, 64, 128])), v_bits=float(rng.choice([1.5, 2.0, 4.0])),
+                  k_bits=float(rng.choice([2.0, 4.0])),
                   window=int(rng.choice([1, 3, 16, 33, 128, 200])), context=int(rng.integers(0, 2600)),
                   seed=500 + case)
         S = int(rng.choice([0, 0, 1, 5, 9]))
