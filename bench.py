@@ -15,6 +15,7 @@ CPU oracle timed on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -36,15 +37,19 @@ MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 77977 * 1024}
 META_BYTES = {"f32": 4, "f16": 2, "e4m3": 1}
 
 
+def code_bytes_per_row(w) -> int:
+    """Packed key row + the token's share of its V block, bytes per (token, kv head)."""
+    return {2.0: 32, 4.0: 64}[w.k_bits] + {1.5: 26, 2.0: 32, 4.0: 64}[w.v_bits]
+
+
 def algorithmic_bytes_decode(w, n_tokens: int, n_sink: int = 0, meta: str = "f32") -> int:
-    """Bytes one decode call must move: packed rows (K 32 B + V 26|32 B + two fp32
+    """Bytes one decode call must move: packed rows (K 32|64 B + V 26|32|64 B + two fp32
     (or fp16 / FP8) (scale, zero) pairs per group each), the fp16 ring and sink rows, the query
     and the fp32 output."""
     nq = max(n_tokens - w.window - n_sink, 0)
     nwin = n_tokens - nq
     ng = D // w.group_size
-    vrow = 26 if w.v_bits == 1.5 else 32
-    per_row = 32 + vrow + 2 * (2 * META_BYTES[meta] * ng)
+    per_row = code_bytes_per_row(w) + 2 * (2 * META_BYTES[meta] * ng)
     return (w.batch * w.n_kv_heads * (nq * per_row + nwin * 2 * D * 2)
             + w.batch * w.n_q_heads * D * (2 + 4))
 
@@ -67,7 +72,7 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta:
         k, v, pk, pv = synth.make_kv_device(w, device, stream=layer)
         c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                         w.context - w.window + headroom, pk, pv, ck, cv, device=device, n_sink=n_sink,
-                        meta=meta)
+                        meta=meta, k_bits=w.k_bits)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         c.skvq_prefill_quantize(k, v)
@@ -95,7 +100,7 @@ def cpu_baseline(w, n_sink: int = 0, meta: str = "f32", seconds_budget: float = 
     pk, pv = synth.make_permutations(ws, k[:, :, :4096], v[:, :, :4096])
     ck, cv = synth.make_clip(ws)
     oc = O.OracleCache(ws.batch, ws.n_q_heads, ws.n_kv_heads, ws.group_size, ws.v_bits, ws.window,
-                       ctx - ws.window + 4, pk, pv, ck, cv, n_sink=n_sink, meta=meta)
+                       ctx - ws.window + 4, pk, pv, ck, cv, n_sink=n_sink, meta=meta, k_bits=ws.k_bits)
     assert oc.prefill(k, v) == 0
     q = synth.make_query(ws)
     kn, vn = synth.make_new_token(ws, 0)
@@ -121,6 +126,10 @@ def main() -> int:
                     help="attention sinks: the first N tokens stay fp16 (the headline workload has none)")
     ap.add_argument("--meta", choices=sorted(META_BYTES), default="f32",
                     help="storage of (scale, zero); the headline workload keeps them in fp32")
+    ap.add_argument("--k-bits", type=float, choices=[2.0, 4.0], default=0.0,
+                    help="override the workload's key width (the headline workload has 2-bit keys)")
+    ap.add_argument("--v-bits", type=float, choices=[1.5, 2.0, 4.0], default=0.0,
+                    help="override the workload's value width (the headline workload has 1.5-bit values)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -140,6 +149,11 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     if args.context:
         w = w.scaled(args.context)
+    headline_format = not args.k_bits and not args.v_bits
+    if args.k_bits:
+        w = dataclasses.replace(w, k_bits=args.k_bits)
+    if args.v_bits:
+        w = dataclasses.replace(w, v_bits=args.v_bits)
     n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers
     headroom = n_warm + 2 * n_steps + 9
 
@@ -218,7 +232,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "layers": n_layers, "batch": w.batch, "n_q_heads": w.n_q_heads,
-                   "n_kv_heads": w.n_kv_heads, "head_dim": D, "context": w.context, "k_bits": 2,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": D, "context": w.context, "k_bits": w.k_bits,
                    "v_bits": w.v_bits, "group_size": w.group_size, "window": w.window, "n_sink": args.sink, "meta": args.meta,
                    "step": "per layer: skvq_quantize_append + skvq_decode_attention"},
         "us_per_layer": ms_per_step * 1e3 / n_layers,
@@ -228,7 +242,7 @@ def main() -> int:
         "prefill_call_us": prefill_med_us,
         "prefill_tokens_per_s": w.batch * w.context / (prefill_med_us * 1e-6),
         "prefill_hbm_gbps": (w.batch * w.n_kv_heads * (w.context * 2 * D * 2 + max(w.context - w.window, 0)
-                                                     * ((58 if w.v_bits == 1.5 else 64)
+                                                     * (code_bytes_per_row(w)
                                                         + 4 * META_BYTES[args.meta] * (D // w.group_size)))
                              / (prefill_med_us * 1e-6) / 1e9),
         "effective_hbm_gbps": achieved,
@@ -237,7 +251,7 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES.get(w.name)
                                  if w.context == synth.WORKLOADS[w.name].context and not args.sink
-                                 and args.meta == "f32" else None),
+                                 and args.meta == "f32" and headline_format else None),
                      "kernel": "skvq_decode_attention", "bytes_per_launch": alg_bytes,
                      "avg_launch_us": dec_avg_us},
     }

@@ -243,9 +243,10 @@ struct alignas(sizeof(typename MetaWord<META>::type) * NG > 16 ? 16 : sizeof(typ
 };
 template <int KL, int VL, int META, int NG>
 struct TileData {
-  uint4_t k[KL == 16 ? 4 : 2];       // lane = token: its 32- or 64-byte key row
+  // (named members, not arrays: with arrays the compiler keeps copies of the buffers in registers)
+  uint4_t k0, k1, k2, k3;            // lane = token: its 32-byte (k0, k1) or 64-byte key row
   MetaBlock<META, NG> kmeta, vmeta;  // lane = token: (scale, zero) per group
-  Unit16 v[2][VL == 16 ? 2 : 1];     // lane = unit of V block 2*tile and 2*tile+1 (16 or 32 bytes)
+  Unit16 v00, v01, v10, v11;         // lane = unit of V block 2*tile (v0x) and 2*tile+1 (v1x): 16 or 32 bytes
 };
 
 // What one wavefront loads for one slice of 4 fp16 ring tokens.
@@ -311,16 +312,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     int t = tile * 64 + lane;
     if (t > safe_last_token) t = safe_last_token;  // only in the last tile; such lanes are masked below
     const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * kRowBytes);
-#pragma unroll
-    for (int x = 0; x < kRowBytes / 16; ++x) d.k[x] = krow[x];
+    d.k0 = krow[0]; d.k1 = krow[1];
+    if constexpr (K4) { d.k2 = krow[2]; d.k3 = krow[3]; }
     d.kmeta = km[t];
     d.vmeta = vm[t];
     const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
     const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
-#pragma unroll
-    for (int x = 0; x < (V4 ? 2 : 1); ++x) {
-      d.v[0][x] = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[x];
-      d.v[1][x] = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[x];
+    d.v00 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[0];
+    d.v10 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[0];
+    if constexpr (V4) {
+      d.v01 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[1];
+      d.v11 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[1];
     }
     return d;
   };
@@ -555,21 +557,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #pragma unroll
     for (int g = 0; g < NG; ++g) dg[g] = dinit[g];
     if constexpr (K4) {
-#define SKVQ_QK4(Q, C, DW) dg[(DW) * NG / 16] = qk_dword4<DW>(cur.k[Q].C, qop_lo, qop_hi, dg[(DW) * NG / 16])
+#define SKVQ_QK4(Q, C, DW) dg[(DW) * NG / 16] = qk_dword4<DW>(cur.k##Q.C, qop_lo, qop_hi, dg[(DW) * NG / 16])
       SKVQ_QK4(0, x, 0);  SKVQ_QK4(0, y, 1);  SKVQ_QK4(0, z, 2);  SKVQ_QK4(0, w, 3);
       SKVQ_QK4(1, x, 4);  SKVQ_QK4(1, y, 5);  SKVQ_QK4(1, z, 6);  SKVQ_QK4(1, w, 7);
       SKVQ_QK4(2, x, 8);  SKVQ_QK4(2, y, 9);  SKVQ_QK4(2, z, 10); SKVQ_QK4(2, w, 11);
       SKVQ_QK4(3, x, 12); SKVQ_QK4(3, y, 13); SKVQ_QK4(3, z, 14); SKVQ_QK4(3, w, 15);
 #undef SKVQ_QK4
     } else {
-      dg[0 * NG / 8] = qk_dword<0>(cur.k[0].x, qop_lo, qop_hi, dg[0 * NG / 8]);
-      dg[1 * NG / 8] = qk_dword<1>(cur.k[0].y, qop_lo, qop_hi, dg[1 * NG / 8]);
-      dg[2 * NG / 8] = qk_dword<2>(cur.k[0].z, qop_lo, qop_hi, dg[2 * NG / 8]);
-      dg[3 * NG / 8] = qk_dword<3>(cur.k[0].w, qop_lo, qop_hi, dg[3 * NG / 8]);
-      dg[4 * NG / 8] = qk_dword<4>(cur.k[1].x, qop_lo, qop_hi, dg[4 * NG / 8]);
-      dg[5 * NG / 8] = qk_dword<5>(cur.k[1].y, qop_lo, qop_hi, dg[5 * NG / 8]);
-      dg[6 * NG / 8] = qk_dword<6>(cur.k[1].z, qop_lo, qop_hi, dg[6 * NG / 8]);
-      dg[7 * NG / 8] = qk_dword<7>(cur.k[1].w, qop_lo, qop_hi, dg[7 * NG / 8]);
+      dg[0 * NG / 8] = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, dg[0 * NG / 8]);
+      dg[1 * NG / 8] = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, dg[1 * NG / 8]);
+      dg[2 * NG / 8] = qk_dword<2>(cur.k0.z, qop_lo, qop_hi, dg[2 * NG / 8]);
+      dg[3 * NG / 8] = qk_dword<3>(cur.k0.w, qop_lo, qop_hi, dg[3 * NG / 8]);
+      dg[4 * NG / 8] = qk_dword<4>(cur.k1.x, qop_lo, qop_hi, dg[4 * NG / 8]);
+      dg[5 * NG / 8] = qk_dword<5>(cur.k1.y, qop_lo, qop_hi, dg[5 * NG / 8]);
+      dg[6 * NG / 8] = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, dg[6 * NG / 8]);
+      dg[7 * NG / 8] = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, dg[7 * NG / 8]);
     }
     // u = log2-domain score minus the running reference
     float u[R];
@@ -666,9 +668,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         pop[g] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
         if (col < 2 * R) pop[g] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col][8 * kb]);
       }
-      const Unit16 raw = cur.v[blk][0];
+      const Unit16 raw = blk ? cur.v10 : cur.v00;
       if constexpr (V4) {
-        const Unit16 raw2 = cur.v[blk][1];
+        const Unit16 raw2 = blk ? cur.v11 : cur.v01;
         const unsigned w[8] = {raw.x, raw.y, raw.z, raw.w, raw2.x, raw2.y, raw2.z, raw2.w};
 #pragma unroll
         for (int n = 0; n < 8; ++n)
