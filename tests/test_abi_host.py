@@ -54,15 +54,19 @@ def cfg_for(B, **kw):
 
 
 def test_sizes_agree_with_the_oracle(B, oracle):
-    for hk, hq, g, vb, tcap, w, b, sink, meta in [(8, 32, 128, 1.5, 4096, 128, 1, 0, "f32"),
-                                                  (4, 4, 32, 2.0, 1000, 16, 3, 5, "f16"),
-                                                  (2, 16, 64, 1.5, 33, 7, 2, 1, "e4m3")]:
+    for hk, hq, g, vb, tcap, w, b, sink, meta, kb in [(8, 32, 128, 1.5, 4096, 128, 1, 0, "f32", 2.0),
+                                                      (4, 4, 32, 2.0, 1000, 16, 3, 5, "f16", 2.0),
+                                                      (2, 16, 64, 1.5, 33, 7, 2, 1, "e4m3", 2.0),
+                                                      (8, 32, 64, 4.0, 4097, 128, 1, 5, "e4m3", 4.0),
+                                                      (2, 4, 128, 2.0, 65, 9, 2, 0, "f32", 4.0),
+                                                      (3, 3, 32, 4.0, 31, 9, 1, 0, "f16", 2.0)]:
         cfg, keep = cfg_for(B, batch=b, n_q_heads=hq, n_kv_heads=hk, group_size=g, v_bits=vb, window=w,
-                            max_quant_tokens=tcap, n_sink=sink, meta=meta)
+                            max_quant_tokens=tcap, n_sink=sink, meta=meta, k_bits=kb)
         sizes = B.skvq_sizes(cfg)
         perm = np.tile(np.arange(D, dtype=np.int32), (hk, 1))
         clip = np.ones((hk, D // g), np.float32)
-        oc = oracle.OracleCache(b, hq, hk, g, vb, w, tcap, perm, perm, clip, clip, n_sink=sink, meta=meta)
+        oc = oracle.OracleCache(b, hq, hk, g, vb, w, tcap, perm, perm, clip, clip, n_sink=sink, meta=meta,
+                                k_bits=kb)
         assert sizes[:6] == oc.sizes
         assert sizes[6] == b * hq * (B.SKVQ_MAX_SPLITS + 1) * (D + 4) * 4
 
