@@ -236,9 +236,11 @@ def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
     assert err <= P.TOL
 
 
-@pytest.mark.parametrize("name,n_heads", [("c5_batch16_32k", 4), ("c4_llama7b_1m", 2)])
-def test_full_size_sampled_heads(P, name, n_heads):
-    """The batch-16 and the 1M-token workloads at full size, library-chosen split count: the
+@pytest.mark.parametrize("name,n_heads,bits", [("c5_batch16_32k", 4, None), ("c4_llama7b_1m", 2, None),
+                                               ("c3_mistral7b_128k", 3, (4.0, 4.0))])
+def test_full_size_sampled_heads(P, name, n_heads, bits):
+    """The batch-16 and the 1M-token workloads (and the 128k one with 4-bit keys and values) at
+    full size, library-chosen split count: the
     whole layer is prefilled, appended to and attended on the GPU; for seeded sampled
     (sequence, kv head) pairs the oracle builds that head's cache from the same inputs and
     must agree bit for bit on every packed byte, (scale, zero) and ring entry of the head and
@@ -247,6 +249,9 @@ def test_full_size_sampled_heads(P, name, n_heads):
     from paper_2405_06219_amd import binding as B
 
     w = synth.WORKLOADS[name]
+    if bits:
+        w = dataclasses.replace(w, k_bits=bits[0], v_bits=bits[1])
+        name = f"{name}_k{bits[0]:g}v{bits[1]:g}"
     dev = torch.device("cuda:0")
     P.log(f"{name}: generating on the device")
     k, v, pk, pv = synth.make_kv_device(w, dev)
@@ -254,7 +259,7 @@ def test_full_size_sampled_heads(P, name, n_heads):
     n_app = 3
     tcap = w.context - w.window + n_app + 1
     gpu = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window, tcap, pk, pv, ck, cv,
-                      fill=0xAB, device=dev)
+                      fill=0xAB, device=dev, k_bits=w.k_bits)
     gpu.skvq_prefill_quantize(k, v)
     news = [synth.make_new_token(w, s) for s in range(n_app)]
     for kn, vn in news:
@@ -267,8 +272,8 @@ def test_full_size_sampled_heads(P, name, n_heads):
 
     R = w.n_q_heads // w.n_kv_heads
     ng = D // w.group_size
-    vb = 832 if w.v_bits == 1.5 else 1024
-    views = {"k_codes": gpu.buffers["k_codes"].view(w.batch, w.n_kv_heads, tcap, 32),
+    vb = {1.5: 832, 2.0: 1024, 4.0: 2048}[w.v_bits]
+    views = {"k_codes": gpu.buffers["k_codes"].view(w.batch, w.n_kv_heads, tcap, 64 if w.k_bits == 4.0 else 32),
              "v_codes": gpu.buffers["v_codes"].view(w.batch, w.n_kv_heads, (tcap + 31) // 32, vb),
              "k_meta": gpu.buffers["k_meta"].view(torch.float32).view(w.batch, w.n_kv_heads, tcap, ng, 2),
              "v_meta": gpu.buffers["v_meta"].view(torch.float32).view(w.batch, w.n_kv_heads, tcap, ng, 2),
@@ -280,7 +285,7 @@ def test_full_size_sampled_heads(P, name, n_heads):
     worst = 0.0
     for b, hk in sorted(picks):
         ref = O.OracleCache(1, R, 1, w.group_size, w.v_bits, w.window, tcap, pk[hk:hk + 1], pv[hk:hk + 1],
-                            ck[hk:hk + 1], cv[hk:hk + 1], fill=0xAB)
+                            ck[hk:hk + 1], cv[hk:hk + 1], fill=0xAB, k_bits=w.k_bits)
         assert ref.prefill(k[b:b + 1, hk:hk + 1].cpu().numpy(), v[b:b + 1, hk:hk + 1].cpu().numpy()) == 0
         for kn, vn in news:
             assert ref.append(np.ascontiguousarray(kn[b:b + 1, hk:hk + 1]), np.ascontiguousarray(vn[b:b + 1, hk:hk + 1])) == 0
