@@ -244,16 +244,30 @@ void skvq_ref_v_put(uint8_t *block, int levels, int s, int p, int code) {
 
 /* --------------------------------------------------- quantize one token --- */
 
+/* Group g covers the reordered positions [group_lo(g), group_lo(g+1)): g*G when
+ * the groups are uniform, else the caller's boundaries (Section 4.1: clustering
+ * the channels gives groups of unequal size; G is then their average). */
+static int group_lo(const skvq_ref_config *c, int g) {
+  return c->group_bounds ? c->group_bounds[g] : g * c->group_size;
+}
+static int group_of(const skvq_ref_config *c, int p) {
+  int g = 0;
+  while (p >= group_lo(c, g + 1)) ++g;
+  return g;
+}
+
 /* x: fp16 bits [D] of one (token, kv head), original channel order.
  * Gathers through perm (out[p] = in[perm[p]]), encodes each group, returns
  * codes[D] in reordered order and meta[D/G][2]. */
-static void encode_token(const uint16_t *x, const int32_t *perm, const float *alpha, int G,
-                         int levels, int meta_format, uint8_t *codes, float *meta) {
+static void encode_token(const skvq_ref_config *c, const uint16_t *x, const int32_t *perm,
+                         const float *alpha, int levels, uint8_t *codes, float *meta) {
   float xp[D];
   for (int p = 0; p < D; ++p) xp[p] = skvq_ref_half_to_float(x[perm[p]]);
-  for (int g = 0; g < D / G; ++g)
-    skvq_ref_encode_group(xp + g * G, G, alpha[g], levels, meta_format, codes + g * G,
+  for (int g = 0; g < D / c->group_size; ++g) {
+    int lo = group_lo(c, g), hi = group_lo(c, g + 1);
+    skvq_ref_encode_group(xp + lo, hi - lo, alpha[g], levels, c->meta_format, codes + lo,
                           &meta[2 * g], &meta[2 * g + 1]);
+  }
 }
 
 /* Quantize token (b, hk) and store it as packed row t. */
@@ -266,14 +280,14 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
   float meta[2 * D];
 
   int fmt = c->meta_format;
-  encode_token(kx, c->perm_k + hk * D, c->clip_k + hk * ng, G, c->k_levels, fmt, codes, meta);
+  encode_token(c, kx, c->perm_k + hk * D, c->clip_k + hk * ng, c->k_levels, codes, meta);
   uint8_t *krow = buf->k_codes + (head * tcap + (size_t)t) * k_row_bytes(c->k_levels);
   memset(krow, 0, k_row_bytes(c->k_levels));
   for (int p = 0; p < D; ++p) skvq_ref_k_put(krow, c->k_levels, p, codes[p]);
   for (int x = 0; x < 2 * ng; ++x)
     meta_store(buf->k_meta, (head * tcap + (size_t)t) * ng * 2 + x, meta[x], fmt);
 
-  encode_token(vx, c->perm_v + hk * D, c->clip_v + hk * ng, G, c->v_levels, fmt, codes, meta);
+  encode_token(c, vx, c->perm_v + hk * D, c->clip_v + hk * ng, c->v_levels, codes, meta);
   size_t nblk = (tcap + VBT - 1) / VBT, bb = v_block_bytes(c->v_levels);
   uint8_t *blk = buf->v_codes + (head * nblk + (size_t)(t / VBT)) * bb;
   if (t % VBT == 0) memset(blk, 0, bb);
@@ -290,6 +304,12 @@ static int check_config(const skvq_ref_config *c) {
   if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1 ||
       c->n_sink < 0 || c->meta_format < 0 || c->meta_format > 2)
     return -1;
+  if (c->group_bounds) { /* 0 = b_0 < b_1 < ... < b_ng = D */
+    int ng = D / c->group_size;
+    if (c->group_bounds[0] != 0 || c->group_bounds[ng] != D) return -1;
+    for (int g = 0; g < ng; ++g)
+      if (c->group_bounds[g + 1] <= c->group_bounds[g]) return -1;
+  }
   return 0;
 }
 
@@ -375,6 +395,8 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
     size_t head = (size_t)b * c->n_kv_heads + hk;
     const int32_t *pk = c->perm_k + hk * D, *pv = c->perm_v + hk * D;
     double qf[D], acc[D];
+    int gof[D]; /* group of reordered position p */
+    for (int p = 0; p < D; ++p) gof[p] = group_of(c, p);
     for (int ch = 0; ch < D; ++ch) qf[ch] = skvq_ref_half_to_float(q[(size_t)bq * D + ch]);
     double *s = (double *)malloc(sizeof(double) * (size_t)T);
     if (!s) {
@@ -391,8 +413,8 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       double dot = 0.0;
       for (int p = 0; p < D; ++p) {
         double kd = (double)skvq_ref_k_get(row, c->k_levels, p) *
-                        (double)meta_load(buf->k_meta, mi + 2 * (p / G), c->meta_format) +
-                    (double)meta_load(buf->k_meta, mi + 2 * (p / G) + 1, c->meta_format);
+                        (double)meta_load(buf->k_meta, mi + 2 * gof[p], c->meta_format) +
+                    (double)meta_load(buf->k_meta, mi + 2 * gof[p] + 1, c->meta_format);
         dot += qf[pk[p]] * kd;
       }
       s[a] = (double)c->sm_scale * dot;
@@ -418,8 +440,8 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       size_t mi = (head * tcap + t) * ng * 2;
       for (int p = 0; p < D; ++p) {
         double vd = (double)skvq_ref_v_get(blk, c->v_levels, (int)(t % VBT), p) *
-                        (double)meta_load(buf->v_meta, mi + 2 * (p / G), c->meta_format) +
-                    (double)meta_load(buf->v_meta, mi + 2 * (p / G) + 1, c->meta_format);
+                        (double)meta_load(buf->v_meta, mi + 2 * gof[p], c->meta_format) +
+                    (double)meta_load(buf->v_meta, mi + 2 * gof[p] + 1, c->meta_format);
         acc[pv[p]] += w * vd;
       }
     }

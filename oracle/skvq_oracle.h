@@ -37,7 +37,9 @@ extern "C" {
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim must be 128      */
-  int32_t group_size;                             /* G, divides head_dim       */
+  int32_t group_size;                             /* G, divides head_dim (with
+                                                     group_bounds: the average
+                                                     group size)               */
   int32_t k_levels, v_levels;                     /* 16 = 4-bit, 4 = 2-bit, 3 = "1.5-bit" (keys: 16 or 4) */
   int32_t window;                                 /* W >= 1                    */
   int32_t n_sink;                                 /* S >= 0: tokens 0..S-1 are
@@ -48,6 +50,11 @@ typedef struct {
   const int32_t *perm_k, *perm_v;                 /* [Hk][D] gather index      */
   const float *clip_k, *clip_v;                   /* [Hk][D/G] alpha           */
   float sm_scale;                                 /* softmax scale             */
+  const int32_t *group_bounds;                    /* NULL = uniform groups; else
+                                                     D/G + 1 ascending entries,
+                                                     0 .. D: group g covers the
+                                                     reordered positions
+                                                     [bounds[g], bounds[g+1])  */
 } skvq_ref_config;
 
 typedef struct {

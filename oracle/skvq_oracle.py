@@ -36,7 +36,7 @@ class _Config(C.Structure):
                 ("v_levels", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
                 ("meta_format", C.c_int32), ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
-                ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
+                ("clip_v", C.c_void_p), ("sm_scale", C.c_float), ("group_bounds", C.c_void_p)]
 
 
 class _Buffers(C.Structure):
@@ -134,17 +134,21 @@ class OracleCache:
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens,
                  perm_k, perm_v, clip_k, clip_v, sm_scale=None, k_bits=2.0, fill=0, n_sink=0,
-                 meta="f32"):
+                 meta="f32", group_bounds=None):
         self.perm_k = np.ascontiguousarray(perm_k, np.int32)
         self.perm_v = np.ascontiguousarray(perm_v, np.int32)
         self.clip_k = np.ascontiguousarray(clip_k, np.float32)
         self.clip_v = np.ascontiguousarray(clip_v, np.float32)
         if sm_scale is None:
             sm_scale = 1.0 / np.sqrt(HEAD_DIM)
+        # unequal groups: HEAD_DIM // group_size + 1 ascending boundaries (group_size = the average)
+        self.group_bounds = None if group_bounds is None else np.ascontiguousarray(group_bounds, np.int32)
+        assert self.group_bounds is None or self.group_bounds.shape == (HEAD_DIM // group_size + 1,)
         self.cfg = _Config(batch, n_q_heads, n_kv_heads, HEAD_DIM, group_size, levels_of(k_bits),
                            levels_of(v_bits), window, n_sink, META_FORMATS[meta], max_quant_tokens,
                            _ptr(self.perm_k),
-                           _ptr(self.perm_v), _ptr(self.clip_k), _ptr(self.clip_v), sm_scale)
+                           _ptr(self.perm_v), _ptr(self.clip_k), _ptr(self.clip_v), sm_scale,
+                           None if self.group_bounds is None else _ptr(self.group_bounds))
         sizes = (C.c_size_t * 6)()
         lib().skvq_ref_sizes(C.byref(self.cfg), sizes)
         self.sizes = [int(s) for s in sizes]

@@ -356,15 +356,17 @@ def numpy_dequantize(c, T):
     kq = np.zeros((B, Hk, nq, D))
     vq = np.zeros((B, Hk, nq, D))
     p = np.arange(D)
+    bounds = getattr(c, "group_bounds", None)
+    gof = p // G if bounds is None else np.searchsorted(np.asarray(bounds), p, side="right") - 1
     if c.cfg.k_levels == 16:
         kc = (c.k_codes[:, :, :nq, p // 2] >> (4 * (p % 2))) & 15
     else:
         kc = (c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3
-    ks = c.k_meta[:, :, :nq, p // G, 0].astype(np.float64)
-    kz = c.k_meta[:, :, :nq, p // G, 1].astype(np.float64)
+    ks = c.k_meta[:, :, :nq, gof, 0].astype(np.float64)
+    kz = c.k_meta[:, :, :nq, gof, 1].astype(np.float64)
     kd = kc * ks + kz
-    vs = c.v_meta[:, :, :nq, p // G, 0].astype(np.float64)
-    vz = c.v_meta[:, :, :nq, p // G, 1].astype(np.float64)
+    vs = c.v_meta[:, :, :nq, gof, 0].astype(np.float64)
+    vz = c.v_meta[:, :, :nq, gof, 1].astype(np.float64)
     vc = np.zeros((B, Hk, nq, D), np.int64)
     for b in range(B):
         for h in range(Hk):
@@ -692,3 +694,102 @@ def test_lossy_cache_with_compact_meta_equals_dequantize_then_textbook_attention
     b.prefill(k, v)
     for x, y in zip(a.arrays(), b.arrays()):
         assert np.array_equal(x, y)
+
+
+# ---- unequal groups (Section 4.1: clustering the channels gives groups of unequal size) ----
+
+UNEQUAL_BOUNDS = [(32, [0, 16, 32, 80, 128]), (64, [0, 48, 128]), (32, [0, 7, 8, 100, 128]), (64, [0, 127, 128])]
+
+
+def grid_data_bounds(rng, shape_bht, bounds, levels, perm):
+    """Like grid_data, with one grid per (token, kv head, unequal group)."""
+    B, Hk, T = shape_bht
+    x = np.zeros((B, Hk, T, D), np.float32)
+    for b in range(B):
+        for h in range(Hk):
+            for t in range(T):
+                for lo, hi in zip(bounds[:-1], bounds[1:]):
+                    step = 2.0 ** int(rng.integers(-5, 2))
+                    base = step * int(rng.integers(-20, 20))
+                    k = rng.integers(0, levels, hi - lo)
+                    if hi - lo >= 2:
+                        k[0], k[-1] = 0, levels - 1
+                    x[b, h, t, perm[h, lo:hi]] = base + step * k
+    return x.astype(np.float16)
+
+
+@pytest.mark.parametrize("G,bounds", UNEQUAL_BOUNDS)
+def test_unequal_groups_scale_and_zero_come_from_exactly_their_positions(oracle, G, bounds):
+    """(scale, zero) of group g are Eq. 2 over the reordered positions [b_g, b_{g+1}) and nothing
+    else; the codes of a group use its own pair."""
+    rng = np.random.default_rng(800 + len(bounds) + bounds[1])
+    B, Hq, Hk, W, T = 1, 2, 2, 4, 30
+    ng = D // G
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    ck = rng.uniform(0.8, 1.0, (Hk, ng)).astype(np.float32)
+    cv = rng.uniform(0.8, 1.0, (Hk, ng)).astype(np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, 2.0, W, 32, pk, pv, ck, cv, group_bounds=bounds)
+    assert c.prefill(k, v) == 0
+    f32 = np.float32
+    for h in range(Hk):
+        for t in range(T - W):
+            for x, perm, clip, meta, code in ((k, pk, ck, c.k_meta, c.k_code), (v, pv, cv, c.v_meta, c.v_code)):
+                xp = x[0, h, t, perm[h]].astype(f32)
+                for g, (lo, hi) in enumerate(zip(bounds[:-1], bounds[1:])):
+                    mn, mx = xp[lo:hi].min(), xp[lo:hi].max()
+                    zero = f32(clip[h, g] * mn)
+                    scale = f32(f32(f32(clip[h, g] * mx) - zero) / f32(3))
+                    assert meta[0, h, t, g, 0] == scale and meta[0, h, t, g, 1] == zero
+                    want, _, _ = oracle.encode_group(xp[lo:hi], float(clip[h, g]), 4)
+                    assert [code(0, h, t, p) for p in range(lo, hi)] == list(want)
+
+
+@pytest.mark.parametrize("G,bounds", UNEQUAL_BOUNDS)
+@pytest.mark.parametrize("k_bits,v_bits", [(2.0, 1.5), (4.0, 4.0)])
+def test_unequal_groups_lossless_and_lossy_caches(oracle, G, bounds, k_bits, v_bits):
+    rng = np.random.default_rng(900 + bounds[1])
+    B, Hq, Hk, W, T = 1, 4, 2, 8, 50
+    ng = D // G
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    ones = np.ones((Hk, ng), np.float32)
+    # lossless: every unequal group on its own exact grid -> the library's attention on the originals
+    k = grid_data_bounds(rng, (B, Hk, T), bounds, oracle.levels_of(k_bits), pk)
+    v = grid_data_bounds(rng, (B, Hk, T), bounds, oracle.levels_of(v_bits), pv)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ones, ones, sm_scale=0.05, k_bits=k_bits,
+                           group_bounds=bounds)
+    assert c.prefill(k, v) == 0
+    ref = sdpa64(q, k, v, 0.05)
+    assert np.abs(c.decode(q) - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    # lossy: independent unpack + dequantize with the same boundaries, then the library's attention
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    ck = rng.uniform(0.8, 1.0, (Hk, ng)).astype(np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, ck, k_bits=k_bits, group_bounds=bounds)
+    assert c.prefill(k[:, :, :20], v[:, :, :20]) == 0
+    for s in range(20, T):
+        assert c.append(k[:, :, s], v[:, :, s]) == 0
+    kq, vq = numpy_dequantize(c, T)
+    kfull = np.concatenate([kq, k[:, :, T - W:].astype(np.float64)], axis=2)
+    vfull = np.concatenate([vq, v[:, :, T - W:].astype(np.float64)], axis=2)
+    ref = sdpa64(q, kfull, vfull, 1 / np.sqrt(D))
+    assert np.abs(c.decode(q) - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+
+
+def test_uniform_boundaries_are_the_uniform_groups_and_bad_boundaries_are_refused(oracle):
+    rng = np.random.default_rng(950)
+    B, Hq, Hk, W, T, G = 1, 2, 2, 4, 40, 32
+    k = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, D // G), 0.9, np.float32)
+    a = oracle.OracleCache(B, Hq, Hk, G, 1.5, W, 64, pk, pv, clip, clip)
+    b = oracle.OracleCache(B, Hq, Hk, G, 1.5, W, 64, pk, pv, clip, clip, group_bounds=[0, 32, 64, 96, 128])
+    assert a.prefill(k, v) == 0 and b.prefill(k, v) == 0
+    for x, y in zip(a.arrays(), b.arrays()):
+        assert np.array_equal(x, y)
+    for bad in ([0, 32, 32, 96, 128], [1, 32, 64, 96, 128], [0, 32, 64, 96, 127], [0, 64, 32, 96, 128]):
+        c = oracle.OracleCache(B, Hq, Hk, G, 1.5, W, 64, pk, pv, clip, clip, group_bounds=bad)
+        assert c.prefill(k, v) == -1
