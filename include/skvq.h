@@ -73,7 +73,8 @@ typedef struct {
   int32_t n_q_heads;    /* Hq, a multiple of n_kv_heads with Hq/Hk <= 8                   */
   int32_t n_kv_heads;   /* Hk                                                             */
   int32_t head_dim;     /* D, must be 128                                                 */
-  int32_t group_size;   /* G in {32, 64, 128}: consecutive REORDERED channels of a token  */
+  int32_t group_size;   /* G in {32, 64, 128}: consecutive REORDERED channels of a token;
+                           with group_bounds, the AVERAGE group size (D/G groups)         */
   int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2 or SKVQ_BITS_4                    */
   int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_1P5, SKVQ_BITS_2 or SKVQ_BITS_4   */
   int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
@@ -86,6 +87,12 @@ typedef struct {
   const float *clip_k;   /* HOST [Hk][D/G]: alpha in (0,1] per (kv head, group), Eq. 2    */
   const float *clip_v;   /* HOST [Hk][D/G]                                                */
   float sm_scale;        /* softmax scale; 0 selects 1/sqrt(D)                            */
+  const int32_t *group_bounds; /* HOST [D/G + 1] or NULL.  NULL: uniform groups of G positions.
+                           Else (Section 4.1: clustering the channels gives groups of unequal
+                           size, G being their average): group g covers the reordered
+                           positions [bounds[g], bounds[g+1]), bounds[0] = 0 < ... < bounds[D/G]
+                           = D, every boundary a multiple of 16 (SKVQ_ERR_UNSUPPORTED
+                           otherwise).  The same boundaries serve keys and values.        */
 } skvq_config;
 
 /* DEVICE buffers of one layer's cache; byte sizes come from skvq_sizes(), in this order.

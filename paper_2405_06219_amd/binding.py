@@ -29,7 +29,7 @@ class skvq_config(C.Structure):
                 ("v_bits", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
                 ("meta_format", C.c_int32), ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
-                ("clip_v", C.c_void_p), ("sm_scale", C.c_float)]
+                ("clip_v", C.c_void_p), ("sm_scale", C.c_float), ("group_bounds", C.c_void_p)]
 
 
 class skvq_buffers(C.Structure):
@@ -81,13 +81,18 @@ def bits_enum(bits: float) -> int:
 
 
 def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
-                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM, n_sink=0, meta="f32"):
+                clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM, n_sink=0, meta="f32",
+                group_bounds=None):
     """Returns (skvq_config, keepalive): the numpy arrays the config points to."""
     keep = [np.ascontiguousarray(perm_k, np.int32), np.ascontiguousarray(perm_v, np.int32),
             np.ascontiguousarray(clip_k, np.float32), np.ascontiguousarray(clip_v, np.float32)]
+    if group_bounds is not None:
+        keep.append(np.ascontiguousarray(group_bounds, np.int32))
+        if keep[4].shape != (head_dim // group_size + 1,):
+            raise ValueError("group_bounds needs head_dim / group_size + 1 entries")
     cfg = skvq_config(batch, n_q_heads, n_kv_heads, head_dim, group_size, bits_enum(k_bits), bits_enum(v_bits),
                       window, n_sink, META_FORMATS[meta], max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
-                      keep[3].ctypes.data, float(sm_scale))
+                      keep[3].ctypes.data, float(sm_scale), keep[4].ctypes.data if group_bounds is not None else None)
     return cfg, keep
 
 
@@ -121,10 +126,10 @@ class SkvqCache:
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
                  clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None, n_sink=0,
-                 meta="f32"):
+                 meta="f32", group_bounds=None):
         self.cfg, self._keep = make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window,
                                            max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale, k_bits,
-                                           n_sink=n_sink, meta=meta)
+                                           n_sink=n_sink, meta=meta, group_bounds=group_bounds)
         self.shape = (batch, n_q_heads, n_kv_heads)
         self.device = torch.device(device)
         self.sizes = skvq_sizes(self.cfg)

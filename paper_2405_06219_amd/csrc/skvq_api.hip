@@ -46,6 +46,14 @@ int check_config(const skvq_config *c) {
     return SKVQ_ERR_INVALID_ARG;
   if (!c->perm_k || !c->perm_v || !c->clip_k || !c->clip_v) return SKVQ_ERR_INVALID_ARG;
   const int ng = kD / c->group_size;
+  if (c->group_bounds) {
+    const int32_t *gb = c->group_bounds;
+    if (gb[0] != 0 || gb[ng] != kD) return SKVQ_ERR_INVALID_ARG;
+    for (int g = 0; g < ng; ++g)
+      if (gb[g + 1] <= gb[g]) return SKVQ_ERR_INVALID_ARG;
+    for (int g = 0; g <= ng; ++g)
+      if (gb[g] % 16) return SKVQ_ERR_UNSUPPORTED;
+  }
   for (int which = 0; which < 2; ++which) {
     const int32_t *perm = which ? c->perm_v : c->perm_k;
     const float *clip = which ? c->clip_v : c->clip_k;
@@ -155,6 +163,17 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.R = L.Hq / L.Hk;
   L.G = cfg->group_size;
   L.NG = kD / L.G;
+  L.uneq = 0;
+  L.gmap = 0;
+  for (int n = 0; n < 8; ++n) {  // group of positions 16n .. 16n+15
+    int g = 16 * n / L.G;
+    if (cfg->group_bounds) {
+      g = 0;
+      while (16 * n >= cfg->group_bounds[g + 1]) ++g;
+      if (g != 16 * n / L.G) L.uneq = 1;
+    }
+    L.gmap |= (unsigned)g << (4 * n);
+  }
   L.W = cfg->window;
   L.S = cfg->n_sink;
   L.meta_fmt = cfg->meta_format;

@@ -1,7 +1,9 @@
 // Matrix-core kernel of skvq_decode_attention for gfx950: packed chunks and the fp16 tokens
 // (attention sinks, window) in one launch, one partial per chunk.  Templated on the query
 // heads a workgroup serves (1, 2, 4), the K format (2-bit, 4-bit), the V format (3-level, 2-bit,
-// 4-bit), the (scale, zero) format and the groups per head (1, 2, 4).  This header is compiled
+// 4-bit), the (scale, zero) format, the groups per head (1, 2, 4) and whether the groups are
+// unequal (whole 16-position pieces of the head, mapped to groups by Layout::gmap: then every
+// piece has its own score accumulator and weight operand).  This header is compiled
 // once per (K format, V format) pair (SKVQ_KL, SKVQ_VL) by skvq_decode_mfma_inst.hip.
 // (Merging the partials inside this launch was tried and dropped: the device-scope fences it
 // needs write back and invalidate a whole L2 each, 25 us over 256 workgroups.)
@@ -255,7 +257,7 @@ struct RingData {
   unsigned v[4];  // lane = channel pair: the 4 tokens' values of channels 2l, 2l+1
 };
 
-template <int R, int KL, int VL, int META, int NG>
+template <int R, int KL, int VL, int META, int NG, bool UNEQ>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
                                                                   int n_splits, int passes) {
@@ -268,6 +270,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // j = sp (mod n_splits), dealt the same way.
   constexpr bool TERNARY = VL == 3, K4 = KL == 16, V4 = VL == 16;
   constexpr float kCentre = 0.5f * (KL - 1);  // the key codes enter the products centred
+  // score accumulators / weight operands: one per group, or (unequal groups) one per 16 positions
+  constexpr int NACC = UNEQ ? 8 : NG;
+  const unsigned gmap = L.gmap;
+  auto piece_group = [&](int n) { return (int)((gmap >> (4 * n)) & 15u); };  // group of positions 16n..16n+15
   __shared__ Smem<R, TERNARY, NG> sm;
   SKVQ_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63;
@@ -443,17 +449,31 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // (4-bit): the products then sum q*(c - centre), centred codes, which keeps both halves of
   // scale*sum q(c-centre) + (zero+centre*scale)*sum q  small.
   float qsc[R][NG];
-  float4_t dinit[NG];
+  float4_t dinit[UNEQ ? 1 : NG];
+  if constexpr (UNEQ) {
+    // (a piece's accumulator sums only 16 products: it starts from zero, uncentred)
 #pragma unroll
-  for (int g = 0; g < NG; ++g)
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float sum = 0.f;
+      for (int r = 0; r < R; ++r) {
+        float sum = 0.f;
 #pragma unroll
-      for (int x = 0; x < 8 / NG; ++x) sum += sm.qpart[r][g * (8 / NG) + x];
-      if (r < R) qsc[r][g] = c * sum;
-      dinit[g][r] = -kCentre * sum * (1.0f / 65536.0f);
-    }
+        for (int x = 0; x < 8; ++x) sum += piece_group(x) == g ? sm.qpart[r][x] : 0.f;
+        qsc[r][g] = c * sum;
+      }
+    dinit[0] = float4_t{0.f, 0.f, 0.f, 0.f};
+  } else {
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float sum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 8 / NG; ++x) sum += sm.qpart[r][g * (8 / NG) + x];
+        if (r < R) qsc[r][g] = c * sum;
+        dinit[g][r] = -kCentre * sum * (1.0f / 65536.0f);
+      }
+  }
 
   // ---- ring slices of this wave (plain vector arithmetic, wave-local) ----
   if (ring_owner) {
@@ -553,37 +573,57 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     const bool valid = tile * 64 + lane <= last_token;
 
     // ---- scores: 32 products of 4 channels each, one accumulator per group ----
-    float4_t dg[NG];
+    float4_t dg[NACC];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) dg[g] = dinit[g];
+    for (int g = 0; g < NACC; ++g) dg[g] = UNEQ ? float4_t{0.f, 0.f, 0.f, 0.f} : dinit[g];
     if constexpr (K4) {
-#define SKVQ_QK4(Q, C, DW) dg[(DW) * NG / 16] = qk_dword4<DW>(cur.k##Q.C, qop_lo, qop_hi, dg[(DW) * NG / 16])
+#define SKVQ_QK4(Q, C, DW) dg[(DW) * NACC / 16] = qk_dword4<DW>(cur.k##Q.C, qop_lo, qop_hi, dg[(DW) * NACC / 16])
       SKVQ_QK4(0, x, 0);  SKVQ_QK4(0, y, 1);  SKVQ_QK4(0, z, 2);  SKVQ_QK4(0, w, 3);
       SKVQ_QK4(1, x, 4);  SKVQ_QK4(1, y, 5);  SKVQ_QK4(1, z, 6);  SKVQ_QK4(1, w, 7);
       SKVQ_QK4(2, x, 8);  SKVQ_QK4(2, y, 9);  SKVQ_QK4(2, z, 10); SKVQ_QK4(2, w, 11);
       SKVQ_QK4(3, x, 12); SKVQ_QK4(3, y, 13); SKVQ_QK4(3, z, 14); SKVQ_QK4(3, w, 15);
 #undef SKVQ_QK4
     } else {
-      dg[0 * NG / 8] = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, dg[0 * NG / 8]);
-      dg[1 * NG / 8] = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, dg[1 * NG / 8]);
-      dg[2 * NG / 8] = qk_dword<2>(cur.k0.z, qop_lo, qop_hi, dg[2 * NG / 8]);
-      dg[3 * NG / 8] = qk_dword<3>(cur.k0.w, qop_lo, qop_hi, dg[3 * NG / 8]);
-      dg[4 * NG / 8] = qk_dword<4>(cur.k1.x, qop_lo, qop_hi, dg[4 * NG / 8]);
-      dg[5 * NG / 8] = qk_dword<5>(cur.k1.y, qop_lo, qop_hi, dg[5 * NG / 8]);
-      dg[6 * NG / 8] = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, dg[6 * NG / 8]);
-      dg[7 * NG / 8] = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, dg[7 * NG / 8]);
+      dg[0 * NACC / 8] = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, dg[0 * NACC / 8]);
+      dg[1 * NACC / 8] = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, dg[1 * NACC / 8]);
+      dg[2 * NACC / 8] = qk_dword<2>(cur.k0.z, qop_lo, qop_hi, dg[2 * NACC / 8]);
+      dg[3 * NACC / 8] = qk_dword<3>(cur.k0.w, qop_lo, qop_hi, dg[3 * NACC / 8]);
+      dg[4 * NACC / 8] = qk_dword<4>(cur.k1.x, qop_lo, qop_hi, dg[4 * NACC / 8]);
+      dg[5 * NACC / 8] = qk_dword<5>(cur.k1.y, qop_lo, qop_hi, dg[5 * NACC / 8]);
+      dg[6 * NACC / 8] = qk_dword<6>(cur.k1.z, qop_lo, qop_hi, dg[6 * NACC / 8]);
+      dg[7 * NACC / 8] = qk_dword<7>(cur.k1.w, qop_lo, qop_hi, dg[7 * NACC / 8]);
     }
     // u = log2-domain score minus the running reference
     float u[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) u[r] = -mref[r];
+    if constexpr (UNEQ) {
+      float a_t[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float2 kmeta = meta_value(cur.kmeta.m[g]);
-      const float a_t = kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
-      const float zc = fmaf(kCentre, kmeta.x, kmeta.y);  // dequantized value of the centre code
+      for (int g = 0; g < NG; ++g) {
+        const float2 kmeta = meta_value(cur.kmeta.m[g]);
+        a_t[g] = kmeta.x * (c * 65536.0f);
 #pragma unroll
-      for (int r = 0; r < R; ++r) u[r] = fmaf(dg[g][r], a_t, fmaf(zc, qsc[r][g], u[r]));
+        for (int r = 0; r < R; ++r) u[r] = fmaf(kmeta.y, qsc[r][g], u[r]);  // zero-point * sum of the query
+      }
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {  // each 16-position piece times the scale of its group
+        const int g = piece_group(x);
+        float a = a_t[0];
+#pragma unroll
+        for (int y = 1; y < NG; ++y) a = g == y ? a_t[y] : a;
+#pragma unroll
+        for (int r = 0; r < R; ++r) u[r] = fmaf(dg[x][r], a, u[r]);
+      }
+    } else {
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const float2 kmeta = meta_value(cur.kmeta.m[g]);
+        const float a_t = kmeta.x * (c * 65536.0f);       // codes carry 2^(s-24), the query 2^(8-s)
+        const float zc = fmaf(kCentre, kmeta.x, kmeta.y);  // dequantized value of the centre code
+#pragma unroll
+        for (int r = 0; r < R; ++r) u[r] = fmaf(dg[g][r], a_t, fmaf(zc, qsc[r][g], u[r]));
+      }
     }
     float vs[NG], vz[NG], vs_top = 0.f;
 #pragma unroll
@@ -662,11 +702,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     const int col = lane & 15, kb = lane >> 4;
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
-      half8_t pop[NG];  // the weights (B operand) of each group of channel tiles
+      half8_t pop[NACC];  // the weights (B operand) of each group (or piece) of channel tiles
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        pop[g] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        if (col < 2 * R) pop[g] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col][8 * kb]);
+      for (int x = 0; x < NACC; ++x) {
+        const int g = UNEQ ? piece_group(x) : x;
+        pop[x] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+        if (col < 2 * R) pop[x] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col][8 * kb]);
       }
       const Unit16 raw = blk ? cur.v10 : cur.v00;
       if constexpr (V4) {
@@ -674,7 +715,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         const unsigned w[8] = {raw.x, raw.y, raw.z, raw.w, raw2.x, raw2.y, raw2.z, raw2.w};
 #pragma unroll
         for (int n = 0; n < 8; ++n)
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v4_field(w[n]), pop[n * NG / 8], acc[n], 0, 0, 0);
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v4_field(w[n]), pop[n * NACC / 8], acc[n], 0, 0, 0);
       } else if (TERNARY) {
         const unsigned u0 = __builtin_amdgcn_alignbyte(raw.y, raw.x, unit_sh);
         const unsigned u1 = __builtin_amdgcn_alignbyte(raw.z, raw.y, unit_sh);
@@ -696,14 +737,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
           aop[n] = *reinterpret_cast<const uint4_t *>(reinterpret_cast<const char *>(sm.lut) + f[n]);
 #pragma unroll
         for (int n = 0; n < 8; ++n)
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop[n * NG / 8],
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop[n * NACC / 8],
                                                           acc[n], 0, 0, 0);
       } else {
         const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
           const unsigned f = (n & 1) ? (w[n >> 1] >> 8) : w[n >> 1];
-          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_field(f), pop[n * NG / 8], acc[n], 0, 0, 0);
+          acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v_field(f), pop[n * NACC / 8], acc[n], 0, 0, 0);
         }
       }
     }
@@ -712,8 +753,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // Whole triples first.  The loop has no early exit: the wait counters the compiler places
   // are exact only if every path into the loop's top has the same loads in flight, in the
   // same order (buffer a's, then buffer b's).
-  // (A 4-bit row or unit takes twice the registers: those formats rotate two buffers.)
-  if constexpr (K4 || V4) {
+  // (A 4-bit row or unit takes twice the registers, and unequal groups need an accumulator and a
+  // weight operand per 16 positions: those variants rotate two buffers.)
+  if constexpr (K4 || V4 || UNEQ) {
     while (tile_b < tile_end) {
       compute_tile(buf_a, tile_a);
       tile_a = tile_of(n_a += 2);
@@ -798,7 +840,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     for (int w = 0; w < kNW; ++w) {
       const float e = wl[w] > 0.f ? fast_exp2(wm[w] - m) : 0.f, g = rl[w] > 0.f ? fast_exp2(rm[w] - m) : 0.f;
       den = fmaf(e, wl[w], fmaf(g, rl[w], den));
-      if (e > 0.f) num = fmaf(e, sm.wb[w].stage[r][p] + sm.wz[w][r][p * NG / kD], num);
+      if (e > 0.f) num = fmaf(e, sm.wb[w].stage[r][p] + sm.wz[w][r][UNEQ ? piece_group(p >> 4) : p * NG / kD], num);
       if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
     float *part =
@@ -834,14 +876,14 @@ hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T,
   const int passes = decode_passes(L.R), rk = L.R == 1 ? 1 : L.R == 2 ? 2 : 4;
   if ((long long)L.Hk * passes > 65535 || L.R > 8) return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
-#define SKVQ_LAUNCH(RR, MM, GG) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes)
-#define SKVQ_LAUNCH_NG(RR, MM)                 \
-  switch (L.NG) {                              \
-    case 1: SKVQ_LAUNCH(RR, MM, 1); break;     \
-    case 2: SKVQ_LAUNCH(RR, MM, 2); break;     \
-    case 4: SKVQ_LAUNCH(RR, MM, 4); break;     \
-    default: return hipErrorInvalidValue;      \
+#define SKVQ_LAUNCH(RR, MM, GG, UU) \
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes)
+#define SKVQ_LAUNCH_NG(RR, MM)                                                                   \
+  switch (L.NG) {                                                                                \
+    case 1: SKVQ_LAUNCH(RR, MM, 1, false); break;                                                \
+    case 2: if (L.uneq) SKVQ_LAUNCH(RR, MM, 2, true); else SKVQ_LAUNCH(RR, MM, 2, false); break; \
+    case 4: if (L.uneq) SKVQ_LAUNCH(RR, MM, 4, true); else SKVQ_LAUNCH(RR, MM, 4, false); break; \
+    default: return hipErrorInvalidValue;                                                        \
   }
 #define SKVQ_LAUNCH_META(RR)                                                \
   switch (L.meta_fmt) {                                                     \

@@ -43,6 +43,9 @@ __device__ __forceinline__ unsigned encode(float x, const GroupParams &g, float 
   return (unsigned)r;
 }
 
+// Group of the 16 positions 16n .. 16n+15 (Layout::gmap).
+__device__ __forceinline__ int tile_group(unsigned gmap, int n) { return (gmap >> (4 * n)) & 15; }
+
 // min and max over the G/2 consecutive lanes that hold one group (lane l: positions 2l, 2l+1)
 __device__ __forceinline__ void group_minmax(float &mn, float &mx, int G) {
   for (int off = 1; off < G / 2; off <<= 1) {
@@ -50,15 +53,38 @@ __device__ __forceinline__ void group_minmax(float &mn, float &mx, int G) {
     mx = fmaxf(mx, __shfl_xor(mx, off));
   }
 }
+// The same for unequal groups (whole 16-position tiles, 8 lanes each): first over the lanes of a
+// tile, then over the other seven tiles, taking those of the lane's own group.
+__device__ __forceinline__ void group_minmax_unequal(float &mn, float &mx, int lane, unsigned gmap) {
+  for (int off = 1; off < 8; off <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off));
+    mx = fmaxf(mx, __shfl_xor(mx, off));
+  }
+  const int tile = lane >> 3, g = tile_group(gmap, tile);
+  const float tmn = mn, tmx = mx;
+#pragma unroll
+  for (int k = 1; k < 8; ++k) {
+    const int other = (tile + k) & 7;
+    const float omn = __shfl(tmn, 8 * other + (lane & 7)), omx = __shfl(tmx, 8 * other + (lane & 7));
+    if (tile_group(gmap, other) == g) {
+      mn = fminf(mn, omn);
+      mx = fmaxf(mx, omx);
+    }
+  }
+}
 
 // Reorder one row through LDS and encode it.  row_lds: 128 halves of this wavefront.
 // Returns this lane's two codes and the group's (scale, zero).
 __device__ __forceinline__ void encode_row(const __half *row_lds, int p0, int p1, float alpha, int G,
-                                           float top, int fmt, unsigned &c0, unsigned &c1, MetaPair &meta) {
+                                           float top, int fmt, bool uneq, unsigned gmap, int lane, unsigned &c0,
+                                           unsigned &c1, MetaPair &meta) {
   const float x0 = __half2float(row_lds[p0]);
   const float x1 = __half2float(row_lds[p1]);
   float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
-  group_minmax(mn, mx, G);
+  if (uneq)
+    group_minmax_unequal(mn, mx, lane, gmap);
+  else
+    group_minmax(mn, mx, G);
   const GroupParams g = group_params(mn, mx, alpha, top, fmt);
   c0 = encode(x0, g, top);
   c1 = encode(x1, g, top);
@@ -122,7 +148,8 @@ constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte a
 // WIDE, four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).
 template <bool WIDE>
 __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
-                                          float top, int fmt, GroupParams &gp) {
+                                          float top, int fmt, bool uneq, unsigned gmap, int lane,
+                                          GroupParams &gp) {
   const int ch[16] = {pm[0].x, pm[0].y, pm[0].z, pm[0].w, pm[1].x, pm[1].y, pm[1].z, pm[1].w,
                       pm[2].x, pm[2].y, pm[2].z, pm[2].w, pm[3].x, pm[3].y, pm[3].z, pm[3].w};
   float x[16];
@@ -134,9 +161,25 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
     mn = fminf(mn, x[e]);
     mx = fmaxf(mx, x[e]);
   }
-  for (int off = 1; off < G / 16; off <<= 1) {
-    mn = fminf(mn, __shfl_xor(mn, off));
-    mx = fmaxf(mx, __shfl_xor(mx, off));
+  if (uneq) {
+    // unequal groups: the other seven 16-position pieces of the token sit in the other seven lanes
+    // of this lane's group of eight; take those that belong to the same group
+    const int n = lane & 7, g = tile_group(gmap, n);
+    const float tmn = mn, tmx = mx;
+#pragma unroll
+    for (int k = 1; k < 8; ++k) {
+      const int other = (n + k) & 7;
+      const float omn = __shfl(tmn, (lane & ~7) + other), omx = __shfl(tmx, (lane & ~7) + other);
+      if (tile_group(gmap, other) == g) {
+        mn = fminf(mn, omn);
+        mx = fmaxf(mx, omx);
+      }
+    }
+  } else {
+    for (int off = 1; off < G / 16; off <<= 1) {
+      mn = fminf(mn, __shfl_xor(mn, off));
+      mx = fmaxf(mx, __shfl_xor(mx, off));
+    }
   }
   gp = group_params(mn, mx, alpha, top, fmt);
   // code = rint(clamp(y, 0, top)): clamping first gives the same integer because the bounds are
@@ -190,8 +233,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     *reinterpret_cast<uint4 *>(&rows[wave][1][4 + lr][8 * lp]) = vb;
   }
   const int i = lane >> 3, n = lane & 7;
-  const int grp = (16 * n) / L.G;
-  const bool writes_meta = (16 * n) % L.G == 0;
+  const bool uneq = L.uneq != 0;
+  const int grp = uneq ? tile_group(L.gmap, n) : (16 * n) / L.G;
+  const bool writes_meta = uneq ? (n == 0 || tile_group(L.gmap, n - 1) != grp) : (16 * n) % L.G == 0;
   const float ak = L.clip_k[hk * L.NG + grp], av = L.clip_v[hk * L.NG + grp];
   int4 pk[4], pv[4];
   {
@@ -208,8 +252,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   __syncthreads();
 
   GroupParams gk, gv;
-  const uint2 kw = encode16<KL == 16>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, gk);
-  const uint2 vw = encode16<VL == 16>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, gv);
+  const uint2 kw = encode16<KL == 16>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, uneq, L.gmap, lane, gk);
+  const uint2 vw = encode16<VL == 16>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, uneq, L.gmap, lane, gv);
   if (valid) {
     if (KL == 16)
       reinterpret_cast<uint2 *>(L.k_codes + (head * L.Tcap + t) * (kD / 2))[n] = kw;
@@ -319,7 +363,8 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   const __half2 fresh2 = reinterpret_cast<const __half2 *>(fresh)[lane];
   const int s = evict ? (int)(te % kVBlock) : 0, kb = s >> 3, i = s & 7;
   uint8_t *blk = L.v_codes + (head * L.n_vblocks + (evict ? te / kVBlock : 0)) * L.v_block_bytes;
-  const int grp = (2 * lane) / L.G;
+  const bool uneq = L.uneq != 0;
+  const int grp = uneq ? tile_group(L.gmap, lane >> 3) : (2 * lane) / L.G;
   __half2 old2 = fresh2;
   int p0 = 0, p1 = 0;
   float alpha = 1.f;
@@ -356,9 +401,11 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   const float top = (float)((wave ? L.v_levels : L.k_levels) - 1);
   unsigned c0, c1;
   MetaPair mp;
-  encode_row(rows[wave], p0, p1, alpha, L.G, top, L.meta_fmt, c0, c1, mp);
+  encode_row(rows[wave], p0, p1, alpha, L.G, top, L.meta_fmt, uneq, L.gmap, lane, c0, c1, mp);
   void *meta = wave ? L.v_meta : L.k_meta;
-  if ((2 * lane) % L.G == 0)
+  const bool first_of_group =
+      uneq ? ((lane & 7) == 0 && (lane == 0 || tile_group(L.gmap, (lane >> 3) - 1) != grp)) : (2 * lane) % L.G == 0;
+  if (first_of_group)
     meta_store_pair(meta, (head * L.Tcap + te) * L.NG + grp, mp, L.meta_fmt);
 
   if (wave == 0) {

@@ -24,15 +24,16 @@ def log(msg: str):
 
 class Pair:
     def __init__(self, w: synth.Workload, max_quant_tokens: int, perm_k, perm_v, clip_k, clip_v, sm_scale=0.0,
-                 fill=0xAB, device="cuda:0", n_sink=0, meta="f32"):
+                 fill=0xAB, device="cuda:0", n_sink=0, meta="f32", group_bounds=None):
         self.w = w
         osm = sm_scale if sm_scale else None
         self.ref = O.OracleCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                  max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=osm, fill=fill,
-                                 n_sink=n_sink, meta=meta, k_bits=w.k_bits)
+                                 n_sink=n_sink, meta=meta, k_bits=w.k_bits, group_bounds=group_bounds)
         self.gpu = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=sm_scale, fill=fill,
-                               device=device, n_sink=n_sink, meta=meta, k_bits=w.k_bits)
+                               device=device, n_sink=n_sink, meta=meta, k_bits=w.k_bits,
+                               group_bounds=group_bounds)
         self.device = device
 
     def prefill(self, k: np.ndarray, v: np.ndarray):

@@ -90,12 +90,20 @@ def test_validation_rejects_bad_configs(B):
         (dict(group_size=16, clip=np.ones((8, 8), np.float32)), B.SKVQ_ERR_UNSUPPORTED),
         (dict(k_bits=1.5), B.SKVQ_ERR_UNSUPPORTED),
         (dict(n_q_heads=128), B.SKVQ_ERR_UNSUPPORTED),     # 16 query heads per kv head
+        # unequal groups: D/G + 1 ascending boundaries from 0 to D, multiples of 16
+        (dict(group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[0, 32, 32, 96, 128]), B.SKVQ_ERR_INVALID_ARG),
+        (dict(group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[16, 32, 64, 96, 128]), B.SKVQ_ERR_INVALID_ARG),
+        (dict(group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[0, 32, 64, 96, 112]), B.SKVQ_ERR_INVALID_ARG),
+        (dict(group_size=64, clip=np.ones((8, 2), np.float32), group_bounds=[0, 40, 128]), B.SKVQ_ERR_UNSUPPORTED),
     ]
     for kw, want in cases:
         cfg, keep = cfg_for(B, **kw)
         assert B.skvq_validate_config(cfg) == want, kw
         with pytest.raises(B.SkvqError):
             B.skvq_sizes(cfg)
+    good, keep2 = cfg_for(B, group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[0, 16, 32, 48, 128])
+    uniform, keep3 = cfg_for(B, group_size=32)
+    assert B.skvq_validate_config(good) == B.SKVQ_OK and B.skvq_sizes(good) == B.skvq_sizes(uniform)
     assert B.lib().skvq_validate_config(None) == B.SKVQ_ERR_INVALID_ARG
     # create refuses a bad config and null / misaligned buffers before touching the device
     cfg, keep = cfg_for(B, window=0)

@@ -418,12 +418,51 @@ def test_compact_meta_special_values_bit_exact(P, meta):
     pair.assert_buffers_equal()
 
 
+# ---- unequal groups (Section 4.1): boundaries at multiples of 16 reordered positions ----
+UNEQUAL_CASES = [
+    (small("uneq_g32_t15", n_q_heads=8, n_kv_heads=2, group_size=32, context=2200), [0, 16, 32, 80, 128], "f32", 0),
+    (small("uneq_g32_v2_mha_b2", group_size=32, v_bits=2.0, context=900, batch=2), [0, 48, 64, 112, 128], "f32", 0),
+    (small("uneq_g32_k4v4_gqa4", k_bits=4.0, v_bits=4.0, n_q_heads=4, n_kv_heads=1, group_size=32, context=1500),
+     [0, 16, 32, 48, 128], "f16", 5),
+    (small("uneq_g64_t15_gqa2", n_q_heads=4, n_kv_heads=2, group_size=64, context=3100, window=33), [0, 48, 128], "e4m3", 0),
+    (small("uneq_g64_k4v2_gqa8", k_bits=4.0, v_bits=2.0, n_q_heads=8, n_kv_heads=1, group_size=64, context=700),
+     [0, 112, 128], "f32", 1),
+    (small("uneq_g64_k2v4_gqa3", k_bits=2.0, v_bits=4.0, n_q_heads=6, n_kv_heads=2, group_size=64, context=450, window=16),
+     [0, 16, 128], "f32", 0),
+    (small("uneq_g32_written_uniform", group_size=32, context=600), [0, 32, 64, 96, 128], "f32", 0),
+]
+
+
+@pytest.mark.parametrize("w,bounds,meta,S", UNEQUAL_CASES, ids=lambda x: x.name if hasattr(x, "name") else None)
+def test_unequal_groups_prefill_appends_and_decode(P, w, bounds, meta, S):
+    """Prefill, a run of appends across V block and sub-block boundaries, then attention: codes,
+    (scale, zero) and ring bit-exact; outputs within 2e-3."""
+    print("case", w, bounds, meta, S, flush=True)
+    n = 41
+    pair, k, v, q = P.make_pair(w, extra_tokens=n, n_sink=S, meta=meta, group_bounds=bounds)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
+    for s in range(n):
+        pair.append(*synth.make_new_token(w, s))
+        if s in (0, 7, 8, 31, 32, n - 1):
+            pair.assert_buffers_equal()
+    out, ref = pair.decode_both(q)
+    err = np.abs(out - ref).max()
+    P.log(f"unequal groups {w.name} {bounds}: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
+    assert err <= P.TOL
+    # the split count must not matter
+    for splits in (1, 7):
+        pair.gpu.skvq_set_num_splits(splits)
+        out2, _ = pair.decode_both(q)
+        assert np.abs(out2 - ref).max() <= P.TOL
+
+
 def test_random_configurations(P):
     """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
     appended tokens and a forced split count.  Buffers bit-exact, outputs within 2e-3."""
     rng = np.random.default_rng(20240506)
-    for case in range(48):
+    for case in range(64):
         hk = int(rng.integers(1, 4))
         r = int(rng.integers(1, 9))
         w = small(f"rand{case}", batch=int(rng.integers(1, 4)), n_kv_heads=hk, n_q_heads=hk * r,
@@ -435,8 +474,13 @@ def test_random_configurations(P):
         meta = str(rng.choice(["f32", "f16", "e4m3"]))
         n_app = int(rng.integers(0, 40))
         splits = int(rng.choice([0, 0, 1, 2, 3, 9, 40, 128]))
-        P.log(f"random case {case}: {w} S={S} meta={meta} appends={n_app} splits={splits}")
-        pair, k, v, q = P.make_pair(w, extra_tokens=n_app + 1, n_sink=S, meta=meta)
+        bounds = None
+        if w.group_size < 128 and rng.integers(2):     # unequal groups: random multiples of 16
+            ng = D // w.group_size
+            cuts = np.sort(rng.choice(np.arange(1, 8), ng - 1, replace=False)) * 16
+            bounds = [0, *[int(x) for x in cuts], D]
+        P.log(f"random case {case}: {w} S={S} meta={meta} appends={n_app} splits={splits} bounds={bounds}")
+        pair, k, v, q = P.make_pair(w, extra_tokens=n_app + 1, n_sink=S, meta=meta, group_bounds=bounds)
         if w.context:
             pair.prefill(k, v)
         for s in range(n_app):
