@@ -54,7 +54,7 @@ def algorithmic_bytes_decode(w, n_tokens: int, n_sink: int = 0, meta: str = "f32
             + w.batch * w.n_q_heads * D * (2 + 4))
 
 
-def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta: str = "f32"):
+def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta: str = "f32", group_bounds=None):
     """Per layer: a cache prefilled with w.context seeded synthetic tokens.  Returns the caches,
     the K/V channel scales on the device, and each prefill call's duration (HIP events, us)."""
     import torch
@@ -72,7 +72,7 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta:
         k, v, pk, pv = synth.make_kv_device(w, device, stream=layer)
         c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                         w.context - w.window + headroom, pk, pv, ck, cv, device=device, n_sink=n_sink,
-                        meta=meta, k_bits=w.k_bits)
+                        meta=meta, k_bits=w.k_bits, group_bounds=group_bounds)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         c.skvq_prefill_quantize(k, v)
@@ -84,7 +84,7 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta:
     return caches, (sk_d, sv_d), prefill_us
 
 
-def cpu_baseline(w, n_sink: int = 0, meta: str = "f32", seconds_budget: float = 25.0):
+def cpu_baseline(w, n_sink: int = 0, meta: str = "f32", group_bounds=None, seconds_budget: float = 25.0):
     """Times the CPU oracle (as it stands) on one layer of the same workload: its own prefill
     from host inputs (untimed), then one append + one decode (timed)."""
     from oracle import skvq_oracle as O
@@ -100,7 +100,8 @@ def cpu_baseline(w, n_sink: int = 0, meta: str = "f32", seconds_budget: float = 
     pk, pv = synth.make_permutations(ws, k[:, :, :4096], v[:, :, :4096])
     ck, cv = synth.make_clip(ws)
     oc = O.OracleCache(ws.batch, ws.n_q_heads, ws.n_kv_heads, ws.group_size, ws.v_bits, ws.window,
-                       ctx - ws.window + 4, pk, pv, ck, cv, n_sink=n_sink, meta=meta, k_bits=ws.k_bits)
+                       ctx - ws.window + 4, pk, pv, ck, cv, n_sink=n_sink, meta=meta, k_bits=ws.k_bits,
+                       group_bounds=group_bounds)
     assert oc.prefill(k, v) == 0
     q = synth.make_query(ws)
     kn, vn = synth.make_new_token(ws, 0)
@@ -130,6 +131,10 @@ def main() -> int:
                     help="override the workload's key width (the headline workload has 2-bit keys)")
     ap.add_argument("--v-bits", type=float, choices=[1.5, 2.0, 4.0], default=0.0,
                     help="override the workload's value width (the headline workload has 1.5-bit values)")
+    ap.add_argument("--group-size", type=int, choices=[32, 64, 128], default=0,
+                    help="override the workload's (average) group size (the headline workload has 128)")
+    ap.add_argument("--group-bounds", default="",
+                    help="unequal groups: comma-separated boundaries, 128/group_size + 1 multiples of 16 from 0 to 128")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -149,7 +154,10 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     if args.context:
         w = w.scaled(args.context)
-    headline_format = not args.k_bits and not args.v_bits
+    headline_format = not args.k_bits and not args.v_bits and not args.group_size and not args.group_bounds
+    if args.group_size:
+        w = dataclasses.replace(w, group_size=args.group_size)
+    bounds = [int(x) for x in args.group_bounds.split(",")] if args.group_bounds else None
     if args.k_bits:
         w = dataclasses.replace(w, k_bits=args.k_bits)
     if args.v_bits:
@@ -157,7 +165,7 @@ def main() -> int:
     n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers
     headroom = n_warm + 2 * n_steps + 9
 
-    caches, (sk_d, sv_d), prefill_us = build_layers(w, n_layers, headroom, device, args.sink, args.meta)
+    caches, (sk_d, sv_d), prefill_us = build_layers(w, n_layers, headroom, device, args.sink, args.meta, bounds)
     prefill_med_us = float(np.median(prefill_us))
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
@@ -234,6 +242,7 @@ def main() -> int:
         "config": {"workload": w.name, "layers": n_layers, "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": D, "context": w.context, "k_bits": w.k_bits,
                    "v_bits": w.v_bits, "group_size": w.group_size, "window": w.window, "n_sink": args.sink, "meta": args.meta,
+                   "group_bounds": bounds,
                    "step": "per layer: skvq_quantize_append + skvq_decode_attention"},
         "us_per_layer": ms_per_step * 1e3 / n_layers,
         "decode_call_us": dec_avg_us,
@@ -256,7 +265,7 @@ def main() -> int:
                      "avg_launch_us": dec_avg_us},
     }
     if not args.no_cpu_baseline:
-        cb = cpu_baseline(w, args.sink, args.meta)
+        cb = cpu_baseline(w, args.sink, args.meta, bounds)
         result["cpu_baseline"] = {
             "value": cb["per_layer_us"] * n_layers, "unit": "us/token", "cores": cb["threads"], "kind": "oracle",
             "sample": (f"1 of {n_layers} layers (append + decode) at context {cb['context_timed']}"
