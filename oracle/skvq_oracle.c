@@ -9,6 +9,11 @@
  *  K codes, one row per (token, kv head).  2-bit: 32 bytes, the code of
  *  reordered position p sits in byte p/4 at bits [2*(p%4), 2*(p%4)+2).
  *  4-bit: 64 bytes, position p in byte p/2 at bits [4*(p%2), 4*(p%2)+4).
+ *  3-bit: 48 bytes in two planes.  Bytes 0..31 hold the low two bits of every
+ *  code exactly as a 2-bit row does.  Bytes 32..47 are four little-endian
+ *  dwords; dword p/32 holds the top bit of position p at bit
+ *  16*((p%16)/8) + KSIG[(p%32)/16][p%8]  (table below; the order is the one
+ *  the GPU kernel unpacks with the fewest shifts).
  *
  *  V codes, one block per 32 consecutive tokens of a kv head, stored so that
  *  the codes of CONSECUTIVE TOKENS of one channel are neighbours (the value
@@ -21,6 +26,10 @@
  *            is bits [13n, 13n+13) and holds sum_i code(n, i) * 3^i  (< 6561).
  *    4-bit : unit = 32 bytes read as a 256-bit little-endian string; code
  *            (n, i) sits at bit 32*n + 16*(i%2) + 4*(i/2).
+ *    3-bit : unit = 24 bytes; bytes 0..15 hold the low two bits of every code
+ *            exactly as the 2-bit unit does; bytes 16..23 are two dwords,
+ *            dword n/4 holds the top bit of code (n, i) at bit
+ *            16*(i%2) + VTAU[n%4][i/2].
  *  A block is zero-filled when its first token arrives, so slots of tokens
  *  that do not exist yet read as code 0.
  *
@@ -166,8 +175,16 @@ double skvq_ref_avg_bits(double code_bits, int meta_bits, int group_size) {
 
 /* -------------------------------------------------------------- format --- */
 
-static size_t v_block_bytes(int levels) { return levels == 3 ? 832 : levels == 16 ? 2048 : 1024; }
-static size_t k_row_bytes(int levels) { return levels == 16 ? D / 2 : D / 4; }
+static size_t v_block_bytes(int levels) {
+  return levels == 3 ? 832 : levels == 16 ? 2048 : levels == 8 ? 1536 : 1024;
+}
+static size_t k_row_bytes(int levels) { return levels == 16 ? 64 : levels == 8 ? 48 : 32; }
+
+/* Bit positions of the top-bit planes of the 3-bit formats (see the format statement). */
+static const int KSIG[2][8] = {{0, 2, 1, 3, 4, 6, 8, 5}, {7, 9, 10, 12, 11, 13, 15, 14}};
+static const int VTAU[4][4] = {{0, 2, 4, 12}, {1, 3, 5, 13}, {6, 8, 10, 14}, {7, 9, 11, 15}};
+static int k3_top_bit(int p) { return 256 + 32 * (p / 32) + 16 * ((p % 16) / 8) + KSIG[(p % 32) / 16][p % 8]; }
+static int v3_top_bit(int n, int i) { return 128 + 32 * (n / 4) + 16 * (i % 2) + VTAU[n % 4][i / 2]; }
 
 void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
   size_t heads = (size_t)c->batch * c->n_kv_heads;
@@ -179,21 +196,6 @@ void skvq_ref_sizes(const skvq_ref_config *c, size_t bytes[6]) {
   bytes[3] = bytes[2];
   bytes[4] = heads * (size_t)(c->window + c->n_sink) * D * 2;
   bytes[5] = bytes[4];
-}
-
-int skvq_ref_k_get(const uint8_t *row, int levels, int p) {
-  if (levels == 16) return (row[p >> 1] >> (4 * (p & 1))) & 15;
-  return (row[p >> 2] >> (2 * (p & 3))) & 3;
-}
-
-void skvq_ref_k_put(uint8_t *row, int levels, int p, int code) {
-  if (levels == 16) {
-    int sh = 4 * (p & 1);
-    row[p >> 1] = (uint8_t)((row[p >> 1] & ~(15 << sh)) | (code << sh));
-    return;
-  }
-  int sh = 2 * (p & 3);
-  row[p >> 2] = (uint8_t)((row[p >> 2] & ~(3 << sh)) | (code << sh));
 }
 
 /* little-endian bit strings */
@@ -213,6 +215,24 @@ static void bits_put(uint8_t *s, int bit, int width, unsigned v) {
   }
 }
 
+int skvq_ref_k_get(const uint8_t *row, int levels, int p) {
+  if (levels == 16) return (row[p >> 1] >> (4 * (p & 1))) & 15;
+  int lo = (row[p >> 2] >> (2 * (p & 3))) & 3;
+  if (levels == 8) return lo + 4 * (int)bits_get(row, k3_top_bit(p), 1);
+  return lo;
+}
+
+void skvq_ref_k_put(uint8_t *row, int levels, int p, int code) {
+  if (levels == 16) {
+    int sh = 4 * (p & 1);
+    row[p >> 1] = (uint8_t)((row[p >> 1] & ~(15 << sh)) | (code << sh));
+    return;
+  }
+  int sh = 2 * (p & 3);
+  row[p >> 2] = (uint8_t)((row[p >> 2] & ~(3 << sh)) | ((code & 3) << sh));
+  if (levels == 8) bits_put(row, k3_top_bit(p), 1, (unsigned)code >> 2);
+}
+
 static const unsigned POW3[8] = {1, 3, 9, 27, 81, 243, 729, 2187};
 
 int skvq_ref_v_get(const uint8_t *block, int levels, int s, int p) {
@@ -223,6 +243,9 @@ int skvq_ref_v_get(const uint8_t *block, int levels, int s, int p) {
     return (int)((f / POW3[i]) % 3);
   }
   if (levels == 16) return (int)bits_get(block + 32 * u, 32 * n + 16 * (i % 2) + 4 * (i / 2), 4);
+  if (levels == 8)
+    return (int)bits_get(block + 24 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2) +
+           4 * (int)bits_get(block + 24 * u, v3_top_bit(n, i), 1);
   return (int)bits_get(block + 16 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2);
 }
 
@@ -236,6 +259,9 @@ void skvq_ref_v_put(uint8_t *block, int levels, int s, int p, int code) {
     bits_put(block + 13 * u, 13 * n, 13, f);
   } else if (levels == 16) {
     bits_put(block + 32 * u, 32 * n + 16 * (i % 2) + 4 * (i / 2), 4, (unsigned)code);
+  } else if (levels == 8) {
+    bits_put(block + 24 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2, (unsigned)code & 3);
+    bits_put(block + 24 * u, v3_top_bit(n, i), 1, (unsigned)code >> 2);
   } else {
     bits_put(block + 16 * u, 32 * (n / 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i / 2), 2,
              (unsigned)code);
@@ -298,8 +324,8 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
 
 static int check_config(const skvq_ref_config *c) {
   if (c->head_dim != D || c->group_size <= 0 || D % c->group_size) return -1;
-  if ((c->k_levels != 4 && c->k_levels != 16) ||
-      (c->v_levels != 4 && c->v_levels != 3 && c->v_levels != 16))
+  if ((c->k_levels != 4 && c->k_levels != 8 && c->k_levels != 16) ||
+      (c->v_levels != 4 && c->v_levels != 3 && c->v_levels != 8 && c->v_levels != 16))
     return -2;
   if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1 ||
       c->n_sink < 0 || c->meta_format < 0 || c->meta_format > 2)

@@ -40,7 +40,7 @@ typedef struct {
   int32_t group_size;                             /* G, divides head_dim (with
                                                      group_bounds: the average
                                                      group size)               */
-  int32_t k_levels, v_levels;                     /* 16 = 4-bit, 4 = 2-bit, 3 = "1.5-bit" (keys: 16 or 4) */
+  int32_t k_levels, v_levels;                     /* 16 = 4-bit, 8 = 3-bit, 4 = 2-bit, 3 = "1.5-bit" (keys: 16, 8 or 4) */
   int32_t window;                                 /* W >= 1                    */
   int32_t n_sink;                                 /* S >= 0: tokens 0..S-1 are
                                                      never quantized           */
@@ -58,8 +58,8 @@ typedef struct {
 } skvq_ref_config;
 
 typedef struct {
-  uint8_t *k_codes;  /* [B][Hk][Tcap][32 (2-bit) or 64 (4-bit)]                */
-  uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][832, 1024 or 2048]              */
+  uint8_t *k_codes;  /* [B][Hk][Tcap][32, 48 or 64: 2-, 3-, 4-bit]             */
+  uint8_t *v_codes;  /* [B][Hk][ceil(Tcap/32)][832, 1024, 1536 or 2048]        */
   void *k_meta;      /* [B][Hk][Tcap][D/G][2] = (scale, zero), 4, 2 or 1 byte  */
   void *v_meta;      /* each (meta_format)                                     */
   uint16_t *k_win;   /* fp16 bits [B][Hk][W+S][D]: rows 0..W-1 are the ring    */

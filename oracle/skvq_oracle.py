@@ -126,7 +126,7 @@ def encode_group(xp: np.ndarray, alpha: float, levels: int, meta: str = "f32"):
 
 
 def levels_of(bits: float) -> int:
-    return {4.0: 16, 2.0: 4, 1.5: 3}[float(bits)]
+    return {4.0: 16, 3.0: 8, 2.0: 4, 1.5: 3}[float(bits)]
 
 
 class OracleCache:
@@ -155,8 +155,8 @@ class OracleCache:
         ng = HEAD_DIM // group_size
         heads = batch * n_kv_heads
         nblk = (max_quant_tokens + VBLOCK - 1) // VBLOCK
-        vb = {3: 832, 4: 1024, 16: 2048}[levels_of(v_bits)]
-        kb = {4: 32, 16: 64}[levels_of(k_bits)]
+        vb = {3: 832, 4: 1024, 8: 1536, 16: 2048}[levels_of(v_bits)]
+        kb = {4: 32, 8: 48, 16: 64}[levels_of(k_bits)]
         self.k_codes = np.full((batch, n_kv_heads, max_quant_tokens, kb), fill, np.uint8)
         self.v_codes = np.full((batch, n_kv_heads, nblk, vb), fill, np.uint8)
         mdt = META_DTYPES[META_FORMATS[meta]]   # fp8 values are kept as their bytes

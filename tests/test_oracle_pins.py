@@ -61,12 +61,15 @@ def test_encoder_hand_derived_values(oracle):
     assert list(c) == [0, 8, 8, 11, 15] and h == 1.0 and z == 0.0
     c, h, z = oracle.encode_group(np.array([0, 1.25, 6, 15, 30], np.float32), 0.5, 16)
     assert h == 1.0 and z == 0.0 and list(c) == [0, 1, 6, 15, 15]
+    # N = 3: eight levels, h = (7 - 0)/7 = 1; 2.5 ties down to 2, 3.5 up to 4
+    c, h, z = oracle.encode_group(np.array([0, 2.5, 3.5, 6.4, 7], np.float32), 1.0, 8)
+    assert list(c) == [0, 2, 4, 6, 7] and h == 1.0 and z == 0.0
     # both ends are scaled by alpha (Eq. 2 and Algorithm 1 agree): all-positive group
     c, h, z = oracle.encode_group(np.array([4, 8, 16], np.float32), 0.5, 4)
     assert z == 2.0 and h == (8.0 - 2.0) / 3 and list(c) == [1, 3, 3]
 
 
-@pytest.mark.parametrize("levels", [4, 3, 16])
+@pytest.mark.parametrize("levels", [4, 3, 16, 8])
 def test_encoder_error_bound_and_clipping(oracle, levels):
     rng = np.random.default_rng(11 + levels)
     top = levels - 1
@@ -87,7 +90,7 @@ def test_encoder_error_bound_and_clipping(oracle, levels):
         assert h == np.float32(np.float32(a32 * x.max()) - np.float32(a32 * x.min())) / np.float32(top)
 
 
-@pytest.mark.parametrize("levels", [4, 3, 16])
+@pytest.mark.parametrize("levels", [4, 3, 16, 8])
 def test_encoder_picks_the_nearest_level(oracle, levels):
     """Brute force: among all codes the chosen one is nearest to x (exact arithmetic)."""
     rng = np.random.default_rng(23 + levels)
@@ -101,7 +104,7 @@ def test_encoder_picks_the_nearest_level(oracle, levels):
         assert np.all(chosen <= best + 1e-6 * h)
 
 
-@pytest.mark.parametrize("levels", [4, 3, 16])
+@pytest.mark.parametrize("levels", [4, 3, 16, 8])
 def test_encoder_lossless_on_a_grid_and_power_of_two_scaling(oracle, levels):
     rng = np.random.default_rng(31 + levels)
     top = levels - 1
@@ -173,6 +176,60 @@ def test_k_row_4bit_layout_is_position_p_at_bit_4p(oracle):
     big = int.from_bytes(row.tobytes(), "little")
     assert [oracle.lib().skvq_ref_k_get(row.ctypes.data, 16, p) for p in range(D)] == \
            [(big >> (4 * p)) & 15 for p in range(D)]
+
+
+KSIG = [[0, 2, 1, 3, 4, 6, 8, 5], [7, 9, 10, 12, 11, 13, 15, 14]]      # the format statement's tables
+VTAU = [[0, 2, 4, 12], [1, 3, 5, 13], [6, 8, 10, 14], [7, 9, 11, 15]]
+
+
+def test_k_row_3bit_layout_is_a_2bit_row_plus_a_top_bit_plane(oracle):
+    seen = 0
+    for p in range(D):
+        row = np.zeros(48, np.uint8)
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, 8, p, 7)
+        big = int.from_bytes(row.tobytes(), "little")
+        top = 256 + 32 * (p // 32) + 16 * ((p % 16) // 8) + KSIG[(p % 32) // 16][p % 8]
+        assert big == (3 << (2 * p)) | (1 << top) and not (big & seen)
+        seen |= big
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, 8, p, 4)       # overwrite: only the top bit stays
+        assert int.from_bytes(row.tobytes(), "little") == 1 << top
+        assert oracle.lib().skvq_ref_k_get(row.ctypes.data, 8, p) == 4
+    assert seen == (1 << 384) - 1
+    rng = np.random.default_rng(7)
+    codes = rng.integers(0, 8, D)
+    row = np.zeros(48, np.uint8)
+    for p in range(D):
+        oracle.lib().skvq_ref_k_put(row.ctypes.data, 8, p, int(codes[p]))
+    assert [oracle.lib().skvq_ref_k_get(row.ctypes.data, 8, p) for p in range(D)] == list(codes)
+    # the first 32 bytes are the 2-bit row of the low two bits
+    two = np.zeros(32, np.uint8)
+    for p in range(D):
+        oracle.lib().skvq_ref_k_put(two.ctypes.data, 4, p, int(codes[p]) & 3)
+    assert np.array_equal(row[:32], two)
+
+
+def test_v_block_3bit_layout_is_a_2bit_unit_plus_a_top_bit_plane(oracle):
+    seen = 0
+    for s_ in range(32):
+        for p in range(D):
+            blk = np.zeros(1536, np.uint8)
+            oracle.lib().skvq_ref_v_put(blk.ctypes.data, 8, s_, p, 7)
+            big = int.from_bytes(blk.tobytes(), "little")
+            u, n, i = 16 * (s_ // 8) + p % 16, p // 16, s_ % 8
+            low = 32 * (n // 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i // 2)
+            top = 128 + 32 * (n // 4) + 16 * (i % 2) + VTAU[n % 4][i // 2]
+            assert big == ((3 << low) | (1 << top)) << (192 * u) and not (big & seen)
+            seen |= big
+            assert oracle.lib().skvq_ref_v_get(blk.ctypes.data, 8, s_, p) == 7
+    assert seen == (1 << (1536 * 8)) - 1
+    rng = np.random.default_rng(8)
+    codes = rng.integers(0, 8, (32, D))
+    blk = np.zeros(1536, np.uint8)
+    for s_ in range(32):
+        for p in range(D):
+            oracle.lib().skvq_ref_v_put(blk.ctypes.data, 8, s_, p, int(codes[s_, p]))
+    got = [[oracle.lib().skvq_ref_v_get(blk.ctypes.data, 8, s_, p) for p in range(D)] for s_ in range(32)]
+    assert np.array_equal(np.array(got), codes)
 
 
 def test_v_block_4bit_layout_is_a_bijection_with_token_neighbours(oracle):
@@ -252,6 +309,10 @@ def test_bytes_per_token_match_the_byte_model(oracle):
     c3 = oracle.OracleCache(1, 32, 8, 64, 4.0, 128, 4096, perm, perm, two, two, k_bits=4.0, meta="e4m3")
     assert sum(c3.sizes[:4]) / (8 * 4096) == 64 + 64 + 4 + 4
     assert sum(c3.sizes[:4]) * 8 / (8 * 4096 * 2 * D) == 4.25
+    # 3-bit, same setting: Table 1's 3.25
+    c4 = oracle.OracleCache(1, 32, 8, 64, 3.0, 128, 4096, perm, perm, two, two, k_bits=3.0, meta="e4m3")
+    assert sum(c4.sizes[:4]) / (8 * 4096) == 48 + 48 + 4 + 4
+    assert sum(c4.sizes[:4]) * 8 / (8 * 4096 * 2 * D) == 3.25
 
 
 # ------------------------------------------------------------ attention ----
@@ -310,7 +371,8 @@ def test_window_only_cache_is_textbook_attention(oracle):
 
 
 @pytest.mark.parametrize("k_bits,v_bits,G", [(2.0, 2.0, 128), (2.0, 1.5, 128), (2.0, 1.5, 32), (2.0, 2.0, 64),
-                                             (4.0, 4.0, 128), (4.0, 4.0, 32), (4.0, 2.0, 64), (2.0, 4.0, 128)])
+                                             (4.0, 4.0, 128), (4.0, 4.0, 32), (4.0, 2.0, 64), (2.0, 4.0, 128),
+                                             (3.0, 3.0, 128), (3.0, 3.0, 32)])
 def test_lossless_cache_equals_textbook_attention(oracle, k_bits, v_bits, G):
     """Data that Eq. 2 represents exactly (alpha = 1) makes the quantized path exact, so the whole
     chain reorder -> encode -> pack -> unpack -> dequantize -> Eq. 1 must reproduce the library's
@@ -360,6 +422,9 @@ def numpy_dequantize(c, T):
     gof = p // G if bounds is None else np.searchsorted(np.asarray(bounds), p, side="right") - 1
     if c.cfg.k_levels == 16:
         kc = (c.k_codes[:, :, :nq, p // 2] >> (4 * (p % 2))) & 15
+    elif c.cfg.k_levels == 8:
+        top = np.array([256 + 32 * (x // 32) + 16 * ((x % 16) // 8) + KSIG[(x % 32) // 16][x % 8] for x in range(D)])
+        kc = ((c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3) + 4 * ((c.k_codes[:, :, :nq, top // 8] >> (top % 8)) & 1)
     else:
         kc = (c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3
     ks = c.k_meta[:, :, :nq, gof, 0].astype(np.float64)
@@ -378,6 +443,11 @@ def numpy_dequantize(c, T):
                     if c.cfg.v_levels == 3:
                         unit = int.from_bytes(blk[13 * u:13 * u + 13].tobytes(), "little")
                         vc[b, h, t, pp] = ((unit >> (13 * n)) & 0x1FFF) // 3 ** i % 3
+                    elif c.cfg.v_levels == 8:
+                        unit = int.from_bytes(blk[24 * u:24 * u + 24].tobytes(), "little")
+                        low = (unit >> (32 * (n // 2) + 16 * (i % 2) + 8 * (n % 2) + 2 * (i // 2))) & 3
+                        top = (unit >> (128 + 32 * (n // 4) + 16 * (i % 2) + VTAU[n % 4][i // 2])) & 1
+                        vc[b, h, t, pp] = low + 4 * top
                     elif c.cfg.v_levels == 16:
                         word = int.from_bytes(blk[32 * u + 4 * n:32 * u + 4 * n + 4].tobytes(), "little")
                         vc[b, h, t, pp] = (word >> (16 * (i % 2) + 4 * (i // 2))) & 15
@@ -392,7 +462,7 @@ def numpy_dequantize(c, T):
 
 
 @pytest.mark.parametrize("k_bits,v_bits,G", [(2.0, 1.5, 128), (2.0, 2.0, 32), (2.0, 1.5, 64), (4.0, 4.0, 128),
-                                             (4.0, 4.0, 32), (4.0, 2.0, 64)])
+                                             (4.0, 4.0, 32), (4.0, 2.0, 64), (3.0, 3.0, 128), (3.0, 3.0, 64)])
 def test_lossy_cache_equals_dequantize_then_textbook_attention(oracle, k_bits, v_bits, G):
     rng = np.random.default_rng(400 + G)
     B, Hq, Hk, W, T = 2, 4, 2, 8, 45
@@ -612,7 +682,7 @@ def test_e4m3_narrowing_is_nearest_even_and_saturates(oracle):
 
 
 @pytest.mark.parametrize("meta", ["f16", "e4m3"])
-@pytest.mark.parametrize("levels", [4, 3, 16])
+@pytest.mark.parametrize("levels", [4, 3, 16, 8])
 def test_encoder_with_compact_meta_uses_the_stored_values(oracle, meta, levels):
     """scale and zero come back exactly representable in the storage format, and every code is
     the nearest level of the grid THOSE values span (so decoding, which only sees them, is
