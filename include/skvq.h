@@ -55,6 +55,7 @@ typedef enum {
  * Table 1 also runs 4-bit keys and values). */
 typedef enum {
   SKVQ_BITS_4 = 16,  /* sixteen levels, codes 0..15 */
+  SKVQ_BITS_3 = 8,   /* eight levels, codes 0..7; keys and values together only */
   SKVQ_BITS_2 = 4,   /* four levels, codes 0..3 */
   SKVQ_BITS_1P5 = 3  /* three levels, codes 0..2 (this build's reading of "1.5-bit") */
 } skvq_bits;
@@ -75,8 +76,9 @@ typedef struct {
   int32_t head_dim;     /* D, must be 128                                                 */
   int32_t group_size;   /* G in {32, 64, 128}: consecutive REORDERED channels of a token;
                            with group_bounds, the AVERAGE group size (D/G groups)         */
-  int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2 or SKVQ_BITS_4                    */
-  int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_1P5, SKVQ_BITS_2 or SKVQ_BITS_4   */
+  int32_t k_bits;       /* skvq_bits; keys: SKVQ_BITS_2, SKVQ_BITS_3 or SKVQ_BITS_4       */
+  int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_1P5, _2, _3 or _4; SKVQ_BITS_3
+                           only together with 3-bit keys (SKVQ_ERR_UNSUPPORTED else)      */
   int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
   int32_t n_sink;       /* S >= 0: the filter rule of Section 3.2 / Algorithm 1 that keeps
                            the first S tokens (attention sinks) fp16 for ever; 0 = off    */
@@ -96,13 +98,19 @@ typedef struct {
 } skvq_config;
 
 /* DEVICE buffers of one layer's cache; byte sizes come from skvq_sizes(), in this order.
- *   k_codes   u8  [B][Hk][Tcap][32 | 64]  row t, 2-bit: code of position p in byte p/4, bits
- *             2(p%4).. ; 4-bit: in byte p/2, bits 4(p%2)..
- *   v_codes   u8  [B][Hk][ceil(Tcap/32)][832 | 1024 | 2048]   blocks of 32 tokens, token-minor:
+ *   k_codes   u8  [B][Hk][Tcap][32 | 48 | 64]  row t, 2-bit: code of position p in byte p/4,
+ *             bits 2(p%4).. ; 4-bit: in byte p/2, bits 4(p%2).. ; 3-bit: bytes 0..31 hold the
+ *             low two bits as a 2-bit row, bytes 32..47 four dwords of top bits: position p in
+ *             dword p/32 at bit 16((p%16)/8) + KSIG[(p%32)/16][p%8],
+ *             KSIG = {{0,2,1,3,4,6,8,5},{7,9,10,12,11,13,15,14}}
+ *   v_codes   u8  [B][Hk][ceil(Tcap/32)][832 | 1024 | 1536 | 2048]   blocks of 32 tokens, token-minor:
  *             token slot s=t%32 -> kb=s/8, i=s%8 ; position p -> n=p/16, j=p%16 ; unit u=16kb+j
  *             2-bit  : unit = 16 B little-endian, code(n,i) at bit 32(n/2)+16(i%2)+8(n%2)+2(i/2)
  *             3-level: unit = 13 B little-endian, field n = bits [13n,13n+13) = sum_i code(n,i)*3^i
  *             4-bit  : unit = 32 B little-endian, code(n,i) at bit 32n+16(i%2)+4(i/2)
+ *             3-bit  : unit = 24 B: bytes 0..15 the low two bits as a 2-bit unit, bytes 16..23
+ *                      two dwords of top bits: code(n,i) in dword n/4 at bit
+ *                      16(i%2) + VTAU[n%4][i/2], VTAU = {{0,2,4,12},{1,3,5,13},{6,8,10,14},{7,9,11,15}}
  *             a block is zero-filled when its first token is stored
  *   k_meta    [B][Hk][Tcap][D/G][2]      (scale, zero) of Eq. 2, zero = alpha*min, each an
  *   v_meta    [B][Hk][Tcap][D/G][2]      fp32, fp16 or FP8 E4M3 value (meta_format)

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libskvq.so")
 
 SKVQ_OK = 0
 SKVQ_ERR_INVALID_ARG, SKVQ_ERR_UNSUPPORTED, SKVQ_ERR_CAPACITY, SKVQ_ERR_STATE, SKVQ_ERR_HIP = -1, -2, -3, -4, -5
-SKVQ_BITS_4, SKVQ_BITS_2, SKVQ_BITS_1P5 = 16, 4, 3
+SKVQ_BITS_4, SKVQ_BITS_3, SKVQ_BITS_2, SKVQ_BITS_1P5 = 16, 8, 4, 3
 SKVQ_MAX_SPLITS = 128
 HEAD_DIM = 128
 BUFFER_NAMES = ("k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win", "workspace")
@@ -77,7 +77,7 @@ META_DTYPES = {0: np.float32, 1: np.float16, 2: np.uint8}
 
 
 def bits_enum(bits: float) -> int:
-    return {4.0: SKVQ_BITS_4, 2.0: SKVQ_BITS_2, 1.5: SKVQ_BITS_1P5}[float(bits)]
+    return {4.0: SKVQ_BITS_4, 3.0: SKVQ_BITS_3, 2.0: SKVQ_BITS_2, 1.5: SKVQ_BITS_1P5}[float(bits)]
 
 
 def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
@@ -205,8 +205,8 @@ class SkvqCache:
         b, _, hk = self.shape
         tcap = self.cfg.max_quant_tokens
         ng = HEAD_DIM // self.cfg.group_size
-        vb = {SKVQ_BITS_1P5: 832, SKVQ_BITS_2: 1024, SKVQ_BITS_4: 2048}[self.cfg.v_bits]
-        kb = 64 if self.cfg.k_bits == SKVQ_BITS_4 else 32
+        vb = {SKVQ_BITS_1P5: 832, SKVQ_BITS_2: 1024, SKVQ_BITS_3: 1536, SKVQ_BITS_4: 2048}[self.cfg.v_bits]
+        kb = {SKVQ_BITS_2: 32, SKVQ_BITS_3: 48, SKVQ_BITS_4: 64}[self.cfg.k_bits]
         torch.cuda.synchronize(self.device)
         raw = {n: self.buffers[n].cpu().numpy() for n in BUFFER_NAMES[:6]}
         return [raw["k_codes"].reshape(b, hk, tcap, kb),

@@ -17,7 +17,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
           "-Wno-unused-command-line-argument"]
 # (source, object, extra flags).  The quantizer's fp32 operations must each round once.  The
 # matrix-core decode kernels are compiled once per (key levels, value levels) pair.
-DECODE_FORMATS = [(4, 3), (4, 4), (4, 16), (16, 3), (16, 4), (16, 16)]
+DECODE_FORMATS = [(4, 3), (4, 4), (4, 16), (8, 8), (16, 3), (16, 4), (16, 16)]
 UNITS = [
     ("skvq_api.hip", "skvq_api.o", []),
     ("skvq_quantize.hip", "skvq_quantize.o", ["-ffp-contract=off"]),

@@ -35,9 +35,11 @@ int check_config(const skvq_config *c) {
   if (c->n_q_heads / c->n_kv_heads > 8) return SKVQ_ERR_UNSUPPORTED;
   if (c->group_size != 32 && c->group_size != 64 && c->group_size != 128)
     return SKVQ_ERR_UNSUPPORTED;
-  if (c->k_bits != SKVQ_BITS_2 && c->k_bits != SKVQ_BITS_4) return SKVQ_ERR_UNSUPPORTED;
-  if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5 && c->v_bits != SKVQ_BITS_4)
+  if (c->k_bits != SKVQ_BITS_2 && c->k_bits != SKVQ_BITS_3 && c->k_bits != SKVQ_BITS_4) return SKVQ_ERR_UNSUPPORTED;
+  if (c->v_bits != SKVQ_BITS_2 && c->v_bits != SKVQ_BITS_1P5 && c->v_bits != SKVQ_BITS_3 && c->v_bits != SKVQ_BITS_4)
     return SKVQ_ERR_UNSUPPORTED;
+  // 3-bit keys go with 3-bit values (the one 3-bit setting of Table 1)
+  if ((c->k_bits == SKVQ_BITS_3) != (c->v_bits == SKVQ_BITS_3)) return SKVQ_ERR_UNSUPPORTED;
   if (c->meta_format != SKVQ_META_F32 && c->meta_format != SKVQ_META_F16 &&
       c->meta_format != SKVQ_META_FP8_E4M3)
     return SKVQ_ERR_UNSUPPORTED;

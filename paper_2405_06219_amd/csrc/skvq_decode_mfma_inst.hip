@@ -4,7 +4,7 @@
 #include "skvq_decode_mfma_kernel.h"
 
 #if !defined(SKVQ_KL) || !defined(SKVQ_VL)
-#error "compile with -DSKVQ_KL=4|16 -DSKVQ_VL=3|4|16"
+#error "compile with -DSKVQ_KL=4|8|16 -DSKVQ_VL=3|4|8|16"
 #endif
 
 namespace skvq {

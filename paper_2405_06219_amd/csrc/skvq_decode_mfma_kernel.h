@@ -1,6 +1,6 @@
 // Matrix-core kernel of skvq_decode_attention for gfx950: packed chunks and the fp16 tokens
 // (attention sinks, window) in one launch, one partial per chunk.  Templated on the query
-// heads a workgroup serves (1, 2, 4), the K format (2-bit, 4-bit), the V format (3-level, 2-bit,
+// heads a workgroup serves (1, 2, 4), the K format (2-, 3-, 4-bit), the V format (3-level, 2-, 3-,
 // 4-bit), the (scale, zero) format, the groups per head (1, 2, 4) and whether the groups are
 // unequal (whole 16-position pieces of the head, mapped to groups by Layout::gmap: then every
 // piece has its own score accumulator and weight operand).  This header is compiled
@@ -29,7 +29,10 @@
 // The matrix core accumulates products of subnormal inputs as if their mantissa were full, so
 // a code at mantissa bit s costs about (10 - s) bits of the accumulator's precision; every
 // 2-bit code is therefore moved to bit 4, 6 or 8 before it is masked out, every 4-bit code to
-// bit 4 (its top bit must stay inside the 10 mantissa bits).
+// bit 4 (its top bit must stay inside the 10 mantissa bits).  A 3-bit code is its two low bits,
+// handled like a 2-bit code, with the top bit ORed in two places higher; at mantissa bit 8 that
+// top bit is the lowest exponent bit, and the value is still code * 2^(8-24): the fp16 numbers
+// 4..7 times 2^-16 are the first normal binade, 2^-14 * (1 + m/4).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -71,6 +74,7 @@ constexpr float kVsTarget = 256.0f;  // max(v scale)*beta is brought below this 
 constexpr float kVsLimit = 512.0f;   // ... and re-normalised when a token exceeds this
 constexpr unsigned kM4 = 0x00300030u, kM6 = 0x00c000c0u, kM8 = 0x03000300u;
 constexpr unsigned kN4 = 0x00f000f0u;  // a 4-bit code at mantissa bit 4 of each half
+constexpr unsigned kB6 = 0x00400040u, kB8 = 0x01000100u, kB10 = 0x04000400u;  // one bit of each half
 
 __device__ __forceinline__ float wave_max(float v) {
   for (int off = 32; off; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
@@ -118,6 +122,22 @@ __device__ __forceinline__ void unpack_k(unsigned w, half4_t b[4]) {
   b[3] = h4(wr & kM6, wr & kM8);
 }
 
+// 3-bit keys: `w` holds the low two bits of 16 codes as a 2-bit dword does, `h` is the plane dword
+// with their top bits (DD = 0: w is the even key dword of the pair that shares h, 1: the odd one).
+// Same operands as unpack_k; the top bit of a code at mantissa bit s goes to bit s + 2.  The plane's
+// bit order makes one shifted copy of h serve three codes.
+template <int DD>
+__device__ __forceinline__ void unpack_k3(unsigned w, unsigned h, half4_t b[4]) {
+  const unsigned wl = w << 4, wr = w >> 6;
+  const unsigned ha = DD ? h >> 1 : h << 6;  // positions e = 0, 1, 4 (and e + 8)
+  const unsigned hb = DD ? h >> 4 : h << 5;  // e = 2, 3, 7
+  const unsigned hc = DD ? h >> 7 : h;       // e = 5, 6
+  b[0] = h4((wl & kM4) | (ha & kB6), (wl & kM6) | (ha & kB8));
+  b[1] = h4((w & kM4) | (hb & kB6), (w & kM6) | (hb & kB8));
+  b[2] = h4((w & kM8) | (ha & kB10), (wr & kM4) | (hc & kB6));
+  b[3] = h4((wr & kM6) | (hc & kB8), (wr & kM8) | (hb & kB10));
+}
+
 // 4-bit key dword (8 codes, position e at bit 4e) -> two B operands.  Operand y holds positions
 // e = {2y, 2y+4, 2y+1, 2y+5}, all at mantissa bit 4.
 __device__ __forceinline__ void unpack_k4(unsigned w, half4_t b[2]) {
@@ -149,6 +169,17 @@ __device__ __forceinline__ void k_slot_of(int p, int &step, int &kslot, int &shi
 __device__ __forceinline__ half8_t unpack_v_field(unsigned f) {
   const unsigned a = f << 4, b = f << 2;
   return __builtin_bit_cast(half8_t, uint4_t{a & kM4, a & kM6, a & kM8, b & kM8});
+}
+
+// From a 3-bit unit: the 2-bit field as above plus the plane dword `h` with the top bits of
+// fields 4J .. 4J+3 (NN = the field's index among those four).
+template <int NN>
+__device__ __forceinline__ half8_t unpack_v3_field(unsigned f, unsigned h) {
+  const unsigned a = f << 4, b = f << 2;
+  const unsigned ha = NN == 0 ? h << 6 : NN == 1 ? h << 5 : NN == 2 ? h : h >> 1;  // token pairs 0, 1, 2
+  const unsigned hb = h >> (2 + NN);                                             // token pair 3
+  return __builtin_bit_cast(half8_t, uint4_t{(a & kM4) | (ha & kB6), (a & kM6) | (ha & kB8), (a & kM8) | (ha & kB10),
+                                             (b & kM8) | (hb & kB10)});
 }
 
 // From a 4-bit unit field (one dword: token pair m at bit 4m of each half), all at bit 4:
@@ -206,6 +237,16 @@ __device__ __forceinline__ float4_t qk_dword(unsigned w, half4_t a_lo, half4_t a
   return d;
 }
 
+template <int D>  // 3-bit keys: dword D of the 2-bit plane and the plane dword of its pair
+__device__ __forceinline__ float4_t qk_dword3(unsigned w, unsigned h, half4_t a_lo, half4_t a_hi, float4_t d) {
+  half4_t bop[4];
+  unpack_k3<D & 1>(w, h, bop);
+  d = qk_step<4 * D + 0>(a_lo, a_hi, bop[0], d);
+  d = qk_step<4 * D + 1>(a_lo, a_hi, bop[1], d);
+  d = qk_step<4 * D + 2>(a_lo, a_hi, bop[2], d);
+  d = qk_step<4 * D + 3>(a_lo, a_hi, bop[3], d);
+  return d;
+}
 template <int D>  // D = 0..15: dword of a 4-bit row, positions 8D .. 8D+7
 __device__ __forceinline__ float4_t qk_dword4(unsigned w, half4_t a_lo, half4_t a_hi, float4_t d) {
   half4_t bop[2];
@@ -246,9 +287,10 @@ struct alignas(sizeof(typename MetaWord<META>::type) * NG > 16 ? 16 : sizeof(typ
 template <int KL, int VL, int META, int NG>
 struct TileData {
   // (named members, not arrays: with arrays the compiler keeps copies of the buffers in registers)
-  uint4_t k0, k1, k2, k3;            // lane = token: its 32-byte (k0, k1) or 64-byte key row
+  uint4_t k0, k1, k2, k3;            // lane = token: its 32-byte (k0, k1), 48-byte or 64-byte key row
   MetaBlock<META, NG> kmeta, vmeta;  // lane = token: (scale, zero) per group
   Unit16 v00, v01, v10, v11;         // lane = unit of V block 2*tile (v0x) and 2*tile+1 (v1x): 16 or 32 bytes
+  uint2_t vt0, vt1;                  // 3-bit units: their 8 bytes of top bits
 };
 
 // What one wavefront loads for one slice of 4 fp16 ring tokens.
@@ -268,7 +310,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   //   Workgroup sp owns an even share of the packed 64-token tiles of
   // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
   // j = sp (mod n_splits), dealt the same way.
-  constexpr bool TERNARY = VL == 3, K4 = KL == 16, V4 = VL == 16;
+  constexpr bool TERNARY = VL == 3, K4 = KL == 16, V4 = VL == 16, K3 = KL == 8, V3 = VL == 8;
   constexpr float kCentre = 0.5f * (KL - 1);  // the key codes enter the products centred
   // score accumulators / weight operands: one per group, or (unequal groups) one per 16 positions
   constexpr int NACC = UNEQ ? 8 : NG;
@@ -288,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int tile_begin = (int)(((long long)sp * n_tiles) / n_splits);
   const int tile_end = (int)(((long long)(sp + 1) * n_tiles) / n_splits);
 
-  constexpr int kRowBytes = K4 ? kD / 2 : kD / 4;
+  constexpr int kRowBytes = K4 ? 64 : K3 ? 48 : 32;
   const uint8_t *kc = L.k_codes + head * L.Tcap * kRowBytes;
   typedef TileData<KL, VL, META, NG> Tile;
   typedef MetaBlock<META, NG> meta_block;
@@ -297,8 +339,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const uint8_t *vc = L.v_codes + head * L.n_vblocks * L.v_block_bytes;
   const int last_token = (int)(nq - 1);  // -1 when nothing is packed (then there are no tiles)
   const int last_blk = last_token >> 5;
-  const int vbb = TERNARY ? kTernaryBlockBytes : V4 ? kFourBitBlockBytes : kTwoBitBlockBytes;
-  const unsigned unit_off = TERNARY ? ((13 * lane) & ~3) : V4 ? 32 * lane : 16 * lane;
+  const int vbb = TERNARY ? kTernaryBlockBytes : V4 ? kFourBitBlockBytes : V3 ? kThreeBitBlockBytes : kTwoBitBlockBytes;
+  const unsigned unit_off = TERNARY ? ((13 * lane) & ~3) : V4 ? 32 * lane : V3 ? 24 * lane : 16 * lane;
   const int unit_sh = TERNARY ? ((13 * lane) & 3) : 0;
   // 2-bit units: token slot i = lane%8 sits in register m = i/2 at bit {4,6,8,8}[m]: undo
   // 2^(bit-4).  3-level units: every slot at bit 8.  4-bit units: every slot at bit 4.
@@ -320,12 +362,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * kRowBytes);
     d.k0 = krow[0]; d.k1 = krow[1];
     if constexpr (K4) { d.k2 = krow[2]; d.k3 = krow[3]; }
+    if constexpr (K3) d.k2 = krow[2];
     d.kmeta = km[t];
     d.vmeta = vm[t];
     const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
     const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
     d.v00 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[0];
     d.v10 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[0];
+    if constexpr (V3) {
+      d.vt0 = *reinterpret_cast<const uint2_t *>(vc + (size_t)blk0 * vbb + unit_off + 16);
+      d.vt1 = *reinterpret_cast<const uint2_t *>(vc + (size_t)blk1 * vbb + unit_off + 16);
+    }
     if constexpr (V4) {
       d.v01 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[1];
       d.v11 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[1];
@@ -583,6 +630,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       SKVQ_QK4(2, x, 8);  SKVQ_QK4(2, y, 9);  SKVQ_QK4(2, z, 10); SKVQ_QK4(2, w, 11);
       SKVQ_QK4(3, x, 12); SKVQ_QK4(3, y, 13); SKVQ_QK4(3, z, 14); SKVQ_QK4(3, w, 15);
 #undef SKVQ_QK4
+    } else if constexpr (K3) {
+      dg[0 * NACC / 8] = qk_dword3<0>(cur.k0.x, cur.k2.x, qop_lo, qop_hi, dg[0 * NACC / 8]);
+      dg[1 * NACC / 8] = qk_dword3<1>(cur.k0.y, cur.k2.x, qop_lo, qop_hi, dg[1 * NACC / 8]);
+      dg[2 * NACC / 8] = qk_dword3<2>(cur.k0.z, cur.k2.y, qop_lo, qop_hi, dg[2 * NACC / 8]);
+      dg[3 * NACC / 8] = qk_dword3<3>(cur.k0.w, cur.k2.y, qop_lo, qop_hi, dg[3 * NACC / 8]);
+      dg[4 * NACC / 8] = qk_dword3<4>(cur.k1.x, cur.k2.z, qop_lo, qop_hi, dg[4 * NACC / 8]);
+      dg[5 * NACC / 8] = qk_dword3<5>(cur.k1.y, cur.k2.z, qop_lo, qop_hi, dg[5 * NACC / 8]);
+      dg[6 * NACC / 8] = qk_dword3<6>(cur.k1.z, cur.k2.w, qop_lo, qop_hi, dg[6 * NACC / 8]);
+      dg[7 * NACC / 8] = qk_dword3<7>(cur.k1.w, cur.k2.w, qop_lo, qop_hi, dg[7 * NACC / 8]);
     } else {
       dg[0 * NACC / 8] = qk_dword<0>(cur.k0.x, qop_lo, qop_hi, dg[0 * NACC / 8]);
       dg[1 * NACC / 8] = qk_dword<1>(cur.k0.y, qop_lo, qop_hi, dg[1 * NACC / 8]);
@@ -739,6 +795,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         for (int n = 0; n < 8; ++n)
           acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, aop[n]), pop[n * NACC / 8],
                                                           acc[n], 0, 0, 0);
+      } else if constexpr (V3) {
+        const uint2_t top = blk ? cur.vt1 : cur.vt0;
+#define SKVQ_PV3(N, WORD, TOP)                                                                              \
+  acc[N] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v3_field<(N) & 3>(((N) & 1) ? (WORD) >> 8 : (WORD), TOP), \
+                                                  pop[(N) * NACC / 8], acc[N], 0, 0, 0)
+        SKVQ_PV3(0, raw.x, top.x); SKVQ_PV3(1, raw.x, top.x); SKVQ_PV3(2, raw.y, top.x); SKVQ_PV3(3, raw.y, top.x);
+        SKVQ_PV3(4, raw.z, top.y); SKVQ_PV3(5, raw.z, top.y); SKVQ_PV3(6, raw.w, top.y); SKVQ_PV3(7, raw.w, top.y);
+#undef SKVQ_PV3
       } else {
         const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -753,9 +817,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // Whole triples first.  The loop has no early exit: the wait counters the compiler places
   // are exact only if every path into the loop's top has the same loads in flight, in the
   // same order (buffer a's, then buffer b's).
-  // (A 4-bit row or unit takes twice the registers, and unequal groups need an accumulator and a
+  // (A 3- or 4-bit row or unit takes more registers, and unequal groups need an accumulator and a
   // weight operand per 16 positions: those variants rotate two buffers.)
-  if constexpr (K4 || V4 || UNEQ) {
+  if constexpr (K4 || V4 || K3 || V3 || UNEQ) {
     while (tile_b < tile_end) {
       compute_tile(buf_a, tile_a);
       tile_a = tile_of(n_a += 2);

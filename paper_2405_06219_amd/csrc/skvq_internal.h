@@ -14,10 +14,14 @@ constexpr int kVBlock = 32;    // tokens per V block
 constexpr int kTernaryBlockBytes = 832;
 constexpr int kTwoBitBlockBytes = 1024;
 constexpr int kFourBitBlockBytes = 2048;
+constexpr int kThreeBitBlockBytes = 1536;
 __host__ __device__ inline int v_block_bytes_of(int levels) {
-  return levels == 3 ? kTernaryBlockBytes : levels == 16 ? kFourBitBlockBytes : kTwoBitBlockBytes;
+  return levels == 3 ? kTernaryBlockBytes
+         : levels == 16 ? kFourBitBlockBytes
+         : levels == 8 ? kThreeBitBlockBytes
+                       : kTwoBitBlockBytes;
 }
-__host__ __device__ inline int k_row_bytes_of(int levels) { return levels == 16 ? kD / 2 : kD / 4; }
+__host__ __device__ inline int k_row_bytes_of(int levels) { return levels == 16 ? 64 : levels == 8 ? 48 : 32; }
 constexpr int kPartialStride = kD + 4;  // floats per split partial: m, l, pad, pad, acc[D]
 
 // Everything a kernel needs to find its data; passed by value.
@@ -29,10 +33,10 @@ struct Layout {
   int W;                 // window
   int S;                 // attention sinks: tokens 0..S-1 are never quantized
   int meta_fmt;          // skvq_meta_format of (scale, zero)
-  int k_levels;          // 4 or 16
-  int k_row_bytes;       // 32 or 64
-  int v_levels;          // 3, 4 or 16
-  int v_block_bytes;     // 832, 1024 or 2048
+  int k_levels;          // 4, 8 or 16
+  int k_row_bytes;       // 32, 48 or 64
+  int v_levels;          // 3, 4, 8 or 16
+  int v_block_bytes;     // 832, 1024, 1536 or 2048
   long long Tcap;        // packed rows per (b, hk)
   long long n_vblocks;   // ceil(Tcap / 32)
   float sm_scale;

@@ -108,6 +108,43 @@ __device__ __forceinline__ void store_k_row4(uint8_t *row, int lane, unsigned c0
   if ((lane & 3) == 0) reinterpret_cast<unsigned *>(row)[lane >> 2] = w;
 }
 
+// 3-bit formats: a 2-bit plane (laid out as the 2-bit format) plus a plane of top bits.  Top bit
+// of the key at position p: dword p/32 of the plane, bit 16*((p%16)/8) + kKsig[(p%32)/16][p%8];
+// of value code (n, i): dword n/4 of the unit's plane, bit 16*(i%2) + vtau(n%4, i/2).  The tables,
+// one nibble per entry:
+constexpr unsigned kKsig0 = 0x58643120u, kKsig1 = 0xefdbca97u;
+__device__ __forceinline__ int ksig(int d, int e) { return ((d ? kKsig1 : kKsig0) >> (4 * e)) & 15; }
+__device__ __forceinline__ int vtau(int nn, int m) { return m < 3 ? (nn & 1) + 6 * (nn >> 1) + 2 * m : 12 + nn; }
+
+// Sixteen top bits of one key dword (position e at bit e) -> their places in the plane dword
+// (d = 0: the even key dword of the pair, d = 1: the odd one).
+__device__ __forceinline__ unsigned place_key_top_bits(unsigned y, int d) {
+  const unsigned x = (y & 0xffu) | ((y & 0xff00u) << 8);  // e = 0..7 at bits 0..7, e = 8..15 at bits 16..23
+  // d = 0: positions e -> {0,2,1,3,4,6,8,5}
+  const unsigned a = (x & 0x00190019u) | ((x & 0x00220022u) << 1) | ((x & 0x00040004u) >> 1) |
+                     ((x & 0x00400040u) << 2) | ((x & 0x00800080u) >> 2);
+  // d = 1: positions e -> {7,9,10,12,11,13,15,14}
+  const unsigned b = ((x & 0x00910091u) << 7) | ((x & 0x00260026u) << 8) | ((x & 0x00480048u) << 9);
+  return d ? b : a;
+}
+
+// 3-bit K row from the append kernel's lanes (lane l: positions 2l, 2l+1): the 2-bit plane as
+// store_k_row, then the top-bit plane (16 lanes form a dword).
+__device__ __forceinline__ void store_k_row3(uint8_t *row, int lane, unsigned c0, unsigned c1) {
+  unsigned w = ((c0 & 3u) | ((c1 & 3u) << 2)) << (4 * (lane & 7));
+  w |= __shfl_xor(w, 1);
+  w |= __shfl_xor(w, 2);
+  w |= __shfl_xor(w, 4);
+  if ((lane & 7) == 0) reinterpret_cast<unsigned *>(row)[lane >> 3] = w;
+  const int p = 2 * lane, d = (p >> 4) & 1, half = (p >> 3) & 1;
+  unsigned h = ((c0 >> 2) << (16 * half + ksig(d, p & 7))) | ((c1 >> 2) << (16 * half + ksig(d, (p & 7) + 1)));
+  h |= __shfl_xor(h, 1);
+  h |= __shfl_xor(h, 2);
+  h |= __shfl_xor(h, 4);
+  h |= __shfl_xor(h, 8);
+  if ((lane & 15) == 0) reinterpret_cast<unsigned *>(row + 32)[lane >> 4] = h;
+}
+
 // Spread eight 2-bit codes (token i at bits [2i,2i+2)) to the V unit order: token i goes to
 // bit 16*(i%2) + 2*(i/2).
 __device__ __forceinline__ unsigned spread_tokens(unsigned c8) {
@@ -144,9 +181,10 @@ constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte a
                                  // puts the same channel of the 8 rows in 8 different banks
 
 // Gathers positions 16n..16n+15 of one parked row, finds the group's Eq. 2 parameters and
-// returns this lane's 16 codes: two bits each in .x (position 16n + e at bits [2e, 2e+2)), or,
-// WIDE, four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).
-template <bool WIDE>
+// returns this lane's 16 codes.  BITS = 2: two bits each in .x (position 16n + e at bits [2e, 2e+2));
+// BITS = 3: the low two bits like that in .x and the top bits in .y (position e at bit e);
+// BITS = 4: four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).
+template <int BITS>
 __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
                                           float top, int fmt, bool uneq, unsigned gmap, int lane,
                                           GroupParams &gp) {
@@ -190,13 +228,18 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
   for (int e = 0; e < 16; ++e) {
     const float y = __fmul_rn(__fsub_rn(x[e], gp.lo), gp.inv);
     const float r = __fadd_rn(__builtin_amdgcn_fmed3f(y, 0.0f, top), 12582912.0f);
-    if (!WIDE)
+    if (BITS == 2) {
       w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 2);
-    else if (e < 8)
+    } else if (BITS == 3) {
+      w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 2);
+      w1 = __builtin_amdgcn_alignbit(__float_as_uint(r) >> 2, w1, 1);
+    } else if (e < 8) {
       w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 4);
-    else
+    } else {
       w1 = __builtin_amdgcn_alignbit(__float_as_uint(r), w1, 4);
+    }
   }
+  if (BITS == 3) w1 >>= 16;
   return make_uint2(w0, w1);
 }
 
@@ -206,6 +249,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
                                                       long long nq) {
   __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
   __shared__ unsigned vq[VL == 16 ? 1 : 4][8][8];             // [wave][token i][n]: 16 codes, j-minor
+  __shared__ unsigned vqtop[VL == 8 ? 4 : 1][8][8];           // 3-bit codes: their top bits, j-minor
   __shared__ uint2 vq4[VL == 16 ? 4 : 1][8][8 + 1];           // the same for 4-bit codes
   __shared__ unsigned pieces[4][64];
   __shared__ __align__(16) uint8_t units[4][208];
@@ -252,12 +296,22 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   __syncthreads();
 
   GroupParams gk, gv;
-  const uint2 kw = encode16<KL == 16>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, uneq, L.gmap, lane, gk);
-  const uint2 vw = encode16<VL == 16>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, uneq, L.gmap, lane, gv);
+  constexpr int kKBits = KL == 16 ? 4 : KL == 8 ? 3 : 2, kVBits = VL == 16 ? 4 : VL == 8 ? 3 : 2;
+  const uint2 kw = encode16<kKBits>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, uneq, L.gmap, lane, gk);
+  const uint2 vw = encode16<kVBits>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, uneq, L.gmap, lane, gv);
+  unsigned ktop = 0;
+  if (KL == 8) {  // the plane dword of a pair of key dwords comes from two lanes
+    ktop = place_key_top_bits(kw.y, n & 1);
+    ktop |= __shfl_xor(ktop, 1);
+  }
   if (valid) {
-    if (KL == 16)
+    if (KL == 16) {
       reinterpret_cast<uint2 *>(L.k_codes + (head * L.Tcap + t) * (kD / 2))[n] = kw;
-    else
+    } else if (KL == 8) {
+      unsigned *krow = reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * 48);
+      krow[n] = kw.x;
+      if ((n & 1) == 0) krow[8 + (n >> 1)] = ktop;
+    } else
       reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw.x;
     if (writes_meta) {
       meta_store_pair(L.k_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, L.meta_fmt);
@@ -265,10 +319,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     }
   }
   // rows past the packed region leave zeros in the block
-  if (VL == 16)
+  if (VL == 16) {
     vq4[wave][i][n] = valid ? vw : make_uint2(0u, 0u);
-  else
+  } else {
     vq[wave][i][n] = valid ? vw.x : 0u;
+    if (VL == 8) vqtop[wave][i][n] = valid ? vw.y : 0u;
+  }
   __syncthreads();
 
   // V units of sub-block kb = wave.  Lane (j = lane % 16, nh = lane / 16) builds fields 2nh and
@@ -287,7 +343,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
       wb |= cb << (16 * (ii & 1) + 4 * (ii >> 1));
     }
     reinterpret_cast<uint2 *>(dst + 512 * wave + 32 * j)[nh] = make_uint2(wa, wb);
-  } else if (VL == 4) {
+  } else if (VL == 4 || VL == 8) {
     unsigned w = 0;
 #pragma unroll
     for (int ii = 0; ii < 8; ++ii) {
@@ -295,7 +351,24 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
       const unsigned cb = (vq[wave][ii][2 * nh + 1] >> (2 * j)) & 3u;
       w |= (ca << (16 * (ii & 1) + 2 * (ii >> 1))) | (cb << (8 + 16 * (ii & 1) + 2 * (ii >> 1)));
     }
-    reinterpret_cast<unsigned *>(dst + 256 * wave)[4 * j + nh] = w;
+    if (VL == 4) {
+      reinterpret_cast<unsigned *>(dst + 256 * wave)[4 * j + nh] = w;
+    } else {
+      // 24-byte units: the 2-bit plane, then the two dwords of top bits (fields 4J .. 4J+3 in
+      // dword J = nh / 2, built by the lanes nh = 2J and 2J + 1)
+      unsigned *unit = reinterpret_cast<unsigned *>(dst + 384 * wave + 24 * j);
+      unit[nh] = w;
+      unsigned h = 0;
+      const int na = (2 * nh) & 3;  // n % 4 of field 2nh; field 2nh+1 has na + 1
+#pragma unroll
+      for (int ii = 0; ii < 8; ++ii) {
+        const unsigned ta = (vqtop[wave][ii][2 * nh] >> j) & 1u;
+        const unsigned tb = (vqtop[wave][ii][2 * nh + 1] >> j) & 1u;
+        h |= (ta << (16 * (ii & 1) + vtau(na, ii >> 1))) | (tb << (16 * (ii & 1) + vtau(na + 1, ii >> 1)));
+      }
+      h |= __shfl_xor(h, 16);
+      if ((nh & 1) == 0) unit[4 + (nh >> 1)] = h;
+    }
   } else {
     unsigned fa = 0, fb = 0, pw = 1;
 #pragma unroll
@@ -370,6 +443,7 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   float alpha = 1.f;
   unsigned old_word = 0;   // 2-bit V: dword nh of unit j (lane = (j, nh))
   uint2 old_pair = make_uint2(0u, 0u);  // 4-bit V: dwords 2nh, 2nh+1 of unit j
+  unsigned old_top = 0;                 // 3-bit V: dword 4 + nh of unit j (nh < 2)
   uint8_t old_unit[13];    // 3-level V: unit j (lane = j < 16)
 #pragma unroll
   for (int q = 0; q < 13; ++q) old_unit[q] = 0;
@@ -383,6 +457,10 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
         old_pair = reinterpret_cast<const uint2 *>(blk + 32 * (16 * kb + (lane & 15)))[lane >> 4];
       } else if (L.v_levels == 4) {
         old_word = reinterpret_cast<const unsigned *>(blk + 16 * (16 * kb + (lane & 15)))[lane >> 4];
+      } else if (L.v_levels == 8) {
+        const unsigned *unit = reinterpret_cast<const unsigned *>(blk + 24 * (16 * kb + (lane & 15)));
+        old_word = unit[lane >> 4];
+        if (lane < 32) old_top = unit[4 + (lane >> 4)];
       } else if (lane < 16) {
         const uint8_t *u = blk + 13 * (16 * kb + lane);
 #pragma unroll
@@ -412,6 +490,8 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
     uint8_t *krow = L.k_codes + (head * L.Tcap + te) * L.k_row_bytes;
     if (L.k_levels == 16)
       store_k_row4(krow, lane, c0, c1);
+    else if (L.k_levels == 8)
+      store_k_row3(krow, lane, c0, c1);
     else
       store_k_row(krow, lane, c0, c1);
   } else {
@@ -434,6 +514,21 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
     old_pair.x |= (unsigned)vcodes[16 * (2 * nh) + j] << bit;  // old_pair is 0 when i == 0
     old_pair.y |= (unsigned)vcodes[16 * (2 * nh + 1) + j] << bit;
     reinterpret_cast<uint2 *>(blk + 32 * (16 * kb + j))[nh] = old_pair;
+  } else if (L.v_levels == 8) {
+    // lane (j, nh): dword nh of unit j holds the low two bits of fields 2nh and 2nh+1; the lanes
+    // nh < 2 also own dword 4 + nh: the top bits of fields 4nh .. 4nh+3
+    const int j = lane & 15, nh = lane >> 4;
+    unsigned *unit = reinterpret_cast<unsigned *>(blk + 24 * (16 * kb + j));
+    const unsigned bit = 16 * (i & 1) + 2 * (i >> 1);
+    const unsigned add = (((unsigned)vcodes[16 * (2 * nh) + j] & 3u) << bit) |
+                         (((unsigned)vcodes[16 * (2 * nh + 1) + j] & 3u) << (bit + 8));
+    unit[nh] = old_word | add;  // old_word and old_top are 0 when i == 0
+    if (nh < 2) {
+#pragma unroll
+      for (int nn = 0; nn < 4; ++nn)
+        old_top |= ((unsigned)vcodes[16 * (4 * nh + nn) + j] >> 2) << (16 * (i & 1) + vtau(nn, i >> 1));
+      unit[4 + nh] = old_top;
+    }
   } else if (L.v_levels == 4) {
     // lane (j, nh): dword nh of unit j holds fields 2nh and 2nh+1
     const int j = lane & 15, nh = lane >> 4;
@@ -474,7 +569,10 @@ hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, lon
     if (nblk > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nblk, L.Hk, L.B), block(256);
 #define SKVQ_PREFILL(KL, VL) hipLaunchKernelGGL((prefill_kernel<KL, VL>), grid, block, 0, s, L, k, v, T, n.n_quant)
-    if (L.k_levels == 16) {
+    if (L.k_levels == 8) {
+      if (L.v_levels != 8) return hipErrorInvalidValue;
+      SKVQ_PREFILL(8, 8);
+    } else if (L.k_levels == 16) {
       if (L.v_levels == 16) SKVQ_PREFILL(16, 16);
       else if (L.v_levels == 4) SKVQ_PREFILL(16, 4);
       else SKVQ_PREFILL(16, 3);

@@ -59,7 +59,8 @@ def test_sizes_agree_with_the_oracle(B, oracle):
                                                       (2, 16, 64, 1.5, 33, 7, 2, 1, "e4m3", 2.0),
                                                       (8, 32, 64, 4.0, 4097, 128, 1, 5, "e4m3", 4.0),
                                                       (2, 4, 128, 2.0, 65, 9, 2, 0, "f32", 4.0),
-                                                      (3, 3, 32, 4.0, 31, 9, 1, 0, "f16", 2.0)]:
+                                                      (3, 3, 32, 4.0, 31, 9, 1, 0, "f16", 2.0),
+                                                      (8, 32, 64, 3.0, 4097, 128, 1, 5, "e4m3", 3.0)]:
         cfg, keep = cfg_for(B, batch=b, n_q_heads=hq, n_kv_heads=hk, group_size=g, v_bits=vb, window=w,
                             max_quant_tokens=tcap, n_sink=sink, meta=meta, k_bits=kb)
         sizes = B.skvq_sizes(cfg)
@@ -89,6 +90,8 @@ def test_validation_rejects_bad_configs(B):
         (dict(head_dim=64), B.SKVQ_ERR_UNSUPPORTED),
         (dict(group_size=16, clip=np.ones((8, 8), np.float32)), B.SKVQ_ERR_UNSUPPORTED),
         (dict(k_bits=1.5), B.SKVQ_ERR_UNSUPPORTED),
+        (dict(k_bits=3.0), B.SKVQ_ERR_UNSUPPORTED),        # 3-bit keys need 3-bit values
+        (dict(v_bits=3.0), B.SKVQ_ERR_UNSUPPORTED),
         (dict(n_q_heads=128), B.SKVQ_ERR_UNSUPPORTED),     # 16 query heads per kv head
         # unequal groups: D/G + 1 ascending boundaries from 0 to D, multiples of 16
         (dict(group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[0, 32, 32, 96, 128]), B.SKVQ_ERR_INVALID_ARG),

@@ -44,6 +44,11 @@ QUANT_CASES = [
     small("k4v2_outlier", k_bits=4.0, v_bits=2.0, channel_profile="outlier4", perm_stat="absmax"),
     small("k4_t15_g64", k_bits=4.0, v_bits=1.5, group_size=64, context=300),
     small("k2v4_g32", k_bits=2.0, v_bits=4.0, group_size=32, context=450),
+    # 3-bit codes (Table 1's 3-bit setting)
+    small("k3v3_g128", k_bits=3.0, v_bits=3.0),
+    small("k3v3_gqa_g64_b2", k_bits=3.0, v_bits=3.0, n_q_heads=8, n_kv_heads=2, group_size=64, batch=2, context=391),
+    small("k3v3_g32_w16_outlier", k_bits=3.0, v_bits=3.0, n_q_heads=8, n_kv_heads=2, group_size=32, context=333, window=16,
+          channel_profile="outlier4", perm_stat="absmax"),
 ]
 
 
@@ -57,7 +62,9 @@ def test_prefill_codes_and_meta_bit_exact(P, w):
 
 @pytest.mark.parametrize("w", [QUANT_CASES[0], QUANT_CASES[2], QUANT_CASES[3], small("from_empty", context=0, window=8),
                                QUANT_CASES[8], QUANT_CASES[9], QUANT_CASES[10], QUANT_CASES[12],
-                               small("k4v4_from_empty", k_bits=4.0, v_bits=4.0, context=0, window=8)],
+                               small("k4v4_from_empty", k_bits=4.0, v_bits=4.0, context=0, window=8),
+                               QUANT_CASES[13], QUANT_CASES[14], QUANT_CASES[15],
+                               small("k3v3_from_empty", k_bits=3.0, v_bits=3.0, context=0, window=8)],
                          ids=lambda w: w.name)
 def test_append_evicts_bit_exact_and_equals_longer_prefill(P, w):
     print("case", w, flush=True)
@@ -129,6 +136,14 @@ DECODE_CASES = [
     small("k4_t15_g32", k_bits=4.0, v_bits=1.5, n_q_heads=4, n_kv_heads=2, group_size=32, context=2500, window=40),
     small("k2v4_g64_b3", k_bits=2.0, v_bits=4.0, group_size=64, context=5000, window=33, batch=3),
     small("k4v4_one_packed_row", k_bits=4.0, v_bits=4.0, context=129),
+    # 3-bit codes
+    small("k3v3_mha", k_bits=3.0, v_bits=3.0, context=1500),
+    small("k3v3_gqa4_b2", k_bits=3.0, v_bits=3.0, n_q_heads=16, n_kv_heads=4, context=1333, batch=2),
+    small("k3v3_gqa2_g64", k_bits=3.0, v_bits=3.0, n_q_heads=8, n_kv_heads=4, group_size=64, context=2100),
+    small("k3v3_gqa8_g32", k_bits=3.0, v_bits=3.0, n_q_heads=8, n_kv_heads=1, group_size=32, context=3000, window=16),
+    small("k3v3_gqa6_outlier", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=1, context=5000,
+          channel_profile="outlier4", perm_stat="absmax"),
+    small("k3v3_one_packed_row", k_bits=3.0, v_bits=3.0, context=129),
     small("window_only", context=77),
     small("exactly_window", context=128),
     small("one_packed_row", context=129),
@@ -237,7 +252,8 @@ def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
 
 
 @pytest.mark.parametrize("name,n_heads,bits", [("c5_batch16_32k", 4, None), ("c4_llama7b_1m", 2, None),
-                                               ("c3_mistral7b_128k", 3, (4.0, 4.0))])
+                                               ("c3_mistral7b_128k", 3, (4.0, 4.0)),
+                                               ("c3_mistral7b_128k", 2, (3.0, 3.0))])
 def test_full_size_sampled_heads(P, name, n_heads, bits):
     """The batch-16 and the 1M-token workloads (and the 128k one with 4-bit keys and values) at
     full size, library-chosen split count: the
@@ -272,8 +288,8 @@ def test_full_size_sampled_heads(P, name, n_heads, bits):
 
     R = w.n_q_heads // w.n_kv_heads
     ng = D // w.group_size
-    vb = {1.5: 832, 2.0: 1024, 4.0: 2048}[w.v_bits]
-    views = {"k_codes": gpu.buffers["k_codes"].view(w.batch, w.n_kv_heads, tcap, 64 if w.k_bits == 4.0 else 32),
+    vb = {1.5: 832, 2.0: 1024, 3.0: 1536, 4.0: 2048}[w.v_bits]
+    views = {"k_codes": gpu.buffers["k_codes"].view(w.batch, w.n_kv_heads, tcap, {2.0: 32, 3.0: 48, 4.0: 64}[w.k_bits]),
              "v_codes": gpu.buffers["v_codes"].view(w.batch, w.n_kv_heads, (tcap + 31) // 32, vb),
              "k_meta": gpu.buffers["k_meta"].view(torch.float32).view(w.batch, w.n_kv_heads, tcap, ng, 2),
              "v_meta": gpu.buffers["v_meta"].view(torch.float32).view(w.batch, w.n_kv_heads, tcap, ng, 2),
@@ -430,6 +446,8 @@ UNEQUAL_CASES = [
     (small("uneq_g64_k2v4_gqa3", k_bits=2.0, v_bits=4.0, n_q_heads=6, n_kv_heads=2, group_size=64, context=450, window=16),
      [0, 16, 128], "f32", 0),
     (small("uneq_g32_written_uniform", group_size=32, context=600), [0, 32, 64, 96, 128], "f32", 0),
+    (small("uneq_g32_k3v3_gqa2", k_bits=3.0, v_bits=3.0, n_q_heads=4, n_kv_heads=2, group_size=32, context=1100),
+     [0, 64, 80, 96, 128], "e4m3", 5),
 ]
 
 
@@ -462,7 +480,7 @@ def test_random_configurations(P):
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
     appended tokens and a forced split count.  Buffers bit-exact, outputs within 2e-3."""
     rng = np.random.default_rng(20240506)
-    for case in range(64):
+    for case in range(80):
         hk = int(rng.integers(1, 4))
         r = int(rng.integers(1, 9))
         w = small(f"rand{case}", batch=int(rng.integers(1, 4)), n_kv_heads=hk, n_q_heads=hk * r,
@@ -470,6 +488,8 @@ def test_random_configurations(P):
                   k_bits=float(rng.choice([2.0, 4.0])),
                   window=int(rng.choice([1, 3, 16, 33, 128, 200])), context=int(rng.integers(0, 2600)),
                   seed=500 + case)
+        if rng.integers(4) == 0:     # the 3-bit setting: keys and values together
+            w = dataclasses.replace(w, k_bits=3.0, v_bits=3.0)
         S = int(rng.choice([0, 0, 1, 5, 9]))
         meta = str(rng.choice(["f32", "f16", "e4m3"]))
         n_app = int(rng.integers(0, 40))
