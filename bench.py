@@ -39,7 +39,7 @@ META_BYTES = {"f32": 4, "f16": 2, "e4m3": 1}
 
 def code_bytes_per_row(w) -> int:
     """Packed key row + the token's share of its V block, bytes per (token, kv head)."""
-    return {2.0: 32, 4.0: 64}[w.k_bits] + {1.5: 26, 2.0: 32, 4.0: 64}[w.v_bits]
+    return {2.0: 32, 3.0: 48, 4.0: 64}[w.k_bits] + {1.5: 26, 2.0: 32, 3.0: 48, 4.0: 64}[w.v_bits]
 
 
 def algorithmic_bytes_decode(w, n_tokens: int, n_sink: int = 0, meta: str = "f32") -> int:
@@ -127,9 +127,9 @@ def main() -> int:
                     help="attention sinks: the first N tokens stay fp16 (the headline workload has none)")
     ap.add_argument("--meta", choices=sorted(META_BYTES), default="f32",
                     help="storage of (scale, zero); the headline workload keeps them in fp32")
-    ap.add_argument("--k-bits", type=float, choices=[2.0, 4.0], default=0.0,
+    ap.add_argument("--k-bits", type=float, choices=[2.0, 3.0, 4.0], default=0.0,
                     help="override the workload's key width (the headline workload has 2-bit keys)")
-    ap.add_argument("--v-bits", type=float, choices=[1.5, 2.0, 4.0], default=0.0,
+    ap.add_argument("--v-bits", type=float, choices=[1.5, 2.0, 3.0, 4.0], default=0.0,
                     help="override the workload's value width (the headline workload has 1.5-bit values)")
     ap.add_argument("--group-size", type=int, choices=[32, 64, 128], default=0,
                     help="override the workload's (average) group size (the headline workload has 128)")

@@ -29,7 +29,7 @@ class Workload:
     n_q_heads: int
     n_kv_heads: int
     context: int            # tokens already in the cache when decode starts
-    v_bits: float           # 4.0, 2.0 or 1.5
+    v_bits: float           # 4.0, 3.0, 2.0 or 1.5
     group_size: int = 128
     clip: float = 0.95
     window: int = 128
@@ -37,7 +37,7 @@ class Workload:
     perm_stat: str = "range"              # or "absmax"
     seed: int = 1000
     head_dim: int = HEAD_DIM
-    k_bits: float = 2.0     # 2.0 or 4.0
+    k_bits: float = 2.0     # 2.0, 3.0 or 4.0 (3.0 only with 3-bit values)
 
     def scaled(self, context: int, batch: int | None = None) -> "Workload":
         """Same layer shape at another context length (for quick tests)."""
