@@ -18,7 +18,8 @@
  * outside this file -- hand-derived values of Eq. 2, the scale/2 error bound,
  * lossless round trips, exact textbook attention (a library routine) on the
  * window-only and lossless cases, permutation invariance of Eq. 1, the
- * paper's printed average-bit figures.  The one thing with no external pin is
+ * paper's printed average-bit figures; prefill attention: the library's
+ * causal attention and a closed form.  The one thing with no external pin is
  * the meaning of "1.5-bit": the paper never defines it; three-level codes are
  * this build's reading ("parity with the authors' 1.5-bit numbers: unpinned").
  */
@@ -136,6 +137,14 @@ int skvq_ref_quantize_append(const skvq_ref_config *cfg, const skvq_ref_buffers 
 int skvq_ref_decode_attention(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
                               int64_t n_tokens, const uint16_t *q, float *out_f32,
                               uint16_t *out_f16);
+
+/* Prefill attention (Section 3.2, phase 1; Algorithm 1 with h = 0 and
+ * l = len(prompt)): the attention of the prompt itself is computed on the
+ * full-precision K and V, before anything is quantized.  Plain causal softmax
+ * attention in fp64: query t of head hq sees keys 0..t of kv head hq/(Hq/Hk).
+ * q: fp16 bits [B][Hq][T][D]; k, v: [B][Hk][T][D]; out_f32: [B][Hq][T][D].   */
+int skvq_ref_prefill_attention(const skvq_ref_config *cfg, const uint16_t *q, const uint16_t *k,
+                               const uint16_t *v, int64_t T, float *out_f32);
 
 /* Number of OpenMP threads the decode/prefill loops will use. */
 int skvq_ref_num_threads(void);

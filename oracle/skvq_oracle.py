@@ -79,6 +79,8 @@ def lib():
                                                   C.c_void_p]
         _lib.skvq_ref_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                                    C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                                    C.c_void_p]
     return _lib
 
 
@@ -217,6 +219,19 @@ class OracleCache:
         if rc != 0:
             raise RuntimeError(f"oracle decode failed: {rc}")
         return (out, out16) if want_f16 else out
+
+    def prefill_attention(self, q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+        """Causal attention of the prompt on the fp16 inputs; q [B][Hq][T][D], k/v [B][Hk][T][D]."""
+        b, hq, hk = self.shape
+        T = q.shape[2]
+        assert q.dtype == k.dtype == v.dtype == np.float16
+        assert q.shape == (b, hq, T, HEAD_DIM) and k.shape == v.shape == (b, hk, T, HEAD_DIM)
+        q, k, v = (np.ascontiguousarray(x) for x in (q, k, v))
+        out = np.zeros((b, hq, T, HEAD_DIM), np.float32)
+        rc = lib().skvq_ref_prefill_attention(C.byref(self.cfg), _ptr(q), _ptr(k), _ptr(v), T, _ptr(out))
+        if rc != 0:
+            raise RuntimeError(f"oracle prefill attention failed: {rc}")
+        return out
 
     # format accessors, for tests that look inside the packed buffers
     def k_code(self, b, h, t, p) -> int:

@@ -863,3 +863,39 @@ def test_uniform_boundaries_are_the_uniform_groups_and_bad_boundaries_are_refuse
     for bad in ([0, 32, 32, 96, 128], [1, 32, 64, 96, 128], [0, 32, 64, 96, 127], [0, 64, 32, 96, 128]):
         c = oracle.OracleCache(B, Hq, Hk, G, 1.5, W, 64, pk, pv, clip, clip, group_bounds=bad)
         assert c.prefill(k, v) == -1
+
+
+# ---- prefill attention (Section 3.2, phase 1: the prompt's own attention, full precision) ----
+
+def test_prefill_attention_is_the_librarys_causal_attention(oracle):
+    rng = np.random.default_rng(1200)
+    for B, Hq, Hk, T in ((1, 4, 2, 37), (2, 6, 2, 130), (1, 3, 3, 1)):
+        q = rng.standard_normal((B, Hq, T, D)).astype(np.float16)
+        k = (rng.standard_normal((B, Hk, T, D)) * 2).astype(np.float16)
+        v = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+        perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
+        one = np.ones((Hk, 1), np.float32)
+        c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one, sm_scale=0.11)
+        out = c.prefill_attention(q, k, v)
+        rep = Hq // Hk
+        qt = torch.from_numpy(q.astype(np.float64))
+        kt = torch.from_numpy(k.astype(np.float64)).repeat_interleave(rep, dim=1)
+        vt = torch.from_numpy(v.astype(np.float64)).repeat_interleave(rep, dim=1)
+        ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, is_causal=True, scale=0.11).numpy()
+        assert np.abs(out - ref).max() < 1e-5
+        # row 0 sees only token 0
+        assert np.abs(out[:, :, 0] - v.astype(np.float64).repeat(rep, axis=1)[:, :, 0]).max() < 1e-6
+
+
+def test_prefill_attention_with_uniform_weights_is_the_running_mean(oracle):
+    rng = np.random.default_rng(1201)
+    B, Hq, Hk, T = 1, 2, 1, 50
+    q = rng.standard_normal((B, Hq, T, D)).astype(np.float16)
+    k = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
+    one = np.ones((Hk, 1), np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one, sm_scale=0.0)
+    out = c.prefill_attention(q, k, v)
+    mean = np.cumsum(v.astype(np.float64), axis=2) / np.arange(1, T + 1)[None, None, :, None]
+    assert np.abs(out - mean.repeat(Hq // Hk, axis=1)).max() < 1e-6
