@@ -8,6 +8,7 @@
  * Section 3.2; Algorithm 1).  This library is that cache's data path for one
  * attention layer on one GPU:
  *
+ *   skvq_prefill_attention  the prompt's own causal attention on the full-precision K and V
  *   skvq_prefill_quantize   bulk-quantize a prompt, keep its last W tokens fp16
  *   skvq_quantize_append    one decode step: the token leaving the window is
  *                           quantized, the new token enters the window
@@ -154,6 +155,16 @@ void skvq_destroy(skvq_cache *cache);
  * SKVQ_ERR_CAPACITY if T-W-S > Tcap. */
 int skvq_prefill_quantize(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
                           void *hip_stream);
+
+/* Section 3.2 prefill phase, first step ("we first compute attention using full-precision KV
+ * cache"; Algorithm 1 with h = 0, l = len(prompt)): causal softmax attention of the prompt on
+ * the fp16 inputs, original channel order, fp32 accumulation: query t of head hq sees keys
+ * 0..t of kv head hq / (Hq/Hk); scale sm_scale.  Reads only the cache's configuration; the cache
+ * contents and counters are untouched (call skvq_prefill_quantize on the same k, v afterwards).
+ * q: DEVICE fp16 [B][Hq][T][D]; k, v: DEVICE fp16 [B][Hk][T][D]; out_f32: DEVICE fp32
+ * [B][Hq][T][D]; out_f16: DEVICE fp16 [B][Hq][T][D] or NULL.  All 16-byte aligned, T >= 1. */
+int skvq_prefill_attention(skvq_cache *cache, const void *q, const void *k, const void *v,
+                           int64_t n_tokens, void *out_f32, void *out_f16, void *hip_stream);
 
 /* Section 3.2 decode phase: with T tokens cached, if T >= W the token T-W (ring slot T % W)
  * leaves the window: it is copied to sink row T-W if T-W < S, else quantized into packed row

@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         L.skvq_destroy.argtypes = [C.c_void_p]
         L.skvq_destroy.restype = None
         L.skvq_prefill_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.skvq_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_get_state.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
@@ -162,7 +164,22 @@ class SkvqCache:
         if rc != SKVQ_OK:
             raise SkvqError(rc, lib().skvq_last_error(self._h).decode())
 
-    # ---- the three hot-path calls, named as in the C ABI ----
+    # ---- the hot-path calls, named as in the C ABI ----
+    def skvq_prefill_attention(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                               out_f32: torch.Tensor | None = None, out_f16: torch.Tensor | None = None,
+                               stream=None) -> torch.Tensor:
+        b, hq, hk = self.shape
+        T = q.shape[2]
+        qp = _dev_ptr(q, torch.float16, (b, hq, T, HEAD_DIM))
+        kp = _dev_ptr(k, torch.float16, (b, hk, T, HEAD_DIM))
+        vp = _dev_ptr(v, torch.float16, (b, hk, T, HEAD_DIM))
+        if out_f32 is None:
+            out_f32 = torch.empty((b, hq, T, HEAD_DIM), dtype=torch.float32, device=self.device)
+        op = _dev_ptr(out_f32, torch.float32, (b, hq, T, HEAD_DIM))
+        o16 = _dev_ptr(out_f16, torch.float16, (b, hq, T, HEAD_DIM)) if out_f16 is not None else None
+        self._check(lib().skvq_prefill_attention(self._h, qp, kp, vp, T, op, o16, _stream_ptr(stream)))
+        return out_f32
+
     def skvq_prefill_quantize(self, k: torch.Tensor, v: torch.Tensor, stream=None):
         b, _, hk = self.shape
         T = k.shape[2]

@@ -250,6 +250,18 @@ int skvq_prefill_quantize(skvq_cache *c, const void *k, const void *v, int64_t T
   return SKVQ_OK;
 }
 
+int skvq_prefill_attention(skvq_cache *c, const void *q, const void *k, const void *v, int64_t T, void *out_f32,
+                           void *out_f16, void *stream) {
+  if (!c || !q || !k || !v || !out_f32 || T < 1) return SKVQ_ERR_INVALID_ARG;
+  const void *ptrs[5] = {q, k, v, out_f32, out_f16};
+  for (const void *p : ptrs)
+    if ((uintptr_t)p & 15) return SKVQ_ERR_INVALID_ARG;
+  hipError_t e = launch_prefill_attention(c->L, (const __half *)q, (const __half *)k, (const __half *)v,
+                                          (float *)out_f32, (__half *)out_f16, T, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_attention launch");
+  return SKVQ_OK;
+}
+
 int skvq_quantize_append(skvq_cache *c, const void *k_new, const void *v_new, void *stream) {
   if (!c || !k_new || !v_new) return SKVQ_ERR_INVALID_ARG;
   const long long T = c->n_tokens;

@@ -69,6 +69,10 @@ hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, lon
 hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T,
                          hipStream_t s);
 
+// prefill attention (skvq_prefill_attn.hip): causal attention of the prompt on fp16 q, k, v
+hipError_t launch_prefill_attention(const Layout &L, const __half *q, const __half *k, const __half *v,
+                                    float *out_f32, __half *out_f16, long long T, hipStream_t s);
+
 // decode kernels (skvq_decode.hip)
 // n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,

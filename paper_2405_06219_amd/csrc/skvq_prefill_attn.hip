@@ -1,0 +1,227 @@
+// Prefill attention (Section 3.2, prefill phase: the prompt's own attention is computed on the
+// full-precision K and V before anything is quantized; Algorithm 1 with h = 0, l = len(prompt))
+// for gfx950: causal softmax attention of fp16 Q, K, V with fp32 accumulation, one pass over the
+// keys with a running maximum and sum per query (online softmax).
+//
+// One workgroup of 4 wavefronts owns 128 consecutive queries of one (sequence, query head); a
+// wavefront owns 32 of them.  Keys and values arrive in tiles of 64 tokens, staged in LDS (K as it
+// is, V transposed so that the keys of one channel are neighbours), double buffered: while a tile
+// is computed the next one travels from HBM into registers.  Per wavefront and tile:
+//   S^T[key][query]  by 16 v_mfma_f32_32x32x16_f16: A = K tile (row = key, 16 channels a step),
+//        B = the wavefront's queries, held in registers for the whole kernel.  Computing the
+//        transpose puts the 32 scores that a lane holds (of 64) in the column of ONE query, so the
+//        running maximum and sum need one cross-lane exchange, and
+//   O^T[channel][query]  by 16 more: A = V^T tile, B = P^T, which is exactly what the lane
+//        already holds: its exp2'd scores, converted to fp16, are the B operand as they are (the
+//        order of the keys inside a step of 16 is the accumulator's: both operands use it).
+// Causality: a workgroup stops at the last tile its queries can see, a wavefront skips the tiles
+// beyond its own queries, and only tiles that straddle the diagonal are masked element-wise.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <math.h>
+
+#include "skvq_internal.h"
+
+namespace skvq {
+namespace {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
+typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kQBlock = 128;    // queries per workgroup (32 per wavefront)
+constexpr int kKTile = 64;      // keys per tile
+constexpr int kKStride = 136;   // halves per K row in LDS (272 B: 16-byte aligned, rows on different banks)
+constexpr int kVStride = 68;    // halves per V^T row in LDS (136 B: 8-byte aligned)
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct Smem {
+  _Float16 k[2][kKTile][kKStride];  // [buffer][key][channel]
+  _Float16 vt[2][kD][kVStride];     // [buffer][channel][key]
+};
+
+// What one thread carries of a tile between HBM and LDS: 4 pieces of 8 channels of K (keys
+// tid/16 + 16 i) and a 4-key x 8-channel block of V (keys 4 (tid/16) .. +3).
+struct Stage {
+  uint4_t k[4], v[4];
+};
+
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const __half *__restrict__ q,
+                                                              const __half *__restrict__ k,
+                                                              const __half *__restrict__ v, float *__restrict__ out_f32,
+                                                              __half *__restrict__ out_f16, int T, int Hq, int Hk,
+                                                              float sm_scale) {
+  __shared__ __align__(16) Smem sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, h = lane >> 5;
+  const int n_qblocks = (T + kQBlock - 1) / kQBlock;
+  const int qb = n_qblocks - 1 - (int)blockIdx.x;  // the longest blocks start first
+  const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hk);
+  const __half *qh = q + ((size_t)b * Hq + hq) * (size_t)T * kD;
+  const __half *kh = k + ((size_t)b * Hk + hk) * (size_t)T * kD;
+  const __half *vh = v + ((size_t)b * Hk + hk) * (size_t)T * kD;
+  const float c = sm_scale * kLog2e;
+
+  const int q0 = qb * kQBlock + 32 * wave;           // this wavefront's first query
+  const int my_q = q0 + col;                         // this lane's query (two lanes share one)
+  const int last_q_block = min(qb * kQBlock + kQBlock - 1, T - 1);
+  const int n_tiles = last_q_block / kKTile + 1;     // tiles the workgroup's queries can see
+  const int wave_last_q = min(q0 + 31, T - 1);       // (q0 may lie beyond T: then nothing is stored)
+  const int wave_tiles = q0 < T ? wave_last_q / kKTile + 1 : 0;
+
+  // the queries: B operand of the score product, channels 16 s + 8 h .. + 7 for step s
+  uint4_t qreg[8];
+  {
+    const int qrow = min(my_q, T - 1);
+    const uint4_t *src = reinterpret_cast<const uint4_t *>(qh + (size_t)qrow * kD);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qreg[s] = src[2 * s + h];
+  }
+
+  auto load_stage = [&](int tile) {
+    Stage st;
+    const int kq = tid >> 4, dc = tid & 15;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int key = min(tile * kKTile + kq + 16 * i, T - 1);  // rows past the end repeat the last one (masked)
+      st.k[i] = reinterpret_cast<const uint4_t *>(kh + (size_t)key * kD)[dc];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int key = min(tile * kKTile + 4 * kq + r, T - 1);
+      st.v[r] = reinterpret_cast<const uint4_t *>(vh + (size_t)key * kD)[dc];
+    }
+    return st;
+  };
+  auto store_stage = [&](const Stage &st, int buf) {
+    const int kq = tid >> 4, dc = tid & 15;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4_t *>(&sm.k[buf][kq + 16 * i][8 * dc]) = st.k[i];
+    // transpose the 4 x 8 block: channel 8 dc + d gets its four keys as one 8-byte piece
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const unsigned a0 = st.v[0][j], a1 = st.v[1][j], a2 = st.v[2][j], a3 = st.v[3][j];
+      const uint2_t even = {__builtin_amdgcn_perm(a1, a0, 0x05040100u), __builtin_amdgcn_perm(a3, a2, 0x05040100u)};
+      const uint2_t odd = {__builtin_amdgcn_perm(a1, a0, 0x07060302u), __builtin_amdgcn_perm(a3, a2, 0x07060302u)};
+      *reinterpret_cast<uint2_t *>(&sm.vt[buf][8 * dc + 2 * j][4 * kq]) = even;
+      *reinterpret_cast<uint2_t *>(&sm.vt[buf][8 * dc + 2 * j + 1][4 * kq]) = odd;
+    }
+  };
+
+  float16_t o[4];  // O^T: channel 32 blk + 8 (x/4) + 4 h + x%4 of this lane's query
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) o[blk][x] = 0.f;
+  float m = -INFINITY, l = 0.f;  // running maximum (log2 domain) and this lane's part of the sum
+
+  Stage st = load_stage(0);
+  store_stage(st, 0);
+  __syncthreads();
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int buf = tile & 1;
+    if (tile + 1 < n_tiles) st = load_stage(tile + 1);  // in flight during the products below
+
+    if (tile < wave_tiles) {
+      // ---- scores ----
+      float16_t s[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) s[kb][x] = 0.f;
+#pragma unroll
+        for (int ds = 0; ds < 8; ++ds) {
+          const half8_t a = *reinterpret_cast<const half8_t *>(&sm.k[buf][32 * kb + col][16 * ds + 8 * h]);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(half8_t, qreg[ds]), s[kb], 0, 0, 0);
+        }
+      }
+      // key of s[kb][x]: tile*64 + 32 kb + 8 (x/4) + 4 h + x%4
+      const bool diagonal = tile * kKTile + kKTile - 1 > q0;  // some key of the tile is beyond some query
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          float sv = s[kb][x] * c;
+          if (diagonal) {
+            const int key = tile * kKTile + 32 * kb + 8 * (x >> 2) + 4 * h + (x & 3);
+            if (key > my_q) sv = -INFINITY;
+          }
+          s[kb][x] = sv;
+          mloc = fmaxf(mloc, sv);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+      // key 0 is visible to every query, so the maximum is finite from the first tile on
+      const float m_new = fmaxf(m, mloc);
+      const float alpha = exp2f(m - m_new);  // 0 at the first tile
+      m = m_new;
+      float psum = 0.f;
+      half8_t p[4];  // B operands of the value product: step t covers keys 16 t .. 16 t + 15 of the tile
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const float pv = __builtin_amdgcn_exp2f(s[kb][x] - m_new);
+          psum += pv;
+          p[2 * kb + (x >> 3)][x & 7] = (_Float16)pv;
+        }
+      l = l * alpha + psum;
+      if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) o[blk][x] *= alpha;
+      }
+      // ---- values: the lane's slot e of step t is key 16 t + 8 (e/4) + 4 h + e%4 ----
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+          const uint2_t lo = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 4 * h]);
+          const uint2_t hi = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 8 + 4 * h]);
+          const half8_t a = __builtin_bit_cast(half8_t, uint4_t{lo.x, lo.y, hi.x, hi.y});
+          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[t], o[blk], 0, 0, 0);
+        }
+    }
+    if (tile + 1 < n_tiles) store_stage(st, buf ^ 1);  // nobody reads that buffer during this tile
+    __syncthreads();
+  }
+
+  // ---- epilogue: divide by the sum, store channel-contiguous pieces of 4 ----
+  const float lt = l + __shfl_xor(l, 32);
+  if (my_q < T) {
+    const float inv = 1.f / lt;
+    const size_t row = (((size_t)b * Hq + hq) * (size_t)T + my_q) * kD;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int ch = 32 * blk + 8 * g + 4 * h;
+        const float4_t val = {o[blk][4 * g] * inv, o[blk][4 * g + 1] * inv, o[blk][4 * g + 2] * inv,
+                              o[blk][4 * g + 3] * inv};
+        *reinterpret_cast<float4_t *>(out_f32 + row + ch) = val;
+        if (out_f16) {
+          const __half2 lo2 = __floats2half2_rn(val[0], val[1]), hi2 = __floats2half2_rn(val[2], val[3]);
+          *reinterpret_cast<uint2_t *>(out_f16 + row + ch) =
+              uint2_t{__builtin_bit_cast(unsigned, lo2), __builtin_bit_cast(unsigned, hi2)};
+        }
+      }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill_attention(const Layout &L, const __half *q, const __half *k, const __half *v,
+                                    float *out_f32, __half *out_f16, long long T, hipStream_t s) {
+  if (T <= 0 || T > 0x3fffffffll || L.Hq > 65535 || L.B > 65535) return hipErrorInvalidValue;
+  const int n_qblocks = (int)((T + kQBlock - 1) / kQBlock);
+  hipLaunchKernelGGL(prefill_attn_kernel, dim3(n_qblocks, L.Hq, L.B), dim3(256), 0, s, q, k, v, out_f32, out_f16,
+                     (int)T, L.Hq, L.Hk, L.sm_scale);
+  return hipGetLastError();
+}
+
+}  // namespace skvq

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_entry_point(B):
     names = declared_functions()
-    assert {"skvq_prefill_quantize", "skvq_quantize_append", "skvq_decode_attention", "skvq_create",
+    assert {"skvq_prefill_attention", "skvq_prefill_quantize", "skvq_quantize_append", "skvq_decode_attention", "skvq_create",
             "skvq_destroy", "skvq_sizes"} <= set(names)
     L = B.lib()
     for n in names:

@@ -475,6 +475,39 @@ def test_unequal_groups_prefill_appends_and_decode(P, w, bounds, meta, S):
         assert np.abs(out2 - ref).max() <= P.TOL
 
 
+# ---- prefill attention (Section 3.2, phase 1): the prompt's causal attention, full precision ----
+PREFILL_ATTN_CASES = [(1, 4, 4, 300), (2, 8, 2, 777), (1, 3, 1, 1000), (1, 2, 2, 1), (1, 2, 1, 64), (1, 8, 1, 128),
+                      (3, 2, 2, 129), (1, 5, 5, 2049)]
+
+
+@pytest.mark.parametrize("B,Hq,Hk,T", PREFILL_ATTN_CASES)
+def test_prefill_attention_matches_oracle(P, B, Hq, Hk, T):
+    """fp32 outputs against the fp64 oracle.  The weights enter the value product as fp16 (11
+    significant bits), so the bound is 2^-11 of the largest value magnitude (plus fp32 rounding)."""
+    from oracle import skvq_oracle as O
+    from paper_2405_06219_amd import binding as Bd
+    print("case", B, Hq, Hk, T, flush=True)
+    rng = np.random.default_rng(3000 + T)
+    q = rng.standard_normal((B, Hq, T, D)).astype(np.float16)
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
+    perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
+    one = np.ones((Hk, 1), np.float32)
+    ref = O.OracleCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one).prefill_attention(q, k, v)
+    gpu = Bd.SkvqCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one)
+    dev = "cuda:0"
+    o16 = torch.empty((B, Hq, T, D), dtype=torch.float16, device=dev)
+    out = gpu.skvq_prefill_attention(torch.from_numpy(q).to(dev), torch.from_numpy(k).to(dev),
+                                     torch.from_numpy(v).to(dev), out_f16=o16)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    err = np.abs(out - ref).max()
+    bound = 2.0 ** -11 * float(np.abs(v.astype(np.float32)).max()) + 1e-5
+    P.log(f"prefill attention B{B} Hq{Hq} Hk{Hk} T{T}: max abs err {err:.3e} (bound {bound:.3e}, ref max {np.abs(ref).max():.3f})")
+    assert err <= bound
+    assert np.array_equal(o16.cpu().numpy(), out.astype(np.float16))
+
+
 def test_random_configurations(P):
     """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
