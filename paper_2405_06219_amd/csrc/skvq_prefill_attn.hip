@@ -3,8 +3,9 @@
 // for gfx950: causal softmax attention of fp16 Q, K, V with fp32 accumulation, one pass over the
 // keys with a running maximum and sum per query (online softmax).
 //
-// One workgroup of 4 wavefronts owns 128 consecutive queries of one (sequence, query head); a
-// wavefront owns 32 of them.  Keys and values arrive in tiles of 64 tokens, staged in LDS (K as it
+// One workgroup of 8 wavefronts owns 256 consecutive queries of one (sequence, query head); a
+// wavefront owns 32 of them (every tile of K and V that the workgroup fetches serves 256 queries:
+// at 128 the kernel was bound by the K/V traffic from L2 and HBM).  Keys and values arrive in tiles of 64 tokens, staged in LDS (K as it
 // is, V transposed so that the keys of one channel are neighbours), double buffered: while a tile
 // is computed the next one travels from HBM into registers.  Per wavefront and tile:
 //   S^T[key][query]  by 16 v_mfma_f32_32x32x16_f16: A = K tile (row = key, 16 channels a step),
@@ -32,30 +33,33 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
 typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kQBlock = 128;    // queries per workgroup (32 per wavefront)
+constexpr int kQBlock = 256;    // queries per workgroup (32 per wavefront)
+constexpr int kThreads = 2 * kQBlock;
 constexpr int kKTile = 64;      // keys per tile
 constexpr int kKStride = 136;   // halves per K row in LDS (272 B: 16-byte aligned, rows on different banks)
 constexpr int kVStride = 68;    // halves per V^T row in LDS (136 B: 8-byte aligned)
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kSlack = 8.0f;  // weights may reach 2^8 before the running reference moves
 
 struct Smem {
   _Float16 k[2][kKTile][kKStride];  // [buffer][key][channel]
   _Float16 vt[2][kD][kVStride];     // [buffer][channel][key]
 };
 
-// What one thread carries of a tile between HBM and LDS: 4 pieces of 8 channels of K (keys
-// tid/16 + 16 i) and a 4-key x 8-channel block of V (keys 4 (tid/16) .. +3).
+// What one thread carries of a tile between HBM and LDS: 2 pieces of 8 channels of K (keys
+// tid/16 + 32 i) and a 2-key x 8-channel block of V (keys 2 (tid/16), 2 (tid/16) + 1).
 struct Stage {
-  uint4_t k[4], v[4];
+  uint4_t k[2], v[2];
 };
 
-__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const __half *__restrict__ q,
+__global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half *__restrict__ q,
                                                               const __half *__restrict__ k,
                                                               const __half *__restrict__ v, float *__restrict__ out_f32,
                                                               __half *__restrict__ out_f16, int T, int Hq, int Hk,
                                                               float sm_scale) {
   __shared__ __align__(16) Smem sm;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, h = lane >> 5;
   const int n_qblocks = (T + kQBlock - 1) / kQBlock;
   const int qb = n_qblocks - 1 - (int)blockIdx.x;  // the longest blocks start first
@@ -85,13 +89,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const __half *__re
     Stage st;
     const int kq = tid >> 4, dc = tid & 15;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int key = min(tile * kKTile + kq + 16 * i, T - 1);  // rows past the end repeat the last one (masked)
+    for (int i = 0; i < 2; ++i) {
+      const int key = min(tile * kKTile + kq + 32 * i, T - 1);  // rows past the end repeat the last one (masked)
       st.k[i] = reinterpret_cast<const uint4_t *>(kh + (size_t)key * kD)[dc];
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int key = min(tile * kKTile + 4 * kq + r, T - 1);
+    for (int r = 0; r < 2; ++r) {
+      const int key = min(tile * kKTile + 2 * kq + r, T - 1);
       st.v[r] = reinterpret_cast<const uint4_t *>(vh + (size_t)key * kD)[dc];
     }
     return st;
@@ -99,15 +103,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const __half *__re
   auto store_stage = [&](const Stage &st, int buf) {
     const int kq = tid >> 4, dc = tid & 15;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4_t *>(&sm.k[buf][kq + 16 * i][8 * dc]) = st.k[i];
-    // transpose the 4 x 8 block: channel 8 dc + d gets its four keys as one 8-byte piece
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4_t *>(&sm.k[buf][kq + 32 * i][8 * dc]) = st.k[i];
+    // transpose the 2 x 8 block: channel 8 dc + d gets its two keys as one dword
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const unsigned a0 = st.v[0][j], a1 = st.v[1][j], a2 = st.v[2][j], a3 = st.v[3][j];
-      const uint2_t even = {__builtin_amdgcn_perm(a1, a0, 0x05040100u), __builtin_amdgcn_perm(a3, a2, 0x05040100u)};
-      const uint2_t odd = {__builtin_amdgcn_perm(a1, a0, 0x07060302u), __builtin_amdgcn_perm(a3, a2, 0x07060302u)};
-      *reinterpret_cast<uint2_t *>(&sm.vt[buf][8 * dc + 2 * j][4 * kq]) = even;
-      *reinterpret_cast<uint2_t *>(&sm.vt[buf][8 * dc + 2 * j + 1][4 * kq]) = odd;
+      const unsigned a0 = st.v[0][j], a1 = st.v[1][j];
+      *reinterpret_cast<unsigned *>(&sm.vt[buf][8 * dc + 2 * j][2 * kq]) = __builtin_amdgcn_perm(a1, a0, 0x05040100u);
+      *reinterpret_cast<unsigned *>(&sm.vt[buf][8 * dc + 2 * j + 1][2 * kq]) = __builtin_amdgcn_perm(a1, a0, 0x07060302u);
     }
   };
 
@@ -121,73 +123,107 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const __half *__re
   Stage st = load_stage(0);
   store_stage(st, 0);
   __syncthreads();
+  // Every load issued so far must have landed before the loop: the compiler counts the loads in
+  // flight at the loop's top over all paths into it, and a query load still pending on entry
+  // would turn into a wait for the NEXT tile's loads on every later trip.
+  asm volatile("" ::"v"(qreg[0]), "v"(qreg[1]), "v"(qreg[2]), "v"(qreg[3]), "v"(qreg[4]), "v"(qreg[5]), "v"(qreg[6]),
+               "v"(qreg[7]));
 
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int buf = tile & 1;
-    if (tile + 1 < n_tiles) st = load_stage(tile + 1);  // in flight during the products below
+    // the next tile, in flight during the products below (unconditional: after the last tile the
+    // same tile is fetched and stored again, which nobody reads)
+    st = load_stage(min(tile + 1, n_tiles - 1));
 
     if (tile < wave_tiles) {
       // ---- scores ----
       float16_t s[2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int x = 0; x < 16; ++x) s[kb][x] = 0.f;
+      {
+        // all sixteen A operands are requested before the first product; the two key blocks'
+        // accumulation chains alternate
+        half8_t a[2][8];
 #pragma unroll
-        for (int ds = 0; ds < 8; ++ds) {
-          const half8_t a = *reinterpret_cast<const half8_t *>(&sm.k[buf][32 * kb + col][16 * ds + 8 * h]);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(half8_t, qreg[ds]), s[kb], 0, 0, 0);
-        }
+        for (int ds = 0; ds < 8; ++ds)
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+            a[kb][ds] = *reinterpret_cast<const half8_t *>(&sm.k[buf][32 * kb + col][16 * ds + 8 * h]);
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products
+#pragma unroll
+        for (int ds = 0; ds < 8; ++ds)
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kb][ds], __builtin_bit_cast(half8_t, qreg[ds]), s[kb], 0, 0, 0);
       }
       // key of s[kb][x]: tile*64 + 32 kb + 8 (x/4) + 4 h + x%4
-      const bool diagonal = tile * kKTile + kKTile - 1 > q0;  // some key of the tile is beyond some query
+      if (tile * kKTile + kKTile - 1 > q0) {  // some key of the tile lies beyond some query: mask
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            const int key = tile * kKTile + 32 * kb + 8 * (x >> 2) + 4 * h + (x & 3);
+            if (key > my_q) s[kb][x] = -INFINITY;
+          }
+      }
+      // The running reference m only moves when a score exceeds it by more than 2^kSlack (log2
+      // domain): then the weights stay below 2^kSlack, which fp16 holds, and the accumulators
+      // are rescaled on few tiles.  (Key 0 is visible to every query, so the first tile sets a
+      // finite reference.)
       float mloc = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          float sv = s[kb][x] * c;
-          if (diagonal) {
-            const int key = tile * kKTile + 32 * kb + 8 * (x >> 2) + 4 * h + (x & 3);
-            if (key > my_q) sv = -INFINITY;
-          }
-          s[kb][x] = sv;
-          mloc = fmaxf(mloc, sv);
-        }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-      // key 0 is visible to every query, so the maximum is finite from the first tile on
-      const float m_new = fmaxf(m, mloc);
-      const float alpha = exp2f(m - m_new);  // 0 at the first tile
-      m = m_new;
-      float psum = 0.f;
-      half8_t p[4];  // B operands of the value product: step t covers keys 16 t .. 16 t + 15 of the tile
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const float pv = __builtin_amdgcn_exp2f(s[kb][x] - m_new);
-          psum += pv;
-          p[2 * kb + (x >> 3)][x & 7] = (_Float16)pv;
-        }
-      l = l * alpha + psum;
-      if (__any(alpha != 1.f)) {
+        for (int x = 0; x < 16; x += 2) mloc = __builtin_fmaxf(mloc, __builtin_fmaxf(s[kb][x], s[kb][x + 1]));
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * c;  // c >= 0
+      if (__any(mloc > m + kSlack)) {
+        const float m_new = fmaxf(m, mloc);
+        const float alpha = exp2f(m - m_new);  // 0 at the first tile
+        m = m_new;
+        l *= alpha;
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
           for (int x = 0; x < 16; ++x) o[blk][x] *= alpha;
       }
-      // ---- values: the lane's slot e of step t is key 16 t + 8 (e/4) + 4 h + e%4 ----
+      float psum = 0.f;
+      half8_t p[4];  // B operands of the value product: step t covers keys 16 t .. 16 t + 15 of the tile
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk) {
-          const uint2_t lo = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 4 * h]);
-          const uint2_t hi = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 8 + 4 * h]);
-          const half8_t a = __builtin_bit_cast(half8_t, uint4_t{lo.x, lo.y, hi.x, hi.y});
-          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, p[t], o[blk], 0, 0, 0);
+        for (int x = 0; x < 16; x += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][x], c, -m));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][x + 1], c, -m));
+          psum += p0 + p1;
+          const __half2 pk = __floats2half2_rn(p0, p1);
+          p[2 * kb + (x >> 3)][x & 7] = __builtin_bit_cast(_Float16, __low2half(pk));
+          p[2 * kb + (x >> 3)][(x & 7) + 1] = __builtin_bit_cast(_Float16, __high2half(pk));
         }
+      l += psum;
+      // ---- values: the lane's slot e of step t is key 16 t + 8 (e/4) + 4 h + e%4 ----
+      auto v_operand = [&](int t, int blk) {
+        const uint2_t lo = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 4 * h]);
+        const uint2_t hi = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 8 + 4 * h]);
+        return __builtin_bit_cast(half8_t, uint4_t{lo.x, lo.y, hi.x, hi.y});
+      };
+      half8_t va[2][4];  // the A operands of one step, requested one step ahead
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) va[0][blk] = v_operand(0, blk);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if (t + 1 < 4) {
+#pragma unroll
+          for (int blk = 0; blk < 4; ++blk) va[(t + 1) & 1][blk] = v_operand(t + 1, blk);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[t & 1][blk], p[t], o[blk], 0, 0, 0);
+      }
     }
-    if (tile + 1 < n_tiles) store_stage(st, buf ^ 1);  // nobody reads that buffer during this tile
+    store_stage(st, buf ^ 1);  // nobody reads that buffer during this tile
     __syncthreads();
   }
 
@@ -219,7 +255,7 @@ hipError_t launch_prefill_attention(const Layout &L, const __half *q, const __ha
                                     float *out_f32, __half *out_f16, long long T, hipStream_t s) {
   if (T <= 0 || T > 0x3fffffffll || L.Hq > 65535 || L.B > 65535) return hipErrorInvalidValue;
   const int n_qblocks = (int)((T + kQBlock - 1) / kQBlock);
-  hipLaunchKernelGGL(prefill_attn_kernel, dim3(n_qblocks, L.Hq, L.B), dim3(256), 0, s, q, k, v, out_f32, out_f16,
+  hipLaunchKernelGGL(prefill_attn_kernel, dim3(n_qblocks, L.Hq, L.B), dim3(kThreads), 0, s, q, k, v, out_f32, out_f16,
                      (int)T, L.Hq, L.Hk, L.sm_scale);
   return hipGetLastError();
 }
