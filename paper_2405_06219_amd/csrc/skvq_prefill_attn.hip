@@ -41,6 +41,13 @@ constexpr int kVStride = 68;    // halves per V^T row in LDS (136 B: 8-byte alig
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kSlack = 8.0f;  // weights may reach 2^8 before the running reference moves
 
+// max(a, b, c) in one instruction (the plain fmaxf first re-canonicalizes every matrix-core result)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 struct Smem {
   _Float16 k[2][kKTile][kKStride];  // [buffer][key][channel]
   _Float16 vt[2][kD][kVStride];     // [buffer][channel][key]
@@ -85,25 +92,35 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
     for (int s = 0; s < 8; ++s) qreg[s] = src[2 * s + h];
   }
 
-  auto load_stage = [&](int tile) {
-    Stage st;
+  auto load_k = [&](Stage &st, int tile) {
     const int kq = tid >> 4, dc = tid & 15;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int key = min(tile * kKTile + kq + 32 * i, T - 1);  // rows past the end repeat the last one (masked)
       st.k[i] = reinterpret_cast<const uint4_t *>(kh + (size_t)key * kD)[dc];
     }
+  };
+  auto load_v = [&](Stage &st, int tile) {
+    const int kq = tid >> 4, dc = tid & 15;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       const int key = min(tile * kKTile + 2 * kq + r, T - 1);
       st.v[r] = reinterpret_cast<const uint4_t *>(vh + (size_t)key * kD)[dc];
     }
+  };
+  auto load_stage = [&](int tile) {
+    Stage st;
+    load_k(st, tile);
+    load_v(st, tile);
     return st;
   };
-  auto store_stage = [&](const Stage &st, int buf) {
+  auto store_k = [&](const Stage &st, int buf) {
     const int kq = tid >> 4, dc = tid & 15;
 #pragma unroll
     for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4_t *>(&sm.k[buf][kq + 32 * i][8 * dc]) = st.k[i];
+  };
+  auto store_v = [&](const Stage &st, int buf) {
+    const int kq = tid >> 4, dc = tid & 15;
     // transpose the 2 x 8 block: channel 8 dc + d gets its two keys as one dword
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -120,44 +137,72 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
     for (int x = 0; x < 16; ++x) o[blk][x] = 0.f;
   float m = -INFINITY, l = 0.f;  // running maximum (log2 domain) and this lane's part of the sum
 
-  Stage st = load_stage(0);
-  store_stage(st, 0);
+  // Scores of tile `tile` from K buffer `kbuf`: sixteen products, two alternating accumulation
+  // chains (key blocks), the LDS operand reads kept four ahead of the products.
+  auto scores = [&](int kbuf, float16_t (&s)[2]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) s[kb][x] = 0.f;
+    half8_t a[2][4];  // [parity of the batch][2 * (ds % 2) + kb]
+    auto read_batch = [&](int bt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int ds = 2 * bt + (i >> 1), kb = i & 1;
+        a[bt & 1][i] = *reinterpret_cast<const half8_t *>(&sm.k[kbuf][32 * kb + col][16 * ds + 8 * h]);
+      }
+    };
+    read_batch(0);
+#pragma unroll
+    for (int bt = 0; bt < 4; ++bt) {
+      if (bt + 1 < 4) read_batch(bt + 1);
+      __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int ds = 2 * bt + (i >> 1), kb = i & 1;
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[bt & 1][i], __builtin_bit_cast(half8_t, qreg[ds]), s[kb], 0, 0, 0);
+      }
+    }
+  };
+
+  // The K tiles run one tile ahead of the V tiles: while a wavefront turns the scores of tile j
+  // into weights on the vector ALU, the matrix core already works on the scores of tile j + 1.
+  float16_t s_a[2], s_b[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) s_a[kb][x] = s_b[kb][x] = 0.f;
+  {
+    Stage st0 = load_stage(0), st1 = load_stage(min(1, n_tiles - 1));
+    store_k(st0, 0);
+    store_v(st0, 0);
+    store_k(st1, 1);
+  }
   __syncthreads();
   // Every load issued so far must have landed before the loop: the compiler counts the loads in
   // flight at the loop's top over all paths into it, and a query load still pending on entry
   // would turn into a wait for the NEXT tile's loads on every later trip.
   asm volatile("" ::"v"(qreg[0]), "v"(qreg[1]), "v"(qreg[2]), "v"(qreg[3]), "v"(qreg[4]), "v"(qreg[5]), "v"(qreg[6]),
                "v"(qreg[7]));
+  if (0 < wave_tiles) scores(0, s_a);
+  __syncthreads();  // K buffer 0 is overwritten at the end of the first trip
 
-  for (int tile = 0; tile < n_tiles; ++tile) {
+  // One trip: the scores of tile + 1 into s_next, softmax and value product of tile from s_cur.
+  // The loop below runs trips in pairs with the two score buffers swapping roles (no register
+  // copies); an odd tile count gets one idle trip (its loads repeat the last tile, its products
+  // are skipped, its stores go to buffers that nobody reads any more).
+  auto trip = [&](const int tile, float16_t (&s_cur)[2], float16_t (&s_next)[2]) {
     const int buf = tile & 1;
-    // the next tile, in flight during the products below (unconditional: after the last tile the
-    // same tile is fetched and stored again, which nobody reads)
-    st = load_stage(min(tile + 1, n_tiles - 1));
+    // K of tile + 2 and V of tile + 1, in flight during the products below (unconditional: past
+    // the last tile the last one is fetched and stored again, which nobody reads)
+    Stage st;
+    load_k(st, min(tile + 2, n_tiles - 1));
+    load_v(st, min(tile + 1, n_tiles - 1));
+
+    if (tile + 1 < wave_tiles) scores(buf ^ 1, s_next);  // runs on the matrix core during the softmax below
 
     if (tile < wave_tiles) {
-      // ---- scores ----
-      float16_t s[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) s[kb][x] = 0.f;
-      {
-        // all sixteen A operands are requested before the first product; the two key blocks'
-        // accumulation chains alternate
-        half8_t a[2][8];
-#pragma unroll
-        for (int ds = 0; ds < 8; ++ds)
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-            a[kb][ds] = *reinterpret_cast<const half8_t *>(&sm.k[buf][32 * kb + col][16 * ds + 8 * h]);
-        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products
-#pragma unroll
-        for (int ds = 0; ds < 8; ++ds)
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kb][ds], __builtin_bit_cast(half8_t, qreg[ds]), s[kb], 0, 0, 0);
-      }
+      float16_t(&s)[2] = s_cur;
       // key of s[kb][x]: tile*64 + 32 kb + 8 (x/4) + 4 h + x%4
       if (tile * kKTile + kKTile - 1 > q0) {  // some key of the tile lies beyond some query: mask
 #pragma unroll
@@ -176,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int x = 0; x < 16; x += 2) mloc = __builtin_fmaxf(mloc, __builtin_fmaxf(s[kb][x], s[kb][x + 1]));
+        for (int x = 0; x < 16; x += 2) mloc = max3(mloc, s[kb][x], s[kb][x + 1]);
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * c;  // c >= 0
       if (__any(mloc > m + kSlack)) {
         const float m_new = fmaxf(m, mloc);
@@ -223,8 +268,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
           o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[t & 1][blk], p[t], o[blk], 0, 0, 0);
       }
     }
-    store_stage(st, buf ^ 1);  // nobody reads that buffer during this tile
+    // K of tile + 2 replaces K of tile (read during the previous trip), V of tile + 1 replaces V
+    // of tile - 1: nobody reads either buffer during this trip
+    store_k(st, buf);
+    store_v(st, buf ^ 1);
     __syncthreads();
+  };
+  for (int tile = 0; tile < n_tiles; tile += 2) {
+    trip(tile, s_a, s_b);
+    trip(tile + 1, s_b, s_a);
   }
 
   // ---- epilogue: divide by the sum, store channel-contiguous pieces of 4 ----
