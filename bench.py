@@ -218,13 +218,35 @@ def main() -> int:
     alg_bytes = algorithmic_bytes_decode(w, n_tokens_roof, args.sink, args.meta)
     achieved = alg_bytes / (dec_avg_us * 1e-6) / 1e9
 
-    # append alone (launch-latency bound, reported for completeness)
-    torch.cuda.synchronize()
-    ta = time.perf_counter()
+    # the prompt's own causal attention (skvq_prefill_attention) at 16k tokens of the same head
+    # layout: a dense contraction, reported against the fp16 matrix-core peak
+    pa_T = min(16384, w.context)
+    pa_q = torch.randn((1, w.n_q_heads, pa_T, D), generator=gen, device=device).to(torch.float16)
+    pa_k = (torch.randn((1, w.n_kv_heads, pa_T, D), generator=gen, device=device) * sk_d).to(torch.float16)
+    pa_v = (torch.randn((1, w.n_kv_heads, pa_T, D), generator=gen, device=device) * sv_d).to(torch.float16)
+    pa_out = torch.empty((1, w.n_q_heads, pa_T, D), dtype=torch.float32, device=device)
+    pa_cache = caches[0] if w.batch == 1 else None
+    pa_ms = None
+    if pa_cache is not None:
+        pa_cache.skvq_prefill_attention(pa_q, pa_k, pa_v, out_f32=pa_out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            pa_cache.skvq_prefill_attention(pa_q, pa_k, pa_v, out_f32=pa_out)
+        e1.record()
+        torch.cuda.synchronize()
+        pa_ms = e0.elapsed_time(e1) / 3
+    del pa_q, pa_k, pa_v, pa_out
+
+    # append alone (launch-latency bound, reported for completeness): one pair of HIP events
+    # around the layers' calls issued back to back
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
     for layer, c in enumerate(caches):
         c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
+    e1.record()
     torch.cuda.synchronize()
-    append_us = (time.perf_counter() - ta) * 1e6 / n_layers
+    append_us = e0.elapsed_time(e1) * 1e3 / n_layers
 
     result = {
         "metric": "decode-attention us/token at 128k ctx" if w.context == 131072 else f"decode-attention us/token at {w.context} ctx",
@@ -254,6 +276,10 @@ def main() -> int:
                                                      * (code_bytes_per_row(w)
                                                         + 4 * META_BYTES[args.meta] * (D // w.group_size)))
                              / (prefill_med_us * 1e-6) / 1e9),
+        "prefill_attention": (None if pa_ms is None else {
+            "tokens": pa_T, "ms_per_call": pa_ms,
+            "tflops": 4.0 * D * w.n_q_heads * pa_T * (pa_T + 1) / 2 / (pa_ms * 1e-3) / 1e12,
+            "frac_of_mfma_peak": 4.0 * D * w.n_q_heads * pa_T * (pa_T + 1) / 2 / (pa_ms * 1e-3) / 2.5e15}),
         "effective_hbm_gbps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
