@@ -536,6 +536,72 @@ int skvq_ref_prefill_attention(const skvq_ref_config *c, const uint16_t *q, cons
   return fail ? -5 : 0;
 }
 
+/* ------------------------------------------------------ clip calibration --- */
+
+/* Eq. 3 (Section 3.1; Algorithm 1 Prologue, get_group_clipping): the clip scale
+ * of a group is the one that minimises the squared error of the attention
+ * output after quantizing the cache, on calibration data.  The paper leaves the
+ * search itself open; this build's is one pass of coordinate descent over a
+ * caller-given grid: keys first, then values; group by group; every candidate is
+ * tried with the other groups at their current choice; each kv head keeps the
+ * candidate with the smallest error summed over its query heads, the queries,
+ * the batch and the channels (ties: the earliest candidate).  An evaluation is
+ * a prefill-quantize of the calibration tokens followed by one decode attention
+ * per calibration query, compared with o_ref, the full-precision outputs. */
+int skvq_ref_calibrate_clip(const skvq_ref_config *c, const skvq_ref_buffers *buf, const uint16_t *k,
+                            const uint16_t *v, int64_t T, const uint16_t *q, int n_queries,
+                            const float *o_ref, const float *alphas, int n_alphas, float *clip_k_out,
+                            float *clip_v_out, double *loss_out) {
+  int rc = check_config(c);
+  if (rc) return rc;
+  if (T < 1 || n_queries < 1 || n_alphas < 1 || c->n_kv_heads > 1024) return -1;
+  int ng = D / c->group_size, hk_n = c->n_kv_heads, rep = c->n_q_heads / hk_n;
+  size_t out_n = (size_t)c->batch * c->n_q_heads * D;
+  float *out = (float *)malloc(sizeof(float) * out_n);
+  double *err = (double *)malloc(sizeof(double) * (size_t)n_alphas * hk_n);
+  if (!out || !err) {
+    free(out);
+    free(err);
+    return -5;
+  }
+  for (int x = 0; x < hk_n * ng; ++x) clip_k_out[x] = c->clip_k[x], clip_v_out[x] = c->clip_v[x];
+  skvq_ref_config cc = *c;
+  cc.clip_k = clip_k_out;
+  cc.clip_v = clip_v_out;
+  for (int which = 0; which < 2 && !rc; ++which) {
+    float *clip = which ? clip_v_out : clip_k_out;
+    for (int g = 0; g < ng && !rc; ++g) {
+      float saved[1024];
+      for (int h = 0; h < hk_n; ++h) saved[h] = clip[h * ng + g];
+      for (int a = 0; a < n_alphas && !rc; ++a) {
+        for (int h = 0; h < hk_n; ++h) clip[h * ng + g] = alphas[a], err[(size_t)a * hk_n + h] = 0.0;
+        int64_t n = 0;
+        rc = skvq_ref_prefill_quantize(&cc, buf, k, v, T, &n);
+        for (int i = 0; i < n_queries && !rc; ++i) {
+          rc = skvq_ref_decode_attention(&cc, buf, n, q + (size_t)i * out_n, out, NULL);
+          for (size_t x = 0; x < out_n && !rc; ++x) {
+            int hq = (int)((x / D) % (size_t)c->n_q_heads);
+            double d = (double)out[x] - (double)o_ref[(size_t)i * out_n + x];
+            err[(size_t)a * hk_n + hq / rep] += d * d;
+          }
+        }
+      }
+      for (int h = 0; h < hk_n && !rc; ++h) {
+        int best = 0;
+        for (int a = 1; a < n_alphas; ++a)
+          if (err[(size_t)a * hk_n + h] < err[(size_t)best * hk_n + h]) best = a;
+        clip[h * ng + g] = alphas[best];
+        if (loss_out) loss_out[h] = err[(size_t)best * hk_n + h];
+      }
+      if (rc)
+        for (int h = 0; h < hk_n; ++h) clip[h * ng + g] = saved[h];
+    }
+  }
+  free(out);
+  free(err);
+  return rc;
+}
+
 int skvq_ref_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

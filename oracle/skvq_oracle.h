@@ -146,6 +146,20 @@ int skvq_ref_decode_attention(const skvq_ref_config *cfg, const skvq_ref_buffers
 int skvq_ref_prefill_attention(const skvq_ref_config *cfg, const uint16_t *q, const uint16_t *k,
                                const uint16_t *v, int64_t T, float *out_f32);
 
+/* Clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping): one pass
+ * of coordinate descent over the candidate grid `alphas` (keys, then values;
+ * group by group; per kv head the candidate with the smallest squared error of
+ * the attention outputs against o_ref; ties: the earliest candidate), starting
+ * from cfg's clips.  k, v: calibration tokens [B][Hk][T][D]; q: [n_queries]
+ * [B][Hq][D], each attending over all T tokens; o_ref: their full-precision
+ * outputs [n_queries][B][Hq][D].  clip_k_out, clip_v_out: [Hk][D/G];
+ * loss_out: [Hk] final summed squared error, or NULL.  buf is scratch (it ends
+ * up holding the last evaluation's cache).  n_kv_heads <= 1024.              */
+int skvq_ref_calibrate_clip(const skvq_ref_config *cfg, const skvq_ref_buffers *buf, const uint16_t *k,
+                            const uint16_t *v, int64_t T, const uint16_t *q, int n_queries,
+                            const float *o_ref, const float *alphas, int n_alphas, float *clip_k_out,
+                            float *clip_v_out, double *loss_out);
+
 /* Number of OpenMP threads the decode/prefill loops will use. */
 int skvq_ref_num_threads(void);
 

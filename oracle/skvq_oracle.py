@@ -79,6 +79,9 @@ def lib():
                                                   C.c_void_p]
         _lib.skvq_ref_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                                    C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                                 C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.skvq_ref_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                     C.c_void_p]
     return _lib
@@ -232,6 +235,24 @@ class OracleCache:
         if rc != 0:
             raise RuntimeError(f"oracle prefill attention failed: {rc}")
         return out
+
+    def calibrate_clip(self, k, v, q, o_ref, alphas):
+        """Eq. 3 by one pass of coordinate descent over `alphas`; returns (clip_k, clip_v, loss[Hk]).
+        k, v [B][Hk][T][D] fp16; q [n][B][Hq][D] fp16; o_ref [n][B][Hq][D] f32."""
+        b, hq, hk = self.shape
+        ng = self.clip_k.shape[1]
+        k, v, q = (np.ascontiguousarray(x) for x in (k, v, q))
+        o_ref = np.ascontiguousarray(o_ref, np.float32)
+        alphas = np.ascontiguousarray(alphas, np.float32)
+        assert q.shape[1:] == (b, hq, HEAD_DIM) and o_ref.shape == q.shape and k.shape == v.shape
+        ck, cv = np.zeros((hk, ng), np.float32), np.zeros((hk, ng), np.float32)
+        loss = np.zeros(hk, np.float64)
+        rc = lib().skvq_ref_calibrate_clip(C.byref(self.cfg), C.byref(self.buf), _ptr(k), _ptr(v), k.shape[2],
+                                           _ptr(q), q.shape[0], _ptr(o_ref), _ptr(alphas), alphas.size,
+                                           _ptr(ck), _ptr(cv), _ptr(loss))
+        if rc != 0:
+            raise RuntimeError(f"oracle clip calibration failed: {rc}")
+        return ck, cv, loss
 
     # format accessors, for tests that look inside the packed buffers
     def k_code(self, b, h, t, p) -> int:

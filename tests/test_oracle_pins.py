@@ -899,3 +899,66 @@ def test_prefill_attention_with_uniform_weights_is_the_running_mean(oracle):
     out = c.prefill_attention(q, k, v)
     mean = np.cumsum(v.astype(np.float64), axis=2) / np.arange(1, T + 1)[None, None, :, None]
     assert np.abs(out - mean.repeat(Hq // Hk, axis=1)).max() < 1e-6
+
+
+# ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
+
+def calib_setup(oracle, rng, G, lossless=False, T=48, W=8, Hq=4, Hk=2, n_q=3, v_bits=2.0):
+    B = 1
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    if lossless:
+        k = grid_data(rng, (B, Hk, T), G, 4, pk)
+        v = grid_data(rng, (B, Hk, T), G, oracle.levels_of(v_bits), pv)
+    else:
+        # heavy-tailed channels: a few outliers per group make clipping pay
+        k = (rng.standard_t(2.5, (B, Hk, T, D)) * 0.5).astype(np.float16)
+        v = (rng.standard_t(2.5, (B, Hk, T, D)) * 0.5).astype(np.float16)
+    q = rng.standard_normal((n_q, B, Hq, D)).astype(np.float16)
+    o_ref = np.stack([sdpa64(q[i], k, v, 1 / np.sqrt(D)) for i in range(n_q)]).astype(np.float32)
+    ones = np.ones((Hk, D // G), np.float32)
+
+    def make(ck=ones, cv=ones):
+        return oracle.OracleCache(B, Hq, Hk, G, v_bits, W, T, pk, pv, ck, cv)
+
+    def loss_of(ck, cv):
+        """Per-kv-head summed squared error of a fresh cache with these clips (numpy arithmetic)."""
+        c = make(ck, cv)
+        assert c.prefill(k, v) == 0
+        out = np.stack([c.decode(q[i]) for i in range(n_q)]).astype(np.float64)
+        d2 = (out - o_ref.astype(np.float64)) ** 2
+        return d2.reshape(n_q, B, Hk, Hq // Hk, D).sum(axis=(0, 1, 3, 4))
+    return make, loss_of, k, v, q, o_ref
+
+
+def test_clip_calibration_follows_coordinate_descent_on_the_output_error(oracle):
+    rng = np.random.default_rng(1300)
+    G = 64
+    make, loss_of, k, v, q, o_ref = calib_setup(oracle, rng, G)
+    alphas = np.array([1.0, 0.9, 0.8, 0.65], np.float32)
+    ck, cv, loss = make().calibrate_clip(k, v, q, o_ref, alphas)
+    # the same search, driven from here with independent evaluations
+    Hk, ng = ck.shape
+    wk, wv = np.ones((Hk, ng), np.float32), np.ones((Hk, ng), np.float32)
+    for clip in (wk, wv):
+        for g in range(ng):
+            errs = []
+            for a in alphas:
+                clip[:, g] = a
+                errs.append(loss_of(wk, wv))
+            clip[:, g] = alphas[np.argmin(np.array(errs), axis=0)]     # first minimum per head
+    assert np.array_equal(ck, wk) and np.array_equal(cv, wv)
+    final = loss_of(ck, cv)
+    assert np.allclose(loss, final, rtol=1e-9)
+    # never worse than where it started, and clipping does pay on heavy-tailed data
+    start = loss_of(np.ones_like(ck), np.ones_like(cv))
+    assert np.all(final <= start) and np.any(ck < 1.0) and np.any(cv < 1.0) and np.all(final < start)
+
+
+def test_clip_calibration_keeps_alpha_one_when_the_data_is_exactly_representable(oracle):
+    rng = np.random.default_rng(1301)
+    make, loss_of, k, v, q, o_ref = calib_setup(oracle, rng, 128, lossless=True)
+    ck, cv, loss = make().calibrate_clip(k, v, q, o_ref, np.array([0.8, 1.0, 0.9], np.float32))
+    assert np.all(ck == 1.0) and np.all(cv == 1.0) and np.all(loss < 1e-9)
+    # a one-point grid returns that point
+    ck, cv, _ = make().calibrate_clip(k, v, q, o_ref, np.array([0.75], np.float32))
+    assert np.all(ck == 0.75) and np.all(cv == 0.75)
