@@ -184,6 +184,33 @@ int skvq_quantize_append(skvq_cache *cache, const void *k_new, const void *v_new
 int skvq_decode_attention(skvq_cache *cache, const void *q, void *out_f32, void *out_f16,
                           void *hip_stream);
 
+/* Replaces the clip scales alpha of Eq. 2.  clip_k, clip_v: HOST [Hk][D/G], each in (0,1].
+ * Ordered after the work already enqueued on hip_stream; synchronises that stream.  Rows
+ * already packed keep the codes they were given. */
+int skvq_set_clip(skvq_cache *cache, const float *clip_k, const float *clip_v, void *hip_stream);
+
+/* Eq. 3 (Section 3.1; Algorithm 1 Prologue, get_group_clipping): chooses the clip scales that
+ * minimise the squared error of the attention output after quantization, on calibration data.
+ * The search (the paper leaves it open) is one pass of coordinate descent over the candidate
+ * grid `alphas` (HOST [n_alphas], each in (0,1]), starting from the cache's current scales:
+ * keys first, then values; group by group; every candidate is tried with the other groups at
+ * their current choice; each kv head keeps the candidate with the smallest error summed over
+ * its query heads, the queries, the batch and the channels (ties: the earliest candidate).
+ * One evaluation = skvq_prefill_quantize of the calibration tokens + one
+ * skvq_decode_attention per calibration query, compared with o_ref.
+ * k, v: DEVICE fp16 [B][Hk][T][D]; q: DEVICE fp16 [n_queries][B][Hq][D]; o_ref: DEVICE fp32
+ * [n_queries][B][Hq][D], the full-precision attention outputs of the queries over all T tokens
+ * (e.g. from a cache whose window holds all T tokens).  clip_k_out, clip_v_out: HOST
+ * [Hk][D/G]; loss_out: HOST double [Hk] (summed squared error at the result) or NULL.
+ * Offline routine: allocates and frees device scratch, synchronises hip_stream repeatedly.
+ * Afterwards the cache uses the new scales; its contents are the calibration tokens as the
+ * LAST candidate quantized them: call skvq_prefill_quantize before using it.
+ * SKVQ_ERR_CAPACITY if T-W-S > Tcap; on any error the cache keeps its old scales. */
+int skvq_calibrate_clip(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                        const void *q, int32_t n_queries, const void *o_ref, const float *alphas,
+                        int32_t n_alphas, float *clip_k_out, float *clip_v_out, double *loss_out,
+                        void *hip_stream);
+
 /* Host counters: tokens cached, of which packed, of which in the ring (the rest, at most S,
  * are sink rows).  Any may be NULL. */
 int skvq_get_state(const skvq_cache *cache, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win);

@@ -52,6 +52,10 @@ def lib() -> C.CDLL:
         L.skvq_destroy.argtypes = [C.c_void_p]
         L.skvq_destroy.restype = None
         L.skvq_prefill_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.skvq_set_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                          C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p]
         L.skvq_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -163,6 +167,32 @@ class SkvqCache:
     def _check(self, rc):
         if rc != SKVQ_OK:
             raise SkvqError(rc, lib().skvq_last_error(self._h).decode())
+
+    # ---- clip scales: Eq. 2's alpha, and its calibration by Eq. 3 ----
+    def skvq_set_clip(self, clip_k: np.ndarray, clip_v: np.ndarray, stream=None):
+        ck = np.ascontiguousarray(clip_k, np.float32)
+        cv = np.ascontiguousarray(clip_v, np.float32)
+        ng = HEAD_DIM // self.cfg.group_size
+        if ck.shape != (self.shape[2], ng) or cv.shape != ck.shape:
+            raise ValueError("clip scales must be [n_kv_heads][head_dim / group_size]")
+        self._check(lib().skvq_set_clip(self._h, ck.ctypes.data, cv.ctypes.data, _stream_ptr(stream)))
+
+    def skvq_calibrate_clip(self, k: torch.Tensor, v: torch.Tensor, q: torch.Tensor, o_ref: torch.Tensor,
+                            alphas, stream=None):
+        """Returns (clip_k, clip_v, loss) as numpy arrays [Hk][NG], [Hk][NG], [Hk]."""
+        b, hq, hk = self.shape
+        T, n = k.shape[2], q.shape[0]
+        kp = _dev_ptr(k, torch.float16, (b, hk, T, HEAD_DIM))
+        vp = _dev_ptr(v, torch.float16, (b, hk, T, HEAD_DIM))
+        qp = _dev_ptr(q, torch.float16, (n, b, hq, HEAD_DIM))
+        op = _dev_ptr(o_ref, torch.float32, (n, b, hq, HEAD_DIM))
+        al = np.ascontiguousarray(alphas, np.float32)
+        ng = HEAD_DIM // self.cfg.group_size
+        ck, cv = np.zeros((hk, ng), np.float32), np.zeros((hk, ng), np.float32)
+        loss = np.zeros(hk, np.float64)
+        self._check(lib().skvq_calibrate_clip(self._h, kp, vp, T, qp, n, op, al.ctypes.data, al.size, ck.ctypes.data,
+                                              cv.ctypes.data, loss.ctypes.data, _stream_ptr(stream)))
+        return ck, cv, loss
 
     # ---- the hot-path calls, named as in the C ABI ----
     def skvq_prefill_attention(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,

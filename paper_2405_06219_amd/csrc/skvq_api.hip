@@ -20,6 +20,7 @@ struct skvq_cache {
   int forced_splits = 0;
   int n_cus = 256;
   void *dev_consts = nullptr;  // one allocation: perm_k, perm_v, clip_k, clip_v
+  std::vector<float> clip_k, clip_v;  // host copies of the clip scales [Hk][NG]
   std::string last_error;
 };
 
@@ -217,6 +218,8 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
     delete c;
     return SKVQ_ERR_HIP;
   }
+  c->clip_k.assign(cfg->clip_k, cfg->clip_k + n_clip);
+  c->clip_v.assign(cfg->clip_v, cfg->clip_v + n_clip);
   uint8_t *d = (uint8_t *)c->dev_consts;
   L.perm_k = (const int *)d;
   L.perm_v = (const int *)(d + off_pv);
@@ -259,6 +262,104 @@ int skvq_prefill_attention(skvq_cache *c, const void *q, const void *k, const vo
   hipError_t e = launch_prefill_attention(c->L, (const __half *)q, (const __half *)k, (const __half *)v,
                                           (float *)out_f32, (__half *)out_f16, T, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_attention launch");
+  return SKVQ_OK;
+}
+
+// Writes the host copies of the clip scales to the device, ordered in `stream`, and waits.
+static int upload_clips(skvq_cache *c, hipStream_t stream) {
+  const size_t bytes = c->clip_k.size() * sizeof(float);
+  hipError_t e = hipMemcpyAsync(const_cast<float *>(c->L.clip_k), c->clip_k.data(), bytes, hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(const_cast<float *>(c->L.clip_v), c->clip_v.data(), bytes, hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  return e == hipSuccess ? SKVQ_OK : fail_hip(c, e, "clip scale upload");
+}
+
+int skvq_set_clip(skvq_cache *c, const float *clip_k, const float *clip_v, void *stream) {
+  if (!c || !clip_k || !clip_v) return SKVQ_ERR_INVALID_ARG;
+  const size_t n = c->clip_k.size();
+  for (size_t x = 0; x < n; ++x)
+    if (!(clip_k[x] > 0.0f && clip_k[x] <= 1.0f) || !(clip_v[x] > 0.0f && clip_v[x] <= 1.0f)) return SKVQ_ERR_INVALID_ARG;
+  c->clip_k.assign(clip_k, clip_k + n);
+  c->clip_v.assign(clip_v, clip_v + n);
+  return upload_clips(c, (hipStream_t)stream);
+}
+
+int skvq_calibrate_clip(skvq_cache *c, const void *k, const void *v, int64_t T, const void *q, int32_t n_queries,
+                        const void *o_ref, const float *alphas, int32_t n_alphas, float *clip_k_out,
+                        float *clip_v_out, double *loss_out, void *stream_) {
+  if (!c || !k || !v || !q || !o_ref || !alphas || !clip_k_out || !clip_v_out || T < 1 || n_queries < 1 ||
+      n_alphas < 1 || n_queries > (1 << 20) || n_alphas > (1 << 16))
+    return SKVQ_ERR_INVALID_ARG;
+  for (int a = 0; a < n_alphas; ++a)
+    if (!(alphas[a] > 0.0f && alphas[a] <= 1.0f)) return SKVQ_ERR_INVALID_ARG;
+  const Layout &L = c->L;
+  if (counts_of(T, L.W, L.S).n_quant > L.Tcap) return SKVQ_ERR_CAPACITY;
+  hipStream_t stream = (hipStream_t)stream_;
+  const size_t out_n = (size_t)L.B * L.Hq * kD, slots = (size_t)L.B * L.Hk;
+  const size_t err_n = (size_t)n_alphas * n_queries * slots;
+  float *d_out = nullptr, *d_err = nullptr;
+  hipError_t e = hipMalloc(&d_out, out_n * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&d_err, err_n * sizeof(float));
+  if (e != hipSuccess) {
+    (void)hipFree(d_out);
+    return fail_hip(c, e, "skvq_calibrate_clip allocation");
+  }
+  std::vector<float> h_err(err_n);
+  const std::vector<float> start_k = c->clip_k, start_v = c->clip_v;
+  const Counts cnt = counts_of(T, L.W, L.S);
+  const int n_splits = choose_splits(c, cnt.n_quant);
+  int rc = SKVQ_OK;
+  for (int which = 0; which < 2 && rc == SKVQ_OK; ++which) {
+    std::vector<float> &clip = which ? c->clip_v : c->clip_k;
+    for (int g = 0; g < L.NG && rc == SKVQ_OK; ++g) {
+      for (int a = 0; a < n_alphas && rc == SKVQ_OK; ++a) {
+        for (int h = 0; h < L.Hk; ++h) clip[(size_t)h * L.NG + g] = alphas[a];
+        rc = upload_clips(c, stream);
+        if (rc != SKVQ_OK) break;
+        e = launch_prefill(L, (const __half *)k, (const __half *)v, T, stream);
+        for (int i = 0; i < n_queries && e == hipSuccess; ++i) {
+          e = launch_decode(L, (const __half *)q + (size_t)i * out_n, d_out, nullptr, T, n_splits, stream);
+          if (e == hipSuccess)
+            e = launch_sqerr(L, d_out, (const float *)o_ref + (size_t)i * out_n,
+                             d_err + ((size_t)a * n_queries + i) * slots, stream);
+        }
+        if (e != hipSuccess) rc = fail_hip(c, e, "skvq_calibrate_clip launch");
+      }
+      if (rc != SKVQ_OK) break;
+      e = hipMemcpyAsync(h_err.data(), d_err, err_n * sizeof(float), hipMemcpyDeviceToHost, stream);
+      if (e == hipSuccess) e = hipStreamSynchronize(stream);
+      if (e != hipSuccess) {
+        rc = fail_hip(c, e, "skvq_calibrate_clip read-back");
+        break;
+      }
+      for (int h = 0; h < L.Hk; ++h) {  // per kv head: the candidate with the smallest error, the earliest on ties
+        int best = 0;
+        double best_err = 0.0;
+        for (int a = 0; a < n_alphas; ++a) {
+          double s = 0.0;
+          for (int i = 0; i < n_queries; ++i)
+            for (int b = 0; b < L.B; ++b) s += (double)h_err[((size_t)a * n_queries + i) * slots + (size_t)b * L.Hk + h];
+          if (a == 0 || s < best_err) best = a, best_err = s;
+        }
+        clip[(size_t)h * L.NG + g] = alphas[best];
+        if (loss_out) loss_out[h] = best_err;
+      }
+    }
+  }
+  (void)hipFree(d_out);
+  (void)hipFree(d_err);
+  if (rc != SKVQ_OK) {  // leave the cache's clip scales as they were
+    c->clip_k = start_k;
+    c->clip_v = start_v;
+    (void)upload_clips(c, stream);
+    return rc;
+  }
+  rc = upload_clips(c, stream);
+  if (rc != SKVQ_OK) return rc;
+  std::memcpy(clip_k_out, c->clip_k.data(), c->clip_k.size() * sizeof(float));
+  std::memcpy(clip_v_out, c->clip_v.data(), c->clip_v.size() * sizeof(float));
+  c->n_tokens = T;  // the buffers hold the calibration tokens as the last candidate quantized them
   return SKVQ_OK;
 }
 

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 #include "skvq.h"
@@ -72,6 +73,10 @@ hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_n
 // prefill attention (skvq_prefill_attn.hip): causal attention of the prompt on fp16 q, k, v
 hipError_t launch_prefill_attention(const Layout &L, const __half *q, const __half *k, const __half *v,
                                     float *out_f32, __half *out_f16, long long T, hipStream_t s);
+
+// clip calibration (skvq_calibrate.hip): err[b * Hk + hk] = squared error of one decode call's
+// outputs [B][Hq][D] against ref, over the kv head's query heads and channels
+hipError_t launch_sqerr(const Layout &L, const float *out, const float *ref, float *err, hipStream_t s);
 
 // decode kernels (skvq_decode.hip)
 // n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).

@@ -508,6 +508,67 @@ def test_prefill_attention_matches_oracle(P, B, Hq, Hk, T):
     assert np.array_equal(o16.cpu().numpy(), out.astype(np.float16))
 
 
+# ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
+
+@pytest.mark.parametrize("G,v_bits,k_bits,Hq,Hk,B", [(64, 2.0, 2.0, 4, 2, 1), (128, 1.5, 2.0, 8, 2, 2), (32, 4.0, 4.0, 3, 3, 1)])
+def test_clip_calibration_matches_oracle_search(P, G, v_bits, k_bits, Hq, Hk, B):
+    """The same calibration tokens, queries, full-precision outputs and grid on both sides.  The
+    chosen scales must be the oracle's; where a near-tie makes them differ, the oracle's own
+    evaluation of the library's choice must be within 0.1 % of the oracle's result.  The scales
+    that the library then uses must encode bit-exactly like the oracle with the same scales."""
+    from oracle import skvq_oracle as O
+    from paper_2405_06219_amd import binding as Bd
+    rng = np.random.default_rng(4000 + G)
+    T, W, n_q = 300, 16, 4
+    dev = "cuda:0"
+    pk = np.stack([rng.permutation(D) for _ in range(Hk)]).astype(np.int32)
+    pv = np.stack([rng.permutation(D) for _ in range(Hk)]).astype(np.int32)
+    k = (rng.standard_t(2.5, (B, Hk, T, D)) * 0.5).astype(np.float16)
+    v = (rng.standard_t(2.5, (B, Hk, T, D)) * 0.5).astype(np.float16)
+    q = rng.standard_normal((n_q, B, Hq, D)).astype(np.float16)
+    kt = torch.from_numpy(k.astype(np.float64)).repeat_interleave(Hq // Hk, dim=1)
+    vt = torch.from_numpy(v.astype(np.float64)).repeat_interleave(Hq // Hk, dim=1)
+    o_ref = np.stack([torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q[i].astype(np.float64))[:, :, None, :], kt, vt)[:, :, 0].numpy() for i in range(n_q)]).astype(np.float32)
+    ones = np.ones((Hk, D // G), np.float32)
+    alphas = np.array([1.0, 0.95, 0.9, 0.8, 0.7], np.float32)
+
+    ref = O.OracleCache(B, Hq, Hk, G, v_bits, W, T, pk, pv, ones, ones, k_bits=k_bits, fill=0xAB)
+    rk, rv, rloss = ref.calibrate_clip(k, v, q, o_ref, alphas)
+    gpu = Bd.SkvqCache(B, Hq, Hk, G, v_bits, W, T, pk, pv, ones, ones, k_bits=k_bits, fill=0xAB, device=dev)
+    kd, vd = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+    gk, gv, gloss = gpu.skvq_calibrate_clip(kd, vd, torch.from_numpy(q).to(dev), torch.from_numpy(o_ref).to(dev), alphas)
+    P.log(f"clip calibration G{G}: oracle K {rk.tolist()} V {rv.tolist()} loss {rloss.tolist()}")
+    P.log(f"clip calibration G{G}: gpu    K {gk.tolist()} V {gv.tolist()} loss {gloss.tolist()}")
+
+    def oracle_loss(ck, cv):
+        c = O.OracleCache(B, Hq, Hk, G, v_bits, W, T, pk, pv, ck, cv, k_bits=k_bits)
+        assert c.prefill(k, v) == 0
+        out = np.stack([c.decode(q[i]) for i in range(n_q)]).astype(np.float64)
+        return ((out - o_ref) ** 2).reshape(n_q, B, Hk, Hq // Hk, D).sum(axis=(0, 1, 3, 4))
+
+    if not (np.array_equal(gk, rk) and np.array_equal(gv, rv)):
+        assert np.all(oracle_loss(gk, gv) <= rloss * 1.001)
+    assert np.allclose(gloss, oracle_loss(gk, gv), rtol=2e-3)
+    assert np.any(gk < 1.0) or np.any(gv < 1.0)           # heavy-tailed data: clipping pays
+    # the library now encodes with the scales it chose
+    want = O.OracleCache(B, Hq, Hk, G, v_bits, W, T, pk, pv, gk, gv, k_bits=k_bits, fill=0xAB)
+    assert want.prefill(k, v) == 0
+    gpu.skvq_prefill_quantize(kd, vd)
+    for name, g, r in zip(["k_codes", "v_codes", "k_meta", "v_meta"], gpu.host_arrays(), want.arrays()):
+        assert np.array_equal(g.view(np.uint8), r.view(np.uint8)), name
+    # skvq_set_clip: back to other scales, bit-exact again
+    other = rng.uniform(0.6, 1.0, (Hk, D // G)).astype(np.float32)
+    gpu.skvq_set_clip(other, ones)
+    want = O.OracleCache(B, Hq, Hk, G, v_bits, W, T, pk, pv, other, ones, k_bits=k_bits, fill=0xAB)
+    assert want.prefill(k, v) == 0
+    gpu.skvq_prefill_quantize(kd, vd)
+    for name, g, r in zip(["k_codes", "v_codes", "k_meta", "v_meta"], gpu.host_arrays(), want.arrays()):
+        assert np.array_equal(g.view(np.uint8), r.view(np.uint8)), name
+    with pytest.raises(Bd.SkvqError):
+        gpu.skvq_set_clip(other * 0.0, ones)
+
+
 def test_random_configurations(P):
     """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
