@@ -90,12 +90,13 @@ typedef struct {
   const float *clip_k;   /* HOST [Hk][D/G]: alpha in (0,1] per (kv head, group), Eq. 2    */
   const float *clip_v;   /* HOST [Hk][D/G]                                                */
   float sm_scale;        /* softmax scale; 0 selects 1/sqrt(D)                            */
-  const int32_t *group_bounds; /* HOST [D/G + 1] or NULL.  NULL: uniform groups of G positions.
+  const int32_t *group_bounds; /* HOST [Hk][D/G + 1] or NULL.  NULL: uniform groups of G positions.
                            Else (Section 4.1: clustering the channels gives groups of unequal
-                           size, G being their average): group g covers the reordered
-                           positions [bounds[g], bounds[g+1]), bounds[0] = 0 < ... < bounds[D/G]
-                           = D, every boundary a multiple of 16 (SKVQ_ERR_UNSUPPORTED
-                           otherwise).  The same boundaries serve keys and values.        */
+                           size, G being their average): group g of kv head h covers the
+                           reordered positions [bounds[h][g], bounds[h][g+1]), bounds[h][0] = 0
+                           < ... < bounds[h][D/G] = D, every boundary a multiple of 16
+                           (SKVQ_ERR_UNSUPPORTED otherwise).  A head's boundaries serve its
+                           keys and its values.                                           */
 } skvq_config;
 
 /* DEVICE buffers of one layer's cache; byte sizes come from skvq_sizes(), in this order.

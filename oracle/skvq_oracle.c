@@ -273,24 +273,25 @@ void skvq_ref_v_put(uint8_t *block, int levels, int s, int p, int code) {
 /* Group g covers the reordered positions [group_lo(g), group_lo(g+1)): g*G when
  * the groups are uniform, else the caller's boundaries (Section 4.1: clustering
  * the channels gives groups of unequal size; G is then their average). */
-static int group_lo(const skvq_ref_config *c, int g) {
-  return c->group_bounds ? c->group_bounds[g] : g * c->group_size;
+static int group_lo(const skvq_ref_config *c, int hk, int g) {
+  int ng = D / c->group_size;
+  return c->group_bounds ? c->group_bounds[hk * (ng + 1) + g] : g * c->group_size;
 }
-static int group_of(const skvq_ref_config *c, int p) {
+static int group_of(const skvq_ref_config *c, int hk, int p) {
   int g = 0;
-  while (p >= group_lo(c, g + 1)) ++g;
+  while (p >= group_lo(c, hk, g + 1)) ++g;
   return g;
 }
 
 /* x: fp16 bits [D] of one (token, kv head), original channel order.
  * Gathers through perm (out[p] = in[perm[p]]), encodes each group, returns
  * codes[D] in reordered order and meta[D/G][2]. */
-static void encode_token(const skvq_ref_config *c, const uint16_t *x, const int32_t *perm,
+static void encode_token(const skvq_ref_config *c, int hk, const uint16_t *x, const int32_t *perm,
                          const float *alpha, int levels, uint8_t *codes, float *meta) {
   float xp[D];
   for (int p = 0; p < D; ++p) xp[p] = skvq_ref_half_to_float(x[perm[p]]);
   for (int g = 0; g < D / c->group_size; ++g) {
-    int lo = group_lo(c, g), hi = group_lo(c, g + 1);
+    int lo = group_lo(c, hk, g), hi = group_lo(c, hk, g + 1);
     skvq_ref_encode_group(xp + lo, hi - lo, alpha[g], levels, c->meta_format, codes + lo,
                           &meta[2 * g], &meta[2 * g + 1]);
   }
@@ -306,14 +307,14 @@ static void store_quantized(const skvq_ref_config *c, const skvq_ref_buffers *bu
   float meta[2 * D];
 
   int fmt = c->meta_format;
-  encode_token(c, kx, c->perm_k + hk * D, c->clip_k + hk * ng, c->k_levels, codes, meta);
+  encode_token(c, hk, kx, c->perm_k + hk * D, c->clip_k + hk * ng, c->k_levels, codes, meta);
   uint8_t *krow = buf->k_codes + (head * tcap + (size_t)t) * k_row_bytes(c->k_levels);
   memset(krow, 0, k_row_bytes(c->k_levels));
   for (int p = 0; p < D; ++p) skvq_ref_k_put(krow, c->k_levels, p, codes[p]);
   for (int x = 0; x < 2 * ng; ++x)
     meta_store(buf->k_meta, (head * tcap + (size_t)t) * ng * 2 + x, meta[x], fmt);
 
-  encode_token(c, vx, c->perm_v + hk * D, c->clip_v + hk * ng, c->v_levels, codes, meta);
+  encode_token(c, hk, vx, c->perm_v + hk * D, c->clip_v + hk * ng, c->v_levels, codes, meta);
   size_t nblk = (tcap + VBT - 1) / VBT, bb = v_block_bytes(c->v_levels);
   uint8_t *blk = buf->v_codes + (head * nblk + (size_t)(t / VBT)) * bb;
   if (t % VBT == 0) memset(blk, 0, bb);
@@ -330,11 +331,14 @@ static int check_config(const skvq_ref_config *c) {
   if (c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads || c->window < 1 || c->batch < 1 ||
       c->n_sink < 0 || c->meta_format < 0 || c->meta_format > 2)
     return -1;
-  if (c->group_bounds) { /* 0 = b_0 < b_1 < ... < b_ng = D */
+  if (c->group_bounds) { /* per kv head: 0 = b_0 < b_1 < ... < b_ng = D */
     int ng = D / c->group_size;
-    if (c->group_bounds[0] != 0 || c->group_bounds[ng] != D) return -1;
-    for (int g = 0; g < ng; ++g)
-      if (c->group_bounds[g + 1] <= c->group_bounds[g]) return -1;
+    for (int h = 0; h < c->n_kv_heads; ++h) {
+      const int32_t *gb = c->group_bounds + h * (ng + 1);
+      if (gb[0] != 0 || gb[ng] != D) return -1;
+      for (int g = 0; g < ng; ++g)
+        if (gb[g + 1] <= gb[g]) return -1;
+    }
   }
   return 0;
 }
@@ -422,7 +426,7 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
     const int32_t *pk = c->perm_k + hk * D, *pv = c->perm_v + hk * D;
     double qf[D], acc[D];
     int gof[D]; /* group of reordered position p */
-    for (int p = 0; p < D; ++p) gof[p] = group_of(c, p);
+    for (int p = 0; p < D; ++p) gof[p] = group_of(c, hk, p);
     for (int ch = 0; ch < D; ++ch) qf[ch] = skvq_ref_half_to_float(q[(size_t)bq * D + ch]);
     double *s = (double *)malloc(sizeof(double) * (size_t)T);
     if (!s) {

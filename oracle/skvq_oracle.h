@@ -52,8 +52,9 @@ typedef struct {
   const float *clip_k, *clip_v;                   /* [Hk][D/G] alpha           */
   float sm_scale;                                 /* softmax scale             */
   const int32_t *group_bounds;                    /* NULL = uniform groups; else
-                                                     D/G + 1 ascending entries,
-                                                     0 .. D: group g covers the
+                                                     [Hk][D/G + 1]: per kv head
+                                                     ascending entries 0 .. D,
+                                                     group g covers the
                                                      reordered positions
                                                      [bounds[g], bounds[g+1])  */
 } skvq_ref_config;

@@ -146,9 +146,15 @@ class OracleCache:
         self.clip_v = np.ascontiguousarray(clip_v, np.float32)
         if sm_scale is None:
             sm_scale = 1.0 / np.sqrt(HEAD_DIM)
-        # unequal groups: HEAD_DIM // group_size + 1 ascending boundaries (group_size = the average)
-        self.group_bounds = None if group_bounds is None else np.ascontiguousarray(group_bounds, np.int32)
-        assert self.group_bounds is None or self.group_bounds.shape == (HEAD_DIM // group_size + 1,)
+        # unequal groups: per kv head HEAD_DIM // group_size + 1 ascending boundaries (group_size = the
+        # average); one row is repeated for every kv head
+        self.group_bounds = None
+        if group_bounds is not None:
+            gb = np.atleast_2d(np.asarray(group_bounds, np.int32))
+            if gb.shape[0] == 1:
+                gb = np.repeat(gb, n_kv_heads, axis=0)
+            self.group_bounds = np.ascontiguousarray(gb)
+            assert self.group_bounds.shape == (n_kv_heads, HEAD_DIM // group_size + 1)
         self.cfg = _Config(batch, n_q_heads, n_kv_heads, HEAD_DIM, group_size, levels_of(k_bits),
                            levels_of(v_bits), window, n_sink, META_FORMATS[meta], max_quant_tokens,
                            _ptr(self.perm_k),

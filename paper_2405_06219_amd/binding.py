@@ -92,10 +92,13 @@ def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_qu
     """Returns (skvq_config, keepalive): the numpy arrays the config points to."""
     keep = [np.ascontiguousarray(perm_k, np.int32), np.ascontiguousarray(perm_v, np.int32),
             np.ascontiguousarray(clip_k, np.float32), np.ascontiguousarray(clip_v, np.float32)]
-    if group_bounds is not None:
-        keep.append(np.ascontiguousarray(group_bounds, np.int32))
-        if keep[4].shape != (head_dim // group_size + 1,):
-            raise ValueError("group_bounds needs head_dim / group_size + 1 entries")
+    if group_bounds is not None:      # [n_kv_heads][head_dim / group_size + 1]; one row serves every head
+        gb = np.atleast_2d(np.asarray(group_bounds, np.int32))
+        if gb.shape[0] == 1:
+            gb = np.repeat(gb, n_kv_heads, axis=0)
+        keep.append(np.ascontiguousarray(gb))
+        if keep[4].shape != (n_kv_heads, head_dim // group_size + 1):
+            raise ValueError("group_bounds needs head_dim / group_size + 1 entries per kv head")
     cfg = skvq_config(batch, n_q_heads, n_kv_heads, head_dim, group_size, bits_enum(k_bits), bits_enum(v_bits),
                       window, n_sink, META_FORMATS[meta], max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
                       keep[3].ctypes.data, float(sm_scale), keep[4].ctypes.data if group_bounds is not None else None)

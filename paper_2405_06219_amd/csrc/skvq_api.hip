@@ -50,12 +50,14 @@ int check_config(const skvq_config *c) {
   if (!c->perm_k || !c->perm_v || !c->clip_k || !c->clip_v) return SKVQ_ERR_INVALID_ARG;
   const int ng = kD / c->group_size;
   if (c->group_bounds) {
-    const int32_t *gb = c->group_bounds;
-    if (gb[0] != 0 || gb[ng] != kD) return SKVQ_ERR_INVALID_ARG;
-    for (int g = 0; g < ng; ++g)
-      if (gb[g + 1] <= gb[g]) return SKVQ_ERR_INVALID_ARG;
-    for (int g = 0; g <= ng; ++g)
-      if (gb[g] % 16) return SKVQ_ERR_UNSUPPORTED;
+    for (int h = 0; h < c->n_kv_heads; ++h) {
+      const int32_t *gb = c->group_bounds + (size_t)h * (ng + 1);
+      if (gb[0] != 0 || gb[ng] != kD) return SKVQ_ERR_INVALID_ARG;
+      for (int g = 0; g < ng; ++g)
+        if (gb[g + 1] <= gb[g]) return SKVQ_ERR_INVALID_ARG;
+    }
+    for (int x = 0; x < c->n_kv_heads * (ng + 1); ++x)
+      if (c->group_bounds[x] % 16) return SKVQ_ERR_UNSUPPORTED;
   }
   for (int which = 0; which < 2; ++which) {
     const int32_t *perm = which ? c->perm_v : c->perm_k;
@@ -167,16 +169,18 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.G = cfg->group_size;
   L.NG = kD / L.G;
   L.uneq = 0;
-  L.gmap = 0;
-  for (int n = 0; n < 8; ++n) {  // group of positions 16n .. 16n+15
-    int g = 16 * n / L.G;
-    if (cfg->group_bounds) {
-      g = 0;
-      while (16 * n >= cfg->group_bounds[g + 1]) ++g;
-      if (g != 16 * n / L.G) L.uneq = 1;
+  std::vector<unsigned> gmaps((size_t)L.Hk, 0u);
+  for (int h = 0; h < L.Hk; ++h)
+    for (int n = 0; n < 8; ++n) {  // group of positions 16n .. 16n+15 of kv head h
+      int g = 16 * n / L.G;
+      if (cfg->group_bounds) {
+        const int32_t *gb = cfg->group_bounds + (size_t)h * (L.NG + 1);
+        g = 0;
+        while (16 * n >= gb[g + 1]) ++g;
+        if (g != 16 * n / L.G) L.uneq = 1;
+      }
+      gmaps[h] |= (unsigned)g << (4 * n);
     }
-    L.gmap |= (unsigned)g << (4 * n);
-  }
   L.W = cfg->window;
   L.S = cfg->n_sink;
   L.meta_fmt = cfg->meta_format;
@@ -196,16 +200,18 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.v_win = (__half *)bufs->v_win;
   L.workspace = (float *)bufs->workspace;
 
-  // constants: [perm_k | perm_v | clip_k | clip_v], one allocation
+  // constants: [perm_k | perm_v | clip_k | clip_v | gmaps], one allocation
   const size_t n_perm = (size_t)L.Hk * kD, n_clip = (size_t)L.Hk * L.NG;
   const size_t off_pv = n_perm * 4, off_ck = off_pv + n_perm * 4;
   const size_t off_cv = off_ck + ((n_clip * 4 + 15) & ~(size_t)15);
-  const size_t total = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
+  const size_t off_gm = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
+  const size_t total = off_gm + (((size_t)L.Hk * 4 + 15) & ~(size_t)15);
   std::vector<uint8_t> host(total, 0);
   std::memcpy(host.data(), cfg->perm_k, n_perm * 4);
   std::memcpy(host.data() + off_pv, cfg->perm_v, n_perm * 4);
   std::memcpy(host.data() + off_ck, cfg->clip_k, n_clip * 4);
   std::memcpy(host.data() + off_cv, cfg->clip_v, n_clip * 4);
+  std::memcpy(host.data() + off_gm, gmaps.data(), (size_t)L.Hk * 4);
 
   hipError_t e = hipMalloc(&c->dev_consts, total);
   if (e != hipSuccess) {
@@ -225,6 +231,7 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.perm_v = (const int *)(d + off_pv);
   L.clip_k = (const float *)(d + off_ck);
   L.clip_v = (const float *)(d + off_cv);
+  L.gmaps = (const unsigned *)(d + off_gm);
 
   int dev = 0;
   hipDeviceProp_t prop;

@@ -314,13 +314,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   constexpr float kCentre = 0.5f * (KL - 1);  // the key codes enter the products centred
   // score accumulators / weight operands: one per group, or (unequal groups) one per 16 positions
   constexpr int NACC = UNEQ ? 8 : NG;
-  const unsigned gmap = L.gmap;
-  auto piece_group = [&](int n) { return (int)((gmap >> (4 * n)) & 15u); };  // group of positions 16n..16n+15
   __shared__ Smem<R, TERNARY, NG> sm;
   SKVQ_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int sp = blockIdx.x, hk = blockIdx.y / passes, b = blockIdx.z;
+  const unsigned gmap = UNEQ ? L.gmaps[hk] : 0u;
+  auto piece_group = [&](int n) { return (int)((gmap >> (4 * n)) & 15u); };  // group of positions 16n..16n+15
   const int head0 = (blockIdx.y % passes) * R;  // first of this workgroup's query heads, within the kv head's
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;

@@ -30,7 +30,8 @@ struct Layout {
   int B, Hq, Hk, R;      // R = Hq / Hk
   int G, NG;             // (average) group size, groups per head
   int uneq;              // 1: the groups are unequal (boundaries at multiples of 16 positions)
-  unsigned gmap;         // group of the 16 positions 16n .. 16n+15: bits [4n, 4n+4), n = 0..7
+  const unsigned *gmaps; // device [Hk]: group of the 16 positions 16n .. 16n+15 of a kv head's rows: bits
+                         // [4n, 4n+4), n = 0..7 (read only when uneq)
   int W;                 // window
   int S;                 // attention sinks: tokens 0..S-1 are never quantized
   int meta_fmt;          // skvq_meta_format of (scale, zero)

@@ -278,8 +278,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   }
   const int i = lane >> 3, n = lane & 7;
   const bool uneq = L.uneq != 0;
-  const int grp = uneq ? tile_group(L.gmap, n) : (16 * n) / L.G;
-  const bool writes_meta = uneq ? (n == 0 || tile_group(L.gmap, n - 1) != grp) : (16 * n) % L.G == 0;
+  const unsigned gmap = uneq ? L.gmaps[hk] : 0u;
+  const int grp = uneq ? tile_group(gmap, n) : (16 * n) / L.G;
+  const bool writes_meta = uneq ? (n == 0 || tile_group(gmap, n - 1) != grp) : (16 * n) % L.G == 0;
   const float ak = L.clip_k[hk * L.NG + grp], av = L.clip_v[hk * L.NG + grp];
   int4 pk[4], pv[4];
   {
@@ -297,8 +298,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
 
   GroupParams gk, gv;
   constexpr int kKBits = KL == 16 ? 4 : KL == 8 ? 3 : 2, kVBits = VL == 16 ? 4 : VL == 8 ? 3 : 2;
-  const uint2 kw = encode16<kKBits>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, uneq, L.gmap, lane, gk);
-  const uint2 vw = encode16<kVBits>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, uneq, L.gmap, lane, gv);
+  const uint2 kw = encode16<kKBits>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, uneq, gmap, lane, gk);
+  const uint2 vw = encode16<kVBits>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, uneq, gmap, lane, gv);
   unsigned ktop = 0;
   if (KL == 8) {  // the plane dword of a pair of key dwords comes from two lanes
     ktop = place_key_top_bits(kw.y, n & 1);
@@ -437,7 +438,8 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   const int s = evict ? (int)(te % kVBlock) : 0, kb = s >> 3, i = s & 7;
   uint8_t *blk = L.v_codes + (head * L.n_vblocks + (evict ? te / kVBlock : 0)) * L.v_block_bytes;
   const bool uneq = L.uneq != 0;
-  const int grp = uneq ? tile_group(L.gmap, lane >> 3) : (2 * lane) / L.G;
+  const unsigned gmap = uneq ? L.gmaps[hk] : 0u;
+  const int grp = uneq ? tile_group(gmap, lane >> 3) : (2 * lane) / L.G;
   __half2 old2 = fresh2;
   int p0 = 0, p1 = 0;
   float alpha = 1.f;
@@ -479,10 +481,10 @@ __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__r
   const float top = (float)((wave ? L.v_levels : L.k_levels) - 1);
   unsigned c0, c1;
   MetaPair mp;
-  encode_row(rows[wave], p0, p1, alpha, L.G, top, L.meta_fmt, uneq, L.gmap, lane, c0, c1, mp);
+  encode_row(rows[wave], p0, p1, alpha, L.G, top, L.meta_fmt, uneq, gmap, lane, c0, c1, mp);
   void *meta = wave ? L.v_meta : L.k_meta;
   const bool first_of_group =
-      uneq ? ((lane & 7) == 0 && (lane == 0 || tile_group(L.gmap, (lane >> 3) - 1) != grp)) : (2 * lane) % L.G == 0;
+      uneq ? ((lane & 7) == 0 && (lane == 0 || tile_group(gmap, (lane >> 3) - 1) != grp)) : (2 * lane) % L.G == 0;
   if (first_of_group)
     meta_store_pair(meta, (head * L.Tcap + te) * L.NG + grp, mp, L.meta_fmt);
 

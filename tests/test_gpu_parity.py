@@ -446,6 +446,11 @@ UNEQUAL_CASES = [
     (small("uneq_g64_k2v4_gqa3", k_bits=2.0, v_bits=4.0, n_q_heads=6, n_kv_heads=2, group_size=64, context=450, window=16),
      [0, 16, 128], "f32", 0),
     (small("uneq_g32_written_uniform", group_size=32, context=600), [0, 32, 64, 96, 128], "f32", 0),
+    (small("uneq_g32_per_head_t15", n_q_heads=8, n_kv_heads=4, group_size=32, context=1300),
+     [[0, 16, 32, 80, 128], [0, 32, 64, 96, 128], [0, 64, 96, 112, 128], [0, 16, 32, 48, 128]],
+     "f16", 0),
+    (small("uneq_g64_per_head_k4v4", k_bits=4.0, v_bits=4.0, n_q_heads=4, n_kv_heads=2, group_size=64, context=800, batch=2),
+     [[0, 16, 128], [0, 112, 128]], "f32", 5),
     (small("uneq_g32_k3v3_gqa2", k_bits=3.0, v_bits=3.0, n_q_heads=4, n_kv_heads=2, group_size=32, context=1100),
      [0, 64, 80, 96, 128], "e4m3", 5),
 ]

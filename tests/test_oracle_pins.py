@@ -418,8 +418,9 @@ def numpy_dequantize(c, T):
     kq = np.zeros((B, Hk, nq, D))
     vq = np.zeros((B, Hk, nq, D))
     p = np.arange(D)
-    bounds = getattr(c, "group_bounds", None)
-    gof = p // G if bounds is None else np.searchsorted(np.asarray(bounds), p, side="right") - 1
+    bounds = getattr(c, "group_bounds", None)       # None or [Hk][D/G + 1]
+    gof = np.stack([p // G if bounds is None else np.searchsorted(np.asarray(bounds[h]), p, side="right") - 1
+                    for h in range(Hk)])             # [Hk][D]: group of position p of head h
     if c.cfg.k_levels == 16:
         kc = (c.k_codes[:, :, :nq, p // 2] >> (4 * (p % 2))) & 15
     elif c.cfg.k_levels == 8:
@@ -427,11 +428,11 @@ def numpy_dequantize(c, T):
         kc = ((c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3) + 4 * ((c.k_codes[:, :, :nq, top // 8] >> (top % 8)) & 1)
     else:
         kc = (c.k_codes[:, :, :nq, p // 4] >> (2 * (p % 4))) & 3
-    ks = c.k_meta[:, :, :nq, gof, 0].astype(np.float64)
-    kz = c.k_meta[:, :, :nq, gof, 1].astype(np.float64)
+    def per_position(meta, x):      # [B][Hk][nq][D]: the group's value for every position
+        return np.stack([meta[:, h, :nq][:, :, gof[h], x] for h in range(Hk)], axis=1).astype(np.float64)
+    ks, kz = per_position(c.k_meta, 0), per_position(c.k_meta, 1)
     kd = kc * ks + kz
-    vs = c.v_meta[:, :, :nq, gof, 0].astype(np.float64)
-    vz = c.v_meta[:, :, :nq, gof, 1].astype(np.float64)
+    vs, vz = per_position(c.v_meta, 0), per_position(c.v_meta, 1)
     vc = np.zeros((B, Hk, nq, D), np.int64)
     for b in range(B):
         for h in range(Hk):
@@ -962,3 +963,34 @@ def test_clip_calibration_keeps_alpha_one_when_the_data_is_exactly_representable
     # a one-point grid returns that point
     ck, cv, _ = make().calibrate_clip(k, v, q, o_ref, np.array([0.75], np.float32))
     assert np.all(ck == 0.75) and np.all(cv == 0.75)
+
+
+def test_unequal_groups_may_differ_between_kv_heads(oracle):
+    """Clustering each kv head's channels gives each head its own group sizes."""
+    rng = np.random.default_rng(960)
+    B, Hq, Hk, W, T, G = 1, 4, 2, 8, 40, 32
+    bounds = np.array([[0, 16, 32, 80, 128], [0, 5, 64, 127, 128]], np.int32)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    clip = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, G, 2.0, W, 64, pk, pv, clip, clip, group_bounds=bounds)
+    assert c.prefill(k, v) == 0
+    f32 = np.float32
+    for h in range(Hk):
+        xp = k[0, h, 3, pk[h]].astype(f32)
+        for g in range(D // G):
+            lo, hi = bounds[h, g], bounds[h, g + 1]
+            zero = f32(clip[h, g] * xp[lo:hi].min())
+            assert c.k_meta[0, h, 3, g, 1] == zero
+            assert c.k_meta[0, h, 3, g, 0] == f32(f32(f32(clip[h, g] * xp[lo:hi].max()) - zero) / f32(3))
+    kq, vq = numpy_dequantize(c, T)
+    kfull = np.concatenate([kq, k[:, :, T - W:].astype(np.float64)], axis=2)
+    vfull = np.concatenate([vq, v[:, :, T - W:].astype(np.float64)], axis=2)
+    ref = sdpa64(q, kfull, vfull, 1 / np.sqrt(D))
+    assert np.abs(c.decode(q) - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    # each head's own head-0 bounds alone give the same head-0 rows
+    c0 = oracle.OracleCache(B, Hq, Hk, G, 2.0, W, 64, pk, pv, clip, clip, group_bounds=bounds[0])
+    assert c0.prefill(k, v) == 0
+    assert np.array_equal(c0.k_codes[:, 0], c.k_codes[:, 0]) and not np.array_equal(c0.k_codes[:, 1], c.k_codes[:, 1])
