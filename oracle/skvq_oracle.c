@@ -606,6 +606,112 @@ int skvq_ref_calibrate_clip(const skvq_ref_config *c, const skvq_ref_buffers *bu
   return rc;
 }
 
+/* ------------------------------------------------------ channel reorder --- */
+
+/* Per (kv head, channel): minimum and maximum over all B*T calibration tokens. */
+void skvq_ref_channel_stats(const uint16_t *x, int B, int Hk, int64_t T, float *stats) {
+  for (int h = 0; h < Hk; ++h)
+    for (int ch = 0; ch < D; ++ch) {
+      float mn = INFINITY, mx = -INFINITY;
+      for (int b = 0; b < B; ++b)
+        for (int64_t t = 0; t < T; ++t) {
+          float f = skvq_ref_half_to_float(x[(((size_t)b * Hk + h) * (size_t)T + (size_t)t) * D + ch]);
+          if (f < mn) mn = f;
+          if (f > mx) mx = f;
+        }
+      stats[((size_t)h * D + ch) * 2] = mn;
+      stats[((size_t)h * D + ch) * 2 + 1] = mx;
+    }
+}
+
+/* Section 3.1 ("we extract the distribution feature of each channel and then use
+ * the KMeans algorithm to cluster channels with similar characteristics into the
+ * same group"; Algorithm 1 Prologue, get_permutation_matrix).  The paper names
+ * neither the feature nor the initialisation; this build's reading, per kv head:
+ *   feature of a channel = (min, max) over the calibration tokens;
+ *   k = D/G clusters; channels ordered by range max-min (ties: channel index),
+ *   initial centroid j = mean feature of the j-th run of G channels in that order;
+ *   Lloyd iterations in fp64 (nearest centroid by squared Euclidean distance, ties:
+ *   the lowest cluster; an empty cluster keeps its centroid) until no channel
+ *   moves, at most max_iter;
+ *   clusters are listed by the range of their centroid, ascending (ties: index),
+ *   the channels of a cluster by their own range, ascending (ties: index):
+ *   perm[p] = channel at reordered position p; the groups are the clusters, their
+ *   boundaries rounded to multiples of `granularity` (nearest; every group keeps
+ *   at least `granularity` positions), which moves the channels next to a
+ *   boundary into the neighbouring group. */
+int skvq_ref_calibrate_reorder(const float *stats, int Hk, int group_size, int granularity,
+                               int max_iter, int32_t *perm, int32_t *bounds) {
+  if (group_size <= 0 || D % group_size || granularity < 1 || group_size % granularity || max_iter < 0)
+    return -1;
+  int ng = D / group_size;
+  for (int h = 0; h < Hk; ++h) {
+    const float *f = stats + (size_t)h * D * 2;
+    double rng[D];
+    int order[D], label[D];
+    for (int ch = 0; ch < D; ++ch) rng[ch] = (double)f[2 * ch + 1] - (double)f[2 * ch], order[ch] = ch;
+    for (int i = 1; i < D; ++i) { /* insertion sort by (range, channel) */
+      int o = order[i], j = i;
+      while (j > 0 && rng[order[j - 1]] > rng[o]) order[j] = order[j - 1], --j;
+      order[j] = o;
+    }
+    double cmin[D], cmax[D];
+    for (int j = 0; j < ng; ++j) {
+      double a = 0.0, b = 0.0;
+      for (int i = 0; i < group_size; ++i) {
+        a += (double)f[2 * order[j * group_size + i]];
+        b += (double)f[2 * order[j * group_size + i] + 1];
+      }
+      cmin[j] = a / group_size, cmax[j] = b / group_size;
+    }
+    for (int ch = 0; ch < D; ++ch) label[ch] = -1;
+    for (int it = 0; it <= max_iter; ++it) {
+      int moved = 0;
+      for (int ch = 0; ch < D; ++ch) {
+        int best = 0;
+        double bd = 0.0;
+        for (int j = 0; j < ng; ++j) {
+          double da = (double)f[2 * ch] - cmin[j], db = (double)f[2 * ch + 1] - cmax[j];
+          double d = da * da + db * db;
+          if (j == 0 || d < bd) best = j, bd = d;
+        }
+        if (best != label[ch]) label[ch] = best, moved = 1;
+      }
+      if (!moved || it == max_iter) break;
+      for (int j = 0; j < ng; ++j) {
+        double a = 0.0, b = 0.0;
+        int n = 0;
+        for (int ch = 0; ch < D; ++ch)
+          if (label[ch] == j) a += (double)f[2 * ch], b += (double)f[2 * ch + 1], ++n;
+        if (n) cmin[j] = a / n, cmax[j] = b / n;
+      }
+    }
+    /* clusters by centroid range */
+    int corder[D];
+    for (int j = 0; j < ng; ++j) corder[j] = j;
+    for (int i = 1; i < ng; ++i) {
+      int o = corder[i], j = i;
+      while (j > 0 && cmax[corder[j - 1]] - cmin[corder[j - 1]] > cmax[o] - cmin[o]) corder[j] = corder[j - 1], --j;
+      corder[j] = o;
+    }
+    int32_t *pm = perm + (size_t)h * D, *gb = bounds + (size_t)h * (ng + 1);
+    int p = 0;
+    gb[0] = 0;
+    for (int jj = 0; jj < ng; ++jj) {
+      for (int i = 0; i < D; ++i) /* `order` is by (range, channel) already */
+        if (label[order[i]] == corder[jj]) pm[p++] = order[i];
+      gb[jj + 1] = p;
+    }
+    /* boundaries to multiples of the granularity, every group at least that large */
+    for (int j = 1; j < ng; ++j) {
+      int b = ((2 * gb[j] + granularity) / (2 * granularity)) * granularity; /* nearest, halves up */
+      int lo = gb[j - 1] + granularity, hi = D - (ng - j) * granularity;
+      gb[j] = b < lo ? lo : b > hi ? hi : b;
+    }
+  }
+  return 0;
+}
+
 int skvq_ref_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -161,6 +161,17 @@ int skvq_ref_calibrate_clip(const skvq_ref_config *cfg, const skvq_ref_buffers *
                             const float *o_ref, const float *alphas, int n_alphas, float *clip_k_out,
                             float *clip_v_out, double *loss_out);
 
+/* Channel reorder (Section 3.1; Algorithm 1 Prologue, get_permutation_matrix).
+ * skvq_ref_channel_stats: stats[Hk][D][2] = (min, max) of every channel of
+ * x (fp16 bits [B][Hk][T][D]) over all tokens.
+ * skvq_ref_calibrate_reorder: KMeans over the channels' (min, max) into D/G
+ * clusters per kv head (the steps are listed in the .c file); perm[Hk][D]:
+ * reordered position p takes channel perm[h][p]; bounds[Hk][D/G + 1]: the
+ * clusters as groups, boundaries at multiples of `granularity`.              */
+void skvq_ref_channel_stats(const uint16_t *x, int B, int Hk, int64_t T, float *stats);
+int skvq_ref_calibrate_reorder(const float *stats, int Hk, int group_size, int granularity,
+                               int max_iter, int32_t *perm, int32_t *bounds);
+
 /* Number of OpenMP threads the decode/prefill loops will use. */
 int skvq_ref_num_threads(void);
 

@@ -82,6 +82,10 @@ def lib():
         _lib.skvq_ref_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                  C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                                  C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_channel_stats.restype = None
+        _lib.skvq_ref_channel_stats.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p]
+        _lib.skvq_ref_calibrate_reorder.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                                    C.c_void_p]
         _lib.skvq_ref_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                     C.c_void_p]
     return _lib
@@ -128,6 +132,27 @@ def encode_group(xp: np.ndarray, alpha: float, levels: int, meta: str = "f32"):
     lib().skvq_ref_encode_group(_ptr(xp), xp.size, float(alpha), int(levels), META_FORMATS[meta],
                                 _ptr(codes), _ptr(scale), _ptr(zero))
     return codes, scale[0], zero[0]
+
+
+def channel_stats(x: np.ndarray) -> np.ndarray:
+    """(min, max) per (kv head, channel) of fp16 x [B][Hk][T][D] -> float32 [Hk][D][2]."""
+    x = np.ascontiguousarray(x)
+    assert x.dtype == np.float16 and x.ndim == 4 and x.shape[3] == HEAD_DIM
+    stats = np.zeros((x.shape[1], HEAD_DIM, 2), np.float32)
+    lib().skvq_ref_channel_stats(_ptr(x), x.shape[0], x.shape[1], x.shape[2], _ptr(stats))
+    return stats
+
+
+def calibrate_reorder(stats: np.ndarray, group_size: int, granularity: int = 1, max_iter: int = 100):
+    """KMeans reorder: returns (perm [Hk][D], bounds [Hk][D/G + 1])."""
+    stats = np.ascontiguousarray(stats, np.float32)
+    hk = stats.shape[0]
+    perm = np.zeros((hk, HEAD_DIM), np.int32)
+    bounds = np.zeros((hk, HEAD_DIM // group_size + 1), np.int32)
+    rc = lib().skvq_ref_calibrate_reorder(_ptr(stats), hk, group_size, granularity, max_iter, _ptr(perm), _ptr(bounds))
+    if rc != 0:
+        raise RuntimeError(f"oracle reorder calibration failed: {rc}")
+    return perm, bounds
 
 
 def levels_of(bits: float) -> int:

@@ -994,3 +994,79 @@ def test_unequal_groups_may_differ_between_kv_heads(oracle):
     c0 = oracle.OracleCache(B, Hq, Hk, G, 2.0, W, 64, pk, pv, clip, clip, group_bounds=bounds[0])
     assert c0.prefill(k, v) == 0
     assert np.array_equal(c0.k_codes[:, 0], c.k_codes[:, 0]) and not np.array_equal(c0.k_codes[:, 1], c.k_codes[:, 1])
+
+
+# ---- channel reorder (Section 3.1; Algorithm 1 Prologue, get_permutation_matrix) ----
+
+def test_channel_stats_are_min_and_max_over_all_tokens(oracle):
+    rng = np.random.default_rng(1400)
+    x = (rng.standard_normal((3, 2, 41, D)) * 10 ** rng.uniform(-1, 1, (1, 2, 1, D))).astype(np.float16)
+    st = oracle.channel_stats(x)
+    assert np.array_equal(st[..., 0], x.min(axis=(0, 2)).astype(np.float32))
+    assert np.array_equal(st[..., 1], x.max(axis=(0, 2)).astype(np.float32))
+
+
+def test_reorder_recovers_planted_channel_families(oracle):
+    """Four families of channels with well separated ranges and unequal sizes: the clusters are
+    the families, listed by range; the permutation lists each family's channels together."""
+    rng = np.random.default_rng(1401)
+    sizes, scales = [16, 48, 24, 40], [8.0, 0.05, 1.0, 0.3]
+    stats = np.zeros((2, D, 2), np.float32)
+    fam = np.zeros((2, D), int)
+    for h in range(2):
+        fam[h] = rng.permutation(np.repeat(np.arange(4), sizes))
+        for ch in range(D):
+            sc = scales[fam[h, ch]] * rng.uniform(0.9, 1.1)
+            stats[h, ch] = (-sc * rng.uniform(0.8, 1.0), sc * rng.uniform(0.8, 1.0))
+    perm, bounds = oracle.calibrate_reorder(stats, 32)
+    by_range = np.argsort(scales)                                  # families from narrow to wide
+    assert np.array_equal(bounds, np.tile(np.concatenate([[0], np.cumsum(np.array(sizes)[by_range])]), (2, 1)))
+    for h in range(2):
+        assert sorted(perm[h]) == list(range(D))
+        for j, f in enumerate(by_range):
+            assert set(perm[h, bounds[h, j]:bounds[h, j + 1]]) == set(np.flatnonzero(fam[h] == f))
+            r = stats[h, perm[h, bounds[h, j]:bounds[h, j + 1]], 1] - stats[h, perm[h, bounds[h, j]:bounds[h, j + 1]], 0]
+            assert np.all(np.diff(r) >= 0)                         # inside a cluster: by range
+    # multiples of 16: every boundary moves to the nearest one, every group keeps 16 positions
+    perm16, bounds16 = oracle.calibrate_reorder(stats, 32, granularity=16)
+    assert np.array_equal(perm16, perm)
+    assert np.all(bounds16 % 16 == 0) and np.all(np.diff(bounds16, axis=1) >= 16)
+    assert np.all(np.abs(bounds16 - bounds) <= 8)
+
+
+def test_reorder_is_lloyds_kmeans_from_the_stated_start(oracle):
+    """Against the library's KMeans (Lloyd, same initial centroids, no restarts) on data without
+    obvious clusters: the same partition of the channels."""
+    from sklearn.cluster import KMeans
+    rng = np.random.default_rng(1402)
+    for G in (32, 64):
+        ng = D // G
+        sc = 10 ** rng.uniform(-1.5, 1.0, D)
+        stats = np.stack([-sc * rng.uniform(0.3, 1.0, D), sc * rng.uniform(0.3, 1.0, D)], axis=1).astype(np.float32)[None]
+        perm, bounds = oracle.calibrate_reorder(stats, G)
+        assert np.all(np.diff(bounds[0]) >= 1)
+        f = stats[0].astype(np.float64)
+        order = np.lexsort((np.arange(D), f[:, 1] - f[:, 0]))
+        init = np.stack([f[order[j * G:(j + 1) * G]].mean(axis=0) for j in range(ng)])
+        km = KMeans(n_clusters=ng, init=init, n_init=1, algorithm="lloyd", max_iter=100, tol=0.0).fit(f)
+        theirs = {frozenset(np.flatnonzero(km.labels_ == j)) for j in range(ng)}
+        ours = {frozenset(perm[0, bounds[0, j]:bounds[0, j + 1]]) for j in range(ng)}
+        assert ours == theirs
+
+
+def test_reorder_lowers_the_quantization_error_on_outlier_channels(oracle):
+    rng = np.random.default_rng(1403)
+    B, Hk, T, G = 1, 2, 64, 32
+    scale = np.where(rng.random((1, Hk, 1, D)) < 0.1, 12.0, 1.0) * 10 ** rng.uniform(-0.3, 0.3, (1, Hk, 1, D))
+    k = (rng.standard_normal((B, Hk, T, D)) * scale).astype(np.float16)
+    perm, bounds = oracle.calibrate_reorder(oracle.channel_stats(k), G, granularity=16)
+    ident = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
+    ones = np.ones((Hk, D // G), np.float32)
+
+    def key_error(pm, gb):
+        c = oracle.OracleCache(B, Hk, Hk, G, 2.0, 1, T, pm, pm, ones, ones, group_bounds=gb)
+        assert c.prefill(k, k) == 0
+        c.perm_v = pm
+        kq, _ = numpy_dequantize(c, T)
+        return ((kq - k[:, :, :T - 1].astype(np.float64)) ** 2).sum()
+    assert key_error(perm, bounds) < 0.5 * key_error(ident, None)
