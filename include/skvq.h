@@ -185,6 +185,30 @@ int skvq_quantize_append(skvq_cache *cache, const void *k_new, const void *v_new
 int skvq_decode_attention(skvq_cache *cache, const void *q, void *out_f32, void *out_f16,
                           void *hip_stream);
 
+/* Section 3.1 / Algorithm 1 Prologue, get_permutation_matrix ("we extract the distribution
+ * feature of each channel and then use the KMeans algorithm to cluster channels with similar
+ * characteristics into the same group"), in two steps.  Offline routines: they allocate and free
+ * their own scratch and synchronise.
+ *
+ * skvq_calibrate_channel_stats: x: DEVICE fp16 [B][Hk][T][D] calibration keys (or values);
+ * stats: HOST [Hk][D][2] = (min, max) of every channel over all B*T tokens.
+ *
+ * skvq_calibrate_reorder: pure host code.  Per kv head, KMeans over the channels' (min, max)
+ * into D/G clusters (the paper names neither feature nor start; this build's): channels
+ * ordered by range max-min (ties: channel index), initial centroid j = mean feature of the j-th
+ * run of G channels in that order; Lloyd iterations in fp64 (nearest centroid by squared
+ * Euclidean distance, ties: the lowest cluster; an empty cluster keeps its centroid) until no
+ * channel moves, at most max_iter; clusters listed by the range of their centroid, ascending,
+ * the channels of a cluster by their own range, ascending (ties: index).
+ * perm: HOST out [Hk][D] (reordered position p takes channel perm[h][p]); bounds: HOST out
+ * [Hk][D/G + 1], the clusters as groups, boundaries rounded to the nearest multiple of
+ * `granularity` with every group keeping at least `granularity` positions (pass 16 to use them
+ * as skvq_config.group_bounds).  group_size must be a multiple of granularity. */
+int skvq_calibrate_channel_stats(const void *x, int32_t batch, int32_t n_kv_heads, int64_t n_tokens,
+                                 float *stats, void *hip_stream);
+int skvq_calibrate_reorder(const float *stats, int32_t n_kv_heads, int32_t group_size,
+                           int32_t granularity, int32_t max_iter, int32_t *perm, int32_t *bounds);
+
 /* Replaces the clip scales alpha of Eq. 2.  clip_k, clip_v: HOST [Hk][D/G], each in (0,1].
  * Ordered after the work already enqueued on hip_stream; synchronises that stream.  Rows
  * already packed keep the codes they were given. */

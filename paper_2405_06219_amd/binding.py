@@ -52,6 +52,9 @@ def lib() -> C.CDLL:
         L.skvq_destroy.argtypes = [C.c_void_p]
         L.skvq_destroy.restype = None
         L.skvq_prefill_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.skvq_calibrate_channel_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
+        L.skvq_calibrate_reorder.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                             C.c_void_p]
         L.skvq_set_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -111,6 +114,30 @@ def skvq_sizes(cfg: skvq_config) -> list[int]:
     if rc != SKVQ_OK:
         raise SkvqError(rc)
     return [int(x) for x in out]
+
+
+def skvq_calibrate_channel_stats(x: torch.Tensor, stream=None) -> np.ndarray:
+    """(min, max) per (kv head, channel) of fp16 x [B][Hk][T][D] on the device -> float32 [Hk][D][2]."""
+    b, hk, T, d = x.shape
+    xp = _dev_ptr(x, torch.float16, (b, hk, T, HEAD_DIM))
+    stats = np.zeros((hk, HEAD_DIM, 2), np.float32)
+    rc = lib().skvq_calibrate_channel_stats(xp, b, hk, T, stats.ctypes.data, _stream_ptr(stream))
+    if rc != SKVQ_OK:
+        raise SkvqError(rc)
+    return stats
+
+
+def skvq_calibrate_reorder(stats: np.ndarray, group_size: int, granularity: int = 16, max_iter: int = 100):
+    """KMeans channel reorder: returns (perm [Hk][D], bounds [Hk][D/G + 1])."""
+    stats = np.ascontiguousarray(stats, np.float32)
+    hk = stats.shape[0]
+    perm = np.zeros((hk, HEAD_DIM), np.int32)
+    bounds = np.zeros((hk, HEAD_DIM // group_size + 1), np.int32)
+    rc = lib().skvq_calibrate_reorder(stats.ctypes.data, hk, group_size, granularity, max_iter, perm.ctypes.data,
+                                      bounds.ctypes.data)
+    if rc != SKVQ_OK:
+        raise SkvqError(rc)
+    return perm, bounds
 
 
 def skvq_validate_config(cfg: skvq_config) -> int:

@@ -282,6 +282,51 @@ static int upload_clips(skvq_cache *c, hipStream_t stream) {
   return e == hipSuccess ? SKVQ_OK : fail_hip(c, e, "clip scale upload");
 }
 
+int skvq_calibrate_channel_stats(const void *x, int32_t batch, int32_t n_kv_heads, int64_t T, float *stats,
+                                 void *stream_) {
+  if (!x || !stats || batch < 1 || n_kv_heads < 1 || T < 1 || ((uintptr_t)x & 15) || batch > 65535 ||
+      n_kv_heads > 65535 || T > (1ll << 40))
+    return SKVQ_ERR_INVALID_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  const long long heads = (long long)batch * n_kv_heads;
+  long long chunks = 4096 / heads;  // about 4096 workgroups over all heads, at least 64 rows each
+  if (chunks > (T + 63) / 64) chunks = (T + 63) / 64;
+  if (chunks < 1) chunks = 1;
+  const size_t n_part = (size_t)heads * chunks * kD * 2;
+  float *d_part = nullptr;
+  if (hipMalloc(&d_part, n_part * sizeof(float)) != hipSuccess) return SKVQ_ERR_HIP;
+  std::vector<float> part(n_part);
+  hipError_t e = launch_channel_stats((const __half *)x, d_part, batch, n_kv_heads, T, (int)chunks, stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(part.data(), d_part, n_part * sizeof(float), hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  (void)hipFree(d_part);
+  if (e != hipSuccess) return SKVQ_ERR_HIP;
+  for (int h = 0; h < n_kv_heads; ++h)
+    for (int ch = 0; ch < kD; ++ch) {
+      float mn = INFINITY, mx = -INFINITY;
+      for (int b = 0; b < batch; ++b)
+        for (long long k = 0; k < chunks; ++k) {
+          const float *p = &part[((((size_t)b * n_kv_heads + h) * chunks + k) * kD + ch) * 2];
+          mn = p[0] < mn ? p[0] : mn;
+          mx = p[1] > mx ? p[1] : mx;
+        }
+      stats[((size_t)h * kD + ch) * 2] = mn;
+      stats[((size_t)h * kD + ch) * 2 + 1] = mx;
+    }
+  return SKVQ_OK;
+}
+
+int skvq_calibrate_reorder(const float *stats, int32_t n_kv_heads, int32_t group_size, int32_t granularity,
+                           int32_t max_iter, int32_t *perm, int32_t *bounds) {
+  if (!stats || !perm || !bounds || n_kv_heads < 1 || max_iter < 0 || granularity < 1) return SKVQ_ERR_INVALID_ARG;
+  if (group_size != 32 && group_size != 64 && group_size != 128) return SKVQ_ERR_UNSUPPORTED;
+  if (group_size % granularity) return SKVQ_ERR_INVALID_ARG;
+  for (size_t x = 0; x < (size_t)n_kv_heads * kD * 2; ++x)
+    if (!std::isfinite(stats[x])) return SKVQ_ERR_INVALID_ARG;
+  return reorder_channels(stats, n_kv_heads, group_size, granularity, max_iter, perm, bounds) ? SKVQ_ERR_INVALID_ARG
+                                                                                               : SKVQ_OK;
+}
+
 int skvq_set_clip(skvq_cache *c, const float *clip_k, const float *clip_v, void *stream) {
   if (!c || !clip_k || !clip_v) return SKVQ_ERR_INVALID_ARG;
   const size_t n = c->clip_k.size();

@@ -79,6 +79,12 @@ hipError_t launch_prefill_attention(const Layout &L, const __half *q, const __ha
 // outputs [B][Hq][D] against ref, over the kv head's query heads and channels
 hipError_t launch_sqerr(const Layout &L, const float *out, const float *ref, float *err, hipStream_t s);
 
+// channel reorder (skvq_calibrate.hip): per-chunk (min, max) of every channel, part[((b*Hk + hk)
+// * chunks + chunk)][D][2]; KMeans over the reduced statistics (host)
+hipError_t launch_channel_stats(const __half *x, float *part, int B, int Hk, long long T, int chunks,
+                                hipStream_t s);
+int reorder_channels(const float *stats, int Hk, int G, int gran, int max_iter, int32_t *perm, int32_t *bounds);
+
 // decode kernels (skvq_decode.hip)
 // n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,

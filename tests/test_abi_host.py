@@ -119,3 +119,30 @@ def test_validation_rejects_bad_configs(B):
     assert not h.value
     assert B.lib().skvq_status_string(B.SKVQ_ERR_CAPACITY) == b"packed region full"
     B.lib().skvq_destroy(None)
+
+
+def test_reorder_calibration_equals_the_oracle(B, oracle):
+    """skvq_calibrate_reorder is host code: the same permutation and boundaries as the oracle's
+    KMeans on the same statistics, for every group size and granularity; bad arguments refused."""
+    rng = np.random.default_rng(77)
+    for trial in range(12):
+        hk = int(rng.integers(1, 5))
+        g = int(rng.choice([32, 64, 128]))
+        gran = int(rng.choice([1, 16, 32]))
+        sc = 10 ** rng.uniform(-1.5, 1.0, (hk, D))
+        if trial % 3 == 0:          # a few outlier channels
+            sc *= np.where(rng.random((hk, D)) < 0.08, 15.0, 1.0)
+        stats = np.stack([-sc * rng.uniform(0.2, 1.0, (hk, D)), sc * rng.uniform(0.2, 1.0, (hk, D))], axis=2).astype(np.float32)
+        perm, bounds = B.skvq_calibrate_reorder(stats, g, gran, 100)
+        rperm, rbounds = oracle.calibrate_reorder(stats, g, gran, 100)
+        assert np.array_equal(perm, rperm) and np.array_equal(bounds, rbounds), (trial, hk, g, gran)
+        assert all(sorted(perm[h]) == list(range(D)) for h in range(hk))
+        assert np.all(bounds % gran == 0) and np.all(np.diff(bounds, axis=1) >= gran)
+    stats = np.zeros((1, D, 2), np.float32)
+    with pytest.raises(B.SkvqError):
+        B.skvq_calibrate_reorder(stats, 48)
+    with pytest.raises(B.SkvqError):
+        B.skvq_calibrate_reorder(stats, 32, 24)
+    stats[0, 3, 1] = np.inf
+    with pytest.raises(B.SkvqError):
+        B.skvq_calibrate_reorder(stats, 32)

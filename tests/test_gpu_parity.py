@@ -574,6 +574,47 @@ def test_clip_calibration_matches_oracle_search(P, G, v_bits, k_bits, Hq, Hk, B)
         gpu.skvq_set_clip(other * 0.0, ones)
 
 
+# ---- channel reorder calibration (Section 3.1; Algorithm 1 Prologue, get_permutation_matrix) ----
+
+@pytest.mark.parametrize("B,Hk,T,G", [(1, 2, 300, 32), (3, 4, 1000, 64), (1, 1, 1, 128), (2, 8, 4099, 32)])
+def test_channel_stats_and_reorder_feed_a_cache_that_matches_the_oracle(P, B, Hk, T, G):
+    """Channel statistics from the GPU equal numpy's; the reorder built on them equals the
+    oracle's; a cache configured with that permutation and those group boundaries is bit-exact
+    with the oracle's and attends within 2e-3."""
+    from oracle import skvq_oracle as O
+    from paper_2405_06219_amd import binding as Bd
+    rng = np.random.default_rng(5000 + T)
+    scale = np.where(rng.random((1, Hk, 1, D)) < 0.1, 12.0, 1.0) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))
+    k = (rng.standard_normal((B, Hk, T, D)) * scale).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * scale[..., ::-1]).astype(np.float16)
+    dev = "cuda:0"
+    kd, vd = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+    sk, sv = Bd.skvq_calibrate_channel_stats(kd), Bd.skvq_calibrate_channel_stats(vd)
+    assert np.array_equal(sk[..., 0], k.min(axis=(0, 2)).astype(np.float32))
+    assert np.array_equal(sk[..., 1], k.max(axis=(0, 2)).astype(np.float32))
+    assert np.array_equal(sv, O.channel_stats(v))
+    pk, bounds = Bd.skvq_calibrate_reorder(sk, G, 16, 100)
+    rpk, rbounds = O.calibrate_reorder(sk, G, 16, 100)
+    assert np.array_equal(pk, rpk) and np.array_equal(bounds, rbounds)
+    pv, _ = Bd.skvq_calibrate_reorder(sv, G, 16, 100)      # values: their own order, the keys' boundaries
+    if T < 40:
+        return
+    W, Hq = 16, 2 * Hk
+    clip = np.full((Hk, D // G), 0.95, np.float32)
+    gb = bounds if G < 128 else None
+    ref = O.OracleCache(B, Hq, Hk, G, 1.5, W, T, pk, pv, clip, clip, fill=0xAB, group_bounds=gb)
+    gpu = Bd.SkvqCache(B, Hq, Hk, G, 1.5, W, T, pk, pv, clip, clip, fill=0xAB, device=dev, group_bounds=gb)
+    assert ref.prefill(k, v) == 0
+    gpu.skvq_prefill_quantize(kd, vd)
+    for name, g, r in zip(["k_codes", "v_codes", "k_meta", "v_meta"], gpu.host_arrays(), ref.arrays()):
+        assert np.array_equal(g.view(np.uint8), r.view(np.uint8)), name
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    out = gpu.skvq_decode_attention(torch.from_numpy(q).to(dev)).cpu().numpy()
+    err = np.abs(out - ref.decode(q)).max()
+    P.log(f"reorder calibration B{B} Hk{Hk} T{T} G{G}: bounds {bounds.tolist()} max abs err {err:.3e}")
+    assert err <= P.TOL
+
+
 def test_random_configurations(P):
     """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
