@@ -406,22 +406,27 @@ int skvq_ref_quantize_append(const skvq_ref_config *c, const skvq_ref_buffers *b
 
 /* ---------------------------------------------------- decode attention --- */
 
-int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *buf,
-                              int64_t T, const uint16_t *q, float *out_f32, uint16_t *out_f16) {
+/* Attention of n_new query tokens per sequence, the last n_new cached tokens being theirs
+ * (Algorithm 1 with l = n_new): query token j sees the cached tokens 0 .. T - n_new + j.
+ * q, out: [B][n_new][Hq][D]. */
+static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, int64_t T,
+                       const uint16_t *q, int n_new, float *out_f32, uint16_t *out_f16) {
   int rc = check_config(c);
   if (rc) return rc;
   if (T <= 0) return -4;
   int64_t W = c->window, S = c->n_sink, first_win = T > W ? T - W : 0;
+  if (n_new < 1 || n_new > T - first_win) return -1; /* the new tokens are all in the window */
   int64_t n_sink = first_win < S ? first_win : S; /* sink tokens present */
   int G = c->group_size, ng = D / G, rep = c->n_q_heads / c->n_kv_heads;
   size_t tcap = (size_t)c->max_quant_tokens, nblk = (tcap + VBT - 1) / VBT;
   size_t bb = v_block_bytes(c->v_levels);
-  int nqh = c->batch * c->n_q_heads;
+  int nqh = c->batch * n_new * c->n_q_heads;
   int fail = 0;
 
 #pragma omp parallel for schedule(dynamic, 1)
   for (int bq = 0; bq < nqh; ++bq) {
-    int b = bq / c->n_q_heads, hq = bq % c->n_q_heads, hk = hq / rep;
+    int hq = bq % c->n_q_heads, j = (bq / c->n_q_heads) % n_new, b = bq / (c->n_q_heads * n_new), hk = hq / rep;
+    int64_t Tv = T - n_new + j + 1; /* tokens this query sees */
     size_t head = (size_t)b * c->n_kv_heads + hk;
     const int32_t *pk = c->perm_k + hk * D, *pv = c->perm_v + hk * D;
     double qf[D], acc[D];
@@ -450,7 +455,7 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       s[a] = (double)c->sm_scale * dot;
     }
     /* scores of sink and ring tokens, original channel order */
-    for (int64_t a = 0; a < T; ++a) {
+    for (int64_t a = 0; a < Tv; ++a) {
       if (a >= n_sink && a < first_win) continue;
       const uint16_t *kw = kwin + (size_t)(a < n_sink ? W + a : a % W) * D;
       double dot = 0.0;
@@ -458,7 +463,7 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
       s[a] = (double)c->sm_scale * dot;
     }
     double m = s[0];
-    for (int64_t t = 1; t < T; ++t)
+    for (int64_t t = 1; t < Tv; ++t)
       if (s[t] > m) m = s[t];
     double denom = 0.0;
     for (int ch = 0; ch < D; ++ch) acc[ch] = 0.0;
@@ -475,7 +480,7 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
         acc[pv[p]] += w * vd;
       }
     }
-    for (int64_t a = 0; a < T; ++a) {
+    for (int64_t a = 0; a < Tv; ++a) {
       if (a >= n_sink && a < first_win) continue;
       double w = exp(s[a] - m);
       denom += w;
@@ -490,6 +495,17 @@ int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *
     free(s);
   }
   return fail ? -5 : 0;
+}
+
+int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                              int64_t T, const uint16_t *q, float *out_f32, uint16_t *out_f16) {
+  return decode_rows(c, buf, T, q, 1, out_f32, out_f16);
+}
+
+int skvq_ref_decode_attention_multi(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                                    int64_t T, const uint16_t *q, int n_new, float *out_f32,
+                                    uint16_t *out_f16) {
+  return decode_rows(c, buf, T, q, n_new, out_f32, out_f16);
 }
 
 /* ---------------------------------------------------- prefill attention --- */

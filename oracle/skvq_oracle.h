@@ -139,6 +139,16 @@ int skvq_ref_decode_attention(const skvq_ref_config *cfg, const skvq_ref_buffers
                               int64_t n_tokens, const uint16_t *q, float *out_f32,
                               uint16_t *out_f16);
 
+/* Several query tokens at once (Algorithm 1 with l = n_new > 1 on a non-empty
+ * cache): the last n_new cached tokens are the new ones (they have been
+ * appended, and all still sit in the fp16 window: n_new <= min(T, W)); query
+ * token j attends over the cached tokens 0 .. T - n_new + j, each in the form
+ * it is stored in now.  q: fp16 bits [B][n_new][Hq][D]; out: [B][n_new][Hq][D].
+ * Returns -1 if n_new is out of range.                                       */
+int skvq_ref_decode_attention_multi(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                                    int64_t n_tokens, const uint16_t *q, int n_new,
+                                    float *out_f32, uint16_t *out_f16);
+
 /* Prefill attention (Section 3.2, phase 1; Algorithm 1 with h = 0 and
  * l = len(prompt)): the attention of the prompt itself is computed on the
  * full-precision K and V, before anything is quantized.  Plain causal softmax

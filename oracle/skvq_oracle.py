@@ -82,6 +82,8 @@ def lib():
         _lib.skvq_ref_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                  C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                                  C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_decode_attention_multi.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int,
+                                                         C.c_void_p, C.c_void_p]
         _lib.skvq_ref_channel_stats.restype = None
         _lib.skvq_ref_channel_stats.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_void_p]
         _lib.skvq_ref_calibrate_reorder.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -253,6 +255,18 @@ class OracleCache:
         if rc != 0:
             raise RuntimeError(f"oracle decode failed: {rc}")
         return (out, out16) if want_f16 else out
+
+    def decode_multi(self, q: np.ndarray) -> np.ndarray:
+        """q [B][n_new][Hq][D]: query token j sees the cached tokens 0 .. T - n_new + j."""
+        b, hq, _ = self.shape
+        assert q.dtype == np.float16 and q.ndim == 4 and q.shape[0] == b and q.shape[2:] == (hq, HEAD_DIM)
+        q = np.ascontiguousarray(q)
+        out = np.zeros(q.shape, np.float32)
+        rc = lib().skvq_ref_decode_attention_multi(C.byref(self.cfg), C.byref(self.buf), self.n_tokens, _ptr(q),
+                                                   q.shape[1], _ptr(out), None)
+        if rc != 0:
+            raise RuntimeError(f"oracle multi-token decode failed: {rc}")
+        return out
 
     def prefill_attention(self, q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
         """Causal attention of the prompt on the fp16 inputs; q [B][Hq][T][D], k/v [B][Hk][T][D]."""

@@ -1070,3 +1070,37 @@ def test_reorder_lowers_the_quantization_error_on_outlier_channels(oracle):
         kq, _ = numpy_dequantize(c, T)
         return ((kq - k[:, :, :T - 1].astype(np.float64)) ** 2).sum()
     assert key_error(perm, bounds) < 0.5 * key_error(ident, None)
+
+
+# ---- several query tokens at once (Algorithm 1 with l > 1 on a non-empty cache) ----
+
+def test_multi_token_decode_is_causal_attention_over_the_stored_cache(oracle):
+    rng = np.random.default_rng(1500)
+    B, Hq, Hk, W, G = 2, 4, 2, 8, 64
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    for T, n_new in ((45, 3), (45, 8), (6, 4), (8, 1)):
+        k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+        v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+        q = rng.standard_normal((B, n_new, Hq, D)).astype(np.float16)
+        c = oracle.OracleCache(B, Hq, Hk, G, 2.0, W, 64, pk, pv, clip, clip)
+        assert c.prefill(k, v) == 0
+        out = c.decode_multi(q)
+        # the last query token is the single-token decode
+        assert np.array_equal(out[:, -1], c.decode(np.ascontiguousarray(q[:, -1])))
+        # every query token: the library's attention over the dequantized cache cut at its own position
+        nq = max(T - W, 0)
+        kq, vq = numpy_dequantize(c, T)
+        kfull = np.concatenate([kq, k[:, :, nq:].astype(np.float64)], axis=2)
+        vfull = np.concatenate([vq, v[:, :, nq:].astype(np.float64)], axis=2)
+        for j in range(n_new):
+            Tv = T - n_new + j + 1
+            ref = sdpa64(np.ascontiguousarray(q[:, j]), kfull[:, :, :Tv], vfull[:, :, :Tv], 1 / np.sqrt(D))
+            assert np.abs(out[:, j] - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+        if T <= W:      # nothing packed: the last rows of the prompt's own causal attention
+            qfull = np.zeros((B, Hq, T, D), np.float16)
+            qfull[:, :, T - n_new:] = q.transpose(0, 2, 1, 3)
+            pa = c.prefill_attention(qfull, k, v)
+            assert np.abs(out - pa[:, :, T - n_new:].transpose(0, 2, 1, 3)).max() < 1e-5
+    with pytest.raises(RuntimeError):       # more new tokens than the window holds
+        c.decode_multi(rng.standard_normal((B, 9, Hq, D)).astype(np.float16))
