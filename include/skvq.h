@@ -90,6 +90,9 @@ typedef struct {
   const float *clip_k;   /* HOST [Hk][D/G]: alpha in (0,1] per (kv head, group), Eq. 2    */
   const float *clip_v;   /* HOST [Hk][D/G]                                                */
   float sm_scale;        /* softmax scale; 0 selects 1/sqrt(D)                            */
+  int32_t max_new_tokens; /* most query tokens per sequence that skvq_decode_attention_multi will be
+                           given (sizes the workspace); 0 or 1: single-token decode only; at most
+                           SKVQ_MAX_NEW_TOKENS                                            */
   const int32_t *group_bounds; /* HOST [Hk][D/G + 1] or NULL.  NULL: uniform groups of G positions.
                            Else (Section 4.1: clustering the channels gives groups of unequal
                            size, G being their average): group g of kv head h covers the
@@ -119,7 +122,7 @@ typedef struct {
  *   k_win     f16 [B][Hk][W+S][D]        rows 0..W-1: the ring, token number a (0-based) sits
  *   v_win     f16 [B][Hk][W+S][D]        in slot a % W; row W+a: sink token a, once it has
  *                                        left the window
- *   workspace f32 [B][Hq][SKVQ_MAX_SPLITS+1][132]  split partials of skvq_decode_attention
+ *   workspace f32 [B][max(max_new_tokens,1)][Hq][SKVQ_MAX_SPLITS+1][132]  split partials of skvq_decode_attention
  *             (running max, sum of weights, two pads, 128 weighted value sums); scratch: any
  *             content is fine before a call and nothing in it survives one
  * All seven must be 16-byte aligned. */
@@ -235,6 +238,18 @@ int skvq_calibrate_clip(skvq_cache *cache, const void *k, const void *v, int64_t
                         const void *q, int32_t n_queries, const void *o_ref, const float *alphas,
                         int32_t n_alphas, float *clip_k_out, float *clip_v_out, double *loss_out,
                         void *hip_stream);
+
+/* Algorithm 1 with l = n_new > 1 on a non-empty cache (several query tokens per sequence in one
+ * call, e.g. to verify speculated tokens): the last n_new cached tokens are the new ones (append
+ * them first; they must all still be in the fp16 window: n_new <= min(T, W)); query token j
+ * attends over the cached tokens 0 .. T - n_new + j, each in the form it is stored in now.
+ * q: DEVICE fp16 [B][n_new][Hq][D]; out_f32: DEVICE fp32 [B][n_new][Hq][D]; out_f16 likewise or
+ * NULL.  n_new = 1 is skvq_decode_attention.  The packed cache is read once per four
+ * (query token, query head) rows of a kv head.
+ * SKVQ_ERR_INVALID_ARG if n_new > max_new_tokens or n_new exceeds the tokens in the window. */
+#define SKVQ_MAX_NEW_TOKENS 64
+int skvq_decode_attention_multi(skvq_cache *cache, const void *q, int32_t n_new, void *out_f32,
+                                void *out_f16, void *hip_stream);
 
 /* Host counters: tokens cached, of which packed, of which in the ring (the rest, at most S,
  * are sink rows).  Any may be NULL. */

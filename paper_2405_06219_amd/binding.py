@@ -29,7 +29,8 @@ class skvq_config(C.Structure):
                 ("v_bits", C.c_int32), ("window", C.c_int32), ("n_sink", C.c_int32),
                 ("meta_format", C.c_int32), ("max_quant_tokens", C.c_int64),
                 ("perm_k", C.c_void_p), ("perm_v", C.c_void_p), ("clip_k", C.c_void_p),
-                ("clip_v", C.c_void_p), ("sm_scale", C.c_float), ("group_bounds", C.c_void_p)]
+                ("clip_v", C.c_void_p), ("sm_scale", C.c_float), ("max_new_tokens", C.c_int32),
+                ("group_bounds", C.c_void_p)]
 
 
 class skvq_buffers(C.Structure):
@@ -55,6 +56,7 @@ def lib() -> C.CDLL:
         L.skvq_calibrate_channel_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         L.skvq_calibrate_reorder.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                              C.c_void_p]
+        L.skvq_decode_attention_multi.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_set_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -91,7 +93,7 @@ def bits_enum(bits: float) -> int:
 
 def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
                 clip_k, clip_v, sm_scale=0.0, k_bits=2.0, head_dim=HEAD_DIM, n_sink=0, meta="f32",
-                group_bounds=None):
+                group_bounds=None, max_new_tokens=0):
     """Returns (skvq_config, keepalive): the numpy arrays the config points to."""
     keep = [np.ascontiguousarray(perm_k, np.int32), np.ascontiguousarray(perm_v, np.int32),
             np.ascontiguousarray(clip_k, np.float32), np.ascontiguousarray(clip_v, np.float32)]
@@ -104,7 +106,8 @@ def make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_qu
             raise ValueError("group_bounds needs head_dim / group_size + 1 entries per kv head")
     cfg = skvq_config(batch, n_q_heads, n_kv_heads, head_dim, group_size, bits_enum(k_bits), bits_enum(v_bits),
                       window, n_sink, META_FORMATS[meta], max_quant_tokens, keep[0].ctypes.data, keep[1].ctypes.data, keep[2].ctypes.data,
-                      keep[3].ctypes.data, float(sm_scale), keep[4].ctypes.data if group_bounds is not None else None)
+                      keep[3].ctypes.data, float(sm_scale), int(max_new_tokens),
+                      keep[4].ctypes.data if group_bounds is not None else None)
     return cfg, keep
 
 
@@ -162,10 +165,11 @@ class SkvqCache:
 
     def __init__(self, batch, n_q_heads, n_kv_heads, group_size, v_bits, window, max_quant_tokens, perm_k, perm_v,
                  clip_k, clip_v, sm_scale=0.0, k_bits=2.0, device="cuda:0", fill=None, n_sink=0,
-                 meta="f32", group_bounds=None):
+                 meta="f32", group_bounds=None, max_new_tokens=0):
         self.cfg, self._keep = make_config(batch, n_q_heads, n_kv_heads, group_size, v_bits, window,
                                            max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale, k_bits,
-                                           n_sink=n_sink, meta=meta, group_bounds=group_bounds)
+                                           n_sink=n_sink, meta=meta, group_bounds=group_bounds,
+                                           max_new_tokens=max_new_tokens)
         self.shape = (batch, n_q_heads, n_kv_heads)
         self.device = torch.device(device)
         self.sizes = skvq_sizes(self.cfg)
@@ -275,6 +279,19 @@ class SkvqCache:
 
     def skvq_set_num_splits(self, n: int):
         self._check(lib().skvq_set_num_splits(self._h, n))
+
+    def skvq_decode_attention_multi(self, q: torch.Tensor, out_f32: torch.Tensor | None = None,
+                                    out_f16: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        """q [B][n_new][Hq][D]: the last n_new cached tokens' queries; returns fp32 [B][n_new][Hq][D]."""
+        b, hq, _ = self.shape
+        n_new = q.shape[1]
+        qp = _dev_ptr(q, torch.float16, (b, n_new, hq, HEAD_DIM))
+        if out_f32 is None:
+            out_f32 = torch.empty((b, n_new, hq, HEAD_DIM), dtype=torch.float32, device=self.device)
+        op = _dev_ptr(out_f32, torch.float32, (b, n_new, hq, HEAD_DIM))
+        o16 = _dev_ptr(out_f16, torch.float16, (b, n_new, hq, HEAD_DIM)) if out_f16 is not None else None
+        self._check(lib().skvq_decode_attention_multi(self._h, qp, n_new, op, o16, _stream_ptr(stream)))
+        return out_f32
 
     # ---- views of the buffers for tests ----
     def host_arrays(self):

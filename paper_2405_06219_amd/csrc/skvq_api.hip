@@ -18,6 +18,7 @@ struct skvq_cache {
   Layout L;
   long long n_tokens = 0;
   int forced_splits = 0;
+  int max_new = 1;  // query tokens per sequence the workspace was sized for
   int n_cus = 256;
   void *dev_consts = nullptr;  // one allocation: perm_k, perm_v, clip_k, clip_v
   std::vector<float> clip_k, clip_v;  // host copies of the clip scales [Hk][NG]
@@ -45,6 +46,7 @@ int check_config(const skvq_config *c) {
       c->meta_format != SKVQ_META_FP8_E4M3)
     return SKVQ_ERR_UNSUPPORTED;
   if (!(c->sm_scale >= 0.0f) || !std::isfinite(c->sm_scale)) return SKVQ_ERR_INVALID_ARG;
+  if (c->max_new_tokens < 0 || c->max_new_tokens > SKVQ_MAX_NEW_TOKENS) return SKVQ_ERR_INVALID_ARG;
   if ((long long)c->window > (1ll << 20) || c->n_sink > (1 << 20) || c->max_quant_tokens > (1ll << 40))
     return SKVQ_ERR_INVALID_ARG;
   if (!c->perm_k || !c->perm_v || !c->clip_k || !c->clip_v) return SKVQ_ERR_INVALID_ARG;
@@ -91,7 +93,8 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
   bytes[4] = heads * ((size_t)c->window + (size_t)c->n_sink) * kD * sizeof(__half);
   bytes[5] = bytes[4];
   // one partial per (sequence, query head, split); the ring is one more split
-  bytes[6] = (size_t)c->batch * c->n_q_heads * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
+  const size_t max_new = c->max_new_tokens > 0 ? (size_t)c->max_new_tokens : 1;
+  bytes[6] = (size_t)c->batch * max_new * c->n_q_heads * (SKVQ_MAX_SPLITS + 1) * kPartialStride * sizeof(float);
 }
 
 int fail_hip(skvq_cache *c, hipError_t e, const char *what) {
@@ -99,7 +102,7 @@ int fail_hip(skvq_cache *c, hipError_t e, const char *what) {
   return SKVQ_ERR_HIP;
 }
 
-int choose_splits(const skvq_cache *c, long long n_quant) {
+int choose_splits(const skvq_cache *c, long long n_quant, int n_new = 1) {
   if (n_quant <= 0) return 0;
   const long long tiles = (n_quant + 63) / 64;  // a split is a whole number of 64-token tiles
   long long s;
@@ -108,7 +111,7 @@ int choose_splits(const skvq_cache *c, long long n_quant) {
   } else {
     // one workgroup per compute unit over all (sequence, kv head) pairs, but every wavefront of
     // a workgroup should have at least two tiles
-    const long long heads = (long long)c->L.B * c->L.Hk * decode_passes(c->L.R);
+    const long long heads = (long long)c->L.B * c->L.Hk * decode_passes(c->L.R * n_new);
     s = c->n_cus / heads;
     const long long cap = tiles / (2 * kMfmaWavesPerGroup);
     if (s > cap) s = cap;
@@ -181,6 +184,7 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
       }
       gmaps[h] |= (unsigned)g << (4 * n);
     }
+  c->max_new = cfg->max_new_tokens > 0 ? cfg->max_new_tokens : 1;
   L.W = cfg->window;
   L.S = cfg->n_sink;
   L.meta_fmt = cfg->meta_format;
@@ -371,7 +375,7 @@ int skvq_calibrate_clip(skvq_cache *c, const void *k, const void *v, int64_t T, 
         if (rc != SKVQ_OK) break;
         e = launch_prefill(L, (const __half *)k, (const __half *)v, T, stream);
         for (int i = 0; i < n_queries && e == hipSuccess; ++i) {
-          e = launch_decode(L, (const __half *)q + (size_t)i * out_n, d_out, nullptr, T, n_splits, stream);
+          e = launch_decode(L, (const __half *)q + (size_t)i * out_n, d_out, nullptr, T, n_splits, 1, stream);
           if (e == hipSuccess)
             e = launch_sqerr(L, d_out, (const float *)o_ref + (size_t)i * out_n,
                              d_err + ((size_t)a * n_queries + i) * slots, stream);
@@ -430,8 +434,20 @@ int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out
   if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
   const long long nq = counts_of(c->n_tokens, c->L.W, c->L.S).n_quant;
   hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16,
-                               c->n_tokens, choose_splits(c, nq), (hipStream_t)stream);
+                               c->n_tokens, choose_splits(c, nq), 1, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention launch");
+  return SKVQ_OK;
+}
+
+int skvq_decode_attention_multi(skvq_cache *c, const void *q, int32_t n_new, void *out_f32, void *out_f16,
+                                void *stream) {
+  if (!c || !q || !out_f32 || n_new < 1) return SKVQ_ERR_INVALID_ARG;
+  if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
+  const Counts n = counts_of(c->n_tokens, c->L.W, c->L.S);
+  if (n_new > c->max_new || n_new > n.n_win) return SKVQ_ERR_INVALID_ARG;
+  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, c->n_tokens,
+                               choose_splits(c, n.n_quant, n_new), n_new, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention_multi launch");
   return SKVQ_OK;
 }
 

@@ -31,12 +31,13 @@ __device__ __forceinline__ float wave_sum(float v) {
 // wavefront 0 turns the (m_i, l_i) into weights, thread (channel, slice) adds every eighth
 // partial.
 __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict__ out_f32,
-                                                     __half *__restrict__ out_f16, int n_all) {
+                                                     __half *__restrict__ out_f16, int n_all, int n_heads) {
   __shared__ float wts[SKVQ_MAX_SPLITS + 1];
   __shared__ float den_s;
   __shared__ float red[8][kD];
   const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const float *base = L.workspace + ((long long)b * L.Hq + hq) * (SKVQ_MAX_SPLITS + 1) * kPartialStride;
+  // n_heads = query tokens x query heads per sequence; hq counts (token, head) pairs
+  const float *base = L.workspace + ((long long)b * n_heads + hq) * (SKVQ_MAX_SPLITS + 1) * kPartialStride;
   const int ch = tid & 127, sl = tid >> 7;
   // the first 32 partials' values are requested before their weights are known: one round trip
   float pre[4];
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
 #pragma unroll
     for (int k = 0; k < 8; ++k) tot += red[k][tid];
     const float o = tot / den_s;
-    const long long idx = ((long long)b * L.Hq + hq) * kD + tid;
+    const long long idx = ((long long)b * n_heads + hq) * kD + tid;
     out_f32[idx] = o;
     if (out_f16) out_f16[idx] = __float2half_rn(o);
   }
@@ -96,15 +97,17 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
 }  // namespace
 
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16, long long T,
-                         int n_splits, hipStream_t s) {
+                         int n_splits, int n_new, hipStream_t s) {
   const Counts n = counts_of(T, L.W, L.S);
-  if (L.Hk > 65535 || L.B > 65535 || L.Hq > 65535) return hipErrorInvalidValue;
+  if (L.Hk > 65535 || L.B > 65535 || (long long)L.Hq * n_new > 65535) return hipErrorInvalidValue;
+  if (n_new < 1 || n_new > n.n_win) return hipErrorInvalidValue;  // the new tokens are all in the window
   if (n_splits > SKVQ_MAX_SPLITS || (n.n_quant > 0 && n_splits < 1)) return hipErrorInvalidValue;
   if (n_splits < 1) n_splits = 1;  // nothing packed yet: one chunk, fp16 tokens only
-  hipError_t e = launch_decode_mfma(L, q, T, n.n_quant, (int)n.n_sink, n_splits, s);
+  hipError_t e = launch_decode_mfma(L, q, T, n.n_quant, (int)n.n_sink, n_splits, n_new, s);
   if (e != hipSuccess) return e;
   // the fp16 tokens are folded into the chunks' partials
-  hipLaunchKernelGGL(merge_kernel, dim3(L.Hq, L.B), dim3(1024), 0, s, L, out_f32, out_f16, n_splits);
+  hipLaunchKernelGGL(merge_kernel, dim3(L.Hq * n_new, L.B), dim3(1024), 0, s, L, out_f32, out_f16, n_splits,
+                     L.Hq * n_new);
   return hipGetLastError();
 }
 

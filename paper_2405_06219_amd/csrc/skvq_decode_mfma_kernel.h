@@ -302,11 +302,14 @@ struct RingData {
 template <int R, int KL, int VL, int META, int NG, bool UNEQ>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
-                                                                  int n_splits, int passes) {
+                                                                  int n_splits, int passes, int n_new) {
   // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
   // head with more than four (or with three) query heads is served by `passes` workgroups per
   // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
   // heads are computed with a zero query and not stored).
+  //   With n_new > 1 query tokens per sequence (the last n_new cached tokens are theirs) the rows
+  // of a kv head are its L.R query heads times the n_new tokens, row x = token x / L.R, head
+  // x % L.R; query token j does not see the fp16 tokens after its own.
   //   Workgroup sp owns an even share of the packed 64-token tiles of
   // its (sequence, kv head), dealt to its wavefronts round robin, and the ring slices
   // j = sp (mod n_splits), dealt the same way.
@@ -415,8 +418,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   //      wait for them and not for the two tiles of packed data behind them. ----
   SKVQ_STAMP(4);
   __half2 q2 = __floats2half2_rn(0.f, 0.f);
-  if (tid < 64 * R && head0 + (tid >> 6) < L.R)
-    q2 = reinterpret_cast<const __half2 *>(q + ((long long)b * L.Hq + hk * L.R + head0 + (tid >> 6)) * kD)[lane];
+  const int n_rows = n_new * L.R;  // rows of this kv head: (query token, query head)
+  // row x of the kv head -> index of its (sequence, query token, query head) in q, the partials and the output
+  auto row_index = [&](int x) {
+    const int j = n_new == 1 ? 0 : x / L.R;  // (no division on the single-token path)
+    return ((long long)b * n_new + j) * L.Hq + hk * L.R + (x - j * L.R);
+  };
+  if (tid < 64 * R && head0 + (tid >> 6) < n_rows)
+    q2 = reinterpret_cast<const __half2 *>(q + row_index(head0 + (tid >> 6)) * kD)[lane];
   const int pk = L.perm_k[hk * kD + (tid & 127)];
   const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
   RingData ring = {};
@@ -527,9 +536,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     float rm[R], rl[R], ro[R][2];  // reference, sum of weights, outputs
 #pragma unroll
     for (int r = 0; r < R; ++r) rm[r] = -INFINITY, rl[r] = 0.f, ro[r][0] = ro[r][1] = 0.f;
+    // query token j sees the fp16 tokens up to its own, index n_fp - n_new + j (all of them if n_new = 1)
+    int ring_last[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) ring_last[r] = n_new == 1 ? n_fp - 1 : n_fp - n_new + (head0 + r) / L.R;
     auto ring_slice = [&](const RingData &rd, const int slice) {
       const int tk = lane >> 4, pc = lane & 15;  // token of the slice, 8-channel piece of its row
-      const bool valid = slice * kRingSlice + tk < n_fp;
+      const int tok = slice * kRingSlice + tk;  // index among the fp16 tokens
+      const bool valid = tok < n_fp;
       const half8_t x = __builtin_bit_cast(half8_t, rd.k);
       float p[R][kRingSlice];  // the four tokens' weights, wave-uniform
 #pragma unroll
@@ -548,15 +562,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         s += row_move<kQuadSwap2>(s);
         s += row_move<kRowHalfMirror>(s);
         s += row_move<kRowMirror>(s);  // all sixteen lanes of a token now hold its score
-        s = valid ? c * s : -INFINITY;
+        s = valid && tok <= ring_last[r] ? c * s : -INFINITY;
         float sk[kRingSlice];  // the four tokens' scores, read from one lane of each row
 #pragma unroll
         for (int k = 0; k < kRingSlice; ++k)
           sk[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 16 * k));
         const float mnew = fmaxf(rm[r], fmaxf(fmaxf(sk[0], sk[1]), fmaxf(sk[2], sk[3])));
-        const float f = fast_exp2(rm[r] - mnew);  // 0 for the first slice
+        // (a query token of a multi-token call may see none of a slice's tokens, nor of the earlier
+        // ones: then everything stays zero; -inf minus -inf must not be formed)
+        const float mref = mnew == -INFINITY ? 0.f : mnew;
+        const float f = fast_exp2(rm[r] - mref);  // 0 for the first slice
 #pragma unroll
-        for (int k = 0; k < kRingSlice; ++k) p[r][k] = fast_exp2(sk[k] - mnew);  // 0 for tokens past the end
+        for (int k = 0; k < kRingSlice; ++k) p[r][k] = fast_exp2(sk[k] - mref);  // 0 for tokens past the end
         rl[r] = rl[r] * f + (p[r][0] + p[r][1]) + (p[r][2] + p[r][3]);
         ro[r][0] *= f;
         ro[r][1] *= f;
@@ -884,7 +901,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   __syncthreads();
   SKVQ_STAMP(8);
   SKVQ_STAMP(9);
-  if (tid < R * kD && head0 + (tid >> 7) < L.R) {
+  if (tid < R * kD && head0 + (tid >> 7) < n_rows) {
     // thread (head r, position p): the chunk's reference m* = max over waves and ring slices,
     // each one's factor 2^(m - m*), the sums that need no channel (every thread of a head
     // computes the same ones: cheaper than another exchange through LDS), its channel's sum
@@ -908,7 +925,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
     }
     float *part =
-        L.workspace + (((long long)b * L.Hq + hk * L.R + head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
+        L.workspace + (row_index(head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
     part[4 + ch] = num;
     if (p == 0) {
       part[0] = m;
@@ -933,15 +950,17 @@ extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
 // The launcher of the kernels with KL-level keys and VL-level values.
 template <int KL, int VL>
 hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
-                                  int n_splits, hipStream_t s) {
+                                  int n_splits, int n_new, hipStream_t s) {
   if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
-  const int passes = decode_passes(L.R), rk = L.R == 1 ? 1 : L.R == 2 ? 2 : 4;
-  if ((long long)L.Hk * passes > 65535 || L.R > 8) return hipErrorInvalidValue;
+  if (n_new < 1 || n_new > SKVQ_MAX_NEW_TOKENS || L.R > 8) return hipErrorInvalidValue;
+  const int n_rows = n_new * L.R;
+  const int passes = decode_passes(n_rows), rk = n_rows == 1 ? 1 : n_rows == 2 ? 2 : 4;
+  if ((long long)L.Hk * passes > 65535) return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
 #define SKVQ_LAUNCH(RR, MM, GG, UU) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new)
 #define SKVQ_LAUNCH_NG(RR, MM)                                                                   \
   switch (L.NG) {                                                                                \
     case 1: SKVQ_LAUNCH(RR, MM, 1, false); break;                                                \

@@ -87,16 +87,18 @@ int reorder_channels(const float *stats, int Hk, int G, int gran, int max_iter, 
 
 // decode kernels (skvq_decode.hip)
 // n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).
+// n_new: query tokens per sequence (q, out: [B][n_new][Hq][D]); the last n_new cached tokens are theirs.
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,
-                         long long T, int n_splits, hipStream_t s);
+                         long long T, int n_splits, int n_new, hipStream_t s);
 
 // Matrix-core chunk kernel (skvq_decode_mfma.hip): packed chunks and the fp16 tokens (n_sink sink
 // rows, then the window's T - nq - n_sink ring tokens); writes partials 0..n_splits-1 (n_splits
 // >= 1 even when nothing is packed yet).  A workgroup serves 1, 2 or 4 query heads of a kv head;
 // kv heads with 5..8 query heads are read by two workgroups per chunk.
-inline int decode_passes(int R) { return R > 4 ? 2 : 1; }
+// (n_rows = query heads per kv head x query tokens)
+inline int decode_passes(int n_rows) { return n_rows > 4 ? (n_rows + 3) / 4 : 1; }
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
-                              int n_splits, hipStream_t s);
+                              int n_splits, int n_new, hipStream_t s);
 constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel
 
 }  // namespace skvq

@@ -24,7 +24,7 @@ def log(msg: str):
 
 class Pair:
     def __init__(self, w: synth.Workload, max_quant_tokens: int, perm_k, perm_v, clip_k, clip_v, sm_scale=0.0,
-                 fill=0xAB, device="cuda:0", n_sink=0, meta="f32", group_bounds=None):
+                 fill=0xAB, device="cuda:0", n_sink=0, meta="f32", group_bounds=None, max_new_tokens=0):
         self.w = w
         osm = sm_scale if sm_scale else None
         self.ref = O.OracleCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
@@ -33,7 +33,7 @@ class Pair:
         self.gpu = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                                max_quant_tokens, perm_k, perm_v, clip_k, clip_v, sm_scale=sm_scale, fill=fill,
                                device=device, n_sink=n_sink, meta=meta, k_bits=w.k_bits,
-                               group_bounds=group_bounds)
+                               group_bounds=group_bounds, max_new_tokens=max_new_tokens)
         self.device = device
 
     def prefill(self, k: np.ndarray, v: np.ndarray):

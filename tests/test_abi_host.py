@@ -85,6 +85,8 @@ def test_validation_rejects_bad_configs(B):
         (dict(n_q_heads=30), B.SKVQ_ERR_INVALID_ARG),
         (dict(window=0), B.SKVQ_ERR_INVALID_ARG),
         (dict(n_sink=-1), B.SKVQ_ERR_INVALID_ARG),
+        (dict(max_new_tokens=-1), B.SKVQ_ERR_INVALID_ARG),
+        (dict(max_new_tokens=65), B.SKVQ_ERR_INVALID_ARG),
         (dict(max_quant_tokens=0), B.SKVQ_ERR_INVALID_ARG),
         (dict(batch=0), B.SKVQ_ERR_INVALID_ARG),
         (dict(head_dim=64), B.SKVQ_ERR_UNSUPPORTED),
@@ -107,6 +109,9 @@ def test_validation_rejects_bad_configs(B):
     good, keep2 = cfg_for(B, group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[0, 16, 32, 48, 128])
     uniform, keep3 = cfg_for(B, group_size=32)
     assert B.skvq_validate_config(good) == B.SKVQ_OK and B.skvq_sizes(good) == B.skvq_sizes(uniform)
+    # the workspace grows with the number of query tokens per call
+    multi, keep4 = cfg_for(B, max_new_tokens=4)
+    assert B.skvq_sizes(multi)[6] == 4 * B.skvq_sizes(ok)[6] and B.skvq_sizes(multi)[:6] == B.skvq_sizes(ok)[:6]
     assert B.lib().skvq_validate_config(None) == B.SKVQ_ERR_INVALID_ARG
     # create refuses a bad config and null / misaligned buffers before touching the device
     cfg, keep = cfg_for(B, window=0)

@@ -615,6 +615,47 @@ def test_channel_stats_and_reorder_feed_a_cache_that_matches_the_oracle(P, B, Hk
     assert err <= P.TOL
 
 
+# ---- several query tokens at once (Algorithm 1 with l > 1 on a non-empty cache) ----
+MULTI_CASES = [
+    (small("multi_mha_t15", context=1500), 3, 0, "f32"),
+    (small("multi_gqa4_v2", n_q_heads=8, n_kv_heads=2, v_bits=2.0, context=999, batch=2), 4, 5, "f32"),
+    (small("multi_gqa8_g32_k4v4", k_bits=4.0, v_bits=4.0, n_q_heads=8, n_kv_heads=1, group_size=32, context=700, window=16), 7, 0, "e4m3"),
+    (small("multi_gqa3_k3v3_g64", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=2, group_size=64, context=450), 2, 1, "f16"),
+    (small("multi_window_only", context=40), 16, 0, "f32"),
+    (small("multi_whole_window", window=8, context=300), 8, 0, "f32"),
+]
+
+
+@pytest.mark.parametrize("w,n_new,S,meta", MULTI_CASES, ids=lambda x: x.name if hasattr(x, "name") else None)
+def test_multi_token_decode_matches_oracle(P, w, n_new, S, meta):
+    """The last n_new cached tokens' queries in one call: every row within 2e-3 of the oracle,
+    the last row equal to the single-token call, and the split count must not matter."""
+    print("case", w, n_new, S, meta, flush=True)
+    pair, k, v, q1 = P.make_pair(w, extra_tokens=n_new + 1, n_sink=S, meta=meta, max_new_tokens=n_new)
+    pair.prefill(k, v)
+    for s in range(n_new):
+        pair.append(*synth.make_new_token(w, s))
+    rng = np.random.default_rng(w.seed + n_new)
+    q = rng.standard_normal((w.batch, n_new, w.n_q_heads, D)).astype(np.float16)
+    ref = pair.ref.decode_multi(q)
+    qd = torch.from_numpy(q).to(pair.device)
+    for splits in (0, 1, 5):
+        pair.gpu.skvq_set_num_splits(splits)
+        o16 = torch.empty(q.shape, dtype=torch.float16, device=pair.device)
+        out = pair.gpu.skvq_decode_attention_multi(qd, out_f16=o16).cpu().numpy()
+        err = np.abs(out - ref).max()
+        P.log(f"multi-token decode {w.name} n_new={n_new} splits={splits}: max abs err {err:.3e}")
+        assert err <= P.TOL
+        assert np.array_equal(o16.cpu().numpy(), out.astype(np.float16))
+    pair.gpu.skvq_set_num_splits(0)
+    single = pair.gpu.skvq_decode_attention(qd[:, -1].contiguous()).cpu().numpy()
+    assert np.abs(single - out[:, -1]).max() <= 2e-4     # other row grouping, other summation order
+    from paper_2405_06219_amd import binding as Bd
+    with pytest.raises(Bd.SkvqError):        # more query tokens than the workspace was sized for
+        pair.gpu.skvq_decode_attention_multi(torch.zeros((w.batch, n_new + 1, w.n_q_heads, D), dtype=torch.float16,
+                                                         device=pair.device))
+
+
 def test_random_configurations(P):
     """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
