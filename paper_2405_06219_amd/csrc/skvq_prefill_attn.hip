@@ -5,8 +5,10 @@
 //
 // One workgroup of 8 wavefronts owns 256 consecutive queries of one (sequence, query head); a
 // wavefront owns 32 of them (every tile of K and V that the workgroup fetches serves 256 queries:
-// at 128 the kernel was bound by the K/V traffic from L2 and HBM).  Keys and values arrive in tiles of 64 tokens, staged in LDS (K as it
-// is, V transposed so that the keys of one channel are neighbours), double buffered: while a tile
+// at 128 the kernel was bound by the K/V traffic from L2 and HBM).  Keys and values arrive in
+// tiles of 64 tokens, staged in LDS (K as it is, V transposed so that the keys of one channel are
+// neighbours, in an order that lets a lane fetch each operand of the value product with one
+// 16-byte read and spreads the transposing stores over the banks), double buffered: while a tile
 // is computed the next one travels from HBM into registers.  Per wavefront and tile:
 //   S^T[key][query]  by 16 v_mfma_f32_32x32x16_f16: A = K tile (row = key, 16 channels a step),
 //        B = the wavefront's queries, held in registers for the whole kernel.  Computing the
@@ -37,7 +39,7 @@ constexpr int kQBlock = 256;    // queries per workgroup (32 per wavefront)
 constexpr int kThreads = 2 * kQBlock;
 constexpr int kKTile = 64;      // keys per tile
 constexpr int kKStride = 136;   // halves per K row in LDS (272 B: 16-byte aligned, rows on different banks)
-constexpr int kVStride = 68;    // halves per V^T row in LDS (136 B: 8-byte aligned)
+constexpr int kVStride = 72;    // halves per V^T row in LDS (144 B: 16-byte aligned, rows on different banks)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kSlack = 8.0f;  // weights may reach 2^8 before the running reference moves
 
@@ -50,7 +52,7 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 
 struct Smem {
   _Float16 k[2][kKTile][kKStride];  // [buffer][key][channel]
-  _Float16 vt[2][kD][kVStride];     // [buffer][channel][key]
+  _Float16 vt[2][kD][kVStride];     // [buffer][channel][key, in the order that store_v describes]
 };
 
 // What one thread carries of a tile between HBM and LDS: 2 pieces of 8 channels of K (keys
@@ -121,12 +123,17 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
   };
   auto store_v = [&](const Stage &st, int buf) {
     const int kq = tid >> 4, dc = tid & 15;
+    // Inside a row the 64 keys sit in eight 16-byte cells: cell 2 (key / 16) + (key / 4) % 2 holds
+    // keys 16 g + 4 h + {0..3} and 16 g + 8 + 4 h + {0..3}, the eight that one lane feeds to a step
+    // of the value product, and the cells of a row are permuted by the row's channel block
+    // (cell ^ 2 blk), which spreads the transposing stores of a wavefront over the banks
+    const int kcol = 8 * ((2 * (kq >> 3) + ((kq >> 1) & 1)) ^ (2 * (dc >> 2))) + 4 * ((kq >> 2) & 1) + 2 * (kq & 1);
     // transpose the 2 x 8 block: channel 8 dc + d gets its two keys as one dword
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const unsigned a0 = st.v[0][j], a1 = st.v[1][j];
-      *reinterpret_cast<unsigned *>(&sm.vt[buf][8 * dc + 2 * j][2 * kq]) = __builtin_amdgcn_perm(a1, a0, 0x05040100u);
-      *reinterpret_cast<unsigned *>(&sm.vt[buf][8 * dc + 2 * j + 1][2 * kq]) = __builtin_amdgcn_perm(a1, a0, 0x07060302u);
+      *reinterpret_cast<unsigned *>(&sm.vt[buf][8 * dc + 2 * j][kcol]) = __builtin_amdgcn_perm(a1, a0, 0x05040100u);
+      *reinterpret_cast<unsigned *>(&sm.vt[buf][8 * dc + 2 * j + 1][kcol]) = __builtin_amdgcn_perm(a1, a0, 0x07060302u);
     }
   };
 
@@ -249,23 +256,23 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
       l += psum;
       // ---- values: the lane's slot e of step t is key 16 t + 8 (e/4) + 4 h + e%4 ----
       auto v_operand = [&](int t, int blk) {
-        const uint2_t lo = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 4 * h]);
-        const uint2_t hi = *reinterpret_cast<const uint2_t *>(&sm.vt[buf][32 * blk + col][16 * t + 8 + 4 * h]);
-        return __builtin_bit_cast(half8_t, uint4_t{lo.x, lo.y, hi.x, hi.y});
+        return *reinterpret_cast<const half8_t *>(&sm.vt[buf][32 * blk + col][16 * (t ^ blk) + 8 * h]);
       };
-      half8_t va[2][4];  // the A operands of one step, requested one step ahead
+      half8_t va[2][2];  // the A operands of half a step (two channel blocks), requested half a step ahead
 #pragma unroll
-      for (int blk = 0; blk < 4; ++blk) va[0][blk] = v_operand(0, blk);
+      for (int i = 0; i < 2; ++i) va[0][i] = v_operand(0, i);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        if (t + 1 < 4) {
+      for (int hs = 0; hs < 8; ++hs) {  // half step: step hs / 2, channel blocks 2 (hs % 2), + 1
+        if (hs + 1 < 8) {
 #pragma unroll
-          for (int blk = 0; blk < 4; ++blk) va[(t + 1) & 1][blk] = v_operand(t + 1, blk);
+          for (int i = 0; i < 2; ++i) va[(hs + 1) & 1][i] = v_operand((hs + 1) >> 1, 2 * ((hs + 1) & 1) + i);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
-          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[t & 1][blk], p[t], o[blk], 0, 0, 0);
+        for (int i = 0; i < 2; ++i) {
+          const int blk = 2 * (hs & 1) + i;
+          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[hs & 1][i], p[hs >> 1], o[blk], 0, 0, 0);
+        }
       }
     }
     // K of tile + 2 replaces K of tile (read during the previous trip), V of tile + 1 replaces V
