@@ -229,7 +229,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int x = 0; x < 16; x += 2) mloc = max3(mloc, s[kb][x], s[kb][x + 1]);
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * c;  // c >= 0
+      {  // the other half of the query's scores is 32 lanes away: one swap of register halves
+        // (lanes 32-63 of the first register trade places with lanes 0-31 of the second)
+        float ma = mloc, mb = mloc;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(ma), "+v"(mb));
+        mloc = max3(ma, mb, mb) * c;  // c >= 0
+      }
       if (__any(mloc > m + kSlack)) {
         const float m_new = fmaxf(m, mloc);
         const float alpha = exp2f(m - m_new);  // 0 at the first tile
