@@ -514,45 +514,71 @@ int skvq_ref_decode_attention_multi(const skvq_ref_config *c, const skvq_ref_buf
  * cache" -- Algorithm 1 with h = 0, l = len(prompt): plain causal softmax
  * attention on the fp16 inputs, original channel order (Eq. 1 with identity
  * permutations), query t seeing keys 0..t. */
+/* One row of the prompt's attention: query `t` of (sequence b, query head hq) over keys 0..t.
+ * Returns nonzero when memory runs out. */
+static int prefill_attention_row(const skvq_ref_config *c, const uint16_t *q, const uint16_t *k,
+                                 const uint16_t *v, int64_t T, int b, int hq, int64_t t, float *out_row) {
+  int hk = hq / (c->n_q_heads / c->n_kv_heads);
+  const uint16_t *qr = q + (((size_t)b * c->n_q_heads + hq) * (size_t)T + (size_t)t) * D;
+  const uint16_t *kh = k + ((size_t)b * c->n_kv_heads + hk) * (size_t)T * D;
+  const uint16_t *vh = v + ((size_t)b * c->n_kv_heads + hk) * (size_t)T * D;
+  double qf[D], acc[D];
+  for (int ch = 0; ch < D; ++ch) qf[ch] = skvq_ref_half_to_float(qr[ch]);
+  double *s = (double *)malloc(sizeof(double) * (size_t)(t + 1));
+  if (!s) return 1;
+  double m = -INFINITY;
+  for (int64_t a = 0; a <= t; ++a) {
+    double dot = 0.0;
+    for (int ch = 0; ch < D; ++ch) dot += qf[ch] * (double)skvq_ref_half_to_float(kh[(size_t)a * D + ch]);
+    s[a] = (double)c->sm_scale * dot;
+    if (s[a] > m) m = s[a];
+  }
+  double denom = 0.0;
+  for (int ch = 0; ch < D; ++ch) acc[ch] = 0.0;
+  for (int64_t a = 0; a <= t; ++a) {
+    double w = exp(s[a] - m);
+    denom += w;
+    for (int ch = 0; ch < D; ++ch) acc[ch] += w * (double)skvq_ref_half_to_float(vh[(size_t)a * D + ch]);
+  }
+  for (int ch = 0; ch < D; ++ch) out_row[ch] = (float)(acc[ch] / denom);
+  free(s);
+  return 0;
+}
+
 int skvq_ref_prefill_attention(const skvq_ref_config *c, const uint16_t *q, const uint16_t *k,
                                const uint16_t *v, int64_t T, float *out_f32) {
   int rc = check_config(c);
   if (rc) return rc;
   if (T < 0) return -1;
-  int rep = c->n_q_heads / c->n_kv_heads;
   int64_t rows = (int64_t)c->batch * c->n_q_heads * T;
   int fail = 0;
 #pragma omp parallel for schedule(dynamic, 16)
   for (int64_t row = 0; row < rows; ++row) {
     int64_t t = row % T, bq = row / T;
-    int b = (int)(bq / c->n_q_heads), hq = (int)(bq % c->n_q_heads), hk = hq / rep;
-    const uint16_t *qr = q + (size_t)row * D;
-    const uint16_t *kh = k + ((size_t)b * c->n_kv_heads + hk) * (size_t)T * D;
-    const uint16_t *vh = v + ((size_t)b * c->n_kv_heads + hk) * (size_t)T * D;
-    double qf[D], acc[D];
-    for (int ch = 0; ch < D; ++ch) qf[ch] = skvq_ref_half_to_float(qr[ch]);
-    double *s = (double *)malloc(sizeof(double) * (size_t)(t + 1));
-    if (!s) {
-      fail = 1;
-      continue;
-    }
-    double m = -INFINITY;
-    for (int64_t a = 0; a <= t; ++a) {
-      double dot = 0.0;
-      for (int ch = 0; ch < D; ++ch) dot += qf[ch] * (double)skvq_ref_half_to_float(kh[(size_t)a * D + ch]);
-      s[a] = (double)c->sm_scale * dot;
-      if (s[a] > m) m = s[a];
-    }
-    double denom = 0.0;
-    for (int ch = 0; ch < D; ++ch) acc[ch] = 0.0;
-    for (int64_t a = 0; a <= t; ++a) {
-      double w = exp(s[a] - m);
-      denom += w;
-      for (int ch = 0; ch < D; ++ch) acc[ch] += w * (double)skvq_ref_half_to_float(vh[(size_t)a * D + ch]);
-    }
-    for (int ch = 0; ch < D; ++ch) out_f32[(size_t)row * D + ch] = (float)(acc[ch] / denom);
-    free(s);
+    int b = (int)(bq / c->n_q_heads), hq = (int)(bq % c->n_q_heads);
+    if (prefill_attention_row(c, q, k, v, T, b, hq, t, out_f32 + (size_t)row * D)) fail = 1;
   }
+  return fail ? -5 : 0;
+}
+
+/* The same for chosen rows only (for prompts too long to compute whole): row i is query
+ * rows[3 i + 2] of (sequence rows[3 i], query head rows[3 i + 1]); out_f32 [n_rows][D]. */
+int skvq_ref_prefill_attention_rows(const skvq_ref_config *c, const uint16_t *q, const uint16_t *k,
+                                    const uint16_t *v, int64_t T, const int64_t *rows, int64_t n_rows,
+                                    float *out_f32) {
+  int rc = check_config(c);
+  if (rc) return rc;
+  if (T < 0 || n_rows < 0) return -1;
+  for (int64_t i = 0; i < n_rows; ++i)
+    if (rows[3 * i] < 0 || rows[3 * i] >= c->batch || rows[3 * i + 1] < 0 || rows[3 * i + 1] >= c->n_q_heads ||
+        rows[3 * i + 2] < 0 || rows[3 * i + 2] >= T)
+      return -1;
+  int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < n_rows; ++i)
+    if (prefill_attention_row(c, q, k, v, T, (int)rows[3 * i], (int)rows[3 * i + 1], rows[3 * i + 2],
+                              out_f32 + (size_t)i * D))
+      fail = 1;
   return fail ? -5 : 0;
 }
 

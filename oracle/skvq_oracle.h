@@ -156,6 +156,12 @@ int skvq_ref_decode_attention_multi(const skvq_ref_config *cfg, const skvq_ref_b
  * q: fp16 bits [B][Hq][T][D]; k, v: [B][Hk][T][D]; out_f32: [B][Hq][T][D].   */
 int skvq_ref_prefill_attention(const skvq_ref_config *cfg, const uint16_t *q, const uint16_t *k,
                                const uint16_t *v, int64_t T, float *out_f32);
+/* The same for chosen rows only (prompts too long to compute whole): row i of
+ * out_f32 [n_rows][D] is query rows[3i+2] of sequence rows[3i], query head
+ * rows[3i+1].  Returns -1 for an index out of range.                          */
+int skvq_ref_prefill_attention_rows(const skvq_ref_config *cfg, const uint16_t *q, const uint16_t *k,
+                                    const uint16_t *v, int64_t T, const int64_t *rows, int64_t n_rows,
+                                    float *out_f32);
 
 /* Clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping): one pass
  * of coordinate descent over the candidate grid `alphas` (keys, then values;

@@ -90,6 +90,8 @@ def lib():
                                                     C.c_void_p]
         _lib.skvq_ref_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                     C.c_void_p]
+        _lib.skvq_ref_prefill_attention_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                                         C.c_void_p, C.c_int64, C.c_void_p]
     return _lib
 
 
@@ -279,6 +281,22 @@ class OracleCache:
         rc = lib().skvq_ref_prefill_attention(C.byref(self.cfg), _ptr(q), _ptr(k), _ptr(v), T, _ptr(out))
         if rc != 0:
             raise RuntimeError(f"oracle prefill attention failed: {rc}")
+        return out
+
+    def prefill_attention_rows(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, rows) -> np.ndarray:
+        """Chosen rows of the prompt's causal attention: rows is a list of (sequence, query head, query);
+        returns [len(rows)][D]."""
+        b, hq, hk = self.shape
+        T = q.shape[2]
+        assert q.dtype == k.dtype == v.dtype == np.float16
+        assert q.shape == (b, hq, T, HEAD_DIM) and k.shape == v.shape == (b, hk, T, HEAD_DIM)
+        q, k, v = (np.ascontiguousarray(x) for x in (q, k, v))
+        rows = np.ascontiguousarray(np.asarray(rows, np.int64).reshape(-1, 3))
+        out = np.zeros((rows.shape[0], HEAD_DIM), np.float32)
+        rc = lib().skvq_ref_prefill_attention_rows(C.byref(self.cfg), _ptr(q), _ptr(k), _ptr(v), T, _ptr(rows),
+                                                   rows.shape[0], _ptr(out))
+        if rc != 0:
+            raise RuntimeError(f"oracle prefill attention (rows) failed: {rc}")
         return out
 
     def calibrate_clip(self, k, v, q, o_ref, alphas):

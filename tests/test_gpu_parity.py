@@ -513,6 +513,39 @@ def test_prefill_attention_matches_oracle(P, B, Hq, Hk, T):
     assert np.array_equal(o16.cpu().numpy(), out.astype(np.float16))
 
 
+@pytest.mark.parametrize("B,Hq,Hk,T", [(1, 32, 8, 32768), (2, 8, 2, 16384 + 77)])
+def test_prefill_attention_long_prompt_sampled_rows(P, B, Hq, Hk, T):
+    """Prompts of the size that is timed (32 q / 8 kv heads, 32k tokens: 128 workgroups per head,
+    up to 512 tiles each) and a ragged one: rows chosen at tile and workgroup edges plus random
+    ones, each computed by the oracle one by one; every output must be finite."""
+    from oracle import skvq_oracle as O
+    from paper_2405_06219_amd import binding as Bd
+    print("case", B, Hq, Hk, T, flush=True)
+    rng = np.random.default_rng(3100 + T)
+    q = rng.standard_normal((B, Hq, T, D), dtype=np.float32).astype(np.float16)
+    k = (rng.standard_normal((B, Hk, T, D), dtype=np.float32) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D), dtype=np.float32) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
+    perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
+    one = np.ones((Hk, 1), np.float32)
+    ts = [0, 1, 31, 32, 63, 64, 65, 127, 255, 256, 257, 511, 512, 8191, 8192, T // 2 - 1, T // 2, T - 257, T - 256,
+          T - 65, T - 64, T - 33, T - 32, T - 2, T - 1]
+    rows = [(int(rng.integers(B)), int(rng.integers(Hq)), t) for t in ts]
+    rows += [(int(rng.integers(B)), int(rng.integers(Hq)), int(rng.integers(T))) for _ in range(40)]
+    rows += [(B - 1, Hq - 1, T - 1), (0, 0, 0), (B - 1, 0, T - 1), (0, Hq - 1, 255)]
+    ref = O.OracleCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one).prefill_attention_rows(q, k, v, rows)
+    gpu = Bd.SkvqCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one)
+    dev = "cuda:0"
+    out = gpu.skvq_prefill_attention(torch.from_numpy(q).to(dev), torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    idx = np.asarray(rows)
+    got = out[idx[:, 0], idx[:, 1], idx[:, 2]].cpu().numpy()
+    err = np.abs(got - ref).max()
+    bound = 2.0 ** -11 * float(np.abs(v.astype(np.float32)).max()) + 1e-5
+    P.log(f"prefill attention (sampled rows) B{B} Hq{Hq} Hk{Hk} T{T}: {len(rows)} rows, max abs err {err:.3e} (bound {bound:.3e})")
+    assert err <= bound
+
+
 # ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
 
 @pytest.mark.parametrize("G,v_bits,k_bits,Hq,Hk,B", [(64, 2.0, 2.0, 4, 2, 1), (128, 1.5, 2.0, 8, 2, 2), (32, 4.0, 4.0, 3, 3, 1)])

@@ -902,6 +902,33 @@ def test_prefill_attention_with_uniform_weights_is_the_running_mean(oracle):
     assert np.abs(out - mean.repeat(Hq // Hk, axis=1)).max() < 1e-6
 
 
+def test_prefill_attention_rows_are_the_librarys_rows(oracle):
+    """The chosen-rows entry (for prompts too long to compute whole) against the library's causal
+    attention and against the whole-prompt entry; an index out of range is refused."""
+    rng = np.random.default_rng(1202)
+    B, Hq, Hk, T = 2, 6, 2, 130
+    q = rng.standard_normal((B, Hq, T, D)).astype(np.float16)
+    k = (rng.standard_normal((B, Hk, T, D)) * 2).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+    perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
+    one = np.ones((Hk, 1), np.float32)
+    c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one, sm_scale=0.11)
+    rows = [(0, 0, 0), (1, 5, 129), (0, 3, 64), (1, 2, 63), (0, 4, 1), (1, 0, 100)]
+    out = c.prefill_attention_rows(q, k, v, rows)
+    rep = Hq // Hk
+    qt = torch.from_numpy(q.astype(np.float64))
+    kt = torch.from_numpy(k.astype(np.float64)).repeat_interleave(rep, dim=1)
+    vt = torch.from_numpy(v.astype(np.float64)).repeat_interleave(rep, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, is_causal=True, scale=0.11).numpy()
+    whole = c.prefill_attention(q, k, v)
+    for i, (b, h, t) in enumerate(rows):
+        assert np.abs(out[i] - ref[b, h, t]).max() < 1e-5
+        assert np.array_equal(out[i], whole[b, h, t])
+    for bad in ((2, 0, 0), (0, 6, 0), (0, 0, 130), (0, -1, 0)):
+        with pytest.raises(RuntimeError):
+            c.prefill_attention_rows(q, k, v, [bad])
+
+
 # ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
 
 def calib_setup(oracle, rng, G, lossless=False, T=48, W=8, Hq=4, Hk=2, n_q=3, v_bits=2.0):
