@@ -3,12 +3,13 @@
 
 A step is one generated token of a 7B-shaped model: for each of `--layers` attention layers
 (each with its own cache, so that no layer's data is still in the 256 MB Infinity Cache when
-its turn comes again) the token leaving the fp16 window is quantized
-(skvq_quantize_append) and the new query attends over the whole cache
-(skvq_decode_attention).  Inputs are seeded synthetic tensors already resident in HBM.
+its turn comes again) the token leaving the fp16 window is quantized and the new query attends
+over the whole cache: one skvq_append_decode_attention call per layer (with --two-calls:
+skvq_quantize_append, then skvq_decode_attention; the other way is timed too and reported
+beside).  Inputs are seeded synthetic tensors already resident in HBM.
 
 Prints ONE JSON line.  `value` is microseconds per token (all layers); `roofline` prices the
-algorithmic bytes of one skvq_decode_attention call against the 8 TB/s HBM peak, its duration
+algorithmic bytes of one layer's attention call against the 8 TB/s HBM peak, its duration
 measured with HIP events around the layers' calls issued back to back; `cpu_baseline` is the
 CPU oracle timed on a bounded sample of the same workload.
 """
@@ -135,6 +136,9 @@ def main() -> int:
                     help="override the workload's (average) group size (the headline workload has 128)")
     ap.add_argument("--group-bounds", default="",
                     help="unequal groups: comma-separated boundaries, 128/group_size + 1 multiples of 16 from 0 to 128")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="time skvq_quantize_append + skvq_decode_attention per layer instead of the one call "
+                         "that does both (skvq_append_decode_attention)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -163,13 +167,13 @@ def main() -> int:
     if args.v_bits:
         w = dataclasses.replace(w, v_bits=args.v_bits)
     n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers
-    headroom = n_warm + 2 * n_steps + 9
+    headroom = n_warm + 3 * n_steps + 9
 
     caches, (sk_d, sv_d), prefill_us = build_layers(w, n_layers, headroom, device, args.sink, args.meta, bounds)
     prefill_med_us = float(np.median(prefill_us))
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
-    total = n_warm + 2 * n_steps + 1
+    total = n_warm + 3 * n_steps + 1
     # per (step, layer) inputs, resident before the timed region
     q_all = torch.randn((total, n_layers, w.batch, w.n_q_heads, D), generator=gen, device=device).to(torch.float16)
     kn_all = (torch.randn((total, n_layers, w.batch, w.n_kv_heads, D), generator=gen, device=device)
@@ -178,11 +182,16 @@ def main() -> int:
               * sv_d[:, :, 0]).to(torch.float16)
     out = torch.empty((n_layers, w.batch, w.n_q_heads, D), dtype=torch.float32, device=device)
 
-    def step(i):
+    def step_one_call(i):
+        for layer, c in enumerate(caches):
+            c.skvq_append_decode_attention(kn_all[i, layer], vn_all[i, layer], q_all[i, layer], out_f32=out[layer])
+
+    def step_two_calls(i):
         for layer, c in enumerate(caches):
             c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
             c.skvq_decode_attention(q_all[i, layer], out_f32=out[layer])
 
+    step, other_step = (step_two_calls, step_one_call) if args.two_calls else (step_one_call, step_two_calls)
     i = 0
     for _ in range(n_warm):
         step(i)
@@ -196,25 +205,37 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / n_steps
     n_tokens_mid = w.context + n_warm + n_steps // 2
+    # the same steps the other way, for comparison
+    t0 = time.perf_counter()
+    for _ in range(n_steps):
+        other_step(i)
+        i += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    other_ms_per_step = (t1 - t0) * 1e3 / n_steps
 
-    # roofline pass: per step, the appends of all layers first, then the decode calls of all
-    # layers back to back between one pair of HIP events (an event pair around every single
-    # call adds about 2 us to each); average launch duration = elapsed / layers
+    # roofline pass: the decode launches of all layers back to back between one pair of HIP events
+    # (an event pair around every single call adds about 2 us to each); average launch duration =
+    # elapsed / layers.  With two calls per layer the appends of all layers go first, untimed.
     dec_us = []
     for _ in range(n_steps):
-        for layer, c in enumerate(caches):
-            c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
+        if args.two_calls:
+            for layer, c in enumerate(caches):
+                c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for layer, c in enumerate(caches):
-            c.skvq_decode_attention(q_all[i, layer], out_f32=out[layer])
+        if args.two_calls:
+            for layer, c in enumerate(caches):
+                c.skvq_decode_attention(q_all[i, layer], out_f32=out[layer])
+        else:
+            step_one_call(i)
         e1.record()
         torch.cuda.synchronize()
         dec_us.append(e0.elapsed_time(e1) * 1e3 / n_layers)
         i += 1
     dec_us = np.array(dec_us)
     dec_avg_us = float(dec_us.mean())
-    n_tokens_roof = w.context + n_warm + n_steps + n_steps // 2
+    n_tokens_roof = w.context + n_warm + 2 * n_steps + n_steps // 2
     alg_bytes = algorithmic_bytes_decode(w, n_tokens_roof, args.sink, args.meta)
     achieved = alg_bytes / (dec_avg_us * 1e-6) / 1e9
 
@@ -265,8 +286,10 @@ def main() -> int:
                    "n_kv_heads": w.n_kv_heads, "head_dim": D, "context": w.context, "k_bits": w.k_bits,
                    "v_bits": w.v_bits, "group_size": w.group_size, "window": w.window, "n_sink": args.sink, "meta": args.meta,
                    "group_bounds": bounds,
-                   "step": "per layer: skvq_quantize_append + skvq_decode_attention"},
+                   "step": ("per layer: skvq_quantize_append + skvq_decode_attention" if args.two_calls else
+                            "per layer: skvq_append_decode_attention (append and attention in one launch + merge)")},
         "us_per_layer": ms_per_step * 1e3 / n_layers,
+        ("one_call_us_per_token" if args.two_calls else "two_calls_us_per_token"): other_ms_per_step * 1e3,
         "decode_call_us": dec_avg_us,
         "decode_call_us_min": float(dec_us.min()),
         "append_call_us": append_us,
@@ -287,7 +310,8 @@ def main() -> int:
                      "traffic": (MEASURED_TRAFFIC_BYTES.get(w.name)
                                  if w.context == synth.WORKLOADS[w.name].context and not args.sink
                                  and args.meta == "f32" and headline_format else None),
-                     "kernel": "skvq_decode_attention", "bytes_per_launch": alg_bytes,
+                     "kernel": "skvq_decode_attention" if args.two_calls else "skvq_append_decode_attention",
+                     "bytes_per_launch": alg_bytes,
                      "avg_launch_us": dec_avg_us},
     }
     if not args.no_cpu_baseline:

@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_append_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p]
         L.skvq_get_state.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.skvq_set_state.argtypes = [C.c_void_p, C.c_int64]
         L.skvq_set_num_splits.argtypes = [C.c_void_p, C.c_int32]
@@ -266,6 +268,20 @@ class SkvqCache:
         op = _dev_ptr(out_f32, torch.float32, (b, hq, HEAD_DIM))
         hp = _dev_ptr(out_f16, torch.float16, (b, hq, HEAD_DIM)) if out_f16 is not None else None
         self._check(lib().skvq_decode_attention(self._h, qp, op, hp, _stream_ptr(stream)))
+        return out_f32
+
+    def skvq_append_decode_attention(self, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor,
+                                     out_f32: torch.Tensor | None = None, out_f16: torch.Tensor | None = None,
+                                     stream=None) -> torch.Tensor:
+        b, hq, hk = self.shape
+        kp = _dev_ptr(k_new, torch.float16, (b, hk, HEAD_DIM))
+        vp = _dev_ptr(v_new, torch.float16, (b, hk, HEAD_DIM))
+        qp = _dev_ptr(q, torch.float16, (b, hq, HEAD_DIM))
+        if out_f32 is None:
+            out_f32 = torch.empty((b, hq, HEAD_DIM), dtype=torch.float32, device=self.device)
+        op = _dev_ptr(out_f32, torch.float32, (b, hq, HEAD_DIM))
+        hp = _dev_ptr(out_f16, torch.float16, (b, hq, HEAD_DIM)) if out_f16 is not None else None
+        self._check(lib().skvq_append_decode_attention(self._h, kp, vp, qp, op, hp, _stream_ptr(stream)))
         return out_f32
 
     # ---- state ----

@@ -439,6 +439,28 @@ int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out
   return SKVQ_OK;
 }
 
+int skvq_append_decode_attention(skvq_cache *c, const void *k_new, const void *v_new, const void *q, void *out_f32,
+                                 void *out_f16, void *stream) {
+  if (!c || !k_new || !v_new || !q || !out_f32) return SKVQ_ERR_INVALID_ARG;
+  const long long T = c->n_tokens;
+  const long long nq = counts_of(T + 1, c->L.W, c->L.S).n_quant;
+  if (nq > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  hipStream_t s = (hipStream_t)stream;
+  if (append_fusable(c->L, T + 1)) {
+    hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, T + 1,
+                                 choose_splits(c, nq), 1, s, (const __half *)k_new, (const __half *)v_new);
+    if (e != hipSuccess) return fail_hip(c, e, "skvq_append_decode_attention launch");
+    c->n_tokens = T + 1;
+    return SKVQ_OK;
+  }
+  hipError_t e = launch_append(c->L, (const __half *)k_new, (const __half *)v_new, T, s);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_append_decode_attention launch (append)");
+  c->n_tokens = T + 1;
+  e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, T + 1, choose_splits(c, nq), 1, s);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_append_decode_attention launch (decode)");
+  return SKVQ_OK;
+}
+
 int skvq_decode_attention_multi(skvq_cache *c, const void *q, int32_t n_new, void *out_f32, void *out_f16,
                                 void *stream) {
   if (!c || !q || !out_f32 || n_new < 1) return SKVQ_ERR_INVALID_ARG;

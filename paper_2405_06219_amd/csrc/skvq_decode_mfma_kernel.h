@@ -40,6 +40,7 @@
 #include <math.h>
 
 #include "skvq_internal.h"
+#include "skvq_append_device.h"
 
 namespace skvq {
 #ifdef SKVQ_TIMING
@@ -191,6 +192,7 @@ constexpr int kNW = 8;              // wavefronts per workgroup (2 per SIMD: 256
 constexpr int kThreads = 64 * kNW;
 constexpr int kOldShare = 3, kYoungShare = 2;                        // tiles per deal: waves 0..3 / 4..7
 constexpr int kDealPeriod = (kNW / 2) * (kOldShare + kYoungShare);  // tiles per deal
+constexpr int kAppendLagTiles = 12;  // tiles that the workgroup which also appends the new token is spared
 constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
 constexpr int kRingSlice = 4;       // ring tokens per slice (the slice code reads four rows of 16 lanes)
 
@@ -302,7 +304,9 @@ struct RingData {
 template <int R, int KL, int VL, int META, int NG, bool UNEQ>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
-                                                                  int n_splits, int passes, int n_new) {
+                                                                  int n_splits, int passes, int n_new,
+                                                                  const __half *__restrict__ knew,
+                                                                  const __half *__restrict__ vnew) {
   // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
   // head with more than four (or with three) query heads is served by `passes` workgroups per
   // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
@@ -328,10 +332,28 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;
 
+  // ---- the new token taken along (knew != null; one query token, passes == 1, and the token
+  //      that leaves the window, if any, is packed: the host sees to that).  T counts the new
+  //      token.  The workgroup of the last chunk does what the append kernel does (its tiles are
+  //      the only ones that read the packed row, the V block and the metadata that this writes;
+  //      nobody reads the ring slot: the new token's row is taken from knew / vnew below).  Its
+  //      stores have completed, in this compute unit's own cache order, before its first tile
+  //      load is issued, and no load of the branch is pending where the paths join. ----
+  const bool fused = knew != nullptr;
+  if (fused && sp == n_splits - 1) {
+    append_token(L, knew, vnew, T - 1, hk, b, wave, lane, reinterpret_cast<__half(*)[kD]>(&sm.ring_o[0][0][0]),
+                 reinterpret_cast<uint8_t *>(&sm.ring_o[0][0][0]) + 2 * kD * sizeof(__half));
+    __threadfence_block();
+    __syncthreads();
+  }
+
   // ---- this chunk, this wave's tiles ----
+  // (with the new token taken along the last chunk is shorter by about the time its workgroup
+  // spends on the append)
   const int n_tiles = (int)((nq + 63) >> 6);
-  const int tile_begin = (int)(((long long)sp * n_tiles) / n_splits);
-  const int tile_end = (int)(((long long)(sp + 1) * n_tiles) / n_splits);
+  const int lag = fused && n_tiles >= 4 * kAppendLagTiles * n_splits ? kAppendLagTiles : 0;
+  const int tile_begin = (int)(((long long)sp * (n_tiles + lag)) / n_splits);
+  const int tile_end = sp == n_splits - 1 ? n_tiles : (int)(((long long)(sp + 1) * (n_tiles + lag)) / n_splits);
 
   constexpr int kRowBytes = K4 ? 64 : K3 ? 48 : 32;
   const uint8_t *kc = L.k_codes + head * L.Tcap * kRowBytes;
@@ -404,12 +426,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     int s = slot0 + t - n_sink;
     return s >= W ? s - W : s;
   };
+  // row of ring token t (clamped to the last one); the newest token's row is the caller's when
+  // it is taken along
+  auto ring_row = [&](const __half *win, const __half *fresh, int t) {
+    const __half *row = win + (size_t)ring_slot(t) * kD;
+    return fused && t >= n_fp - 1 ? fresh + head * kD : row;
+  };
   auto load_ring = [&](int slice) {
     RingData d;
-    d.k = reinterpret_cast<const uint4_t *>(kwin + (size_t)ring_slot(slice * kRingSlice + (lane >> 4)) * kD)[lane & 15];
+    d.k = reinterpret_cast<const uint4_t *>(ring_row(kwin, knew, slice * kRingSlice + (lane >> 4)))[lane & 15];
 #pragma unroll
     for (int k = 0; k < kRingSlice; ++k)
-      d.v[k] = reinterpret_cast<const unsigned *>(vwin + (size_t)ring_slot(slice * kRingSlice + k) * kD)[lane];
+      d.v[k] = reinterpret_cast<const unsigned *>(ring_row(vwin, vnew, slice * kRingSlice + k))[lane];
     return d;
   };
 
@@ -950,17 +978,18 @@ extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
 // The launcher of the kernels with KL-level keys and VL-level values.
 template <int KL, int VL>
 hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
-                                  int n_splits, int n_new, hipStream_t s) {
+                                  int n_splits, int n_new, const __half *knew, const __half *vnew, hipStream_t s) {
   if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
   if (n_new < 1 || n_new > SKVQ_MAX_NEW_TOKENS || L.R > 8) return hipErrorInvalidValue;
   const int n_rows = n_new * L.R;
   const int passes = decode_passes(n_rows), rk = n_rows == 1 ? 1 : n_rows == 2 ? 2 : 4;
+  if ((knew != nullptr) != (vnew != nullptr) || (knew && (passes != 1 || n_new != 1))) return hipErrorInvalidValue;
   if ((long long)L.Hk * passes > 65535) return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
 #define SKVQ_LAUNCH(RR, MM, GG, UU) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew)
 #define SKVQ_LAUNCH_NG(RR, MM)                                                                   \
   switch (L.NG) {                                                                                \
     case 1: SKVQ_LAUNCH(RR, MM, 1, false); break;                                                \

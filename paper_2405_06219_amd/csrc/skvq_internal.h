@@ -88,8 +88,11 @@ int reorder_channels(const float *stats, int Hk, int G, int gran, int max_iter, 
 // decode kernels (skvq_decode.hip)
 // n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).
 // n_new: query tokens per sequence (q, out: [B][n_new][Hq][D]); the last n_new cached tokens are theirs.
+// k_new, v_new (both or neither): the newest of the T tokens is not in the cache yet, the chunk
+// kernel appends it on the way (see append_fusable).
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,
-                         long long T, int n_splits, int n_new, hipStream_t s);
+                         long long T, int n_splits, int n_new, hipStream_t s, const __half *k_new = nullptr,
+                         const __half *v_new = nullptr);
 
 // Matrix-core chunk kernel (skvq_decode_mfma.hip): packed chunks and the fp16 tokens (n_sink sink
 // rows, then the window's T - nq - n_sink ring tokens); writes partials 0..n_splits-1 (n_splits
@@ -98,7 +101,16 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
 // (n_rows = query heads per kv head x query tokens)
 inline int decode_passes(int n_rows) { return n_rows > 4 ? (n_rows + 3) / 4 : 1; }
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
-                              int n_splits, int n_new, hipStream_t s);
+                              int n_splits, int n_new, const __half *knew, const __half *vnew, hipStream_t s);
+// Whether the decode of T_after tokens (one query token) may append the newest token itself: one
+// workgroup per chunk (at most four query heads per kv head), and the token that leaves the
+// window, if any, is packed rather than copied to a sink row (a sink row has other readers in
+// the same launch).
+inline bool append_fusable(const Layout &L, long long T_after) {
+  const long long T = T_after - 1;  // tokens cached before
+  const bool leaves = T >= L.W, evict = T - L.W >= L.S;
+  return decode_passes(L.R) == 1 && !(leaves && !evict);
+}
 constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel
 
 }  // namespace skvq

@@ -72,6 +72,17 @@ class Pair:
         return out.cpu().numpy(), ref
 
 
+    def append_decode_both(self, k_new: np.ndarray, v_new: np.ndarray, q: np.ndarray):
+        """One decode step as a single library call against the oracle's append followed by its decode."""
+        assert self.ref.append(k_new, v_new) == 0
+        ref = self.ref.decode(q)
+        out = self.gpu.skvq_append_decode_attention(torch.from_numpy(k_new).to(self.device),
+                                                    torch.from_numpy(v_new).to(self.device),
+                                                    torch.from_numpy(q).to(self.device))
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), ref
+
+
 def make_pair(w: synth.Workload, extra_tokens: int = 0, **kw):
     """Pair + its seeded inputs (k, v, q) for workload w."""
     k, v = synth.make_kv(w)

@@ -207,6 +207,69 @@ def test_decode_after_appends_and_peaked_softmax(P):
     assert np.abs(out - ref).max() <= P.TOL
 
 
+# ---- one decode step as one call: the new token is appended inside the attention launch ----
+STEP_CASES = [
+    (small("step_mha_t15", context=700), {}, 0),
+    (small("step_from_empty", context=0, window=16), {}, 0),                      # ring fills, then the first evictions
+    (small("step_gqa4_v2_g64", n_q_heads=8, n_kv_heads=2, group_size=64, v_bits=2.0, context=391, batch=2), {}, 2),
+    (small("step_gqa2_k4v4_g32_w16", k_bits=4.0, v_bits=4.0, n_q_heads=4, n_kv_heads=2, group_size=32, context=333, window=16), {}, 3),
+    (small("step_gqa3_k3v3", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=2, context=450), {"meta": "f16"}, 0),
+    (small("step_k4_t15_e4m3", k_bits=4.0, v_bits=1.5, group_size=64, context=300), {"meta": "e4m3"}, 1),
+    (small("step_k2v4", k_bits=2.0, v_bits=4.0, n_q_heads=2, n_kv_heads=1, context=200), {}, 0),
+    (small("step_sinks", n_q_heads=8, n_kv_heads=2, context=120), {"n_sink": 5}, 0),  # sink rows first: two launches
+    (small("step_gqa8_two_launches", n_q_heads=8, n_kv_heads=1, context=450, window=16), {}, 0),
+    (small("step_uneq_g32", n_q_heads=8, n_kv_heads=2, group_size=32, context=600),
+     {"group_bounds": [0, 16, 32, 80, 128]}, 2),
+    (small("step_long_b2", group_size=64, context=9000, batch=2), {}, 2),  # the last chunk is the shorter one
+    (small("step_long_w33", window=33, context=5000, batch=3), {}, 1),
+]
+
+
+@pytest.mark.parametrize("w,kw,splits", STEP_CASES, ids=[c[0].name for c in STEP_CASES])
+def test_append_and_attention_in_one_call(P, w, kw, splits):
+    """skvq_append_decode_attention step by step against the oracle's append followed by its
+    decode: outputs within 2e-3 at every step, every packed byte, (scale, zero) and ring row
+    bit-exact along the way (V block and tile boundaries included)."""
+    print("case", w, kw, splits, flush=True)
+    n = 70
+    pair, k, v, q = P.make_pair(w, extra_tokens=n, **kw)
+    if w.context:
+        pair.prefill(k, v)
+    if splits:
+        pair.gpu.skvq_set_num_splits(splits)
+    rng = np.random.default_rng(77)
+    worst = 0.0
+    for s in range(n):
+        kn, vn = synth.make_new_token(w, s)
+        qs = (q * rng.uniform(0.5, 1.5)).astype(np.float16)
+        out, ref = pair.append_decode_both(kn, vn, qs)
+        worst = max(worst, float(np.abs(out - ref).max()))
+        assert np.abs(out - ref).max() <= P.TOL, s
+        if s in (0, 1, 7, 8, 15, 16, 31, 32, 33, 63, 64, n - 1):
+            pair.assert_buffers_equal()
+    P.log(f"one-call step {w.name}: max abs err over {n} steps {worst:.3e}")
+
+
+def test_one_call_step_equals_the_two_calls(P):
+    """The same steps through skvq_quantize_append + skvq_decode_attention on a second cache: the
+    packed buffers end up identical bit for bit and the outputs equal to rounding."""
+    w = small("step_vs_two", n_q_heads=8, n_kv_heads=2, context=2100)
+    pair, k, v, q = P.make_pair(w, extra_tokens=40)
+    other, _, _, _ = P.make_pair(w, extra_tokens=40)
+    pair.prefill(k, v)
+    other.gpu.skvq_prefill_quantize(torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda())
+    qd = torch.from_numpy(q).cuda()
+    for s in range(40):
+        kn, vn = (torch.from_numpy(x).cuda() for x in synth.make_new_token(w, s))
+        a = pair.gpu.skvq_append_decode_attention(kn, vn, qd)
+        other.gpu.skvq_quantize_append(kn, vn)
+        b = other.gpu.skvq_decode_attention(qd)
+        torch.cuda.synchronize()
+        assert float((a - b).abs().max()) <= 2e-5, s
+    for x, y in zip(pair.gpu.host_arrays(), other.gpu.host_arrays()):
+        assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
+
+
 def test_runtime_errors(P):
     w = small("errors", context=300)
     pair, k, v, q = P.make_pair(w, extra_tokens=2)
@@ -249,6 +312,12 @@ def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
     err = np.abs(out - ref).max()
     P.log(f"full size c3: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
     assert err <= P.TOL
+    P.log("full size: one-call step (oracle + gpu)")
+    out, ref = pair.append_decode_both(*synth.make_new_token(w, 3), q)
+    err = np.abs(out - ref).max()
+    P.log(f"full size c3, append + attention in one call: max abs err {err:.3e}")
+    assert err <= P.TOL
+    pair.assert_buffers_equal()
 
 
 @pytest.mark.parametrize("name,n_heads,bits", [("c5_batch16_32k", 4, None), ("c4_llama7b_1m", 2, None),
