@@ -29,10 +29,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 D = 128
-# HBM bytes per skvq_decode_attention call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (chunk kernel + merge kernel, counters scaled by a plain copy of known size); see
-# profiles/decode_c3_mistral7b_128k_pmc.txt.  Only workloads that were measured have an entry.
-MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": 77977 * 1024}
+# HBM bytes per attention call (one call with the append inside / skvq_decode_attention alone)
+# measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (chunk kernel + merge kernel, counters
+# scaled by a plain copy of known size); see profiles/decode_c3_mistral7b_128k_pmc.txt.  Only
+# workloads that were measured have an entry.
+MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": (78037 * 1024, 78007 * 1024)}
 
 
 META_BYTES = {"f32": 4, "f16": 2, "e4m3": 1}
@@ -307,8 +308,8 @@ def main() -> int:
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES.get(w.name)
-                                 if w.context == synth.WORKLOADS[w.name].context and not args.sink
+                     "traffic": (MEASURED_TRAFFIC_BYTES[w.name][1 if args.two_calls else 0]
+                                 if w.name in MEASURED_TRAFFIC_BYTES and w.context == synth.WORKLOADS[w.name].context and not args.sink
                                  and args.meta == "f32" and headline_format else None),
                      "kernel": "skvq_decode_attention" if args.two_calls else "skvq_append_decode_attention",
                      "bytes_per_launch": alg_bytes,

@@ -1,8 +1,12 @@
-"""Workload for hardware-counter runs: a few decode calls on the benchmark's layer shape and a
-plain device-to-device copy of known size (the yardstick that FETCH_SIZE / WRITE_SIZE are
-scaled by).  Run under `rocprofv3 --pmc FETCH_SIZE` (and again with WRITE_SIZE):
+"""Workload for hardware-counter runs: a few decode steps on the benchmark's layer shape (first
+skvq_decode_attention alone, then skvq_append_decode_attention) and a plain device-to-device
+copy of known size (the yardstick that FETCH_SIZE / WRITE_SIZE are scaled by).  Run under
+`rocprofv3 --pmc FETCH_SIZE` (and again with WRITE_SIZE):
 
     python3 paper_2405_06219_amd/pmc_probe.py [workload] [layers] [meta format] [sinks]
+
+The chunk kernel's dispatches come in two sets of 3 x layers: the first without, the second with
+the append.
 """
 from __future__ import annotations
 
@@ -31,6 +35,11 @@ def main() -> int:
     for _ in range(3):
         for i, c in enumerate(caches):
             c.skvq_decode_attention(q[i], out_f32=out[i])
+    kn = torch.randn((n_layers, w.batch, w.n_kv_heads, 128), device=dev).to(torch.float16)
+    vn = torch.randn((n_layers, w.batch, w.n_kv_heads, 128), device=dev).to(torch.float16)
+    for _ in range(3):
+        for i, c in enumerate(caches):
+            c.skvq_append_decode_attention(kn[i], vn[i], q[i], out_f32=out[i])
     torch.cuda.synchronize()
     # yardstick: copy 256 MiB (reads 268435456 bytes, writes 268435456 bytes)
     src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
