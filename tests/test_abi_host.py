@@ -122,6 +122,11 @@ def test_validation_rejects_bad_configs(B):
     bufs = B.skvq_buffers(*([16] * 6 + [8]))
     assert B.lib().skvq_create(C.byref(ok), C.byref(bufs), C.byref(h)) == B.SKVQ_ERR_INVALID_ARG
     assert not h.value
+    # the hot calls refuse a null cache before anything else
+    L = B.lib()
+    assert L.skvq_quantize_append(None, None, None, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_decode_attention(None, None, None, None, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_append_decode_attention(None, None, None, None, None, None, None) == B.SKVQ_ERR_INVALID_ARG
     assert B.lib().skvq_status_string(B.SKVQ_ERR_CAPACITY) == b"packed region full"
     B.lib().skvq_destroy(None)
 
