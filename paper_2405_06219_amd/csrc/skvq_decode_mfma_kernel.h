@@ -344,6 +344,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     append_token(L, knew, vnew, T - 1, hk, b, wave, lane, reinterpret_cast<__half(*)[kD]>(&sm.ring_o[0][0][0]),
                  reinterpret_cast<uint8_t *>(&sm.ring_o[0][0][0]) + 2 * kD * sizeof(__half));
     __threadfence_block();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (the fence alone need not wait for the stores)
     __syncthreads();
   }
 
