@@ -189,8 +189,9 @@ int skvq_decode_attention(skvq_cache *cache, const void *q, void *out_f32, void 
                           void *hip_stream);
 /* One decode step of Algorithm 1 with l = 1 as a single call: skvq_quantize_append(k_new, v_new)
  * followed by skvq_decode_attention(q), same arguments, same results in the cache and in the
- * outputs, same errors.  When a kv head has at most four query heads and the token that leaves
- * the window is packed (not kept as a sink), both run as one launch: the workgroup that reads the
+ * outputs, same errors.  When a kv head has at most four query heads, its packed rows are split
+ * into at least four chunks (long caches, few sequences) and the token that leaves the window
+ * is packed (not kept as a sink), both run as one launch: the workgroup that reads the
  * last packed rows quantizes the leaving token itself before it reads them, and the new token's
  * fp16 row is taken from k_new / v_new; otherwise the two kernels are launched one after the
  * other.  k_new and v_new must stay valid until the call has finished on the stream. */

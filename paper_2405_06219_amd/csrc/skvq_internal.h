@@ -106,6 +106,7 @@ hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, lon
 // workgroup per chunk (at most four query heads per kv head), and the token that leaves the
 // window, if any, is packed rather than copied to a sink row (a sink row has other readers in
 // the same launch).
+constexpr int kMinSplitsForOneLaunch = 4;  // chunks per kv head from which the one-launch step is used
 inline bool append_fusable(const Layout &L, long long T_after) {
   const long long T = T_after - 1;  // tokens cached before
   const bool leaves = T >= L.W, evict = T - L.W >= L.S;

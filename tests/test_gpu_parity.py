@@ -209,19 +209,21 @@ def test_decode_after_appends_and_peaked_softmax(P):
 
 # ---- one decode step as one call: the new token is appended inside the attention launch ----
 STEP_CASES = [
-    (small("step_mha_t15", context=700), {}, 0),
-    (small("step_from_empty", context=0, window=16), {}, 0),                      # ring fills, then the first evictions
-    (small("step_gqa4_v2_g64", n_q_heads=8, n_kv_heads=2, group_size=64, v_bits=2.0, context=391, batch=2), {}, 2),
-    (small("step_gqa2_k4v4_g32_w16", k_bits=4.0, v_bits=4.0, n_q_heads=4, n_kv_heads=2, group_size=32, context=333, window=16), {}, 3),
-    (small("step_gqa3_k3v3", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=2, context=450), {"meta": "f16"}, 0),
-    (small("step_k4_t15_e4m3", k_bits=4.0, v_bits=1.5, group_size=64, context=300), {"meta": "e4m3"}, 1),
+    # (workload, cache options, forced chunks per kv head: from four on the step is one launch)
+    (small("step_mha_t15", context=700), {}, 4),
+    (small("step_from_empty", context=0, window=16), {}, 0),            # ring fills, then the first evictions: two launches
+    (small("step_gqa4_v2_g64", n_q_heads=8, n_kv_heads=2, group_size=64, v_bits=2.0, context=391, batch=2), {}, 4),
+    (small("step_gqa2_k4v4_g32_w16", k_bits=4.0, v_bits=4.0, n_q_heads=4, n_kv_heads=2, group_size=32, context=333, window=16), {}, 5),
+    (small("step_gqa3_k3v3", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=2, context=450), {"meta": "f16"}, 6),
+    (small("step_k4_t15_e4m3", k_bits=4.0, v_bits=1.5, group_size=64, context=300), {"meta": "e4m3"}, 4),
     (small("step_k2v4", k_bits=2.0, v_bits=4.0, n_q_heads=2, n_kv_heads=1, context=200), {}, 0),
-    (small("step_sinks", n_q_heads=8, n_kv_heads=2, context=120), {"n_sink": 5}, 0),  # sink rows first: two launches
-    (small("step_gqa8_two_launches", n_q_heads=8, n_kv_heads=1, context=450, window=16), {}, 0),
+    (small("step_sinks", n_q_heads=8, n_kv_heads=2, context=120), {"n_sink": 5}, 4),  # sink rows first (two launches), then packed rows
+    (small("step_gqa8_two_launches", n_q_heads=8, n_kv_heads=1, context=450, window=16), {}, 4),
     (small("step_uneq_g32", n_q_heads=8, n_kv_heads=2, group_size=32, context=600),
-     {"group_bounds": [0, 16, 32, 80, 128]}, 2),
-    (small("step_long_b2", group_size=64, context=9000, batch=2), {}, 2),  # the last chunk is the shorter one
-    (small("step_long_w33", window=33, context=5000, batch=3), {}, 1),
+     {"group_bounds": [0, 16, 32, 80, 128]}, 4),
+    (small("step_long_b2", group_size=64, context=9000, batch=2), {}, 7),
+    (small("step_long_w33", window=33, context=5000, batch=3), {}, 2),   # two chunks: two launches
+    (small("step_long_short_last_chunk", n_q_heads=8, n_kv_heads=2, context=13000), {}, 4),  # the last chunk is the shorter one
 ]
 
 
@@ -256,6 +258,8 @@ def test_one_call_step_equals_the_two_calls(P):
     w = small("step_vs_two", n_q_heads=8, n_kv_heads=2, context=2100)
     pair, k, v, q = P.make_pair(w, extra_tokens=40)
     other, _, _, _ = P.make_pair(w, extra_tokens=40)
+    pair.gpu.skvq_set_num_splits(4)   # one launch per step
+    other.gpu.skvq_set_num_splits(4)
     pair.prefill(k, v)
     other.gpu.skvq_prefill_quantize(torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda())
     qd = torch.from_numpy(q).cuda()
