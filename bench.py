@@ -37,6 +37,7 @@ MEASURED_TRAFFIC_BYTES = {"c3_mistral7b_128k": (78037 * 1024, 78007 * 1024)}
 
 
 META_BYTES = {"f32": 4, "f16": 2, "e4m3": 1}
+MULTI_TOKENS = (2, 4)  # query tokens per call timed for skvq_decode_attention_multi
 
 
 def code_bytes_per_row(w) -> int:
@@ -74,7 +75,7 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta:
         k, v, pk, pv = synth.make_kv_device(w, device, stream=layer)
         c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
                         w.context - w.window + headroom, pk, pv, ck, cv, device=device, n_sink=n_sink,
-                        meta=meta, k_bits=w.k_bits, group_bounds=group_bounds)
+                        meta=meta, k_bits=w.k_bits, group_bounds=group_bounds, max_new_tokens=MULTI_TOKENS[-1])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         c.skvq_prefill_quantize(k, v)
@@ -260,6 +261,22 @@ def main() -> int:
         pa_ms = e0.elapsed_time(e1) / 3
     del pa_q, pa_k, pa_v, pa_out
 
+    # several query tokens per call (skvq_decode_attention_multi): the layers' calls back to back
+    multi_us = {}
+    for n_new in MULTI_TOKENS:
+        qm = torch.randn((n_layers, w.batch, n_new, w.n_q_heads, D), generator=gen, device=device).to(torch.float16)
+        om = torch.empty((n_layers, w.batch, n_new, w.n_q_heads, D), dtype=torch.float32, device=device)
+        for rep in range(4):  # the first repetition warms up
+            if rep == 1:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            for layer, c in enumerate(caches):
+                c.skvq_decode_attention_multi(qm[layer], out_f32=om[layer])
+        e1.record()
+        torch.cuda.synchronize()
+        multi_us[str(n_new)] = e0.elapsed_time(e1) * 1e3 / (3 * n_layers)
+        del qm, om
+
     # append alone (launch-latency bound, reported for completeness): one pair of HIP events
     # around the layers' calls issued back to back
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -294,6 +311,7 @@ def main() -> int:
         "decode_call_us": dec_avg_us,
         "decode_call_us_min": float(dec_us.min()),
         "append_call_us": append_us,
+        "decode_multi_call_us": multi_us,
         "prefill_call_us": prefill_med_us,
         "prefill_tokens_per_s": w.batch * w.context / (prefill_med_us * 1e-6),
         "prefill_hbm_gbps": (w.batch * w.n_kv_heads * (w.context * 2 * D * 2 + max(w.context - w.window, 0)
