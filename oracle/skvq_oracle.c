@@ -343,14 +343,29 @@ static int check_config(const skvq_ref_config *c) {
   return 0;
 }
 
-int skvq_ref_prefill_quantize(const skvq_ref_config *c, const skvq_ref_buffers *buf,
-                              const uint16_t *k, const uint16_t *v, int64_t T,
-                              int64_t *n_tokens) {
+/* The filter rules of Algorithm 1 as a mask over the tokens that have left the window: keep[a]
+ * != 0 keeps token a in full precision.  keep == NULL is the attention-sink rule, a < S.  The
+ * kept tokens take the rows W, W+1, ... of the fp16 buffers in token order, the others the
+ * packed rows 0, 1, ... in token order. */
+static int token_kept(const skvq_ref_config *c, const uint8_t *keep, int64_t a) {
+  return keep ? keep[a] != 0 : a < c->n_sink;
+}
+/* number of kept tokens among 0 .. a-1 */
+static int64_t kept_before(const skvq_ref_config *c, const uint8_t *keep, int64_t a) {
+  int64_t n = 0;
+  for (int64_t x = 0; x < a; ++x) n += token_kept(c, keep, x);
+  return n;
+}
+
+int skvq_ref_prefill_quantize_filtered(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                                       const uint16_t *k, const uint16_t *v, int64_t T,
+                                       const uint8_t *keep, int64_t *n_tokens) {
   int rc = check_config(c);
   if (rc) return rc;
   if (T < 0) return -1;
   int64_t W = c->window, S = c->n_sink, first_win = T > W ? T - W : 0;
-  if (first_win - S > c->max_quant_tokens) return -3;
+  int64_t n_kept = kept_before(c, keep, first_win);
+  if (n_kept > S || first_win - n_kept > c->max_quant_tokens) return -3;
   int heads = c->batch * c->n_kv_heads;
 #pragma omp parallel for schedule(static)
   for (int bh = 0; bh < heads; ++bh) {
@@ -359,12 +374,14 @@ int skvq_ref_prefill_quantize(const skvq_ref_config *c, const skvq_ref_buffers *
     const uint16_t *vh = v + (size_t)bh * (size_t)T * D;
     uint16_t *kw = buf->k_win + (size_t)bh * (size_t)(W + S) * D;
     uint16_t *vw = buf->v_win + (size_t)bh * (size_t)(W + S) * D;
+    int64_t nk = 0; /* kept so far */
     for (int64_t a = 0; a < first_win; ++a) {
-      if (a < S) { /* the filter rule keeps a sink token in full precision */
-        memcpy(kw + (size_t)(W + a) * D, kh + a * D, D * 2);
-        memcpy(vw + (size_t)(W + a) * D, vh + a * D, D * 2);
+      if (token_kept(c, keep, a)) { /* a filter rule keeps the token in full precision */
+        memcpy(kw + (size_t)(W + nk) * D, kh + a * D, D * 2);
+        memcpy(vw + (size_t)(W + nk) * D, vh + a * D, D * 2);
+        ++nk;
       } else {
-        store_quantized(c, buf, b, hk, a - S, kh + a * D, vh + a * D);
+        store_quantized(c, buf, b, hk, a - nk, kh + a * D, vh + a * D);
       }
     }
     for (int64_t a = first_win; a < T; ++a) {
@@ -376,25 +393,34 @@ int skvq_ref_prefill_quantize(const skvq_ref_config *c, const skvq_ref_buffers *
   return 0;
 }
 
-int skvq_ref_quantize_append(const skvq_ref_config *c, const skvq_ref_buffers *buf,
-                             const uint16_t *k_new, const uint16_t *v_new, int64_t *n_tokens) {
+int skvq_ref_prefill_quantize(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                              const uint16_t *k, const uint16_t *v, int64_t T,
+                              int64_t *n_tokens) {
+  return skvq_ref_prefill_quantize_filtered(c, buf, k, v, T, NULL, n_tokens);
+}
+
+int skvq_ref_quantize_append_filtered(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                                      const uint16_t *k_new, const uint16_t *v_new,
+                                      const uint8_t *keep, int64_t *n_tokens) {
   int rc = check_config(c);
   if (rc) return rc;
   int64_t T = *n_tokens, W = c->window, S = c->n_sink;
-  if (T >= W && T - W >= S && T - W - S >= c->max_quant_tokens) return -3;
+  int64_t a = T - W; /* the token that leaves the window, if a >= 0 */
+  int64_t nk = a >= 0 ? kept_before(c, keep, a) : 0;
+  int keeps = a >= 0 && token_kept(c, keep, a);
+  if (a >= 0 && (keeps ? nk >= S : a - nk >= c->max_quant_tokens)) return -3;
   for (int b = 0; b < c->batch; ++b)
     for (int hk = 0; hk < c->n_kv_heads; ++hk) {
       size_t bh = (size_t)b * c->n_kv_heads + hk;
       uint16_t *kw = buf->k_win + bh * (size_t)(W + S) * D;
       uint16_t *vw = buf->v_win + bh * (size_t)(W + S) * D;
       size_t slot = (size_t)(T % W);
-      if (T >= W) { /* the slot holds token T-W, which now leaves the window */
-        int64_t a = T - W;
-        if (a < S) {
-          memcpy(kw + (size_t)(W + a) * D, kw + slot * D, D * 2);
-          memcpy(vw + (size_t)(W + a) * D, vw + slot * D, D * 2);
+      if (a >= 0) { /* the slot holds token T-W, which now leaves the window */
+        if (keeps) {
+          memcpy(kw + (size_t)(W + nk) * D, kw + slot * D, D * 2);
+          memcpy(vw + (size_t)(W + nk) * D, vw + slot * D, D * 2);
         } else {
-          store_quantized(c, buf, b, hk, a - S, kw + slot * D, vw + slot * D);
+          store_quantized(c, buf, b, hk, a - nk, kw + slot * D, vw + slot * D);
         }
       }
       memcpy(kw + slot * D, k_new + bh * D, D * 2);
@@ -404,19 +430,46 @@ int skvq_ref_quantize_append(const skvq_ref_config *c, const skvq_ref_buffers *b
   return 0;
 }
 
+int skvq_ref_quantize_append(const skvq_ref_config *c, const skvq_ref_buffers *buf,
+                             const uint16_t *k_new, const uint16_t *v_new, int64_t *n_tokens) {
+  return skvq_ref_quantize_append_filtered(c, buf, k_new, v_new, NULL, n_tokens);
+}
+
 /* ---------------------------------------------------- decode attention --- */
 
 /* Attention of n_new query tokens per sequence, the last n_new cached tokens being theirs
  * (Algorithm 1 with l = n_new): query token j sees the cached tokens 0 .. T - n_new + j.
  * q, out: [B][n_new][Hq][D]. */
-static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, int64_t T,
+static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, int64_t T, const uint8_t *keep,
                        const uint16_t *q, int n_new, float *out_f32, uint16_t *out_f16) {
   int rc = check_config(c);
   if (rc) return rc;
   if (T <= 0) return -4;
   int64_t W = c->window, S = c->n_sink, first_win = T > W ? T - W : 0;
   if (n_new < 1 || n_new > T - first_win) return -1; /* the new tokens are all in the window */
-  int64_t n_sink = first_win < S ? first_win : S; /* sink tokens present */
+  /* where each token older than the window lives: its row of the fp16 buffers (kept) or its
+   * packed row */
+  int64_t *fp_row = (int64_t *)malloc(sizeof(int64_t) * (size_t)(first_win + 1));
+  int64_t *packed_row = (int64_t *)malloc(sizeof(int64_t) * (size_t)(first_win + 1));
+  if (!fp_row || !packed_row) {
+    free(fp_row);
+    free(packed_row);
+    return -5;
+  }
+  {
+    int64_t nk = 0;
+    for (int64_t a = 0; a < first_win; ++a) {
+      int kept = token_kept(c, keep, a);
+      fp_row[a] = kept ? W + nk : -1;
+      packed_row[a] = kept ? -1 : a - nk;
+      nk += kept;
+    }
+    if (nk > S) {
+      free(fp_row);
+      free(packed_row);
+      return -1;
+    }
+  }
   int G = c->group_size, ng = D / G, rep = c->n_q_heads / c->n_kv_heads;
   size_t tcap = (size_t)c->max_quant_tokens, nblk = (tcap + VBT - 1) / VBT;
   size_t bb = v_block_bytes(c->v_levels);
@@ -441,8 +494,9 @@ static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, in
     const uint16_t *kwin = buf->k_win + head * (size_t)(W + S) * D;
     const uint16_t *vwin = buf->v_win + head * (size_t)(W + S) * D;
     /* scores of packed rows: reordered query . dequantized reordered key */
-    for (int64_t a = n_sink; a < first_win; ++a) {
-      size_t t = (size_t)(a - S);
+    for (int64_t a = 0; a < first_win; ++a) {
+      if (packed_row[a] < 0) continue;
+      size_t t = (size_t)packed_row[a];
       const uint8_t *row = buf->k_codes + (head * tcap + t) * k_row_bytes(c->k_levels);
       size_t mi = (head * tcap + t) * ng * 2;
       double dot = 0.0;
@@ -454,10 +508,10 @@ static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, in
       }
       s[a] = (double)c->sm_scale * dot;
     }
-    /* scores of sink and ring tokens, original channel order */
+    /* scores of kept and ring tokens, original channel order */
     for (int64_t a = 0; a < Tv; ++a) {
-      if (a >= n_sink && a < first_win) continue;
-      const uint16_t *kw = kwin + (size_t)(a < n_sink ? W + a : a % W) * D;
+      if (a < first_win && fp_row[a] < 0) continue;
+      const uint16_t *kw = kwin + (size_t)(a < first_win ? fp_row[a] : a % W) * D;
       double dot = 0.0;
       for (int ch = 0; ch < D; ++ch) dot += qf[ch] * (double)skvq_ref_half_to_float(kw[ch]);
       s[a] = (double)c->sm_scale * dot;
@@ -467,10 +521,11 @@ static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, in
       if (s[t] > m) m = s[t];
     double denom = 0.0;
     for (int ch = 0; ch < D; ++ch) acc[ch] = 0.0;
-    for (int64_t a = n_sink; a < first_win; ++a) {
+    for (int64_t a = 0; a < first_win; ++a) {
+      if (packed_row[a] < 0) continue;
       double w = exp(s[a] - m);
       denom += w;
-      size_t t = (size_t)(a - S);
+      size_t t = (size_t)packed_row[a];
       const uint8_t *blk = buf->v_codes + (head * nblk + t / VBT) * bb;
       size_t mi = (head * tcap + t) * ng * 2;
       for (int p = 0; p < D; ++p) {
@@ -481,10 +536,10 @@ static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, in
       }
     }
     for (int64_t a = 0; a < Tv; ++a) {
-      if (a >= n_sink && a < first_win) continue;
+      if (a < first_win && fp_row[a] < 0) continue;
       double w = exp(s[a] - m);
       denom += w;
-      const uint16_t *vw = vwin + (size_t)(a < n_sink ? W + a : a % W) * D;
+      const uint16_t *vw = vwin + (size_t)(a < first_win ? fp_row[a] : a % W) * D;
       for (int ch = 0; ch < D; ++ch) acc[ch] += w * (double)skvq_ref_half_to_float(vw[ch]);
     }
     for (int ch = 0; ch < D; ++ch) {
@@ -494,18 +549,26 @@ static int decode_rows(const skvq_ref_config *c, const skvq_ref_buffers *buf, in
     }
     free(s);
   }
+  free(fp_row);
+  free(packed_row);
   return fail ? -5 : 0;
 }
 
 int skvq_ref_decode_attention(const skvq_ref_config *c, const skvq_ref_buffers *buf,
                               int64_t T, const uint16_t *q, float *out_f32, uint16_t *out_f16) {
-  return decode_rows(c, buf, T, q, 1, out_f32, out_f16);
+  return decode_rows(c, buf, T, NULL, q, 1, out_f32, out_f16);
+}
+
+int skvq_ref_decode_attention_filtered(const skvq_ref_config *c, const skvq_ref_buffers *buf, int64_t T,
+                                       const uint8_t *keep, const uint16_t *q, int n_new, float *out_f32,
+                                       uint16_t *out_f16) {
+  return decode_rows(c, buf, T, keep, q, n_new, out_f32, out_f16);
 }
 
 int skvq_ref_decode_attention_multi(const skvq_ref_config *c, const skvq_ref_buffers *buf,
                                     int64_t T, const uint16_t *q, int n_new, float *out_f32,
                                     uint16_t *out_f16) {
-  return decode_rows(c, buf, T, q, n_new, out_f32, out_f16);
+  return decode_rows(c, buf, T, NULL, q, n_new, out_f32, out_f16);
 }
 
 /* ---------------------------------------------------- prefill attention --- */

@@ -139,6 +139,24 @@ int skvq_ref_decode_attention(const skvq_ref_config *cfg, const skvq_ref_buffers
                               int64_t n_tokens, const uint16_t *q, float *out_f32,
                               uint16_t *out_f16);
 
+/* The same three steps with the filter rules of Section 3.2 / Algorithm 1 ("for filter in F")
+ * given as a mask over the tokens that have left the window: keep[a] != 0 keeps token a in full
+ * precision.  The kept tokens take the rows W, W+1, ... of the fp16 buffers in token order
+ * (at most S = n_sink of them: -3 beyond), the others the packed rows 0, 1, ... in token
+ * order.  keep == NULL is the attention-sink rule (a < S), i.e. the functions above.
+ * prefill: keep covers tokens 0 .. T-W-1.  append: keep covers tokens 0 .. n_tokens-W (the last
+ * entry is the decision for the token that leaves now).  decode: keep covers 0 .. T-W-1;
+ * n_new query tokens as in skvq_ref_decode_attention_multi.                              */
+int skvq_ref_prefill_quantize_filtered(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                                       const uint16_t *k, const uint16_t *v, int64_t T,
+                                       const uint8_t *keep, int64_t *n_tokens);
+int skvq_ref_quantize_append_filtered(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                                      const uint16_t *k_new, const uint16_t *v_new,
+                                      const uint8_t *keep, int64_t *n_tokens);
+int skvq_ref_decode_attention_filtered(const skvq_ref_config *cfg, const skvq_ref_buffers *buf,
+                                       int64_t n_tokens, const uint8_t *keep, const uint16_t *q,
+                                       int n_new, float *out_f32, uint16_t *out_f16);
+
 /* Several query tokens at once (Algorithm 1 with l = n_new > 1 on a non-empty
  * cache): the last n_new cached tokens are the new ones (they have been
  * appended, and all still sit in the fp16 window: n_new <= min(T, W)); query

@@ -79,6 +79,12 @@ def lib():
                                                   C.c_void_p]
         _lib.skvq_ref_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                                    C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_prefill_quantize_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                            C.c_int64, C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_quantize_append_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                           C.c_void_p, C.c_void_p]
+        _lib.skvq_ref_decode_attention_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                                            C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         _lib.skvq_ref_calibrate_clip.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                                  C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                                  C.c_void_p, C.c_void_p, C.c_void_p]
@@ -210,6 +216,7 @@ class OracleCache:
         assert [a.nbytes for a in self.arrays()] == self.sizes, (self.sizes, heads)
         self.buf = _Buffers(*[_ptr(a) for a in self.arrays()])
         self.n_tokens = 0
+        self.keep = None     # filter mask over the tokens that have left the window (None: the sink rule a < S)
         self.window = window
         self.n_sink = n_sink
         self.shape = (batch, n_q_heads, n_kv_heads)
@@ -219,9 +226,38 @@ class OracleCache:
 
     @property
     def n_quant(self) -> int:
-        return max(self.n_tokens - self.window - self.n_sink, 0)
+        left = max(self.n_tokens - self.window, 0)
+        if self.keep is not None:
+            return left - int(np.count_nonzero(self.keep[:left]))
+        return max(left - self.n_sink, 0)
 
-    def prefill(self, k: np.ndarray, v: np.ndarray) -> int:
+    def _keep_array(self, n: int) -> np.ndarray:
+        """The mask as a contiguous uint8 array of at least n (and at least one) entries."""
+        a = np.zeros(max(n, 1), np.uint8)
+        a[:len(self.keep)] = self.keep[:len(a)]
+        return a
+
+    def prefill(self, k: np.ndarray, v: np.ndarray, keep=None) -> int:
+        """keep (optional): one entry per token older than the window, nonzero = kept in fp16 (a filter rule's
+        decision); without it the first n_sink tokens are kept."""
+        if keep is not None:
+            b, _, hk = self.shape
+            T = k.shape[2]
+            keep = np.asarray(keep).astype(bool).astype(np.uint8)
+            assert keep.shape == (max(T - self.window, 0),)
+            k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)
+            old = self.keep
+            self.keep = keep.copy()
+            n = C.c_int64(0)
+            km = self._keep_array(len(keep))   # (kept alive across the call)
+            rc = lib().skvq_ref_prefill_quantize_filtered(C.byref(self.cfg), C.byref(self.buf), _ptr(k), _ptr(v), T,
+                                                          _ptr(km), C.byref(n))
+            if rc == 0:
+                self.n_tokens = n.value
+            else:
+                self.keep = old
+            return rc
+        self.keep = None
         b, _, hk = self.shape
         assert k.dtype == np.float16 and v.dtype == np.float16
         assert k.shape == v.shape and k.shape[:2] == (b, hk) and k.shape[3] == HEAD_DIM
@@ -234,12 +270,29 @@ class OracleCache:
             self.n_tokens = n.value
         return rc
 
-    def append(self, k_new: np.ndarray, v_new: np.ndarray) -> int:
+    def append(self, k_new: np.ndarray, v_new: np.ndarray, keep=None) -> int:
+        """keep (optional): the filter rules' decision for the token that leaves the window in this step."""
         b, _, hk = self.shape
         assert k_new.dtype == np.float16 and k_new.shape == (b, hk, HEAD_DIM) == v_new.shape
         k_new = np.ascontiguousarray(k_new)
         v_new = np.ascontiguousarray(v_new)
         n = C.c_int64(self.n_tokens)
+        if keep is not None or self.keep is not None:
+            left = max(self.n_tokens - self.window, 0)
+            mask = self.keep if self.keep is not None else (np.arange(left) < self.n_sink).astype(np.uint8)
+            leaving = self.n_tokens >= self.window
+            if leaving:
+                decision = bool(keep) if keep is not None else False
+                mask = np.concatenate([mask[:left], np.array([decision], np.uint8)])
+            old, self.keep = self.keep, mask
+            km = self._keep_array(len(mask))
+            rc = lib().skvq_ref_quantize_append_filtered(C.byref(self.cfg), C.byref(self.buf), _ptr(k_new),
+                                                         _ptr(v_new), _ptr(km), C.byref(n))
+            if rc == 0:
+                self.n_tokens = n.value
+            else:
+                self.keep = old
+            return rc
         rc = lib().skvq_ref_quantize_append(C.byref(self.cfg), C.byref(self.buf), _ptr(k_new),
                                             _ptr(v_new), C.byref(n))
         if rc == 0:
@@ -252,8 +305,14 @@ class OracleCache:
         q = np.ascontiguousarray(q)
         out = np.zeros((b, hq, HEAD_DIM), np.float32)
         out16 = np.zeros((b, hq, HEAD_DIM), np.float16) if want_f16 else None
-        rc = lib().skvq_ref_decode_attention(C.byref(self.cfg), C.byref(self.buf), self.n_tokens,
-                                             _ptr(q), _ptr(out), _ptr(out16) if want_f16 else None)
+        if self.keep is not None:
+            km = self._keep_array(len(self.keep))
+            rc = lib().skvq_ref_decode_attention_filtered(C.byref(self.cfg), C.byref(self.buf), self.n_tokens,
+                                                          _ptr(km), _ptr(q), 1, _ptr(out),
+                                                          _ptr(out16) if want_f16 else None)
+        else:
+            rc = lib().skvq_ref_decode_attention(C.byref(self.cfg), C.byref(self.buf), self.n_tokens,
+                                                 _ptr(q), _ptr(out), _ptr(out16) if want_f16 else None)
         if rc != 0:
             raise RuntimeError(f"oracle decode failed: {rc}")
         return (out, out16) if want_f16 else out
@@ -264,8 +323,13 @@ class OracleCache:
         assert q.dtype == np.float16 and q.ndim == 4 and q.shape[0] == b and q.shape[2:] == (hq, HEAD_DIM)
         q = np.ascontiguousarray(q)
         out = np.zeros(q.shape, np.float32)
-        rc = lib().skvq_ref_decode_attention_multi(C.byref(self.cfg), C.byref(self.buf), self.n_tokens, _ptr(q),
-                                                   q.shape[1], _ptr(out), None)
+        if self.keep is not None:
+            km = self._keep_array(len(self.keep))
+            rc = lib().skvq_ref_decode_attention_filtered(C.byref(self.cfg), C.byref(self.buf), self.n_tokens,
+                                                          _ptr(km), _ptr(q), q.shape[1], _ptr(out), None)
+        else:
+            rc = lib().skvq_ref_decode_attention_multi(C.byref(self.cfg), C.byref(self.buf), self.n_tokens, _ptr(q),
+                                                       q.shape[1], _ptr(out), None)
         if rc != 0:
             raise RuntimeError(f"oracle multi-token decode failed: {rc}")
         return out

@@ -607,6 +607,116 @@ def test_lossy_cache_with_sinks_equals_dequantize_then_textbook_attention(oracle
     assert np.abs(out - want).max() < 1e-3 * np.abs(want).max()
 
 
+# ---- general filter rules: any mask over the tokens that leave the window (Algorithm 1, "for filter in F") ----
+
+def test_filter_mask_of_the_first_tokens_is_the_sink_rule(oracle):
+    """keep[a] = (a < S) through the general entry points: buffers and outputs identical to the sink rule's,
+    at prefill and over appends."""
+    rng = np.random.default_rng(630)
+    B, Hq, Hk, W, T, S = 2, 4, 2, 8, 40, 3
+    k = (rng.standard_normal((B, Hk, T + 20, D)) * 3).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T + 20, D)) * 3).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, 2), 0.9, np.float32)
+    a = oracle.OracleCache(B, Hq, Hk, 64, 1.5, W, 64, pk, pv, clip, clip, n_sink=S)
+    b = oracle.OracleCache(B, Hq, Hk, 64, 1.5, W, 64, pk, pv, clip, clip, n_sink=S)
+    assert a.prefill(k[:, :, :T], v[:, :, :T]) == 0
+    assert b.prefill(k[:, :, :T], v[:, :, :T], keep=np.arange(T - W) < S) == 0
+    for t in range(T, T + 20):
+        kn, vn = np.ascontiguousarray(k[:, :, t]), np.ascontiguousarray(v[:, :, t])
+        assert a.append(kn, vn) == 0 and b.append(kn, vn, keep=False) == 0
+    assert a.n_quant == b.n_quant
+    for x, y in zip(a.arrays(), b.arrays()):
+        assert np.array_equal(x, y)
+    assert np.array_equal(a.decode(q), b.decode(q))
+
+
+def test_filter_mask_packed_rows_are_the_unkept_tokens_in_order(oracle):
+    """A random mask: the packed region equals what a cache without kept rows stores for the sequence with the
+    kept tokens taken out; kept row j is the j-th kept token bit for bit; more kept tokens than rows is refused."""
+    rng = np.random.default_rng(631)
+    B, Hq, Hk, W, T, S = 1, 2, 2, 8, 70, 9
+    k = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, 1), 0.9, np.float32)
+    keep = np.zeros(T - W, bool)
+    keep[[0, 1, 17, 18, 40, 61]] = True
+    for v_bits, k_bits in ((1.5, 2.0), (4.0, 4.0)):
+        a = oracle.OracleCache(B, Hq, Hk, 128, v_bits, W, 64, pk, pv, clip, clip, n_sink=S, k_bits=k_bits)
+        b = oracle.OracleCache(B, Hq, Hk, 128, v_bits, W, 64, pk, pv, clip, clip, k_bits=k_bits)
+        rest = np.concatenate([np.flatnonzero(~keep), np.arange(T - W, T)])
+        assert a.prefill(k, v, keep=keep) == 0 and b.prefill(k[:, :, rest], v[:, :, rest]) == 0
+        assert a.n_quant == b.n_quant == T - W - 6
+        for x, y in zip(a.arrays()[:4], b.arrays()[:4]):
+            assert np.array_equal(x, y)
+        for j, t in enumerate(np.flatnonzero(keep)):
+            assert np.array_equal(a.k_win[:, :, W + j].view(np.float16), k[:, :, t])
+            assert np.array_equal(a.v_win[:, :, W + j].view(np.float16), v[:, :, t])
+    too_many = np.zeros(T - W, bool)
+    too_many[:S + 1] = True
+    assert a.prefill(k, v, keep=too_many) == -3
+
+
+@pytest.mark.parametrize("v_bits,G", [(1.5, 128), (2.0, 32)])
+def test_filter_mask_attention_equals_dequantize_then_textbook_attention(oracle, v_bits, G):
+    """Kept tokens exact, the others decoded independently from the format statement, the window exact; also
+    through appends with per-step decisions, and for several query tokens."""
+    rng = np.random.default_rng(632 + G)
+    B, Hq, Hk, W, T0, n_app, S = 2, 4, 2, 8, 30, 25, 12
+    T = T0 + n_app
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1, 1, (1, Hk, 1, D))).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    ck = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    cv = rng.uniform(0.8, 1.0, (Hk, D // G)).astype(np.float32)
+    keep = rng.random(T - W) < 0.2
+    keep[T0 - W] = True              # the first token that an append moves out is kept
+    assert keep.sum() <= S
+    c = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S)
+    assert c.prefill(k[:, :, :T0], v[:, :, :T0], keep=keep[:T0 - W]) == 0
+    for t in range(T0, T):
+        assert c.append(np.ascontiguousarray(k[:, :, t]), np.ascontiguousarray(v[:, :, t]), keep=keep[t - W]) == 0
+    # the same cache state from one prefill with the whole mask
+    d = oracle.OracleCache(B, Hq, Hk, G, v_bits, W, 64, pk, pv, ck, cv, n_sink=S)
+    assert d.prefill(k, v, keep=keep) == 0
+    for x, y in zip(c.arrays(), d.arrays()):
+        assert np.array_equal(x, y)
+    n_packed = int((~keep).sum())
+    assert c.n_quant == n_packed
+    kq, vq = numpy_dequantize(c, n_packed + W)
+    f64 = np.float64
+    kept_ids = np.flatnonzero(keep)
+    kfull = np.concatenate([k[:, :, kept_ids].astype(f64), kq, k[:, :, T - W:].astype(f64)], axis=2)
+    vfull = np.concatenate([v[:, :, kept_ids].astype(f64), vq, v[:, :, T - W:].astype(f64)], axis=2)
+    assert kfull.shape[2] == T
+    ref = sdpa64(q, kfull, vfull, 1 / np.sqrt(D))
+    assert np.abs(c.decode(q) - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    # two query tokens: the last one is the single-token call, the first one does not see the newest token
+    q2 = np.stack([rng.standard_normal((B, Hq, D)).astype(np.float16), q], axis=1)
+    out2 = c.decode_multi(q2)
+    assert np.abs(out2[:, 1] - c.decode(q)).max() < 1e-6
+    ref0 = sdpa64(q2[:, 0], kfull[:, :, :T - 1], vfull[:, :, :T - 1], 1 / np.sqrt(D))
+    assert np.abs(out2[:, 0] - ref0).max() < 1e-5 * max(1.0, np.abs(ref0).max())
+
+
+def test_filter_mask_that_keeps_everything_gives_textbook_attention(oracle):
+    rng = np.random.default_rng(634)
+    B, Hq, Hk, W, T = 1, 4, 2, 8, 24
+    k = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    v = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    c = oracle.OracleCache(B, Hq, Hk, 128, 1.5, W, 4, random_perms(rng, Hk), random_perms(rng, Hk),
+                           np.full((Hk, 1), 0.9, np.float32), np.full((Hk, 1), 0.9, np.float32), n_sink=T - W)
+    assert c.prefill(k, v, keep=np.ones(T - W, bool)) == 0 and c.n_quant == 0
+    assert np.abs(c.decode(q) - sdpa64(q, k, v, 1 / np.sqrt(D))).max() < 2e-6
+    # the kept rows are full: the next token to leave can only be packed
+    x = np.zeros((B, Hk, D), np.float16)
+    assert c.append(x, x, keep=True) == -3 and c.append(x, x, keep=False) == 0 and c.n_quant == 1
+
+
 def test_prefill_then_appends_equals_one_longer_prefill_with_sinks(oracle):
     """Appends walk tokens through all three places: ring -> sink rows (the first S) -> packed."""
     rng = np.random.default_rng(620)
