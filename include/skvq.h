@@ -160,6 +160,29 @@ void skvq_destroy(skvq_cache *cache);
 int skvq_prefill_quantize(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
                           void *hip_stream);
 
+/* The filter rules of Section 3.2 / Algorithm 1 ("for filter in F": tokens that a filter selects
+ * keep full precision when they slide out of the window) as the caller's own decisions.  The
+ * cache has n_sink rows of fp16 storage for kept tokens; the attention-sink rule of the entry
+ * points without "_filtered" fills them with the first n_sink tokens.  Here the caller decides
+ * token by token: a kept token takes the next free fp16 row (the j-th kept token row W + j of
+ * k_win / v_win), every other token the next packed row, both in token order.  Attention reads
+ * kept rows like window rows.  A cache may be driven with either set of entry points (the
+ * sink rule then means: keep token a if a < n_sink and a row is free).
+ *
+ * skvq_prefill_quantize_filtered: as skvq_prefill_quantize; keep: HOST array, one byte per token
+ * older than the window (tokens 0 .. n_tokens - W - 1), nonzero = keep; NULL = the sink rule.
+ * SKVQ_ERR_CAPACITY if more than n_sink tokens are kept or the others exceed Tcap;
+ * SKVQ_ERR_UNSUPPORTED for n_tokens >= 2^31 with a mask.  Copies the kept tokens' numbers to
+ * the device before it returns (a synchronous copy of at most n_sink integers).
+ *
+ * skvq_quantize_append_filtered: as skvq_quantize_append; keep_leaving != 0 keeps the token that
+ * leaves the window in this step (ignored while the window is not full).  SKVQ_ERR_CAPACITY if
+ * no fp16 row (or no packed row) is free; the cache is unchanged then. */
+int skvq_prefill_quantize_filtered(skvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                                   const uint8_t *keep, void *hip_stream);
+int skvq_quantize_append_filtered(skvq_cache *cache, const void *k_new, const void *v_new,
+                                  int32_t keep_leaving, void *hip_stream);
+
 /* Section 3.2 prefill phase, first step ("we first compute attention using full-precision KV
  * cache"; Algorithm 1 with h = 0, l = len(prompt)): causal softmax attention of the prompt on
  * the fp16 inputs, original channel order, fp32 accumulation: query t of head hq sees keys

@@ -282,7 +282,8 @@ class OracleCache:
             mask = self.keep if self.keep is not None else (np.arange(left) < self.n_sink).astype(np.uint8)
             leaving = self.n_tokens >= self.window
             if leaving:
-                decision = bool(keep) if keep is not None else False
+                # without a decision: the sink rule (keep token a if a < S and a row is free)
+                decision = bool(keep) if keep is not None else (left < self.n_sink and int(np.count_nonzero(mask[:left])) < self.n_sink)
                 mask = np.concatenate([mask[:left], np.array([decision], np.uint8)])
             old, self.keep = self.keep, mask
             km = self._keep_array(len(mask))

@@ -64,6 +64,9 @@ def lib() -> C.CDLL:
         L.skvq_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_prefill_quantize_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                                     C.c_void_p]
+        L.skvq_quantize_append_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.skvq_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_append_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                    C.c_void_p, C.c_void_p]
@@ -173,6 +176,7 @@ class SkvqCache:
                                            n_sink=n_sink, meta=meta, group_bounds=group_bounds,
                                            max_new_tokens=max_new_tokens)
         self.shape = (batch, n_q_heads, n_kv_heads)
+        self.window = window
         self.device = torch.device(device)
         self.sizes = skvq_sizes(self.cfg)
         self.buffers = {}
@@ -252,6 +256,28 @@ class SkvqCache:
         kp = _dev_ptr(k, torch.float16, (b, hk, T, HEAD_DIM))
         vp = _dev_ptr(v, torch.float16, (b, hk, T, HEAD_DIM))
         self._check(lib().skvq_prefill_quantize(self._h, kp, vp, T, _stream_ptr(stream)))
+
+    def skvq_prefill_quantize_filtered(self, k: torch.Tensor, v: torch.Tensor, keep, stream=None):
+        """keep: one entry per token older than the window (host array-like; nonzero = kept in fp16) or None."""
+        b, _, hk = self.shape
+        T = k.shape[2]
+        kp = _dev_ptr(k, torch.float16, (b, hk, T, HEAD_DIM))
+        vp = _dev_ptr(v, torch.float16, (b, hk, T, HEAD_DIM))
+        mask = None
+        if keep is not None:
+            mask = np.ascontiguousarray(np.asarray(keep).astype(bool).astype(np.uint8))
+            if mask.shape != (max(T - self.window, 0),):
+                raise ValueError("keep must have one entry per token older than the window")
+            if mask.size == 0:
+                mask = np.zeros(1, np.uint8)
+        self._check(lib().skvq_prefill_quantize_filtered(self._h, kp, vp, T, mask.ctypes.data if mask is not None else None,
+                                                         _stream_ptr(stream)))
+
+    def skvq_quantize_append_filtered(self, k_new: torch.Tensor, v_new: torch.Tensor, keep_leaving: bool, stream=None):
+        b, _, hk = self.shape
+        kp = _dev_ptr(k_new, torch.float16, (b, hk, HEAD_DIM))
+        vp = _dev_ptr(v_new, torch.float16, (b, hk, HEAD_DIM))
+        self._check(lib().skvq_quantize_append_filtered(self._h, kp, vp, 1 if keep_leaving else 0, _stream_ptr(stream)))
 
     def skvq_quantize_append(self, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
         b, _, hk = self.shape

@@ -17,6 +17,8 @@ using namespace skvq;
 struct skvq_cache {
   Layout L;
   long long n_tokens = 0;
+  long long n_kept = 0;  // tokens older than the window that the filter rules keep in fp16 (<= L.S)
+  int *dev_kept_ids = nullptr;  // device [S]: their token numbers (written by a prefill with a mask)
   int forced_splits = 0;
   int max_new = 1;  // query tokens per sequence the workspace was sized for
   int n_cus = 256;
@@ -100,6 +102,25 @@ void compute_sizes(const skvq_config *c, size_t bytes[7]) {
 int fail_hip(skvq_cache *c, hipError_t e, const char *what) {
   c->last_error = std::string(what) + ": " + hipGetErrorString(e);
   return SKVQ_ERR_HIP;
+}
+
+// where the cached tokens are now
+Counts counts_now(const skvq_cache *c) { return counts_with(c->n_tokens, c->L.W, c->n_kept); }
+// the sink rule's decision for token a when it leaves the window
+bool sink_rule_keeps(const skvq_cache *c, long long a) { return a < c->L.S && c->n_kept < c->L.S; }
+
+// One append with the filter rules' decision for the token that leaves the window (if any).
+int append_with(skvq_cache *c, const void *k_new, const void *v_new, bool keep, hipStream_t s, const char *what) {
+  const long long T = c->n_tokens;
+  const bool leaves = T >= c->L.W;
+  const Counts n = counts_now(c);
+  if (leaves && (keep ? c->n_kept >= c->L.S : n.n_quant >= c->L.Tcap)) return SKVQ_ERR_CAPACITY;
+  hipError_t e = launch_append(c->L, (const __half *)k_new, (const __half *)v_new, T,
+                               leaves && keep ? (int)c->n_kept : -1, n.n_quant, s);
+  if (e != hipSuccess) return fail_hip(c, e, what);
+  c->n_tokens = T + 1;
+  if (leaves && keep) ++c->n_kept;
+  return SKVQ_OK;
 }
 
 int choose_splits(const skvq_cache *c, long long n_quant, int n_new = 1) {
@@ -204,12 +225,13 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.v_win = (__half *)bufs->v_win;
   L.workspace = (float *)bufs->workspace;
 
-  // constants: [perm_k | perm_v | clip_k | clip_v | gmaps], one allocation
+  // constants: [perm_k | perm_v | clip_k | clip_v | gmaps | kept token numbers], one allocation
   const size_t n_perm = (size_t)L.Hk * kD, n_clip = (size_t)L.Hk * L.NG;
   const size_t off_pv = n_perm * 4, off_ck = off_pv + n_perm * 4;
   const size_t off_cv = off_ck + ((n_clip * 4 + 15) & ~(size_t)15);
   const size_t off_gm = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
-  const size_t total = off_gm + (((size_t)L.Hk * 4 + 15) & ~(size_t)15);
+  const size_t off_ids = off_gm + (((size_t)L.Hk * 4 + 15) & ~(size_t)15);
+  const size_t total = off_ids + (((size_t)L.S * 4 + 15) & ~(size_t)15);
   std::vector<uint8_t> host(total, 0);
   std::memcpy(host.data(), cfg->perm_k, n_perm * 4);
   std::memcpy(host.data() + off_pv, cfg->perm_v, n_perm * 4);
@@ -236,6 +258,7 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.clip_k = (const float *)(d + off_ck);
   L.clip_v = (const float *)(d + off_cv);
   L.gmaps = (const unsigned *)(d + off_gm);
+  c->dev_kept_ids = (int *)(d + off_ids);
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -253,14 +276,41 @@ void skvq_destroy(skvq_cache *c) {
 }
 
 int skvq_prefill_quantize(skvq_cache *c, const void *k, const void *v, int64_t T, void *stream) {
+  return skvq_prefill_quantize_filtered(c, k, v, T, nullptr, stream);
+}
+
+int skvq_prefill_quantize_filtered(skvq_cache *c, const void *k, const void *v, int64_t T, const uint8_t *keep,
+                                   void *stream) {
   if (!c) return SKVQ_ERR_INVALID_ARG;
   if (T < 0 || (T > 0 && (!k || !v))) return SKVQ_ERR_INVALID_ARG;
-  if (counts_of(T, c->L.W, c->L.S).n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  const long long left = T > c->L.W ? T - c->L.W : 0;  // tokens older than the window
+  long long n_kept;
+  const int *ids = nullptr;
+  if (keep) {
+    if (T > 0x7fffffffll) return SKVQ_ERR_UNSUPPORTED;
+    std::vector<int> list;
+    for (long long a = 0; a < left; ++a)
+      if (keep[a]) {
+        if ((long long)list.size() >= c->L.S) return SKVQ_ERR_CAPACITY;
+        list.push_back((int)a);
+      }
+    n_kept = (long long)list.size();
+    if (n_kept > 0) {
+      // (a synchronous copy: the list is gone when this function returns)
+      hipError_t e = hipMemcpy(c->dev_kept_ids, list.data(), list.size() * sizeof(int), hipMemcpyHostToDevice);
+      if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_quantize_filtered copy of the kept tokens");
+      ids = c->dev_kept_ids;
+    }
+  } else {
+    n_kept = left < c->L.S ? left : c->L.S;
+  }
+  if (left - n_kept > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   if (T > 0) {
-    hipError_t e = launch_prefill(c->L, (const __half *)k, (const __half *)v, T, (hipStream_t)stream);
+    hipError_t e = launch_prefill(c->L, (const __half *)k, (const __half *)v, T, n_kept, ids, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_quantize launch");
   }
   c->n_tokens = T;
+  c->n_kept = n_kept;
   return SKVQ_OK;
 }
 
@@ -373,9 +423,9 @@ int skvq_calibrate_clip(skvq_cache *c, const void *k, const void *v, int64_t T, 
         for (int h = 0; h < L.Hk; ++h) clip[(size_t)h * L.NG + g] = alphas[a];
         rc = upload_clips(c, stream);
         if (rc != SKVQ_OK) break;
-        e = launch_prefill(L, (const __half *)k, (const __half *)v, T, stream);
+        e = launch_prefill(L, (const __half *)k, (const __half *)v, T, cnt.n_sink, nullptr, stream);
         for (int i = 0; i < n_queries && e == hipSuccess; ++i) {
-          e = launch_decode(L, (const __half *)q + (size_t)i * out_n, d_out, nullptr, T, n_splits, 1, stream);
+          e = launch_decode(L, (const __half *)q + (size_t)i * out_n, d_out, nullptr, T, cnt.n_sink, n_splits, 1, stream);
           if (e == hipSuccess)
             e = launch_sqerr(L, d_out, (const float *)o_ref + (size_t)i * out_n,
                              d_err + ((size_t)a * n_queries + i) * slots, stream);
@@ -416,25 +466,27 @@ int skvq_calibrate_clip(skvq_cache *c, const void *k, const void *v, int64_t T, 
   std::memcpy(clip_k_out, c->clip_k.data(), c->clip_k.size() * sizeof(float));
   std::memcpy(clip_v_out, c->clip_v.data(), c->clip_v.size() * sizeof(float));
   c->n_tokens = T;  // the buffers hold the calibration tokens as the last candidate quantized them
+  c->n_kept = cnt.n_sink;
   return SKVQ_OK;
 }
 
 int skvq_quantize_append(skvq_cache *c, const void *k_new, const void *v_new, void *stream) {
   if (!c || !k_new || !v_new) return SKVQ_ERR_INVALID_ARG;
-  const long long T = c->n_tokens;
-  if (counts_of(T + 1, c->L.W, c->L.S).n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
-  hipError_t e = launch_append(c->L, (const __half *)k_new, (const __half *)v_new, T, (hipStream_t)stream);
-  if (e != hipSuccess) return fail_hip(c, e, "skvq_quantize_append launch");
-  c->n_tokens = T + 1;
-  return SKVQ_OK;
+  return append_with(c, k_new, v_new, sink_rule_keeps(c, c->n_tokens - c->L.W), (hipStream_t)stream,
+                     "skvq_quantize_append launch");
+}
+
+int skvq_quantize_append_filtered(skvq_cache *c, const void *k_new, const void *v_new, int32_t keep_leaving,
+                                  void *stream) {
+  if (!c || !k_new || !v_new) return SKVQ_ERR_INVALID_ARG;
+  return append_with(c, k_new, v_new, keep_leaving != 0, (hipStream_t)stream, "skvq_quantize_append_filtered launch");
 }
 
 int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out_f16, void *stream) {
   if (!c || !q || !out_f32) return SKVQ_ERR_INVALID_ARG;
   if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
-  const long long nq = counts_of(c->n_tokens, c->L.W, c->L.S).n_quant;
-  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16,
-                               c->n_tokens, choose_splits(c, nq), 1, (hipStream_t)stream);
+  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, c->n_tokens, c->n_kept,
+                               choose_splits(c, counts_now(c).n_quant), 1, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention launch");
   return SKVQ_OK;
 }
@@ -443,24 +495,26 @@ int skvq_append_decode_attention(skvq_cache *c, const void *k_new, const void *v
                                  void *out_f16, void *stream) {
   if (!c || !k_new || !v_new || !q || !out_f32) return SKVQ_ERR_INVALID_ARG;
   const long long T = c->n_tokens;
-  const long long nq = counts_of(T + 1, c->L.W, c->L.S).n_quant;
+  const bool leaves = T >= c->L.W, keep = leaves && sink_rule_keeps(c, T - c->L.W);
+  const Counts now = counts_now(c);
+  const long long nq = now.n_quant + (leaves && !keep ? 1 : 0);  // packed rows after the step
   if (nq > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   hipStream_t s = (hipStream_t)stream;
   const int n_splits = choose_splits(c, nq);
   // One launch pays when few workgroups do the append (one per kv head, of n_splits): with one or
   // two chunks per kv head every (other) workgroup would wait for its own append, which costs more
   // than the separate launch (measured at 16 sequences x 32 heads x 32k tokens: 240 against 236 us).
-  if (append_fusable(c->L, T + 1) && n_splits >= kMinSplitsForOneLaunch) {
-    hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, T + 1,
+  if (append_fusable(c->L, T + 1, keep) && n_splits >= kMinSplitsForOneLaunch) {
+    hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, T + 1, c->n_kept,
                                  n_splits, 1, s, (const __half *)k_new, (const __half *)v_new);
     if (e != hipSuccess) return fail_hip(c, e, "skvq_append_decode_attention launch");
     c->n_tokens = T + 1;
     return SKVQ_OK;
   }
-  hipError_t e = launch_append(c->L, (const __half *)k_new, (const __half *)v_new, T, s);
-  if (e != hipSuccess) return fail_hip(c, e, "skvq_append_decode_attention launch (append)");
-  c->n_tokens = T + 1;
-  e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, T + 1, n_splits, 1, s);
+  const int rc = append_with(c, k_new, v_new, keep, s, "skvq_append_decode_attention launch (append)");
+  if (rc != SKVQ_OK) return rc;
+  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, T + 1, c->n_kept,
+                               n_splits, 1, s);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_append_decode_attention launch (decode)");
   return SKVQ_OK;
 }
@@ -469,9 +523,9 @@ int skvq_decode_attention_multi(skvq_cache *c, const void *q, int32_t n_new, voi
                                 void *stream) {
   if (!c || !q || !out_f32 || n_new < 1) return SKVQ_ERR_INVALID_ARG;
   if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
-  const Counts n = counts_of(c->n_tokens, c->L.W, c->L.S);
+  const Counts n = counts_now(c);
   if (n_new > c->max_new || n_new > n.n_win) return SKVQ_ERR_INVALID_ARG;
-  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, c->n_tokens,
+  hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, c->n_tokens, c->n_kept,
                                choose_splits(c, n.n_quant, n_new), n_new, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention_multi launch");
   return SKVQ_OK;
@@ -479,7 +533,7 @@ int skvq_decode_attention_multi(skvq_cache *c, const void *q, int32_t n_new, voi
 
 int skvq_get_state(const skvq_cache *c, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win) {
   if (!c) return SKVQ_ERR_INVALID_ARG;
-  const Counts n = counts_of(c->n_tokens, c->L.W, c->L.S);
+  const Counts n = counts_now(c);
   if (n_tokens) *n_tokens = c->n_tokens;
   if (n_quant) *n_quant = n.n_quant;
   if (n_win) *n_win = (int32_t)n.n_win;
@@ -488,8 +542,10 @@ int skvq_get_state(const skvq_cache *c, int64_t *n_tokens, int64_t *n_quant, int
 
 int skvq_set_state(skvq_cache *c, int64_t n_tokens) {
   if (!c || n_tokens < 0) return SKVQ_ERR_INVALID_ARG;
-  if (counts_of(n_tokens, c->L.W, c->L.S).n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  const Counts n = counts_of(n_tokens, c->L.W, c->L.S);  // (the sink rule)
+  if (n.n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   c->n_tokens = n_tokens;
+  c->n_kept = n.n_sink;
   return SKVQ_OK;
 }
 

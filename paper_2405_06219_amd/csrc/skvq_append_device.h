@@ -156,16 +156,16 @@ __device__ __forceinline__ void store_k_row3(uint8_t *row, int lane, unsigned c0
 // Appends one token per (b, hk): wavefront 0 of the calling workgroup does K, wavefront 1 does V
 // (`wave` is the caller's wavefront index; every wavefront of the workgroup must call, the others
 // only keep the barriers).  T is the number of tokens cached before the call.  If the ring is full
-// the slot's old token (number T - W) leaves the window first: a sink token is copied to its sink
-// row, any other is quantized into packed row te = T - W - S.  rows: 2 x 128 halves and vcodes:
-// 128 bytes of LDS.
+// the slot's old token (number T - W) leaves the window first: with keep_row >= 0 (a filter rule
+// keeps it in full precision) it is copied to row W + keep_row of the fp16 buffers, else it is
+// quantized into packed row te.  rows: 2 x 128 halves and vcodes: 128 bytes of LDS.
 __device__ __forceinline__ void append_token(const Layout &L, const __half *__restrict__ knew,
-                                             const __half *__restrict__ vnew, long long T, int hk, int b, int wave,
-                                             int lane, __half (*rows)[kD], uint8_t *vcodes) {
+                                             const __half *__restrict__ vnew, long long T, int keep_row,
+                                             long long te, int hk, int b, int wave, int lane, __half (*rows)[kD],
+                                             uint8_t *vcodes) {
   const long long head = (long long)b * L.Hk + hk;
   const long long slot = (head * (L.W + L.S) + T % L.W) * kD;
-  const bool leaves = T >= L.W, evict = T - L.W >= L.S;  // a token leaves the window; it is packed
-  const long long te = T - L.W - L.S;
+  const bool leaves = T >= L.W, evict = leaves && keep_row < 0;  // a token leaves the window; it is packed
   if (wave >= 2) {  // (a larger workgroup: the other wavefronts only keep the two barriers below)
     if (evict) {
       __syncthreads();
@@ -217,8 +217,8 @@ __device__ __forceinline__ void append_token(const Layout &L, const __half *__re
   }
   // the old token is in registers; the new one may take its slot
   reinterpret_cast<__half2 *>(ring + slot)[lane] = fresh2;
-  if (leaves && !evict)  // an attention sink: kept as it is
-    reinterpret_cast<__half2 *>(ring + (head * (L.W + L.S) + L.W + (T - L.W)) * kD)[lane] = old2;
+  if (leaves && !evict)  // kept as it is
+    reinterpret_cast<__half2 *>(ring + (head * (L.W + L.S) + L.W + keep_row) * kD)[lane] = old2;
   if (!evict) return;
   reinterpret_cast<__half2 *>(rows[wave])[lane] = old2;
   __syncthreads();

@@ -97,14 +97,18 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
 }  // namespace
 
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16, long long T,
-                         int n_splits, int n_new, hipStream_t s, const __half *k_new, const __half *v_new) {
-  const Counts n = counts_of(T, L.W, L.S);
+                         long long n_kept, int n_splits, int n_new, hipStream_t s, const __half *k_new,
+                         const __half *v_new) {
+  const Counts n = counts_with(T, L.W, n_kept);
+  if (n_kept < 0 || n_kept > L.S || n.n_quant < 0 || n.n_quant > L.Tcap) return hipErrorInvalidValue;
   if (L.Hk > 65535 || L.B > 65535 || (long long)L.Hq * n_new > 65535) return hipErrorInvalidValue;
   if (n_new < 1 || n_new > n.n_win) return hipErrorInvalidValue;  // the new tokens are all in the window
   if (n_splits > SKVQ_MAX_SPLITS || (n.n_quant > 0 && n_splits < 1)) return hipErrorInvalidValue;
   if (n_splits < 1) n_splits = 1;  // nothing packed yet: one chunk, fp16 tokens only
-  if (k_new && (n_new != 1 || !append_fusable(L, T))) return hipErrorInvalidValue;
-  hipError_t e = launch_decode_mfma(L, q, T, n.n_quant, (int)n.n_sink, n_splits, n_new, k_new, v_new, s);
+  if (k_new && (n_new != 1 || !append_fusable(L, T, false))) return hipErrorInvalidValue;
+  // (with the new token taken along: the leaving token's packed row is the last one)
+  const long long te = k_new && T - 1 >= L.W ? n.n_quant - 1 : -1;
+  hipError_t e = launch_decode_mfma(L, q, T, n.n_quant, (int)n.n_sink, n_splits, n_new, k_new, v_new, te, s);
   if (e != hipSuccess) return e;
   // the fp16 tokens are folded into the chunks' partials
   hipLaunchKernelGGL(merge_kernel, dim3(L.Hq * n_new, L.B), dim3(1024), 0, s, L, out_f32, out_f16, n_splits,

@@ -9,5 +9,6 @@
 
 namespace skvq {
 template hipError_t launch_decode_mfma_fmt<SKVQ_KL, SKVQ_VL>(const Layout &, const __half *, long long, long long,
-                                                             int, int, int, const __half *, const __half *, hipStream_t);
+                                                             int, int, int, const __half *, const __half *, long long,
+                                                             hipStream_t);
 }  // namespace skvq

@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
                                                                   long long T, long long nq, int n_sink,
                                                                   int n_splits, int passes, int n_new,
                                                                   const __half *__restrict__ knew,
-                                                                  const __half *__restrict__ vnew) {
+                                                                  const __half *__restrict__ vnew, long long te) {
   // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
   // head with more than four (or with three) query heads is served by `passes` workgroups per
   // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   //      load is issued, and no load of the branch is pending where the paths join. ----
   const bool fused = knew != nullptr;
   if (fused && sp == n_splits - 1) {
-    append_token(L, knew, vnew, T - 1, hk, b, wave, lane, reinterpret_cast<__half(*)[kD]>(&sm.ring_o[0][0][0]),
+    append_token(L, knew, vnew, T - 1, -1, te, hk, b, wave, lane, reinterpret_cast<__half(*)[kD]>(&sm.ring_o[0][0][0]),
                  reinterpret_cast<uint8_t *>(&sm.ring_o[0][0][0]) + 2 * kD * sizeof(__half));
     __threadfence_block();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (the fence alone need not wait for the stores)
@@ -979,7 +979,8 @@ extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
 // The launcher of the kernels with KL-level keys and VL-level values.
 template <int KL, int VL>
 hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
-                                  int n_splits, int n_new, const __half *knew, const __half *vnew, hipStream_t s) {
+                                  int n_splits, int n_new, const __half *knew, const __half *vnew, long long te,
+                                  hipStream_t s) {
   if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
@@ -987,10 +988,11 @@ hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T,
   const int n_rows = n_new * L.R;
   const int passes = decode_passes(n_rows), rk = n_rows == 1 ? 1 : n_rows == 2 ? 2 : 4;
   if ((knew != nullptr) != (vnew != nullptr) || (knew && (passes != 1 || n_new != 1))) return hipErrorInvalidValue;
+  if (knew && T - 1 >= L.W && (te < 0 || te >= L.Tcap || te != nq - 1)) return hipErrorInvalidValue;
   if ((long long)L.Hk * passes > 65535) return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
 #define SKVQ_LAUNCH(RR, MM, GG, UU) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew, te)
 #define SKVQ_LAUNCH_NG(RR, MM)                                                                   \
   switch (L.NG) {                                                                                \
     case 1: SKVQ_LAUNCH(RR, MM, 1, false); break;                                                \

@@ -56,6 +56,15 @@ struct Layout {
 struct Counts {
   long long n_win, n_sink, n_quant;
 };
+// ... with n_kept tokens kept in full precision by the filter rules (whichever they are)
+inline Counts counts_with(long long T, int W, long long n_kept) {
+  Counts c;
+  c.n_win = T < W ? T : W;
+  c.n_sink = n_kept;
+  c.n_quant = T - c.n_win - n_kept;
+  return c;
+}
+// ... under the attention-sink rule (the first S tokens are kept)
 inline Counts counts_of(long long T, int W, int S) {
   Counts c;
   c.n_win = T < W ? T : W;
@@ -66,10 +75,15 @@ inline Counts counts_of(long long T, int W, int S) {
 }
 
 // quantize kernels (skvq_quantize.hip)
-hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T,
-                          hipStream_t s);
-hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T,
-                         hipStream_t s);
+// n_kept: tokens older than the window that the filter rules keep in fp16 (rows W .. of the fp16
+// buffers); kept_ids: device list of their token numbers, ascending, or null for the sink rule
+// (tokens 0 .. n_kept-1).
+hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T, long long n_kept,
+                          const int *kept_ids, hipStream_t s);
+// T: tokens cached before.  The token that leaves the window (if T >= W) goes to fp16 row
+// W + keep_row if keep_row >= 0, else to packed row te.
+hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T, int keep_row,
+                         long long te, hipStream_t s);
 
 // prefill attention (skvq_prefill_attn.hip): causal attention of the prompt on fp16 q, k, v
 hipError_t launch_prefill_attention(const Layout &L, const __half *q, const __half *k, const __half *v,
@@ -88,11 +102,13 @@ int reorder_channels(const float *stats, int Hk, int G, int gran, int max_iter, 
 // decode kernels (skvq_decode.hip)
 // n_splits: chunks of the packed region per kv head (>= 1 when n_quant > 0).
 // n_new: query tokens per sequence (q, out: [B][n_new][Hq][D]); the last n_new cached tokens are theirs.
+// n_kept: tokens kept in fp16 by the filter rules, of the T cached ones.
 // k_new, v_new (both or neither): the newest of the T tokens is not in the cache yet, the chunk
-// kernel appends it on the way (see append_fusable).
+// kernel appends it on the way (see append_fusable); the token that leaves the window, if any, is
+// packed (n_kept is the same before and after).
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16,
-                         long long T, int n_splits, int n_new, hipStream_t s, const __half *k_new = nullptr,
-                         const __half *v_new = nullptr);
+                         long long T, long long n_kept, int n_splits, int n_new, hipStream_t s,
+                         const __half *k_new = nullptr, const __half *v_new = nullptr);
 
 // Matrix-core chunk kernel (skvq_decode_mfma.hip): packed chunks and the fp16 tokens (n_sink sink
 // rows, then the window's T - nq - n_sink ring tokens); writes partials 0..n_splits-1 (n_splits
@@ -100,17 +116,18 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
 // kv heads with 5..8 query heads are read by two workgroups per chunk.
 // (n_rows = query heads per kv head x query tokens)
 inline int decode_passes(int n_rows) { return n_rows > 4 ? (n_rows + 3) / 4 : 1; }
+// te: with knew / vnew, the packed row of the token that leaves the window.
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
-                              int n_splits, int n_new, const __half *knew, const __half *vnew, hipStream_t s);
+                              int n_splits, int n_new, const __half *knew, const __half *vnew, long long te,
+                              hipStream_t s);
 // Whether the decode of T_after tokens (one query token) may append the newest token itself: one
 // workgroup per chunk (at most four query heads per kv head), and the token that leaves the
 // window, if any, is packed rather than copied to a sink row (a sink row has other readers in
 // the same launch).
 constexpr int kMinSplitsForOneLaunch = 4;  // chunks per kv head from which the one-launch step is used
-inline bool append_fusable(const Layout &L, long long T_after) {
+inline bool append_fusable(const Layout &L, long long T_after, bool leaving_token_is_kept) {
   const long long T = T_after - 1;  // tokens cached before
-  const bool leaves = T >= L.W, evict = T - L.W >= L.S;
-  return decode_passes(L.R) == 1 && !(leaves && !evict);
+  return decode_passes(L.R) == 1 && !(T >= L.W && leaving_token_is_kept);
 }
 constexpr int kMfmaWavesPerGroup = 8;  // wavefronts per workgroup of the matrix-core kernel
 

@@ -118,7 +118,8 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
 template <int KL, int VL>  // levels of the key and value codes
 __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
-                                                      long long nq) {
+                                                      long long nq, int n_kept,
+                                                      const int *__restrict__ kept_ids) {
   __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
   __shared__ unsigned vq[VL == 16 ? 1 : 4][8][8];             // [wave][token i][n]: 16 codes, j-minor
   __shared__ unsigned vqtop[VL == 8 ? 4 : 1][8][8];           // 3-bit codes: their top bits, j-minor
@@ -132,11 +133,23 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   const long long blk = blockIdx.x;
   const long long t0 = blk * kVBlock + 8 * wave;
 
-  // Source rows (packed row r is token r + S); rows past the end of the prompt are replaced by
+  // Source rows: packed row r is the r-th token that no filter rule keeps.  With the sink rule
+  // (kept_ids == null) the first n_kept tokens are the kept ones: token r + n_kept.  With a list
+  // of kept tokens (ascending) token r + (number of j with kept_ids[j] - j <= r); that difference
+  // does not decrease with j: binary search.  Rows past the end of the prompt are replaced by
   // its last row and never stored.
+  auto token_of = [&](long long r) {
+    if (!kept_ids) return r + n_kept;
+    int lo = 0, hi = n_kept;  // the count lies in [lo, hi]
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if ((long long)kept_ids[mid] - mid <= r) lo = mid + 1; else hi = mid;
+    }
+    return r + lo;
+  };
   {
     const int lr = lane >> 4, lp = lane & 15;
-    long long ta = t0 + L.S + lr, tb = t0 + L.S + 4 + lr;
+    long long ta = token_of(t0 + lr), tb = token_of(t0 + 4 + lr);
     ta = ta < T ? ta : T - 1;
     tb = tb < T ? tb : T - 1;
     const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + head * T * kD);
@@ -270,13 +283,16 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
 }
 
 // Copies the tokens of the prompt that stay fp16: the last n_win into the ring (token a -> row
-// a % W) and the first n_sink into the sink rows (token a -> row W + a).
+// a % W) and the kept ones into the rows after the ring (the j-th kept token -> row W + j; it is
+// token kept_ids[j], or token j under the sink rule, kept_ids == null).
 __global__ __launch_bounds__(64) void ring_fill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
-                                                      long long first_win, int n_win) {
+                                                      long long first_win, int n_win,
+                                                      const int *__restrict__ kept_ids) {
   const bool sink = (int)blockIdx.x >= n_win;
-  const long long a = sink ? (long long)blockIdx.x - n_win : first_win + blockIdx.x;
-  const long long row = sink ? L.W + a : a % L.W;
+  const long long j = (long long)blockIdx.x - n_win;
+  const long long a = sink ? (kept_ids ? (long long)kept_ids[j] : j) : first_win + blockIdx.x;
+  const long long row = sink ? L.W + j : a % L.W;
   const long long head = (long long)blockIdx.z * L.Hk + blockIdx.y;
   const long long src = (head * T + a) * kD, dst = (head * (L.W + L.S) + row) * kD;
   const int lane = threadIdx.x;
@@ -286,21 +302,25 @@ __global__ __launch_bounds__(64) void ring_fill_kernel(Layout L, const __half *_
 
 // Append: one workgroup of two wavefronts per (b, hk) (skvq_append_device.h).
 __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__restrict__ knew,
-                                                     const __half *__restrict__ vnew, long long T) {
+                                                     const __half *__restrict__ vnew, long long T, int keep_row,
+                                                     long long te) {
   __shared__ __half rows[2][kD];
   __shared__ uint8_t vcodes[kD];
-  append_token(L, knew, vnew, T, blockIdx.x, blockIdx.y, threadIdx.x >> 6, threadIdx.x & 63, rows, vcodes);
+  append_token(L, knew, vnew, T, keep_row, te, blockIdx.x, blockIdx.y, threadIdx.x >> 6, threadIdx.x & 63, rows,
+               vcodes);
 }
 
 }  // namespace
 
-hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T, hipStream_t s) {
-  const Counts n = counts_of(T, L.W, L.S);
+hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, long long T, long long n_kept,
+                          const int *kept_ids, hipStream_t s) {
+  const Counts n = counts_with(T, L.W, n_kept);
+  if (n_kept < 0 || n_kept > L.S || n.n_quant < 0) return hipErrorInvalidValue;
   if (n.n_quant > 0) {
     const long long nblk = (n.n_quant + kVBlock - 1) / kVBlock;
     if (nblk > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nblk, L.Hk, L.B), block(256);
-#define SKVQ_PREFILL(KL, VL) hipLaunchKernelGGL((prefill_kernel<KL, VL>), grid, block, 0, s, L, k, v, T, n.n_quant)
+#define SKVQ_PREFILL(KL, VL) hipLaunchKernelGGL((prefill_kernel<KL, VL>), grid, block, 0, s, L, k, v, T, n.n_quant, (int)n_kept, kept_ids)
     if (L.k_levels == 8) {
       if (L.v_levels != 8) return hipErrorInvalidValue;
       SKVQ_PREFILL(8, 8);
@@ -321,15 +341,16 @@ hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, lon
   if (n_fp > 0) {
     if (L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
     hipLaunchKernelGGL(ring_fill_kernel, dim3((unsigned)n_fp, L.Hk, L.B), dim3(64), 0, s, L, k, v, T, T - n.n_win,
-                       (int)n.n_win);
+                       (int)n.n_win, kept_ids);
     return hipGetLastError();
   }
   return hipSuccess;
 }
 
-hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T, hipStream_t s) {
-  if (L.B > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(append_kernel, dim3(L.Hk, L.B), dim3(128), 0, s, L, k_new, v_new, T);
+hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T, int keep_row,
+                         long long te, hipStream_t s) {
+  if (L.B > 65535 || keep_row >= L.S || (T >= L.W && keep_row < 0 && (te < 0 || te >= L.Tcap))) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(append_kernel, dim3(L.Hk, L.B), dim3(128), 0, s, L, k_new, v_new, T, keep_row, te);
   return hipGetLastError();
 }
 

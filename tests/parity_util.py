@@ -47,6 +47,16 @@ class Pair:
         assert self.ref.append(k_new, v_new) == 0
         self.gpu.skvq_quantize_append(torch.from_numpy(k_new).to(self.device), torch.from_numpy(v_new).to(self.device))
 
+    def prefill_filtered(self, k: np.ndarray, v: np.ndarray, keep):
+        assert self.ref.prefill(k, v, keep=keep) == 0
+        self.gpu.skvq_prefill_quantize_filtered(torch.from_numpy(k).to(self.device), torch.from_numpy(v).to(self.device), keep)
+        torch.cuda.synchronize()
+
+    def append_filtered(self, k_new: np.ndarray, v_new: np.ndarray, keep: bool):
+        assert self.ref.append(k_new, v_new, keep=keep) == 0
+        self.gpu.skvq_quantize_append_filtered(torch.from_numpy(k_new).to(self.device),
+                                               torch.from_numpy(v_new).to(self.device), keep)
+
     def assert_buffers_equal(self):
         names = ["k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win"]
         got = self.gpu.host_arrays()

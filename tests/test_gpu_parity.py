@@ -461,6 +461,65 @@ META_CASES = [
 ]
 
 
+# ---- general filter rules: the caller decides which tokens stay fp16 when they leave the window ----
+FILTER_CASES = [
+    (small("filter_gqa4_t15", n_q_heads=8, n_kv_heads=2, context=700), {}, 9, 0.01),
+    (small("filter_k4v4_g32_b2", k_bits=4.0, v_bits=4.0, group_size=32, context=391, batch=2), {"meta": "f16"}, 16, 0.03),
+    (small("filter_k3v3_w16", k_bits=3.0, v_bits=3.0, n_q_heads=4, n_kv_heads=1, context=333, window=16), {}, 7, 0.015),
+    (small("filter_v2_uneq", v_bits=2.0, n_q_heads=4, n_kv_heads=2, group_size=64, context=600),
+     {"group_bounds": [0, 48, 128], "meta": "e4m3"}, 12, 0.01),
+    (small("filter_long", n_q_heads=8, n_kv_heads=2, context=5000), {}, 40, 0.005),
+    (small("filter_from_empty", context=0, window=16), {}, 6, 0.0),
+]
+
+
+@pytest.mark.parametrize("w,kw,S,frac", FILTER_CASES, ids=[c[0].name for c in FILTER_CASES])
+def test_filter_mask_prefill_appends_and_attention(P, w, kw, S, frac):
+    """A seeded mask over the prompt's old tokens, then appends with a decision per step (kept while rows are
+    free): every packed byte, (scale, zero), ring and kept row bit-exact, attention within 2e-3 along the way;
+    a kept token beyond the rows is refused and leaves the cache unchanged."""
+    print("case", w, kw, S, frac, flush=True)
+    n = 60
+    pair, k, v, q = P.make_pair(w, extra_tokens=n, n_sink=S, **kw)
+    rng = np.random.default_rng(99)
+    if w.context:
+        keep = rng.random(max(w.context - w.window, 0)) < frac
+        keep[:2] = True
+        while keep.sum() > S - 3:
+            keep[np.flatnonzero(keep)[-1]] = False
+        pair.prefill_filtered(k, v, keep)
+        pair.assert_buffers_equal()
+        out, ref = pair.decode_both(q)
+        assert np.abs(out - ref).max() <= P.TOL
+    used = int(pair.gpu.skvq_get_state()[0] - pair.gpu.skvq_get_state()[1] - pair.gpu.skvq_get_state()[2])
+    for s in range(n):
+        leaving = pair.ref.n_tokens >= w.window
+        want = bool(s % 7 == 3) and used < S
+        pair.append_filtered(*synth.make_new_token(w, s), want)
+        used += int(want and leaving)
+        if s in (0, 3, 4, 10, 17, 31, 32, 33, n - 1):
+            pair.assert_buffers_equal()
+            out, ref = pair.decode_both(q)
+            assert np.abs(out - ref).max() <= P.TOL, s
+    # fill the kept rows, then one more kept token must be refused
+    s = n
+    while used < S:
+        leaving = pair.ref.n_tokens >= w.window
+        pair.append_filtered(*synth.make_new_token(w, s), True)
+        used += int(leaving)
+        s += 1
+    state = pair.gpu.skvq_get_state()
+    kn, vn = (torch.from_numpy(x).cuda() for x in synth.make_new_token(w, s))
+    with pytest.raises(P.B.SkvqError) as e:
+        pair.gpu.skvq_quantize_append_filtered(kn, vn, True)
+    assert e.value.status == P.B.SKVQ_ERR_CAPACITY and pair.gpu.skvq_get_state() == state
+    # the sink rule's entry points go on from here (no row is free: the token is packed), and so does the one-call step
+    pair.append(*synth.make_new_token(w, s))
+    out, ref = pair.append_decode_both(*synth.make_new_token(w, s + 1), q)
+    assert np.abs(out - ref).max() <= P.TOL
+    pair.assert_buffers_equal()
+
+
 @pytest.mark.parametrize("w,meta,S", META_CASES, ids=lambda x: x.name if hasattr(x, "name") else str(x))
 def test_compact_meta_prefill_appends_bit_exact_and_decode_matches_oracle(P, w, meta, S):
     print("case", w, meta, S, flush=True)
