@@ -81,8 +81,9 @@ typedef struct {
   int32_t v_bits;       /* skvq_bits; values: SKVQ_BITS_1P5, _2, _3 or _4; SKVQ_BITS_3
                            only together with 3-bit keys (SKVQ_ERR_UNSUPPORTED else)      */
   int32_t window;       /* W >= 1 most recent tokens stay fp16 (Section 3.2)              */
-  int32_t n_sink;       /* S >= 0: the filter rule of Section 3.2 / Algorithm 1 that keeps
-                           the first S tokens (attention sinks) fp16 for ever; 0 = off    */
+  int32_t n_sink;       /* S >= 0: fp16 rows for tokens that the filter rules of Section 3.2 /
+                           Algorithm 1 keep in full precision; the built-in rule keeps the
+                           first S tokens (attention sinks) for ever; 0 = off             */
   int32_t meta_format;  /* skvq_meta_format                                              */
   int64_t max_quant_tokens; /* Tcap: rows of the packed region per sequence, >= 1         */
   const int32_t *perm_k; /* HOST [Hk][D]: reordered position p takes channel perm[h][p]   */
@@ -286,11 +287,12 @@ int skvq_decode_attention_multi(skvq_cache *cache, const void *q, int32_t n_new,
                                 void *out_f16, void *hip_stream);
 
 /* Host counters: tokens cached, of which packed, of which in the ring (the rest, at most S,
- * are sink rows).  Any may be NULL. */
+ * are the kept tokens' fp16 rows).  Any may be NULL. */
 int skvq_get_state(const skvq_cache *cache, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win);
 
-/* Declares that the buffers hold a valid cache of n_tokens tokens (e.g. to rewind after
- * appends, or to adopt buffers filled elsewhere).  SKVQ_ERR_CAPACITY if it cannot fit. */
+/* Declares that the buffers hold a valid cache of n_tokens tokens laid out by the sink rule
+ * (the first min(n_tokens - W, S) tokens kept), e.g. to rewind after appends or to adopt
+ * buffers filled elsewhere.  SKVQ_ERR_CAPACITY if it cannot fit. */
 int skvq_set_state(skvq_cache *cache, int64_t n_tokens);
 
 /* Number of sequence chunks of the packed region per kv head used by
