@@ -194,6 +194,14 @@ int skvq_quantize_append_filtered(skvq_cache *cache, const void *k_new, const vo
 int skvq_prefill_attention(skvq_cache *cache, const void *q, const void *k, const void *v,
                            int64_t n_tokens, void *out_f32, void *out_f16, void *hip_stream);
 
+/* The whole prefill phase of Section 3.2 as one call: skvq_prefill_attention on q, k, v, then
+ * skvq_prefill_quantize of the same k, v (sink rule), on the same stream; arguments, results
+ * and errors as those two (a prompt that does not fit is refused before anything is launched).
+ * The two stay separate launches: the attention streams every K/V tile once per block of 256
+ * queries, the quantizer once in all, so a merged kernel would save one pass out of hundreds. */
+int skvq_prefill_attention_quantize(skvq_cache *cache, const void *q, const void *k, const void *v,
+                                    int64_t n_tokens, void *out_f32, void *out_f16, void *hip_stream);
+
 /* Section 3.2 decode phase: with T tokens cached, if T >= W the token T-W (ring slot T % W)
  * leaves the window: it is copied to sink row T-W if T-W < S, else quantized into packed row
  * T-W-S by the same arithmetic; then the new token is written to slot T % W.

@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
                                           C.c_void_p]
         L.skvq_prefill_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_prefill_attention_quantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_quantize_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_prefill_quantize_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                                      C.c_void_p]
@@ -248,6 +250,21 @@ class SkvqCache:
         op = _dev_ptr(out_f32, torch.float32, (b, hq, T, HEAD_DIM))
         o16 = _dev_ptr(out_f16, torch.float16, (b, hq, T, HEAD_DIM)) if out_f16 is not None else None
         self._check(lib().skvq_prefill_attention(self._h, qp, kp, vp, T, op, o16, _stream_ptr(stream)))
+        return out_f32
+
+    def skvq_prefill_attention_quantize(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                                        out_f32: torch.Tensor | None = None, out_f16: torch.Tensor | None = None,
+                                        stream=None) -> torch.Tensor:
+        b, hq, hk = self.shape
+        T = q.shape[2]
+        qp = _dev_ptr(q, torch.float16, (b, hq, T, HEAD_DIM))
+        kp = _dev_ptr(k, torch.float16, (b, hk, T, HEAD_DIM))
+        vp = _dev_ptr(v, torch.float16, (b, hk, T, HEAD_DIM))
+        if out_f32 is None:
+            out_f32 = torch.empty((b, hq, T, HEAD_DIM), dtype=torch.float32, device=self.device)
+        op = _dev_ptr(out_f32, torch.float32, (b, hq, T, HEAD_DIM))
+        o16 = _dev_ptr(out_f16, torch.float16, (b, hq, T, HEAD_DIM)) if out_f16 is not None else None
+        self._check(lib().skvq_prefill_attention_quantize(self._h, qp, kp, vp, T, op, o16, _stream_ptr(stream)))
         return out_f32
 
     def skvq_prefill_quantize(self, k: torch.Tensor, v: torch.Tensor, stream=None):

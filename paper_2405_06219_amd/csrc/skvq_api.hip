@@ -336,6 +336,17 @@ static int upload_clips(skvq_cache *c, hipStream_t stream) {
   return e == hipSuccess ? SKVQ_OK : fail_hip(c, e, "clip scale upload");
 }
 
+int skvq_prefill_attention_quantize(skvq_cache *c, const void *q, const void *k, const void *v, int64_t T,
+                                    void *out_f32, void *out_f16, void *stream) {
+  // refuse before anything is launched what the second step would refuse
+  if (!c || T < 1) return SKVQ_ERR_INVALID_ARG;
+  const long long left = T > c->L.W ? T - c->L.W : 0;
+  if (left - (left < c->L.S ? left : c->L.S) > c->L.Tcap) return SKVQ_ERR_CAPACITY;
+  const int rc = skvq_prefill_attention(c, q, k, v, T, out_f32, out_f16, stream);
+  if (rc != SKVQ_OK) return rc;
+  return skvq_prefill_quantize(c, k, v, T, stream);
+}
+
 int skvq_calibrate_channel_stats(const void *x, int32_t batch, int32_t n_kv_heads, int64_t T, float *stats,
                                  void *stream_) {
   if (!x || !stats || batch < 1 || n_kv_heads < 1 || T < 1 || ((uintptr_t)x & 15) || batch > 65535 ||

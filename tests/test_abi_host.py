@@ -128,6 +128,7 @@ def test_validation_rejects_bad_configs(B):
     assert L.skvq_decode_attention(None, None, None, None, None) == B.SKVQ_ERR_INVALID_ARG
     assert L.skvq_append_decode_attention(None, None, None, None, None, None, None) == B.SKVQ_ERR_INVALID_ARG
     assert L.skvq_prefill_quantize_filtered(None, None, None, 0, None, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_prefill_attention_quantize(None, None, None, None, 1, None, None, None) == B.SKVQ_ERR_INVALID_ARG
     assert L.skvq_quantize_append_filtered(None, None, None, 1, None) == B.SKVQ_ERR_INVALID_ARG
     assert B.lib().skvq_status_string(B.SKVQ_ERR_CAPACITY) == b"packed region full"
     B.lib().skvq_destroy(None)

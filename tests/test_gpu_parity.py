@@ -678,6 +678,32 @@ def test_prefill_attention_long_prompt_sampled_rows(P, B, Hq, Hk, T):
     assert err <= bound
 
 
+def test_prefill_phase_in_one_call(P):
+    """skvq_prefill_attention_quantize: the prompt's attention against the oracle's, the cache against the
+    oracle's prefill, then a decode step; a prompt that does not fit is refused with the cache untouched."""
+    from oracle import skvq_oracle as O
+    w = small("prefill_one_call", n_q_heads=8, n_kv_heads=2, context=777, group_size=64)
+    pair, k, v, q = P.make_pair(w, extra_tokens=4, n_sink=3)
+    rng = np.random.default_rng(5)
+    qp = rng.standard_normal((w.batch, w.n_q_heads, w.context, D)).astype(np.float16)
+    ref_attn = pair.ref.prefill_attention(qp, k, v)
+    assert pair.ref.prefill(k, v) == 0
+    dev = "cuda:0"
+    out = pair.gpu.skvq_prefill_attention_quantize(torch.from_numpy(qp).to(dev), torch.from_numpy(k).to(dev),
+                                                   torch.from_numpy(v).to(dev))
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy() - ref_attn).max() <= 2.0 ** -11 * float(np.abs(v.astype(np.float32)).max()) + 1e-5
+    pair.assert_buffers_equal()
+    o, r = pair.append_decode_both(*synth.make_new_token(w, 0), q)
+    assert np.abs(o - r).max() <= P.TOL
+    state = pair.gpu.skvq_get_state()
+    big = torch.zeros((w.batch, w.n_kv_heads, w.context + 50, D), dtype=torch.float16, device=dev)
+    bigq = torch.zeros((w.batch, w.n_q_heads, w.context + 50, D), dtype=torch.float16, device=dev)
+    with pytest.raises(P.B.SkvqError) as e:
+        pair.gpu.skvq_prefill_attention_quantize(bigq, big, big)
+    assert e.value.status == P.B.SKVQ_ERR_CAPACITY and pair.gpu.skvq_get_state() == state
+
+
 # ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
 
 @pytest.mark.parametrize("G,v_bits,k_bits,Hq,Hk,B", [(64, 2.0, 2.0, 4, 2, 1), (128, 1.5, 2.0, 8, 2, 2), (32, 4.0, 4.0, 3, 3, 1)])
