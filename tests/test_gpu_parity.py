@@ -850,7 +850,9 @@ def test_multi_token_decode_matches_oracle(P, w, n_new, S, meta):
 def test_random_configurations(P):
     """Seeded random walk over the configuration space the ABI accepts: batch, kv heads, query
     heads per kv head (1..8), group size, V format, (scale, zero) format, window, sinks, context,
-    appended tokens and a forced split count.  Buffers bit-exact, outputs within 2e-3."""
+    appended tokens and a forced split count; the sink rule or a seeded mask of the caller's, and
+    every appended token through one of the three append paths.  Buffers bit-exact, outputs
+    within 2e-3."""
     rng = np.random.default_rng(20240506)
     for case in range(80):
         hk = int(rng.integers(1, 4))
@@ -873,14 +875,33 @@ def test_random_configurations(P):
             bounds = [0, *[int(x) for x in cuts], D]
         P.log(f"random case {case}: {w} S={S} meta={meta} appends={n_app} splits={splits} bounds={bounds}")
         pair, k, v, q = P.make_pair(w, extra_tokens=n_app + 1, n_sink=S, meta=meta, group_bounds=bounds)
+        # the caller's own filter rules in every other case with rows for kept tokens; each step through
+        # one of the three append paths (sink rule, caller's decision, append + attention in one call)
+        rng2 = np.random.default_rng(7000 + case)
+        own_rules = S > 0 and case % 2 == 1
         if w.context:
-            pair.prefill(k, v)
+            if own_rules:
+                keep = rng2.random(max(w.context - w.window, 0)) < 0.002
+                keep[np.flatnonzero(keep)[S:]] = False
+                pair.prefill_filtered(k, v, keep)
+            else:
+                pair.prefill(k, v)
+        pair.gpu.skvq_set_num_splits(splits)
         for s in range(n_app):
-            pair.append(*synth.make_new_token(w, s))
+            kn, vn = synth.make_new_token(w, s)
+            how = int(rng2.integers(3))
+            if how == 0:
+                pair.append(kn, vn)
+            elif how == 1:
+                st = pair.gpu.skvq_get_state()
+                free = S - (st[0] - st[1] - st[2])
+                pair.append_filtered(kn, vn, bool(own_rules and free > 0 and rng2.integers(3) == 0))
+            else:
+                o, r = pair.append_decode_both(kn, vn, q)
+                assert np.abs(o - r).max() <= P.TOL, (case, s)
         pair.assert_buffers_equal()
         if pair.ref.n_tokens == 0:
             continue
-        pair.gpu.skvq_set_num_splits(splits)
         out, ref = pair.decode_both(q)
         err = np.abs(out - ref).max()
         P.log(f"random case {case}: max abs err {err:.3e} (ref max {np.abs(ref).max():.3f})")
