@@ -224,6 +224,11 @@ STEP_CASES = [
     (small("step_long_b2", group_size=64, context=9000, batch=2), {}, 7),
     (small("step_long_w33", window=33, context=5000, batch=3), {}, 2),   # two chunks: two launches
     (small("step_long_short_last_chunk", n_q_heads=8, n_kv_heads=2, context=13000), {}, 4),  # the last chunk is the shorter one
+    (small("step_long_k4v4_g64", k_bits=4.0, v_bits=4.0, n_q_heads=4, n_kv_heads=2, context=14000, group_size=64), {"meta": "f16"}, 4),
+    (small("step_long_k3v3_g32", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=2, context=13500, group_size=32), {"meta": "e4m3"}, 4),
+    (small("step_long_k2v4_uneq", k_bits=2.0, v_bits=4.0, n_q_heads=4, n_kv_heads=1, context=13000, group_size=32),
+     {"group_bounds": [0, 16, 32, 80, 128]}, 4),
+    (small("step_long_sinks_b2", k_bits=4.0, v_bits=1.5, n_q_heads=2, n_kv_heads=2, context=16000, batch=2), {"n_sink": 5}, 5),
 ]
 
 
