@@ -819,6 +819,7 @@ MULTI_CASES = [
     (small("multi_gqa3_k3v3_g64", k_bits=3.0, v_bits=3.0, n_q_heads=6, n_kv_heads=2, group_size=64, context=450), 2, 1, "f16"),
     (small("multi_window_only", context=40), 16, 0, "f32"),
     (small("multi_whole_window", window=8, context=300), 8, 0, "f32"),
+    (small("multi_most_tokens_gqa8", n_q_heads=8, n_kv_heads=1, context=600), 64, 0, "f32"),   # the most query tokens a call takes
 ]
 
 
