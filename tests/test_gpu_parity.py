@@ -301,6 +301,15 @@ def test_runtime_errors(P):
     assert e.value.status == B.SKVQ_ERR_CAPACITY
     assert pair.gpu.skvq_get_state() == (302, 174, 128)
     torch.cuda.synchronize()
+    # an empty prompt empties the cache; the first tokens then arrive one by one
+    assert B.lib().skvq_prefill_quantize(pair.gpu._h, None, None, 0, None) == B.SKVQ_OK
+    assert pair.gpu.skvq_get_state() == (0, 0, 0)
+    with pytest.raises(B.SkvqError) as e:
+        pair.gpu.skvq_decode_attention(qd)
+    assert e.value.status == B.SKVQ_ERR_STATE
+    pair.gpu.skvq_append_decode_attention(x, x, qd)
+    assert pair.gpu.skvq_get_state() == (1, 0, 1)
+    torch.cuda.synchronize()
 
 
 def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
