@@ -174,7 +174,7 @@ int skvq_prefill_quantize(skvq_cache *cache, const void *k, const void *v, int64
  * older than the window (tokens 0 .. n_tokens - W - 1), nonzero = keep; NULL = the sink rule.
  * SKVQ_ERR_CAPACITY if more than n_sink tokens are kept or the others exceed Tcap;
  * SKVQ_ERR_UNSUPPORTED for n_tokens >= 2^31 with a mask.  Copies the kept tokens' numbers to
- * the device before it returns (a synchronous copy of at most n_sink integers).
+ * the device on the stream and waits for that copy (at most n_sink integers) before it returns.
  *
  * skvq_quantize_append_filtered: as skvq_quantize_append; keep_leaving != 0 keeps the token that
  * leaves the window in this step (ignored while the window is not full).  SKVQ_ERR_CAPACITY if

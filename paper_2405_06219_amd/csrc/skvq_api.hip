@@ -296,8 +296,11 @@ int skvq_prefill_quantize_filtered(skvq_cache *c, const void *k, const void *v, 
       }
     n_kept = (long long)list.size();
     if (n_kept > 0) {
-      // (a synchronous copy: the list is gone when this function returns)
-      hipError_t e = hipMemcpy(c->dev_kept_ids, list.data(), list.size() * sizeof(int), hipMemcpyHostToDevice);
+      // On the caller's stream (an earlier prefill on it may still be reading the previous list), and
+      // waited for: the host list is gone when this function returns.
+      hipError_t e = hipMemcpyAsync(c->dev_kept_ids, list.data(), list.size() * sizeof(int), hipMemcpyHostToDevice,
+                                    (hipStream_t)stream);
+      if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
       if (e != hipSuccess) return fail_hip(c, e, "skvq_prefill_quantize_filtered copy of the kept tokens");
       ids = c->dev_kept_ids;
     }
