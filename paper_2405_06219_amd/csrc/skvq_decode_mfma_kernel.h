@@ -301,12 +301,34 @@ struct RingData {
   unsigned v[4];  // lane = channel pair: the 4 tokens' values of channels 2l, 2l+1
 };
 
+// What the host works out once per launch, so that no workgroup spends its first few hundred
+// instructions on divisions: the share of the packed tiles per chunk and the ring's first row.
+struct ChunkPlan {
+  int tiles_q;     // chunk sp holds tiles_q tiles, one more from chunk first_long on: a share of the
+  int first_long;  //   tiles plus, when the last chunk's workgroup also appends the new token, the
+                   //   kAppendLagTiles it is spared (the last chunk ends at the last tile either way)
+  int slot0;       // ring row of the window's oldest token
+};
+
+inline ChunkPlan plan_chunks(const Layout &L, long long T, long long nq, int n_sink, int n_splits, bool fused) {
+  ChunkPlan p;
+  const int n_tiles = (int)((nq + 63) >> 6);
+  const int lag = fused && n_tiles >= 4 * kAppendLagTiles * n_splits ? kAppendLagTiles : 0;
+  const int nt = n_tiles + lag;
+  p.tiles_q = nt / n_splits;
+  p.first_long = n_splits - nt % n_splits;
+  const long long n_win = (T - nq) - n_sink;
+  p.slot0 = (int)((T - n_win) % L.W);
+  return p;
+}
+
 template <int R, int KL, int VL, int META, int NG, bool UNEQ>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, const __half *__restrict__ q,
                                                                   long long T, long long nq, int n_sink,
                                                                   int n_splits, int passes, int n_new,
                                                                   const __half *__restrict__ knew,
-                                                                  const __half *__restrict__ vnew, long long te) {
+                                                                  const __half *__restrict__ vnew, long long te,
+                                                                  ChunkPlan plan) {
   // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
   // head with more than four (or with three) query heads is served by `passes` workgroups per
   // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
@@ -325,10 +347,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   SKVQ_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sp = blockIdx.x, hk = blockIdx.y / passes, b = blockIdx.z;
+  const int sp = blockIdx.x, hk = passes == 1 ? blockIdx.y : blockIdx.y / passes, b = blockIdx.z;
   const unsigned gmap = UNEQ ? L.gmaps[hk] : 0u;
   auto piece_group = [&](int n) { return (int)((gmap >> (4 * n)) & 15u); };  // group of positions 16n..16n+15
-  const int head0 = (blockIdx.y % passes) * R;  // first of this workgroup's query heads, within the kv head's
+  const int head0 = passes == 1 ? 0 : (blockIdx.y % passes) * R;  // first of this workgroup's query heads, within the kv head's
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;
 
@@ -344,7 +366,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     append_token(L, knew, vnew, T - 1, -1, te, hk, b, wave, lane, reinterpret_cast<__half(*)[kD]>(&sm.ring_o[0][0][0]),
                  reinterpret_cast<uint8_t *>(&sm.ring_o[0][0][0]) + 2 * kD * sizeof(__half));
     __threadfence_block();
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (the fence alone need not wait for the stores)
+    // (the fence alone need not wait for the stores.  The builtin, not inline assembly: the
+    // compiler then knows that no load of this branch is pending, and adds no wait for one to
+    // the common path below.)  vmcnt(0), the other counters left alone
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
     __syncthreads();
   }
 
@@ -352,9 +378,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // (with the new token taken along the last chunk is shorter by about the time its workgroup
   // spends on the append)
   const int n_tiles = (int)((nq + 63) >> 6);
-  const int lag = fused && n_tiles >= 4 * kAppendLagTiles * n_splits ? kAppendLagTiles : 0;
-  const int tile_begin = (int)(((long long)sp * (n_tiles + lag)) / n_splits);
-  const int tile_end = sp == n_splits - 1 ? n_tiles : (int)(((long long)(sp + 1) * (n_tiles + lag)) / n_splits);
+  // (the later chunks hold the odd tiles: the last chunk is never empty while there is a tile,
+  // and the tile of the token that leaves the window is always its own)
+  const int n_long = sp > plan.first_long ? sp - plan.first_long : 0;  // longer chunks before this one
+  const int tile_begin = sp * plan.tiles_q + n_long;
+  const int tile_end = sp == n_splits - 1 ? n_tiles : tile_begin + plan.tiles_q + (sp >= plan.first_long ? 1 : 0);
 
   constexpr int kRowBytes = K4 ? 64 : K3 ? 48 : 32;
   const uint8_t *kc = L.k_codes + head * L.Tcap * kRowBytes;
@@ -418,7 +446,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int ring_rank = (wave + kNW / 2) % kNW;
   const int ring_first = sp + n_splits * ring_rank;
   const bool ring_owner = ring_first < n_slices;
-  const int slot0 = (int)((T - n_win) % W);  // ring row of the window's oldest token
+  const int slot0 = plan.slot0;  // ring row of the window's oldest token
   const __half *kwin = L.k_win + head * (W + L.S) * kD;
   const __half *vwin = L.v_win + head * (W + L.S) * kD;
   auto ring_slot = [&](int t) {  // ring slot of ring token t (clamped to the last one)
@@ -486,10 +514,20 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       sm.lut4[half][x] = uint2_t{(d0 << 8) | (d1 << 24), (d2 << 8) | (d3 << 24)};
     }
     __syncthreads();
-    for (int e = tid; e < 6561; e += kThreads) {
+    // (all reads of the small tables first, then all writes: one LDS latency, not one per entry)
+    constexpr int kEntriesPerThread = (6561 + kThreads - 1) / kThreads;
+    uint2_t lo4[kEntriesPerThread], hi4[kEntriesPerThread];
+#pragma unroll
+    for (int i = 0; i < kEntriesPerThread; ++i) {
+      const unsigned e = min(tid + i * kThreads, 6560);
       const unsigned hi = e / 81u, lo = e - 81u * hi;
-      const uint2_t a = sm.lut4[0][lo], b2 = sm.lut4[1][hi];
-      sm.lut[e] = uint4_t{a.x, a.y, b2.x, b2.y};
+      lo4[i] = sm.lut4[0][lo];
+      hi4[i] = sm.lut4[1][hi];
+    }
+#pragma unroll
+    for (int i = 0; i < kEntriesPerThread; ++i) {
+      const int e = tid + i * kThreads;
+      if (e < 6561) sm.lut[e] = uint4_t{lo4[i].x, lo4[i].y, hi4[i].x, hi4[i].y};
     }
   }
   {
@@ -991,8 +1029,9 @@ hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T,
   if (knew && T - 1 >= L.W && (te < 0 || te >= L.Tcap || te != nq - 1)) return hipErrorInvalidValue;
   if ((long long)L.Hk * passes > 65535) return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
+  const ChunkPlan plan = plan_chunks(L, T, nq, n_sink, n_splits, knew != nullptr);
 #define SKVQ_LAUNCH(RR, MM, GG, UU) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew, te)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew, te, plan)
 #define SKVQ_LAUNCH_NG(RR, MM)                                                                   \
   switch (L.NG) {                                                                                \
     case 1: SKVQ_LAUNCH(RR, MM, 1, false); break;                                                \
