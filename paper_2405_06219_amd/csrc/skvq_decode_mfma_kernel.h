@@ -978,18 +978,28 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     float m = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kNW; ++w) {
+      const float wm_w = sm.wm[w][r], rm_w = sm.rm[w][r];
       wl[w] = sm.wl[w][r], rl[w] = sm.rl[w][r];
-      wm[w] = wl[w] > 0.f ? sm.wm[w][r] : -INFINITY;
-      rm[w] = rl[w] > 0.f ? sm.rm[w][r] : -INFINITY;
+      wm[w] = wl[w] > 0.f ? wm_w : -INFINITY;
+      rm[w] = rl[w] > 0.f ? rm_w : -INFINITY;
       m = fmaxf(m, fmaxf(wm[w], rm[w]));
+    }
+    // (every read unconditional, what a wave or slice without tokens left there is deselected
+    // afterwards: the reads then go out together and are waited for once, not one LDS round
+    // trip after the other)
+    float ws[kNW], rs[kNW];
+#pragma unroll
+    for (int w = 0; w < kNW; ++w) {
+      ws[w] = sm.wb[w].stage[r][p] + sm.wz[w][r][UNEQ ? piece_group(p >> 4) : p * NG / kD];
+      rs[w] = sm.ring_o[w][r][ch];
     }
     float den = 0.f, num = 0.f;
 #pragma unroll
     for (int w = 0; w < kNW; ++w) {
       const float e = wl[w] > 0.f ? fast_exp2(wm[w] - m) : 0.f, g = rl[w] > 0.f ? fast_exp2(rm[w] - m) : 0.f;
       den = fmaf(e, wl[w], fmaf(g, rl[w], den));
-      if (e > 0.f) num = fmaf(e, sm.wb[w].stage[r][p] + sm.wz[w][r][UNEQ ? piece_group(p >> 4) : p * NG / kD], num);
-      if (g > 0.f) num = fmaf(g, sm.ring_o[w][r][ch], num);
+      num = fmaf(e, e > 0.f ? ws[w] : 0.f, num);
+      num = fmaf(g, g > 0.f ? rs[w] : 0.f, num);
     }
     float *part =
         L.workspace + (row_index(head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
