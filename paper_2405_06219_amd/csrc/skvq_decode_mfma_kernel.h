@@ -514,20 +514,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       sm.lut4[half][x] = uint2_t{(d0 << 8) | (d1 << 24), (d2 << 8) | (d3 << 24)};
     }
     __syncthreads();
-    // (all reads of the small tables first, then all writes: one LDS latency, not one per entry)
-    constexpr int kEntriesPerThread = (6561 + kThreads - 1) / kThreads;
-    uint2_t lo4[kEntriesPerThread], hi4[kEntriesPerThread];
+    // Thread t < 486 keeps the low half of its entries (digits t % 81) and walks through every
+    // sixth high half from t / 81 on: one read per entry instead of two, all reads first, then
+    // all writes (one LDS latency, not one per entry).
+    constexpr int kWalk = 6, kSteps = (81 + kWalk - 1) / kWalk;
+    const unsigned first_hi = tid / 81u, lo = tid - 81u * first_hi;
+    if (first_hi < kWalk) {
+      const uint2_t lo4 = sm.lut4[0][lo];
+      uint2_t hi4[kSteps];
 #pragma unroll
-    for (int i = 0; i < kEntriesPerThread; ++i) {
-      const unsigned e = min(tid + i * kThreads, 6560);
-      const unsigned hi = e / 81u, lo = e - 81u * hi;
-      lo4[i] = sm.lut4[0][lo];
-      hi4[i] = sm.lut4[1][hi];
-    }
+      for (int i = 0; i < kSteps; ++i) hi4[i] = sm.lut4[1][min(first_hi + kWalk * i, 80u)];
 #pragma unroll
-    for (int i = 0; i < kEntriesPerThread; ++i) {
-      const int e = tid + i * kThreads;
-      if (e < 6561) sm.lut[e] = uint4_t{lo4[i].x, lo4[i].y, hi4[i].x, hi4[i].y};
+      for (int i = 0; i < kSteps; ++i) {
+        const unsigned hi = first_hi + kWalk * i;
+        if (hi < 81u) sm.lut[81u * hi + lo] = uint4_t{lo4.x, lo4.y, hi4[i].x, hi4[i].y};
+      }
     }
   }
   {
