@@ -115,11 +115,21 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
   return make_uint2(w0, w1);
 }
 
+// Orders a wavefront's own LDS writes before its own later LDS reads (other lanes' data).  The
+// LDS serves one wavefront's operations in the order they were issued, so no instruction is
+// needed: the fences only keep the compiler from moving the accesses across this point.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int KL, int VL>  // levels of the key and value codes
 __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
                                                       long long nq, int n_kept,
                                                       const int *__restrict__ kept_ids) {
+  // (everything in LDS is private to one wavefront: the four wavefronts never wait for each other)
   __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
   __shared__ unsigned vq[VL == 16 ? 1 : 4][8][8];             // [wave][token i][n]: 16 codes, j-minor
   __shared__ unsigned vqtop[VL == 8 ? 4 : 1][8][8];           // 3-bit codes: their top bits, j-minor
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   }
   const long long t = t0 + i;
   const bool valid = t < nq;
-  __syncthreads();
+  wave_lds_sync();
 
   GroupParams gk, gv;
   constexpr int kKBits = KL == 16 ? 4 : KL == 8 ? 3 : 2, kVBits = VL == 16 ? 4 : VL == 8 ? 3 : 2;
@@ -211,7 +221,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     vq[wave][i][n] = valid ? vw.x : 0u;
     if (VL == 8) vqtop[wave][i][n] = valid ? vw.y : 0u;
   }
-  __syncthreads();
+  wave_lds_sync();
 
   // V units of sub-block kb = wave.  Lane (j = lane % 16, nh = lane / 16) builds fields 2nh and
   // 2nh+1 of unit j from the codes of its eight tokens.
@@ -264,7 +274,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
       pw *= 3;
     }
     pieces[wave][lane] = fa | (fb << 13);  // 26 bits
-    __syncthreads();
+    wave_lds_sync();
     if (lane < 16) {
       const unsigned long long a0 = pieces[wave][lane], a1 = pieces[wave][16 + lane];
       const unsigned long long a2 = pieces[wave][32 + lane], a3 = pieces[wave][48 + lane];
@@ -276,7 +286,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
 #pragma unroll
       for (int q = 0; q < 5; ++q) u[8 + q] = (uint8_t)(hi >> (8 * q));
     }
-    __syncthreads();
+    wave_lds_sync();
     if (lane < 52)
       reinterpret_cast<unsigned *>(dst + 208 * wave)[lane] = reinterpret_cast<const unsigned *>(units[wave])[lane];
   }
