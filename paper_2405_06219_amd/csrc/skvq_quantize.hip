@@ -56,6 +56,12 @@ constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte a
 // returns this lane's 16 codes.  BITS = 2: two bits each in .x (position 16n + e at bits [2e, 2e+2));
 // BITS = 3: the low two bits like that in .x and the top bits in .y (position e at bit e);
 // BITS = 4: four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).
+// The value of another lane of the same row of 16, chosen by a DPP control word.
+template <int CTRL>
+__device__ __forceinline__ float lane_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
 template <int BITS>
 __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
                                           float top, int fmt, bool uneq, unsigned gmap, int lane,
@@ -86,9 +92,20 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
       }
     }
   } else {
-    for (int off = 1; off < G / 16; off <<= 1) {
-      mn = fminf(mn, __shfl_xor(mn, off));
-      mx = fmaxf(mx, __shfl_xor(mx, off));
+    // the group's other lanes are neighbours within eight: lane ^ 1, lane ^ 2, then the mirror
+    // image within the eight (both quads hold their own result by then); data-parallel moves
+    const int lanes = G / 16;
+    if (lanes > 1) {
+      mn = fminf(mn, lane_move<0xB1>(mn));  // quad_perm [1, 0, 3, 2]
+      mx = fmaxf(mx, lane_move<0xB1>(mx));
+    }
+    if (lanes > 2) {
+      mn = fminf(mn, lane_move<0x4E>(mn));  // quad_perm [2, 3, 0, 1]
+      mx = fmaxf(mx, lane_move<0x4E>(mx));
+    }
+    if (lanes > 4) {
+      mn = fminf(mn, lane_move<0x141>(mn));  // row_half_mirror
+      mx = fmaxf(mx, lane_move<0x141>(mx));
     }
   }
   gp = group_params(mn, mx, alpha, top, fmt);
