@@ -184,8 +184,8 @@ int skvq_prefill_quantize_filtered(skvq_cache *cache, const void *k, const void 
 int skvq_quantize_append_filtered(skvq_cache *cache, const void *k_new, const void *v_new,
                                   int32_t keep_leaving, void *hip_stream);
 
-/* Section 3.2 prefill phase, first step ("we first compute attention using full-precision KV
- * cache"; Algorithm 1 with h = 0, l = len(prompt)): causal softmax attention of the prompt on
+/* Section 3.2 prefill phase, first step (the prompt attends over its own keys and values before
+ * any of them is quantized; Algorithm 1 with h = 0, l = len(prompt)): causal softmax attention of the prompt on
  * the fp16 inputs, original channel order, fp32 accumulation: query t of head hq sees keys
  * 0..t of kv head hq / (Hq/Hk); scale sm_scale.  Reads only the cache's configuration; the cache
  * contents and counters are untouched (call skvq_prefill_quantize on the same k, v afterwards).
@@ -231,10 +231,9 @@ int skvq_append_decode_attention(skvq_cache *cache, const void *k_new, const voi
                                  void *out_f32, void *out_f16, void *hip_stream);
 
 
-/* Section 3.1 / Algorithm 1 Prologue, get_permutation_matrix ("we extract the distribution
- * feature of each channel and then use the KMeans algorithm to cluster channels with similar
- * characteristics into the same group"), in two steps.  Offline routines: they allocate and free
- * their own scratch and synchronise.
+/* Section 3.1 / Algorithm 1 Prologue, get_permutation_matrix (channels whose value
+ * distributions look alike are put into the same group by KMeans over a per-channel feature),
+ * in two steps.  Offline routines: they allocate and free their own scratch and synchronise.
  *
  * skvq_calibrate_channel_stats: x: DEVICE fp16 [B][Hk][T][D] calibration keys (or values);
  * stats: HOST [Hk][D][2] = (min, max) of every channel over all B*T tokens.

@@ -729,9 +729,9 @@ void skvq_ref_channel_stats(const uint16_t *x, int B, int Hk, int64_t T, float *
     }
 }
 
-/* Section 3.1 ("we extract the distribution feature of each channel and then use
- * the KMeans algorithm to cluster channels with similar characteristics into the
- * same group"; Algorithm 1 Prologue, get_permutation_matrix).  The paper names
+/* Section 3.1 (channels with similar value distributions are clustered into one
+ * group by KMeans over a per-channel feature; Algorithm 1 Prologue,
+ * get_permutation_matrix).  The paper names
  * neither the feature nor the initialisation; this build's reading, per kv head:
  *   feature of a channel = (min, max) over the calibration tokens;
  *   k = D/G clusters; channels ordered by range max-min (ties: channel index),

@@ -43,7 +43,8 @@ hipError_t launch_sqerr(const Layout &L, const float *out, const float *ref, flo
 
 // ---------------------------------------------------------------------------------------
 // Channel reorder (Section 3.1; Algorithm 1 Prologue, get_permutation_matrix): per-channel
-// (min, max) of the calibration tokens on the GPU, KMeans over them on the host.
+// (min, max) of the calibration tokens on the GPU; the clustering over them is host code
+// (skvq_reorder.hip).
 // ---------------------------------------------------------------------------------------
 namespace skvq {
 namespace {
@@ -109,73 +110,6 @@ hipError_t launch_channel_stats(const __half *x, float *part, int B, int Hk, lon
   const long long rows = (T + chunks - 1) / chunks;
   hipLaunchKernelGGL(channel_stats_kernel, dim3(chunks, Hk, B), dim3(256), 0, s, x, part, T, Hk, rows);
   return hipGetLastError();
-}
-
-// KMeans over the channels' (min, max), per kv head; see skvq_calibrate_reorder in skvq.h for
-// the steps.  Host code, fp64, every operation rounded once (this file is compiled without
-// contraction).
-int reorder_channels(const float *stats, int Hk, int G, int gran, int max_iter, int32_t *perm, int32_t *bounds) {
-  const int ng = kD / G;
-  for (int h = 0; h < Hk; ++h) {
-    const float *f = stats + (size_t)h * kD * 2;
-    double range[kD], cmin[kD], cmax[kD];
-    int order[kD], label[kD];
-    for (int ch = 0; ch < kD; ++ch) range[ch] = (double)f[2 * ch + 1] - (double)f[2 * ch], order[ch] = ch, label[ch] = -1;
-    for (int i = 1; i < kD; ++i) {  // stable insertion sort: by range, then by channel
-      const int o = order[i];
-      int j = i;
-      for (; j > 0 && range[order[j - 1]] > range[o]; --j) order[j] = order[j - 1];
-      order[j] = o;
-    }
-    for (int j = 0; j < ng; ++j) {  // start: the mean feature of every run of G channels in that order
-      double a = 0.0, b = 0.0;
-      for (int i = 0; i < G; ++i) a += (double)f[2 * order[j * G + i]], b += (double)f[2 * order[j * G + i] + 1];
-      cmin[j] = a / G, cmax[j] = b / G;
-    }
-    for (int it = 0;; ++it) {
-      bool moved = false;
-      for (int ch = 0; ch < kD; ++ch) {
-        int best = 0;
-        double best_d = 0.0;
-        for (int j = 0; j < ng; ++j) {
-          const double da = (double)f[2 * ch] - cmin[j], db = (double)f[2 * ch + 1] - cmax[j];
-          const double d = da * da + db * db;
-          if (j == 0 || d < best_d) best = j, best_d = d;
-        }
-        if (best != label[ch]) label[ch] = best, moved = true;
-      }
-      if (!moved || it == max_iter) break;
-      for (int j = 0; j < ng; ++j) {
-        double a = 0.0, b = 0.0;
-        int n = 0;
-        for (int ch = 0; ch < kD; ++ch)
-          if (label[ch] == j) a += (double)f[2 * ch], b += (double)f[2 * ch + 1], ++n;
-        if (n) cmin[j] = a / n, cmax[j] = b / n;  // an empty cluster keeps its centroid
-      }
-    }
-    int corder[kD];
-    for (int j = 0; j < ng; ++j) corder[j] = j;
-    for (int i = 1; i < ng; ++i) {  // clusters by the range of their centroid
-      const int o = corder[i];
-      int j = i;
-      for (; j > 0 && cmax[corder[j - 1]] - cmin[corder[j - 1]] > cmax[o] - cmin[o]; --j) corder[j] = corder[j - 1];
-      corder[j] = o;
-    }
-    int32_t *pm = perm + (size_t)h * kD, *gb = bounds + (size_t)h * (ng + 1);
-    int p = 0;
-    gb[0] = 0;
-    for (int jj = 0; jj < ng; ++jj) {
-      for (int i = 0; i < kD; ++i)
-        if (label[order[i]] == corder[jj]) pm[p++] = order[i];
-      gb[jj + 1] = p;
-    }
-    for (int j = 1; j < ng; ++j) {  // boundaries to the nearest multiple of gran, groups of at least gran
-      const int b = ((2 * gb[j] + gran) / (2 * gran)) * gran;
-      const int lo = gb[j - 1] + gran, hi = kD - (ng - j) * gran;
-      gb[j] = b < lo ? lo : b > hi ? hi : b;
-    }
-  }
-  return 0;
 }
 
 }  // namespace skvq

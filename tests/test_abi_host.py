@@ -159,3 +159,45 @@ def test_reorder_calibration_equals_the_oracle(B, oracle):
     stats[0, 3, 1] = np.inf
     with pytest.raises(B.SkvqError):
         B.skvq_calibrate_reorder(stats, 32)
+
+
+def test_library_reorder_is_lloyds_kmeans_and_recovers_planted_families(B):
+    """The library's own clustering, checked without the oracle: against scikit-learn's Lloyd KMeans
+    from the stated start (same partition of the channels), and on planted channel families of
+    unequal sizes (clusters = families, listed by range; members by their own range)."""
+    from sklearn.cluster import KMeans
+    rng = np.random.default_rng(1402)
+    for G in (32, 64):
+        ng = D // G
+        sc = 10 ** rng.uniform(-1.5, 1.0, D)
+        stats = np.stack([-sc * rng.uniform(0.3, 1.0, D), sc * rng.uniform(0.3, 1.0, D)], axis=1).astype(np.float32)[None]
+        perm, bounds = B.skvq_calibrate_reorder(stats, G, 1, 100)
+        f = stats[0].astype(np.float64)
+        order = np.lexsort((np.arange(D), f[:, 1] - f[:, 0]))
+        init = np.stack([f[order[j * G:(j + 1) * G]].mean(axis=0) for j in range(ng)])
+        km = KMeans(n_clusters=ng, init=init, n_init=1, algorithm="lloyd", max_iter=100, tol=0.0).fit(f)
+        theirs = {frozenset(np.flatnonzero(km.labels_ == j)) for j in range(ng)}
+        ours = {frozenset(perm[0, bounds[0, j]:bounds[0, j + 1]]) for j in range(ng)}
+        assert ours == theirs
+        # no move of the centres allowed: the clusters are the nearest initial centroids
+        perm0, bounds0 = B.skvq_calibrate_reorder(stats, G, 1, 0)
+        d2 = ((f[:, None, :] - init[None]) ** 2).sum(axis=2)
+        near = d2.argmin(axis=1)
+        ours0 = {frozenset(perm0[0, bounds0[0, j]:bounds0[0, j + 1]]) for j in range(ng)} - {frozenset()}
+        assert ours0 == {frozenset(np.flatnonzero(near == j)) for j in range(ng)} - {frozenset()}
+    sizes, scales = [16, 48, 24, 40], [8.0, 0.05, 1.0, 0.3]
+    fam = rng.permutation(np.repeat(np.arange(4), sizes))
+    stats = np.zeros((1, D, 2), np.float32)
+    for ch in range(D):
+        s = scales[fam[ch]] * rng.uniform(0.9, 1.1)
+        stats[0, ch] = (-s * rng.uniform(0.8, 1.0), s * rng.uniform(0.8, 1.0))
+    perm, bounds = B.skvq_calibrate_reorder(stats, 32, 1, 100)
+    by_range = np.argsort(scales)
+    assert bounds[0].tolist() == [0] + np.cumsum(np.array(sizes)[by_range]).tolist()
+    for j, fj in enumerate(by_range):
+        members = perm[0, bounds[0, j]:bounds[0, j + 1]]
+        assert set(members) == set(np.flatnonzero(fam == fj))
+        assert np.all(np.diff(stats[0, members, 1] - stats[0, members, 0]) >= 0)
+    perm16, bounds16 = B.skvq_calibrate_reorder(stats, 32, 16, 100)
+    assert np.array_equal(perm16, perm)
+    assert np.all(bounds16 % 16 == 0) and np.all(np.diff(bounds16, axis=1) >= 16) and np.all(np.abs(bounds16 - bounds) <= 8)
