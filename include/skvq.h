@@ -48,7 +48,7 @@ typedef enum {
   SKVQ_ERR_INVALID_ARG = -1, /* NULL pointer, bad shape, non-permutation, alpha outside (0,1] */
   SKVQ_ERR_UNSUPPORTED = -2, /* a bit-width / head_dim / group size this build has no kernel for */
   SKVQ_ERR_CAPACITY = -3,    /* the packed region (max_quant_tokens) would overflow */
-  SKVQ_ERR_STATE = -4,       /* e.g. attention over an empty cache */
+  SKVQ_ERR_STATE = -4,       /* e.g. attention over an empty cache, a rewind by skvq_set_state */
   SKVQ_ERR_HIP = -5          /* a HIP runtime call failed; see skvq_last_error */
 } skvq_status;
 
@@ -69,6 +69,9 @@ typedef enum {
   SKVQ_META_FP8_E4M3 = 2 /* bias 7, largest finite value 448, saturating */
 } skvq_meta_format;
 
+/* Most packed rows per sequence: the kernels count packed tokens in 32-bit integers. */
+#define SKVQ_MAX_QUANT_TOKENS 2147483583LL /* 2^31 - 1 - 64 */
+
 /* Parameters of Algorithm 1: window W, group size G; Prologue outputs P_k, P_v, clipping. */
 typedef struct {
   int32_t batch;        /* B >= 1; all sequences of a batch have the same length          */
@@ -85,7 +88,8 @@ typedef struct {
                            Algorithm 1 keep in full precision; the built-in rule keeps the
                            first S tokens (attention sinks) for ever; 0 = off             */
   int32_t meta_format;  /* skvq_meta_format                                              */
-  int64_t max_quant_tokens; /* Tcap: rows of the packed region per sequence, >= 1         */
+  int64_t max_quant_tokens; /* Tcap: rows of the packed region per sequence, >= 1 and at
+                           most SKVQ_MAX_QUANT_TOKENS (SKVQ_ERR_UNSUPPORTED beyond)       */
   const int32_t *perm_k; /* HOST [Hk][D]: reordered position p takes channel perm[h][p]   */
   const int32_t *perm_v; /* HOST [Hk][D]  (each row a permutation of 0..D-1)              */
   const float *clip_k;   /* HOST [Hk][D/G]: alpha in (0,1] per (kv head, group), Eq. 2    */
@@ -297,9 +301,13 @@ int skvq_decode_attention_multi(skvq_cache *cache, const void *q, int32_t n_new,
  * are the kept tokens' fp16 rows).  Any may be NULL. */
 int skvq_get_state(const skvq_cache *cache, int64_t *n_tokens, int64_t *n_quant, int32_t *n_win);
 
-/* Declares that the buffers hold a valid cache of n_tokens tokens laid out by the sink rule
- * (the first min(n_tokens - W, S) tokens kept), e.g. to rewind after appends or to adopt
- * buffers filled elsewhere.  SKVQ_ERR_CAPACITY if it cannot fit. */
+/* Adopts a cache that was filled elsewhere: declares that the buffers hold a valid cache of
+ * n_tokens tokens laid out by the sink rule (the first min(n_tokens - W, S) tokens kept), e.g.
+ * copied from the buffers of another cache of the same configuration.  The count only moves
+ * forward: a cache cannot be rewound (the ring rows of the tokens that would come back have
+ * been overwritten, and an append assumes that the slots after its own in a V unit are still
+ * zero), so n_tokens below the current count is refused with SKVQ_ERR_STATE and nothing changes;
+ * skvq_prefill_quantize (also with n_tokens = 0) starts over.  SKVQ_ERR_CAPACITY if it cannot fit. */
 int skvq_set_state(skvq_cache *cache, int64_t n_tokens);
 
 /* Number of sequence chunks of the packed region per kv head used by

@@ -49,8 +49,9 @@ int check_config(const skvq_config *c) {
     return SKVQ_ERR_UNSUPPORTED;
   if (!(c->sm_scale >= 0.0f) || !std::isfinite(c->sm_scale)) return SKVQ_ERR_INVALID_ARG;
   if (c->max_new_tokens < 0 || c->max_new_tokens > SKVQ_MAX_NEW_TOKENS) return SKVQ_ERR_INVALID_ARG;
-  if ((long long)c->window > (1ll << 20) || c->n_sink > (1 << 20) || c->max_quant_tokens > (1ll << 40))
-    return SKVQ_ERR_INVALID_ARG;
+  if ((long long)c->window > (1ll << 20) || c->n_sink > (1 << 20)) return SKVQ_ERR_INVALID_ARG;
+  // the kernels hold packed token numbers (and a tile's 64 tokens past the last one) in 32-bit integers
+  if (c->max_quant_tokens > SKVQ_MAX_QUANT_TOKENS) return SKVQ_ERR_UNSUPPORTED;
   if (!c->perm_k || !c->perm_v || !c->clip_k || !c->clip_v) return SKVQ_ERR_INVALID_ARG;
   const int ng = kD / c->group_size;
   if (c->group_bounds) {
@@ -556,6 +557,7 @@ int skvq_get_state(const skvq_cache *c, int64_t *n_tokens, int64_t *n_quant, int
 
 int skvq_set_state(skvq_cache *c, int64_t n_tokens) {
   if (!c || n_tokens < 0) return SKVQ_ERR_INVALID_ARG;
+  if (n_tokens < c->n_tokens) return SKVQ_ERR_STATE;  // no rewind: ring rows and V unit tails are gone
   const Counts n = counts_of(n_tokens, c->L.W, c->L.S);  // (the sink rule)
   if (n.n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   c->n_tokens = n_tokens;
@@ -575,7 +577,7 @@ const char *skvq_status_string(int s) {
     case SKVQ_ERR_INVALID_ARG: return "invalid argument";
     case SKVQ_ERR_UNSUPPORTED: return "unsupported configuration";
     case SKVQ_ERR_CAPACITY: return "packed region full";
-    case SKVQ_ERR_STATE: return "invalid state (empty cache)";
+    case SKVQ_ERR_STATE: return "invalid state (empty cache, or a rewind)";
     case SKVQ_ERR_HIP: return "HIP runtime error";
     default: return "unknown status";
   }

@@ -1030,7 +1030,7 @@ template <int KL, int VL>
 hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                                   int n_splits, int n_new, const __half *knew, const __half *vnew, long long te,
                                   hipStream_t s) {
-  if (T <= 0 || nq < 0 || nq > 0x7fffffffll * 32 || T - nq > 0x7fffffff || n_splits < 1 ||
+  if (T <= 0 || nq < 0 || nq > SKVQ_MAX_QUANT_TOKENS || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
   if (n_new < 1 || n_new > SKVQ_MAX_NEW_TOKENS || L.R > 8) return hipErrorInvalidValue;

@@ -14,9 +14,11 @@
 //        B = the wavefront's queries, held in registers for the whole kernel.  Computing the
 //        transpose puts the 32 scores that a lane holds (of 64) in the column of ONE query, so the
 //        running maximum and sum need one cross-lane exchange, and
-//   O^T[channel][query]  by 16 more: A = V^T tile, B = P^T, which is exactly what the lane
+//   O^T[channel][query]  by 32 more: A = V^T tile, B = P^T, which is exactly what the lane
 //        already holds: its exp2'd scores, converted to fp16, are the B operand as they are (the
-//        order of the keys inside a step of 16 is the accumulator's: both operands use it).
+//        order of the keys inside a step of 16 is the accumulator's: both operands use it).  Every
+//        weight enters twice, as a high and a low fp16 part on the same A operand, so that the
+//        output keeps ~22 bits of the weights (one fp16 part alone: an error up to 2^-12 max|V|).
 // Causality: a workgroup stops at the last tile its queries can see, a wavefront skips the tiles
 // beyond its own queries, and only tiles that straddle the diagonal are masked element-wise.
 #include <hip/hip_runtime.h>
@@ -41,7 +43,10 @@ constexpr int kKTile = 64;      // keys per tile
 constexpr int kKStride = 136;   // halves per K row in LDS (272 B: 16-byte aligned, rows on different banks)
 constexpr int kVStride = 72;    // halves per V^T row in LDS (144 B: 16-byte aligned, rows on different banks)
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kSlack = 8.0f;  // weights may reach 2^8 before the running reference moves
+// The running reference sits kBias below the largest score it was set from (that key's weight is
+// 2^kBias) and moves when a score exceeds it by more than kSlack: weights stay below 2^15, which fp16
+// holds, and a weight only falls under fp16's smallest step (2^-24) when it is 2^-31 of the largest.
+constexpr float kBias = 7.0f, kSlack = 15.0f;
 
 // max(a, b, c) in one instruction (the plain fmaxf first re-canonicalizes every matrix-core result)
 __device__ __forceinline__ float max3(float a, float b, float c) {
@@ -220,10 +225,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
             if (key > my_q) s[kb][x] = -INFINITY;
           }
       }
-      // The running reference m only moves when a score exceeds it by more than 2^kSlack (log2
-      // domain): then the weights stay below 2^kSlack, which fp16 holds, and the accumulators
-      // are rescaled on few tiles.  (Key 0 is visible to every query, so the first tile sets a
-      // finite reference.)
+      // The running reference m only moves when a score exceeds it by more than kSlack (log2
+      // domain): the weights stay below 2^kSlack, and the accumulators are rescaled on few
+      // tiles.  (Key 0 is visible to every query, so the first tile sets a finite reference.)
       float mloc = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -236,7 +240,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
         mloc = max3(ma, mb, mb) * c;  // c >= 0
       }
       if (__any(mloc > m + kSlack)) {
-        const float m_new = fmaxf(m, mloc);
+        const float m_new = fmaxf(m, mloc - kBias);
         const float alpha = exp2f(m - m_new);  // 0 at the first tile
         m = m_new;
         l *= alpha;
@@ -246,7 +250,11 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
           for (int x = 0; x < 16; ++x) o[blk][x] *= alpha;
       }
       float psum = 0.f;
-      half8_t p[4];  // B operands of the value product: step t covers keys 16 t .. 16 t + 15 of the tile
+      // B operands of the value product: step t covers keys 16 t .. 16 t + 15 of the tile.  A weight
+      // enters as two fp16 numbers, its top 11 significant bits (cut out of the fp32 value, so the
+      // conversion is exact) and the rest (rounded toward zero to 11 more): ~22 bits in all, so the
+      // weights' rounding stays below 2^-21 of the largest value instead of 2^-12.
+      uint4_t p[4], plo[4];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -254,9 +262,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
           const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][x], c, -m));
           const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][x + 1], c, -m));
           psum += p0 + p1;
-          const __half2 pk = __floats2half2_rn(p0, p1);
-          p[2 * kb + (x >> 3)][x & 7] = __builtin_bit_cast(_Float16, __low2half(pk));
-          p[2 * kb + (x >> 3)][(x & 7) + 1] = __builtin_bit_cast(_Float16, __high2half(pk));
+          const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, p0) & 0xffffe000u);
+          const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, p1) & 0xffffe000u);
+          p[2 * kb + (x >> 3)][(x & 7) >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(h0, h1));
+          plo[2 * kb + (x >> 3)][(x & 7) >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(p0 - h0, p1 - h1));
         }
       l += psum;
       // ---- values: the lane's slot e of step t is key 16 t + 8 (e/4) + 4 h + e%4 ----
@@ -276,7 +285,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           const int blk = 2 * (hs & 1) + i;
-          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[hs & 1][i], p[hs >> 1], o[blk], 0, 0, 0);
+          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[hs & 1][i], __builtin_bit_cast(half8_t, p[hs >> 1]), o[blk], 0, 0, 0);
+          o[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[hs & 1][i], __builtin_bit_cast(half8_t, plo[hs >> 1]), o[blk], 0, 0, 0);
         }
       }
     }

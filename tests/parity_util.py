@@ -1,8 +1,6 @@
 """Builds the same cache twice -- CPU oracle and HIP library -- from one set of seeded inputs."""
 from __future__ import annotations
 
-import os
-
 import numpy as np
 import torch
 
@@ -10,18 +8,12 @@ from oracle import skvq_oracle as O
 from paper_2405_06219_amd import binding as B
 from paper_2405_06219_amd import synth
 
-LOG_DIR = "gpurun_out"
 TOL = 2e-3  # max-abs bound on attention outputs (fp32), the build's stated floating-point bar
 
 
 def log(msg: str):
-    """Progress line on stdout and, when the run's output folder exists, in its parity.log (names the case
-    that was running if a run ends without a report)."""
+    """Progress line on stdout, flushed (names the case that was running if a run ends without a report)."""
     print(msg, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), LOG_DIR)
-    if os.path.isdir(d):
-        with open(os.path.join(d, "parity.log"), "a") as f:
-            f.write(msg + "\n")
 
 
 class Pair:

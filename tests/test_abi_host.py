@@ -88,6 +88,7 @@ def test_validation_rejects_bad_configs(B):
         (dict(max_new_tokens=-1), B.SKVQ_ERR_INVALID_ARG),
         (dict(max_new_tokens=65), B.SKVQ_ERR_INVALID_ARG),
         (dict(max_quant_tokens=0), B.SKVQ_ERR_INVALID_ARG),
+        (dict(max_quant_tokens=2 ** 31 - 64), B.SKVQ_ERR_UNSUPPORTED),   # packed token numbers are 32-bit in the kernels
         (dict(batch=0), B.SKVQ_ERR_INVALID_ARG),
         (dict(head_dim=64), B.SKVQ_ERR_UNSUPPORTED),
         (dict(group_size=16, clip=np.ones((8, 8), np.float32)), B.SKVQ_ERR_UNSUPPORTED),
@@ -106,6 +107,8 @@ def test_validation_rejects_bad_configs(B):
         assert B.skvq_validate_config(cfg) == want, kw
         with pytest.raises(B.SkvqError):
             B.skvq_sizes(cfg)
+    largest, keep_l = cfg_for(B, max_quant_tokens=2 ** 31 - 65)
+    assert B.skvq_validate_config(largest) == B.SKVQ_OK
     good, keep2 = cfg_for(B, group_size=32, clip=np.ones((8, 4), np.float32), group_bounds=[0, 16, 32, 48, 128])
     uniform, keep3 = cfg_for(B, group_size=32)
     assert B.skvq_validate_config(good) == B.SKVQ_OK and B.skvq_sizes(good) == B.skvq_sizes(uniform)

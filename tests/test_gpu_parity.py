@@ -105,6 +105,27 @@ def test_encoder_special_values_bit_exact(P):
     pair.assert_buffers_equal()
 
 
+@pytest.mark.parametrize("bits,vals", [(2.0, (0.0, 37.5, 45.0, 15.0, 30.0)), (4.0, (0.0, 45.5, 105.0, 87.5, 101.5, 7.0))])
+def test_encoder_reciprocal_ties_bit_exact(P, bits, vals):
+    """Groups whose step h has an inexact reciprocal and whose values sit exactly on a tie of (x - z)/h:
+    (x - z) * fl(1/h) lands on the other side (codes worked out in the oracle's pin of this reading)."""
+    w = small("recip_ties", n_q_heads=2, n_kv_heads=2, context=8 + 40, window=8, group_size=32, v_bits=bits, k_bits=bits)
+    rng = np.random.default_rng(19)
+    T = w.context
+    k = np.zeros((1, 2, T, D), np.float16)
+    v = np.zeros((1, 2, T, D), np.float16)
+    for t in range(T):
+        for h in range(2):
+            scale = np.float16(2.0 ** int(rng.integers(-6, 3)))     # power-of-two scalings keep the ties
+            k[0, h, t] = rng.choice(np.array(vals, np.float16), D) * scale
+            v[0, h, t] = rng.choice(np.array(vals, np.float16), D) * scale
+    ident = np.tile(np.arange(D, dtype=np.int32), (2, 1))
+    ones = np.ones((2, 4), np.float32)
+    pair = P.Pair(w, 64, ident, ident, ones, ones)
+    pair.prefill(k, v)
+    pair.assert_buffers_equal()
+
+
 DECODE_CASES = [
     small("mha_t15", context=1500),
     small("mha_v2_outlier", v_bits=2.0, channel_profile="outlier4", perm_stat="absmax", context=2048),
@@ -312,6 +333,44 @@ def test_runtime_errors(P):
     torch.cuda.synchronize()
 
 
+def test_set_state_adopts_buffers_and_refuses_a_rewind(P):
+    """skvq_set_state: a second cache whose buffers are copies of a filled cache's, told the token
+    count, continues exactly like the first (appends, sink rows and attention against the oracle);
+    a count below the current one is refused (SKVQ_ERR_STATE) and changes nothing."""
+    B = P.B
+    w = small("adopt", n_q_heads=8, n_kv_heads=2, context=300, window=16, v_bits=1.5)
+    S = 3
+    pair, k, v, q = P.make_pair(w, extra_tokens=40, n_sink=S)
+    pair.prefill(k, v)
+    for s in range(5):
+        pair.append(*synth.make_new_token(w, s))
+    torch.cuda.synchronize()
+    other = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
+                        pair.gpu.cfg.max_quant_tokens, pair.gpu._keep[0], pair.gpu._keep[1], pair.gpu._keep[2],
+                        pair.gpu._keep[3], n_sink=S, k_bits=w.k_bits, fill=0x5C)
+    for name in B.BUFFER_NAMES[:6]:
+        other.buffers[name].copy_(pair.gpu.buffers[name])
+    n_now = pair.gpu.skvq_get_state()[0]
+    with pytest.raises(B.SkvqError) as e:
+        other.skvq_set_state(10 ** 9)                    # cannot fit
+    assert e.value.status == B.SKVQ_ERR_CAPACITY and other.skvq_get_state() == (0, 0, 0)
+    other.skvq_set_state(n_now)
+    assert other.skvq_get_state() == pair.gpu.skvq_get_state()
+    with pytest.raises(B.SkvqError) as e:
+        other.skvq_set_state(n_now - 1)                  # no rewind
+    assert e.value.status == B.SKVQ_ERR_STATE and other.skvq_get_state() == pair.gpu.skvq_get_state()
+    other.skvq_set_state(n_now)                          # the same count again is fine
+    pair.gpu = other                                     # from here on the adopted cache is the one compared
+    for s in range(5, 40):
+        pair.append(*synth.make_new_token(w, s))
+    pair.assert_buffers_equal()
+    out, ref = pair.decode_both(q)
+    assert np.abs(out - ref).max() <= P.TOL
+    out, ref = pair.append_decode_both(*synth.make_new_token(w, 40), q)
+    assert np.abs(out - ref).max() <= P.TOL
+    pair.assert_buffers_equal()
+
+
 def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
     """Mistral-7B-shaped layer at 131072 tokens (the benchmark's workload, library-chosen split
     count): every packed byte, every (scale, zero) and the ring bit-exact against the oracle's
@@ -338,7 +397,8 @@ def test_full_size_c3_in_the_benchmarked_launch_configuration(P):
     pair.assert_buffers_equal()
 
 
-@pytest.mark.parametrize("name,n_heads,bits", [("c5_batch16_32k", 4, None), ("c4_llama7b_1m", 2, None),
+@pytest.mark.parametrize("name,n_heads,bits", [("c1_mha4_2k", 8, None), ("c2_llama7b_32k", 3, None),
+                                               ("c5_batch16_32k", 4, None), ("c4_llama7b_1m", 2, None),
                                                ("c3_mistral7b_128k", 3, (4.0, 4.0)),
                                                ("c3_mistral7b_128k", 2, (3.0, 3.0))])
 def test_full_size_sampled_heads(P, name, n_heads, bits):
@@ -633,15 +693,16 @@ PREFILL_ATTN_CASES = [(1, 4, 4, 300), (2, 8, 2, 777), (1, 3, 1, 1000), (1, 2, 2,
 
 @pytest.mark.parametrize("B,Hq,Hk,T", PREFILL_ATTN_CASES)
 def test_prefill_attention_matches_oracle(P, B, Hq, Hk, T):
-    """fp32 outputs against the fp64 oracle.  The weights enter the value product as fp16 (11
-    significant bits), so the bound is 2^-11 of the largest value magnitude (plus fp32 rounding)."""
+    """fp32 outputs against the fp64 oracle, within the 2e-3 of every attention output (the weights
+    enter the value product as a high and a low fp16 part); K and V with the channel spread of the
+    baseline workloads (scales 0.1 .. 10)."""
     from oracle import skvq_oracle as O
     from paper_2405_06219_amd import binding as Bd
     print("case", B, Hq, Hk, T, flush=True)
     rng = np.random.default_rng(3000 + T)
     q = rng.standard_normal((B, Hq, T, D)).astype(np.float16)
-    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
-    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
+    k = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1.0, 1.0, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D)) * 10 ** rng.uniform(-1.0, 1.0, (1, Hk, 1, D))).astype(np.float16)
     perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
     one = np.ones((Hk, 1), np.float32)
     ref = O.OracleCache(B, Hq, Hk, 128, 1.5, 8, 8, perm, perm, one, one).prefill_attention(q, k, v)
@@ -653,7 +714,7 @@ def test_prefill_attention_matches_oracle(P, B, Hq, Hk, T):
     torch.cuda.synchronize()
     out = out.cpu().numpy()
     err = np.abs(out - ref).max()
-    bound = 2.0 ** -11 * float(np.abs(v.astype(np.float32)).max()) + 1e-5
+    bound = P.TOL
     P.log(f"prefill attention B{B} Hq{Hq} Hk{Hk} T{T}: max abs err {err:.3e} (bound {bound:.3e}, ref max {np.abs(ref).max():.3f})")
     assert err <= bound
     assert np.array_equal(o16.cpu().numpy(), out.astype(np.float16))
@@ -669,8 +730,8 @@ def test_prefill_attention_long_prompt_sampled_rows(P, B, Hq, Hk, T):
     print("case", B, Hq, Hk, T, flush=True)
     rng = np.random.default_rng(3100 + T)
     q = rng.standard_normal((B, Hq, T, D), dtype=np.float32).astype(np.float16)
-    k = (rng.standard_normal((B, Hk, T, D), dtype=np.float32) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
-    v = (rng.standard_normal((B, Hk, T, D), dtype=np.float32) * 10 ** rng.uniform(-0.5, 0.5, (1, Hk, 1, D))).astype(np.float16)
+    k = (rng.standard_normal((B, Hk, T, D), dtype=np.float32) * 10 ** rng.uniform(-1.0, 1.0, (1, Hk, 1, D))).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, T, D), dtype=np.float32) * 10 ** rng.uniform(-1.0, 1.0, (1, Hk, 1, D))).astype(np.float16)
     perm = np.tile(np.arange(D, dtype=np.int32), (Hk, 1))
     one = np.ones((Hk, 1), np.float32)
     ts = [0, 1, 31, 32, 63, 64, 65, 127, 255, 256, 257, 511, 512, 8191, 8192, T // 2 - 1, T // 2, T - 257, T - 256,
@@ -687,7 +748,7 @@ def test_prefill_attention_long_prompt_sampled_rows(P, B, Hq, Hk, T):
     idx = np.asarray(rows)
     got = out[idx[:, 0], idx[:, 1], idx[:, 2]].cpu().numpy()
     err = np.abs(got - ref).max()
-    bound = 2.0 ** -11 * float(np.abs(v.astype(np.float32)).max()) + 1e-5
+    bound = P.TOL
     P.log(f"prefill attention (sampled rows) B{B} Hq{Hq} Hk{Hk} T{T}: {len(rows)} rows, max abs err {err:.3e} (bound {bound:.3e})")
     assert err <= bound
 
@@ -706,7 +767,7 @@ def test_prefill_phase_in_one_call(P):
     out = pair.gpu.skvq_prefill_attention_quantize(torch.from_numpy(qp).to(dev), torch.from_numpy(k).to(dev),
                                                    torch.from_numpy(v).to(dev))
     torch.cuda.synchronize()
-    assert np.abs(out.cpu().numpy() - ref_attn).max() <= 2.0 ** -11 * float(np.abs(v.astype(np.float32)).max()) + 1e-5
+    assert np.abs(out.cpu().numpy() - ref_attn).max() <= P.TOL
     pair.assert_buffers_equal()
     o, r = pair.append_decode_both(*synth.make_new_token(w, 0), q)
     assert np.abs(o - r).max() <= P.TOL

@@ -69,6 +69,31 @@ def test_encoder_hand_derived_values(oracle):
     assert z == 2.0 and h == (8.0 - 2.0) / 3 and list(c) == [1, 3, 3]
 
 
+def test_encoder_divides_by_multiplying_with_the_rounded_reciprocal(oracle):
+    """Reading of Eq. 2's division (X - z)/h: t = (x - z) * fl(1/h), one fp32 reciprocal per group and one
+    fp32 multiply per value -- not an fp32 division per value.  The two differ on rare ties; groups worked
+    out by hand where they do:
+      2-bit, alpha = 1, group {0, 37.5, 45}: z = 0, h = 45/3 = 15.  Exact quotient of 37.5: 2.5, a tie, which
+        a division would round to the even code 2.  fl(1/15) = 0x3D888889 = 0.0666666701436..., above 1/15 by
+        5.2e-8 relative; 37.5 * fl(1/15) = 2.50000013..., more than half an ulp (1.19e-7) above 2.5, so the fp32
+        product is 2.5 + 2^-22 and rounds to code 3.
+      4-bit, alpha = 1, group {0, 45.5, 105}: h = 105/15 = 7; exact quotient 6.5 (division: code 6);
+        fl(1/7) = 0x3E124925 is 4.5e-8 relative above 1/7, the product 6.50000029... rounds to 6.5 + 2^-21: code 7."""
+    f32 = np.float32
+    inv15 = f32(1) / f32(15)
+    assert inv15.view(np.uint32) == 0x3D888889 and float(f32(37.5) * inv15) == 2.5 + 2.0 ** -22
+    assert float(f32(37.5) / f32(15)) == 2.5                       # what a per-value division would see
+    c, h, z = oracle.encode_group(np.array([0, 37.5, 45], np.float32), 1.0, 4)
+    assert h == 15.0 and z == 0.0 and list(c) == [0, 3, 3]
+    inv7 = f32(1) / f32(7)
+    assert inv7.view(np.uint32) == 0x3E124925 and float(f32(45.5) * inv7) == 6.5 + 2.0 ** -21
+    c, h, z = oracle.encode_group(np.array([0, 45.5, 105], np.float32), 1.0, 16)
+    assert h == 7.0 and z == 0.0 and list(c) == [0, 7, 15]
+    # the same groups scaled by a power of two (exact in every step): same codes
+    c, h, z = oracle.encode_group(np.array([0, 37.5, 45], np.float32) / 64, 1.0, 4)
+    assert h == 15.0 / 64 and list(c) == [0, 3, 3]
+
+
 @pytest.mark.parametrize("levels", [4, 3, 16, 8])
 def test_encoder_error_bound_and_clipping(oracle, levels):
     rng = np.random.default_rng(11 + levels)
@@ -630,6 +655,52 @@ def test_filter_mask_of_the_first_tokens_is_the_sink_rule(oracle):
     for x, y in zip(a.arrays(), b.arrays()):
         assert np.array_equal(x, y)
     assert np.array_equal(a.decode(q), b.decode(q))
+
+
+def test_append_without_a_decision_follows_the_sink_rule(oracle):
+    """A cache driven by masks, then appended to without a decision (keep=None): the token that leaves is
+    kept exactly when its number is below S (the attention-sink rule; a row is then always free, since at
+    most that many older tokens can have been kept).  Expected buffers are built from the statement of the
+    rule: kept token j-th in order sits in fp16 row W + j bit for bit, the others are the packed rows of a
+    cache without kept rows over the same tokens in order."""
+    rng = np.random.default_rng(640)
+    B, Hq, Hk, W, S = 1, 2, 2, 4, 3
+    n = 12
+    k = (rng.standard_normal((B, Hk, n, D)) * 3).astype(np.float16)
+    v = (rng.standard_normal((B, Hk, n, D)) * 3).astype(np.float16)
+    pk, pv = random_perms(rng, Hk), random_perms(rng, Hk)
+    clip = np.full((Hk, 1), 0.9, np.float32)
+
+    def tok(t):
+        return np.ascontiguousarray(k[:, :, t]), np.ascontiguousarray(v[:, :, t])
+
+    # (a) the mask kept token 0 at prefill; tokens 1 and 2 leave undecided -> kept (1, 2 < S); token 3 -> packed
+    a = oracle.OracleCache(B, Hq, Hk, 128, 2.0, W, 16, pk, pv, clip, clip, n_sink=S)
+    assert a.prefill(k[:, :, :W + 1], v[:, :, :W + 1], keep=np.array([True])) == 0
+    for t in range(W + 1, W + 4):
+        assert a.append(*tok(t)) == 0
+    assert a.n_quant == 1
+    for j in range(3):
+        assert np.array_equal(a.k_win[:, :, W + j].view(np.float16), k[:, :, j])
+        assert np.array_equal(a.v_win[:, :, W + j].view(np.float16), v[:, :, j])
+    ref = oracle.OracleCache(B, Hq, Hk, 128, 2.0, W, 16, pk, pv, clip, clip)
+    assert ref.prefill(k[:, :, 3:W + 4], v[:, :, 3:W + 4]) == 0 and ref.n_quant == 1
+    for x, y in zip(a.arrays()[:4], ref.arrays()[:4]):
+        assert np.array_equal(x, y)
+    # (b) the mask kept nothing of tokens 0, 1 (rows free): undecided token 2 < S is kept, in the first free row
+    b = oracle.OracleCache(B, Hq, Hk, 128, 2.0, W, 16, pk, pv, clip, clip, n_sink=S)
+    assert b.prefill(k[:, :, :W + 2], v[:, :, :W + 2], keep=np.array([False, False])) == 0
+    assert b.append(*tok(W + 2)) == 0 and b.n_quant == 2
+    assert np.array_equal(b.k_win[:, :, W].view(np.float16), k[:, :, 2])
+    assert b.append(*tok(W + 3)) == 0 and b.n_quant == 3          # token 3 >= S: packed although rows are free
+    # (c) no row free (S = 1, taken by the mask): undecided token 1 >= S is packed
+    c = oracle.OracleCache(B, Hq, Hk, 128, 2.0, W, 16, pk, pv, clip, clip, n_sink=1)
+    assert c.prefill(k[:, :, :W + 1], v[:, :, :W + 1], keep=np.array([True])) == 0
+    assert c.append(*tok(W + 1)) == 0 and c.n_quant == 1
+    ref = oracle.OracleCache(B, Hq, Hk, 128, 2.0, W, 16, pk, pv, clip, clip)
+    assert ref.prefill(k[:, :, 1:W + 2], v[:, :, 1:W + 2]) == 0
+    for x, y in zip(c.arrays()[:4], ref.arrays()[:4]):
+        assert np.array_equal(x, y)
 
 
 def test_filter_mask_packed_rows_are_the_unkept_tokens_in_order(oracle):
