@@ -223,6 +223,21 @@ int skvq_quantize_append(skvq_cache *cache, const void *k_new, const void *v_new
  * SKVQ_ERR_STATE if the cache is empty. */
 int skvq_decode_attention(skvq_cache *cache, const void *q, void *out_f32, void *out_f16,
                           void *hip_stream);
+/* skvq_decode_attention for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and
+ * the same results, but the split partials go to a fixed array inside the library's device image
+ * (SKVQ_STATIC_MAX_ROWS * (SKVQ_MAX_SPLITS + 1) * 132 floats = 4.4 MB per GPU, held until the
+ * process ends) instead of skvq_buffers.workspace, and the call makes no hipMalloc / hipFree or any
+ * allocating library call.  The array's address on the cache's device is looked up once, in
+ * skvq_create.  SKVQ_ERR_UNSUPPORTED if batch * n_q_heads > SKVQ_STATIC_MAX_ROWS (nothing is
+ * launched); SKVQ_ERR_HIP if that lookup had failed.  Every cache on one GPU shares the array:
+ * calls of this entry point that overlap on one GPU (different streams) race -- keep them on one
+ * stream or order the streams.  Nothing in the array has to start at zero (every partial that the
+ * merge reads is written by the same call first), so it is never cleared. */
+#define SKVQ_STATIC_MAX_ROWS 64
+int skvq_decode_attention_static(skvq_cache *cache, const void *q, void *out_f32, void *out_f16,
+                                 void *hip_stream);
+
 /* One decode step of Algorithm 1 with l = 1 as a single call: skvq_quantize_append(k_new, v_new)
  * followed by skvq_decode_attention(q), same arguments, same results in the cache and in the
  * outputs, same errors.  When a kv head has at most four query heads, its packed rows are split

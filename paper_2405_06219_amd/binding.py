@@ -19,6 +19,7 @@ SKVQ_OK = 0
 SKVQ_ERR_INVALID_ARG, SKVQ_ERR_UNSUPPORTED, SKVQ_ERR_CAPACITY, SKVQ_ERR_STATE, SKVQ_ERR_HIP = -1, -2, -3, -4, -5
 SKVQ_BITS_4, SKVQ_BITS_3, SKVQ_BITS_2, SKVQ_BITS_1P5 = 16, 8, 4, 3
 SKVQ_MAX_SPLITS = 128
+SKVQ_STATIC_MAX_ROWS = 64
 HEAD_DIM = 128
 BUFFER_NAMES = ("k_codes", "v_codes", "k_meta", "v_meta", "k_win", "v_win", "workspace")
 
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
                                                      C.c_void_p]
         L.skvq_quantize_append_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.skvq_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.skvq_decode_attention_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.skvq_append_decode_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                    C.c_void_p, C.c_void_p]
         L.skvq_get_state.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
@@ -311,6 +313,16 @@ class SkvqCache:
         op = _dev_ptr(out_f32, torch.float32, (b, hq, HEAD_DIM))
         hp = _dev_ptr(out_f16, torch.float16, (b, hq, HEAD_DIM)) if out_f16 is not None else None
         self._check(lib().skvq_decode_attention(self._h, qp, op, hp, _stream_ptr(stream)))
+        return out_f32
+
+    def skvq_decode_attention_static(self, q: torch.Tensor, out_f32: torch.Tensor, out_f16: torch.Tensor | None = None,
+                                     stream=None) -> torch.Tensor:
+        """The variant that allocates nothing: the caller passes the output tensor too."""
+        b, hq, _ = self.shape
+        qp = _dev_ptr(q, torch.float16, (b, hq, HEAD_DIM))
+        op = _dev_ptr(out_f32, torch.float32, (b, hq, HEAD_DIM))
+        hp = _dev_ptr(out_f16, torch.float16, (b, hq, HEAD_DIM)) if out_f16 is not None else None
+        self._check(lib().skvq_decode_attention_static(self._h, qp, op, hp, _stream_ptr(stream)))
         return out_f32
 
     def skvq_append_decode_attention(self, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor,

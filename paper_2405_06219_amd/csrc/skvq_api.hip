@@ -14,7 +14,17 @@
 
 using namespace skvq;
 
+// Split partials of skvq_decode_attention_static: device memory that exists from load time, so that
+// the call itself allocates nothing.  One copy per GPU, shared by every cache on that GPU; the name
+// below is only a host-side handle, the device address comes from hipGetSymbolAddress (per device).
+// (File scope, not an unnamed namespace: the runtime finds the device copy by the symbol's name.)
+constexpr size_t kStaticScratchFloats =
+    (size_t)SKVQ_STATIC_MAX_ROWS * (SKVQ_MAX_SPLITS + 1) * skvq::kPartialStride;
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
 struct skvq_cache {
+  float *static_scratch = nullptr;  // this cache's device's copy of `scratch` (looked up at creation)
+  int device = -1;                  // the HIP device that was current at creation
   Layout L;
   long long n_tokens = 0;
   long long n_kept = 0;  // tokens older than the window that the filter rules keep in fp16 (<= L.S)
@@ -266,6 +276,17 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
       prop.multiProcessorCount > 0)
     c->n_cus = prop.multiProcessorCount;
+  // the static scratch array's address on this device (each GPU has its own copy at its own address)
+  c->device = dev;
+  void *sp = nullptr;
+  e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
+  if (e == hipSuccess) {
+    c->static_scratch = (float *)sp;
+  } else {
+    c->static_scratch = nullptr;  // skvq_decode_attention_static reports it; the other calls do not need it
+    c->last_error = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+    (void)hipGetLastError();
+  }
   *out = c;
   return SKVQ_OK;
 }
@@ -503,6 +524,22 @@ int skvq_decode_attention(skvq_cache *c, const void *q, void *out_f32, void *out
   hipError_t e = launch_decode(c->L, (const __half *)q, (float *)out_f32, (__half *)out_f16, c->n_tokens, c->n_kept,
                                choose_splits(c, counts_now(c).n_quant), 1, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention launch");
+  return SKVQ_OK;
+}
+
+int skvq_decode_attention_static(skvq_cache *c, const void *q, void *out_f32, void *out_f16, void *stream) {
+  if (!c || !q || !out_f32) return SKVQ_ERR_INVALID_ARG;
+  if (c->n_tokens <= 0) return SKVQ_ERR_STATE;
+  if ((long long)c->L.B * c->L.Hq > SKVQ_STATIC_MAX_ROWS) {
+    c->last_error = "skvq_decode_attention_static: batch * n_q_heads exceeds SKVQ_STATIC_MAX_ROWS";
+    return SKVQ_ERR_UNSUPPORTED;
+  }
+  if (!c->static_scratch) return SKVQ_ERR_HIP;  // the lookup at creation failed; last_error says why
+  Layout L = c->L;
+  L.workspace = c->static_scratch;  // the kernels take it as they take the caller's workspace
+  hipError_t e = launch_decode(L, (const __half *)q, (float *)out_f32, (__half *)out_f16, c->n_tokens, c->n_kept,
+                               choose_splits(c, counts_now(c).n_quant), 1, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e, "skvq_decode_attention_static launch");
   return SKVQ_OK;
 }
 
