@@ -330,6 +330,16 @@ int skvq_set_state(skvq_cache *cache, int64_t n_tokens);
 #define SKVQ_MAX_SPLITS 128
 int skvq_set_num_splits(skvq_cache *cache, int32_t n_splits);
 
+/* Where the chunks' partial results are combined.  A kv head that is read as ONE chunk has its
+ * output written by that chunk's workgroup (no second launch).  Several chunks are combined by a
+ * second launch (the default), or, with enable != 0, inside the same launch by the workgroup that
+ * finishes last, whenever the chunks of a kv head can be placed on one XCD of the chip (found out by
+ * a probe when the cache is created; the chunk count must be a multiple of 8, and so must
+ * n_kv_heads x passes on a chip whose workgroups go round 8 XCDs).  Results agree to rounding.
+ * Measured on MI355X the two take the same time (the hand-off through the L2 costs what the second
+ * launch costs), hence the default.  A tuning and test knob. */
+int skvq_set_merge_in_kernel(skvq_cache *cache, int32_t enable);
+
 /* Static description of a status code; the cache's last HIP error text (owned by cache). */
 const char *skvq_status_string(int status);
 const char *skvq_last_error(const skvq_cache *cache);

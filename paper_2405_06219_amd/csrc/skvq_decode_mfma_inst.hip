@@ -10,5 +10,5 @@
 namespace skvq {
 template hipError_t launch_decode_mfma_fmt<SKVQ_KL, SKVQ_VL>(const Layout &, const __half *, long long, long long,
                                                              int, int, int, const __half *, const __half *, long long,
-                                                             hipStream_t);
+                                                             MergeOut, hipStream_t);
 }  // namespace skvq

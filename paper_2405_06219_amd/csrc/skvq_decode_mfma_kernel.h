@@ -43,21 +43,6 @@
 #include "skvq_append_device.h"
 
 namespace skvq {
-#ifdef SKVQ_TIMING
-__device__ unsigned long long skvq_timing[16 * 4096];
-#define SKVQ_STAMP(slot)                                                                    \
-  if (threadIdx.x == 0)                                                                     \
-  skvq_timing[16 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + (slot)] = \
-      __builtin_amdgcn_s_memrealtime()
-__device__ unsigned long long skvq_timing_w[32 * 4096];
-#define SKVQ_WSTAMP(slot)                                                                   \
-  if ((threadIdx.x & 63) == 0)                                                              \
-  skvq_timing_w[32 * ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) + 2 * (threadIdx.x >> 6) + (slot)] = \
-      __builtin_amdgcn_s_memrealtime()
-#else
-#define SKVQ_STAMP(slot)
-#define SKVQ_WSTAMP(slot)
-#endif
 namespace {
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -196,6 +181,8 @@ constexpr int kAppendLagTiles = 12;  // tiles that the workgroup which also appe
 constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
 constexpr int kRingSlice = 4;       // ring tokens per slice (the slice code reads four rows of 16 lanes)
 
+constexpr int kHwRegXccId = 20 | (0 << 6) | (3 << 11);  // s_getreg operand: HW_REG_XCC_ID, bits 0..3 (the XCD this wave runs on)
+
 constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumulator columns over the banks
 
 template <int R, bool TERNARY, int NG>
@@ -215,8 +202,10 @@ struct Smem {
   float qpart[4][8];                   // per head: sums of the reordered query over 16 positions each
   // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
   // tiles (w*) and for the ring slices (r*) of the wave
-  float wm[kNW][R], wl[kNW][R], wz[kNW][R][NG], rm[kNW][R], rl[kNW][R];
+  // ([head][...][wave]: the epilogue reads a head's eight entries as two 16-byte pieces)
+  alignas(16) float wm[R][kNW], wl[R][kNW], wz[R][NG][kNW], rm[R][kNW], rl[R][kNW];
   float ring_o[kNW][R][kD];            // per wave: its ring slices' outputs, original channel order
+  unsigned merge_ticket;               // in-kernel merge: how many chunks of the kv head had finished before this one
 };
 
 // One 4-channel step of the score product.  The A operand of step ST lives in lanes
@@ -328,7 +317,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
                                                                   int n_splits, int passes, int n_new,
                                                                   const __half *__restrict__ knew,
                                                                   const __half *__restrict__ vnew, long long te,
-                                                                  ChunkPlan plan) {
+                                                                  ChunkPlan plan, MergeOut mo) {
   // grid (n_splits, Hk * passes, B): R is the number of query heads one workgroup serves; a kv
   // head with more than four (or with three) query heads is served by `passes` workgroups per
   // chunk, each with R of its L.R query heads (the last one possibly with fewer: the missing
@@ -344,13 +333,22 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // score accumulators / weight operands: one per group, or (unequal groups) one per 16 positions
   constexpr int NACC = UNEQ ? 8 : NG;
   __shared__ Smem<R, TERNARY, NG> sm;
-  SKVQ_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sp = blockIdx.x, hk = passes == 1 ? blockIdx.y : blockIdx.y / passes, b = blockIdx.z;
+  // Chunk and (kv head, pass) of this workgroup.  For the in-kernel merge on a chip whose workgroups go
+  // round the 8 XCDs (grid x and y are multiples of 8 then, so the XCD is blockIdx.x % 8), the low three
+  // bits of the two block indices trade places: all chunks of a (kv head, pass) then run on XCD
+  // (its index) % 8, and their partials meet in that XCD's L2.
+  int sp = blockIdx.x, by = blockIdx.y;
+  if (mo.mode == kMergeInKernel && mo.check_xcd) {
+    const int lo_x = sp & 7, lo_y = by & 7;
+    sp = (sp & ~7) | lo_y;
+    by = (by & ~7) | lo_x;
+  }
+  const int hk = passes == 1 ? by : by / passes, b = blockIdx.z;
   const unsigned gmap = UNEQ ? L.gmaps[hk] : 0u;
   auto piece_group = [&](int n) { return (int)((gmap >> (4 * n)) & 15u); };  // group of positions 16n..16n+15
-  const int head0 = passes == 1 ? 0 : (blockIdx.y % passes) * R;  // first of this workgroup's query heads, within the kv head's
+  const int head0 = passes == 1 ? 0 : (by % passes) * R;  // first of this workgroup's query heads, within the kv head's
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;
 
@@ -473,14 +471,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // ---- prologue: one memory round trip.  The small loads (query, permutations, table) are
   //      issued BEFORE the tile loads: loads return in order, so the staging below only has to
   //      wait for them and not for the two tiles of packed data behind them. ----
-  SKVQ_STAMP(4);
-  __half2 q2 = __floats2half2_rn(0.f, 0.f);
   const int n_rows = n_new * L.R;  // rows of this kv head: (query token, query head)
   // row x of the kv head -> index of its (sequence, query token, query head) in q, the partials and the output
   auto row_index = [&](int x) {
     const int j = n_new == 1 ? 0 : x / L.R;  // (no division on the single-token path)
     return ((long long)b * n_new + j) * L.Hq + hk * L.R + (x - j * L.R);
   };
+  __half2 q2 = __floats2half2_rn(0.f, 0.f);
   if (tid < 64 * R && head0 + (tid >> 6) < n_rows)
     q2 = reinterpret_cast<const __half2 *>(q + row_index(head0 + (tid >> 6)) * kD)[lane];
   const int pk = L.perm_k[hk * kD + (tid & 127)];
@@ -536,12 +533,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       sm.qraw[tid >> 6][2 * lane] = __low2float(q2);
       sm.qraw[tid >> 6][2 * lane + 1] = __high2float(q2);
     }
-    SKVQ_STAMP(5);
-    SKVQ_STAMP(6);
     __syncthreads();
     asm volatile("" ::: "memory");
     buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
-    SKVQ_STAMP(10);
     if (tid < 256) {
 #pragma unroll
       for (int rr = 0; rr < 2; ++rr) {  // thread (p = tid%128, heads tid/128 and tid/128 + 2)
@@ -563,7 +557,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       }
     }
     __syncthreads();
-    SKVQ_STAMP(11);
   }
   // lane l supplies row l%4 (= head) of step l/4 (first register pair) and 16 + l/4 (second)
   const half4_t qop_lo = *reinterpret_cast<const half4_t *>(sm.qa[lane >> 2][lane & 3]);
@@ -677,11 +670,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     for (int r = 0; r < R; ++r) {
       sm.ring_o[wave][r][2 * lane] = ro[r][0];
       sm.ring_o[wave][r][2 * lane + 1] = ro[r][1];
-      if (lane == 0) sm.rm[wave][r] = rm[r], sm.rl[wave][r] = rl[r];
+      if (lane == 0) sm.rm[r][wave] = rm[r], sm.rl[r][wave] = rl[r];
     }
   } else if (lane < R) {
-    sm.rm[wave][lane] = -INFINITY;
-    sm.rl[wave][lane] = 0.f;
+    sm.rm[lane][wave] = -INFINITY;
+    sm.rl[lane][wave] = 0.f;
   }
   // (No ring load younger than the tile loads may be pending here: it would turn every wait
   // inside the tile loop into a wait for all loads.)
@@ -699,8 +692,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   for (int n = 0; n < 8; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
   bool first = true;
 
-  SKVQ_STAMP(1);
-  SKVQ_WSTAMP(0);
   auto compute_tile = [&](const Tile &cur, const int tile) {
     const bool valid = tile * 64 + lane <= last_token;
 
@@ -917,9 +908,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   while (tile_c < tile_end) {
     buf_c = load_tile(tile_c);
     compute_tile(buf_a, tile_a);
-#ifdef SKVQ_TIMING
-    if (n_a == 0) { SKVQ_STAMP(12); }
-#endif
     tile_a = tile_of(n_a += 3);
     buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
     compute_tile(buf_b, tile_b);
@@ -938,20 +926,18 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     tile_b = tile_end;
   }
 
-  SKVQ_STAMP(2);
-  SKVQ_WSTAMP(1);
   // ---- epilogue: fold lanes, columns, waves and ring slices; write this chunk's partial ----
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const float ls = wave_sum_fast(lsum[r]);
     if (lane == 0) {
-      sm.wm[wave][r] = first ? -INFINITY : mref[r];
-      sm.wl[wave][r] = ls;
+      sm.wm[r][wave] = first ? -INFINITY : mref[r];
+      sm.wl[r][wave] = ls;
     }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       const float zs = wave_sum_fast(zacc[r][g]);
-      if (lane == 0) sm.wz[wave][r][g] = zs;
+      if (lane == 0) sm.wz[r][g][wave] = zs;
     }
   }
   if (!first) {
@@ -960,29 +946,39 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     const float unscale = (TERNARY ? 65536.0f : 1048576.0f) / beta;
 #pragma unroll
     for (int n = 0; n < 8; ++n)
+    {
+      float4_t o4;
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        const float lo_part = row_move<kRowShl + R>(acc[n][rr]);  // column R + r: the low halves' sum
-        if (col < R) sm.wb[wave].stage[col][16 * n + 4 * kb + rr] = (acc[n][rr] + lo_part) * unscale;
-      }
+      for (int rr = 0; rr < 4; ++rr)
+        o4[rr] = (acc[n][rr] + row_move<kRowShl + R>(acc[n][rr])) * unscale;  // + column R + r: the low halves' sum
+      if (col < R) *reinterpret_cast<float4_t *>(&sm.wb[wave].stage[col][16 * n + 4 * kb]) = o4;
+    }
   }
   __syncthreads();
-  SKVQ_STAMP(8);
-  SKVQ_STAMP(9);
   if (tid < R * kD && head0 + (tid >> 7) < n_rows) {
     // thread (head r, position p): the chunk's reference m* = max over waves and ring slices,
     // each one's factor 2^(m - m*), the sums that need no channel (every thread of a head
     // computes the same ones: cheaper than another exchange through LDS), its channel's sum
     const int r = tid >> 7, p = tid & 127;
     const int ch = pv_ch;
-    float wm[kNW], wl[kNW], rm[kNW], rl[kNW];
+    static_assert(kNW == 8, "the epilogue reads eight per-wave entries as two 16-byte pieces");
+    float wm[kNW], wl[kNW], rm[kNW], rl[kNW], wz[kNW];
+    const int zg = UNEQ ? piece_group(p >> 4) : p * NG / kD;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const float4_t a = *reinterpret_cast<const float4_t *>(&sm.wm[r][4 * h]);
+      const float4_t b4 = *reinterpret_cast<const float4_t *>(&sm.wl[r][4 * h]);
+      const float4_t c4 = *reinterpret_cast<const float4_t *>(&sm.rm[r][4 * h]);
+      const float4_t d = *reinterpret_cast<const float4_t *>(&sm.rl[r][4 * h]);
+      const float4_t z = *reinterpret_cast<const float4_t *>(&sm.wz[r][zg][4 * h]);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) wm[4 * h + x] = a[x], wl[4 * h + x] = b4[x], rm[4 * h + x] = c4[x], rl[4 * h + x] = d[x], wz[4 * h + x] = z[x];
+    }
     float m = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kNW; ++w) {
-      const float wm_w = sm.wm[w][r], rm_w = sm.rm[w][r];
-      wl[w] = sm.wl[w][r], rl[w] = sm.rl[w][r];
-      wm[w] = wl[w] > 0.f ? wm_w : -INFINITY;
-      rm[w] = rl[w] > 0.f ? rm_w : -INFINITY;
+      wm[w] = wl[w] > 0.f ? wm[w] : -INFINITY;
+      rm[w] = rl[w] > 0.f ? rm[w] : -INFINITY;
       m = fmaxf(m, fmaxf(wm[w], rm[w]));
     }
     // (every read unconditional, what a wave or slice without tokens left there is deselected
@@ -991,7 +987,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     float ws[kNW], rs[kNW];
 #pragma unroll
     for (int w = 0; w < kNW; ++w) {
-      ws[w] = sm.wb[w].stage[r][p] + sm.wz[w][r][UNEQ ? piece_group(p >> 4) : p * NG / kD];
+      ws[w] = sm.wb[w].stage[r][p] + wz[w];
       rs[w] = sm.ring_o[w][r][ch];
     }
     float den = 0.f, num = 0.f;
@@ -1002,34 +998,112 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       num = fmaf(e, e > 0.f ? ws[w] : 0.f, num);
       num = fmaf(g, g > 0.f ? rs[w] : 0.f, num);
     }
-    float *part =
-        L.workspace + (row_index(head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
-    part[4 + ch] = num;
-    if (p == 0) {
-      part[0] = m;
-      part[1] = den;
+    if (mo.mode == kMergeDirect) {
+      // the only chunk of its kv head: this is the result
+      const float o = num / den;
+      const long long idx = row_index(head0 + r) * kD + ch;
+      mo.out_f32[idx] = o;
+      if (mo.out_f16) mo.out_f16[idx] = __float2half_rn(o);
+    } else {
+      float *part =
+          L.workspace + (row_index(head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
+      part[4 + ch] = num;
+      if (p == 0) {
+        // (a workgroup that does not run where the plan puts it marks its partial: the merge then
+        // writes NaN instead of reading, perhaps, an old partial through the wrong L2)
+        const bool misplaced = mo.mode == kMergeInKernel && mo.check_xcd &&
+                               (__builtin_amdgcn_s_getreg(kHwRegXccId) & 7u) != (blockIdx.x & 7u);
+        part[0] = m;
+        part[1] = misplaced ? __builtin_nanf("") : den;
+      }
     }
   }
-  SKVQ_STAMP(3);
+  if (mo.mode != kMergeInKernel) return;
+
+  // ---- merge inside the launch: the chunks of this (kv head, pass) all run on one XCD.  A workgroup's
+  //      partial has reached that XCD's L2 when its stores are acknowledged; then it takes a ticket from
+  //      a counter in the same L2, and whoever draws the last ticket reads all partials (past its own
+  //      L1) and writes the output.  The counter wraps to zero with the last ticket. ----
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0)
+    sm.merge_ticket = __builtin_amdgcn_atomic_inc32(&L.merge_counters[blockIdx.z * gridDim.y + by],
+                                                    (unsigned)(n_splits - 1), __ATOMIC_RELAXED, "workgroup");
+  __syncthreads();
+  if (sm.merge_ticket != (unsigned)(n_splits - 1)) return;
+  // The last one.  Thread (row r, channel p) requests its channel of the first 32 partials at once;
+  // meanwhile the first wavefront of each row turns the partials' (reference, sum of weights) into
+  // normalised weights, lane k for partials k and k + 64, and leaves them in LDS.  (n_splits is a
+  // multiple of 8 here.)
+  const bool active = tid < R * kD && head0 + (tid >> 7) < n_rows;
+  const int r = active ? tid >> 7 : 0, p = tid & 127;
+  const long long row = row_index(head0 + r);
+  const float *base = L.workspace + row * (SKVQ_MAX_SPLITS + 1) * kPartialStride;
+  const float *vbase = base + 4 + p;
+  constexpr int kBatch = 32;
+  float val[kBatch];
+  auto request = [&](int first) {  // up to 32 partials from `first` on, in groups of 8 (uniform branches)
+#pragma unroll
+    for (int g = 0; g < kBatch / 8; ++g)
+      if (first + 8 * g < n_splits) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) val[8 * g + k] = vbase[(first + 8 * g + k) * kPartialStride];
+      }
+  };
+  float *wts = &sm.qraw[r][0];  // (the query is no longer needed) [row][partial]: weight / sum of all weights
+  auto accumulate = [&](int first, float num) {
+#pragma unroll
+    for (int g = 0; g < kBatch / 8; ++g)
+      if (first + 8 * g < n_splits) {
+        const float4_t wa = *reinterpret_cast<const float4_t *>(wts + first + 8 * g);
+        const float4_t wb = *reinterpret_cast<const float4_t *>(wts + first + 8 * g + 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) num = fmaf(wa[k], wa[k] != 0.f ? val[8 * g + k] : 0.f, num);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) num = fmaf(wb[k], wb[k] != 0.f ? val[8 * g + 4 + k] : 0.f, num);
+      }
+    return num;
+  };
+  if (active) request(0);
+  if (active && (wave & 1) == 0) {
+    float m2[2], l2[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int k = lane + 64 * x;
+      float2 ml = make_float2(-INFINITY, 0.f);
+      if (k < n_splits) ml = *reinterpret_cast<const float2 *>(base + k * kPartialStride);
+      // (a sum of weights that is not a number marks a partial from a misplaced workgroup: it is kept, and
+      // turns the whole row into NaN)
+      l2[x] = ml.y > 0.f || ml.y != ml.y ? ml.y : 0.f;
+      m2[x] = l2[x] != 0.f ? ml.x : -INFINITY;
+    }
+    const float mstar = wave_max(fmaxf(m2[0], m2[1]));
+    float w2[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) w2[x] = l2[x] != 0.f ? fast_exp2(m2[x] - mstar) : 0.f;
+    const float inv = 1.0f / wave_sum(fmaf(w2[0], l2[0], w2[1] * l2[1]));
+    wts[lane] = w2[0] * inv;
+    wts[lane + 64] = w2[1] * inv;
+  }
+  __syncthreads();
+  if (active) {
+    float num = accumulate(0, 0.f);
+    for (int first = kBatch; first < n_splits; first += kBatch) {  // (more than 32 chunks: short caches with a forced split count)
+      request(first);
+      num = accumulate(first, num);
+    }
+    mo.out_f32[row * kD + p] = num;
+    if (mo.out_f16) mo.out_f16[row * kD + p] = __float2half_rn(num);
+  }
 }
 
 }  // namespace
-
-#ifdef SKVQ_TIMING
-extern "C" int skvq_debug_read_timing(unsigned long long *host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(skvq_timing), sizeof(unsigned long long) * n);
-}
-extern "C" int skvq_debug_read_timing_w(unsigned long long *host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(skvq_timing_w), sizeof(unsigned long long) * n);
-}
-#endif
-
 
 // The launcher of the kernels with KL-level keys and VL-level values.
 template <int KL, int VL>
 hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                                   int n_splits, int n_new, const __half *knew, const __half *vnew, long long te,
-                                  hipStream_t s) {
+                                  MergeOut mo, hipStream_t s) {
   if (T <= 0 || nq < 0 || nq > SKVQ_MAX_QUANT_TOKENS || T - nq > 0x7fffffff || n_splits < 1 ||
       n_splits > SKVQ_MAX_SPLITS)
     return hipErrorInvalidValue;
@@ -1039,10 +1113,15 @@ hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T,
   if ((knew != nullptr) != (vnew != nullptr) || (knew && (passes != 1 || n_new != 1))) return hipErrorInvalidValue;
   if (knew && T - 1 >= L.W && (te < 0 || te >= L.Tcap || te != nq - 1)) return hipErrorInvalidValue;
   if ((long long)L.Hk * passes > 65535) return hipErrorInvalidValue;
+  if (mo.mode != kMergeSeparate && !mo.out_f32) return hipErrorInvalidValue;
+  if (mo.mode == kMergeDirect && n_splits != 1) return hipErrorInvalidValue;
+  if (mo.mode == kMergeInKernel &&
+      (!L.merge_counters || (mo.check_xcd && (n_splits % 8 != 0 || (L.Hk * passes) % 8 != 0))))
+    return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
   const ChunkPlan plan = plan_chunks(L, T, nq, n_sink, n_splits, knew != nullptr);
 #define SKVQ_LAUNCH(RR, MM, GG, UU) \
-  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew, te, plan)
+  hipLaunchKernelGGL((decode_mfma_kernel<RR, KL, VL, MM, GG, UU>), grid, block, 0, s, L, q, T, nq, n_sink, n_splits, passes, n_new, knew, vnew, te, plan, mo)
 #define SKVQ_LAUNCH_NG(RR, MM)                                                                   \
   switch (L.NG) {                                                                                \
     case 1: SKVQ_LAUNCH(RR, MM, 1, false); break;                                                \
