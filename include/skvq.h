@@ -340,6 +340,14 @@ int skvq_set_num_splits(skvq_cache *cache, int32_t n_splits);
  * launch costs), hence the default.  A tuning and test knob. */
 int skvq_set_merge_in_kernel(skvq_cache *cache, int32_t enable);
 
+/* Measurement yardstick, no part of the method (for benchmarks that price the decode path against
+ * what the device can read): a kernel that only reads `bytes` bytes (a multiple of 16) from src
+ * (DEVICE, 16-byte aligned) in the decode kernel's launch shape -- one workgroup of 512 threads per
+ * compute unit, contiguous slices, 16-byte loads, four in flight per lane -- on hip_stream,
+ * asynchronously.  sink: DEVICE, 4 bytes, written only if the XOR of all words read equals a magic
+ * number (so that the loads cannot be dropped). */
+int skvq_read_yardstick(const void *src, size_t bytes, void *sink, void *hip_stream);
+
 /* Static description of a status code; the cache's last HIP error text (owned by cache). */
 const char *skvq_status_string(int status);
 const char *skvq_last_error(const skvq_cache *cache);

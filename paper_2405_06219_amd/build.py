@@ -25,6 +25,7 @@ UNITS = [
     ("skvq_prefill_attn.hip", "skvq_prefill_attn.o", []),
     ("skvq_calibrate.hip", "skvq_calibrate.o", ["-ffp-contract=off"]),
     ("skvq_reorder.hip", "skvq_reorder.o", ["-ffp-contract=off"]),
+    ("skvq_yardstick.hip", "skvq_yardstick.o", []),
     ("skvq_decode_mfma.hip", "skvq_decode_mfma.o", []),
 ] + [("skvq_decode_mfma_inst.hip", f"skvq_decode_mfma_k{kl}_v{vl}.o", [f"-DSKVQ_KL={kl}", f"-DSKVQ_VL={vl}"])
      for kl, vl in DECODE_FORMATS]

@@ -62,6 +62,29 @@ __device__ __forceinline__ float lane_move(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
+// Minimum / maximum of finite numbers as single instructions (fminf / fmaxf first re-canonicalize every
+// operand, one more instruction each, for the sake of signalling NaNs that cannot occur here).
+__device__ __forceinline__ float min3_raw(float a, float b, float c) {
+  float r;
+  asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float max3_raw(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float min_raw(float a, float b) {
+  float r;
+  asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float max_raw(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 template <int BITS>
 __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
                                           float top, int fmt, bool uneq, unsigned gmap, int lane,
@@ -71,12 +94,14 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
   float x[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = __half2float(row[ch[e]]);
-  float mn = x[0], mx = x[0];
+  float mn = min3_raw(x[0], x[1], x[2]), mx = max3_raw(x[0], x[1], x[2]);
 #pragma unroll
-  for (int e = 1; e < 16; ++e) {
-    mn = fminf(mn, x[e]);
-    mx = fmaxf(mx, x[e]);
+  for (int e = 3; e < 15; e += 2) {
+    mn = min3_raw(mn, x[e], x[e + 1]);
+    mx = max3_raw(mx, x[e], x[e + 1]);
   }
+  mn = min_raw(mn, x[15]);
+  mx = max_raw(mx, x[15]);
   if (uneq) {
     // unequal groups: the other seven 16-position pieces of the token sit in the other seven lanes
     // of this lane's group of eight; take those that belong to the same group
@@ -96,16 +121,16 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
     // image within the eight (both quads hold their own result by then); data-parallel moves
     const int lanes = G / 16;
     if (lanes > 1) {
-      mn = fminf(mn, lane_move<0xB1>(mn));  // quad_perm [1, 0, 3, 2]
-      mx = fmaxf(mx, lane_move<0xB1>(mx));
+      mn = min_raw(mn, lane_move<0xB1>(mn));  // quad_perm [1, 0, 3, 2]
+      mx = max_raw(mx, lane_move<0xB1>(mx));
     }
     if (lanes > 2) {
-      mn = fminf(mn, lane_move<0x4E>(mn));  // quad_perm [2, 3, 0, 1]
-      mx = fmaxf(mx, lane_move<0x4E>(mx));
+      mn = min_raw(mn, lane_move<0x4E>(mn));  // quad_perm [2, 3, 0, 1]
+      mx = max_raw(mx, lane_move<0x4E>(mx));
     }
     if (lanes > 4) {
-      mn = fminf(mn, lane_move<0x141>(mn));  // row_half_mirror
-      mx = fmaxf(mx, lane_move<0x141>(mx));
+      mn = min_raw(mn, lane_move<0x141>(mn));  // row_half_mirror
+      mx = max_raw(mx, lane_move<0x141>(mx));
     }
   }
   gp = group_params(mn, mx, alpha, top, fmt);
@@ -141,11 +166,34 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int KL, int VL>  // levels of the key and value codes
+// KL, VL: levels of the key and value codes.  PLAIN: the common configuration -- one group per head
+// (G = 128), fp32 (scale, zero), kept tokens by the sink rule -- with everything that other
+// configurations decide at run time fixed at compile time.
+// Grid x: the V blocks, then (first_ring_block on) blocks of four fp16 rows to copy: the last
+// n_win tokens into the ring (token a -> row a % W) and the kept ones into the rows after the ring
+// (the j-th kept token -> row W + j; it is token kept_ids[j], or token j under the sink rule).
+template <int KL, int VL, bool PLAIN>
 __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__restrict__ ksrc,
                                                       const __half *__restrict__ vsrc, long long T,
                                                       long long nq, int n_kept,
-                                                      const int *__restrict__ kept_ids) {
+                                                      const int *__restrict__ kept_ids_arg,
+                                                      unsigned first_ring_block, int n_win) {
+  if (blockIdx.x >= first_ring_block) {
+    const long long x = 4ll * (blockIdx.x - first_ring_block) + (threadIdx.x >> 6);  // fp16 row: window first, then kept
+    if (x >= n_win + n_kept) return;
+    const bool kept = x >= n_win;
+    const long long j = x - n_win;
+    const long long a = kept ? (kept_ids_arg ? (long long)kept_ids_arg[j] : j) : T - n_win + x;
+    const long long row = kept ? L.W + j : a % L.W;
+    const long long head = (long long)blockIdx.z * L.Hk + blockIdx.y;
+    const long long src = (head * T + a) * kD, dst = (head * (L.W + L.S) + row) * kD;
+    const int l = threadIdx.x & 63;
+    reinterpret_cast<__half2 *>(L.k_win + dst)[l] = reinterpret_cast<const __half2 *>(ksrc + src)[l];
+    reinterpret_cast<__half2 *>(L.v_win + dst)[l] = reinterpret_cast<const __half2 *>(vsrc + src)[l];
+    return;
+  }
+  const int *__restrict__ kept_ids = PLAIN ? nullptr : kept_ids_arg;
+  const int cfg_G = PLAIN ? kD : L.G, cfg_NG = PLAIN ? 1 : L.NG, cfg_fmt = PLAIN ? (int)SKVQ_META_F32 : L.meta_fmt;
   // (everything in LDS is private to one wavefront: the four wavefronts never wait for each other)
   __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
   __shared__ unsigned vq[VL == 16 ? 1 : 4][8][8];             // [wave][token i][n]: 16 codes, j-minor
@@ -189,11 +237,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     *reinterpret_cast<uint4 *>(&rows[wave][1][4 + lr][8 * lp]) = vb;
   }
   const int i = lane >> 3, n = lane & 7;
-  const bool uneq = L.uneq != 0;
+  const bool uneq = PLAIN ? false : L.uneq != 0;
   const unsigned gmap = uneq ? L.gmaps[hk] : 0u;
-  const int grp = uneq ? tile_group(gmap, n) : (16 * n) / L.G;
-  const bool writes_meta = uneq ? (n == 0 || tile_group(gmap, n - 1) != grp) : (16 * n) % L.G == 0;
-  const float ak = L.clip_k[hk * L.NG + grp], av = L.clip_v[hk * L.NG + grp];
+  const int grp = uneq ? tile_group(gmap, n) : (16 * n) / cfg_G;
+  const bool writes_meta = uneq ? (n == 0 || tile_group(gmap, n - 1) != grp) : (16 * n) % cfg_G == 0;
+  const float ak = L.clip_k[hk * cfg_NG + grp], av = L.clip_v[hk * cfg_NG + grp];
   int4 pk[4], pv[4];
   {
     const int4 *ppk = reinterpret_cast<const int4 *>(L.perm_k + hk * kD + 16 * n);
@@ -210,8 +258,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
 
   GroupParams gk, gv;
   constexpr int kKBits = KL == 16 ? 4 : KL == 8 ? 3 : 2, kVBits = VL == 16 ? 4 : VL == 8 ? 3 : 2;
-  const uint2 kw = encode16<kKBits>(rows[wave][0][i], pk, ak, L.G, (float)(KL - 1), L.meta_fmt, uneq, gmap, lane, gk);
-  const uint2 vw = encode16<kVBits>(rows[wave][1][i], pv, av, L.G, (float)(VL - 1), L.meta_fmt, uneq, gmap, lane, gv);
+  const uint2 kw = encode16<kKBits>(rows[wave][0][i], pk, ak, cfg_G, (float)(KL - 1), cfg_fmt, uneq, gmap, lane, gk);
+  const uint2 vw = encode16<kVBits>(rows[wave][1][i], pv, av, cfg_G, (float)(VL - 1), cfg_fmt, uneq, gmap, lane, gv);
   unsigned ktop = 0;
   if (KL == 8) {  // the plane dword of a pair of key dwords comes from two lanes
     ktop = place_key_top_bits(kw.y, n & 1);
@@ -227,8 +275,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     } else
       reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw.x;
     if (writes_meta) {
-      meta_store_pair(L.k_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, L.meta_fmt);
-      meta_store_pair(L.v_meta, (head * L.Tcap + t) * L.NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, L.meta_fmt);
+      meta_store_pair(L.k_meta, (head * L.Tcap + t) * cfg_NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, cfg_fmt);
+      meta_store_pair(L.v_meta, (head * L.Tcap + t) * cfg_NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, cfg_fmt);
     }
   }
   // rows past the packed region leave zeros in the block
@@ -309,24 +357,6 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   }
 }
 
-// Copies the tokens of the prompt that stay fp16: the last n_win into the ring (token a -> row
-// a % W) and the kept ones into the rows after the ring (the j-th kept token -> row W + j; it is
-// token kept_ids[j], or token j under the sink rule, kept_ids == null).
-__global__ __launch_bounds__(64) void ring_fill_kernel(Layout L, const __half *__restrict__ ksrc,
-                                                      const __half *__restrict__ vsrc, long long T,
-                                                      long long first_win, int n_win,
-                                                      const int *__restrict__ kept_ids) {
-  const bool sink = (int)blockIdx.x >= n_win;
-  const long long j = (long long)blockIdx.x - n_win;
-  const long long a = sink ? (kept_ids ? (long long)kept_ids[j] : j) : first_win + blockIdx.x;
-  const long long row = sink ? L.W + j : a % L.W;
-  const long long head = (long long)blockIdx.z * L.Hk + blockIdx.y;
-  const long long src = (head * T + a) * kD, dst = (head * (L.W + L.S) + row) * kD;
-  const int lane = threadIdx.x;
-  reinterpret_cast<__half2 *>(L.k_win + dst)[lane] = reinterpret_cast<const __half2 *>(ksrc + src)[lane];
-  reinterpret_cast<__half2 *>(L.v_win + dst)[lane] = reinterpret_cast<const __half2 *>(vsrc + src)[lane];
-}
-
 // Append: one workgroup of two wavefronts per (b, hk) (skvq_append_device.h).
 __global__ __launch_bounds__(128) void append_kernel(Layout L, const __half *__restrict__ knew,
                                                      const __half *__restrict__ vnew, long long T, int keep_row,
@@ -343,35 +373,32 @@ hipError_t launch_prefill(const Layout &L, const __half *k, const __half *v, lon
                           const int *kept_ids, hipStream_t s) {
   const Counts n = counts_with(T, L.W, n_kept);
   if (n_kept < 0 || n_kept > L.S || n.n_quant < 0) return hipErrorInvalidValue;
-  if (n.n_quant > 0) {
-    const long long nblk = (n.n_quant + kVBlock - 1) / kVBlock;
-    if (nblk > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)nblk, L.Hk, L.B), block(256);
-#define SKVQ_PREFILL(KL, VL) hipLaunchKernelGGL((prefill_kernel<KL, VL>), grid, block, 0, s, L, k, v, T, n.n_quant, (int)n_kept, kept_ids)
-    if (L.k_levels == 8) {
-      if (L.v_levels != 8) return hipErrorInvalidValue;
-      SKVQ_PREFILL(8, 8);
-    } else if (L.k_levels == 16) {
-      if (L.v_levels == 16) SKVQ_PREFILL(16, 16);
-      else if (L.v_levels == 4) SKVQ_PREFILL(16, 4);
-      else SKVQ_PREFILL(16, 3);
-    } else {
-      if (L.v_levels == 16) SKVQ_PREFILL(4, 16);
-      else if (L.v_levels == 4) SKVQ_PREFILL(4, 4);
-      else SKVQ_PREFILL(4, 3);
-    }
+  const long long nblk = (n.n_quant + kVBlock - 1) / kVBlock;       // V blocks of packed rows
+  const long long n_fp = n.n_win + n.n_sink, ring_blocks = (n_fp + 3) / 4;  // fp16 rows, four per workgroup
+  if (nblk + ring_blocks == 0) return hipSuccess;
+  if (nblk + ring_blocks > 0x7fffffffll || L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(nblk + ring_blocks), L.Hk, L.B), block(256);
+  const bool plain = L.NG == 1 && !L.uneq && L.meta_fmt == SKVQ_META_F32 && kept_ids == nullptr;
+#define SKVQ_PREFILL_P(KL, VL, PP)                                                                             \
+  hipLaunchKernelGGL((prefill_kernel<KL, VL, PP>), grid, block, 0, s, L, k, v, T, n.n_quant, (int)n_kept, kept_ids, \
+                     (unsigned)nblk, (int)n.n_win)
+#define SKVQ_PREFILL(KL, VL) \
+  if (plain) SKVQ_PREFILL_P(KL, VL, true); else SKVQ_PREFILL_P(KL, VL, false)
+  if (L.k_levels == 8) {
+    if (L.v_levels != 8) return hipErrorInvalidValue;
+    SKVQ_PREFILL(8, 8);
+  } else if (L.k_levels == 16) {
+    if (L.v_levels == 16) { SKVQ_PREFILL(16, 16); }
+    else if (L.v_levels == 4) { SKVQ_PREFILL(16, 4); }
+    else { SKVQ_PREFILL(16, 3); }
+  } else {
+    if (L.v_levels == 16) { SKVQ_PREFILL(4, 16); }
+    else if (L.v_levels == 4) { SKVQ_PREFILL(4, 4); }
+    else { SKVQ_PREFILL(4, 3); }
+  }
 #undef SKVQ_PREFILL
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  const long long n_fp = n.n_win + n.n_sink;
-  if (n_fp > 0) {
-    if (L.Hk > 65535 || L.B > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(ring_fill_kernel, dim3((unsigned)n_fp, L.Hk, L.B), dim3(64), 0, s, L, k, v, T, T - n.n_win,
-                       (int)n.n_win, kept_ids);
-    return hipGetLastError();
-  }
-  return hipSuccess;
+#undef SKVQ_PREFILL_P
+  return hipGetLastError();
 }
 
 hipError_t launch_append(const Layout &L, const __half *k_new, const __half *v_new, long long T, int keep_row,
