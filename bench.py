@@ -17,7 +17,7 @@ is the CPU oracle timed on a bounded sample of the same workload.
 
 `--probe NAME` runs a workload for a profiler instead (`rocprofv3 ... -- python3 bench.py --probe
 decode`) and prints plain text: `decode` (a few decode calls and a 256 MiB copy, the yardstick of
-the traffic counters), `prefill-attention`, `read` (the library's read-only kernel over slices
+the traffic counters), `prefill` (prefill-quantize calls back to back), `prefill-attention`, `read` (the library's read-only kernel over slices
 of the decode call's size).
 """
 from __future__ import annotations
@@ -304,19 +304,15 @@ def bounded_context(w, token_heads: int) -> int:
 
 # ------------------------------------------------------------------ profiler workloads ----
 
-def probe(args, device) -> int:
+def probe(args, w, bounds, device) -> int:
     import torch
     from paper_2405_06219_amd import binding as B
-    from paper_2405_06219_amd import synth
 
-    w = synth.WORKLOADS[args.workload]
-    if args.context:
-        w = w.scaled(args.context)
     if args.probe == "decode":
         # a few decode calls (first skvq_decode_attention alone, then skvq_append_decode_attention), then a
         # plain 256 MiB device-to-device copy: what FETCH_SIZE / WRITE_SIZE read for it scales the counters
         n_layers = args.layers if args.layers else 4
-        caches = build_layers(w, n_layers, 8, device, args.sink, args.meta)[0]
+        caches = build_layers(w, n_layers, 8, device, args.sink, args.meta, bounds)[0]
         q = torch.randn((n_layers, w.batch, w.n_q_heads, D), device=device).to(torch.float16)
         out = torch.empty((n_layers, w.batch, w.n_q_heads, D), dtype=torch.float32, device=device)
         kn = torch.randn((n_layers, w.batch, w.n_kv_heads, D), device=device).to(torch.float16)
@@ -339,8 +335,23 @@ def probe(args, device) -> int:
               f"prefill algorithmic bytes per call: {algorithmic_bytes_prefill(w, args.meta)}; "
               f"source_fingerprint: {source_fingerprint()}")
         return 0
+    if args.probe == "prefill":
+        # skvq_prefill_quantize of every layer, the calls back to back, three rounds
+        n_layers = args.layers if args.layers else 8
+        caches, _, first_us, sources = build_layers(w, n_layers, 8, device, args.sink, args.meta, bounds, keep_sources=True)
+
+        def prefill_all():
+            for c, (k, v) in zip(caches, sources):
+                c.skvq_prefill_quantize(k, v)
+        us = timed_us(prefill_all, n_layers, 3, warm=0)
+        by = algorithmic_bytes_prefill(w, args.meta)
+        print(f"probe prefill: {w.name}, {n_layers} layers: first call of each layer (own pair of events) {np.median(first_us):.2f} us, "
+              f"then 3 rounds back to back {us.mean():.2f} us per call ({by / us.mean() / 1e3:.0f} GB/s = "
+              f"{100 * by / us.mean() / 1e3 / HBM_PEAK_GBPS:.1f} % of {HBM_PEAK_GBPS:.0f} GB/s); algorithmic bytes per call {by}; "
+              f"source_fingerprint: {source_fingerprint()}")
+        return 0
     if args.probe == "prefill-attention":
-        T = args.context if args.context else 32768
+        T = w.context if args.context else 32768
         perm = np.tile(np.arange(D, dtype=np.int32), (w.n_kv_heads, 1))
         one = np.ones((w.n_kv_heads, 1), np.float32)
         cache = B.SkvqCache(1, w.n_q_heads, w.n_kv_heads, 128, 1.5, 8, 8, perm, perm, one, one, device=device)
@@ -408,7 +419,7 @@ def main() -> int:
                     help="also measure the other baseline configurations (default, when the headline workload runs "
                          "in its own format)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--probe", default="", help="run a profiler workload instead: decode | prefill-attention | read")
+    ap.add_argument("--probe", default="", help="run a profiler workload instead: decode | prefill | prefill-attention | read")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -424,8 +435,6 @@ def main() -> int:
     B.lib()  # fail loudly if the HIP library is missing
     device = torch.device("cuda:0")
     torch.cuda.set_device(device)
-    if args.probe:
-        return probe(args, device)
     w = synth.WORKLOADS[args.workload]
     if args.context:
         w = w.scaled(args.context)
@@ -437,6 +446,8 @@ def main() -> int:
         w = dataclasses.replace(w, k_bits=args.k_bits)
     if args.v_bits:
         w = dataclasses.replace(w, v_bits=args.v_bits)
+    if args.probe:
+        return probe(args, w, bounds, device)
     n_steps, n_warm, n_layers = args.steps, args.warmup, args.layers if args.layers else 32
     headroom = n_warm + 3 * n_steps + 9
     as_baseline = (headline_format and w.context == synth.WORKLOADS[w.name].context and not args.sink

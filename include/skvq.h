@@ -330,21 +330,10 @@ int skvq_set_state(skvq_cache *cache, int64_t n_tokens);
 #define SKVQ_MAX_SPLITS 128
 int skvq_set_num_splits(skvq_cache *cache, int32_t n_splits);
 
-/* Where the chunks' partial results are combined.  A kv head that is read as ONE chunk has its
- * output written by that chunk's workgroup (no second launch).  Several chunks are combined by a
- * second launch (the default), or, with enable != 0, inside the same launch by the workgroup that
- * finishes last, whenever the chunks of a kv head can be placed on one XCD of the chip (found out by
- * a probe when the cache is created; the chunk count must be a multiple of 8, and so must
- * n_kv_heads x passes on a chip whose workgroups go round 8 XCDs).  Results agree to rounding.
- * Measured on MI355X the two take the same time (the hand-off through the L2 costs what the second
- * launch costs), hence the default.  A tuning and test knob. */
-int skvq_set_merge_in_kernel(skvq_cache *cache, int32_t enable);
-
 /* Measurement yardstick, no part of the method (for benchmarks that price the decode path against
  * what the device can read): a kernel that only reads `bytes` bytes (a multiple of 16) from src
- * (DEVICE, 16-byte aligned) in the decode kernel's launch shape -- one workgroup of 512 threads per
- * compute unit, contiguous slices, 16-byte loads, four in flight per lane -- on hip_stream,
- * asynchronously.  sink: DEVICE, 4 bytes, written only if the XOR of all words read equals a magic
+ * (DEVICE, 16-byte aligned) with grid-strided 16-byte loads, eight workgroups of 256 threads per
+ * compute unit (the fastest shape of a sweep), on hip_stream, asynchronously.  sink: DEVICE, 4 bytes, written only if the XOR of all words read equals a magic
  * number (so that the loads cannot be dropped). */
 int skvq_read_yardstick(const void *src, size_t bytes, void *sink, void *hip_stream);
 

@@ -77,7 +77,6 @@ def lib() -> C.CDLL:
         L.skvq_get_state.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.skvq_set_state.argtypes = [C.c_void_p, C.c_int64]
         L.skvq_set_num_splits.argtypes = [C.c_void_p, C.c_int32]
-        L.skvq_set_merge_in_kernel.argtypes = [C.c_void_p, C.c_int32]
         L.skvq_read_yardstick.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.skvq_status_string.argtypes = [C.c_int]
         L.skvq_status_string.restype = C.c_char_p
@@ -356,9 +355,6 @@ class SkvqCache:
 
     def skvq_set_state(self, n_tokens: int):
         self._check(lib().skvq_set_state(self._h, n_tokens))
-
-    def skvq_set_merge_in_kernel(self, enable: bool):
-        self._check(lib().skvq_set_merge_in_kernel(self._h, 1 if enable else 0))
 
     def skvq_set_num_splits(self, n: int):
         self._check(lib().skvq_set_num_splits(self._h, n))

@@ -30,7 +30,6 @@ struct skvq_cache {
   long long n_kept = 0;  // tokens older than the window that the filter rules keep in fp16 (<= L.S)
   int *dev_kept_ids = nullptr;  // device [S]: their token numbers (written by a prefill with a mask)
   int forced_splits = 0;
-  int xcd_mode_probed = 0;  // XcdMode of the device (what skvq_set_merge_in_kernel(1) restores)
   int max_new = 1;  // query tokens per sequence the workspace was sized for
   int n_cus = 256;
   void *dev_consts = nullptr;  // one allocation: perm_k, perm_v, clip_k, clip_v
@@ -237,16 +236,13 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.v_win = (__half *)bufs->v_win;
   L.workspace = (float *)bufs->workspace;
 
-  // constants: [perm_k | perm_v | clip_k | clip_v | gmaps | kept token numbers | merge counters], one allocation
+  // constants: [perm_k | perm_v | clip_k | clip_v | gmaps | kept token numbers], one allocation
   const size_t n_perm = (size_t)L.Hk * kD, n_clip = (size_t)L.Hk * L.NG;
   const size_t off_pv = n_perm * 4, off_ck = off_pv + n_perm * 4;
   const size_t off_cv = off_ck + ((n_clip * 4 + 15) & ~(size_t)15);
   const size_t off_gm = off_cv + ((n_clip * 4 + 15) & ~(size_t)15);
   const size_t off_ids = off_gm + (((size_t)L.Hk * 4 + 15) & ~(size_t)15);
-  const size_t off_cnt = off_ids + (((size_t)L.S * 4 + 15) & ~(size_t)15);
-  // one counter per (sequence, kv head, pass of four rows); all zero whenever no call is running
-  const size_t n_cnt = (size_t)L.B * L.Hk * decode_passes(L.R * c->max_new);
-  const size_t total = off_cnt + ((n_cnt * 4 + 15) & ~(size_t)15);
+  const size_t total = off_ids + (((size_t)L.S * 4 + 15) & ~(size_t)15);
   std::vector<uint8_t> host(total, 0);
   std::memcpy(host.data(), cfg->perm_k, n_perm * 4);
   std::memcpy(host.data() + off_pv, cfg->perm_v, n_perm * 4);
@@ -274,11 +270,6 @@ int skvq_create(const skvq_config *cfg, const skvq_buffers *bufs, skvq_cache **o
   L.clip_v = (const float *)(d + off_cv);
   L.gmaps = (const unsigned *)(d + off_gm);
   c->dev_kept_ids = (int *)(d + off_ids);
-  L.merge_counters = (unsigned *)(d + off_cnt);
-  // (the in-kernel merge of several chunks is off unless asked for: measured, it is no faster than the
-  // second launch; see skvq_set_merge_in_kernel)
-  c->xcd_mode_probed = probe_xcd_mode();
-  L.xcd_mode = kXcdUnknown;
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -608,12 +599,6 @@ int skvq_set_state(skvq_cache *c, int64_t n_tokens) {
   if (n.n_quant > c->L.Tcap) return SKVQ_ERR_CAPACITY;
   c->n_tokens = n_tokens;
   c->n_kept = n.n_sink;
-  return SKVQ_OK;
-}
-
-int skvq_set_merge_in_kernel(skvq_cache *c, int32_t enable) {
-  if (!c) return SKVQ_ERR_INVALID_ARG;
-  c->L.xcd_mode = enable ? c->xcd_mode_probed : kXcdUnknown;
   return SKVQ_OK;
 }
 

@@ -4,15 +4,12 @@
 // The packed region of every (sequence, kv head) is cut into n_splits chunks of whole 64-token
 // tiles; the chunk kernel (skvq_decode_mfma.hip) keeps a running (max, sum, weighted value sum)
 // per query head (online softmax) and writes one partial per chunk, in original channel order.
-// The partials are combined inside the chunk launch when a kv head's chunks can be put on one XCD
-// (see MergeMode), else by the merge kernel below.
+// A kv head read as one chunk has its output written by the chunk kernel; several chunks' partials
+// are combined by the merge kernel below.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
 #include <math.h>
-
-#include <mutex>
-#include <vector>
 
 #include "skvq_internal.h"
 
@@ -98,40 +95,7 @@ __global__ __launch_bounds__(1024) void merge_kernel(Layout L, float *__restrict
   }
 }
 
-// Where the workgroups of a grid run: out[i] = XCD of workgroup i.
-__global__ void xcd_probe_kernel(unsigned *out) {
-  if (threadIdx.x == 0) out[blockIdx.x] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u;  // HW_REG_XCC_ID
-}
-
 }  // namespace
-
-int probe_xcd_mode() {
-  constexpr int kMaxDevices = 64, kProbeGroups = 512;
-  static std::mutex mu;
-  static int cached[kMaxDevices];  // 0: not probed yet, else XcdMode + 1
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kXcdUnknown;
-  std::lock_guard<std::mutex> lock(mu);
-  if (cached[dev]) return cached[dev] - 1;
-  int mode = kXcdUnknown;
-  unsigned *d = nullptr;
-  if (hipMalloc(&d, kProbeGroups * sizeof(unsigned)) == hipSuccess) {
-    std::vector<unsigned> h(kProbeGroups, 0xffffffffu);
-    hipLaunchKernelGGL(xcd_probe_kernel, dim3(kProbeGroups), dim3(64), 0, 0, d);
-    if (hipGetLastError() == hipSuccess &&
-        hipMemcpy(h.data(), d, kProbeGroups * sizeof(unsigned), hipMemcpyDeviceToHost) == hipSuccess) {
-      bool single = true, round_robin = true;
-      for (int i = 0; i < kProbeGroups; ++i) {
-        single &= h[i] == h[0];
-        round_robin &= h[i] == (unsigned)(i % 8);
-      }
-      mode = single ? kXcdSingle : round_robin ? kXcdRoundRobin8 : kXcdUnknown;
-    }
-    (void)hipFree(d);
-  }
-  cached[dev] = mode + 1;
-  return mode;
-}
 
 hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __half *out_f16, long long T,
                          long long n_kept, int n_splits, int n_new, hipStream_t s, const __half *k_new,
@@ -148,8 +112,7 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
   MergeOut mo;
   mo.out_f32 = out_f32;
   mo.out_f16 = out_f16;
-  mo.mode = choose_merge_mode(L, n_splits, decode_passes(L.R * n_new));
-  mo.check_xcd = L.xcd_mode == kXcdRoundRobin8;
+  mo.mode = n_splits == 1 ? kMergeDirect : kMergeSeparate;
   hipError_t e = launch_decode_mfma(L, q, T, n.n_quant, (int)n.n_sink, n_splits, n_new, k_new, v_new, te, mo, s);
   if (e != hipSuccess || mo.mode != kMergeSeparate) return e;
   // the fp16 tokens are folded into the chunks' partials

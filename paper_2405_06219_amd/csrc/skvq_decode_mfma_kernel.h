@@ -5,8 +5,15 @@
 // unequal (whole 16-position pieces of the head, mapped to groups by Layout::gmap: then every
 // piece has its own score accumulator and weight operand).  This header is compiled
 // once per (K format, V format) pair (SKVQ_KL, SKVQ_VL) by skvq_decode_mfma_inst.hip.
-// (Merging the partials inside this launch was tried and dropped: the device-scope fences it
-// needs write back and invalidate a whole L2 each, 25 us over 256 workgroups.)
+// A kv head that is read as one chunk has its output written by that chunk's workgroup; several
+// chunks leave partials for merge_kernel.  (Merging them inside this launch was built twice and
+// dropped.  With device-scope fences: each fence writes back and invalidates a whole L2, 25 us over
+// 256 workgroups.  With all chunks of a kv head on one XCD -- workgroup i of a grid runs on XCD
+// i % 8 -- and the hand-off through that XCD's L2 (stores acknowledged, a ticket from an atomic
+// counter, the last workgroup reads the partials): correct, and as long as the second launch:
+// acknowledgement 0.3 us + ticket 0.8 us + reading and combining 32 partials 1.6 - 2.8 us on the
+// slowest workgroup's tail, against 3.0 us for merge_kernel, of which 2.0 us is what any dependent
+// launch costs.)
 //
 // One workgroup of 8 wavefronts per chunk (one per compute unit when the cache is long
 // enough).  Per wavefront, per tile of 64 packed tokens:
@@ -181,8 +188,6 @@ constexpr int kAppendLagTiles = 12;  // tiles that the workgroup which also appe
 constexpr int kRingWaves = kNW;     // every wavefront of a workgroup may own ring slices
 constexpr int kRingSlice = 4;       // ring tokens per slice (the slice code reads four rows of 16 lanes)
 
-constexpr int kHwRegXccId = 20 | (0 << 6) | (3 << 11);  // s_getreg operand: HW_REG_XCC_ID, bits 0..3 (the XCD this wave runs on)
-
 constexpr int kCombStride = kD + 16;  // floats; the padding spreads the accumulator columns over the banks
 
 template <int R, bool TERNARY, int NG>
@@ -205,7 +210,6 @@ struct Smem {
   // ([head][...][wave]: the epilogue reads a head's eight entries as two 16-byte pieces)
   alignas(16) float wm[R][kNW], wl[R][kNW], wz[R][NG][kNW], rm[R][kNW], rl[R][kNW];
   float ring_o[kNW][R][kD];            // per wave: its ring slices' outputs, original channel order
-  unsigned merge_ticket;               // in-kernel merge: how many chunks of the kv head had finished before this one
 };
 
 // One 4-channel step of the score product.  The A operand of step ST lives in lanes
@@ -335,16 +339,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   __shared__ Smem<R, TERNARY, NG> sm;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // Chunk and (kv head, pass) of this workgroup.  For the in-kernel merge on a chip whose workgroups go
-  // round the 8 XCDs (grid x and y are multiples of 8 then, so the XCD is blockIdx.x % 8), the low three
-  // bits of the two block indices trade places: all chunks of a (kv head, pass) then run on XCD
-  // (its index) % 8, and their partials meet in that XCD's L2.
-  int sp = blockIdx.x, by = blockIdx.y;
-  if (mo.mode == kMergeInKernel && mo.check_xcd) {
-    const int lo_x = sp & 7, lo_y = by & 7;
-    sp = (sp & ~7) | lo_y;
-    by = (by & ~7) | lo_x;
-  }
+  const int sp = blockIdx.x, by = blockIdx.y;
   const int hk = passes == 1 ? by : by / passes, b = blockIdx.z;
   const unsigned gmap = UNEQ ? L.gmaps[hk] : 0u;
   auto piece_group = [&](int n) { return (int)((gmap >> (4 * n)) & 15u); };  // group of positions 16n..16n+15
@@ -1009,91 +1004,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
           L.workspace + (row_index(head0 + r) * (SKVQ_MAX_SPLITS + 1) + sp) * kPartialStride;
       part[4 + ch] = num;
       if (p == 0) {
-        // (a workgroup that does not run where the plan puts it marks its partial: the merge then
-        // writes NaN instead of reading, perhaps, an old partial through the wrong L2)
-        const bool misplaced = mo.mode == kMergeInKernel && mo.check_xcd &&
-                               (__builtin_amdgcn_s_getreg(kHwRegXccId) & 7u) != (blockIdx.x & 7u);
         part[0] = m;
-        part[1] = misplaced ? __builtin_nanf("") : den;
+        part[1] = den;
       }
     }
-  }
-  if (mo.mode != kMergeInKernel) return;
-
-  // ---- merge inside the launch: the chunks of this (kv head, pass) all run on one XCD.  A workgroup's
-  //      partial has reached that XCD's L2 when its stores are acknowledged; then it takes a ticket from
-  //      a counter in the same L2, and whoever draws the last ticket reads all partials (past its own
-  //      L1) and writes the output.  The counter wraps to zero with the last ticket. ----
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (tid == 0)
-    sm.merge_ticket = __builtin_amdgcn_atomic_inc32(&L.merge_counters[blockIdx.z * gridDim.y + by],
-                                                    (unsigned)(n_splits - 1), __ATOMIC_RELAXED, "workgroup");
-  __syncthreads();
-  if (sm.merge_ticket != (unsigned)(n_splits - 1)) return;
-  // The last one.  Thread (row r, channel p) requests its channel of the first 32 partials at once;
-  // meanwhile the first wavefront of each row turns the partials' (reference, sum of weights) into
-  // normalised weights, lane k for partials k and k + 64, and leaves them in LDS.  (n_splits is a
-  // multiple of 8 here.)
-  const bool active = tid < R * kD && head0 + (tid >> 7) < n_rows;
-  const int r = active ? tid >> 7 : 0, p = tid & 127;
-  const long long row = row_index(head0 + r);
-  const float *base = L.workspace + row * (SKVQ_MAX_SPLITS + 1) * kPartialStride;
-  const float *vbase = base + 4 + p;
-  constexpr int kBatch = 32;
-  float val[kBatch];
-  auto request = [&](int first) {  // up to 32 partials from `first` on, in groups of 8 (uniform branches)
-#pragma unroll
-    for (int g = 0; g < kBatch / 8; ++g)
-      if (first + 8 * g < n_splits) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) val[8 * g + k] = vbase[(first + 8 * g + k) * kPartialStride];
-      }
-  };
-  float *wts = &sm.qraw[r][0];  // (the query is no longer needed) [row][partial]: weight / sum of all weights
-  auto accumulate = [&](int first, float num) {
-#pragma unroll
-    for (int g = 0; g < kBatch / 8; ++g)
-      if (first + 8 * g < n_splits) {
-        const float4_t wa = *reinterpret_cast<const float4_t *>(wts + first + 8 * g);
-        const float4_t wb = *reinterpret_cast<const float4_t *>(wts + first + 8 * g + 4);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) num = fmaf(wa[k], wa[k] != 0.f ? val[8 * g + k] : 0.f, num);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) num = fmaf(wb[k], wb[k] != 0.f ? val[8 * g + 4 + k] : 0.f, num);
-      }
-    return num;
-  };
-  if (active) request(0);
-  if (active && (wave & 1) == 0) {
-    float m2[2], l2[2];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const int k = lane + 64 * x;
-      float2 ml = make_float2(-INFINITY, 0.f);
-      if (k < n_splits) ml = *reinterpret_cast<const float2 *>(base + k * kPartialStride);
-      // (a sum of weights that is not a number marks a partial from a misplaced workgroup: it is kept, and
-      // turns the whole row into NaN)
-      l2[x] = ml.y > 0.f || ml.y != ml.y ? ml.y : 0.f;
-      m2[x] = l2[x] != 0.f ? ml.x : -INFINITY;
-    }
-    const float mstar = wave_max(fmaxf(m2[0], m2[1]));
-    float w2[2];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) w2[x] = l2[x] != 0.f ? fast_exp2(m2[x] - mstar) : 0.f;
-    const float inv = 1.0f / wave_sum(fmaf(w2[0], l2[0], w2[1] * l2[1]));
-    wts[lane] = w2[0] * inv;
-    wts[lane + 64] = w2[1] * inv;
-  }
-  __syncthreads();
-  if (active) {
-    float num = accumulate(0, 0.f);
-    for (int first = kBatch; first < n_splits; first += kBatch) {  // (more than 32 chunks: short caches with a forced split count)
-      request(first);
-      num = accumulate(first, num);
-    }
-    mo.out_f32[row * kD + p] = num;
-    if (mo.out_f16) mo.out_f16[row * kD + p] = __float2half_rn(num);
   }
 }
 
@@ -1115,9 +1029,6 @@ hipError_t launch_decode_mfma_fmt(const Layout &L, const __half *q, long long T,
   if ((long long)L.Hk * passes > 65535) return hipErrorInvalidValue;
   if (mo.mode != kMergeSeparate && !mo.out_f32) return hipErrorInvalidValue;
   if (mo.mode == kMergeDirect && n_splits != 1) return hipErrorInvalidValue;
-  if (mo.mode == kMergeInKernel &&
-      (!L.merge_counters || (mo.check_xcd && (n_splits % 8 != 0 || (L.Hk * passes) % 8 != 0))))
-    return hipErrorInvalidValue;
   const dim3 grid(n_splits, L.Hk * passes, L.B), block(kThreads);
   const ChunkPlan plan = plan_chunks(L, T, nq, n_sink, n_splits, knew != nullptr);
 #define SKVQ_LAUNCH(RR, MM, GG, UU) \

@@ -48,34 +48,17 @@ struct Layout {
   float *workspace;
   const int *perm_k, *perm_v;    // device copies [Hk][D]
   const float *clip_k, *clip_v;  // device copies [Hk][NG]
-  unsigned *merge_counters;      // device [B * Hk * passes]: chunks of a kv head that have written their partial
-                                 // (zero between calls; see MergeMode)
-  int xcd_mode;                  // how workgroups land on the chip's XCDs (see XcdMode), probed at creation
 };
-
-// How workgroups of a grid are spread over the XCDs (each XCD has its own L2): found by a probe
-// kernel when a cache is created.
-enum XcdMode {
-  kXcdUnknown = 0,     // not as below: partials are merged by a second launch
-  kXcdRoundRobin8 = 1, // workgroup i (x fastest) runs on XCD i % 8
-  kXcdSingle = 2       // every workgroup reports the same XCD
-};
-int probe_xcd_mode();  // (skvq_decode.hip) cached per device
 
 // Where the chunk partials of a decode call are combined.
 enum MergeMode {
   kMergeSeparate = 0,  // the chunk kernel writes partials, merge_kernel combines them (a second launch)
-  kMergeDirect = 1,    // one chunk per kv head: its workgroup writes the output itself
-  kMergeInKernel = 2   // the chunks of a kv head run on one XCD; the workgroup that finishes last (an atomic
-                       // counter in that XCD's L2) reads the others' partials through the same L2 and
-                       // writes the output
+  kMergeDirect = 1     // one chunk per kv head: its workgroup writes the output itself
 };
 struct MergeOut {
   float *out_f32;
   __half *out_f16;  // or null
   int mode;         // MergeMode
-  int check_xcd;    // 1: every workgroup verifies that it runs on the XCD the plan assumes (a partial from
-                    // elsewhere poisons the output with NaN instead of going unnoticed)
 };
 
 // Where the T cached tokens of a sequence live (Section 3.2 with the attention-sink rule): the
@@ -145,16 +128,6 @@ hipError_t launch_decode(const Layout &L, const __half *q, float *out_f32, __hal
 // (n_rows = query heads per kv head x query tokens)
 inline int decode_passes(int n_rows) { return n_rows > 4 ? (n_rows + 3) / 4 : 1; }
 // te: with knew / vnew, the packed row of the token that leaves the window.
-// Which MergeMode a launch of this shape takes (host; the in-kernel merge needs the chunk count and the
-// kv heads x passes both to be multiples of 8, so that a bit swap of the block indices puts a kv head's
-// chunks on one XCD).
-inline int choose_merge_mode(const Layout &L, int n_splits, int passes) {
-  if (n_splits == 1) return kMergeDirect;
-  if (n_splits % 8 != 0 || !L.merge_counters) return kMergeSeparate;  // (the in-kernel merge reads partials eight at a time)
-  if (L.xcd_mode == kXcdSingle) return kMergeInKernel;
-  if (L.xcd_mode == kXcdRoundRobin8 && (L.Hk * passes) % 8 == 0) return kMergeInKernel;
-  return kMergeSeparate;
-}
 hipError_t launch_decode_mfma(const Layout &L, const __half *q, long long T, long long nq, int n_sink,
                               int n_splits, int n_new, const __half *knew, const __half *vnew, long long te,
                               MergeOut mo, hipStream_t s);

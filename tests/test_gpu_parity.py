@@ -201,43 +201,39 @@ def test_decode_is_independent_of_the_split_count(P):
 
 
 MERGE_CASES = [
-    (small("merge_gqa4_hk8", n_q_heads=32, n_kv_heads=8, context=9000), (8, 16, 24, 128)),
-    (small("merge_mha_hk8_b2_v2", n_q_heads=8, n_kv_heads=8, context=2500, batch=2, v_bits=2.0), (8, 32)),
-    (small("merge_gqa6_two_passes", n_q_heads=24, n_kv_heads=4, context=3000, group_size=64), (8, 40)),
-    (small("merge_k4v4_hk16", n_q_heads=32, n_kv_heads=16, context=1200, k_bits=4.0, v_bits=4.0), (8, 16)),
+    (small("merge_gqa4_hk8", n_q_heads=32, n_kv_heads=8, context=9000), (1, 8, 24, 128)),
+    (small("merge_mha_hk8_b2_v2", n_q_heads=8, n_kv_heads=8, context=2500, batch=2, v_bits=2.0), (1, 32)),
+    (small("merge_gqa6_two_passes", n_q_heads=24, n_kv_heads=4, context=3000, group_size=64), (1, 40)),
+    (small("merge_k4v4_hk16", n_q_heads=32, n_kv_heads=16, context=1200, k_bits=4.0, v_bits=4.0), (1, 16)),
 ]
 
 
 @pytest.mark.parametrize("w,splits", MERGE_CASES, ids=[c[0].name for c in MERGE_CASES])
-def test_partials_merged_inside_the_launch_match_oracle_and_the_merge_kernel(P, w, splits):
-    """Chunk counts and head counts that let the library combine the partials inside the chunk launch
-    (multiples of 8, incl. more than 32 chunks: several batches of partials): outputs against the
-    oracle, and against the same call with the second launch doing the merge; the fp16 copy too; the
-    one-call step and several calls in a row (the counters must be back at zero after each)."""
+def test_one_chunk_writes_the_output_itself_and_many_chunks_are_merged(P, w, splits):
+    """A kv head read as one chunk (no merge launch: the chunk's workgroup writes the output) and as many
+    chunks (merge launch, up to 128 partials): outputs against the oracle and against each other, the
+    fp16 copy too, also with the fp16 workspace poisoned in between; then the one-call step."""
     print("case", w, splits, flush=True)
     pair, k, v, q = P.make_pair(w, extra_tokens=8)
     pair.prefill(k, v)
     qd = torch.from_numpy(q).cuda()
     ref = pair.ref.decode(q)
+    outs = []
     for n in splits:
         pair.gpu.skvq_set_num_splits(n)
-        outs = []
-        for in_kernel in (True, False, True):
-            pair.gpu.skvq_set_merge_in_kernel(in_kernel)
-            o16 = torch.zeros(q.shape, dtype=torch.float16, device="cuda")
-            out = pair.gpu.skvq_decode_attention(qd, out_f16=o16)
-            torch.cuda.synchronize()
-            outs.append(out.cpu().numpy())
-            assert np.abs(outs[-1] - ref).max() <= P.TOL, (n, in_kernel)
-            assert np.array_equal(o16.cpu().numpy(), outs[-1].astype(np.float16))
-        assert np.abs(outs[0] - outs[1]).max() <= 1e-5 * max(1.0, np.abs(ref).max())
-        assert np.array_equal(outs[0], outs[2])
-    pair.gpu.skvq_set_merge_in_kernel(True)
-    pair.gpu.skvq_set_num_splits(splits[0])
-    assert pair.gpu.skvq_get_state()[0] > 0
-    for s_ in range(3):
-        out, ref2 = pair.append_decode_both(*synth.make_new_token(w, s_), q)
-        assert np.abs(out - ref2).max() <= P.TOL
+        pair.gpu.buffers["workspace"].fill_(0xFF)       # NaN patterns: nothing may be read before it is written
+        o16 = torch.zeros(q.shape, dtype=torch.float16, device="cuda")
+        out = pair.gpu.skvq_decode_attention(qd, out_f16=o16)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+        assert np.abs(outs[-1] - ref).max() <= P.TOL, n
+        assert np.array_equal(o16.cpu().numpy(), outs[-1].astype(np.float16))
+        assert np.abs(outs[-1] - outs[0]).max() <= 1e-5 * max(1.0, np.abs(ref).max())
+    for n in (1, splits[-1]):
+        pair.gpu.skvq_set_num_splits(n)
+        for s_ in range(2):
+            out, ref2 = pair.append_decode_both(*synth.make_new_token(w, s_ if n == 1 else 2 + s_), q)
+            assert np.abs(out - ref2).max() <= P.TOL
     pair.assert_buffers_equal()
 
 
