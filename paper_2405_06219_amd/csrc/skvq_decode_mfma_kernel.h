@@ -60,6 +60,37 @@ typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
 struct __attribute__((aligned(4))) Unit16 {  // a 16-byte load that is only 4-byte aligned
   unsigned x, y, z, w;
 };
+typedef uint4_t uint4_a4_t __attribute__((aligned(4)));
+typedef uint2_t uint2_a4_t __attribute__((aligned(4)));
+// Loads of packed cache data: every byte is read once per call, so it is marked as streaming (it
+// need not displace what the caches hold for longer: the query, the permutations, the partials).
+__device__ __forceinline__ uint4_t stream_load(const uint4_t *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ Unit16 stream_load_unit(const void *p) {
+  const uint4_t v = __builtin_nontemporal_load(reinterpret_cast<const uint4_a4_t *>(p));
+  return Unit16{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ uint2_t stream_load_pair(const void *p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const uint2_a4_t *>(p));
+}
+template <class T>  // a naturally aligned block of 2, 4, 8, 16 or 32 bytes
+__device__ __forceinline__ T stream_load_block(const T *p) {
+  if constexpr (sizeof(T) == 2) {
+    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const unsigned short *>(p)));
+  } else if constexpr (sizeof(T) == 4) {
+    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p)));
+  } else if constexpr (sizeof(T) == 8) {
+    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const uint2_t *>(p)));
+  } else if constexpr (sizeof(T) == 16) {
+    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(p)));
+  } else {
+    static_assert(sizeof(T) == 32, "unexpected block size");
+    struct Two {
+      uint4_t a, b;
+    };
+    const uint4_t *q = reinterpret_cast<const uint4_t *>(p);
+    return __builtin_bit_cast(T, Two{__builtin_nontemporal_load(q), __builtin_nontemporal_load(q + 1)});
+  }
+}
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRefSlack = 6.0f;    // scores may exceed the running reference by 2^6
@@ -407,22 +438,22 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     int t = tile * 64 + lane;
     if (t > safe_last_token) t = safe_last_token;  // only in the last tile; such lanes are masked below
     const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * kRowBytes);
-    d.k0 = krow[0]; d.k1 = krow[1];
-    if constexpr (K4) { d.k2 = krow[2]; d.k3 = krow[3]; }
-    if constexpr (K3) d.k2 = krow[2];
-    d.kmeta = km[t];
-    d.vmeta = vm[t];
+    d.k0 = stream_load(krow); d.k1 = stream_load(krow + 1);
+    if constexpr (K4) { d.k2 = stream_load(krow + 2); d.k3 = stream_load(krow + 3); }
+    if constexpr (K3) d.k2 = stream_load(krow + 2);
+    d.kmeta = stream_load_block(&km[t]);
+    d.vmeta = stream_load_block(&vm[t]);
     const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
     const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
-    d.v00 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[0];
-    d.v10 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[0];
+    d.v00 = stream_load_unit(vc + (size_t)blk0 * vbb + unit_off);
+    d.v10 = stream_load_unit(vc + (size_t)blk1 * vbb + unit_off);
     if constexpr (V3) {
-      d.vt0 = *reinterpret_cast<const uint2_t *>(vc + (size_t)blk0 * vbb + unit_off + 16);
-      d.vt1 = *reinterpret_cast<const uint2_t *>(vc + (size_t)blk1 * vbb + unit_off + 16);
+      d.vt0 = stream_load_pair(vc + (size_t)blk0 * vbb + unit_off + 16);
+      d.vt1 = stream_load_pair(vc + (size_t)blk1 * vbb + unit_off + 16);
     }
     if constexpr (V4) {
-      d.v01 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk0 * vbb + unit_off)[1];
-      d.v11 = reinterpret_cast<const Unit16 *>(vc + (size_t)blk1 * vbb + unit_off)[1];
+      d.v01 = stream_load_unit(vc + (size_t)blk0 * vbb + unit_off + 16);
+      d.v11 = stream_load_unit(vc + (size_t)blk1 * vbb + unit_off + 16);
     }
     return d;
   };

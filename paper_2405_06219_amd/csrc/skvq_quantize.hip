@@ -229,8 +229,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     tb = tb < T ? tb : T - 1;
     const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + head * T * kD);
     const uint4 *vs = reinterpret_cast<const uint4 *>(vsrc + head * T * kD);
-    const uint4 ka = ks[ta * 16 + lp], kb = ks[tb * 16 + lp];
-    const uint4 va = vs[ta * 16 + lp], vb = vs[tb * 16 + lp];
+    // (the prompt's K and V are read once: streaming loads)
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    auto stream = [](const uint4 *p) {
+      const u4 x = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(p));
+      return make_uint4(x.x, x.y, x.z, x.w);
+    };
+    const uint4 ka = stream(&ks[ta * 16 + lp]), kb = stream(&ks[tb * 16 + lp]);
+    const uint4 va = stream(&vs[ta * 16 + lp]), vb = stream(&vs[tb * 16 + lp]);
     *reinterpret_cast<uint4 *>(&rows[wave][0][lr][8 * lp]) = ka;
     *reinterpret_cast<uint4 *>(&rows[wave][0][4 + lr][8 * lp]) = kb;
     *reinterpret_cast<uint4 *>(&rows[wave][1][lr][8 * lp]) = va;
@@ -273,7 +279,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
       krow[n] = kw.x;
       if ((n & 1) == 0) krow[8 + (n >> 1)] = ktop;
     } else
-      reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4))[n] = kw.x;
+      __builtin_nontemporal_store(kw.x, reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4)) + n);
     if (writes_meta) {
       meta_store_pair(L.k_meta, (head * L.Tcap + t) * cfg_NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, cfg_fmt);
       meta_store_pair(L.v_meta, (head * L.Tcap + t) * cfg_NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, cfg_fmt);
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
     }
     wave_lds_sync();
     if (lane < 52)
-      reinterpret_cast<unsigned *>(dst + 208 * wave)[lane] = reinterpret_cast<const unsigned *>(units[wave])[lane];
+      __builtin_nontemporal_store(reinterpret_cast<const unsigned *>(units[wave])[lane], reinterpret_cast<unsigned *>(dst + 208 * wave) + lane);
   }
 }
 
