@@ -17,26 +17,6 @@ namespace skvq {
 namespace {
 
 
-// Spread eight 2-bit codes (token i at bits [2i,2i+2)) to the V unit order: token i goes to
-// bit 16*(i%2) + 2*(i/2).
-__device__ __forceinline__ unsigned spread_tokens(unsigned c8) {
-  unsigned r = 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) r |= ((c8 >> (2 * i)) & 3u) << (16 * (i & 1) + 2 * (i >> 1));
-  return r;
-}
-
-// Base-3 number of eight codes (token i is digit i).
-__device__ __forceinline__ unsigned trit_field(unsigned c8) {
-  unsigned f = 0, pw = 1;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    f += ((c8 >> (2 * i)) & 3u) * pw;
-    pw *= 3;
-  }
-  return f;
-}
-
 // ---------------------------------------------------------------------------------------
 // Prefill: one workgroup (4 wavefronts) per V block of 32 tokens of one (b, hk); wavefront w
 // handles the 8 tokens of sub-block kb = w, K and V, and builds that sub-block's 16 V units.
@@ -52,10 +32,6 @@ __device__ __forceinline__ unsigned trit_field(unsigned c8) {
 constexpr int kRowStride = 136;  // halves per parked row: 272 B keeps 16-byte alignment and
                                  // puts the same channel of the 8 rows in 8 different banks
 
-// Gathers positions 16n..16n+15 of one parked row, finds the group's Eq. 2 parameters and
-// returns this lane's 16 codes.  BITS = 2: two bits each in .x (position 16n + e at bits [2e, 2e+2));
-// BITS = 3: the low two bits like that in .x and the top bits in .y (position e at bit e);
-// BITS = 4: four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).
 // The value of another lane of the same row of 16, chosen by a DPP control word.
 template <int CTRL>
 __device__ __forceinline__ float lane_move(float v) {
@@ -85,13 +61,12 @@ __device__ __forceinline__ float max_raw(float a, float b) {
   return r;
 }
 
-template <int BITS>
-__device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4], float alpha, int G,
-                                          float top, int fmt, bool uneq, unsigned gmap, int lane,
-                                          GroupParams &gp) {
+// Gathers positions 16n..16n+15 of one parked row into x and finds the group's Eq. 2 parameters.
+__device__ __forceinline__ void gather16(const __half *row, const int4 (&pm)[4], float alpha, int G, float top,
+                                         int fmt, bool uneq, unsigned gmap, int lane, float (&x)[16],
+                                         GroupParams &gp) {
   const int ch[16] = {pm[0].x, pm[0].y, pm[0].z, pm[0].w, pm[1].x, pm[1].y, pm[1].z, pm[1].w,
                       pm[2].x, pm[2].y, pm[2].z, pm[2].w, pm[3].x, pm[3].y, pm[3].z, pm[3].w};
-  float x[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) x[e] = __half2float(row[ch[e]]);
   float mn = min3_raw(x[0], x[1], x[2]), mx = max3_raw(x[0], x[1], x[2]);
@@ -134,23 +109,35 @@ __device__ __forceinline__ uint2 encode16(const __half *row, const int4 (&pm)[4]
     }
   }
   gp = group_params(mn, mx, alpha, top, fmt);
-  // code = rint(clamp(y, 0, top)): clamping first gives the same integer because the bounds are
-  // integers; adding 1.5 * 2^23 rounds to the nearest integer, ties to even, and leaves the code
-  // in the low bits of the sum, which alignbit shifts into the row word from the top.
+}
+
+// code = rint(clamp(y, 0, top)): clamping first gives the same integer because the bounds are
+// integers; adding 1.5 * 2^23 rounds to the nearest integer, ties to even, and leaves the code
+// in the low bits of the sum.
+__device__ __forceinline__ unsigned code_in_low_bits(float x, const GroupParams &gp, float top) {
+  const float y = __fmul_rn(__fsub_rn(x, gp.lo), gp.inv);
+  return __float_as_uint(__fadd_rn(__builtin_amdgcn_fmed3f(y, 0.0f, top), 12582912.0f));
+}
+
+// The 16 codes of a lane as row words.  BITS = 2: two bits each in .x (position 16n + e at bits
+// [2e, 2e+2)); BITS = 3: the low two bits like that in .x and the top bits in .y (position e at bit e);
+// BITS = 4: four bits each in .x (e = 0..7 at bits [4e, 4e+4)) and .y (e = 8..15).  alignbit shifts
+// each code into the word from the top.
+template <int BITS>
+__device__ __forceinline__ uint2 pack16(const float (&x)[16], const GroupParams &gp, float top) {
   unsigned w0 = 0, w1 = 0;
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
-    const float y = __fmul_rn(__fsub_rn(x[e], gp.lo), gp.inv);
-    const float r = __fadd_rn(__builtin_amdgcn_fmed3f(y, 0.0f, top), 12582912.0f);
+    const unsigned r = code_in_low_bits(x[e], gp, top);
     if (BITS == 2) {
-      w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 2);
+      w0 = __builtin_amdgcn_alignbit(r, w0, 2);
     } else if (BITS == 3) {
-      w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 2);
-      w1 = __builtin_amdgcn_alignbit(__float_as_uint(r) >> 2, w1, 1);
+      w0 = __builtin_amdgcn_alignbit(r, w0, 2);
+      w1 = __builtin_amdgcn_alignbit(r >> 2, w1, 1);
     } else if (e < 8) {
-      w0 = __builtin_amdgcn_alignbit(__float_as_uint(r), w0, 4);
+      w0 = __builtin_amdgcn_alignbit(r, w0, 4);
     } else {
-      w1 = __builtin_amdgcn_alignbit(__float_as_uint(r), w1, 4);
+      w1 = __builtin_amdgcn_alignbit(r, w1, 4);
     }
   }
   if (BITS == 3) w1 >>= 16;
@@ -194,49 +181,66 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   }
   const int *__restrict__ kept_ids = PLAIN ? nullptr : kept_ids_arg;
   const int cfg_G = PLAIN ? kD : L.G, cfg_NG = PLAIN ? 1 : L.NG, cfg_fmt = PLAIN ? (int)SKVQ_META_F32 : L.meta_fmt;
+  constexpr bool TERNARY = VL == 3;
   // (everything in LDS is private to one wavefront: the four wavefronts never wait for each other)
   __shared__ __align__(16) __half rows[4][2][8][kRowStride];  // [wave][K|V][token][channel]
-  __shared__ unsigned vq[VL == 16 ? 1 : 4][8][8];             // [wave][token i][n]: 16 codes, j-minor
+  __shared__ unsigned vq[VL == 4 || VL == 8 ? 4 : 1][8][8];   // [wave][token i][n]: 16 codes, j-minor
   __shared__ unsigned vqtop[VL == 8 ? 4 : 1][8][8];           // 3-bit codes: their top bits, j-minor
   __shared__ uint2 vq4[VL == 16 ? 4 : 1][8][8 + 1];           // the same for 4-bit codes
-  __shared__ unsigned pieces[4][64];
-  __shared__ __align__(16) uint8_t units[4][208];
+  // ternary codes, one byte each: [wave][position j of the 16][piece n][token i] ...
+  __shared__ __align__(16) uint8_t vbytes[TERNARY ? 4 : 1][16][8][8];
+  // ... and the 13-bit fields made of them, in the order of the block's bytes: field 8j + n
+  __shared__ __align__(4) unsigned short vfields[TERNARY ? 4 : 1][128 + 4];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // (the wavefront's number in a scalar register: everything derived from it stays scalar)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int hk = blockIdx.y, b = blockIdx.z;
   const long long head = (long long)b * L.Hk + hk;
   const long long blk = blockIdx.x;
-  const long long t0 = blk * kVBlock + 8 * wave;
+  const long long t0 = blk * kVBlock + 8 * wave;  // first packed row of this wavefront
 
   // Source rows: packed row r is the r-th token that no filter rule keeps.  With the sink rule
   // (kept_ids == null) the first n_kept tokens are the kept ones: token r + n_kept.  With a list
   // of kept tokens (ascending) token r + (number of j with kept_ids[j] - j <= r); that difference
   // does not decrease with j: binary search.  Rows past the end of the prompt are replaced by
   // its last row and never stored.
-  auto token_of = [&](long long r) {
-    if (!kept_ids) return r + n_kept;
-    int lo = 0, hi = n_kept;  // the count lies in [lo, hi]
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if ((long long)kept_ids[mid] - mid <= r) lo = mid + 1; else hi = mid;
-    }
-    return r + lo;
-  };
   {
-    const int lr = lane >> 4, lp = lane & 15;
-    long long ta = token_of(t0 + lr), tb = token_of(t0 + 4 + lr);
-    ta = ta < T ? ta : T - 1;
-    tb = tb < T ? tb : T - 1;
-    const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + head * T * kD);
-    const uint4 *vs = reinterpret_cast<const uint4 *>(vsrc + head * T * kD);
     // (the prompt's K and V are read once: streaming loads)
     typedef unsigned u4 __attribute__((ext_vector_type(4)));
     auto stream = [](const uint4 *p) {
       const u4 x = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(p));
       return make_uint4(x.x, x.y, x.z, x.w);
     };
-    const uint4 ka = stream(&ks[ta * 16 + lp]), kb = stream(&ks[tb * 16 + lp]);
-    const uint4 va = stream(&vs[ta * 16 + lp]), vb = stream(&vs[tb * 16 + lp]);
+    const int lr = lane >> 4, lp = lane & 15;
+    uint4 ka, kb, va, vb;
+    if (!kept_ids) {
+      // the wavefront's eight rows are one run of the source: a scalar base, lane offsets of 32 bits
+      // (rows beyond the prompt's last one repeat it; a run that lies beyond it altogether starts there)
+      const long long row0 = t0 + n_kept;                                   // token of packed row t0
+      const long long first = row0 < T - 1 ? row0 : T - 1;
+      const unsigned last = (unsigned)(T - 1 - first < 7 ? T - 1 - first : 7);  // the prompt's last row, counted from `first`
+      const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + (head * T + first) * kD);
+      const uint4 *vs = reinterpret_cast<const uint4 *>(vsrc + (head * T + first) * kD);
+      const unsigned oa = 16u * min((unsigned)lr, last) + lp, ob = 16u * min(4u + lr, last) + lp;
+      ka = stream(&ks[oa]), kb = stream(&ks[ob]);
+      va = stream(&vs[oa]), vb = stream(&vs[ob]);
+    } else {
+      auto token_of = [&](long long r) {
+        int lo = 0, hi = n_kept;  // the count lies in [lo, hi]
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if ((long long)kept_ids[mid] - mid <= r) lo = mid + 1; else hi = mid;
+        }
+        return r + lo;
+      };
+      long long ta = token_of(t0 + lr), tb = token_of(t0 + 4 + lr);
+      ta = ta < T ? ta : T - 1;
+      tb = tb < T ? tb : T - 1;
+      const uint4 *ks = reinterpret_cast<const uint4 *>(ksrc + head * T * kD);
+      const uint4 *vs = reinterpret_cast<const uint4 *>(vsrc + head * T * kD);
+      ka = stream(&ks[ta * 16 + lp]), kb = stream(&ks[tb * 16 + lp]);
+      va = stream(&vs[ta * 16 + lp]), vb = stream(&vs[tb * 16 + lp]);
+    }
     *reinterpret_cast<uint4 *>(&rows[wave][0][lr][8 * lp]) = ka;
     *reinterpret_cast<uint4 *>(&rows[wave][0][4 + lr][8 * lp]) = kb;
     *reinterpret_cast<uint4 *>(&rows[wave][1][lr][8 * lp]) = va;
@@ -250,45 +254,63 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
   const float ak = L.clip_k[hk * cfg_NG + grp], av = L.clip_v[hk * cfg_NG + grp];
   int4 pk[4], pv[4];
   {
-    const int4 *ppk = reinterpret_cast<const int4 *>(L.perm_k + hk * kD + 16 * n);
-    const int4 *ppv = reinterpret_cast<const int4 *>(L.perm_v + hk * kD + 16 * n);
+    const int4 *ppk = reinterpret_cast<const int4 *>(L.perm_k + hk * kD) + 4 * n;
+    const int4 *ppv = reinterpret_cast<const int4 *>(L.perm_v + hk * kD) + 4 * n;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       pk[q] = ppk[q];
       pv[q] = ppv[q];
     }
   }
-  const long long t = t0 + i;
-  const bool valid = t < nq;
+  // the wavefront's rows that exist: rows t0 .. t0 + n_valid - 1 (rows past the packed region are
+  // computed from the stand-in data and dropped)
+  const int n_valid = (int)(nq - t0 < 8 ? (nq - t0 < 0 ? 0 : nq - t0) : 8);
+  const bool valid = i < n_valid;
   wave_lds_sync();
 
   GroupParams gk, gv;
   constexpr int kKBits = KL == 16 ? 4 : KL == 8 ? 3 : 2, kVBits = VL == 16 ? 4 : VL == 8 ? 3 : 2;
-  const uint2 kw = encode16<kKBits>(rows[wave][0][i], pk, ak, cfg_G, (float)(KL - 1), cfg_fmt, uneq, gmap, lane, gk);
-  const uint2 vw = encode16<kVBits>(rows[wave][1][i], pv, av, cfg_G, (float)(VL - 1), cfg_fmt, uneq, gmap, lane, gv);
+  float x[16];
+  gather16(rows[wave][0][i], pk, ak, cfg_G, (float)(KL - 1), cfg_fmt, uneq, gmap, lane, x, gk);
+  const uint2 kw = pack16<kKBits>(x, gk, (float)(KL - 1));
+  gather16(rows[wave][1][i], pv, av, cfg_G, (float)(VL - 1), cfg_fmt, uneq, gmap, lane, x, gv);
+  uint2 vw = make_uint2(0u, 0u);
+  if constexpr (TERNARY) {
+    // the sum's low byte is the code: sixteen byte stores, no packing
+    uint8_t *col = &vbytes[wave][0][n][i];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) col[64 * e] = (uint8_t)code_in_low_bits(x[e], gv, 2.0f);
+  } else {
+    vw = pack16<kVBits>(x, gv, (float)(VL - 1));
+  }
   unsigned ktop = 0;
   if (KL == 8) {  // the plane dword of a pair of key dwords comes from two lanes
     ktop = place_key_top_bits(kw.y, n & 1);
     ktop |= __shfl_xor(ktop, 1);
   }
+  // packed key rows and (scale, zero) pairs of the wavefront's rows: scalar bases at row t0, the
+  // lane's row and piece as 32-bit offsets
   if (valid) {
+    uint8_t *krows = L.k_codes + (head * L.Tcap + t0) * k_row_bytes_of(KL);
     if (KL == 16) {
-      reinterpret_cast<uint2 *>(L.k_codes + (head * L.Tcap + t) * (kD / 2))[n] = kw;
+      reinterpret_cast<uint2 *>(krows)[lane] = kw;  // row i, dwords 2n and 2n+1
     } else if (KL == 8) {
-      unsigned *krow = reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * 48);
+      unsigned *krow = reinterpret_cast<unsigned *>(krows) + 12 * i;
       krow[n] = kw.x;
       if ((n & 1) == 0) krow[8 + (n >> 1)] = ktop;
     } else
-      __builtin_nontemporal_store(kw.x, reinterpret_cast<unsigned *>(L.k_codes + (head * L.Tcap + t) * (kD / 4)) + n);
+      __builtin_nontemporal_store(kw.x, reinterpret_cast<unsigned *>(krows) + lane);  // row i, dword n
     if (writes_meta) {
-      meta_store_pair(L.k_meta, (head * L.Tcap + t) * cfg_NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, cfg_fmt);
-      meta_store_pair(L.v_meta, (head * L.Tcap + t) * cfg_NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, cfg_fmt);
+      const size_t pair_bytes = cfg_fmt == SKVQ_META_F32 ? 8 : cfg_fmt == SKVQ_META_F16 ? 4 : 2;
+      const size_t first = (size_t)(head * L.Tcap + t0) * cfg_NG * pair_bytes;
+      meta_store_pair(reinterpret_cast<uint8_t *>(L.k_meta) + first, i * cfg_NG + grp, MetaPair{gk.scale, gk.lo, gk.stored}, cfg_fmt);
+      meta_store_pair(reinterpret_cast<uint8_t *>(L.v_meta) + first, i * cfg_NG + grp, MetaPair{gv.scale, gv.lo, gv.stored}, cfg_fmt);
     }
   }
   // rows past the packed region leave zeros in the block
   if (VL == 16) {
     vq4[wave][i][n] = valid ? vw : make_uint2(0u, 0u);
-  } else {
+  } else if (!TERNARY) {
     vq[wave][i][n] = valid ? vw.x : 0u;
     if (VL == 8) vqtop[wave][i][n] = valid ? vw.y : 0u;
   }
@@ -337,29 +359,29 @@ __global__ __launch_bounds__(256) void prefill_kernel(Layout L, const __half *__
       if ((nh & 1) == 0) unit[4 + (nh >> 1)] = h;
     }
   } else {
-    unsigned fa = 0, fb = 0, pw = 1;
-#pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-      fa += ((vq[wave][ii][2 * nh] >> (2 * j)) & 3u) * pw;
-      fb += ((vq[wave][ii][2 * nh + 1] >> (2 * j)) & 3u) * pw;
-      pw *= 3;
+    // A field is the base-3 number whose digit i is token i's code: the codes of tokens 0..3 and 4..7
+    // arrive as the bytes of two dwords, and a byte-wise dot product with (1, 3, 9, 27) sums four
+    // digits at once.
+    uint4 c = *reinterpret_cast<const uint4 *>(&vbytes[wave][j][2 * nh][0]);
+    if (n_valid < 8) {  // (a scalar condition) bytes of rows that do not exist count as zero
+      const unsigned lo = n_valid >= 4 ? ~0u : (1u << (8 * n_valid)) - 1u;
+      const unsigned hi = n_valid <= 4 ? 0u : (1u << (8 * (n_valid - 4))) - 1u;
+      c.x &= lo, c.z &= lo, c.y &= hi, c.w &= hi;
     }
-    pieces[wave][lane] = fa | (fb << 13);  // 26 bits
+    constexpr unsigned kPowers = 1u | (3u << 8) | (9u << 16) | (27u << 24);
+    const unsigned fa = __builtin_amdgcn_udot4(c.x, kPowers, __umul24(81u, __builtin_amdgcn_udot4(c.y, kPowers, 0u, false)), false);
+    const unsigned fb = __builtin_amdgcn_udot4(c.z, kPowers, __umul24(81u, __builtin_amdgcn_udot4(c.w, kPowers, 0u, false)), false);
+    reinterpret_cast<unsigned *>(vfields[wave])[4 * j + nh] = fa | (fb << 16);  // fields 8j + 2nh and the next
     wave_lds_sync();
-    if (lane < 16) {
-      const unsigned long long a0 = pieces[wave][lane], a1 = pieces[wave][16 + lane];
-      const unsigned long long a2 = pieces[wave][32 + lane], a3 = pieces[wave][48 + lane];
-      const unsigned long long lo = a0 | (a1 << 26) | (a2 << 52);       // bits 0..63
-      const unsigned long long hi = (a2 >> 12) | (a3 << 14);            // bits 64..103
-      uint8_t *u = units[wave] + 13 * lane;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) u[q] = (uint8_t)(lo >> (8 * q));
-#pragma unroll
-      for (int q = 0; q < 5; ++q) u[8 + q] = (uint8_t)(hi >> (8 * q));
+    // The sub-block's 208 bytes are its 128 fields of 13 bits in a row.  Lane d < 52 builds dword d:
+    // bits 32d .. 32d+31 lie in the four fields from number 32d / 13 on.
+    if (lane < 52) {
+      const unsigned first = (32u * lane) / 13u, shift = 32u * lane - 13u * first;
+      const unsigned short *f = &vfields[wave][first];
+      const unsigned f0 = f[0], f1 = f[1], f2 = f[2], f3 = f[3];  // (f3 of the last dword is padding, shifted out)
+      const unsigned low = f0 | (f1 << 13) | (f2 << 26), high = (f2 >> 6) | (f3 << 7);  // bits 0..31 and 32..51
+      __builtin_nontemporal_store(__builtin_amdgcn_alignbit(high, low, shift), reinterpret_cast<unsigned *>(dst + 208 * wave) + lane);
     }
-    wave_lds_sync();
-    if (lane < 52)
-      __builtin_nontemporal_store(reinterpret_cast<const unsigned *>(units[wave])[lane], reinterpret_cast<unsigned *>(dst + 208 * wave) + lane);
   }
 }
 

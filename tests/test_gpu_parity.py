@@ -855,7 +855,10 @@ def test_clip_calibration_matches_oracle_search(P, G, v_bits, k_bits, Hq, Hk, B)
         out = np.stack([c.decode(q[i]) for i in range(n_q)]).astype(np.float64)
         return ((out - o_ref) ** 2).reshape(n_q, B, Hk, Hq // Hk, D).sum(axis=(0, 1, 3, 4))
 
-    if not (np.array_equal(gk, rk) and np.array_equal(gv, rv)):
+    same_choice = np.array_equal(gk, rk) and np.array_equal(gv, rv)
+    P.log(f"clip calibration G{G}: the library's scales {'are' if same_choice else 'are NOT'} the oracle's "
+          f"({int(np.sum(gk != rk) + np.sum(gv != rv))} of {gk.size + gv.size} differ)")
+    if not same_choice:
         assert np.all(oracle_loss(gk, gv) <= rloss * 1.001)
     assert np.allclose(gloss, oracle_loss(gk, gv), rtol=2e-3)
     assert np.any(gk < 1.0) or np.any(gv < 1.0)           # heavy-tailed data: clipping pays
