@@ -575,7 +575,7 @@ def main() -> int:
     def append_all():
         for layer, c in enumerate(caches):
             c.skvq_quantize_append(kn_all[i, layer], vn_all[i, layer])
-    append_us = float(timed_us(append_all, n_layers, 1, warm=0).mean())
+    append_us = float(timed_us(append_all, n_layers, 3, warm=0).min())  # (the first round also loads the kernel)
 
     pre_alg = algorithmic_bytes_prefill(w, args.meta)
     facts = profile_facts(w.name) if as_baseline else {}

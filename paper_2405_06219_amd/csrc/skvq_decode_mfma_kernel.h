@@ -62,33 +62,45 @@ struct __attribute__((aligned(4))) Unit16 {  // a 16-byte load that is only 4-by
 };
 typedef uint4_t uint4_a4_t __attribute__((aligned(4)));
 typedef uint2_t uint2_a4_t __attribute__((aligned(4)));
-// Loads of packed cache data: every byte is read once per call, so it is marked as streaming (it
-// need not displace what the caches hold for longer: the query, the permutations, the partials).
-__device__ __forceinline__ uint4_t stream_load(const uint4_t *p) { return __builtin_nontemporal_load(p); }
+// Loads of packed cache data.  Every byte is read once per call, so a load may be marked as
+// streaming (STREAM): the data then need not displace what the caches hold for longer (the query,
+// the permutations, the partials).  That pays where one load instruction takes all that a
+// wavefront wants of a cache line soon (32-byte key rows, 13- and 16-byte V units: 4-7 % at long
+// contexts); where a row or unit is fetched by several instructions in turn (48- and 64-byte key
+// rows, 24- and 32-byte V units) the later ones would miss, and the kernel is 20 % slower: those
+// formats load plainly.
+template <bool STREAM, class T>
+__device__ __forceinline__ T load_as(const T *p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(p); else return *p;
+}
+template <bool STREAM>
+__device__ __forceinline__ uint4_t stream_load(const uint4_t *p) { return load_as<STREAM>(p); }
+template <bool STREAM>
 __device__ __forceinline__ Unit16 stream_load_unit(const void *p) {
-  const uint4_t v = __builtin_nontemporal_load(reinterpret_cast<const uint4_a4_t *>(p));
+  const uint4_t v = load_as<STREAM>(reinterpret_cast<const uint4_a4_t *>(p));
   return Unit16{v.x, v.y, v.z, v.w};
 }
+template <bool STREAM>
 __device__ __forceinline__ uint2_t stream_load_pair(const void *p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const uint2_a4_t *>(p));
+  return load_as<STREAM>(reinterpret_cast<const uint2_a4_t *>(p));
 }
-template <class T>  // a naturally aligned block of 2, 4, 8, 16 or 32 bytes
+template <bool STREAM, class T>  // a naturally aligned block of 2, 4, 8, 16 or 32 bytes
 __device__ __forceinline__ T stream_load_block(const T *p) {
   if constexpr (sizeof(T) == 2) {
-    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const unsigned short *>(p)));
+    return __builtin_bit_cast(T, load_as<STREAM>(reinterpret_cast<const unsigned short *>(p)));
   } else if constexpr (sizeof(T) == 4) {
-    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p)));
+    return __builtin_bit_cast(T, load_as<STREAM>(reinterpret_cast<const unsigned *>(p)));
   } else if constexpr (sizeof(T) == 8) {
-    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const uint2_t *>(p)));
+    return __builtin_bit_cast(T, load_as<STREAM>(reinterpret_cast<const uint2_t *>(p)));
   } else if constexpr (sizeof(T) == 16) {
-    return __builtin_bit_cast(T, __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(p)));
+    return __builtin_bit_cast(T, load_as<STREAM>(reinterpret_cast<const uint4_t *>(p)));
   } else {
     static_assert(sizeof(T) == 32, "unexpected block size");
     struct Two {
       uint4_t a, b;
     };
     const uint4_t *q = reinterpret_cast<const uint4_t *>(p);
-    return __builtin_bit_cast(T, Two{__builtin_nontemporal_load(q), __builtin_nontemporal_load(q + 1)});
+    return __builtin_bit_cast(T, Two{load_as<STREAM>(q), load_as<STREAM>(q + 1)});
   }
 }
 
@@ -431,6 +443,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int safe_last_tile = n_tiles > 0 ? n_tiles - 1 : 0;
   const int safe_last_token = last_token > 0 ? last_token : 0;
   const int safe_last_blk = last_blk > 0 ? last_blk : 0;
+  // which of the streams are marked as streaming loads (see load_as)
+  constexpr bool kStreamK = KL == 4, kStreamV = VL == 3 || VL == 4;
   auto load_tile = [&](int tile) {
     Tile d;
     if (tile > safe_last_tile) tile = safe_last_tile;
@@ -438,22 +452,22 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     int t = tile * 64 + lane;
     if (t > safe_last_token) t = safe_last_token;  // only in the last tile; such lanes are masked below
     const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * kRowBytes);
-    d.k0 = stream_load(krow); d.k1 = stream_load(krow + 1);
-    if constexpr (K4) { d.k2 = stream_load(krow + 2); d.k3 = stream_load(krow + 3); }
-    if constexpr (K3) d.k2 = stream_load(krow + 2);
-    d.kmeta = stream_load_block(&km[t]);
-    d.vmeta = stream_load_block(&vm[t]);
+    d.k0 = stream_load<kStreamK>(krow); d.k1 = stream_load<kStreamK>(krow + 1);
+    if constexpr (K4) { d.k2 = stream_load<kStreamK>(krow + 2); d.k3 = stream_load<kStreamK>(krow + 3); }
+    if constexpr (K3) d.k2 = stream_load<kStreamK>(krow + 2);
+    d.kmeta = stream_load_block<kStreamK>(&km[t]);
+    d.vmeta = stream_load_block<kStreamK>(&vm[t]);
     const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
     const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
-    d.v00 = stream_load_unit(vc + (size_t)blk0 * vbb + unit_off);
-    d.v10 = stream_load_unit(vc + (size_t)blk1 * vbb + unit_off);
+    d.v00 = stream_load_unit<kStreamV>(vc + (size_t)blk0 * vbb + unit_off);
+    d.v10 = stream_load_unit<kStreamV>(vc + (size_t)blk1 * vbb + unit_off);
     if constexpr (V3) {
-      d.vt0 = stream_load_pair(vc + (size_t)blk0 * vbb + unit_off + 16);
-      d.vt1 = stream_load_pair(vc + (size_t)blk1 * vbb + unit_off + 16);
+      d.vt0 = stream_load_pair<kStreamV>(vc + (size_t)blk0 * vbb + unit_off + 16);
+      d.vt1 = stream_load_pair<kStreamV>(vc + (size_t)blk1 * vbb + unit_off + 16);
     }
     if constexpr (V4) {
-      d.v01 = stream_load_unit(vc + (size_t)blk0 * vbb + unit_off + 16);
-      d.v11 = stream_load_unit(vc + (size_t)blk1 * vbb + unit_off + 16);
+      d.v01 = stream_load_unit<kStreamV>(vc + (size_t)blk0 * vbb + unit_off + 16);
+      d.v11 = stream_load_unit<kStreamV>(vc + (size_t)blk1 * vbb + unit_off + 16);
     }
     return d;
   };
