@@ -122,8 +122,9 @@ def build_layers(w, n_layers: int, headroom: int, device, n_sink: int = 0, meta:
     for layer in range(n_layers):
         # seeded synthetic K/V and the reorder index from their channel ranges (offline calibration stand-in)
         k, v, pk, pv = synth.make_kv_device(w, device, stream=layer)
+        # (packed capacity in whole 64-token tiles: every kv head's rows then start on a cache line)
         c = B.SkvqCache(w.batch, w.n_q_heads, w.n_kv_heads, w.group_size, w.v_bits, w.window,
-                        w.context - w.window + headroom, pk, pv, ck, cv, device=device, n_sink=n_sink,
+                        -(-(w.context - w.window + headroom) // 64) * 64, pk, pv, ck, cv, device=device, n_sink=n_sink,
                         meta=meta, k_bits=w.k_bits, group_bounds=group_bounds, max_new_tokens=MULTI_TOKENS[-1])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -397,7 +398,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--layers", type=int, default=0, help="layer caches rotated (default 32; probes: 4)")
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--context", type=int, default=0, help="override the workload's context (tests)")
@@ -492,12 +493,18 @@ def main() -> int:
             c.skvq_decode_attention(q, out_f32=o, stream=stream)
 
     step, other_step = (step_two_calls, step_one_call) if args.two_calls else (step_one_call, step_two_calls)
+    # (an idle GPU takes about ten milliseconds of work to come back to its clocks: nothing slow may sit
+    # between the warm-up steps and the timed ones)
+    gc.collect()
+    gc.disable()
+    # (decode calls that change nothing, about 15 ms of them, whatever the warm-up count asked for)
+    for _ in range(20):
+        for c, (kn, vn, q, o) in zip(caches, views[0]):
+            c.skvq_decode_attention(q, out_f32=o, stream=stream)
     i = 0
     for _ in range(n_warm):
         step(i)
         i += 1
-    gc.collect()
-    gc.disable()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(n_steps):
