@@ -332,9 +332,10 @@ int skvq_set_num_splits(skvq_cache *cache, int32_t n_splits);
 
 /* Measurement yardstick, no part of the method (for benchmarks that price the decode path against
  * what the device can read): a kernel that only reads `bytes` bytes (a multiple of 16) from src
- * (DEVICE, 16-byte aligned) with grid-strided 16-byte loads, eight workgroups of 256 threads per
- * compute unit (the fastest shape of a sweep), on hip_stream, asynchronously.  sink: DEVICE, 4 bytes, written only if the XOR of all words read equals a magic
- * number (so that the loads cannot be dropped). */
+ * (DEVICE, 16-byte aligned) once, with grid-strided streaming 16-byte loads, eight workgroups of 256
+ * threads per compute unit (the fastest shape of a sweep), on hip_stream, asynchronously.  sink:
+ * DEVICE, 4 bytes, written only if the XOR of all words read equals a magic number (so that the
+ * loads cannot be dropped). */
 int skvq_read_yardstick(const void *src, size_t bytes, void *sink, void *hip_stream);
 
 /* Static description of a status code; the cache's last HIP error text (owned by cache). */
