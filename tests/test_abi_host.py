@@ -204,3 +204,16 @@ def test_library_reorder_is_lloyds_kmeans_and_recovers_planted_families(B):
     perm16, bounds16 = B.skvq_calibrate_reorder(stats, 32, 16, 100)
     assert np.array_equal(perm16, perm)
     assert np.all(bounds16 % 16 == 0) and np.all(np.diff(bounds16, axis=1) >= 16) and np.all(np.abs(bounds16 - bounds) <= 8)
+
+
+def test_read_yardstick_refuses_bad_arguments_before_touching_a_device(B):
+    """Null pointers, a length that is no multiple of 16 and a misaligned source are refused by the
+    host checks (no GPU call is made for them)."""
+    L = B.lib()
+    L.skvq_read_yardstick.restype = C.c_int
+    L.skvq_read_yardstick.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    assert L.skvq_read_yardstick(None, 1024, 0x1000, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_read_yardstick(0x1000, 1024, None, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_read_yardstick(0x1000, 0, 0x2000, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_read_yardstick(0x1000, 1000, 0x2000, None) == B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_read_yardstick(0x1008, 1024, 0x2000, None) == B.SKVQ_ERR_INVALID_ARG

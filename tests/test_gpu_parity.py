@@ -816,6 +816,25 @@ def test_prefill_phase_in_one_call(P):
     assert e.value.status == P.B.SKVQ_ERR_CAPACITY and pair.gpu.skvq_get_state() == state
 
 
+# ---- the read-only kernel that bench.py prices the decode call against ----
+
+@pytest.mark.gpu
+def test_read_yardstick_reads_and_leaves_memory_alone(P):
+    """The kernel runs over whole buffers and ragged ones (a tail shorter than the grid's stride),
+    changes neither the source nor the sink, and refuses a length that is no multiple of 16."""
+    from paper_2405_06219_amd import binding as Bd
+    dev = "cuda:0"
+    for n_bytes in (16, 4096, 1 << 20, (1 << 20) + 16 * 37, 78065664):
+        src = torch.arange(n_bytes // 4, dtype=torch.int32, device=dev)
+        want = src.clone()
+        sink = torch.full((1,), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+        Bd.skvq_read_yardstick(src, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(src, want) and int(sink.item()) == 0x5A5A5A5A, n_bytes
+    with pytest.raises(Bd.SkvqError):
+        Bd.skvq_read_yardstick(torch.zeros(5, dtype=torch.int32, device=dev), sink)
+
+
 # ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
 
 @pytest.mark.parametrize("G,v_bits,k_bits,Hq,Hk,B", [(64, 2.0, 2.0, 4, 2, 1), (128, 1.5, 2.0, 8, 2, 2), (32, 4.0, 4.0, 3, 3, 1)])
