@@ -247,7 +247,7 @@ struct Smem {
   } wb[kNW];
   float qraw[4][kD];                   // the query heads as loaded (rows >= R are zero)
   _Float16 qa[32][4][4];               // A operands of the score product: [step][head][k slot]
-  float qpart[4][8];                   // per head: sums of the reordered query over 16 positions each
+  alignas(16) float qpart[4][8];       // per head: sums of the reordered query over 16 positions each
   // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
   // tiles (w*) and for the ring slices (r*) of the wave
   // ([head][...][wave]: the epilogue reads a head's eight entries as two 16-byte pieces)
@@ -390,6 +390,22 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const long long head = (long long)b * L.Hk + hk;
   const float c = L.sm_scale * kLog2e;
 
+  // ---- the query and the permutations: the first requests of the workgroup, ahead of everything
+  //      else (the start-up waits for the query longer than for anything: it queues with the tile
+  //      requests of all workgroups) ----
+  const int n_rows = n_new * L.R;  // rows of this kv head: (query token, query head)
+  // row x of the kv head -> index of its (sequence, query token, query head) in q, the partials and the output
+  auto row_index = [&](int x) {
+    const int j = n_new == 1 ? 0 : x / L.R;  // (no division on the single-token path)
+    return ((long long)b * n_new + j) * L.Hq + hk * L.R + (x - j * L.R);
+  };
+  __half2 q2 = __floats2half2_rn(0.f, 0.f);
+  if (tid < 64 * R && head0 + (tid >> 6) < n_rows)
+    q2 = reinterpret_cast<const __half2 *>(q + row_index(head0 + (tid >> 6)) * kD)[lane];
+  // (staging: wavefront w < 4 places head w's query at the positions lane and 64 + lane)
+  const int pk0 = L.perm_k[hk * kD + lane], pk1 = L.perm_k[hk * kD + 64 + lane];
+  const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
+
   // ---- the new token taken along (knew != null; one query token, passes == 1, and the token
   //      that leaves the window, if any, is packed: the host sees to that).  T counts the new
   //      token.  The workgroup of the last chunk does what the append kernel does (its tiles are
@@ -508,20 +524,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     return d;
   };
 
-  // ---- prologue: one memory round trip.  The small loads (query, permutations, table) are
-  //      issued BEFORE the tile loads: loads return in order, so the staging below only has to
-  //      wait for them and not for the two tiles of packed data behind them. ----
-  const int n_rows = n_new * L.R;  // rows of this kv head: (query token, query head)
-  // row x of the kv head -> index of its (sequence, query token, query head) in q, the partials and the output
-  auto row_index = [&](int x) {
-    const int j = n_new == 1 ? 0 : x / L.R;  // (no division on the single-token path)
-    return ((long long)b * n_new + j) * L.Hq + hk * L.R + (x - j * L.R);
-  };
-  __half2 q2 = __floats2half2_rn(0.f, 0.f);
-  if (tid < 64 * R && head0 + (tid >> 6) < n_rows)
-    q2 = reinterpret_cast<const __half2 *>(q + row_index(head0 + (tid >> 6)) * kD)[lane];
-  const int pk = L.perm_k[hk * kD + (tid & 127)];
-  const int pv_ch = L.perm_v[hk * kD + (tid & 127)];  // for the epilogue: channel of position tid%128
+  // ---- prologue: one memory round trip.  The small loads (query and permutations above, ring
+  //      slice here) are issued BEFORE the tile loads: loads return in order, so the staging below
+  //      only has to wait for them and not for the two tiles of packed data behind them. ----
   RingData ring = {};
   if (ring_owner) ring = load_ring(ring_first);  // landed before the tile loop either way (see below)
   asm volatile("" ::: "memory");
@@ -569,23 +574,27 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     }
   }
   {
-    if (tid < 256) {
-      sm.qraw[tid >> 6][2 * lane] = __low2float(q2);
-      sm.qraw[tid >> 6][2 * lane + 1] = __high2float(q2);
-    }
-    __syncthreads();
     asm volatile("" ::: "memory");
     buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
+    // Wavefront w < 4 stages head w by itself: it parks the head's query in LDS as loaded (for the
+    // fp16 slices later), reads it back through the permutation (its own writes: no barrier, the
+    // LDS serves a wavefront's operations in order) and writes the head's matrix operands and piece
+    // sums.  One barrier then covers the operands, the sums and the table.
     if (tid < 256) {
+      sm.qraw[wave][2 * lane] = __low2float(q2);
+      sm.qraw[wave][2 * lane + 1] = __high2float(q2);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {  // thread (p = tid%128, heads tid/128 and tid/128 + 2)
-        const int row = (tid >> 7) + 2 * rr, p = tid & 127;
+      for (int j = 0; j < 2; ++j) {
+        const int row = wave, p = lane + 64 * j;
         int step, kslot, shift;
         if (K4)
           k4_slot_of(p, step, kslot, shift);
         else
           k_slot_of(p, step, kslot, shift);
-        const float x = sm.qraw[row][pk];
+        const float x = sm.qraw[row][j ? pk1 : pk0];
         sm.qa[step][row][kslot] = (_Float16)ldexpf(x, 8 - shift);  // exact: a power of two
         // sum of the reordered query over the 16 positions of this row of lanes
         float s16 = x;
@@ -607,6 +616,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   // scale*sum q(c-centre) + (zero+centre*scale)*sum q  small.
   float qsc[R][NG];
   float4_t dinit[UNEQ ? 1 : NG];
+  float qp[4][8];  // the piece sums of the four heads (two 16-byte reads per head)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const float4_t lo4 = *reinterpret_cast<const float4_t *>(&sm.qpart[r][0]);
+    const float4_t hi4 = *reinterpret_cast<const float4_t *>(&sm.qpart[r][4]);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) qp[r][x] = lo4[x], qp[r][4 + x] = hi4[x];
+  }
   if constexpr (UNEQ) {
     // (a piece's accumulator sums only 16 products: it starts from zero, uncentred)
 #pragma unroll
@@ -615,7 +632,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       for (int r = 0; r < R; ++r) {
         float sum = 0.f;
 #pragma unroll
-        for (int x = 0; x < 8; ++x) sum += piece_group(x) == g ? sm.qpart[r][x] : 0.f;
+        for (int x = 0; x < 8; ++x) sum += piece_group(x) == g ? qp[r][x] : 0.f;
         qsc[r][g] = c * sum;
       }
     dinit[0] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -626,7 +643,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       for (int r = 0; r < 4; ++r) {
         float sum = 0.f;
 #pragma unroll
-        for (int x = 0; x < 8 / NG; ++x) sum += sm.qpart[r][g * (8 / NG) + x];
+        for (int x = 0; x < 8 / NG; ++x) sum += qp[r][g * (8 / NG) + x];
         if (r < R) qsc[r][g] = c * sum;
         dinit[g][r] = -kCentre * sum * (1.0f / 65536.0f);
       }
