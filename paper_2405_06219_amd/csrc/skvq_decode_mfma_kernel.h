@@ -133,16 +133,18 @@ constexpr int kQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]
 constexpr int kRowHalfMirror = 0x141;  // lane i reads lane 7 - i of its half row
 constexpr int kRowMirror = 0x140;      // lane i reads lane 15 - i of its row
 constexpr int kRowShl = 0x100;         // + n: lane i reads lane i + n of its row
-// Sum over the wavefront, returned in every lane (as a wave-uniform value).
-__device__ __forceinline__ float wave_sum_fast(float v) {
+
+// The sum over the 64 lanes, valid in lane 63 only: the row sums as above, then two broadcasts from
+// row to row (no lane reads through scalar registers: six dependent moves in all).
+__device__ __forceinline__ float wave_sum_in_last_lane(float v) {
   v += row_move<kQuadSwap1>(v);
   v += row_move<kQuadSwap2>(v);
   v += row_move<kRowHalfMirror>(v);
   v += row_move<kRowMirror>(v);  // every lane: the sum of its row
-  return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0)) +
-          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16))) +
-         (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32)) +
-          __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48)));
+  // lane 15 of rows 0 and 2 to rows 1 and 3; lane 31 to rows 2 and 3 (other rows get 0)
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));
+  return v;
 }
 
 __device__ __forceinline__ half4_t h4(unsigned a, unsigned b) { return __builtin_bit_cast(half4_t, uint2_t{a, b}); }
@@ -984,17 +986,23 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   }
 
   // ---- epilogue: fold lanes, columns, waves and ring slices; write this chunk's partial ----
+  {
+    // (all the sums first, then all the stores from lane 63: the chains of row moves interleave)
+    float ls[R], zs[R][NG];
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const float ls = wave_sum_fast(lsum[r]);
-    if (lane == 0) {
-      sm.wm[r][wave] = first ? -INFINITY : mref[r];
-      sm.wl[r][wave] = ls;
+    for (int r = 0; r < R; ++r) {
+      ls[r] = wave_sum_in_last_lane(lsum[r]);
+#pragma unroll
+      for (int g = 0; g < NG; ++g) zs[r][g] = wave_sum_in_last_lane(zacc[r][g]);
     }
+    if (lane == 63) {
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float zs = wave_sum_fast(zacc[r][g]);
-      if (lane == 0) sm.wz[r][g][wave] = zs;
+      for (int r = 0; r < R; ++r) {
+        sm.wm[r][wave] = first ? -INFINITY : mref[r];
+        sm.wl[r][wave] = ls[r];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) sm.wz[r][g][wave] = zs[r][g];
+      }
     }
   }
   if (!first) {
@@ -1013,31 +1021,36 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   }
   __syncthreads();
   if (tid < R * kD && head0 + (tid >> 7) < n_rows) {
-    // thread (head r, position p): the chunk's reference m* = max over waves and ring slices,
-    // each one's factor 2^(m - m*), the sums that need no channel (every thread of a head
-    // computes the same ones: cheaper than another exchange through LDS), its channel's sum
+    // thread (head r, position p); a wavefront serves one head.  The sixteen things to combine --
+    // the eight wavefronts' tile sums and their eight ring-slice sums -- are spread over the lanes of
+    // every row of sixteen: lane i holds the reference and the weight sum of thing i, the chunk's
+    // reference m* is a row maximum, thing i's factor 2^(m_i - m*) one exponential per lane instead
+    // of sixteen per thread, the weight sum a row sum; the factors then reach every thread as
+    // wave-uniform values read from lanes 0..15.
     const int r = tid >> 7, p = tid & 127;
     const int ch = pv_ch;
-    static_assert(kNW == 8, "the epilogue reads eight per-wave entries as two 16-byte pieces");
-    float wm[kNW], wl[kNW], rm[kNW], rl[kNW], wz[kNW];
+    static_assert(kNW == 8, "the epilogue spreads eight tile sums and eight ring sums over sixteen lanes");
+    const int thing = lane & 15, src = thing & 7;
+    const bool ring_thing = thing >= 8;
+    float x = ring_thing ? sm.rm[r][src] : sm.wm[r][src];   // its reference
+    const float y = ring_thing ? sm.rl[r][src] : sm.wl[r][src];  // its sum of weights
+    const bool has_tokens = y > 0.f;  // (a wave or slice without tokens left no meaningful reference)
+    x = has_tokens ? x : -INFINITY;
+    float m = x;
+    m = fmaxf(m, row_move<kQuadSwap1>(m));
+    m = fmaxf(m, row_move<kQuadSwap2>(m));
+    m = fmaxf(m, row_move<kRowHalfMirror>(m));
+    m = fmaxf(m, row_move<kRowMirror>(m));  // every lane: the maximum of its row
+    const float factor = has_tokens ? fast_exp2(x - m) : 0.f;
+    float den = factor * y;
+    den += row_move<kQuadSwap1>(den);
+    den += row_move<kQuadSwap2>(den);
+    den += row_move<kRowHalfMirror>(den);
+    den += row_move<kRowMirror>(den);
     const int zg = UNEQ ? piece_group(p >> 4) : p * NG / kD;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const float4_t a = *reinterpret_cast<const float4_t *>(&sm.wm[r][4 * h]);
-      const float4_t b4 = *reinterpret_cast<const float4_t *>(&sm.wl[r][4 * h]);
-      const float4_t c4 = *reinterpret_cast<const float4_t *>(&sm.rm[r][4 * h]);
-      const float4_t d = *reinterpret_cast<const float4_t *>(&sm.rl[r][4 * h]);
-      const float4_t z = *reinterpret_cast<const float4_t *>(&sm.wz[r][zg][4 * h]);
-#pragma unroll
-      for (int x = 0; x < 4; ++x) wm[4 * h + x] = a[x], wl[4 * h + x] = b4[x], rm[4 * h + x] = c4[x], rl[4 * h + x] = d[x], wz[4 * h + x] = z[x];
-    }
-    float m = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kNW; ++w) {
-      wm[w] = wl[w] > 0.f ? wm[w] : -INFINITY;
-      rm[w] = rl[w] > 0.f ? rm[w] : -INFINITY;
-      m = fmaxf(m, fmaxf(wm[w], rm[w]));
-    }
+    const float4_t z0 = *reinterpret_cast<const float4_t *>(&sm.wz[r][zg][0]);
+    const float4_t z1 = *reinterpret_cast<const float4_t *>(&sm.wz[r][zg][4]);
+    const float wz[kNW] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
     // (every read unconditional, what a wave or slice without tokens left there is deselected
     // afterwards: the reads then go out together and are waited for once, not one LDS round
     // trip after the other)
@@ -1047,11 +1060,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       ws[w] = sm.wb[w].stage[r][p] + wz[w];
       rs[w] = sm.ring_o[w][r][ch];
     }
-    float den = 0.f, num = 0.f;
+    float num = 0.f;
 #pragma unroll
     for (int w = 0; w < kNW; ++w) {
-      const float e = wl[w] > 0.f ? fast_exp2(wm[w] - m) : 0.f, g = rl[w] > 0.f ? fast_exp2(rm[w] - m) : 0.f;
-      den = fmaf(e, wl[w], fmaf(g, rl[w], den));
+      const float e = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, factor), w));
+      const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, factor), 8 + w));
       num = fmaf(e, e > 0.f ? ws[w] : 0.f, num);
       num = fmaf(g, g > 0.f ? rs[w] : 0.f, num);
     }
