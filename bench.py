@@ -75,6 +75,31 @@ def algorithmic_bytes_prefill(w, meta: str = "f32") -> int:
     return w.batch * w.n_kv_heads * (w.context * 2 * D * 2 + nq * per_row + min(w.context, w.window) * 2 * D * 2)
 
 
+def read_write_yardstick(B, torch, w, device, budget_bytes: int = 9 << 30) -> dict:
+    """The library's read/write kernel on the prefill quantizer's traffic: as many bytes read as the call's
+    fp16 K and V, a seventh of that written (the packed codes are 1/6.9 of it), rotating through distinct
+    buffers so that every launch finds cold data."""
+    ratio = 7
+    read_bytes = w.batch * w.n_kv_heads * w.context * 2 * D * 2
+    write_bytes = (read_bytes // ratio) & ~0xFFF
+    n_bufs = int(max(1, min(8, budget_bytes // (ratio * write_bytes))))
+    src = torch.ones(n_bufs * ratio * write_bytes, dtype=torch.uint8, device=device)
+    dst = torch.empty(n_bufs * write_bytes, dtype=torch.uint8, device=device)
+    pairs = [(src[j * ratio * write_bytes:(j + 1) * ratio * write_bytes], dst[j * write_bytes:(j + 1) * write_bytes])
+             for j in range(n_bufs)]
+
+    def sweep():
+        for s_, d_ in pairs:
+            B.skvq_read_write_yardstick(s_, d_, ratio)
+    us = float(timed_us(sweep, n_bufs, 5).mean())
+    moved = (ratio + 1) * write_bytes
+    del src, dst, pairs
+    return {"read_bytes": ratio * write_bytes, "write_bytes": write_bytes, "us_per_launch": us,
+            "gbps": moved / us / 1e3, "frac_of_hbm_peak": moved / us / 1e3 / HBM_PEAK_GBPS,
+            "what": "skvq_read_write_yardstick: the prefill call's fp16 bytes read, a seventh of that written, "
+                    "nothing computed, launches back to back on cold data"}
+
+
 # ------------------------------------------------------- facts from profiles/ ----
 
 def source_fingerprint() -> str:
@@ -162,6 +187,7 @@ def measure_config(name: str, device, steps: int) -> dict:
     (enough layers that the calls' data exceeds the Infinity Cache), HIP events around the calls issued
     back to back.  The batch-16 configuration: its prefill, then 64 append + attention steps."""
     import torch
+    from paper_2405_06219_amd import binding as B
     from paper_2405_06219_amd import synth
 
     w = synth.WORKLOADS[name]
@@ -228,6 +254,9 @@ def measure_config(name: str, device, steps: int) -> dict:
     if name == "c1_mha4_2k":
         res["note"] = "latency-bound (0.9 MB per call): microseconds are the figure, not the bandwidth"
     del caches
+    torch.cuda.empty_cache()
+    res["read_write_kernel"] = read_write_yardstick(B, torch, w, device)
+    res["prefill_frac_of_read_write_kernel"] = res["read_write_kernel"]["gbps"] and res["prefill_hbm_gbps"] / res["read_write_kernel"]["gbps"]
     torch.cuda.empty_cache()
     return res
 
@@ -309,6 +338,7 @@ def bounded_context(w, token_heads: int) -> int:
 def probe(args, w, bounds, device) -> int:
     import torch
     from paper_2405_06219_amd import binding as B
+    from paper_2405_06219_amd import synth
 
     if args.probe == "decode":
         # a few decode calls (first skvq_decode_attention alone, then skvq_append_decode_attention), then a
@@ -387,6 +417,14 @@ def probe(args, w, bounds, device) -> int:
             print(f"probe read: {nbytes} bytes ({label}), {n_slices} slices back to back: {us.mean():.2f} us per launch "
                   f"(min {us.min():.2f}), {nbytes / us.mean() / 1e3:.0f} GB/s = {100 * nbytes / us.mean() / 1e3 / HBM_PEAK_GBPS:.1f} % "
                   f"of {HBM_PEAK_GBPS:.0f} GB/s")
+        del buf, slices
+        torch.cuda.empty_cache()
+        # the read/write kernel on the prefill call's traffic, at this workload and at the batch-16 one
+        for wl in (w, synth.WORKLOADS["c5_batch16_32k"]):
+            r = read_write_yardstick(B, torch, wl, device)
+            print(f"probe read/write: prefill call of {wl.name}: {r['read_bytes']} bytes read + {r['write_bytes']} written, "
+                  f"back to back: {r['us_per_launch']:.2f} us per launch, {r['gbps']:.0f} GB/s = "
+                  f"{100 * r['frac_of_hbm_peak']:.1f} % of {HBM_PEAK_GBPS:.0f} GB/s")
         return 0
     print(f"unknown probe {args.probe}", file=sys.stderr)
     return 2
@@ -559,6 +597,10 @@ def main() -> int:
             B.skvq_read_yardstick(s_, read_sink)
     read_us = float(timed_us(read_sweep, len(slices), 5).mean())
     del read_buf, slices
+    torch.cuda.empty_cache()
+    # the read/write kernel on the prefill call's traffic
+    rw = read_write_yardstick(B, torch, w, device)
+    torch.cuda.empty_cache()
 
     # the prompt's own causal attention (skvq_prefill_attention) at 16k tokens of the same head
     # layout: a dense contraction, reported against the fp16 matrix-core peak
@@ -634,6 +676,8 @@ def main() -> int:
         "prefill_tokens_per_s": w.batch * w.context / (prefill_call_us * 1e-6),
         "prefill_hbm_gbps": pre_alg / (prefill_call_us * 1e-6) / 1e9,
         "prefill_frac_of_hbm_peak": pre_alg / (prefill_call_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        "prefill_frac_of_read_write_kernel": pre_alg / (prefill_call_us * 1e-6) / 1e9 / rw["gbps"],
+        "read_write_kernel": rw,
         "prefill_attention": pa,
         "effective_hbm_gbps": achieved,
         "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,

@@ -338,6 +338,14 @@ int skvq_set_num_splits(skvq_cache *cache, int32_t n_splits);
  * loads cannot be dropped). */
 int skvq_read_yardstick(const void *src, size_t bytes, void *sink, void *hip_stream);
 
+/* Second yardstick, for the prefill quantizer (which reads the prompt's fp16 K and V and writes about a
+ * seventh of that): a kernel that reads ratio * write_bytes bytes from src once and writes write_bytes
+ * bytes to dst, computing nothing -- 4 KB piece g of dst becomes the XOR of the 4 KB pieces g * ratio ..
+ * g * ratio + ratio - 1 of src (16-byte word by word).  src, dst: DEVICE, 16-byte aligned, not
+ * overlapping; write_bytes: a multiple of 4096, below 2^43; ratio: 1..8.  One workgroup of 256 threads per
+ * 4 KB written, streaming loads and stores, on hip_stream, asynchronously. */
+int skvq_read_write_yardstick(const void *src, void *dst, size_t write_bytes, int32_t ratio, void *hip_stream);
+
 /* Static description of a status code; the cache's last HIP error text (owned by cache). */
 const char *skvq_status_string(int status);
 const char *skvq_last_error(const skvq_cache *cache);

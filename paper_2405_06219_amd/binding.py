@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
         L.skvq_set_state.argtypes = [C.c_void_p, C.c_int64]
         L.skvq_set_num_splits.argtypes = [C.c_void_p, C.c_int32]
         L.skvq_read_yardstick.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.skvq_read_write_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
         L.skvq_status_string.argtypes = [C.c_int]
         L.skvq_status_string.restype = C.c_char_p
         L.skvq_last_error.argtypes = [C.c_void_p]
@@ -156,6 +157,17 @@ def skvq_calibrate_reorder(stats: np.ndarray, group_size: int, granularity: int 
 def skvq_read_yardstick(src: torch.Tensor, sink: torch.Tensor, stream=None):
     """The library's read-only kernel over the bytes of `src` (a contiguous device tensor)."""
     rc = lib().skvq_read_yardstick(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream_ptr(stream))
+    if rc != SKVQ_OK:
+        raise SkvqError(rc)
+
+
+def skvq_read_write_yardstick(src: torch.Tensor, dst: torch.Tensor, ratio: int, stream=None):
+    """The library's read/write kernel: reads ratio times the bytes of `dst` from `src` and fills `dst`
+    (contiguous device tensors; `src` must hold at least that many bytes)."""
+    nbytes = dst.numel() * dst.element_size()
+    if src.numel() * src.element_size() < ratio * nbytes:
+        raise SkvqError(SKVQ_ERR_INVALID_ARG)
+    rc = lib().skvq_read_write_yardstick(src.data_ptr(), dst.data_ptr(), nbytes, ratio, _stream_ptr(stream))
     if rc != SKVQ_OK:
         raise SkvqError(rc)
 

@@ -1,4 +1,5 @@
-// Measurement yardstick of the library (no part of the method): a kernel that only reads.  The
+// Measurement yardsticks of the library (no part of the method): a kernel that only reads, and one
+// that reads and writes in the prefill quantizer's proportion.  The
 // decode path is bound by how fast the packed cache can be read from HBM; this gives the time that
 // reading the same number of bytes, and nothing else, takes on the device at hand, in the launch
 // shape that a sweep found fastest for it: eight workgroups of 256 threads per compute unit,
@@ -7,6 +8,15 @@
 // 12.9 / 391 us; 1 to 4 workgroups per compute unit with 4 to 32 loads per thread in flight 13.1 to
 // 14.7 / 362 to 476 us; each workgroup of 512 threads its own contiguous slice, the decode kernel's
 // pattern, 13.1 us.
+//
+// The prefill quantizer reads the prompt's fp16 K and V once and writes about a seventh of that as
+// packed codes; reads and writes that share the memory system run slower than reads alone.  The
+// read/write kernel moves the same mix and computes nothing: a workgroup of 256 threads makes one
+// trip, `ratio` streaming 16-byte loads per thread (each a contiguous 4 KB piece per workgroup) and
+// one streaming 16-byte store of their XOR -- the fastest shape of a sweep.  Measured for 537 MB
+// read + 77 MB written / 8.6 GB + 1.2 GB: 101 us / 1.74 ms (6.0 / 5.65 TB/s); grid-strided with
+// fewer, longer-lived workgroups 5.3 to 5.8 / 4.7 to 5.3 TB/s; plain instead of streaming stores or
+// loads 5 to 10 % less.
 #include <hip/hip_runtime.h>
 
 #include "skvq_internal.h"
@@ -28,8 +38,41 @@ __global__ __launch_bounds__(256) void read_yardstick_kernel(const uint4_t *__re
   if (acc == 0x5ca1ab1eu) sink[0] = acc;  // (keeps the loads alive; practically never taken)
 }
 
+constexpr int kMaxRatio = 8;
+
+template <int RATIO>
+__global__ __launch_bounds__(256) void read_write_yardstick_kernel(const uint4_t *__restrict__ src,
+                                                                   uint4_t *__restrict__ dst) {
+  // workgroup g reads the RATIO 4 KB pieces from piece g * RATIO on and writes 4 KB piece g
+  const uint4_t *from = src + ((size_t)blockIdx.x * RATIO) * 256 + threadIdx.x;
+  uint4_t a[RATIO];
+#pragma unroll
+  for (int j = 0; j < RATIO; ++j) a[j] = __builtin_nontemporal_load(from + (size_t)j * 256);
+  uint4_t acc = a[0];
+#pragma unroll
+  for (int j = 1; j < RATIO; ++j) acc ^= a[j];
+  __builtin_nontemporal_store(acc, dst + (size_t)blockIdx.x * 256 + threadIdx.x);
+}
+
 }  // namespace
 }  // namespace skvq
+
+extern "C" int skvq_read_write_yardstick(const void *src, void *dst, size_t write_bytes, int32_t ratio, void *stream) {
+  if (!src || !dst || write_bytes == 0 || (write_bytes & 4095) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||
+      ratio < 1 || ratio > skvq::kMaxRatio || write_bytes / 4096 > 0x7fffffffull)
+    return SKVQ_ERR_INVALID_ARG;
+  const dim3 grid((unsigned)(write_bytes / 4096)), block(256);
+#define SKVQ_RW(R)                                                                                             \
+  case R:                                                                                                      \
+    hipLaunchKernelGGL(skvq::read_write_yardstick_kernel<R>, grid, block, 0, (hipStream_t)stream,               \
+                       (const skvq::uint4_t *)src, (skvq::uint4_t *)dst);                                        \
+    break
+  switch (ratio) {
+    SKVQ_RW(1); SKVQ_RW(2); SKVQ_RW(3); SKVQ_RW(4); SKVQ_RW(5); SKVQ_RW(6); SKVQ_RW(7); SKVQ_RW(8);
+  }
+#undef SKVQ_RW
+  return hipGetLastError() == hipSuccess ? SKVQ_OK : SKVQ_ERR_HIP;
+}
 
 extern "C" int skvq_read_yardstick(const void *src, size_t bytes, void *sink, void *stream) {
   if (!src || !sink || bytes == 0 || (bytes & 15) || ((uintptr_t)src & 15)) return SKVQ_ERR_INVALID_ARG;

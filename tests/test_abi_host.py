@@ -217,3 +217,20 @@ def test_read_yardstick_refuses_bad_arguments_before_touching_a_device(B):
     assert L.skvq_read_yardstick(0x1000, 0, 0x2000, None) == B.SKVQ_ERR_INVALID_ARG
     assert L.skvq_read_yardstick(0x1000, 1000, 0x2000, None) == B.SKVQ_ERR_INVALID_ARG
     assert L.skvq_read_yardstick(0x1008, 1024, 0x2000, None) == B.SKVQ_ERR_INVALID_ARG
+
+
+def test_read_write_yardstick_refuses_bad_arguments_before_touching_a_device(B):
+    """Null pointers, a length that is no multiple of 4096, misaligned buffers and a ratio outside 1..8
+    are refused by the host checks (no GPU call is made for them)."""
+    L = B.lib()
+    L.skvq_read_write_yardstick.restype = C.c_int
+    L.skvq_read_write_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+    bad = B.SKVQ_ERR_INVALID_ARG
+    assert L.skvq_read_write_yardstick(None, 0x2000, 4096, 7, None) == bad
+    assert L.skvq_read_write_yardstick(0x1000, None, 4096, 7, None) == bad
+    assert L.skvq_read_write_yardstick(0x1000, 0x100000, 0, 7, None) == bad
+    assert L.skvq_read_write_yardstick(0x1000, 0x100000, 4096 + 16, 7, None) == bad
+    assert L.skvq_read_write_yardstick(0x1008, 0x100000, 4096, 7, None) == bad
+    assert L.skvq_read_write_yardstick(0x1000, 0x100008, 4096, 7, None) == bad
+    assert L.skvq_read_write_yardstick(0x1000, 0x100000, 4096, 0, None) == bad
+    assert L.skvq_read_write_yardstick(0x1000, 0x100000, 4096, 9, None) == bad

@@ -835,6 +835,31 @@ def test_read_yardstick_reads_and_leaves_memory_alone(P):
         Bd.skvq_read_yardstick(torch.zeros(5, dtype=torch.int32, device=dev), sink)
 
 
+@pytest.mark.gpu
+def test_read_write_yardstick_writes_the_xor_of_what_it_reads(P):
+    """4 KB piece g of the destination is the XOR of the source's pieces g * ratio .. g * ratio + ratio - 1,
+    for every ratio the kernel takes; the source stays as it was and nothing is written past the end."""
+    from paper_2405_06219_amd import binding as Bd
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    for ratio, pieces in ((1, 3), (2, 1), (7, 5), (7, 2500), (8, 129)):
+        src = torch.randint(-2**31, 2**31 - 1, (pieces * ratio, 1024), generator=gen, dtype=torch.int32, device=dev)
+        keep = src.clone()
+        dst = torch.full((pieces + 1, 1024), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+        Bd.skvq_read_write_yardstick(src, dst[:pieces], ratio)
+        torch.cuda.synchronize()
+        want = src.view(pieces, ratio, 1024)[:, 0].clone()
+        for j in range(1, ratio):
+            want ^= src.view(pieces, ratio, 1024)[:, j]
+        assert torch.equal(dst[:pieces], want), (ratio, pieces)
+        assert torch.equal(src, keep) and bool((dst[pieces] == 0x5A5A5A5A).all()), (ratio, pieces)
+    with pytest.raises(Bd.SkvqError):
+        Bd.skvq_read_write_yardstick(src, dst[:1, :1000], 7)
+    with pytest.raises(Bd.SkvqError):
+        Bd.skvq_read_write_yardstick(src[:3], dst[:1], 7)
+
+
 # ---- clip calibration (Eq. 3; Algorithm 1 Prologue, get_group_clipping) ----
 
 @pytest.mark.parametrize("G,v_bits,k_bits,Hq,Hk,B", [(64, 2.0, 2.0, 4, 2, 1), (128, 1.5, 2.0, 8, 2, 2), (32, 4.0, 4.0, 3, 3, 1)])
