@@ -112,14 +112,6 @@ constexpr unsigned kM4 = 0x00300030u, kM6 = 0x00c000c0u, kM8 = 0x03000300u;
 constexpr unsigned kN4 = 0x00f000f0u;  // a 4-bit code at mantissa bit 4 of each half
 constexpr unsigned kB6 = 0x00400040u, kB8 = 0x01000100u, kB10 = 0x04000400u;  // one bit of each half
 
-__device__ __forceinline__ float wave_max(float v) {
-  for (int off = 32; off; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-  for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Cross-lane moves inside a row of 16 lanes (data-parallel primitives: no LDS round trip).
@@ -145,6 +137,21 @@ __device__ __forceinline__ float wave_sum_in_last_lane(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false));
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));
   return v;
+}
+
+// The maximum over the 64 lanes as a wave-uniform value: the same moves with maxima (rows that a
+// broadcast does not reach keep -inf), then one lane read.  (The median with +inf is the maximum as
+// one instruction: fmaxf would first re-canonicalize both operands.)
+__device__ __forceinline__ float max_of(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, INFINITY); }
+__device__ __forceinline__ float wave_max(float v) {
+  v = max_of(v, row_move<kQuadSwap1>(v));
+  v = max_of(v, row_move<kQuadSwap2>(v));
+  v = max_of(v, row_move<kRowHalfMirror>(v));
+  v = max_of(v, row_move<kRowMirror>(v));  // every lane: the maximum of its row
+  const int lowest = __builtin_bit_cast(int, -INFINITY);
+  v = max_of(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(lowest, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false)));
+  v = max_of(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(lowest, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false)));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 __device__ __forceinline__ half4_t h4(unsigned a, unsigned b) { return __builtin_bit_cast(half4_t, uint2_t{a, b}); }
