@@ -142,6 +142,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
     }
   };
 
+  // (-1 as a value the compiler cannot see through: p - hi then stays one mixed-precision
+  // multiply-add on the fp16 operand instead of a conversion and a subtraction)
+  float minus_one = -1.0f;
+  asm("" : "+v"(minus_one));
   float16_t o[4];  // O^T: channel 32 blk + 8 (x/4) + 4 h + x%4 of this lane's query
 #pragma unroll
   for (int blk = 0; blk < 4; ++blk)
@@ -251,8 +255,9 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
       }
       float psum = 0.f;
       // B operands of the value product: step t covers keys 16 t .. 16 t + 15 of the tile.  A weight
-      // enters as two fp16 numbers, its top 11 significant bits (cut out of the fp32 value, so the
-      // conversion is exact) and the rest (rounded toward zero to 11 more): ~22 bits in all, so the
+      // enters as two fp16 numbers, its top 11 significant bits (converted toward zero; the
+      // difference to the fp32 value is exact and comes from one mixed-precision multiply-add) and
+      // the rest (rounded toward zero to 11 more): ~22 bits in all, so the
       // weights' rounding stays below 2^-21 of the largest value instead of 2^-12.
       uint4_t p[4], plo[4];
 #pragma unroll
@@ -262,10 +267,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_attn_kernel(const __half 
           const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][x], c, -m));
           const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][x + 1], c, -m));
           psum += p0 + p1;
-          const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, p0) & 0xffffe000u);
-          const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, p1) & 0xffffe000u);
-          p[2 * kb + (x >> 3)][(x & 7) >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(h0, h1));
-          plo[2 * kb + (x >> 3)][(x & 7) >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(p0 - h0, p1 - h1));
+          const auto hi = __builtin_amdgcn_cvt_pkrtz(p0, p1);  // toward zero: the top 11 significant bits
+          const float l0 = __builtin_fmaf((float)hi[0], minus_one, p0), l1 = __builtin_fmaf((float)hi[1], minus_one, p1);  // exact
+          p[2 * kb + (x >> 3)][(x & 7) >> 1] = __builtin_bit_cast(unsigned, hi);
+          plo[2 * kb + (x >> 3)][(x & 7) >> 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(l0, l1));
         }
       l += psum;
       // ---- values: the lane's slot e of step t is key 16 t + 8 (e/4) + 4 h + e%4 ----
