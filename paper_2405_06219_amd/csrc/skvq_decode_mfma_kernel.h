@@ -827,13 +827,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       const float2 vmeta = meta_value(cur.vmeta.m[g]);
-      vs[g] = valid ? vmeta.x : 0.f;
-      vz[g] = valid ? vmeta.y : 0.f;
-      vs_top = fmaxf(vs_top, vs[g]);
+      vs[g] = vmeta.x, vz[g] = vmeta.y;
+    }
+    if (tile * 64 + 63 > last_token) {  // (a scalar condition) only the cache's last tile has tokens to drop
+#pragma unroll
+      for (int g = 0; g < NG; ++g) vs[g] = valid ? vs[g] : 0.f, vz[g] = valid ? vz[g] : 0.f;
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (!valid) u[r] = -INFINITY;
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r)
-      if (!valid) u[r] = -INFINITY;
+    for (int g = 0; g < NG; ++g) vs_top = fmaxf(vs_top, vs[g]);
     bool trig = vs_top * beta > kVsLimit;
 #pragma unroll
     for (int r = 0; r < R; ++r) trig |= u[r] > kRefSlack;
