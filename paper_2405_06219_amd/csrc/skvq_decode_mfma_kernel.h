@@ -470,29 +470,46 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int safe_last_blk = last_blk > 0 ? last_blk : 0;
   // which of the streams are marked as streaming loads (see load_as)
   constexpr bool kStreamK = KL == 4, kStreamV = VL == 3 || VL == 4;
-  auto load_tile = [&](int tile) {
+  // (a tile index past the workgroup's share is redirected to tile_cap, the share's last tile, or tile
+  // 0 of an empty cache, by the callers: one scalar minimum per load)
+  const int tile_cap = max(min(tile_end - 1, safe_last_tile), 0);
+  auto load_tile = [&](const int tile) {
     Tile d;
-    if (tile > safe_last_tile) tile = safe_last_tile;
-    if (tile < 0) tile = 0;
-    int t = tile * 64 + lane;
-    if (t > safe_last_token) t = safe_last_token;  // only in the last tile; such lanes are masked below
-    const uint4_t *krow = reinterpret_cast<const uint4_t *>(kc + (size_t)t * kRowBytes);
-    d.k0 = stream_load<kStreamK>(krow); d.k1 = stream_load<kStreamK>(krow + 1);
-    if constexpr (K4) { d.k2 = stream_load<kStreamK>(krow + 2); d.k3 = stream_load<kStreamK>(krow + 3); }
-    if constexpr (K3) d.k2 = stream_load<kStreamK>(krow + 2);
-    d.kmeta = stream_load_block<kStreamK>(&km[t]);
-    d.vmeta = stream_load_block<kStreamK>(&vm[t]);
+    // every address is a wave-uniform base (the tile's first row, its two V blocks) plus a 32-bit lane
+    // offset: the bases are scalar arithmetic, the offsets cost one vector instruction per stream
+    // (lanes past the last token -- only in the last tile, masked below -- repeat its row)
+    const int rows_here = safe_last_token - tile * 64;  // >= 0
+    const unsigned row = min((unsigned)lane, (unsigned)rows_here);
+    const uint8_t *kt = kc + (size_t)tile * (64 * kRowBytes);
+    const uint8_t *krow = kt + row * (unsigned)kRowBytes;
+    d.k0 = stream_load<kStreamK>(reinterpret_cast<const uint4_t *>(krow));
+    d.k1 = stream_load<kStreamK>(reinterpret_cast<const uint4_t *>(krow + 16));
+    if constexpr (K4) {
+      d.k2 = stream_load<kStreamK>(reinterpret_cast<const uint4_t *>(krow + 32));
+      d.k3 = stream_load<kStreamK>(reinterpret_cast<const uint4_t *>(krow + 48));
+    }
+    if constexpr (K3) d.k2 = stream_load<kStreamK>(reinterpret_cast<const uint4_t *>(krow + 32));
+    const unsigned moff = row * (unsigned)sizeof(meta_block);
+    d.kmeta = stream_load_block<kStreamK>(reinterpret_cast<const meta_block *>(
+        reinterpret_cast<const uint8_t *>(km + (size_t)tile * 64) + moff));
+    d.vmeta = stream_load_block<kStreamK>(reinterpret_cast<const meta_block *>(
+        reinterpret_cast<const uint8_t *>(vm + (size_t)tile * 64) + moff));
     const int blk0 = 2 * tile > safe_last_blk ? safe_last_blk : 2 * tile;
     const int blk1 = blk0 + 1 > safe_last_blk ? safe_last_blk : blk0 + 1;
-    d.v00 = stream_load_unit<kStreamV>(vc + (size_t)blk0 * vbb + unit_off);
-    d.v10 = stream_load_unit<kStreamV>(vc + (size_t)blk1 * vbb + unit_off);
+    const uint8_t *vb0 = vc + (size_t)blk0 * vbb, *vb1 = vc + (size_t)blk1 * vbb;
+    // (the lane's offset is hidden from the compiler here: seen as loop-invariant it is folded into a
+    // 64-bit vector base once, and every tile then pays vector multiply-adds for the block's address)
+    unsigned uoff = unit_off;
+    asm("" : "+v"(uoff));
+    d.v00 = stream_load_unit<kStreamV>(vb0 + uoff);
+    d.v10 = stream_load_unit<kStreamV>(vb1 + uoff);
     if constexpr (V3) {
-      d.vt0 = stream_load_pair<kStreamV>(vc + (size_t)blk0 * vbb + unit_off + 16);
-      d.vt1 = stream_load_pair<kStreamV>(vc + (size_t)blk1 * vbb + unit_off + 16);
+      d.vt0 = stream_load_pair<kStreamV>(vb0 + uoff + 16);
+      d.vt1 = stream_load_pair<kStreamV>(vb1 + uoff + 16);
     }
     if constexpr (V4) {
-      d.v01 = stream_load_unit<kStreamV>(vc + (size_t)blk0 * vbb + unit_off + 16);
-      d.v11 = stream_load_unit<kStreamV>(vc + (size_t)blk1 * vbb + unit_off + 16);
+      d.v01 = stream_load_unit<kStreamV>(vb0 + uoff + 16);
+      d.v11 = stream_load_unit<kStreamV>(vb1 + uoff + 16);
     }
     return d;
   };
@@ -554,7 +571,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   int n_a = 0, n_b = 1, n_c = 2;
   int tile_a = tile_of(n_a), tile_b = tile_of(n_b), tile_c = tile_of(n_c);
   Tile buf_a, buf_b, buf_c;
-  buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
+  buf_a = load_tile(min(tile_a, tile_cap));
   if (TERNARY) {
     // While the loads are in flight the workgroup builds the table: entry f (a base-3 number of
     // eight digits, digit i = code of token i) is the operand itself, register m = codes of
@@ -584,7 +601,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   }
   {
     asm volatile("" ::: "memory");
-    buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
+    buf_b = load_tile(min(tile_b, tile_cap));
     // Wavefront w < 4 stages head w by itself: it parks the head's query in LDS as loaded (for the
     // fp16 slices later), reads it back through the permutation (its own writes: no barrier, the
     // LDS serves a wavefront's operations in order) and writes the head's matrix operands and piece
@@ -969,20 +986,20 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     while (tile_b < tile_end) {
       compute_tile(buf_a, tile_a);
       tile_a = tile_of(n_a += 2);
-      buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
+      buf_a = load_tile(min(tile_a, tile_cap));
       compute_tile(buf_b, tile_b);
       tile_b = tile_of(n_b += 2);
-      buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
+      buf_b = load_tile(min(tile_b, tile_cap));
     }
   } else {
   while (tile_c < tile_end) {
-    buf_c = load_tile(tile_c);
+    buf_c = load_tile(min(tile_c, tile_cap));
     compute_tile(buf_a, tile_a);
     tile_a = tile_of(n_a += 3);
-    buf_a = load_tile(tile_a < tile_end ? tile_a : tile_end - 1);
+    buf_a = load_tile(min(tile_a, tile_cap));
     compute_tile(buf_b, tile_b);
     tile_b = tile_of(n_b += 3);
-    buf_b = load_tile(tile_b < tile_end ? tile_b : tile_end - 1);
+    buf_b = load_tile(min(tile_b, tile_cap));
     compute_tile(buf_c, tile_c);
     tile_c = tile_of(n_c += 3);
   }
