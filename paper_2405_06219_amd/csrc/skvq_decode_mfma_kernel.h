@@ -769,7 +769,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #pragma unroll
     for (int g = 0; g < NG; ++g) zacc[r][g] = 0.f;
   }
-  float beta = 1.f;
+  float beta = 1.f, vs_limit = kVsLimit;
   float4_t acc[8];
 #pragma unroll
   for (int n = 0; n < 8; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -853,11 +853,16 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       for (int r = 0; r < R; ++r)
         if (!valid) u[r] = -INFINITY;
     }
+    // (scales are not negative: one group's scale is the largest as it is)
+    vs_top = vs[0];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) vs_top = fmaxf(vs_top, vs[g]);
-    bool trig = vs_top * beta > kVsLimit;
+    for (int g = 1; g < NG; ++g) vs_top = fmaxf(vs_top, vs[g]);
+    // one comparison for the heads' scores (their maximum) and one for the value scale, against
+    // the limit divided by beta (a power of two: the same decision as the product against the limit)
+    float u_top = u[0];
 #pragma unroll
-    for (int r = 0; r < R; ++r) trig |= u[r] > kRefSlack;
+    for (int r = 1; r < R; ++r) u_top = fmaxf(u_top, u[r]);
+    const bool trig = (vs_top > vs_limit) | (u_top > kRefSlack);
     if (first || __any(trig)) {
       // move the reference (and the value-scale normalisation) and rescale what is accumulated
       float f[R];
@@ -883,6 +888,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
         }
         g = nb / beta;
         beta = nb;
+        vs_limit = kVsLimit / nb;
       }
       if (!first) {
         const int col = lane & 15;
