@@ -770,6 +770,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     for (int g = 0; g < NG; ++g) zacc[r][g] = 0.f;
   }
   float beta = 1.f, vs_limit = kVsLimit;
+  float minus_one = -1.0f;
+  asm("" : "+v"(minus_one));
   float4_t acc[8];
 #pragma unroll
   for (int n = 0; n < 8; ++n) acc[n] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -905,18 +907,30 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
     // ---- weights: p = 2^u, P' = p * vscale * beta * 2^-(bit-4), split into high and low fp16 ----
     const float bk = beta * kslot_scale;
     _Float16 *pw = &sm.wb[wave].pbuf[lane >> 5][0][0][lane & 31];
+    // (the high part is the weight converted to fp16 toward zero, two heads per instruction; the
+    // low part the fp32 weight minus that fp16 number -- exact -- rounded to fp16 once, as one
+    // mixed-precision multiply-add: minus_one is -1 in a form the compiler does not see through)
+    float pr[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const float p = fast_exp2(u[r]);
-      lsum[r] += p;
+      pr[r] = fast_exp2(u[r]);
+      lsum[r] += pr[r];
+    }
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        zacc[r][g] = fmaf(p, vz[g], zacc[r][g]);
-        const float pp = p * (vs[g] * bk);
-        const float hi = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, pp) & 0xffffe000u);
-        const float lo = pp - hi;
-        pw[(g * 2 * R + r) * 32] = (_Float16)hi;
-        pw[(g * 2 * R + R + r) * 32] = (_Float16)lo;
+    for (int g = 0; g < NG; ++g) {
+      const float vsb = vs[g] * bk;
+#pragma unroll
+      for (int r = 0; r < R; r += 2) {
+        const float pa = pr[r] * vsb, pb = r + 1 < R ? pr[r + 1] * vsb : 0.f;
+        const auto hi = __builtin_amdgcn_cvt_pkrtz(pa, pb);
+        zacc[r][g] = fmaf(pr[r], vz[g], zacc[r][g]);
+        pw[(g * 2 * R + r) * 32] = hi[0];
+        pw[(g * 2 * R + R + r) * 32] = (_Float16)__builtin_fmaf((float)hi[0], minus_one, pa);
+        if (r + 1 < R) {
+          zacc[r + 1][g] = fmaf(pr[r + 1], vz[g], zacc[r + 1][g]);
+          pw[(g * 2 * R + r + 1) * 32] = hi[1];
+          pw[(g * 2 * R + R + r + 1) * 32] = (_Float16)__builtin_fmaf((float)hi[1], minus_one, pb);
+        }
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -931,8 +945,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
 #pragma unroll
       for (int x = 0; x < NACC; ++x) {
         const int g = UNEQ ? piece_group(x) : x;
-        pop[x] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-        if (col < 2 * R) pop[x] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col][8 * kb]);
+        // (columns from 2R on re-read the first ones: nobody reads their results, and an
+        // unconditional read needs neither a zeroed operand nor a change of the execution mask)
+        pop[x] = *reinterpret_cast<const half8_t *>(&sm.wb[wave].pbuf[blk][g][col % (2 * R)][8 * kb]);
       }
       const Unit16 raw = blk ? cur.v10 : cur.v00;
       if constexpr (V4) {
