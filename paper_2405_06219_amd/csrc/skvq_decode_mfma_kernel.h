@@ -257,6 +257,7 @@ struct Smem {
   float qraw[4][kD];                   // the query heads as loaded (rows >= R are zero)
   _Float16 qa[32][4][4];               // A operands of the score product: [step][head][k slot]
   alignas(16) float qpart[4][8];       // per head: sums of the reordered query over 16 positions each
+  alignas(16) float qtotal[4];         // per head: the sum of the whole query (one group per head)
   // epilogue: per-wave running reference, sum of weights, sum of weight*zero, for the packed
   // tiles (w*) and for the ring slices (r*) of the wave
   // ([head][...][wave]: the epilogue reads a head's eight entries as two 16-byte pieces)
@@ -612,6 +613,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      float both = 0.f;  // the lane's two positions
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int row = wave, p = lane + 64 * j;
@@ -622,13 +624,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
           k_slot_of(p, step, kslot, shift);
         const float x = sm.qraw[row][j ? pk1 : pk0];
         sm.qa[step][row][kslot] = (_Float16)ldexpf(x, 8 - shift);  // exact: a power of two
-        // sum of the reordered query over the 16 positions of this row of lanes
-        float s16 = x;
-        s16 += row_move<kQuadSwap1>(s16);
-        s16 += row_move<kQuadSwap2>(s16);
-        s16 += row_move<kRowHalfMirror>(s16);
-        s16 += row_move<kRowMirror>(s16);
-        if ((lane & 15) == 0) sm.qpart[row][p >> 4] = s16;
+        both += x;
+        if constexpr (UNEQ || NG > 1) {
+          // sum of the reordered query over the 16 positions of this row of lanes
+          float s16 = x;
+          s16 += row_move<kQuadSwap1>(s16);
+          s16 += row_move<kQuadSwap2>(s16);
+          s16 += row_move<kRowHalfMirror>(s16);
+          s16 += row_move<kRowMirror>(s16);
+          if ((lane & 15) == 0) sm.qpart[row][p >> 4] = s16;
+        }
+      }
+      if constexpr (!UNEQ && NG == 1) {
+        // one group per head: the head's whole sum, formed here once instead of by every wavefront
+        both = wave_sum_in_last_lane(both);
+        if (lane == 63) sm.qtotal[wave] = both;
       }
     }
     __syncthreads();
@@ -643,14 +653,23 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   float qsc[R][NG];
   float4_t dinit[UNEQ ? 1 : NG];
   float qp[4][8];  // the piece sums of the four heads (two 16-byte reads per head)
+  if constexpr (UNEQ || NG > 1) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const float4_t lo4 = *reinterpret_cast<const float4_t *>(&sm.qpart[r][0]);
-    const float4_t hi4 = *reinterpret_cast<const float4_t *>(&sm.qpart[r][4]);
+    for (int r = 0; r < 4; ++r) {
+      const float4_t lo4 = *reinterpret_cast<const float4_t *>(&sm.qpart[r][0]);
+      const float4_t hi4 = *reinterpret_cast<const float4_t *>(&sm.qpart[r][4]);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) qp[r][x] = lo4[x], qp[r][4 + x] = hi4[x];
+      for (int x = 0; x < 4; ++x) qp[r][x] = lo4[x], qp[r][4 + x] = hi4[x];
+    }
   }
-  if constexpr (UNEQ) {
+  if constexpr (!UNEQ && NG == 1) {
+    const float4_t tot = *reinterpret_cast<const float4_t *>(&sm.qtotal[0]);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (r < R) qsc[r][0] = c * tot[r];
+      dinit[0][r] = -kCentre * tot[r] * (1.0f / 65536.0f);
+    }
+  } else if constexpr (UNEQ) {
     // (a piece's accumulator sums only 16 products: it starts from zero, uncentred)
 #pragma unroll
     for (int g = 0; g < NG; ++g)
