@@ -530,24 +530,28 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(Layout L, cons
   const int slot0 = plan.slot0;  // ring row of the window's oldest token
   const __half *kwin = L.k_win + head * (W + L.S) * kD;
   const __half *vwin = L.v_win + head * (W + L.S) * kD;
-  auto ring_slot = [&](int t) {  // ring slot of ring token t (clamped to the last one)
-    if (t >= n_fp) t = n_fp - 1;
-    if (t < n_sink) return W + t;
-    int s = slot0 + t - n_sink;
-    return s >= W ? s - W : s;
-  };
-  // row of ring token t (clamped to the last one); the newest token's row is the caller's when
-  // it is taken along
-  auto ring_row = [&](const __half *win, const __half *fresh, int t) {
-    const __half *row = win + (size_t)ring_slot(t) * kD;
-    return fused && t >= n_fp - 1 ? fresh + head * kD : row;
-  };
+  // (ring token t, clamped to the last one, sits in sink row W + t if it is a sink, else in ring
+  // slot slot0 + t - n_sink modulo W; the newest token's row is the caller's when it is taken along)
   auto load_ring = [&](int slice) {
     RingData d;
-    d.k = reinterpret_cast<const uint4_t *>(ring_row(kwin, knew, slice * kRingSlice + (lane >> 4)))[lane & 15];
+    // Lane (token l/16 of the slice, piece l%16) works out the row of its own token with vector
+    // arithmetic (the same for every slice: no scalar branches per row); the four value rows take
+    // theirs from lanes 0, 16, 32 and 48.
+    const int t = min(slice * kRingSlice + (lane >> 4), n_fp - 1);
+    const int s = slot0 + t - n_sink;
+    const int slot = t < n_sink ? W + t : (s >= W ? s - W : s);
+    const int fresh = fused && t >= n_fp - 1 ? 1 : 0;  // the caller's row of the new token
+    const unsigned row_bytes = (unsigned)slot * (unsigned)(kD * sizeof(__half));
+    const char *krow = fresh ? reinterpret_cast<const char *>(knew + head * kD)
+                             : reinterpret_cast<const char *>(kwin) + row_bytes;
+    d.k = reinterpret_cast<const uint4_t *>(krow)[lane & 15];
 #pragma unroll
-    for (int k = 0; k < kRingSlice; ++k)
-      d.v[k] = reinterpret_cast<const unsigned *>(ring_row(vwin, vnew, slice * kRingSlice + k))[lane];
+    for (int k = 0; k < kRingSlice; ++k) {
+      const unsigned vb = (unsigned)__builtin_amdgcn_readlane((int)row_bytes, 16 * k);
+      const char *vrow = __builtin_amdgcn_readlane(fresh, 16 * k) ? reinterpret_cast<const char *>(vnew + head * kD)
+                                                                   : reinterpret_cast<const char *>(vwin) + vb;
+      d.v[k] = reinterpret_cast<const unsigned *>(vrow)[lane];
+    }
     return d;
   };
 
